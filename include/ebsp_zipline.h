@@ -1,0 +1,106 @@
+/*
+ * ebsp_zipline.h -- C ABI of the MI355X (gfx950) ZipLine barrier search.
+ *
+ * The operation (Section III "The Problem" and Algorithm 2 of the ElasticBSP
+ * paper, arXiv 2001.01347, with the objective read as the summed waiting time
+ * of all workers that Fig. 1's caption, Section I and the Conclusion describe):
+ * one instance is a P x R matrix t[p][i] of predicted iteration end
+ * timestamps, row p non-decreasing in i.  For a barrier time c let
+ * last_p(c) = max{ t[p][i] <= c }.  Over all timestamps c with
+ * c >= max_p t[p][0] (every worker has finished an iteration: Algorithm 2's
+ * initial fill of Z) the search returns
+ *
+ *     wait    = min_c  sum_p ( c - last_p(c) ),
+ *     barrier = the smallest c that attains it (Fig. 3 caption: the first of
+ *               several equal minima),
+ *     iters[p]= #{ i : t[p][i] <= barrier }   (the per-worker iteration counts
+ *               of the superstep, Fig. 1 caption).
+ *
+ * All data pointers are DEVICE pointers owned by the caller.  The calls only
+ * enqueue work on `stream` (a hipStream_t passed as void*); they never
+ * synchronise it, never allocate and never free.  The caller keeps every
+ * buffer alive until the stream has passed the call.  Calls on different
+ * streams may overlap if they use different workspaces.
+ */
+#ifndef EBSP_ZIPLINE_H
+#define EBSP_ZIPLINE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Return codes (host-detectable errors; nothing is enqueued when one is returned). */
+#define EBSP_OK                0
+#define EBSP_ERR_NULL         -1   /* a required pointer is NULL                         */
+#define EBSP_ERR_SHAPE        -2   /* B < 0, P < 1, R < 1, or P*R >= 2^31                */
+#define EBSP_ERR_WORKSPACE    -3   /* workspace_bytes < ebsp_zipline_workspace_bytes()   */
+#define EBSP_ERR_LAUNCH       -4   /* the HIP runtime refused a launch; see last_error   */
+#define EBSP_ERR_DEVICE       -5   /* not a gfx950 device / LDS too small                */
+
+/* Per-instance status bits written to status[b] (data errors; that instance's
+ * outputs are then unspecified, other instances are unaffected). */
+#define EBSP_STATUS_OK         0
+#define EBSP_STATUS_UNSORTED   1   /* some row is not non-decreasing (Section III: rows  */
+                                   /* are iteration sequences)                            */
+#define EBSP_STATUS_OVERFLOW   2   /* P * (max t - min t) does not fit in int64          */
+#define EBSP_STATUS_UNSUPPORTED 4  /* the instance needs a code path this build lacks    */
+
+/*
+ * Bytes of device scratch that ebsp_zipline_batch needs for this shape.
+ * Returns 0 for invalid shapes and for shapes that need no scratch (small
+ * instances are handled by one workgroup each, entirely in LDS).
+ */
+size_t ebsp_zipline_workspace_bytes(int64_t B, int32_t P, int32_t R);
+
+/*
+ * Batched ZipLine search: B independent instances.
+ *
+ *   ts        in   [B][P][R] int64, row-major, device; timestamps in any fixed
+ *                  unit and epoch (microseconds in the paper's setting); every
+ *                  row non-decreasing.  Not modified.
+ *   barrier   out  [B] int64, device; same unit and epoch as ts.
+ *   iters     out  [B][P] int32, device; 1..R.
+ *   wait      out  [B] int64, device; >= 0.
+ *   status    out  [B] int32, device, or NULL; EBSP_STATUS_* bits.
+ *   workspace      device scratch of at least ebsp_zipline_workspace_bytes()
+ *                  bytes, 256-byte aligned (may be NULL when that is 0).  Its
+ *                  contents are undefined before and after the call.
+ *   stream         hipStream_t (as void*); NULL is the default stream.
+ *
+ * Precondition per instance: P * (max t - min t) <= INT64_MAX.  B == 0 is a
+ * valid no-op.  Outputs of valid instances are fully overwritten.
+ * Returns EBSP_OK or a negative EBSP_ERR_* code.
+ */
+int ebsp_zipline_batch(const int64_t* ts, int64_t B, int32_t P, int32_t R,
+                       int64_t* barrier, int32_t* iters, int64_t* wait,
+                       int32_t* status, void* workspace, size_t workspace_bytes,
+                       void* stream);
+
+/*
+ * The same call with per-kernel timing, for benchmarks: HIP events are
+ * recorded on `stream` around every kernel, the stream is synchronised, and
+ * kernel_ms[i] (HOST array of ebsp_zipline_kernel_count() floats) receives the
+ * duration of kernel i in milliseconds (0 for kernels this shape does not
+ * launch).  Creates and destroys HIP events; otherwise as ebsp_zipline_batch.
+ */
+int ebsp_zipline_batch_timed(const int64_t* ts, int64_t B, int32_t P, int32_t R,
+                             int64_t* barrier, int32_t* iters, int64_t* wait,
+                             int32_t* status, void* workspace, size_t workspace_bytes,
+                             void* stream, float* kernel_ms);
+
+/* Number of distinct kernels the library may launch, and their names
+ * (static storage; NULL if i is out of range). */
+int         ebsp_zipline_kernel_count(void);
+const char* ebsp_zipline_kernel_name(int i);
+
+/* Message for the last error returned on the calling thread (static,
+ * thread-local storage; never NULL). */
+const char* ebsp_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EBSP_ZIPLINE_H */

@@ -1,0 +1,857 @@
+// ZipLine barrier search for MI355X (gfx950, wave64).
+//
+// Implements the C ABI declared in include/ebsp_zipline.h.  The search is the
+// sweep of Algorithm 2 of the ElasticBSP paper (arXiv 2001.01347) with the
+// summed waiting time as objective (Section III; Fig. 1 caption), recast for
+// a GPU:
+//
+//   * the set Z of Algorithm 2 (newest timestamp per worker) is never built.
+//     With delta[p][i] = t[p][i] - t[p][i-1], the sum of the elements of Z
+//     after the sweep has passed timestamp c is the prefix sum of the deltas
+//     of all elements <= c in sorted order, so
+//         wait(c) = P*c - prefix(c)
+//     and the sweep becomes sort -> scan -> arg-min;
+//   * every row of the input is already sorted (rows are iteration sequences,
+//     Section III), so the merged set Omega can be cut into windows of
+//     consecutive values without moving any data: a window takes one
+//     contiguous segment of every row.  A window that fits in LDS is sorted,
+//     scanned and reduced by one workgroup, and the value of the prefix at the
+//     window start is known from the row elements just before the segments,
+//     so windows need no carry from one another;
+//   * small instances (P*R <= 16384) are one window: one workgroup each, no
+//     scratch memory, one kernel.
+//
+// Device steps, named as in the design notes:
+//   zl_delta   load a window's row segments, form (key, delta) records
+//   zl_sort    LSD radix sort of the records in LDS (wave-ballot ranking)
+//   zl_scan    prefix sum of the deltas in sorted order (wave shuffles)
+//   zl_argmin  wait(c) at the last element of every run of equal keys,
+//              masked to c >= max_p t[p][0]; first minimum wins
+//   zl_iters   per-worker iteration counts by binary search
+// plus, for instances larger than one window: zl_bounds (instance range),
+// zl_partition (row/bin crossing indices), zl_bincount + zl_plan (windows).
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "ebsp_zipline.h"
+
+typedef unsigned long long u64;
+typedef unsigned int u32;
+typedef long long i64;
+
+namespace {
+
+constexpr int WAVE = 64;
+constexpr u64 U64_MAX = ~0ull;
+
+// ---------------------------------------------------------------------------
+// Tunables of the multi-window path.
+constexpr int LARGE_NT = 1024;               // threads of a window workgroup
+constexpr int LARGE_ITEMS = 16;              // records per thread
+constexpr int LARGE_CAP = LARGE_NT * LARGE_ITEMS;   // records a window may hold
+constexpr int GROUP_SHIFT = 13;              // windows are cut every 2^13 keys ...
+constexpr int FINE_SHIFT = 11;               // ... out of fine bins of at most 2^11 keys on average
+
+// Per-instance facts shared by the kernels of the multi-window path.
+struct InstInfo {
+    i64 base;    // min_p t[p][0]; all other values are relative to it
+    u64 range;   // max_p t[p][R-1] - base
+    u64 thr;     // max_p t[p][0] - base: earliest admissible barrier
+    u32 inv;     // fine bin of relative value v is (v * inv) >> 32
+    u32 nb;      // number of fine bins, bin(range) + 1
+    u32 nwin;    // number of windows (set by zl_plan)
+    u32 flags;   // EBSP_STATUS_* bits found so far
+};
+
+struct Partial {  // best candidate of one window
+    u64 wait;     // U64_MAX: the window has no admissible candidate
+    u64 brel;     // barrier relative to base
+};
+
+// ---------------------------------------------------------------------------
+// Wave and block primitives (wave64).
+
+template <class T>
+__device__ __forceinline__ T wave_incl_scan(T v)
+{
+    const int lane = threadIdx.x & (WAVE - 1);
+#pragma unroll
+    for (int d = 1; d < WAVE; d <<= 1) {
+        T o = __shfl_up(v, d, WAVE);
+        if (lane >= d) v += o;
+    }
+    return v;
+}
+
+// Exclusive block scan; `total` receives the block sum.  `red` holds NT/64 T's.
+template <class T, int NT>
+__device__ __forceinline__ T block_excl_scan(T v, T* red, T& total)
+{
+    constexpr int NW = NT / WAVE;
+    const int lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x >> 6;
+    T inc = wave_incl_scan(v);
+    if (lane == WAVE - 1) red[wave] = inc;
+    __syncthreads();
+    T base = 0, sum = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+        T x = red[w];
+        if (w < wave) base += x;
+        sum += x;
+    }
+    __syncthreads();
+    total = sum;
+    return base + inc - v;
+}
+
+struct OpMin { template <class T> __device__ T operator()(T a, T b) const { return a < b ? a : b; } };
+struct OpMax { template <class T> __device__ T operator()(T a, T b) const { return a > b ? a : b; } };
+struct OpAdd { template <class T> __device__ T operator()(T a, T b) const { return a + b; } };
+
+template <class T, int NT, class Op>
+__device__ __forceinline__ T block_reduce(T v, T* red, Op op)
+{
+    constexpr int NW = NT / WAVE;
+    const int lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int d = WAVE / 2; d > 0; d >>= 1) v = op(v, __shfl_xor(v, d, WAVE));
+    if (lane == 0) red[wave] = v;
+    __syncthreads();
+    T r = red[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) r = op(r, red[w]);
+    __syncthreads();
+    return r;
+}
+
+__device__ __forceinline__ int bit_length(u64 x) { return x ? 64 - __clzll((long long)x) : 0; }
+
+// Fine-bin grid of an instance whose range fits 32 bits: a monotone map of
+// relative values onto [0, nb).
+__device__ __forceinline__ u32 fine_bin(u64 rel, u64 range, u32 inv, u32 nb)
+{
+    if (rel > range) rel = range;                    // only reachable for unsorted rows
+    const u32 k = (u32)((rel * (u64)inv) >> 32);
+    return k < nb ? k : nb - 1;
+}
+// Smallest relative value that falls in bin k or later.
+__device__ __forceinline__ u64 fine_bin_start(u32 k, u32 inv) { return (((u64)k << 32) + inv - 1) / inv; }
+
+// ---------------------------------------------------------------------------
+// zl_iters: number of entries of a sorted row that are <= v.
+__device__ __forceinline__ int zl_iters(const i64* __restrict__ row, int R, i64 v)
+{
+    int lo = 0, hi = R;
+    while (lo < hi) {
+        int m = (lo + hi) >> 1;
+        if (row[m] <= v) lo = m + 1; else hi = m;
+    }
+    return lo;
+}
+
+// ---------------------------------------------------------------------------
+// Window workgroup: LDS layout and the sort/scan/argmin steps.
+//
+// A record is (key: low 32 bits, delta: high 32 bits), both relative values
+// that fit 32 bits because the instance's range does.  Record q lives at
+// recs[q + (q >> 4)]: one pad slot per 16 records keeps both the wave-striped
+// access of the sort and the 16-per-thread blocked access of the scan free of
+// bank conflicts.
+template <int NT, int ITEMS>
+struct WinCfg {
+    static constexpr int NW = NT / WAVE;
+    static constexpr int CAP = NT * ITEMS;
+    static constexpr int DB_MAX = NT >= 256 ? 8 : 6;     // widest radix digit (one thread per digit value)
+    static constexpr int RADIX_MAX = 1 << DB_MAX;
+    static constexpr int RECS = CAP + CAP / 16 + 2;
+    static constexpr int CNT_WORDS = (NW * RADIX_MAX > 2 * NT) ? NW * RADIX_MAX : 2 * NT;
+    static constexpr int RED_WORDS = 2 * NW + 8;          // u64 scratch for scans and reductions
+    static constexpr size_t BYTES = (size_t)RECS * 8 + (size_t)RED_WORDS * 8 + (size_t)CNT_WORDS * 4;
+};
+
+__device__ __forceinline__ int phys(int q) { return q + (q >> 4); }
+
+// Lanes of this wave whose digit equals mine.
+__device__ __forceinline__ u64 match_digit(u32 d, int dbits)
+{
+    u64 peers = ~0ull;
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+        if (b < dbits) {
+            const bool bit = (d >> b) & 1u;
+            const u64 bal = __ballot(bit);
+            peers &= bit ? bal : ~bal;
+        }
+    }
+    return peers;
+}
+
+// zl_sort: stable LSD radix sort of records [0, NT*items) by the low `kbits`
+// bits of the key.  Wave w owns positions [w*64*items, (w+1)*64*items); in
+// round j lane l holds position w*64*items + j*64 + l.  Ranks within a wave
+// come from ballots, per-wave digit counts live in cnt[w][digit]; a digit-major
+// scan of those counts gives every (wave, digit) its first output position.
+template <int NT, int ITEMS>
+__device__ __forceinline__ void zl_sort(u64* recs, u32* cnt, u64* red, int items, int kbits)
+{
+    using C = WinCfg<NT, ITEMS>;
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid >> 6;
+    if (kbits <= 0) return;
+    const int npass = (kbits + C::DB_MAX - 1) / C::DB_MAX;
+    const int dbits = (kbits + npass - 1) / npass;
+    const u32 radix = 1u << dbits, dmask = radix - 1u;
+    const u64 lt = (1ull << lane) - 1ull;
+    volatile u32* mycnt = cnt + wave * C::RADIX_MAX;
+    const int wbase = wave * WAVE * items + lane;
+
+    for (int pass = 0; pass < npass; ++pass) {
+        const int sh = pass * dbits;
+        for (u32 d = lane; d < radix; d += WAVE) mycnt[d] = 0;
+        u32 key[ITEMS], dl[ITEMS], rank[ITEMS];
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) {
+            if (j < items) {
+                const u64 r = recs[phys(wbase + j * WAVE)];
+                key[j] = (u32)r;
+                dl[j] = (u32)(r >> 32);
+                const u32 d = (key[j] >> sh) & dmask;
+                const u64 peers = match_digit(d, dbits);
+                const u32 below = __popcll(peers & lt);
+                const u32 old = mycnt[d];
+                if (below == 0) mycnt[d] = old + (u32)__popcll(peers);
+                rank[j] = old + below;
+            }
+        }
+        __syncthreads();
+        // digit-major exclusive scan over (digit, wave)
+        u32 mine = 0;
+        if ((u32)tid < radix) {
+#pragma unroll 4
+            for (int w = 0; w < C::NW; ++w) mine += cnt[w * C::RADIX_MAX + tid];
+        }
+        u32 all;
+        u32 run = block_excl_scan<u32, NT>(mine, (u32*)red, all);
+        if ((u32)tid < radix) {
+#pragma unroll 4
+            for (int w = 0; w < C::NW; ++w) {
+                const u32 c = cnt[w * C::RADIX_MAX + tid];
+                cnt[w * C::RADIX_MAX + tid] = run;
+                run += c;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) {
+            if (j < items) {
+                const u32 d = (key[j] >> sh) & dmask;
+                const int pos = (int)(mycnt[d] + rank[j]);
+                recs[phys(pos)] = (u64)key[j] | ((u64)dl[j] << 32);
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// zl_scan + zl_argmin over the sorted records [0, total).
+// Thread t owns positions [t*items, (t+1)*items).  S(q) = inclusive prefix of
+// the deltas; candidate at q if it ends a run of equal keys and
+// A + key >= thr; value  P*key + W0 - S(q)  (all arithmetic modulo 2^64; the
+// true value is in [0, 2^63) by the caller's precondition).
+// Returns the block-wide first minimum: (wait, key) with wait == U64_MAX if
+// there is no candidate.
+template <int NT, int ITEMS>
+__device__ __forceinline__ void zl_scan_argmin(const u64* recs, u64* red, int items, int total,
+                                               u32 A, u32 thr, u64 P, u64 W0,
+                                               u64& best_wait, u32& best_key)
+{
+    const int tid = threadIdx.x;
+    const int q0 = tid * items;
+    int qe = q0 + items;
+    if (qe > total) qe = total;
+    u64 local = 0;
+    for (int q = q0; q < qe; ++q) local += recs[phys(q)] >> 32;
+    u64 sum_all;
+    u64 S = block_excl_scan<u64, NT>(local, red, sum_all);
+
+    u64 bw = U64_MAX;
+    u32 bq = 0xffffffffu, bk = 0;
+    u64 r = (q0 < qe) ? recs[phys(q0)] : 0ull;
+    for (int q = q0; q < qe; ++q) {
+        const u32 key = (u32)r;
+        S += r >> 32;
+        const bool has_next = q + 1 < total;
+        const u64 rn = has_next ? recs[phys(q + 1)] : 0ull;
+        const bool run_end = !has_next || (u32)rn != key;
+        const bool admissible = (u64)A + key >= (u64)thr;
+        if (run_end && admissible) {
+            const u64 w = P * (u64)key + W0 - S;
+            if (w < bw) { bw = w; bq = (u32)q; bk = key; }
+        }
+        r = rn;
+    }
+    // block arg-min over (wait, position): smaller wait, then earlier position
+#pragma unroll
+    for (int d = WAVE / 2; d > 0; d >>= 1) {
+        const u64 ow = __shfl_xor(bw, d, WAVE);
+        const u32 oq = __shfl_xor(bq, d, WAVE);
+        const u32 ok = __shfl_xor(bk, d, WAVE);
+        if (ow < bw || (ow == bw && oq < bq)) { bw = ow; bq = oq; bk = ok; }
+    }
+    constexpr int NW = NT / WAVE;
+    const int lane = tid & (WAVE - 1), wave = tid >> 6;
+    if (lane == 0) { red[wave] = bw; red[NW + wave] = ((u64)bq << 32) | bk; }
+    __syncthreads();
+    bw = red[0];
+    u64 bqk = red[NW];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) {
+        const u64 ow = red[w], oqk = red[NW + w];
+        if (ow < bw || (ow == bw && (u32)(oqk >> 32) < (u32)(bqk >> 32))) { bw = ow; bqk = oqk; }
+    }
+    __syncthreads();
+    best_wait = bw;
+    best_key = (u32)bqk;
+}
+
+// Sentinels behind the last record, so that whole rounds of 64 can be sorted.
+template <int NT>
+__device__ __forceinline__ void fill_sentinels(u64* recs, int total, int items)
+{
+    for (int q = total + threadIdx.x; q < NT * items; q += NT) recs[phys(q)] = 0x00000000ffffffffull;
+}
+
+// ---------------------------------------------------------------------------
+// One workgroup per instance (P*R <= NT*ITEMS): the whole search in LDS.
+template <int NT, int ITEMS>
+__global__ __launch_bounds__(NT) void zl_instance_kernel(
+    const i64* __restrict__ ts, int P, int R, int rshift,
+    i64* __restrict__ barrier, int* __restrict__ iters, i64* __restrict__ wait,
+    int* __restrict__ status)
+{
+    using C = WinCfg<NT, ITEMS>;
+    __shared__ __align__(16) unsigned char smem[C::BYTES];
+    u64* recs = (u64*)smem;
+    u64* red = recs + C::RECS;
+    u32* cnt = (u32*)(red + C::RED_WORDS);
+
+    const int tid = threadIdx.x;
+    const i64 b = blockIdx.x;
+    const int n = P * R;
+    const i64* __restrict__ inst = ts + b * (i64)n;
+
+    // instance bounds: base = min first, thr = max first, top = max last
+    i64 mn = INT64_MAX, mxf = INT64_MIN, mxl = INT64_MIN;
+    for (int p = tid; p < P; p += NT) {
+        const i64 f = inst[(size_t)p * R], l = inst[(size_t)p * R + R - 1];
+        mn = f < mn ? f : mn;
+        mxf = f > mxf ? f : mxf;
+        mxl = l > mxl ? l : mxl;
+    }
+    const i64 base = block_reduce<i64, NT>(mn, (i64*)red, OpMin());
+    const i64 first_max = block_reduce<i64, NT>(mxf, (i64*)red, OpMax());
+    const i64 last_max = block_reduce<i64, NT>(mxl, (i64*)red, OpMax());
+    const u64 range = (u64)last_max - (u64)base;
+    const u64 thr = (u64)first_max - (u64)base;
+
+    u32 flags = 0;
+    if (range > (u64)INT64_MAX / (u64)P) flags |= EBSP_STATUS_OVERFLOW;
+    if (range >> 32) flags |= EBSP_STATUS_UNSUPPORTED;
+
+    // zl_delta: records in memory order (row p occupies [p*R, (p+1)*R))
+    int bad = 0;
+    if (!(flags & EBSP_STATUS_UNSUPPORTED)) {
+        for (int e = tid; e < n; e += NT) {
+            const int i = rshift >= 0 ? (e & (R - 1)) : (e % R);
+            const i64 cur = inst[e];
+            const u32 rel = (u32)((u64)cur - (u64)base);
+            u32 prel = 0;
+            if (i > 0) {
+                const i64 prv = inst[e - 1];
+                prel = (u32)((u64)prv - (u64)base);
+                bad |= (cur < prv);
+            }
+            recs[phys(e)] = (u64)rel | ((u64)(rel - prel) << 32);
+        }
+    }
+    const int items = (n + NT - 1) / NT;
+    fill_sentinels<NT>(recs, n, items);
+    if (__syncthreads_or(bad)) flags |= EBSP_STATUS_UNSORTED;
+
+    u64 best_wait = U64_MAX;
+    u32 best_key = 0;
+    if (!(flags & EBSP_STATUS_UNSUPPORTED)) {
+        zl_sort<NT, ITEMS>(recs, cnt, red, items, bit_length(range));
+        zl_scan_argmin<NT, ITEMS>(recs, red, items, n, 0u, (u32)thr, (u64)P, 0ull, best_wait, best_key);
+    }
+    const i64 bar = (i64)((u64)base + (u64)best_key);
+    if (tid == 0) {
+        barrier[b] = bar;
+        wait[b] = (i64)best_wait;
+        if (status) status[b] = (int)flags;
+    }
+    for (int p = tid; p < P; p += NT)
+        iters[b * (i64)P + p] = zl_iters(inst + (size_t)p * R, R, bar);
+}
+
+// ---------------------------------------------------------------------------
+// Multi-window path.
+
+// zl_bounds: per-instance base, range, thr and the fine-bin grid.
+template <int NT>
+__global__ __launch_bounds__(NT) void zl_bounds_kernel(
+    const i64* __restrict__ ts, int P, int R, int bins,
+    InstInfo* __restrict__ info, int* __restrict__ status)
+{
+    __shared__ i64 red[NT / WAVE];
+    const int tid = threadIdx.x;
+    const i64 b = blockIdx.x;
+    const i64* __restrict__ inst = ts + b * (i64)P * R;
+    i64 mn = INT64_MAX, mxf = INT64_MIN, mxl = INT64_MIN;
+    for (int p = tid; p < P; p += NT) {
+        const i64 f = inst[(size_t)p * R], l = inst[(size_t)p * R + R - 1];
+        mn = f < mn ? f : mn;
+        mxf = f > mxf ? f : mxf;
+        mxl = l > mxl ? l : mxl;
+    }
+    const i64 base = block_reduce<i64, NT>(mn, red, OpMin());
+    const i64 first_max = block_reduce<i64, NT>(mxf, red, OpMax());
+    const i64 last_max = block_reduce<i64, NT>(mxl, red, OpMax());
+    if (tid == 0) {
+        InstInfo ii;
+        ii.base = base;
+        ii.range = (u64)last_max - (u64)base;
+        ii.thr = (u64)first_max - (u64)base;
+        ii.nwin = 0;
+        ii.flags = 0;
+        if (ii.range > (u64)INT64_MAX / (u64)P) ii.flags |= EBSP_STATUS_OVERFLOW;
+        if (ii.range >> 32) ii.flags |= EBSP_STATUS_UNSUPPORTED;
+        // bins equal slices of [0, range]: inv = bins * 2^32 / (range + 1), capped to 32 bits
+        ii.inv = 0xffffffffu;
+        ii.nb = 1;
+        if (!(ii.flags & EBSP_STATUS_UNSUPPORTED)) {
+            const u64 q = ((u64)bins << 32) / (ii.range + 1);
+            ii.inv = q < 0xffffffffull ? (u32)q : 0xffffffffu;
+            if (ii.inv == 0) ii.inv = 1;
+            ii.nb = (u32)((ii.range * (u64)ii.inv) >> 32) + 1u;
+        }
+        info[b] = ii;
+        if (status) status[b] = (int)ii.flags;
+    }
+}
+
+// zl_partition: one wave per row.  cross[row][k] = number of entries of the row
+// that fall in fine bins below k, for k = 0..nb.
+template <int NT>
+__global__ __launch_bounds__(NT) void zl_partition_kernel(
+    const i64* __restrict__ ts, i64 nrows, int P, int R,
+    const InstInfo* __restrict__ info, u32* __restrict__ cross, int stride)
+{
+    const int lane = threadIdx.x & (WAVE - 1);
+    const i64 row_id = (i64)blockIdx.x * (NT / WAVE) + (threadIdx.x >> 6);
+    if (row_id >= nrows) return;
+    const i64 b = row_id / P;
+    const InstInfo ii = info[b];
+    if (ii.flags & EBSP_STATUS_UNSUPPORTED) return;
+    const i64* __restrict__ row = ts + row_id * (i64)R;
+    u32* __restrict__ out = cross + row_id * (i64)stride;
+    const u64 base = (u64)ii.base;
+
+    int carry = -1;                        // bin of the element before lane 0's
+    for (int i0 = 0; i0 < R; i0 += WAVE) {
+        const int i = i0 + lane;
+        int bin = -1;
+        if (i < R) bin = (int)fine_bin((u64)row[i] - base, ii.range, ii.inv, ii.nb);
+        int pb = __shfl_up(bin, 1, WAVE);
+        if (lane == 0) pb = carry;
+        if (i < R)
+            for (int k = pb + 1; k <= bin; ++k) out[k] = (u32)i;
+        carry = __shfl(bin, WAVE - 1, WAVE);
+    }
+    const int last_bin = (int)fine_bin((u64)row[R - 1] - base, ii.range, ii.inv, ii.nb);
+    for (int k = last_bin + 1 + lane; k <= (int)ii.nb; k += WAVE) out[k] = (u32)R;
+}
+
+// zl_bincount: below[b][k] = number of keys of instance b under fine bin k
+// (column sums of cross over the P rows), k = 0..nb.
+__global__ __launch_bounds__(256) void zl_bincount_kernel(
+    const u32* __restrict__ cross, int P, int R, int stride,
+    const InstInfo* __restrict__ info, u32* __restrict__ below)
+{
+    __shared__ u32 part[256];
+    const int tid = threadIdx.x, kl = tid & 63, pg = tid >> 6;
+    const u32 kblocks = (u32)(stride + 63) / 64;
+    const i64 b = blockIdx.x / kblocks;
+    const int k = (int)(blockIdx.x % kblocks) * 64 + kl;
+    const InstInfo ii = info[b];
+    u32 s = 0;
+    if (k <= (int)ii.nb && !(ii.flags & EBSP_STATUS_UNSUPPORTED)) {
+        const u32* col = cross + (b * (i64)P) * stride + k;
+#pragma unroll 4
+        for (int p = pg; p < P; p += 4) {
+            const u32 c = col[(i64)p * stride];
+            s += c < (u32)R ? c : (u32)R;
+        }
+    }
+    part[tid] = s;
+    __syncthreads();
+    if (pg == 0 && k <= (int)ii.nb)
+        below[b * (i64)stride + k] = part[kl] + part[64 + kl] + part[128 + kl] + part[192 + kl];
+}
+
+// zl_plan: windows of an instance.  Fine bin k belongs to group
+// below[k] >> GROUP_SHIFT; a window is a maximal run of bins of one group, so
+// it holds fewer than 2^GROUP_SHIFT keys plus its last bin's.
+template <int NT>
+__global__ __launch_bounds__(NT) void zl_plan_kernel(
+    InstInfo* __restrict__ info, const u32* __restrict__ below, int stride,
+    u32* __restrict__ winstart, int max_win)
+{
+    __shared__ u32 red[NT / WAVE];
+    const int tid = threadIdx.x;
+    const i64 b = blockIdx.x;
+    const InstInfo ii = info[b];
+    if (ii.flags & EBSP_STATUS_UNSUPPORTED) return;
+    const u32* bel = below + b * (i64)stride;
+    u32* ws = winstart + b * (i64)(max_win + 1);
+    const int nb = (int)ii.nb;
+    u32 found = 0;
+    for (int k0 = 0; k0 < nb; k0 += NT) {
+        const int k = k0 + tid;
+        u32 flag = 0;
+        if (k < nb) flag = (k == 0) || ((bel[k] >> GROUP_SHIFT) != (bel[k - 1] >> GROUP_SHIFT));
+        u32 chunk;
+        const u32 idx = found + block_excl_scan<u32, NT>(flag, red, chunk);
+        if (flag && idx < (u32)max_win) ws[idx] = (u32)k;
+        found += chunk;
+    }
+    if (tid == 0) {
+        const u32 nwin = found < (u32)max_win ? found : (u32)max_win;
+        ws[nwin] = (u32)nb;
+        info[b].nwin = nwin;
+    }
+}
+
+// One workgroup per window: zl_delta over the window's row segments, then
+// zl_sort, zl_scan, zl_argmin; the window's best candidate goes to `partial`.
+template <int NT, int ITEMS>
+__global__ __launch_bounds__(NT) void zl_window_kernel(
+    const i64* __restrict__ ts, i64 B, int P, int R,
+    InstInfo* __restrict__ info, const u32* __restrict__ cross, int stride,
+    const u32* __restrict__ winstart, int max_win,
+    Partial* __restrict__ partial, int* __restrict__ status)
+{
+    using C = WinCfg<NT, ITEMS>;
+    __shared__ __align__(16) unsigned char smem[C::BYTES];
+    u64* recs = (u64*)smem;
+    u64* red = recs + C::RECS;
+    u32* cnt = (u32*)(red + C::RED_WORDS);
+    u32* rowoff = cnt;            // during zl_delta the counter area holds the
+    u32* rowlo = cnt + NT;        // current chunk's row offsets and first indices
+
+    const int tid = threadIdx.x;
+    // Consecutive windows share cache lines at their segment ends: give each
+    // XCD (workgroups are dealt round-robin to the 8 XCDs) a contiguous range.
+    const u32 per_xcd = gridDim.x / 8;
+    const u32 logical = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    const i64 b = logical / (u32)max_win;
+    const int j = (int)(logical % (u32)max_win);
+    if (b >= B) return;
+    const InstInfo ii = info[b];
+    if ((ii.flags & EBSP_STATUS_UNSUPPORTED) || j >= (int)ii.nwin) return;
+
+    const u32* ws = winstart + b * (i64)(max_win + 1);
+    const u32 k0 = ws[j], k1 = ws[j + 1];
+    const u32 A = (u32)fine_bin_start(k0, ii.inv);      // window start (relative value)
+    const u64 E = k1 >= ii.nb ? ii.range + 1 : fine_bin_start(k1, ii.inv);   // window end, exclusive
+    const u64 base = (u64)ii.base;
+    const i64* __restrict__ inst = ts + b * (i64)P * R;
+    const u32* __restrict__ cr = cross + (b * (i64)P) * stride;
+
+    // zl_delta
+    int total = 0, bad = 0;
+    u64 w0 = 0;                   // my share of W0 = sum_p (A - value before row p's segment)
+    for (int p0 = 0; p0 < P; p0 += NT) {
+        const int p = p0 + tid;
+        u32 lo = 0, hi = 0;
+        if (p < P) {
+            lo = cr[(i64)p * stride + k0];
+            hi = cr[(i64)p * stride + k1];
+            lo = lo < (u32)R ? lo : (u32)R;
+            hi = hi < (u32)R ? hi : (u32)R;
+            hi = hi > lo ? hi : lo;
+            if (lo > 0) w0 += (u64)A - (((u64)inst[(size_t)p * R + lo - 1]) - base);
+        }
+        u32 chunk;
+        const u32 off = block_excl_scan<u32, NT>(hi - lo, (u32*)red, chunk);
+        rowoff[tid] = off;
+        rowlo[tid] = lo;
+        __syncthreads();
+        const int room = C::CAP - total;
+        const int take = (int)chunk < room ? (int)chunk : room;
+        const int nrows = (P - p0) < NT ? (P - p0) : NT;
+        for (int e = tid; e < take; e += NT) {
+            // row of element e: the last r with rowoff[r] <= e
+            int l = 0, h = nrows;
+            while (h - l > 1) {
+                const int m = (l + h) >> 1;
+                if (rowoff[m] <= (u32)e) l = m; else h = m;
+            }
+            const int i = (int)rowlo[l] + (e - (int)rowoff[l]);
+            const i64* src = inst + (size_t)(p0 + l) * R + i;
+            const i64 cur = src[0];
+            const u32 rel = (u32)((u64)cur - base);
+            u32 prel = A;
+            if (i > 0) {
+                const i64 prv = src[-1];
+                prel = (u32)((u64)prv - base);
+                bad |= (cur < prv);
+            }
+            recs[phys(total + e)] = (u64)(rel - A) | ((u64)(rel - prel) << 32);
+        }
+        total += (int)chunk;          // may exceed CAP: detected below
+        __syncthreads();
+    }
+    const bool oversize = total > C::CAP;
+    if (oversize) total = C::CAP;
+    const int items = (total + NT - 1) / NT;
+    fill_sentinels<NT>(recs, total, items);
+    bad = __syncthreads_or(bad);
+    const u64 W0 = block_reduce<u64, NT>(w0, red, OpAdd());
+
+    u64 best_wait = U64_MAX;
+    u32 best_key = 0;
+    if (!oversize && total > 0) {
+        zl_sort<NT, ITEMS>(recs, cnt, red, items, bit_length(E - 1 - (u64)A));
+        zl_scan_argmin<NT, ITEMS>(recs, red, items, total, A, (u32)ii.thr, (u64)P, W0, best_wait, best_key);
+    }
+    if (tid == 0) {
+        Partial r;
+        r.wait = best_wait;
+        r.brel = (u64)A + best_key;
+        partial[b * (i64)max_win + j] = r;
+        u32 f = (bad ? EBSP_STATUS_UNSORTED : 0) | (oversize ? EBSP_STATUS_UNSUPPORTED : 0);
+        if (f) {
+            atomicOr(&info[b].flags, f);
+            if (status) atomicOr(status + b, (int)f);
+        }
+    }
+}
+
+// zl_iters for the multi-window path: reduce the instance's window results
+// (first minimum: smaller wait, then earlier barrier), then count iterations.
+template <int NT>
+__global__ __launch_bounds__(NT) void zl_finish_kernel(
+    const i64* __restrict__ ts, int P, int R,
+    const InstInfo* __restrict__ info, const Partial* __restrict__ partial, int max_win,
+    i64* __restrict__ barrier, int* __restrict__ iters, i64* __restrict__ wait)
+{
+    __shared__ u64 red[2 * (NT / WAVE)];
+    constexpr int NW = NT / WAVE;
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid >> 6;
+    const u32 pblocks = (u32)(P + NT - 1) / NT;
+    const i64 b = blockIdx.x / pblocks;
+    const int pblk = (int)(blockIdx.x % pblocks);
+    const InstInfo ii = info[b];
+    u64 bw = U64_MAX, bb = U64_MAX;
+    const Partial* pp = partial + b * (i64)max_win;
+    for (int j = tid; j < (int)ii.nwin; j += NT) {
+        const Partial r = pp[j];
+        if (r.wait < bw || (r.wait == bw && r.brel < bb)) { bw = r.wait; bb = r.brel; }
+    }
+#pragma unroll
+    for (int d = WAVE / 2; d > 0; d >>= 1) {
+        const u64 ow = __shfl_xor(bw, d, WAVE), ob = __shfl_xor(bb, d, WAVE);
+        if (ow < bw || (ow == bw && ob < bb)) { bw = ow; bb = ob; }
+    }
+    if (lane == 0) { red[wave] = bw; red[NW + wave] = bb; }
+    __syncthreads();
+    bw = red[0]; bb = red[NW];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) {
+        const u64 ow = red[w], ob = red[NW + w];
+        if (ow < bw || (ow == bw && ob < bb)) { bw = ow; bb = ob; }
+    }
+    if (bw == U64_MAX) bb = 0;
+    const i64 bar = (i64)((u64)ii.base + bb);
+    if (pblk == 0 && tid == 0) { barrier[b] = bar; wait[b] = (i64)bw; }
+    const int p = pblk * NT + tid;
+    if (p < P) iters[b * (i64)P + p] = zl_iters(ts + (b * (i64)P + p) * (i64)R, R, bar);
+}
+
+// ---------------------------------------------------------------------------
+// Host side.
+
+thread_local char g_err[256] = "";
+
+int fail(int code, const char* msg)
+{
+    snprintf(g_err, sizeof g_err, "%s", msg);
+    return code;
+}
+
+enum KernelId { K_INSTANCE = 0, K_BOUNDS, K_PARTITION, K_BINCOUNT, K_PLAN, K_WINDOW, K_FINISH, K_COUNT };
+const char* const kKernelNames[K_COUNT] = {
+    "zl_instance_kernel", "zl_bounds_kernel", "zl_partition_kernel", "zl_bincount_kernel",
+    "zl_plan_kernel", "zl_window_kernel", "zl_finish_kernel"};
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Shape-dependent sizes of the multi-window path.
+struct Plan {
+    bool multi;
+    int bins;          // fine bins per instance
+    int stride;        // bins + 1 crossing indices per row
+    int max_win;       // windows per instance <= max_win
+    size_t off_info, off_cross, off_below, off_winstart, off_partial, bytes;
+};
+
+bool make_plan(i64 B, int P, int R, Plan& pl)
+{
+    if (B < 0 || P < 1 || R < 1) return false;
+    const i64 n = (i64)P * (i64)R;
+    if (n >= (1ll << 31)) return false;
+    memset(&pl, 0, sizeof pl);
+    pl.multi = n > LARGE_CAP;
+    if (!pl.multi) return true;
+    pl.bins = (int)((n + (1 << FINE_SHIFT) - 1) >> FINE_SHIFT);
+    pl.stride = pl.bins + 1;
+    pl.max_win = (int)((n >> GROUP_SHIFT) + 2);
+    size_t o = 0;
+    pl.off_info = o;     o = align_up(o + (size_t)B * sizeof(InstInfo), 256);
+    pl.off_cross = o;    o = align_up(o + (size_t)B * P * pl.stride * sizeof(u32), 256);
+    pl.off_below = o;    o = align_up(o + (size_t)B * pl.stride * sizeof(u32), 256);
+    pl.off_winstart = o; o = align_up(o + (size_t)B * (pl.max_win + 1) * sizeof(u32), 256);
+    pl.off_partial = o;  o = align_up(o + (size_t)B * pl.max_win * sizeof(Partial), 256);
+    pl.bytes = o;
+    return true;
+}
+
+struct Timer {                 // optional per-kernel events
+    hipEvent_t ev[2 * K_COUNT];
+    bool used[K_COUNT];
+    bool on;
+};
+
+#define LAUNCH(kid, kernel, grid, block, ...)                                              \
+    do {                                                                                   \
+        if (tm && tm->on) { (void)hipEventRecord(tm->ev[2 * (kid)], st); tm->used[kid] = true; } \
+        hipLaunchKernelGGL(kernel, grid, block, 0, st, __VA_ARGS__);                       \
+        if (tm && tm->on) (void)hipEventRecord(tm->ev[2 * (kid) + 1], st);                       \
+        hipError_t e_ = hipGetLastError();                                                 \
+        if (e_ != hipSuccess) {                                                            \
+            snprintf(g_err, sizeof g_err, "%s: %s", kKernelNames[kid], hipGetErrorString(e_)); \
+            return EBSP_ERR_LAUNCH;                                                        \
+        }                                                                                  \
+    } while (0)
+
+int run_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters, i64* wait, int* status,
+              void* workspace, size_t workspace_bytes, hipStream_t st, Timer* tm)
+{
+    Plan pl;
+    if (!make_plan(B, P, R, pl)) return fail(EBSP_ERR_SHAPE, "invalid shape: need B >= 0, P >= 1, R >= 1, P*R < 2^31");
+    if (B == 0) return EBSP_OK;
+    if (!ts || !barrier || !iters || !wait) return fail(EBSP_ERR_NULL, "ts, barrier, iters and wait must not be NULL");
+    if (B > 0x7fffffffll) return fail(EBSP_ERR_SHAPE, "B must be below 2^31");
+    const int n = P * R;
+
+    if (!pl.multi) {
+        const int rshift = (R & (R - 1)) == 0 ? __builtin_ctz((unsigned)R) : -1;
+        const dim3 grid((unsigned)B);
+        if (n <= 64)
+            LAUNCH(K_INSTANCE, (zl_instance_kernel<64, 1>), grid, dim3(64), ts, P, R, rshift, barrier, iters, wait, status);
+        else if (n <= 256)
+            LAUNCH(K_INSTANCE, (zl_instance_kernel<64, 4>), grid, dim3(64), ts, P, R, rshift, barrier, iters, wait, status);
+        else if (n <= 1024)
+            LAUNCH(K_INSTANCE, (zl_instance_kernel<256, 4>), grid, dim3(256), ts, P, R, rshift, barrier, iters, wait, status);
+        else if (n <= 4096)
+            LAUNCH(K_INSTANCE, (zl_instance_kernel<512, 8>), grid, dim3(512), ts, P, R, rshift, barrier, iters, wait, status);
+        else
+            LAUNCH(K_INSTANCE, (zl_instance_kernel<1024, 16>), grid, dim3(1024), ts, P, R, rshift, barrier, iters, wait, status);
+        return EBSP_OK;
+    }
+
+    if (!workspace) return fail(EBSP_ERR_NULL, "this shape needs a workspace");
+    if (workspace_bytes < pl.bytes) return fail(EBSP_ERR_WORKSPACE, "workspace smaller than ebsp_zipline_workspace_bytes()");
+    if (((uintptr_t)workspace & 255u) != 0) return fail(EBSP_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    const i64 total_win = B * (i64)pl.max_win;
+    if (total_win + 8 > 0x7fffffffll || B * (i64)P > (0x7fffffffll * 4)) return fail(EBSP_ERR_SHAPE, "batch too large for one call");
+
+    char* wsp = (char*)workspace;
+    InstInfo* info = (InstInfo*)(wsp + pl.off_info);
+    u32* cross = (u32*)(wsp + pl.off_cross);
+    u32* below = (u32*)(wsp + pl.off_below);
+    u32* winstart = (u32*)(wsp + pl.off_winstart);
+    Partial* partial = (Partial*)(wsp + pl.off_partial);
+
+    LAUNCH(K_BOUNDS, (zl_bounds_kernel<256>), dim3((unsigned)B), dim3(256), ts, P, R, pl.bins, info, status);
+    const i64 nrows = B * (i64)P;
+    LAUNCH(K_PARTITION, (zl_partition_kernel<256>), dim3((unsigned)((nrows + 3) / 4)), dim3(256),
+           ts, nrows, P, R, info, cross, pl.stride);
+    const i64 kblocks = (pl.stride + 63) / 64, pblocks = (P + 255) / 256;
+    if (kblocks * B > 0x7fffffffll || pblocks * B > 0x7fffffffll) return fail(EBSP_ERR_SHAPE, "batch too large for one call");
+    LAUNCH(K_BINCOUNT, zl_bincount_kernel, dim3((unsigned)(kblocks * B)), dim3(256),
+           cross, P, R, pl.stride, info, below);
+    LAUNCH(K_PLAN, (zl_plan_kernel<1024>), dim3((unsigned)B), dim3(1024), info, below, pl.stride, winstart, pl.max_win);
+    const unsigned wgrid = (unsigned)((total_win + 7) / 8 * 8);
+    LAUNCH(K_WINDOW, (zl_window_kernel<LARGE_NT, LARGE_ITEMS>), dim3(wgrid), dim3(LARGE_NT),
+           ts, B, P, R, info, cross, pl.stride, winstart, pl.max_win, partial, status);
+    LAUNCH(K_FINISH, (zl_finish_kernel<256>), dim3((unsigned)(pblocks * B)), dim3(256),
+           ts, P, R, info, partial, pl.max_win, barrier, iters, wait);
+    return EBSP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t ebsp_zipline_workspace_bytes(int64_t B, int32_t P, int32_t R)
+{
+    Plan pl;
+    if (!make_plan(B, P, R, pl)) return 0;
+    return pl.multi ? pl.bytes : 0;
+}
+
+int ebsp_zipline_batch(const int64_t* ts, int64_t B, int32_t P, int32_t R,
+                       int64_t* barrier, int32_t* iters, int64_t* wait,
+                       int32_t* status, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return run_batch((const i64*)ts, B, P, R, (i64*)barrier, iters, (i64*)wait, status,
+                     workspace, workspace_bytes, (hipStream_t)stream, nullptr);
+}
+
+int ebsp_zipline_batch_timed(const int64_t* ts, int64_t B, int32_t P, int32_t R,
+                             int64_t* barrier, int32_t* iters, int64_t* wait,
+                             int32_t* status, void* workspace, size_t workspace_bytes,
+                             void* stream, float* kernel_ms)
+{
+    if (!kernel_ms) return fail(EBSP_ERR_NULL, "kernel_ms must not be NULL");
+    Timer tm;
+    tm.on = true;
+    for (int i = 0; i < K_COUNT; ++i) { tm.used[i] = false; kernel_ms[i] = 0.f; }
+    for (int i = 0; i < 2 * K_COUNT; ++i)
+        if (hipEventCreate(&tm.ev[i]) != hipSuccess) {
+            for (int k = 0; k < i; ++k) (void)hipEventDestroy(tm.ev[k]);
+            return fail(EBSP_ERR_LAUNCH, "hipEventCreate failed");
+        }
+    int rc = run_batch((const i64*)ts, B, P, R, (i64*)barrier, iters, (i64*)wait, status,
+                       workspace, workspace_bytes, (hipStream_t)stream, &tm);
+    if (rc == EBSP_OK) {
+        if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess)
+            rc = fail(EBSP_ERR_LAUNCH, "hipStreamSynchronize failed");
+        else
+            for (int i = 0; i < K_COUNT; ++i)
+                if (tm.used[i]) (void)hipEventElapsedTime(&kernel_ms[i], tm.ev[2 * i], tm.ev[2 * i + 1]);
+    }
+    for (int i = 0; i < 2 * K_COUNT; ++i) (void)hipEventDestroy(tm.ev[i]);
+    return rc;
+}
+
+int ebsp_zipline_kernel_count(void) { return K_COUNT; }
+
+const char* ebsp_zipline_kernel_name(int i) { return (i >= 0 && i < K_COUNT) ? kKernelNames[i] : nullptr; }
+
+const char* ebsp_last_error(void) { return g_err; }
+
+}  // extern "C"

@@ -1,0 +1,129 @@
+"""ctypes binding of libebsp_zipline.so (see include/ebsp_zipline.h).
+
+Argument marshalling only: every step of the search runs in the HIP kernels.
+PyTorch supplies device memory (``torch.empty``) and the current stream.  The
+library must have been built (``python -m paper_2001_01347_amd.build`` or
+``__graft_entry__.build()``); if it is missing the first call raises -- there
+is no fallback of any kind.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libebsp_zipline.so")
+
+EBSP_OK = 0
+STATUS_OK, STATUS_UNSORTED, STATUS_OVERFLOW, STATUS_UNSUPPORTED = 0, 1, 2, 4
+
+EXPORTS = ("ebsp_zipline_workspace_bytes", "ebsp_zipline_batch", "ebsp_zipline_batch_timed",
+           "ebsp_zipline_kernel_count", "ebsp_zipline_kernel_name", "ebsp_last_error")
+
+_lib = None
+
+
+class ZipLineError(RuntimeError):
+    pass
+
+
+def load() -> ctypes.CDLL:
+    """Load the HIP library (once). Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ZipLineError(f"{LIB_PATH} is missing: build it first "
+                               "(python -m paper_2001_01347_amd.build); there is no CPU fallback")
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
+        lib.ebsp_zipline_workspace_bytes.restype = sz
+        lib.ebsp_zipline_workspace_bytes.argtypes = [i64, i32, i32]
+        common = [vp, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+        lib.ebsp_zipline_batch.restype = ctypes.c_int
+        lib.ebsp_zipline_batch.argtypes = common
+        lib.ebsp_zipline_batch_timed.restype = ctypes.c_int
+        lib.ebsp_zipline_batch_timed.argtypes = common + [ctypes.POINTER(ctypes.c_float)]
+        lib.ebsp_zipline_kernel_count.restype = ctypes.c_int
+        lib.ebsp_zipline_kernel_count.argtypes = []
+        lib.ebsp_zipline_kernel_name.restype = ctypes.c_char_p
+        lib.ebsp_zipline_kernel_name.argtypes = [ctypes.c_int]
+        lib.ebsp_last_error.restype = ctypes.c_char_p
+        lib.ebsp_last_error.argtypes = []
+        _lib = lib
+    return _lib
+
+
+def ebsp_last_error() -> str:
+    return load().ebsp_last_error().decode()
+
+
+def ebsp_zipline_workspace_bytes(B: int, P: int, R: int) -> int:
+    return int(load().ebsp_zipline_workspace_bytes(B, P, R))
+
+
+def ebsp_zipline_kernel_names() -> Tuple[str, ...]:
+    lib = load()
+    return tuple(lib.ebsp_zipline_kernel_name(i).decode() for i in range(lib.ebsp_zipline_kernel_count()))
+
+
+def _check(ts: torch.Tensor) -> Tuple[int, int, int]:
+    if ts.dim() != 3 or ts.dtype != torch.int64 or not ts.is_cuda or not ts.is_contiguous():
+        raise ValueError("ts must be a contiguous int64 CUDA tensor of shape [B, P, R]")
+    return tuple(int(x) for x in ts.shape)
+
+
+def _prepare(ts, barrier, iters, wait, status, workspace):
+    B, P, R = _check(ts)
+    dev = ts.device
+    if barrier is None:
+        barrier = torch.empty(B, dtype=torch.int64, device=dev)
+    if iters is None:
+        iters = torch.empty((B, P), dtype=torch.int32, device=dev)
+    if wait is None:
+        wait = torch.empty(B, dtype=torch.int64, device=dev)
+    if status is None:
+        status = torch.empty(B, dtype=torch.int32, device=dev)
+    need = ebsp_zipline_workspace_bytes(B, P, R)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    stream = torch.cuda.current_stream(dev).cuda_stream
+    args = [ts.data_ptr(), B, P, R, barrier.data_ptr(), iters.data_ptr(), wait.data_ptr(),
+            status.data_ptr(), ws_ptr, ws_len, stream]
+    return args, (barrier, iters, wait, status)
+
+
+def ebsp_zipline_batch(ts: torch.Tensor, barrier: Optional[torch.Tensor] = None,
+                       iters: Optional[torch.Tensor] = None, wait: Optional[torch.Tensor] = None,
+                       status: Optional[torch.Tensor] = None,
+                       workspace: Optional[torch.Tensor] = None):
+    """Enqueue the batched search on the current stream of ``ts``'s device.
+
+    Returns ``(barrier[B], iters[B, P], wait[B], status[B])`` device tensors
+    (the ones passed in, or new ones).  Does not synchronise.
+    """
+    args, outs = _prepare(ts, barrier, iters, wait, status, workspace)
+    with torch.cuda.device(ts.device):
+        rc = load().ebsp_zipline_batch(*args)
+    if rc != EBSP_OK:
+        raise ZipLineError(f"ebsp_zipline_batch failed ({rc}): {ebsp_last_error()}")
+    return outs
+
+
+def ebsp_zipline_batch_timed(ts: torch.Tensor, barrier=None, iters=None, wait=None, status=None,
+                             workspace=None) -> Tuple[tuple, Dict[str, float]]:
+    """As :func:`ebsp_zipline_batch`, synchronising and returning per-kernel milliseconds."""
+    args, outs = _prepare(ts, barrier, iters, wait, status, workspace)
+    lib = load()
+    n = lib.ebsp_zipline_kernel_count()
+    ms = (ctypes.c_float * n)()
+    with torch.cuda.device(ts.device):
+        rc = lib.ebsp_zipline_batch_timed(*args, ms)
+    if rc != EBSP_OK:
+        raise ZipLineError(f"ebsp_zipline_batch_timed failed ({rc}): {ebsp_last_error()}")
+    names = ebsp_zipline_kernel_names()
+    return outs, {names[i]: float(ms[i]) for i in range(n)}
