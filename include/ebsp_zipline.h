@@ -80,16 +80,19 @@ int ebsp_zipline_batch(const int64_t* ts, int64_t B, int32_t P, int32_t R,
                        void* stream);
 
 /*
- * The same call with per-kernel timing, for benchmarks: HIP events are
- * recorded on `stream` around every kernel, the stream is synchronised, and
- * kernel_ms[i] (HOST array of ebsp_zipline_kernel_count() floats) receives the
- * duration of kernel i in milliseconds (0 for kernels this shape does not
- * launch).  Creates and destroys HIP events; otherwise as ebsp_zipline_batch.
+ * Per-kernel timing for benchmarks.  Between ebsp_zipline_profile_begin() and
+ * ebsp_zipline_profile_end() every ebsp_zipline_batch call made by the calling
+ * thread records a pair of HIP events around each kernel it launches, on the
+ * call's own stream, without synchronising (events are created up front, for
+ * at most max_calls calls; further calls run untimed).
+ * ebsp_zipline_profile_end() synchronises the device, writes to kernel_ms
+ * (HOST array of ebsp_zipline_kernel_count() floats, may be NULL) the summed
+ * duration in milliseconds of each kernel over the profiled calls and to
+ * *calls (may be NULL) their number, and destroys the events.
+ * These two calls allocate and free host memory and HIP events.
  */
-int ebsp_zipline_batch_timed(const int64_t* ts, int64_t B, int32_t P, int32_t R,
-                             int64_t* barrier, int32_t* iters, int64_t* wait,
-                             int32_t* status, void* workspace, size_t workspace_bytes,
-                             void* stream, float* kernel_ms);
+int ebsp_zipline_profile_begin(int32_t max_calls);
+int ebsp_zipline_profile_end(float* kernel_ms, int32_t* calls);
 
 /* Number of distinct kernels the library may launch, and their names
  * (static storage; NULL if i is out of range). */

@@ -59,10 +59,12 @@ struct InstInfo {
     i64 base;    // min_p t[p][0]; all other values are relative to it
     u64 range;   // max_p t[p][R-1] - base
     u64 thr;     // max_p t[p][0] - base: earliest admissible barrier
-    u32 inv;     // fine bin of relative value v is (v * inv) >> 32
+    u32 inv;     // fine bin of relative value v is ((v >> wshift) * inv) >> 32
+    u32 wshift;  // 0 unless the range needs more than 32 bits
     u32 nb;      // number of fine bins, bin(range) + 1
     u32 nwin;    // number of windows (set by zl_plan)
     u32 flags;   // EBSP_STATUS_* bits found so far
+    u32 pad_;
 };
 
 struct Partial {  // best candidate of one window
@@ -128,16 +130,61 @@ __device__ __forceinline__ T block_reduce(T v, T* red, Op op)
 
 __device__ __forceinline__ int bit_length(u64 x) { return x ? 64 - __clzll((long long)x) : 0; }
 
-// Fine-bin grid of an instance whose range fits 32 bits: a monotone map of
-// relative values onto [0, nb).
-__device__ __forceinline__ u32 fine_bin(u64 rel, u64 range, u32 inv, u32 nb)
+// Fine-bin grid of an instance: a monotone map of relative values onto [0, nb).
+__device__ __forceinline__ u32 fine_bin(u64 rel, const InstInfo& ii)
 {
-    if (rel > range) rel = range;                    // only reachable for unsorted rows
-    const u32 k = (u32)((rel * (u64)inv) >> 32);
-    return k < nb ? k : nb - 1;
+    if (rel > ii.range) rel = ii.range;              // only reachable for unsorted rows
+    const u32 k = (u32)(((rel >> ii.wshift) * (u64)ii.inv) >> 32);
+    return k < ii.nb ? k : ii.nb - 1;
 }
 // Smallest relative value that falls in bin k or later.
-__device__ __forceinline__ u64 fine_bin_start(u32 k, u32 inv) { return (((u64)k << 32) + inv - 1) / inv; }
+__device__ __forceinline__ u64 fine_bin_start(u32 k, const InstInfo& ii)
+{
+    return ((((u64)k << 32) + ii.inv - 1) / ii.inv) << ii.wshift;
+}
+
+// ---------------------------------------------------------------------------
+// Rows of one instance and, per row, the index range under consideration:
+// the whole row, or [cross[p][k0], cross[p][k1]) from zl_partition.
+struct Rows {
+    const i64* inst;
+    int P, R;
+    u64 base;
+    const u32* cr;      // crossing indices of this instance, or nullptr for whole rows
+    int stride;
+    u32 k0, k1;
+
+    __device__ __forceinline__ void range(int p, u32& lo, u32& hi) const
+    {
+        if (!cr) { lo = 0; hi = (u32)R; return; }
+        lo = cr[(i64)p * stride + k0];
+        hi = cr[(i64)p * stride + k1];
+        lo = lo < (u32)R ? lo : (u32)R;               // stale scratch (unsorted rows) cannot
+        hi = hi < (u32)R ? hi : (u32)R;               // lead outside the row
+        hi = hi > lo ? hi : lo;
+    }
+    __device__ __forceinline__ u64 rel(int p, u32 i) const { return (u64)inst[(size_t)p * R + i] - base; }
+};
+
+// First index in [lo, hi) of row p whose relative value is >= v (hi if none).
+__device__ __forceinline__ u32 row_lower_bound(const Rows& rw, int p, u32 lo, u32 hi, u64 v)
+{
+    while (lo < hi) {
+        const u32 m = (lo + hi) >> 1;
+        if (rw.rel(p, m) < v) lo = m + 1; else hi = m;
+    }
+    return lo;
+}
+
+// Index range of row p inside the value interval [a, el] (both inclusive).
+// lx / rx: the interval starts / ends exactly where the row ranges do.
+__device__ __forceinline__ void sub_range(const Rows& rw, int p, u64 a, u64 el, bool lx, bool rx,
+                                          u32& lo, u32& hi)
+{
+    rw.range(p, lo, hi);
+    if (!lx) lo = row_lower_bound(rw, p, lo, hi, a);
+    if (!rx && el != U64_MAX) hi = row_lower_bound(rw, p, lo, hi, el + 1);
+}
 
 // ---------------------------------------------------------------------------
 // zl_iters: number of entries of a sorted row that are <= v.
@@ -154,10 +201,12 @@ __device__ __forceinline__ int zl_iters(const i64* __restrict__ row, int R, i64 
 // ---------------------------------------------------------------------------
 // Window workgroup: LDS layout and the sort/scan/argmin steps.
 //
-// A record is (key: low 32 bits, delta: high 32 bits), both relative values
-// that fit 32 bits because the instance's range does.  Record q lives at
-// recs[q + (q >> 4)]: one pad slot per 16 records keeps both the wave-striped
-// access of the sort and the 16-per-thread blocked access of the scan free of
+// A record is (key: low 32 bits, delta: high 32 bits).  Keys are relative to
+// the window start and windows are at most 2^32 wide.  Deltas fit 32 bits when
+// the instance's range does; otherwise (WIDE) the upper half of each delta
+// lives in a second plane and a window holds half as many records.  Record q
+// lives at slot q + (q >> 4): one pad slot per 16 records keeps both the
+// wave-striped access of the sort and the blocked access of the scan free of
 // bank conflicts.
 template <int NT, int ITEMS>
 struct WinCfg {
@@ -166,10 +215,33 @@ struct WinCfg {
     static constexpr int DB_MAX = NT >= 256 ? 8 : 6;     // widest radix digit (one thread per digit value)
     static constexpr int RADIX_MAX = 1 << DB_MAX;
     static constexpr int RECS = CAP + CAP / 16 + 2;
+    static constexpr int CAP_WIDE = CAP / 2 > 0 ? CAP / 2 : 1;
+    static constexpr int ITEMS_WIDE = ITEMS / 2 > 0 ? ITEMS / 2 : 1;
+    static constexpr int RECS_WIDE = NT * ITEMS_WIDE + NT * ITEMS_WIDE / 16 + 2;
+    static constexpr size_t REC_BYTES = (size_t)RECS * 8 > (size_t)RECS_WIDE * 12 ? (size_t)RECS * 8 : (size_t)RECS_WIDE * 12;
     static constexpr int CNT_WORDS = (NW * RADIX_MAX > 2 * NT) ? NW * RADIX_MAX : 2 * NT;
     static constexpr int RED_WORDS = 2 * NW + 8;          // u64 scratch for scans and reductions
-    static constexpr size_t BYTES = (size_t)RECS * 8 + (size_t)RED_WORDS * 8 + (size_t)CNT_WORDS * 4;
+    static constexpr size_t BYTES = (REC_BYTES + 15) / 16 * 16 + (size_t)RED_WORDS * 8 + (size_t)CNT_WORDS * 4;
 };
+
+struct Smem {       // carved from one static LDS array
+    u64* recs;      // record plane
+    u32* dhi;       // upper halves of the deltas (WIDE only)
+    u64* red;       // reduction scratch
+    u32* cnt;       // per-wave digit counters; row offsets while loading
+};
+
+template <int NT, int ITEMS>
+__device__ __forceinline__ Smem carve(unsigned char* smem)
+{
+    using C = WinCfg<NT, ITEMS>;
+    Smem s;
+    s.recs = (u64*)smem;
+    s.dhi = (u32*)(s.recs + C::RECS_WIDE);
+    s.red = (u64*)(smem + (C::REC_BYTES + 15) / 16 * 16);
+    s.cnt = (u32*)(s.red + C::RED_WORDS);
+    return s;
+}
 
 __device__ __forceinline__ int phys(int q) { return q + (q >> 4); }
 
@@ -193,10 +265,13 @@ __device__ __forceinline__ u64 match_digit(u32 d, int dbits)
 // round j lane l holds position w*64*items + j*64 + l.  Ranks within a wave
 // come from ballots, per-wave digit counts live in cnt[w][digit]; a digit-major
 // scan of those counts gives every (wave, digit) its first output position.
-template <int NT, int ITEMS>
-__device__ __forceinline__ void zl_sort(u64* recs, u32* cnt, u64* red, int items, int kbits)
+template <int NT, int ITEMS, bool WIDE>
+__device__ __forceinline__ void zl_sort(const Smem& sm, int items, int kbits)
 {
     using C = WinCfg<NT, ITEMS>;
+    constexpr int IT = WIDE ? C::ITEMS_WIDE : ITEMS;
+    u64* recs = sm.recs;
+    u32* cnt = sm.cnt;
     const int tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid >> 6;
     if (kbits <= 0) return;
     const int npass = (kbits + C::DB_MAX - 1) / C::DB_MAX;
@@ -209,13 +284,14 @@ __device__ __forceinline__ void zl_sort(u64* recs, u32* cnt, u64* red, int items
     for (int pass = 0; pass < npass; ++pass) {
         const int sh = pass * dbits;
         for (u32 d = lane; d < radix; d += WAVE) mycnt[d] = 0;
-        u32 key[ITEMS], dl[ITEMS], rank[ITEMS];
+        u32 key[IT], dl[IT], dh[WIDE ? IT : 1], rank[IT];
 #pragma unroll
-        for (int j = 0; j < ITEMS; ++j) {
+        for (int j = 0; j < IT; ++j) {
             if (j < items) {
                 const u64 r = recs[phys(wbase + j * WAVE)];
                 key[j] = (u32)r;
                 dl[j] = (u32)(r >> 32);
+                if (WIDE) dh[j] = sm.dhi[phys(wbase + j * WAVE)];
                 const u32 d = (key[j] >> sh) & dmask;
                 const u64 peers = match_digit(d, dbits);
                 const u32 below = __popcll(peers & lt);
@@ -232,7 +308,7 @@ __device__ __forceinline__ void zl_sort(u64* recs, u32* cnt, u64* red, int items
             for (int w = 0; w < C::NW; ++w) mine += cnt[w * C::RADIX_MAX + tid];
         }
         u32 all;
-        u32 run = block_excl_scan<u32, NT>(mine, (u32*)red, all);
+        u32 run = block_excl_scan<u32, NT>(mine, (u32*)sm.red, all);
         if ((u32)tid < radix) {
 #pragma unroll 4
             for (int w = 0; w < C::NW; ++w) {
@@ -243,11 +319,12 @@ __device__ __forceinline__ void zl_sort(u64* recs, u32* cnt, u64* red, int items
         }
         __syncthreads();
 #pragma unroll
-        for (int j = 0; j < ITEMS; ++j) {
+        for (int j = 0; j < IT; ++j) {
             if (j < items) {
                 const u32 d = (key[j] >> sh) & dmask;
                 const int pos = (int)(mycnt[d] + rank[j]);
                 recs[phys(pos)] = (u64)key[j] | ((u64)dl[j] << 32);
+                if (WIDE) sm.dhi[phys(pos)] = dh[j];
             }
         }
         __syncthreads();
@@ -257,21 +334,26 @@ __device__ __forceinline__ void zl_sort(u64* recs, u32* cnt, u64* red, int items
 // zl_scan + zl_argmin over the sorted records [0, total).
 // Thread t owns positions [t*items, (t+1)*items).  S(q) = inclusive prefix of
 // the deltas; candidate at q if it ends a run of equal keys and
-// A + key >= thr; value  P*key + W0 - S(q)  (all arithmetic modulo 2^64; the
+// a + key >= thr; value  P*key + W0 - S(q)  (all arithmetic modulo 2^64; the
 // true value is in [0, 2^63) by the caller's precondition).
 // Returns the block-wide first minimum: (wait, key) with wait == U64_MAX if
 // there is no candidate.
-template <int NT, int ITEMS>
-__device__ __forceinline__ void zl_scan_argmin(const u64* recs, u64* red, int items, int total,
-                                               u32 A, u32 thr, u64 P, u64 W0,
+template <int NT, bool WIDE>
+__device__ __forceinline__ void zl_scan_argmin(const Smem& sm, int items, int total,
+                                               u64 a, u64 thr, u64 P, u64 W0,
                                                u64& best_wait, u32& best_key)
 {
+    const u64* recs = sm.recs;
+    u64* red = sm.red;
     const int tid = threadIdx.x;
     const int q0 = tid * items;
     int qe = q0 + items;
     if (qe > total) qe = total;
     u64 local = 0;
-    for (int q = q0; q < qe; ++q) local += recs[phys(q)] >> 32;
+    for (int q = q0; q < qe; ++q) {
+        local += recs[phys(q)] >> 32;
+        if (WIDE) local += (u64)sm.dhi[phys(q)] << 32;
+    }
     u64 sum_all;
     u64 S = block_excl_scan<u64, NT>(local, red, sum_all);
 
@@ -281,10 +363,11 @@ __device__ __forceinline__ void zl_scan_argmin(const u64* recs, u64* red, int it
     for (int q = q0; q < qe; ++q) {
         const u32 key = (u32)r;
         S += r >> 32;
+        if (WIDE) S += (u64)sm.dhi[phys(q)] << 32;
         const bool has_next = q + 1 < total;
         const u64 rn = has_next ? recs[phys(q + 1)] : 0ull;
         const bool run_end = !has_next || (u32)rn != key;
-        const bool admissible = (u64)A + key >= (u64)thr;
+        const bool admissible = a + key >= thr;
         if (run_end && admissible) {
             const u64 w = P * (u64)key + W0 - S;
             if (w < bw) { bw = w; bq = (u32)q; bk = key; }
@@ -322,6 +405,157 @@ __device__ __forceinline__ void fill_sentinels(u64* recs, int total, int items)
     for (int q = total + threadIdx.x; q < NT * items; q += NT) recs[phys(q)] = 0x00000000ffffffffull;
 }
 
+// zl_delta for a value interval [a, el] (el - a < 2^32) of the rows in `rw`:
+// gathers every row's segment into records (key = value - a, delta = value -
+// the row's previous value, or value - a for a row's very first entry) in
+// slots [0, total).  At most `cap` records are stored; the true total is
+// returned.  w0 accumulates this thread's share of W0 = sum_p (a - last value
+// of row p before the interval).  Rows are taken NT at a time: a block scan of
+// the segment lengths gives every row its first slot, then consecutive threads
+// take consecutive slots, so reads within a segment coalesce.
+template <int NT, bool WIDE>
+__device__ __forceinline__ int zl_delta(const Smem& sm, const Rows& rw, u64 a, u64 el, bool lx, bool rx,
+                                        int cap, u64& w0, int& bad)
+{
+    const int tid = threadIdx.x;
+    u32* rowoff = sm.cnt;
+    u32* rowlo = sm.cnt + NT;
+    int total = 0;
+    for (int p0 = 0; p0 < rw.P; p0 += NT) {
+        const int p = p0 + tid;
+        u32 lo = 0, hi = 0;
+        if (p < rw.P) {
+            sub_range(rw, p, a, el, lx, rx, lo, hi);
+            if (lo > 0) w0 += a - rw.rel(p, lo - 1);
+        }
+        u32 chunk;
+        const u32 off = block_excl_scan<u32, NT>(hi - lo, (u32*)sm.red, chunk);
+        rowoff[tid] = off;
+        rowlo[tid] = lo;
+        __syncthreads();
+        const int room = cap - total;
+        const int take = (int)chunk < room ? (int)chunk : room;
+        const int nrows = (rw.P - p0) < NT ? (rw.P - p0) : NT;
+        for (int e = tid; e < take; e += NT) {
+            int l = 0, h = nrows;                 // the last row r with rowoff[r] <= e
+            while (h - l > 1) {
+                const int m = (l + h) >> 1;
+                if (rowoff[m] <= (u32)e) l = m; else h = m;
+            }
+            const u32 i = rowlo[l] + ((u32)e - rowoff[l]);
+            const i64* src = rw.inst + (size_t)(p0 + l) * rw.R + i;
+            const i64 cur = src[0];
+            const u64 rel = (u64)cur - rw.base;
+            u64 prel = a;
+            if (i > 0) {
+                const i64 prv = src[-1];
+                prel = (u64)prv - rw.base;
+                bad |= (cur < prv);
+            }
+            const u64 dl = rel - prel;
+            const int slot = phys(total + e);
+            sm.recs[slot] = (u64)(u32)(rel - a) | (dl << 32);
+            if (WIDE) sm.dhi[slot] = (u32)(dl >> 32);
+        }
+        total += (int)chunk;
+        __syncthreads();
+    }
+    return total;
+}
+
+// Number of entries of the rows inside [a, el].
+template <int NT>
+__device__ __forceinline__ u32 count_interval(const Smem& sm, const Rows& rw, u64 a, u64 el, bool lx)
+{
+    u32 c = 0;
+    for (int p = threadIdx.x; p < rw.P; p += NT) {
+        u32 lo, hi;
+        sub_range(rw, p, a, el, lx, false, lo, hi);
+        c += hi - lo;
+    }
+    return block_reduce<u32, NT>(c, (u32*)sm.red, OpAdd());
+}
+
+// Search one value interval [A, Elast] of the rows in `rw`: the general form of
+// zl_delta -> zl_sort -> zl_scan -> zl_argmin.  Normally the interval is at
+// most 2^32 wide and holds at most `cap` entries and is handled in one go.
+// Otherwise it is walked in pieces that do fit, cut by bisection on the value;
+// a single value that alone occurs more than `cap` times is one candidate and
+// is evaluated directly from the rows.  (bw, bb) is updated with the first
+// minimum found: smaller wait, then smaller barrier (relative to base).
+template <int NT, int ITEMS, bool WIDE>
+__device__ __forceinline__ void zl_window(const Smem& sm, const Rows& rw, u64 thr, u64 A, u64 Elast,
+                                          u64& bw, u64& bb, int& bad)
+{
+    using C = WinCfg<NT, ITEMS>;
+    constexpr int CAPW = WIDE ? C::CAP_WIDE : C::CAP;
+    u64 a = A;
+    bool lx = true;
+    for (;;) {
+        u64 el = Elast;
+        bool rx = true;
+        if (el - a > 0xffffffffull) { el = a + 0xffffffffull; rx = false; }
+        u64 w0 = 0;
+        int total = zl_delta<NT, WIDE>(sm, rw, a, el, lx, rx, CAPW, w0, bad);
+        bool single = false;
+        if (total > CAPW) {
+            if (count_interval<NT>(sm, rw, a, a, lx) > (u32)CAPW) {
+                single = true;                     // the value `a` alone overflows a window
+                el = a;
+            } else {
+                u64 l = a, h = el;                 // count(a, l) <= CAPW < count(a, h)
+                while (h - l > 1) {
+                    const u64 m = l + ((h - l) >> 1);
+                    if (count_interval<NT>(sm, rw, a, m, lx) <= (u32)CAPW) l = m; else h = m;
+                }
+                el = l;
+                w0 = 0;
+                total = zl_delta<NT, WIDE>(sm, rw, a, el, lx, false, CAPW, w0, bad);
+            }
+            rx = false;
+        }
+        if (single) {
+            // candidate c = a: every row stops at its last entry <= a
+            u64 s = 0;
+            int missing = 0;
+            for (int p = threadIdx.x; p < rw.P; p += NT) {
+                u32 lo, hi;
+                sub_range(rw, p, a, a, lx, false, lo, hi);
+                if (hi > 0) s += a - rw.rel(p, hi - 1); else missing = 1;
+            }
+            const u64 w = block_reduce<u64, NT>(s, sm.red, OpAdd());
+            missing = __syncthreads_or(missing);
+            if (!missing && a >= thr && (w < bw || (w == bw && a < bb))) { bw = w; bb = a; }
+        } else if (total > 0) {
+            const int items = (total + NT - 1) / NT;
+            fill_sentinels<NT>(sm.recs, total, items);
+            const u64 W0 = block_reduce<u64, NT>(w0, sm.red, OpAdd());   // also orders the record writes
+            zl_sort<NT, ITEMS, WIDE>(sm, items, bit_length(el - a));
+            u64 w;
+            u32 key;
+            zl_scan_argmin<NT, WIDE>(sm, items, total, a, thr, (u64)rw.P, W0, w, key);
+            if (w != U64_MAX && (w < bw || (w == bw && a + key < bb))) { bw = w; bb = a + key; }
+        }
+        if (rx) break;
+        // continue at the smallest entry above el, if any
+        u64 nxt = U64_MAX;
+        int have = 0;
+        if (el != U64_MAX) {
+            for (int p = threadIdx.x; p < rw.P; p += NT) {
+                u32 lo, hi;
+                rw.range(p, lo, hi);
+                const u32 i = row_lower_bound(rw, p, lo, hi, el + 1);
+                if (i < hi) { const u64 v = rw.rel(p, i); nxt = v < nxt ? v : nxt; have = 1; }
+            }
+        }
+        nxt = block_reduce<u64, NT>(nxt, sm.red, OpMin());
+        have = __syncthreads_or(have);
+        if (!have || nxt > Elast || nxt <= el) break;
+        a = nxt;
+        lx = false;
+    }
+}
+
 // ---------------------------------------------------------------------------
 // One workgroup per instance (P*R <= NT*ITEMS): the whole search in LDS.
 template <int NT, int ITEMS>
@@ -332,9 +566,7 @@ __global__ __launch_bounds__(NT) void zl_instance_kernel(
 {
     using C = WinCfg<NT, ITEMS>;
     __shared__ __align__(16) unsigned char smem[C::BYTES];
-    u64* recs = (u64*)smem;
-    u64* red = recs + C::RECS;
-    u32* cnt = (u32*)(red + C::RED_WORDS);
+    const Smem sm = carve<NT, ITEMS>(smem);
 
     const int tid = threadIdx.x;
     const i64 b = blockIdx.x;
@@ -349,19 +581,19 @@ __global__ __launch_bounds__(NT) void zl_instance_kernel(
         mxf = f > mxf ? f : mxf;
         mxl = l > mxl ? l : mxl;
     }
-    const i64 base = block_reduce<i64, NT>(mn, (i64*)red, OpMin());
-    const i64 first_max = block_reduce<i64, NT>(mxf, (i64*)red, OpMax());
-    const i64 last_max = block_reduce<i64, NT>(mxl, (i64*)red, OpMax());
+    const i64 base = block_reduce<i64, NT>(mn, (i64*)sm.red, OpMin());
+    const i64 first_max = block_reduce<i64, NT>(mxf, (i64*)sm.red, OpMax());
+    const i64 last_max = block_reduce<i64, NT>(mxl, (i64*)sm.red, OpMax());
     const u64 range = (u64)last_max - (u64)base;
     const u64 thr = (u64)first_max - (u64)base;
 
     u32 flags = 0;
     if (range > (u64)INT64_MAX / (u64)P) flags |= EBSP_STATUS_OVERFLOW;
-    if (range >> 32) flags |= EBSP_STATUS_UNSUPPORTED;
 
-    // zl_delta: records in memory order (row p occupies [p*R, (p+1)*R))
     int bad = 0;
-    if (!(flags & EBSP_STATUS_UNSUPPORTED)) {
+    u64 best_wait = U64_MAX, best_rel = 0;
+    if (!(range >> 32)) {
+        // zl_delta in memory order (row p occupies slots [p*R, (p+1)*R)): no row lookup
         for (int e = tid; e < n; e += NT) {
             const int i = rshift >= 0 ? (e & (R - 1)) : (e % R);
             const i64 cur = inst[e];
@@ -372,20 +604,23 @@ __global__ __launch_bounds__(NT) void zl_instance_kernel(
                 prel = (u32)((u64)prv - (u64)base);
                 bad |= (cur < prv);
             }
-            recs[phys(e)] = (u64)rel | ((u64)(rel - prel) << 32);
+            sm.recs[phys(e)] = (u64)rel | ((u64)(rel - prel) << 32);
         }
+        const int items = (n + NT - 1) / NT;
+        fill_sentinels<NT>(sm.recs, n, items);
+        __syncthreads();
+        zl_sort<NT, ITEMS, false>(sm, items, bit_length(range));
+        u32 key;
+        zl_scan_argmin<NT, false>(sm, items, n, 0ull, thr, (u64)P, 0ull, best_wait, key);
+        best_rel = key;
+    } else {
+        Rows rw;
+        rw.inst = inst; rw.P = P; rw.R = R; rw.base = (u64)base;
+        rw.cr = nullptr; rw.stride = 0; rw.k0 = rw.k1 = 0;
+        zl_window<NT, ITEMS, true>(sm, rw, thr, 0ull, range, best_wait, best_rel, bad);
     }
-    const int items = (n + NT - 1) / NT;
-    fill_sentinels<NT>(recs, n, items);
     if (__syncthreads_or(bad)) flags |= EBSP_STATUS_UNSORTED;
-
-    u64 best_wait = U64_MAX;
-    u32 best_key = 0;
-    if (!(flags & EBSP_STATUS_UNSUPPORTED)) {
-        zl_sort<NT, ITEMS>(recs, cnt, red, items, bit_length(range));
-        zl_scan_argmin<NT, ITEMS>(recs, red, items, n, 0u, (u32)thr, (u64)P, 0ull, best_wait, best_key);
-    }
-    const i64 bar = (i64)((u64)base + (u64)best_key);
+    const i64 bar = (i64)((u64)base + best_rel);
     if (tid == 0) {
         barrier[b] = bar;
         wait[b] = (i64)best_wait;
@@ -425,17 +660,16 @@ __global__ __launch_bounds__(NT) void zl_bounds_kernel(
         ii.thr = (u64)first_max - (u64)base;
         ii.nwin = 0;
         ii.flags = 0;
+        ii.pad_ = 0;
         if (ii.range > (u64)INT64_MAX / (u64)P) ii.flags |= EBSP_STATUS_OVERFLOW;
-        if (ii.range >> 32) ii.flags |= EBSP_STATUS_UNSUPPORTED;
-        // bins equal slices of [0, range]: inv = bins * 2^32 / (range + 1), capped to 32 bits
-        ii.inv = 0xffffffffu;
-        ii.nb = 1;
-        if (!(ii.flags & EBSP_STATUS_UNSUPPORTED)) {
-            const u64 q = ((u64)bins << 32) / (ii.range + 1);
-            ii.inv = q < 0xffffffffull ? (u32)q : 0xffffffffu;
-            if (ii.inv == 0) ii.inv = 1;
-            ii.nb = (u32)((ii.range * (u64)ii.inv) >> 32) + 1u;
-        }
+        // bins are equal slices of [0, range >> wshift]: inv = bins * 2^32 / (top + 1), capped to 32 bits
+        const int bl = bit_length(ii.range);
+        ii.wshift = bl > 32 ? (u32)(bl - 32) : 0u;
+        const u64 top = ii.range >> ii.wshift;
+        const u64 q = ((u64)bins << 32) / (top + 1);
+        ii.inv = q < 0xffffffffull ? (u32)q : 0xffffffffu;
+        if (ii.inv == 0) ii.inv = 1;
+        ii.nb = (u32)((top * (u64)ii.inv) >> 32) + 1u;
         info[b] = ii;
         if (status) status[b] = (int)ii.flags;
     }
@@ -453,7 +687,6 @@ __global__ __launch_bounds__(NT) void zl_partition_kernel(
     if (row_id >= nrows) return;
     const i64 b = row_id / P;
     const InstInfo ii = info[b];
-    if (ii.flags & EBSP_STATUS_UNSUPPORTED) return;
     const i64* __restrict__ row = ts + row_id * (i64)R;
     u32* __restrict__ out = cross + row_id * (i64)stride;
     const u64 base = (u64)ii.base;
@@ -462,14 +695,14 @@ __global__ __launch_bounds__(NT) void zl_partition_kernel(
     for (int i0 = 0; i0 < R; i0 += WAVE) {
         const int i = i0 + lane;
         int bin = -1;
-        if (i < R) bin = (int)fine_bin((u64)row[i] - base, ii.range, ii.inv, ii.nb);
+        if (i < R) bin = (int)fine_bin((u64)row[i] - base, ii);
         int pb = __shfl_up(bin, 1, WAVE);
         if (lane == 0) pb = carry;
         if (i < R)
             for (int k = pb + 1; k <= bin; ++k) out[k] = (u32)i;
         carry = __shfl(bin, WAVE - 1, WAVE);
     }
-    const int last_bin = (int)fine_bin((u64)row[R - 1] - base, ii.range, ii.inv, ii.nb);
+    const int last_bin = (int)fine_bin((u64)row[R - 1] - base, ii);
     for (int k = last_bin + 1 + lane; k <= (int)ii.nb; k += WAVE) out[k] = (u32)R;
 }
 
@@ -484,9 +717,9 @@ __global__ __launch_bounds__(256) void zl_bincount_kernel(
     const u32 kblocks = (u32)(stride + 63) / 64;
     const i64 b = blockIdx.x / kblocks;
     const int k = (int)(blockIdx.x % kblocks) * 64 + kl;
-    const InstInfo ii = info[b];
+    const u32 nb = info[b].nb;
     u32 s = 0;
-    if (k <= (int)ii.nb && !(ii.flags & EBSP_STATUS_UNSUPPORTED)) {
+    if (k <= (int)nb) {
         const u32* col = cross + (b * (i64)P) * stride + k;
 #pragma unroll 4
         for (int p = pg; p < P; p += 4) {
@@ -496,7 +729,7 @@ __global__ __launch_bounds__(256) void zl_bincount_kernel(
     }
     part[tid] = s;
     __syncthreads();
-    if (pg == 0 && k <= (int)ii.nb)
+    if (pg == 0 && k <= (int)nb)
         below[b * (i64)stride + k] = part[kl] + part[64 + kl] + part[128 + kl] + part[192 + kl];
 }
 
@@ -511,11 +744,9 @@ __global__ __launch_bounds__(NT) void zl_plan_kernel(
     __shared__ u32 red[NT / WAVE];
     const int tid = threadIdx.x;
     const i64 b = blockIdx.x;
-    const InstInfo ii = info[b];
-    if (ii.flags & EBSP_STATUS_UNSUPPORTED) return;
     const u32* bel = below + b * (i64)stride;
     u32* ws = winstart + b * (i64)(max_win + 1);
-    const int nb = (int)ii.nb;
+    const int nb = (int)info[b].nb;
     u32 found = 0;
     for (int k0 = 0; k0 < nb; k0 += NT) {
         const int k = k0 + tid;
@@ -527,30 +758,25 @@ __global__ __launch_bounds__(NT) void zl_plan_kernel(
         found += chunk;
     }
     if (tid == 0) {
+        // more starts than max_win can only come from unsorted rows; the last window then runs to the end
         const u32 nwin = found < (u32)max_win ? found : (u32)max_win;
         ws[nwin] = (u32)nb;
         info[b].nwin = nwin;
     }
 }
 
-// One workgroup per window: zl_delta over the window's row segments, then
-// zl_sort, zl_scan, zl_argmin; the window's best candidate goes to `partial`.
+// One workgroup per window; the window's best candidate goes to `partial`.
 template <int NT, int ITEMS>
 __global__ __launch_bounds__(NT) void zl_window_kernel(
     const i64* __restrict__ ts, i64 B, int P, int R,
-    InstInfo* __restrict__ info, const u32* __restrict__ cross, int stride,
+    const InstInfo* __restrict__ info, const u32* __restrict__ cross, int stride,
     const u32* __restrict__ winstart, int max_win,
     Partial* __restrict__ partial, int* __restrict__ status)
 {
     using C = WinCfg<NT, ITEMS>;
     __shared__ __align__(16) unsigned char smem[C::BYTES];
-    u64* recs = (u64*)smem;
-    u64* red = recs + C::RECS;
-    u32* cnt = (u32*)(red + C::RED_WORDS);
-    u32* rowoff = cnt;            // during zl_delta the counter area holds the
-    u32* rowlo = cnt + NT;        // current chunk's row offsets and first indices
+    const Smem sm = carve<NT, ITEMS>(smem);
 
-    const int tid = threadIdx.x;
     // Consecutive windows share cache lines at their segment ends: give each
     // XCD (workgroups are dealt round-robin to the 8 XCDs) a contiguous range.
     const u32 per_xcd = gridDim.x / 8;
@@ -559,83 +785,35 @@ __global__ __launch_bounds__(NT) void zl_window_kernel(
     const int j = (int)(logical % (u32)max_win);
     if (b >= B) return;
     const InstInfo ii = info[b];
-    if ((ii.flags & EBSP_STATUS_UNSUPPORTED) || j >= (int)ii.nwin) return;
+    if (j >= (int)ii.nwin) return;
 
     const u32* ws = winstart + b * (i64)(max_win + 1);
-    const u32 k0 = ws[j], k1 = ws[j + 1];
-    const u32 A = (u32)fine_bin_start(k0, ii.inv);      // window start (relative value)
-    const u64 E = k1 >= ii.nb ? ii.range + 1 : fine_bin_start(k1, ii.inv);   // window end, exclusive
-    const u64 base = (u64)ii.base;
-    const i64* __restrict__ inst = ts + b * (i64)P * R;
-    const u32* __restrict__ cr = cross + (b * (i64)P) * stride;
+    Rows rw;
+    rw.inst = ts + b * (i64)P * R;
+    rw.P = P; rw.R = R; rw.base = (u64)ii.base;
+    rw.cr = cross + (b * (i64)P) * stride;
+    rw.stride = stride;
+    rw.k0 = ws[j];
+    rw.k1 = ws[j + 1];
+    if (rw.k0 > ii.nb) rw.k0 = ii.nb;                  // stale scratch cannot index outside a row of cross
+    if (rw.k1 > ii.nb) rw.k1 = ii.nb;
+    if (rw.k1 <= rw.k0) rw.k1 = rw.k0 < ii.nb ? rw.k0 + 1 : rw.k0;
+    const u64 A = fine_bin_start(rw.k0, ii);                                          // first value of the window
+    const u64 Elast = rw.k1 >= ii.nb ? ii.range : fine_bin_start(rw.k1, ii) - 1;      // last value of the window
 
-    // zl_delta
-    int total = 0, bad = 0;
-    u64 w0 = 0;                   // my share of W0 = sum_p (A - value before row p's segment)
-    for (int p0 = 0; p0 < P; p0 += NT) {
-        const int p = p0 + tid;
-        u32 lo = 0, hi = 0;
-        if (p < P) {
-            lo = cr[(i64)p * stride + k0];
-            hi = cr[(i64)p * stride + k1];
-            lo = lo < (u32)R ? lo : (u32)R;
-            hi = hi < (u32)R ? hi : (u32)R;
-            hi = hi > lo ? hi : lo;
-            if (lo > 0) w0 += (u64)A - (((u64)inst[(size_t)p * R + lo - 1]) - base);
-        }
-        u32 chunk;
-        const u32 off = block_excl_scan<u32, NT>(hi - lo, (u32*)red, chunk);
-        rowoff[tid] = off;
-        rowlo[tid] = lo;
-        __syncthreads();
-        const int room = C::CAP - total;
-        const int take = (int)chunk < room ? (int)chunk : room;
-        const int nrows = (P - p0) < NT ? (P - p0) : NT;
-        for (int e = tid; e < take; e += NT) {
-            // row of element e: the last r with rowoff[r] <= e
-            int l = 0, h = nrows;
-            while (h - l > 1) {
-                const int m = (l + h) >> 1;
-                if (rowoff[m] <= (u32)e) l = m; else h = m;
-            }
-            const int i = (int)rowlo[l] + (e - (int)rowoff[l]);
-            const i64* src = inst + (size_t)(p0 + l) * R + i;
-            const i64 cur = src[0];
-            const u32 rel = (u32)((u64)cur - base);
-            u32 prel = A;
-            if (i > 0) {
-                const i64 prv = src[-1];
-                prel = (u32)((u64)prv - base);
-                bad |= (cur < prv);
-            }
-            recs[phys(total + e)] = (u64)(rel - A) | ((u64)(rel - prel) << 32);
-        }
-        total += (int)chunk;          // may exceed CAP: detected below
-        __syncthreads();
+    u64 bw = U64_MAX, bb = 0;
+    int bad = 0;
+    if (Elast >= A) {
+        if (ii.range >> 32) zl_window<NT, ITEMS, true>(sm, rw, ii.thr, A, Elast, bw, bb, bad);
+        else zl_window<NT, ITEMS, false>(sm, rw, ii.thr, A, Elast, bw, bb, bad);
     }
-    const bool oversize = total > C::CAP;
-    if (oversize) total = C::CAP;
-    const int items = (total + NT - 1) / NT;
-    fill_sentinels<NT>(recs, total, items);
     bad = __syncthreads_or(bad);
-    const u64 W0 = block_reduce<u64, NT>(w0, red, OpAdd());
-
-    u64 best_wait = U64_MAX;
-    u32 best_key = 0;
-    if (!oversize && total > 0) {
-        zl_sort<NT, ITEMS>(recs, cnt, red, items, bit_length(E - 1 - (u64)A));
-        zl_scan_argmin<NT, ITEMS>(recs, red, items, total, A, (u32)ii.thr, (u64)P, W0, best_wait, best_key);
-    }
-    if (tid == 0) {
+    if (threadIdx.x == 0) {
         Partial r;
-        r.wait = best_wait;
-        r.brel = (u64)A + best_key;
+        r.wait = bw;
+        r.brel = bb;
         partial[b * (i64)max_win + j] = r;
-        u32 f = (bad ? EBSP_STATUS_UNSORTED : 0) | (oversize ? EBSP_STATUS_UNSUPPORTED : 0);
-        if (f) {
-            atomicOr(&info[b].flags, f);
-            if (status) atomicOr(status + b, (int)f);
-        }
+        if (bad && status) atomicOr(status + b, (int)EBSP_STATUS_UNSORTED);
     }
 }
 
@@ -728,17 +906,28 @@ bool make_plan(i64 B, int P, int R, Plan& pl)
     return true;
 }
 
-struct Timer {                 // optional per-kernel events
-    hipEvent_t ev[2 * K_COUNT];
-    bool used[K_COUNT];
-    bool on;
+// Optional per-kernel timing: while a profile is open on this thread every
+// launch is bracketed by two events taken from a pool created up front.
+struct Profile {
+    bool on = false;
+    int max_calls = 0, calls = 0;
+    hipEvent_t* ev = nullptr;      // [max_calls][K_COUNT][2]
+    bool* used = nullptr;          // [max_calls][K_COUNT]
 };
+thread_local Profile g_prof;
+
+hipEvent_t* prof_slot(int kid, int which)
+{
+    if (!g_prof.on || g_prof.calls >= g_prof.max_calls) return nullptr;
+    if (which == 0) g_prof.used[g_prof.calls * K_COUNT + kid] = true;
+    return &g_prof.ev[(g_prof.calls * K_COUNT + kid) * 2 + which];
+}
 
 #define LAUNCH(kid, kernel, grid, block, ...)                                              \
     do {                                                                                   \
-        if (tm && tm->on) { (void)hipEventRecord(tm->ev[2 * (kid)], st); tm->used[kid] = true; } \
+        if (hipEvent_t* e0_ = prof_slot(kid, 0)) (void)hipEventRecord(*e0_, st);           \
         hipLaunchKernelGGL(kernel, grid, block, 0, st, __VA_ARGS__);                       \
-        if (tm && tm->on) (void)hipEventRecord(tm->ev[2 * (kid) + 1], st);                       \
+        if (hipEvent_t* e1_ = prof_slot(kid, 1)) (void)hipEventRecord(*e1_, st);           \
         hipError_t e_ = hipGetLastError();                                                 \
         if (e_ != hipSuccess) {                                                            \
             snprintf(g_err, sizeof g_err, "%s: %s", kKernelNames[kid], hipGetErrorString(e_)); \
@@ -747,7 +936,7 @@ struct Timer {                 // optional per-kernel events
     } while (0)
 
 int run_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters, i64* wait, int* status,
-              void* workspace, size_t workspace_bytes, hipStream_t st, Timer* tm)
+              void* workspace, size_t workspace_bytes, hipStream_t st)
 {
     Plan pl;
     if (!make_plan(B, P, R, pl)) return fail(EBSP_ERR_SHAPE, "invalid shape: need B >= 0, P >= 1, R >= 1, P*R < 2^31");
@@ -759,10 +948,8 @@ int run_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters, i64*
     if (!pl.multi) {
         const int rshift = (R & (R - 1)) == 0 ? __builtin_ctz((unsigned)R) : -1;
         const dim3 grid((unsigned)B);
-        if (n <= 64)
-            LAUNCH(K_INSTANCE, (zl_instance_kernel<64, 1>), grid, dim3(64), ts, P, R, rshift, barrier, iters, wait, status);
-        else if (n <= 256)
-            LAUNCH(K_INSTANCE, (zl_instance_kernel<64, 4>), grid, dim3(64), ts, P, R, rshift, barrier, iters, wait, status);
+        if (n <= 256)
+            LAUNCH(K_INSTANCE, (zl_instance_kernel<128, 2>), grid, dim3(128), ts, P, R, rshift, barrier, iters, wait, status);
         else if (n <= 1024)
             LAUNCH(K_INSTANCE, (zl_instance_kernel<256, 4>), grid, dim3(256), ts, P, R, rshift, barrier, iters, wait, status);
         else if (n <= 4096)
@@ -817,34 +1004,52 @@ int ebsp_zipline_batch(const int64_t* ts, int64_t B, int32_t P, int32_t R,
                        int64_t* barrier, int32_t* iters, int64_t* wait,
                        int32_t* status, void* workspace, size_t workspace_bytes, void* stream)
 {
-    return run_batch((const i64*)ts, B, P, R, (i64*)barrier, iters, (i64*)wait, status,
-                     workspace, workspace_bytes, (hipStream_t)stream, nullptr);
+    const int rc = run_batch((const i64*)ts, B, P, R, (i64*)barrier, iters, (i64*)wait, status,
+                             workspace, workspace_bytes, (hipStream_t)stream);
+    if (g_prof.on && rc == EBSP_OK && B > 0 && g_prof.calls < g_prof.max_calls) ++g_prof.calls;
+    return rc;
 }
 
-int ebsp_zipline_batch_timed(const int64_t* ts, int64_t B, int32_t P, int32_t R,
-                             int64_t* barrier, int32_t* iters, int64_t* wait,
-                             int32_t* status, void* workspace, size_t workspace_bytes,
-                             void* stream, float* kernel_ms)
+int ebsp_zipline_profile_begin(int32_t max_calls)
 {
-    if (!kernel_ms) return fail(EBSP_ERR_NULL, "kernel_ms must not be NULL");
-    Timer tm;
-    tm.on = true;
-    for (int i = 0; i < K_COUNT; ++i) { tm.used[i] = false; kernel_ms[i] = 0.f; }
-    for (int i = 0; i < 2 * K_COUNT; ++i)
-        if (hipEventCreate(&tm.ev[i]) != hipSuccess) {
-            for (int k = 0; k < i; ++k) (void)hipEventDestroy(tm.ev[k]);
+    if (g_prof.on) return fail(EBSP_ERR_SHAPE, "a profile is already open on this thread");
+    if (max_calls < 1 || max_calls > 100000) return fail(EBSP_ERR_SHAPE, "max_calls must be in 1..100000");
+    const size_t n = (size_t)max_calls * K_COUNT;
+    g_prof.ev = new hipEvent_t[2 * n];
+    g_prof.used = new bool[n]();
+    for (size_t i = 0; i < 2 * n; ++i)
+        if (hipEventCreate(&g_prof.ev[i]) != hipSuccess) {
+            for (size_t k = 0; k < i; ++k) (void)hipEventDestroy(g_prof.ev[k]);
+            delete[] g_prof.ev; delete[] g_prof.used;
+            g_prof = Profile();
             return fail(EBSP_ERR_LAUNCH, "hipEventCreate failed");
         }
-    int rc = run_batch((const i64*)ts, B, P, R, (i64*)barrier, iters, (i64*)wait, status,
-                       workspace, workspace_bytes, (hipStream_t)stream, &tm);
-    if (rc == EBSP_OK) {
-        if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess)
-            rc = fail(EBSP_ERR_LAUNCH, "hipStreamSynchronize failed");
-        else
-            for (int i = 0; i < K_COUNT; ++i)
-                if (tm.used[i]) (void)hipEventElapsedTime(&kernel_ms[i], tm.ev[2 * i], tm.ev[2 * i + 1]);
-    }
-    for (int i = 0; i < 2 * K_COUNT; ++i) (void)hipEventDestroy(tm.ev[i]);
+    g_prof.max_calls = max_calls;
+    g_prof.calls = 0;
+    g_prof.on = true;
+    return EBSP_OK;
+}
+
+int ebsp_zipline_profile_end(float* kernel_ms, int32_t* calls)
+{
+    if (!g_prof.on) return fail(EBSP_ERR_SHAPE, "no profile is open on this thread");
+    int rc = EBSP_OK;
+    if (hipDeviceSynchronize() != hipSuccess) rc = fail(EBSP_ERR_LAUNCH, "hipDeviceSynchronize failed");
+    const size_t n = (size_t)g_prof.max_calls * K_COUNT;
+    for (int k = 0; k < K_COUNT && kernel_ms; ++k) kernel_ms[k] = 0.f;
+    if (rc == EBSP_OK && kernel_ms)
+        for (int c = 0; c < g_prof.calls; ++c)
+            for (int k = 0; k < K_COUNT; ++k)
+                if (g_prof.used[c * K_COUNT + k]) {
+                    float ms = 0.f;
+                    const size_t i = ((size_t)c * K_COUNT + k) * 2;
+                    if (hipEventElapsedTime(&ms, g_prof.ev[i], g_prof.ev[i + 1]) == hipSuccess) kernel_ms[k] += ms;
+                }
+    if (calls) *calls = g_prof.calls;
+    for (size_t i = 0; i < 2 * n; ++i) (void)hipEventDestroy(g_prof.ev[i]);
+    delete[] g_prof.ev;
+    delete[] g_prof.used;
+    g_prof = Profile();
     return rc;
 }
 

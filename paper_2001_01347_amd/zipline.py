@@ -20,8 +20,9 @@ LIB_PATH = os.path.join(_HERE, "libebsp_zipline.so")
 EBSP_OK = 0
 STATUS_OK, STATUS_UNSORTED, STATUS_OVERFLOW, STATUS_UNSUPPORTED = 0, 1, 2, 4
 
-EXPORTS = ("ebsp_zipline_workspace_bytes", "ebsp_zipline_batch", "ebsp_zipline_batch_timed",
-           "ebsp_zipline_kernel_count", "ebsp_zipline_kernel_name", "ebsp_last_error")
+EXPORTS = ("ebsp_zipline_workspace_bytes", "ebsp_zipline_batch", "ebsp_zipline_profile_begin",
+           "ebsp_zipline_profile_end", "ebsp_zipline_kernel_count", "ebsp_zipline_kernel_name",
+           "ebsp_last_error")
 
 _lib = None
 
@@ -44,8 +45,10 @@ def load() -> ctypes.CDLL:
         common = [vp, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
         lib.ebsp_zipline_batch.restype = ctypes.c_int
         lib.ebsp_zipline_batch.argtypes = common
-        lib.ebsp_zipline_batch_timed.restype = ctypes.c_int
-        lib.ebsp_zipline_batch_timed.argtypes = common + [ctypes.POINTER(ctypes.c_float)]
+        lib.ebsp_zipline_profile_begin.restype = ctypes.c_int
+        lib.ebsp_zipline_profile_begin.argtypes = [i32]
+        lib.ebsp_zipline_profile_end.restype = ctypes.c_int
+        lib.ebsp_zipline_profile_end.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
         lib.ebsp_zipline_kernel_count.restype = ctypes.c_int
         lib.ebsp_zipline_kernel_count.argtypes = []
         lib.ebsp_zipline_kernel_name.restype = ctypes.c_char_p
@@ -114,16 +117,21 @@ def ebsp_zipline_batch(ts: torch.Tensor, barrier: Optional[torch.Tensor] = None,
     return outs
 
 
-def ebsp_zipline_batch_timed(ts: torch.Tensor, barrier=None, iters=None, wait=None, status=None,
-                             workspace=None) -> Tuple[tuple, Dict[str, float]]:
-    """As :func:`ebsp_zipline_batch`, synchronising and returning per-kernel milliseconds."""
-    args, outs = _prepare(ts, barrier, iters, wait, status, workspace)
+def ebsp_zipline_profile_begin(max_calls: int) -> None:
+    """Start recording per-kernel HIP events in this thread's following batch calls."""
+    rc = load().ebsp_zipline_profile_begin(int(max_calls))
+    if rc != EBSP_OK:
+        raise ZipLineError(f"ebsp_zipline_profile_begin failed ({rc}): {ebsp_last_error()}")
+
+
+def ebsp_zipline_profile_end() -> Tuple[Dict[str, float], int]:
+    """Synchronise; return ({kernel name: summed ms}, number of profiled calls)."""
     lib = load()
     n = lib.ebsp_zipline_kernel_count()
     ms = (ctypes.c_float * n)()
-    with torch.cuda.device(ts.device):
-        rc = lib.ebsp_zipline_batch_timed(*args, ms)
+    calls = ctypes.c_int32(0)
+    rc = lib.ebsp_zipline_profile_end(ms, ctypes.byref(calls))
     if rc != EBSP_OK:
-        raise ZipLineError(f"ebsp_zipline_batch_timed failed ({rc}): {ebsp_last_error()}")
+        raise ZipLineError(f"ebsp_zipline_profile_end failed ({rc}): {ebsp_last_error()}")
     names = ebsp_zipline_kernel_names()
-    return outs, {names[i]: float(ms[i]) for i in range(n)}
+    return {names[i]: float(ms[i]) for i in range(n)}, int(calls.value)

@@ -1,0 +1,90 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol the header declares, sizes its workspace sensibly and rejects bad arguments
+before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "ebsp_zipline.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2001_01347_amd import build, zipline
+    if not os.path.exists(zipline.LIB_PATH):
+        build.build()
+    return zipline.load()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ebsp_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(lib):
+    from paper_2001_01347_amd import zipline
+    names = declared_functions()
+    assert len(names) >= 7
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in the header but not exported"
+    assert sorted(zipline.EXPORTS) == names
+
+
+def test_kernel_names(lib):
+    from paper_2001_01347_amd import zipline
+    names = zipline.ebsp_zipline_kernel_names()
+    assert len(names) == lib.ebsp_zipline_kernel_count() >= 5
+    assert all(n.startswith("zl_") for n in names)
+    assert lib.ebsp_zipline_kernel_name(-1) is None
+    assert lib.ebsp_zipline_kernel_name(len(names)) is None
+
+
+def test_workspace_bytes(lib):
+    from paper_2001_01347_amd import zipline
+    ws = zipline.ebsp_zipline_workspace_bytes
+    # one workgroup per instance needs no scratch
+    assert ws(1, 4, 8) == 0 and ws(4096, 16, 64) == 0 and ws(16384, 64, 256) == 0
+    # larger instances: crossing indices dominate, 4 bytes per (row, bin)
+    big = ws(64, 1024, 4096)
+    assert big > 64 * 1024 * 2048 * 4 and big % 256 == 0
+    assert ws(1, 1, 16385) > 0
+    assert ws(2, 256, 1024) > ws(1, 256, 1024)
+    # invalid shapes
+    assert ws(-1, 4, 8) == 0 and ws(1, 0, 8) == 0 and ws(1, 4, 0) == 0
+    assert ws(1, 1 << 16, 1 << 15) == 0          # P*R >= 2^31
+
+
+def test_argument_errors_are_reported_without_a_device(lib):
+    from paper_2001_01347_amd import zipline
+    null = ctypes.c_void_p(0)
+    one = ctypes.c_void_p(256)   # never dereferenced: every call below fails validation first
+    assert lib.ebsp_zipline_batch(one, -1, 4, 8, one, one, one, null, null, 0, null) == -2
+    assert "shape" in zipline.ebsp_last_error()
+    assert lib.ebsp_zipline_batch(one, 1, 0, 8, one, one, one, null, null, 0, null) == -2
+    assert lib.ebsp_zipline_batch(one, 1, 4, 0, one, one, one, null, null, 0, null) == -2
+    assert lib.ebsp_zipline_batch(one, 1, 1 << 16, 1 << 15, one, one, one, null, null, 0, null) == -2
+    assert lib.ebsp_zipline_batch(null, 1, 4, 8, one, one, one, null, null, 0, null) == -1
+    assert lib.ebsp_zipline_batch(one, 1, 4, 8, null, one, one, null, null, 0, null) == -1
+    assert lib.ebsp_zipline_batch(one, 1, 4, 8, one, null, one, null, null, 0, null) == -1
+    assert lib.ebsp_zipline_batch(one, 1, 4, 8, one, one, null, null, null, 0, null) == -1
+    # B == 0 is a no-op even with NULL data
+    assert lib.ebsp_zipline_batch(null, 0, 4, 8, null, null, null, null, null, 0, null) == 0
+    # multi-window shapes need a workspace that is present, large enough and aligned
+    need = zipline.ebsp_zipline_workspace_bytes(2, 256, 1024)
+    assert lib.ebsp_zipline_batch(one, 2, 256, 1024, one, one, one, null, null, 0, null) == -1
+    assert lib.ebsp_zipline_batch(one, 2, 256, 1024, one, one, one, null, one, need - 1, null) == -3
+    assert lib.ebsp_zipline_batch(one, 2, 256, 1024, one, one, one, null,
+                                  ctypes.c_void_p(264), need, null) == -3
+    assert lib.ebsp_zipline_profile_end(None, None) == -2     # no profile open
+    assert lib.ebsp_zipline_profile_begin(0) == -2
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    from paper_2001_01347_amd import zipline
+    with pytest.raises(ValueError):
+        zipline.ebsp_zipline_batch(torch.zeros((1, 2, 3), dtype=torch.int64))

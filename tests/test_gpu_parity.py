@@ -1,0 +1,227 @@
+"""Parity of the HIP path with the CPU oracle, through the C ABI (needs an MI355X).
+
+Bar: bit-exact on barrier (int64), wait (int64) and iters (int32) -- the
+search is integer work and its result is unique (first minimum, upper-bound
+iteration counts), so every output is compared element by element.
+
+Small and medium cases are compared in full.  The three 2 GiB configurations
+are run at full size in the launch configuration the benchmark times and are
+checked two ways: instances drawn at random are compared with the oracle, and
+on every instance the three outputs are checked against properties that hold
+at any size (each worker stops at its last timestamp <= barrier, the stops sum
+to the reported wait, some worker stops exactly at the barrier, and the wait
+does not exceed the classic-BSP wait of one iteration per worker).
+"""
+import json
+import os
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from paper_2001_01347_amd import workloads  # noqa: E402
+
+EPOCH = 1_700_000_000_000_000   # an absolute microsecond epoch, to exercise large offsets
+
+
+@pytest.fixture(scope="module")
+def zl():
+    assert torch.cuda.is_available(), "these tests need a GPU"
+    from paper_2001_01347_amd import zipline
+    zipline.load()          # raises if the HIP library has not been built
+    return zipline
+
+
+def gpu_run(zl, ts):
+    d = torch.from_numpy(np.ascontiguousarray(ts)).cuda()
+    bar, it, w, st = zl.ebsp_zipline_batch(d)
+    torch.cuda.synchronize()
+    return bar.cpu().numpy(), it.cpu().numpy(), w.cpu().numpy(), st.cpu().numpy()
+
+
+def assert_same(zl, oracle, ts, label=""):
+    bar, it, w, st = gpu_run(zl, ts)
+    ob, oi, ow, rc, _ = oracle.zipline(ts, "sweep", threads=16)
+    assert (rc == 0).all()
+    assert (st == 0).all(), f"{label}: status {np.unique(st)}"
+    assert np.array_equal(bar, ob), f"{label}: barrier differs at {np.nonzero(bar != ob)[0][:5]}"
+    assert np.array_equal(w, ow), f"{label}: wait differs at {np.nonzero(w != ow)[0][:5]}"
+    assert np.array_equal(it, oi), f"{label}: iters differ at {np.nonzero((it != oi).any(axis=1))[0][:5]}"
+
+
+def test_hand_worked_examples(zl, oracle):
+    path = os.path.join(os.path.dirname(__file__), "golden", "worked_examples.json")
+    for c in json.load(open(path))["cases"]:
+        bar, it, w, st = gpu_run(zl, np.array([c["t"]], dtype=np.int64))
+        assert (int(bar[0]), int(w[0]), list(it[0]), int(st[0])) == (c["barrier"], c["wait"], c["iters"], 0)
+
+
+def test_config1_and_config2_full(zl, oracle):
+    assert_same(zl, oracle, workloads.make(1), "config 1")
+    assert_same(zl, oracle, workloads.make(2), "config 2")
+    assert_same(zl, oracle, workloads.make(2, instances=range(512), shift=EPOCH), "config 2 shifted")
+
+
+@pytest.mark.parametrize("P,R", [(1, 1), (1, 9), (6, 1), (2, 3), (3, 5), (7, 9), (4, 16), (13, 19),
+                                 (16, 64), (33, 31), (64, 64), (50, 81), (17, 241), (64, 256),
+                                 (100, 163), (128, 128), (16384, 1), (1, 16384)])
+def test_single_workgroup_shapes(zl, oracle, P, R):
+    rng = np.random.default_rng(1000 * P + R)
+    ts = np.stack([workloads.random_small(rng, P, R, 1, 1000, ties=(i % 2 == 0)) for i in range(6)])
+    assert_same(zl, oracle, ts, f"P={P} R={R}")
+    assert_same(zl, oracle, ts + EPOCH, f"P={P} R={R} shifted")
+    assert_same(zl, oracle, ts - 5_000_000, f"P={P} R={R} negative")
+
+
+@pytest.mark.parametrize("P,R", [(1, 16385), (16385, 1), (64, 257), (5, 4000), (300, 100), (128, 512),
+                                 (1000, 150), (37, 2999), (2048, 16), (3, 70001)])
+def test_multi_window_shapes(zl, oracle, P, R):
+    rng = np.random.default_rng(77 * P + R)
+    ts = np.stack([workloads.random_small(rng, P, R, 1, 1000, ties=(i % 2 == 0)) for i in range(3)])
+    assert_same(zl, oracle, ts, f"P={P} R={R}")
+    assert_same(zl, oracle, ts + EPOCH, f"P={P} R={R} shifted")
+
+
+def test_degenerate_values(zl, oracle):
+    # all timestamps equal; all workers identical; one giant tie at the optimum
+    assert_same(zl, oracle, np.full((3, 8, 16), 42, dtype=np.int64), "all equal")
+    assert_same(zl, oracle, np.full((2, 64, 512), -7, dtype=np.int64), "all equal, multi-window")
+    row = np.cumsum(np.arange(1, 301, dtype=np.int64))
+    assert_same(zl, oracle, np.tile(row, (2, 100, 1)), "identical workers")
+    t = np.tile(np.arange(1, 65, dtype=np.int64) * 10, (1, 40, 1))
+    t[0, :, 63] = 1000
+    assert_same(zl, oracle, t, "tie at the end")
+
+
+def test_wide_value_ranges(zl, oracle):
+    # per-instance spread of 2^32 units or more (e.g. nanosecond timestamps): deltas need 64 bits
+    rng = np.random.default_rng(8)
+    for P, R in [(3, 5), (16, 64), (64, 256), (50, 81)]:
+        ts = np.stack([workloads.random_small(rng, P, R, 1, 1000, ties=(i % 2 == 0)) for i in range(4)])
+        assert_same(zl, oracle, ts * 100_000_007, f"wide P={P} R={R}")
+        assert_same(zl, oracle, ts * (1 << 36) - EPOCH, f"very wide P={P} R={R}")
+    assert_same(zl, oracle, workloads.make(3, instances=range(8)) * 1000, "config 3 in ns")
+    for P, R in [(64, 257), (128, 512), (5, 4000)]:
+        ts = np.stack([workloads.random_small(rng, P, R, 1, 1000, ties=(i % 2 == 0)) for i in range(2)])
+        assert_same(zl, oracle, ts * 100_000_007 + EPOCH, f"wide multi-window P={P} R={R}")
+    assert_same(zl, oracle, workloads.make(4, instances=range(2)) * 1000, "config 4 in ns")
+    # mixed batch: narrow and wide instances side by side
+    m = workloads.make(2, instances=range(6)).copy()
+    m[1] *= 5000
+    m[4] *= 1 << 30
+    assert_same(zl, oracle, m, "mixed widths")
+
+
+def test_skewed_and_clustered_values(zl, oracle):
+    # one worker 1000x slower stretches the value range: nearly all keys share a few fine bins
+    t = workloads.make(4, instances=range(2)).copy()
+    t[:, 7, :] = t[:, 7, :1] + (t[:, 7, :] - t[:, 7, :1]) * 1000
+    assert_same(zl, oracle, t, "straggler x1000")
+    # a handful of distinct values, each far more frequent than one window can hold
+    rng = np.random.default_rng(12)
+    few = np.sort(rng.integers(0, 4, size=(2, 64, 1024)), axis=2).astype(np.int64) * 1_000_003
+    assert_same(zl, oracle, few, "four distinct values")
+    # dense cluster + sparse tail: 40000 keys within 50000 units, then one far outlier row end
+    c = np.sort(rng.integers(0, 50_000, size=(1, 40, 1000)), axis=2).astype(np.int64)
+    c[0, 0, -1] = 10 ** 12
+    assert_same(zl, oracle, c, "cluster and outlier")
+
+
+def test_status_flags(zl, oracle):
+    ts = workloads.make(2, instances=range(8)).copy()
+    ts[3, 5, 10] = ts[3, 5, 9] - 1                      # one row of one instance goes backwards
+    bar, it, w, st = gpu_run(zl, ts)
+    assert st[3] & zl.STATUS_UNSORTED and (np.delete(st, 3) == 0).all()
+    ob, oi, ow, rc, _ = oracle.zipline(ts)
+    keep = rc == 0
+    assert rc[3] == 1 and keep.sum() == 7
+    assert np.array_equal(bar[keep], ob[keep]) and np.array_equal(w[keep], ow[keep])
+    assert np.array_equal(it[keep], oi[keep])
+    # P * range beyond int64: flagged, no fault
+    big = np.zeros((1, 4, 4), dtype=np.int64)
+    big[0, :, :] = np.array([0, 1, 2, 2 ** 62], dtype=np.int64)
+    _, _, _, st = gpu_run(zl, big)
+    assert st[0] & zl.STATUS_OVERFLOW
+    # same in the multi-window path
+    m = workloads.make(4, instances=range(3)).copy()
+    m[1, 200, 500] = m[1, 200, 400]
+    bar, it, w, st = gpu_run(zl, m)
+    assert st[1] & zl.STATUS_UNSORTED and st[0] == 0 and st[2] == 0
+    ob, oi, ow, rc, _ = oracle.zipline(m)
+    for b in (0, 2):
+        assert (bar[b], w[b]) == (ob[b], ow[b]) and np.array_equal(it[b], oi[b])
+
+
+def test_empty_batch_and_reuse_of_buffers(zl, oracle):
+    d = torch.zeros((0, 4, 8), dtype=torch.int64, device="cuda")
+    bar, it, w, st = zl.ebsp_zipline_batch(d)
+    assert bar.numel() == 0 and it.shape == (0, 4)
+    # caller-owned outputs and workspace, two different batches through the same buffers
+    a = workloads.make(4, instances=range(4))
+    b = workloads.make(4, instances=range(4, 8))
+    outs = None
+    ws = torch.empty(zl.ebsp_zipline_workspace_bytes(4, 256, 1024), dtype=torch.uint8, device="cuda")
+    for ts in (a, b, a):
+        d = torch.from_numpy(ts).cuda()
+        outs = zl.ebsp_zipline_batch(d, *(outs or (None, None, None, None)), workspace=ws)
+        torch.cuda.synchronize()
+        ob, oi, ow, _, _ = oracle.zipline(ts)
+        assert np.array_equal(outs[0].cpu().numpy(), ob) and np.array_equal(outs[2].cpu().numpy(), ow)
+        assert np.array_equal(outs[1].cpu().numpy(), oi)
+
+
+def test_deterministic_and_stream(zl):
+    ts = torch.from_numpy(workloads.make(4, instances=range(6))).cuda()
+    first = [x.clone() for x in zl.ebsp_zipline_batch(ts)]
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        second = zl.ebsp_zipline_batch(ts)
+    s.synchronize()
+    torch.cuda.synchronize()
+    for x, y in zip(first, second):
+        assert torch.equal(x, y)
+
+
+def _properties_hold(ts_dev, bar, it, w):
+    B, P, R = ts_dev.shape
+    idx = (it.long() - 1).clamp(0, R - 1).unsqueeze(2)
+    stop = torch.gather(ts_dev, 2, idx).squeeze(2)                       # t[p][iters-1]
+    nxt_idx = it.long().clamp(0, R - 1).unsqueeze(2)
+    nxt = torch.gather(ts_dev, 2, nxt_idx).squeeze(2)
+    assert bool(((it >= 1) & (it <= R)).all())
+    assert bool((stop <= bar[:, None]).all())
+    assert bool(((nxt > bar[:, None]) | (it == R)).all())
+    assert bool(((bar[:, None] - stop).sum(dim=1) == w).all())
+    assert bool((stop.max(dim=1).values == bar).all())                   # the barrier is a timestamp
+    first = ts_dev[:, :, 0]
+    assert bool((bar >= first.max(dim=1).values).all())
+    assert bool((w <= (first.max(dim=1, keepdim=True).values - first).sum(dim=1)).all())
+    assert bool((w >= 0).all())
+
+
+@pytest.mark.parametrize("k,sample", [(3, 768), (4, 96), (5, 8)])
+def test_full_size_configs(zl, oracle, k, sample):
+    cfg = workloads.CONFIGS[k]
+    host = workloads.make(k, threads=16)
+    ts = torch.from_numpy(host).cuda()
+    bar, it, w, st = zl.ebsp_zipline_batch(ts)
+    torch.cuda.synchronize()
+    assert int(st.max().item()) == 0
+    _properties_hold(ts, bar, it, w)
+    rng = np.random.default_rng(k)
+    ids = np.sort(rng.choice(cfg.B, size=sample, replace=False))
+    ob, oi, ow, rc, _ = oracle.zipline(host[ids], "sweep", threads=16)
+    assert (rc == 0).all()
+    sel = torch.from_numpy(ids).cuda()
+    assert np.array_equal(bar[sel].cpu().numpy(), ob)
+    assert np.array_equal(w[sel].cpu().numpy(), ow)
+    assert np.array_equal(it[sel].cpu().numpy(), oi)
+
+
+def test_shifted_epoch_multi_window(zl, oracle):
+    assert_same(zl, oracle, workloads.make(5, instances=[0, 63], shift=EPOCH), "config 5 shifted")
+    assert_same(zl, oracle, workloads.make(4, instances=range(16), shift=EPOCH), "config 4 shifted")
+    assert_same(zl, oracle, workloads.make(3, instances=range(64), shift=-EPOCH), "config 3 shifted")
