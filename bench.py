@@ -56,6 +56,9 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=5, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--cpu-instances", type=int, default=-1,
                     help="instances in the CPU-oracle sample (default: sized for roughly 10-30 s of CPU work)")
+    ap.add_argument("--copy-probe", type=int, default=3,
+                    help="launches of the plain copy kernel (the input's size) after the timed region; "
+                         "its bandwidth and byte counters are the yardstick for the others (0: skip)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (instances are independent and would "
@@ -105,6 +108,19 @@ def main() -> int:
     ms_per_step = (w1 - w0) * 1e3 / args.steps
     assert int(status.max().item()) == 0, "the search flagged a data error on synthetic input"
 
+    # yardstick: a plain streaming copy of the same 8 B/key input (reads and writes n_keys * 8 bytes)
+    copy_gbs = None
+    if args.copy_probe > 0:
+        dst = torch.empty_like(ts)
+        zipline.ebsp_zipline_copy_probe(ts, dst)
+        torch.cuda.synchronize()
+        zipline.ebsp_zipline_profile_begin(args.copy_probe)
+        for _ in range(args.copy_probe):
+            zipline.ebsp_zipline_copy_probe(ts, dst)
+        copy_ms, ncopy = zipline.ebsp_zipline_profile_end()
+        copy_gbs = 2.0 * 8.0 * n_keys / (copy_ms["zl_copy_kernel"] / ncopy * 1e-3) / 1e9
+        del dst
+
     # shape-dependent constants of the multi-window path (for the byte model only)
     bins = (P * R + 2047) // 2048 if P * R > 16384 else 0
     windows = B * ((P * R + 8191) // 8192) if P * R > 16384 else 0
@@ -121,7 +137,7 @@ def main() -> int:
     if args.cpu_instances > 0:
         n_cpu = min(B, args.cpu_instances)
     else:
-        n_cpu = max(1, min(B, int(3.0e7 * cores / 8 // (P * R)) or 1))
+        n_cpu = max(1, min(B, int(1.7e7 * cores // (P * R)) or 1))
     sample = host[:n_cpu]
     oracle.zipline(sample[:1], "sweep", threads=1)          # load the library, touch the pages
     c0 = time.perf_counter()
@@ -161,6 +177,7 @@ def main() -> int:
                          "sample": f"sweep oracle on the first {n_cpu} of {B} instances "
                                    f"({n_cpu * P * R} timestamps), {c1 - c0:.2f} s wall",
                          "matches_gpu": bool(same)},
+        "copy_probe_GBs": copy_gbs,
         "setup_s": gen_s,
     }
     print(json.dumps(out))

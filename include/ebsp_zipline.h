@@ -94,6 +94,15 @@ int ebsp_zipline_batch(const int64_t* ts, int64_t B, int32_t P, int32_t R,
 int ebsp_zipline_profile_begin(int32_t max_calls);
 int ebsp_zipline_profile_end(float* kernel_ms, int32_t* calls);
 
+/*
+ * Measurement yardstick, not part of the search: copies `bytes` (a positive
+ * multiple of 16; both pointers 16-byte aligned device memory) from src to dst
+ * with a plain streaming kernel on `stream`.  Benchmarks use it to see what
+ * bandwidth, and what the HBM byte counters, read for a transfer of known size.
+ * Counts as one call of an open profile.
+ */
+int ebsp_zipline_copy_probe(const void* src, void* dst, size_t bytes, void* stream);
+
 /* Number of distinct kernels the library may launch, and their names
  * (static storage; NULL if i is out of range). */
 int         ebsp_zipline_kernel_count(void);

@@ -45,6 +45,8 @@ namespace {
 
 constexpr int WAVE = 64;
 constexpr u64 U64_MAX = ~0ull;
+constexpr i64 DEFERRED = INT64_MIN;            // wait[b] of an instance left to the general kernel
+constexpr u64 DEFERRED_WINDOW = ~0ull - 1;      // Partial::brel of a window left to the general kernel
 
 // ---------------------------------------------------------------------------
 // Tunables of the multi-window path.
@@ -124,6 +126,7 @@ __device__ __forceinline__ T block_reduce(T v, T* red, Op op)
     T r = red[0];
 #pragma unroll
     for (int w = 1; w < NW; ++w) r = op(r, red[w]);
+    asm volatile("" : "+v"(r));      // finish the reduction here, not wherever the result is first used
     __syncthreads();
     return r;
 }
@@ -590,35 +593,79 @@ __global__ __launch_bounds__(NT) void zl_instance_kernel(
     u32 flags = 0;
     if (range > (u64)INT64_MAX / (u64)P) flags |= EBSP_STATUS_OVERFLOW;
 
+    if (range >> 32) {
+        // deltas need more than 32 bits: left to zl_instance_general_kernel
+        if (tid == 0) wait[b] = DEFERRED;
+        return;
+    }
+    // zl_delta in memory order (row p occupies slots [p*R, (p+1)*R)): no row lookup
+    int bad = 0;
+    for (int e = tid; e < n; e += NT) {
+        const int i = rshift >= 0 ? (e & (R - 1)) : (e % R);
+        const i64 cur = inst[e];
+        const u32 rel = (u32)((u64)cur - (u64)base);
+        u32 prel = 0;
+        if (i > 0) {
+            const i64 prv = inst[e - 1];
+            prel = (u32)((u64)prv - (u64)base);
+            bad |= (cur < prv);
+        }
+        sm.recs[phys(e)] = (u64)rel | ((u64)(rel - prel) << 32);
+    }
+    const int items = (n + NT - 1) / NT;
+    fill_sentinels<NT>(sm.recs, n, items);
+    if (__syncthreads_or(bad)) flags |= EBSP_STATUS_UNSORTED;
+    zl_sort<NT, ITEMS, false>(sm, items, bit_length(range));
+    u64 best_wait;
+    u32 key;
+    zl_scan_argmin<NT, false>(sm, items, n, 0ull, thr, (u64)P, 0ull, best_wait, key);
+    const i64 bar = (i64)((u64)base + key);
+    if (tid == 0) {
+        barrier[b] = bar;
+        wait[b] = (i64)best_wait;
+        if (status) status[b] = (int)flags;
+    }
+    for (int p = tid; p < P; p += NT)
+        iters[b * (i64)P + p] = zl_iters(inst + (size_t)p * R, R, bar);
+}
+
+// The instances zl_instance_kernel deferred (value spread of 2^32 or more):
+// the general window search over whole rows, one workgroup per instance.
+template <int NT, int ITEMS>
+__global__ __launch_bounds__(NT) void zl_instance_general_kernel(
+    const i64* __restrict__ ts, int P, int R,
+    i64* __restrict__ barrier, int* __restrict__ iters, i64* __restrict__ wait,
+    int* __restrict__ status)
+{
+    using C = WinCfg<NT, ITEMS>;
+    __shared__ __align__(16) unsigned char smem[C::BYTES];
+    const Smem sm = carve<NT, ITEMS>(smem);
+    const int tid = threadIdx.x;
+    const i64 b = blockIdx.x;
+    if (wait[b] != DEFERRED) return;
+    const i64* __restrict__ inst = ts + b * (i64)P * R;
+
+    i64 mn = INT64_MAX, mxf = INT64_MIN, mxl = INT64_MIN;
+    for (int p = tid; p < P; p += NT) {
+        const i64 f = inst[(size_t)p * R], l = inst[(size_t)p * R + R - 1];
+        mn = f < mn ? f : mn;
+        mxf = f > mxf ? f : mxf;
+        mxl = l > mxl ? l : mxl;
+    }
+    const i64 base = block_reduce<i64, NT>(mn, (i64*)sm.red, OpMin());
+    const i64 first_max = block_reduce<i64, NT>(mxf, (i64*)sm.red, OpMax());
+    const i64 last_max = block_reduce<i64, NT>(mxl, (i64*)sm.red, OpMax());
+    const u64 range = (u64)last_max - (u64)base;
+    const u64 thr = (u64)first_max - (u64)base;
+    u32 flags = 0;
+    if (range > (u64)INT64_MAX / (u64)P) flags |= EBSP_STATUS_OVERFLOW;
+
+    Rows rw;
+    rw.inst = inst; rw.P = P; rw.R = R; rw.base = (u64)base;
+    rw.cr = nullptr; rw.stride = 0; rw.k0 = rw.k1 = 0;
     int bad = 0;
     u64 best_wait = U64_MAX, best_rel = 0;
-    if (!(range >> 32)) {
-        // zl_delta in memory order (row p occupies slots [p*R, (p+1)*R)): no row lookup
-        for (int e = tid; e < n; e += NT) {
-            const int i = rshift >= 0 ? (e & (R - 1)) : (e % R);
-            const i64 cur = inst[e];
-            const u32 rel = (u32)((u64)cur - (u64)base);
-            u32 prel = 0;
-            if (i > 0) {
-                const i64 prv = inst[e - 1];
-                prel = (u32)((u64)prv - (u64)base);
-                bad |= (cur < prv);
-            }
-            sm.recs[phys(e)] = (u64)rel | ((u64)(rel - prel) << 32);
-        }
-        const int items = (n + NT - 1) / NT;
-        fill_sentinels<NT>(sm.recs, n, items);
-        __syncthreads();
-        zl_sort<NT, ITEMS, false>(sm, items, bit_length(range));
-        u32 key;
-        zl_scan_argmin<NT, false>(sm, items, n, 0ull, thr, (u64)P, 0ull, best_wait, key);
-        best_rel = key;
-    } else {
-        Rows rw;
-        rw.inst = inst; rw.P = P; rw.R = R; rw.base = (u64)base;
-        rw.cr = nullptr; rw.stride = 0; rw.k0 = rw.k1 = 0;
-        zl_window<NT, ITEMS, true>(sm, rw, thr, 0ull, range, best_wait, best_rel, bad);
-    }
+    zl_window<NT, ITEMS, true>(sm, rw, thr, 0ull, range, best_wait, best_rel, bad);
     if (__syncthreads_or(bad)) flags |= EBSP_STATUS_UNSORTED;
     const i64 bar = (i64)((u64)base + best_rel);
     if (tid == 0) {
@@ -765,7 +812,49 @@ __global__ __launch_bounds__(NT) void zl_plan_kernel(
     }
 }
 
+// Where a window sits: instance b, window j, fine bins [k0, k1), values [A, Elast].
+struct WinPos {
+    i64 b;
+    int j;
+    bool valid;
+    Rows rw;
+    u64 A, Elast;
+};
+
+__device__ __forceinline__ WinPos locate_window(const i64* ts, i64 B, int P, int R, const InstInfo* info,
+                                                const InstInfo& ii_unused, const u32* cross, int stride,
+                                                const u32* winstart, int max_win, InstInfo& ii)
+{
+    WinPos w;
+    // Consecutive windows share cache lines at their segment ends: give each
+    // XCD (workgroups are dealt round-robin to the 8 XCDs) a contiguous range.
+    const u32 per_xcd = gridDim.x / 8;
+    const u32 logical = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    w.b = logical / (u32)max_win;
+    w.j = (int)(logical % (u32)max_win);
+    w.valid = false;
+    if (w.b >= B) return w;
+    ii = info[w.b];
+    if (w.j >= (int)ii.nwin) return w;
+    const u32* ws = winstart + w.b * (i64)(max_win + 1);
+    w.rw.inst = ts + w.b * (i64)P * R;
+    w.rw.P = P; w.rw.R = R; w.rw.base = (u64)ii.base;
+    w.rw.cr = cross + (w.b * (i64)P) * stride;
+    w.rw.stride = stride;
+    w.rw.k0 = ws[w.j];
+    w.rw.k1 = ws[w.j + 1];
+    if (w.rw.k0 > ii.nb) w.rw.k0 = ii.nb;              // stale scratch cannot index outside a row of cross
+    if (w.rw.k1 > ii.nb) w.rw.k1 = ii.nb;
+    if (w.rw.k1 <= w.rw.k0) w.rw.k1 = w.rw.k0 < ii.nb ? w.rw.k0 + 1 : w.rw.k0;
+    w.A = fine_bin_start(w.rw.k0, ii);                                            // first value of the window
+    w.Elast = w.rw.k1 >= ii.nb ? ii.range : fine_bin_start(w.rw.k1, ii) - 1;      // last value of the window
+    w.valid = w.Elast >= w.A;
+    return w;
+}
+
 // One workgroup per window; the window's best candidate goes to `partial`.
+// Handles the normal case (32-bit value spread, the window fits in LDS) and
+// marks every other window as deferred to zl_window_general_kernel.
 template <int NT, int ITEMS>
 __global__ __launch_bounds__(NT) void zl_window_kernel(
     const i64* __restrict__ ts, i64 B, int P, int R,
@@ -776,44 +865,69 @@ __global__ __launch_bounds__(NT) void zl_window_kernel(
     using C = WinCfg<NT, ITEMS>;
     __shared__ __align__(16) unsigned char smem[C::BYTES];
     const Smem sm = carve<NT, ITEMS>(smem);
+    InstInfo ii;
+    const WinPos w = locate_window(ts, B, P, R, info, ii, cross, stride, winstart, max_win, ii);
+    if (w.b >= B || w.j >= (int)ii.nwin) return;
 
-    // Consecutive windows share cache lines at their segment ends: give each
-    // XCD (workgroups are dealt round-robin to the 8 XCDs) a contiguous range.
-    const u32 per_xcd = gridDim.x / 8;
-    const u32 logical = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
-    const i64 b = logical / (u32)max_win;
-    const int j = (int)(logical % (u32)max_win);
-    if (b >= B) return;
-    const InstInfo ii = info[b];
-    if (j >= (int)ii.nwin) return;
+    Partial r;
+    r.wait = U64_MAX;
+    r.brel = 0;
+    int bad = 0;
+    if (w.valid) {
+        bool defer = (ii.range >> 32) != 0;
+        int total = 0;
+        u64 w0 = 0;
+        if (!defer) {
+            total = zl_delta<NT, false>(sm, w.rw, w.A, w.Elast, true, true, C::CAP, w0, bad);
+            defer = total > C::CAP;
+        }
+        if (defer) {
+            r.brel = DEFERRED_WINDOW;
+        } else if (total > 0) {
+            const int items = (total + NT - 1) / NT;
+            fill_sentinels<NT>(sm.recs, total, items);
+            const u64 W0 = block_reduce<u64, NT>(w0, sm.red, OpAdd());   // also orders the record writes
+            zl_sort<NT, ITEMS, false>(sm, items, bit_length(w.Elast - w.A));
+            u32 key;
+            zl_scan_argmin<NT, false>(sm, items, total, w.A, ii.thr, (u64)P, W0, r.wait, key);
+            r.brel = w.A + key;
+        }
+    }
+    bad = __syncthreads_or(bad);
+    if (threadIdx.x == 0) {
+        partial[w.b * (i64)max_win + w.j] = r;
+        if (bad && status) atomicOr(status + w.b, (int)EBSP_STATUS_UNSORTED);
+    }
+}
 
-    const u32* ws = winstart + b * (i64)(max_win + 1);
-    Rows rw;
-    rw.inst = ts + b * (i64)P * R;
-    rw.P = P; rw.R = R; rw.base = (u64)ii.base;
-    rw.cr = cross + (b * (i64)P) * stride;
-    rw.stride = stride;
-    rw.k0 = ws[j];
-    rw.k1 = ws[j + 1];
-    if (rw.k0 > ii.nb) rw.k0 = ii.nb;                  // stale scratch cannot index outside a row of cross
-    if (rw.k1 > ii.nb) rw.k1 = ii.nb;
-    if (rw.k1 <= rw.k0) rw.k1 = rw.k0 < ii.nb ? rw.k0 + 1 : rw.k0;
-    const u64 A = fine_bin_start(rw.k0, ii);                                          // first value of the window
-    const u64 Elast = rw.k1 >= ii.nb ? ii.range : fine_bin_start(rw.k1, ii) - 1;      // last value of the window
+// The windows zl_window_kernel deferred: the general window search.
+template <int NT, int ITEMS>
+__global__ __launch_bounds__(NT) void zl_window_general_kernel(
+    const i64* __restrict__ ts, i64 B, int P, int R,
+    const InstInfo* __restrict__ info, const u32* __restrict__ cross, int stride,
+    const u32* __restrict__ winstart, int max_win,
+    Partial* __restrict__ partial, int* __restrict__ status)
+{
+    using C = WinCfg<NT, ITEMS>;
+    __shared__ __align__(16) unsigned char smem[C::BYTES];
+    const Smem sm = carve<NT, ITEMS>(smem);
+    InstInfo ii;
+    const WinPos w = locate_window(ts, B, P, R, info, ii, cross, stride, winstart, max_win, ii);
+    if (w.b >= B || w.j >= (int)ii.nwin) return;
+    Partial* out = partial + w.b * (i64)max_win + w.j;
+    if (!(out->wait == U64_MAX && out->brel == DEFERRED_WINDOW)) return;
 
     u64 bw = U64_MAX, bb = 0;
     int bad = 0;
-    if (Elast >= A) {
-        if (ii.range >> 32) zl_window<NT, ITEMS, true>(sm, rw, ii.thr, A, Elast, bw, bb, bad);
-        else zl_window<NT, ITEMS, false>(sm, rw, ii.thr, A, Elast, bw, bb, bad);
-    }
+    if (ii.range >> 32) zl_window<NT, ITEMS, true>(sm, w.rw, ii.thr, w.A, w.Elast, bw, bb, bad);
+    else zl_window<NT, ITEMS, false>(sm, w.rw, ii.thr, w.A, w.Elast, bw, bb, bad);
     bad = __syncthreads_or(bad);
     if (threadIdx.x == 0) {
         Partial r;
         r.wait = bw;
         r.brel = bb;
-        partial[b * (i64)max_win + j] = r;
-        if (bad && status) atomicOr(status + b, (int)EBSP_STATUS_UNSORTED);
+        *out = r;
+        if (bad && status) atomicOr(status + w.b, (int)EBSP_STATUS_UNSORTED);
     }
 }
 
@@ -858,6 +972,14 @@ __global__ __launch_bounds__(NT) void zl_finish_kernel(
     if (p < P) iters[b * (i64)P + p] = zl_iters(ts + (b * (i64)P + p) * (i64)R, R, bar);
 }
 
+// Plain streaming copy of n 16-byte words: the yardstick that HBM byte counters
+// and achieved bandwidth of the other kernels are read against.
+__global__ __launch_bounds__(256) void zl_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, i64 n)
+{
+    const i64 stride = (i64)gridDim.x * blockDim.x;
+    for (i64 i = (i64)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+}
+
 // ---------------------------------------------------------------------------
 // Host side.
 
@@ -869,10 +991,12 @@ int fail(int code, const char* msg)
     return code;
 }
 
-enum KernelId { K_INSTANCE = 0, K_BOUNDS, K_PARTITION, K_BINCOUNT, K_PLAN, K_WINDOW, K_FINISH, K_COUNT };
+enum KernelId { K_INSTANCE = 0, K_INSTANCE_GENERAL, K_BOUNDS, K_PARTITION, K_BINCOUNT, K_PLAN, K_WINDOW,
+                K_WINDOW_GENERAL, K_FINISH, K_COPY, K_COUNT };
 const char* const kKernelNames[K_COUNT] = {
-    "zl_instance_kernel", "zl_bounds_kernel", "zl_partition_kernel", "zl_bincount_kernel",
-    "zl_plan_kernel", "zl_window_kernel", "zl_finish_kernel"};
+    "zl_instance_kernel", "zl_instance_general_kernel", "zl_bounds_kernel", "zl_partition_kernel",
+    "zl_bincount_kernel", "zl_plan_kernel", "zl_window_kernel", "zl_window_general_kernel",
+    "zl_finish_kernel", "zl_copy_kernel"};
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -956,6 +1080,8 @@ int run_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters, i64*
             LAUNCH(K_INSTANCE, (zl_instance_kernel<512, 8>), grid, dim3(512), ts, P, R, rshift, barrier, iters, wait, status);
         else
             LAUNCH(K_INSTANCE, (zl_instance_kernel<1024, 16>), grid, dim3(1024), ts, P, R, rshift, barrier, iters, wait, status);
+        LAUNCH(K_INSTANCE_GENERAL, (zl_instance_general_kernel<LARGE_NT, LARGE_ITEMS>), grid, dim3(LARGE_NT),
+               ts, P, R, barrier, iters, wait, status);
         return EBSP_OK;
     }
 
@@ -984,6 +1110,8 @@ int run_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters, i64*
     const unsigned wgrid = (unsigned)((total_win + 7) / 8 * 8);
     LAUNCH(K_WINDOW, (zl_window_kernel<LARGE_NT, LARGE_ITEMS>), dim3(wgrid), dim3(LARGE_NT),
            ts, B, P, R, info, cross, pl.stride, winstart, pl.max_win, partial, status);
+    LAUNCH(K_WINDOW_GENERAL, (zl_window_general_kernel<LARGE_NT, LARGE_ITEMS>), dim3(wgrid), dim3(LARGE_NT),
+           ts, B, P, R, info, cross, pl.stride, winstart, pl.max_win, partial, status);
     LAUNCH(K_FINISH, (zl_finish_kernel<256>), dim3((unsigned)(pblocks * B)), dim3(256),
            ts, P, R, info, partial, pl.max_win, barrier, iters, wait);
     return EBSP_OK;
@@ -1008,6 +1136,20 @@ int ebsp_zipline_batch(const int64_t* ts, int64_t B, int32_t P, int32_t R,
                              workspace, workspace_bytes, (hipStream_t)stream);
     if (g_prof.on && rc == EBSP_OK && B > 0 && g_prof.calls < g_prof.max_calls) ++g_prof.calls;
     return rc;
+}
+
+int ebsp_zipline_copy_probe(const void* src, void* dst, size_t bytes, void* stream)
+{
+    if (!src || !dst) return fail(EBSP_ERR_NULL, "src and dst must not be NULL");
+    if (bytes == 0 || bytes % 16 != 0 || (((uintptr_t)src | (uintptr_t)dst) & 15u))
+        return fail(EBSP_ERR_SHAPE, "copy probe needs a positive multiple of 16 bytes and 16-byte aligned pointers");
+    hipStream_t st = (hipStream_t)stream;
+    const i64 n = (i64)(bytes / 16);
+    i64 blocks = (n + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    LAUNCH(K_COPY, zl_copy_kernel, dim3((unsigned)blocks), dim3(256), (const uint4*)src, (uint4*)dst, n);
+    if (g_prof.on && g_prof.calls < g_prof.max_calls) ++g_prof.calls;
+    return EBSP_OK;
 }
 
 int ebsp_zipline_profile_begin(int32_t max_calls)

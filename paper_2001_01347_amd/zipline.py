@@ -21,8 +21,8 @@ EBSP_OK = 0
 STATUS_OK, STATUS_UNSORTED, STATUS_OVERFLOW, STATUS_UNSUPPORTED = 0, 1, 2, 4
 
 EXPORTS = ("ebsp_zipline_workspace_bytes", "ebsp_zipline_batch", "ebsp_zipline_profile_begin",
-           "ebsp_zipline_profile_end", "ebsp_zipline_kernel_count", "ebsp_zipline_kernel_name",
-           "ebsp_last_error")
+           "ebsp_zipline_profile_end", "ebsp_zipline_copy_probe", "ebsp_zipline_kernel_count",
+           "ebsp_zipline_kernel_name", "ebsp_last_error")
 
 _lib = None
 
@@ -49,6 +49,8 @@ def load() -> ctypes.CDLL:
         lib.ebsp_zipline_profile_begin.argtypes = [i32]
         lib.ebsp_zipline_profile_end.restype = ctypes.c_int
         lib.ebsp_zipline_profile_end.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
+        lib.ebsp_zipline_copy_probe.restype = ctypes.c_int
+        lib.ebsp_zipline_copy_probe.argtypes = [vp, vp, sz, vp]
         lib.ebsp_zipline_kernel_count.restype = ctypes.c_int
         lib.ebsp_zipline_kernel_count.argtypes = []
         lib.ebsp_zipline_kernel_name.restype = ctypes.c_char_p
@@ -115,6 +117,19 @@ def ebsp_zipline_batch(ts: torch.Tensor, barrier: Optional[torch.Tensor] = None,
     if rc != EBSP_OK:
         raise ZipLineError(f"ebsp_zipline_batch failed ({rc}): {ebsp_last_error()}")
     return outs
+
+
+def ebsp_zipline_copy_probe(src: torch.Tensor, dst: torch.Tensor) -> None:
+    """Plain streaming device copy src -> dst (same byte size) on the current stream: a bandwidth yardstick."""
+    nbytes = src.numel() * src.element_size()
+    if not (src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous()
+            and dst.numel() * dst.element_size() == nbytes):
+        raise ValueError("src and dst must be contiguous CUDA tensors of the same byte size")
+    with torch.cuda.device(src.device):
+        rc = load().ebsp_zipline_copy_probe(src.data_ptr(), dst.data_ptr(), nbytes,
+                                            torch.cuda.current_stream(src.device).cuda_stream)
+    if rc != EBSP_OK:
+        raise ZipLineError(f"ebsp_zipline_copy_probe failed ({rc}): {ebsp_last_error()}")
 
 
 def ebsp_zipline_profile_begin(max_calls: int) -> None:
