@@ -416,7 +416,7 @@ __device__ __forceinline__ void fill_sentinels(u64* recs, int total, int items)
 // of row p before the interval).  Rows are taken NT at a time: a block scan of
 // the segment lengths gives every row its first slot, then consecutive threads
 // take consecutive slots, so reads within a segment coalesce.
-template <int NT, bool WIDE>
+template <int NT, bool WIDE, bool PAD>
 __device__ __forceinline__ int zl_delta(const Smem& sm, const Rows& rw, u64 a, u64 el, bool lx, bool rx,
                                         int cap, u64& w0, int& bad)
 {
@@ -456,7 +456,7 @@ __device__ __forceinline__ int zl_delta(const Smem& sm, const Rows& rw, u64 a, u
                 bad |= (cur < prv);
             }
             const u64 dl = rel - prel;
-            const int slot = phys(total + e);
+            const int slot = PAD ? phys(total + e) : total + e;
             sm.recs[slot] = (u64)(u32)(rel - a) | (dl << 32);
             if (WIDE) sm.dhi[slot] = (u32)(dl >> 32);
         }
@@ -464,6 +464,137 @@ __device__ __forceinline__ int zl_delta(const Smem& sm, const Rows& rw, u64 a, u
         __syncthreads();
     }
     return total;
+}
+
+// ---------------------------------------------------------------------------
+// Fast path of zl_sort + zl_scan + zl_argmin for one window whose keys are
+// spread evenly enough: a counting sort into NB value buckets (LDS atomics; the
+// order inside a bucket does not matter) followed by direct evaluation.
+// With BP(b) = sum of the deltas in all buckets below b, the prefix sum at an
+// element of bucket b is BP(b) + the deltas of the bucket's elements whose key
+// is <= its own; equal keys get equal values, so no run-end rule is needed.
+// The work is total + sum over buckets of size^2: a bucket with more than
+// BUCKET_LIMIT entries makes the caller fall back to the radix sort.
+template <int NT, int ITEMS>
+struct HotCfg {
+    static constexpr int NW = NT / WAVE;
+    static constexpr int CAP = NT * ITEMS;
+    static constexpr int NB = 2 * NT;                     // value buckets; each thread scans two
+    static constexpr int RED_WORDS = 2 * NW + 8;
+    static constexpr size_t BYTES = (size_t)CAP * 8 + (size_t)NB * 8 + (size_t)RED_WORDS * 8 + (size_t)NB * 4;
+};
+constexpr u32 BUCKET_LIMIT = 64;
+
+template <int NT, int ITEMS>
+__device__ __forceinline__ Smem carve_hot(unsigned char* smem)
+{
+    using H = HotCfg<NT, ITEMS>;
+    Smem s;
+    s.recs = (u64*)smem;
+    s.dhi = nullptr;
+    s.red = s.recs + H::CAP + H::NB;      // bucket sums sit between the records and the scratch
+    s.cnt = (u32*)(s.red + H::RED_WORDS);
+    return s;
+}
+
+// Records [0, total) in any order -> first minimum (wait, key) of
+// P*key + W0 - S(key) over keys with a + key >= thr.  `span` = largest possible key.
+// Returns false (nothing computed) if some bucket is over the limit.
+template <int NT, int ITEMS>
+__device__ __forceinline__ bool zl_bucket_search(const Smem& sm, int total, u64 a, u64 thr, u64 P, u64 W0,
+                                                 u64 span, u64& best_wait, u32& best_key)
+{
+    using H = HotCfg<NT, ITEMS>;
+    u64* recs = sm.recs;
+    u64* bsum = sm.recs + H::CAP;
+    u32* cnt = sm.cnt;
+    const int tid = threadIdx.x;
+    const u64 qv = ((u64)H::NB << 32) / (span + 1);
+    const u32 invb = qv >= 0xffffffffull ? 0xffffffffu : (qv ? (u32)qv : 1u);   // bucket = (key * invb) >> 32
+
+    cnt[tid] = 0; cnt[tid + NT] = 0;
+    bsum[tid] = 0; bsum[tid + NT] = 0;
+    __syncthreads();
+    // zl_sort, step 1: histogram of bucket ids and of the deltas per bucket
+    u32 key[ITEMS], dl[ITEMS];
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        const int q = j * NT + tid;
+        if (q < total) {
+            const u64 r = recs[q];
+            key[j] = (u32)r;
+            dl[j] = (u32)(r >> 32);
+            const u32 bid = (u32)(((u64)key[j] * invb) >> 32);
+            atomicAdd(&cnt[bid], 1u);
+            atomicAdd(&bsum[bid], (u64)dl[j]);
+        }
+    }
+    __syncthreads();
+    // step 2: exclusive scans over the buckets (two per thread)
+    const u32 c0 = cnt[2 * tid], c1 = cnt[2 * tid + 1];
+    const u64 s0 = bsum[2 * tid], s1 = bsum[2 * tid + 1];
+    u32 call;
+    u64 sall;
+    const u32 cbase = block_excl_scan<u32, NT>(c0 + c1, (u32*)sm.red, call);
+    const u64 sbase = block_excl_scan<u64, NT>(s0 + s1, sm.red, sall);
+    const u32 biggest = block_reduce<u32, NT>(c0 > c1 ? c0 : c1, (u32*)sm.red, OpMax());
+    if (biggest > BUCKET_LIMIT) return false;
+    cnt[2 * tid] = cbase; cnt[2 * tid + 1] = cbase + c0;
+    bsum[2 * tid] = sbase; bsum[2 * tid + 1] = sbase + s0;
+    __syncthreads();
+    // step 3: scatter; afterwards cnt[b] is the end of bucket b
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        const int q = j * NT + tid;
+        if (q < total) {
+            const u32 bid = (u32)(((u64)key[j] * invb) >> 32);
+            const u32 slot = atomicAdd(&cnt[bid], 1u);
+            recs[slot] = (u64)key[j] | ((u64)dl[j] << 32);
+        }
+    }
+    __syncthreads();
+    // zl_scan + zl_argmin: every element evaluates its own candidate
+    u64 bw = U64_MAX;
+    u32 bk = 0xffffffffu;
+    for (int q = tid; q < total; q += NT) {
+        const u32 k = (u32)recs[q];
+        const u32 bid = (u32)(((u64)k * invb) >> 32);
+        const u32 e = cnt[bid];
+        u32 x = bid ? cnt[bid - 1] : 0u;
+        u64 S = bsum[bid];
+        for (; x < e; ++x) {
+            const u64 r = recs[x];
+            if ((u32)r <= k) S += r >> 32;
+        }
+        if (a + k >= thr) {
+            const u64 w = P * (u64)k + W0 - S;
+            if (w < bw || (w == bw && k < bk)) { bw = w; bk = k; }
+        }
+    }
+    // block arg-min over (wait, key): smaller wait, then smaller key
+#pragma unroll
+    for (int d = WAVE / 2; d > 0; d >>= 1) {
+        const u64 ow = __shfl_xor(bw, d, WAVE);
+        const u32 ok = __shfl_xor(bk, d, WAVE);
+        if (ow < bw || (ow == bw && ok < bk)) { bw = ow; bk = ok; }
+    }
+    constexpr int NW = NT / WAVE;
+    const int lane = tid & (WAVE - 1), wave = tid >> 6;
+    u64* red = sm.red;
+    if (lane == 0) { red[wave] = bw; red[NW + wave] = bk; }
+    __syncthreads();
+    bw = red[0];
+    bk = (u32)red[NW];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) {
+        const u64 ow = red[w];
+        const u32 ok = (u32)red[NW + w];
+        if (ow < bw || (ow == bw && ok < bk)) { bw = ow; bk = ok; }
+    }
+    __syncthreads();
+    best_wait = bw;
+    best_key = bk;
+    return true;
 }
 
 // Number of entries of the rows inside [a, el].
@@ -499,7 +630,7 @@ __device__ __forceinline__ void zl_window(const Smem& sm, const Rows& rw, u64 th
         bool rx = true;
         if (el - a > 0xffffffffull) { el = a + 0xffffffffull; rx = false; }
         u64 w0 = 0;
-        int total = zl_delta<NT, WIDE>(sm, rw, a, el, lx, rx, CAPW, w0, bad);
+        int total = zl_delta<NT, WIDE, true>(sm, rw, a, el, lx, rx, CAPW, w0, bad);
         bool single = false;
         if (total > CAPW) {
             if (count_interval<NT>(sm, rw, a, a, lx) > (u32)CAPW) {
@@ -513,7 +644,7 @@ __device__ __forceinline__ void zl_window(const Smem& sm, const Rows& rw, u64 th
                 }
                 el = l;
                 w0 = 0;
-                total = zl_delta<NT, WIDE>(sm, rw, a, el, lx, false, CAPW, w0, bad);
+                total = zl_delta<NT, WIDE, true>(sm, rw, a, el, lx, false, CAPW, w0, bad);
             }
             rx = false;
         }
@@ -567,9 +698,9 @@ __global__ __launch_bounds__(NT) void zl_instance_kernel(
     i64* __restrict__ barrier, int* __restrict__ iters, i64* __restrict__ wait,
     int* __restrict__ status)
 {
-    using C = WinCfg<NT, ITEMS>;
-    __shared__ __align__(16) unsigned char smem[C::BYTES];
-    const Smem sm = carve<NT, ITEMS>(smem);
+    using H = HotCfg<NT, ITEMS>;
+    __shared__ __align__(16) unsigned char smem[H::BYTES];
+    const Smem sm = carve_hot<NT, ITEMS>(smem);
 
     const int tid = threadIdx.x;
     const i64 b = blockIdx.x;
@@ -610,15 +741,15 @@ __global__ __launch_bounds__(NT) void zl_instance_kernel(
             prel = (u32)((u64)prv - (u64)base);
             bad |= (cur < prv);
         }
-        sm.recs[phys(e)] = (u64)rel | ((u64)(rel - prel) << 32);
+        sm.recs[e] = (u64)rel | ((u64)(rel - prel) << 32);
     }
-    const int items = (n + NT - 1) / NT;
-    fill_sentinels<NT>(sm.recs, n, items);
     if (__syncthreads_or(bad)) flags |= EBSP_STATUS_UNSORTED;
-    zl_sort<NT, ITEMS, false>(sm, items, bit_length(range));
     u64 best_wait;
     u32 key;
-    zl_scan_argmin<NT, false>(sm, items, n, 0ull, thr, (u64)P, 0ull, best_wait, key);
+    if (!zl_bucket_search<NT, ITEMS>(sm, n, 0ull, thr, (u64)P, 0ull, range, best_wait, key)) {
+        if (tid == 0) wait[b] = DEFERRED;      // clustered values: left to zl_instance_general_kernel
+        return;
+    }
     const i64 bar = (i64)((u64)base + key);
     if (tid == 0) {
         barrier[b] = bar;
@@ -629,8 +760,9 @@ __global__ __launch_bounds__(NT) void zl_instance_kernel(
         iters[b * (i64)P + p] = zl_iters(inst + (size_t)p * R, R, bar);
 }
 
-// The instances zl_instance_kernel deferred (value spread of 2^32 or more):
-// the general window search over whole rows, one workgroup per instance.
+// The instances zl_instance_kernel deferred (value spread of 2^32 or more, or
+// values too clustered for the bucket search): the general window search over
+// whole rows, one workgroup per instance.
 template <int NT, int ITEMS>
 __global__ __launch_bounds__(NT) void zl_instance_general_kernel(
     const i64* __restrict__ ts, int P, int R,
@@ -665,6 +797,7 @@ __global__ __launch_bounds__(NT) void zl_instance_general_kernel(
     rw.cr = nullptr; rw.stride = 0; rw.k0 = rw.k1 = 0;
     int bad = 0;
     u64 best_wait = U64_MAX, best_rel = 0;
+    // the 64-bit-delta form serves every deferred instance, narrow ones included
     zl_window<NT, ITEMS, true>(sm, rw, thr, 0ull, range, best_wait, best_rel, bad);
     if (__syncthreads_or(bad)) flags |= EBSP_STATUS_UNSORTED;
     const i64 bar = (i64)((u64)base + best_rel);
@@ -862,9 +995,9 @@ __global__ __launch_bounds__(NT) void zl_window_kernel(
     const u32* __restrict__ winstart, int max_win,
     Partial* __restrict__ partial, int* __restrict__ status)
 {
-    using C = WinCfg<NT, ITEMS>;
-    __shared__ __align__(16) unsigned char smem[C::BYTES];
-    const Smem sm = carve<NT, ITEMS>(smem);
+    using H = HotCfg<NT, ITEMS>;
+    __shared__ __align__(16) unsigned char smem[H::BYTES];
+    const Smem sm = carve_hot<NT, ITEMS>(smem);
     InstInfo ii;
     const WinPos w = locate_window(ts, B, P, R, info, ii, cross, stride, winstart, max_win, ii);
     if (w.b >= B || w.j >= (int)ii.nwin) return;
@@ -878,19 +1011,20 @@ __global__ __launch_bounds__(NT) void zl_window_kernel(
         int total = 0;
         u64 w0 = 0;
         if (!defer) {
-            total = zl_delta<NT, false>(sm, w.rw, w.A, w.Elast, true, true, C::CAP, w0, bad);
-            defer = total > C::CAP;
+            total = zl_delta<NT, false, false>(sm, w.rw, w.A, w.Elast, true, true, H::CAP, w0, bad);
+            defer = total > H::CAP;
+        }
+        if (!defer && total > 0) {
+            const u64 W0 = block_reduce<u64, NT>(w0, sm.red, OpAdd());   // also orders the record writes
+            u32 key;
+            if (zl_bucket_search<NT, ITEMS>(sm, total, w.A, ii.thr, (u64)P, W0, w.Elast - w.A, r.wait, key))
+                r.brel = w.A + key;
+            else
+                defer = true;
         }
         if (defer) {
+            r.wait = U64_MAX;
             r.brel = DEFERRED_WINDOW;
-        } else if (total > 0) {
-            const int items = (total + NT - 1) / NT;
-            fill_sentinels<NT>(sm.recs, total, items);
-            const u64 W0 = block_reduce<u64, NT>(w0, sm.red, OpAdd());   // also orders the record writes
-            zl_sort<NT, ITEMS, false>(sm, items, bit_length(w.Elast - w.A));
-            u32 key;
-            zl_scan_argmin<NT, false>(sm, items, total, w.A, ii.thr, (u64)P, W0, r.wait, key);
-            r.brel = w.A + key;
         }
     }
     bad = __syncthreads_or(bad);
