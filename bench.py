@@ -59,6 +59,8 @@ def main() -> int:
     ap.add_argument("--copy-probe", type=int, default=3,
                     help="launches of the plain copy kernel (the input's size) after the timed region; "
                          "its bandwidth and byte counters are the yardstick for the others (0: skip)")
+    ap.add_argument("--window-cap", type=int, default=0, help="tuning: records per window workgroup (0: default)")
+    ap.add_argument("--single-max", type=int, default=0, help="tuning: largest P*R taken by one workgroup (0: default)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (instances are independent and would "
@@ -70,6 +72,7 @@ def main() -> int:
     import torch
     from paper_2001_01347_amd import workloads, zipline
 
+    zipline.ebsp_zipline_tune(args.window_cap, args.single_max)
     cfg = workloads.CONFIGS[args.config]
     B, P, R = cfg.B, cfg.P, cfg.R
     n_keys = cfg.n_keys

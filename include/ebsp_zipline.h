@@ -80,6 +80,18 @@ int ebsp_zipline_batch(const int64_t* ts, int64_t B, int32_t P, int32_t R,
                        void* stream);
 
 /*
+ * Tuning knobs (process-wide; call before ebsp_zipline_workspace_bytes, since
+ * the workspace size depends on them; not thread-safe against running calls).
+ *   window_cap  records one window workgroup holds on the multi-window path:
+ *               4096, 8192 or 16384; 0 = chosen from P (the default).
+ *   single_max  largest P*R that one workgroup handles whole (1..16384);
+ *               0 = 16384 (the default).  Larger instances take the
+ *               multi-window path.
+ * Results do not depend on either.  Returns EBSP_OK or EBSP_ERR_SHAPE.
+ */
+int ebsp_zipline_tune(int32_t window_cap, int32_t single_max);
+
+/*
  * Per-kernel timing for benchmarks.  Between ebsp_zipline_profile_begin() and
  * ebsp_zipline_profile_end() every ebsp_zipline_batch call made by the calling
  * thread records a pair of HIP events around each kernel it launches, on the

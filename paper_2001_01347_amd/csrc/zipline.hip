@@ -50,11 +50,12 @@ constexpr u64 DEFERRED_WINDOW = ~0ull - 1;      // Partial::brel of a window lef
 
 // ---------------------------------------------------------------------------
 // Tunables of the multi-window path.
-constexpr int LARGE_NT = 1024;               // threads of a window workgroup
+constexpr int LARGE_NT = 1024;               // threads of a general-path workgroup
 constexpr int LARGE_ITEMS = 16;              // records per thread
-constexpr int LARGE_CAP = LARGE_NT * LARGE_ITEMS;   // records a window may hold
-constexpr int GROUP_SHIFT = 13;              // windows are cut every 2^13 keys ...
-constexpr int FINE_SHIFT = 11;               // ... out of fine bins of at most 2^11 keys on average
+constexpr int SINGLE_MAX = LARGE_NT * LARGE_ITEMS;  // largest P*R one workgroup takes whole
+constexpr int GENERAL_GRID = 256;            // workgroups of a general-path kernel (one per CU)
+// A window workgroup holds up to `cap` records (4096, 8192 or 16384).  Windows are
+// cut every cap/2 keys out of fine bins that hold at most cap/8 keys on average.
 
 // Per-instance facts shared by the kernels of the multi-window path.
 struct InstInfo {
@@ -129,6 +130,33 @@ __device__ __forceinline__ T block_reduce(T v, T* red, Op op)
     asm volatile("" : "+v"(r));      // finish the reduction here, not wherever the result is first used
     __syncthreads();
     return r;
+}
+
+// min of a, max of b, max of c over the block in one exchange.  `red` holds 3*NT/64 words.
+template <int NT>
+__device__ __forceinline__ void block_bounds(i64 a, i64 b, i64 c, i64* red, i64& amin, i64& bmax, i64& cmax)
+{
+    constexpr int NW = NT / WAVE;
+    const int lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int d = WAVE / 2; d > 0; d >>= 1) {
+        const i64 oa = __shfl_xor(a, d, WAVE), ob = __shfl_xor(b, d, WAVE), oc = __shfl_xor(c, d, WAVE);
+        a = oa < a ? oa : a;
+        b = ob > b ? ob : b;
+        c = oc > c ? oc : c;
+    }
+    if (lane == 0) { red[wave] = a; red[NW + wave] = b; red[2 * NW + wave] = c; }
+    __syncthreads();
+    a = red[0]; b = red[NW]; c = red[2 * NW];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) {
+        const i64 oa = red[w], ob = red[NW + w], oc = red[2 * NW + w];
+        a = oa < a ? oa : a;
+        b = ob > b ? ob : b;
+        c = oc > c ? oc : c;
+    }
+    __syncthreads();
+    amin = a; bmax = b; cmax = c;
 }
 
 __device__ __forceinline__ int bit_length(u64 x) { return x ? 64 - __clzll((long long)x) : 0; }
@@ -223,7 +251,7 @@ struct WinCfg {
     static constexpr int RECS_WIDE = NT * ITEMS_WIDE + NT * ITEMS_WIDE / 16 + 2;
     static constexpr size_t REC_BYTES = (size_t)RECS * 8 > (size_t)RECS_WIDE * 12 ? (size_t)RECS * 8 : (size_t)RECS_WIDE * 12;
     static constexpr int CNT_WORDS = (NW * RADIX_MAX > 2 * NT) ? NW * RADIX_MAX : 2 * NT;
-    static constexpr int RED_WORDS = 2 * NW + 8;          // u64 scratch for scans and reductions
+    static constexpr int RED_WORDS = 3 * NW + 8;          // u64 scratch for scans and reductions
     static constexpr size_t BYTES = (REC_BYTES + 15) / 16 * 16 + (size_t)RED_WORDS * 8 + (size_t)CNT_WORDS * 4;
 };
 
@@ -475,12 +503,46 @@ __device__ __forceinline__ int zl_delta(const Smem& sm, const Rows& rw, u64 a, u
 // is <= its own; equal keys get equal values, so no run-end rule is needed.
 // The work is total + sum over buckets of size^2: a bucket with more than
 // BUCKET_LIMIT entries makes the caller fall back to the radix sort.
+// One exchange for three block-wide results: exclusive scans of c (u32) and s (u64)
+// and the maximum of m.  `red` holds 3*NT/64 u64 words.
+template <int NT>
+__device__ __forceinline__ void block_scan_pair(u32 c, u64 s, u32 m, u64* red, u32& cbase, u64& sbase, u32& mmax)
+{
+    constexpr int NW = NT / WAVE;
+    const int lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x >> 6;
+    u32 ci = c;
+    u64 si = s;
+#pragma unroll
+    for (int d = 1; d < WAVE; d <<= 1) {
+        const u32 oc = __shfl_up(ci, d, WAVE);
+        const u64 os = __shfl_up(si, d, WAVE);
+        if (lane >= d) { ci += oc; si += os; }
+    }
+#pragma unroll
+    for (int d = WAVE / 2; d > 0; d >>= 1) { const u32 o = __shfl_xor(m, d, WAVE); m = o > m ? o : m; }
+    if (lane == WAVE - 1) { red[wave] = si; red[NW + wave] = ((u64)m << 32) | ci; }
+    __syncthreads();
+    u32 cb = 0, mm = 0;
+    u64 sb = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+        const u64 xs = red[w], xc = red[NW + w];
+        if (w < wave) { sb += xs; cb += (u32)xc; }
+        const u32 xm = (u32)(xc >> 32);
+        mm = xm > mm ? xm : mm;
+    }
+    __syncthreads();
+    cbase = cb + ci - c;
+    sbase = sb + si - s;
+    mmax = mm;
+}
+
 template <int NT, int ITEMS>
 struct HotCfg {
     static constexpr int NW = NT / WAVE;
     static constexpr int CAP = NT * ITEMS;
     static constexpr int NB = 2 * NT;                     // value buckets; each thread scans two
-    static constexpr int RED_WORDS = 2 * NW + 8;
+    static constexpr int RED_WORDS = 3 * NW + 8;
     static constexpr size_t BYTES = (size_t)CAP * 8 + (size_t)NB * 8 + (size_t)RED_WORDS * 8 + (size_t)NB * 4;
 };
 constexpr u32 BUCKET_LIMIT = 64;
@@ -498,11 +560,12 @@ __device__ __forceinline__ Smem carve_hot(unsigned char* smem)
 }
 
 // Records [0, total) in any order -> first minimum (wait, key) of
-// P*key + W0 - S(key) over keys with a + key >= thr.  `span` = largest possible key.
+// P*key + W0 - S(key) over keys with a + key >= thr.  `span` = largest possible key;
+// `shift` is added (mod 2^32) to every stored key first.
 // Returns false (nothing computed) if some bucket is over the limit.
 template <int NT, int ITEMS>
 __device__ __forceinline__ bool zl_bucket_search(const Smem& sm, int total, u64 a, u64 thr, u64 P, u64 W0,
-                                                 u64 span, u64& best_wait, u32& best_key)
+                                                 u64 span, u32 shift, u64& best_wait, u32& best_key)
 {
     using H = HotCfg<NT, ITEMS>;
     u64* recs = sm.recs;
@@ -522,7 +585,7 @@ __device__ __forceinline__ bool zl_bucket_search(const Smem& sm, int total, u64 
         const int q = j * NT + tid;
         if (q < total) {
             const u64 r = recs[q];
-            key[j] = (u32)r;
+            key[j] = (u32)r + shift;
             dl[j] = (u32)(r >> 32);
             const u32 bid = (u32)(((u64)key[j] * invb) >> 32);
             atomicAdd(&cnt[bid], 1u);
@@ -533,11 +596,9 @@ __device__ __forceinline__ bool zl_bucket_search(const Smem& sm, int total, u64 
     // step 2: exclusive scans over the buckets (two per thread)
     const u32 c0 = cnt[2 * tid], c1 = cnt[2 * tid + 1];
     const u64 s0 = bsum[2 * tid], s1 = bsum[2 * tid + 1];
-    u32 call;
-    u64 sall;
-    const u32 cbase = block_excl_scan<u32, NT>(c0 + c1, (u32*)sm.red, call);
-    const u64 sbase = block_excl_scan<u64, NT>(s0 + s1, sm.red, sall);
-    const u32 biggest = block_reduce<u32, NT>(c0 > c1 ? c0 : c1, (u32*)sm.red, OpMax());
+    u32 cbase, biggest;
+    u64 sbase;
+    block_scan_pair<NT>(c0 + c1, s0 + s1, c0 > c1 ? c0 : c1, sm.red, cbase, sbase, biggest);
     if (biggest > BUCKET_LIMIT) return false;
     cnt[2 * tid] = cbase; cnt[2 * tid + 1] = cbase + c0;
     bsum[2 * tid] = sbase; bsum[2 * tid + 1] = sbase + s0;
@@ -562,9 +623,16 @@ __device__ __forceinline__ bool zl_bucket_search(const Smem& sm, int total, u64 
         const u32 e = cnt[bid];
         u32 x = bid ? cnt[bid - 1] : 0u;
         u64 S = bsum[bid];
-        for (; x < e; ++x) {
-            const u64 r = recs[x];
-            if ((u32)r <= k) S += r >> 32;
+        for (; x < e; x += 4) {                       // four entries per trip: one LDS round trip, not four
+            const u32 last = e - 1;
+            const u64 r0 = recs[x];
+            const u64 r1 = recs[x + 1 < e ? x + 1 : last];
+            const u64 r2 = recs[x + 2 < e ? x + 2 : last];
+            const u64 r3 = recs[x + 3 < e ? x + 3 : last];
+            S += ((u32)r0 <= k) ? r0 >> 32 : 0ull;
+            S += (x + 1 < e && (u32)r1 <= k) ? r1 >> 32 : 0ull;
+            S += (x + 2 < e && (u32)r2 <= k) ? r2 >> 32 : 0ull;
+            S += (x + 3 < e && (u32)r3 <= k) ? r3 >> 32 : 0ull;
         }
         if (a + k >= thr) {
             const u64 w = P * (u64)k + W0 - S;
@@ -595,6 +663,77 @@ __device__ __forceinline__ bool zl_bucket_search(const Smem& sm, int total, u64 
     best_wait = bw;
     best_key = bk;
     return true;
+}
+
+// zl_delta for the fast window path: the rows' index ranges are exactly the
+// window (no searching) and everything fits 32 bits.  Two sweeps:
+//   1. one thread per row: its segment length, its share of W0, a block scan for
+//      its first slot, and the source index of every element of the segment
+//      written into that element's slot;
+//   2. one thread per slot: read the source index, load the element and its
+//      predecessor (all loads of a thread in flight together; consecutive slots
+//      are consecutive addresses within a segment), overwrite the slot with the
+//      (key, delta) record.
+// Returns the number of entries; nothing is loaded if it exceeds `cap`.
+template <int NT, int ITEMS>
+__device__ __forceinline__ int zl_delta_rows(const Smem& sm, const Rows& rw, u64 a, int cap, u64& w0, int& bad)
+{
+    const int tid = threadIdx.x;
+    u64* recs = sm.recs;
+    int total = 0;
+    for (int p0 = 0; p0 < rw.P; p0 += NT) {
+        const int p = p0 + tid;
+        u32 lo = 0, hi = 0;
+        if (p < rw.P) {
+            rw.range(p, lo, hi);
+            if (lo > 0) w0 += a - rw.rel(p, lo - 1);
+        }
+        u32 chunk;
+        const u32 off = block_excl_scan<u32, NT>(hi - lo, (u32*)sm.red, chunk);
+        // source = index into the instance; bit 31 marks a row's very first entry
+        u32 src = (u32)p * (u32)rw.R + lo;
+        u32 slot = (u32)total + off;
+        for (u32 i = lo; i < hi && slot < (u32)cap; ++i, ++src, ++slot)
+            recs[slot] = i == 0 ? (src | 0x80000000u) : src;
+        total += (int)chunk;
+    }
+    __syncthreads();
+    if (total > cap) return total;
+
+    constexpr int G = ITEMS < 8 ? ITEMS : 8;              // loads in flight per thread and sweep
+#pragma unroll
+    for (int g = 0; g < ITEMS; g += G) {
+        if (g * NT < total) {
+            u32 src[G];
+            i64 cur[G], prv[G];
+#pragma unroll
+            for (int j = 0; j < G; ++j) {
+                const int q = (g + j) * NT + tid;
+                src[j] = q < total ? (u32)recs[q] : 0x80000000u;
+            }
+#pragma unroll
+            for (int j = 0; j < G; ++j) {
+                const int q = (g + j) * NT + tid;
+                const u32 at = src[j] & 0x7fffffffu;
+                cur[j] = q < total ? rw.inst[at] : 0;
+                prv[j] = (q < total && !(src[j] >> 31)) ? rw.inst[at - 1] : 0;
+            }
+#pragma unroll
+            for (int j = 0; j < G; ++j) {
+                const int q = (g + j) * NT + tid;
+                if (q < total) {
+                    const u32 key = (u32)((u64)cur[j] - rw.base - a);
+                    u32 dl = key;                              // first entry of its row: delta from the window start
+                    if (!(src[j] >> 31)) {
+                        dl = (u32)((u64)cur[j] - (u64)prv[j]);
+                        bad |= (cur[j] < prv[j]);
+                    }
+                    recs[q] = (u64)key | ((u64)dl << 32);
+                }
+            }
+        }
+    }
+    return total;
 }
 
 // Number of entries of the rows inside [a, el].
@@ -707,19 +846,45 @@ __global__ __launch_bounds__(NT) void zl_instance_kernel(
     const int n = P * R;
     const i64* __restrict__ inst = ts + b * (i64)n;
 
-    // instance bounds: base = min first, thr = max first, top = max last
-    i64 mn = INT64_MAX, mxf = INT64_MIN, mxl = INT64_MIN;
-    for (int p = tid; p < P; p += NT) {
-        const i64 f = inst[(size_t)p * R], l = inst[(size_t)p * R + R - 1];
-        mn = f < mn ? f : mn;
-        mxf = f > mxf ? f : mxf;
-        mxl = l > mxl ? l : mxl;
+    // zl_delta.  Every element is loaded once, all loads of a thread in flight
+    // together: wave w takes elements [w*64*items, (w+1)*64*items), 64 consecutive
+    // ones per round, so the previous element sits in the neighbouring lane.
+    // The instance minimum is not known yet, so keys are first taken relative to
+    // the instance's first element t00 (mod 2^32) and shifted afterwards.
+    const int lane = tid & (WAVE - 1), wave = tid >> 6;
+    const int items = (n + NT - 1) / NT;
+    const int wbase = wave * WAVE * items;
+    const i64 t00 = inst[0];
+    i64 v[ITEMS];
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        const int e = wbase + j * WAVE + lane;
+        v[j] = (j < items && e < n) ? inst[e] : 0;
     }
-    const i64 base = block_reduce<i64, NT>(mn, (i64*)sm.red, OpMin());
-    const i64 first_max = block_reduce<i64, NT>(mxf, (i64*)sm.red, OpMax());
-    const i64 last_max = block_reduce<i64, NT>(mxl, (i64*)sm.red, OpMax());
+    i64 carry = (wbase > 0 && wbase < n) ? inst[wbase - 1] : 0;   // element ahead of the wave's first
+    i64 mn = INT64_MAX, mxf = INT64_MIN, mxl = INT64_MIN;         // min first, max first, max last of the rows
+    int bad = 0;
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        const int e = wbase + j * WAVE + lane;
+        i64 prv = __shfl_up(v[j], 1, WAVE);
+        if (lane == 0) prv = carry;
+        carry = __shfl(v[j], WAVE - 1, WAVE);
+        if (j < items && e < n) {
+            const int i = rshift >= 0 ? (e & (R - 1)) : (e % R);
+            const u32 rel = (u32)((u64)v[j] - (u64)t00);
+            u32 dl = rel;                                          // a row's first entry: completed below
+            if (i == 0) { mn = v[j] < mn ? v[j] : mn; mxf = v[j] > mxf ? v[j] : mxf; }
+            else { dl = (u32)((u64)v[j] - (u64)prv); bad |= (v[j] < prv); }
+            if (i == R - 1) mxl = v[j] > mxl ? v[j] : mxl;
+            sm.recs[e] = (u64)rel | ((u64)dl << 32);
+        }
+    }
+    i64 base, first_max, last_max;
+    block_bounds<NT>(mn, mxf, mxl, (i64*)sm.red, base, first_max, last_max);   // also orders the record writes
     const u64 range = (u64)last_max - (u64)base;
     const u64 thr = (u64)first_max - (u64)base;
+    const u32 shift = (u32)((u64)t00 - (u64)base);                 // key relative to base = stored key + shift
 
     u32 flags = 0;
     if (range > (u64)INT64_MAX / (u64)P) flags |= EBSP_STATUS_OVERFLOW;
@@ -729,24 +894,15 @@ __global__ __launch_bounds__(NT) void zl_instance_kernel(
         if (tid == 0) wait[b] = DEFERRED;
         return;
     }
-    // zl_delta in memory order (row p occupies slots [p*R, (p+1)*R)): no row lookup
-    int bad = 0;
-    for (int e = tid; e < n; e += NT) {
-        const int i = rshift >= 0 ? (e & (R - 1)) : (e % R);
-        const i64 cur = inst[e];
-        const u32 rel = (u32)((u64)cur - (u64)base);
-        u32 prel = 0;
-        if (i > 0) {
-            const i64 prv = inst[e - 1];
-            prel = (u32)((u64)prv - (u64)base);
-            bad |= (cur < prv);
-        }
-        sm.recs[e] = (u64)rel | ((u64)(rel - prel) << 32);
+    // a row's first delta is its key relative to base
+    for (int p = tid; p < P; p += NT) {
+        const u64 r = sm.recs[(size_t)p * R];
+        sm.recs[(size_t)p * R] = (u64)(u32)r | ((u64)((u32)(r >> 32) + shift) << 32);
     }
     if (__syncthreads_or(bad)) flags |= EBSP_STATUS_UNSORTED;
     u64 best_wait;
     u32 key;
-    if (!zl_bucket_search<NT, ITEMS>(sm, n, 0ull, thr, (u64)P, 0ull, range, best_wait, key)) {
+    if (!zl_bucket_search<NT, ITEMS>(sm, n, 0ull, thr, (u64)P, 0ull, range, shift, best_wait, key)) {
         if (tid == 0) wait[b] = DEFERRED;      // clustered values: left to zl_instance_general_kernel
         return;
     }
@@ -762,10 +918,11 @@ __global__ __launch_bounds__(NT) void zl_instance_kernel(
 
 // The instances zl_instance_kernel deferred (value spread of 2^32 or more, or
 // values too clustered for the bucket search): the general window search over
-// whole rows, one workgroup per instance.
+// whole rows.  A small fixed grid; every workgroup looks through its share of
+// wait[] for deferred marks and handles the marked instances one after the other.
 template <int NT, int ITEMS>
 __global__ __launch_bounds__(NT) void zl_instance_general_kernel(
-    const i64* __restrict__ ts, int P, int R,
+    const i64* __restrict__ ts, i64 B, int P, int R,
     i64* __restrict__ barrier, int* __restrict__ iters, i64* __restrict__ wait,
     int* __restrict__ status)
 {
@@ -773,41 +930,51 @@ __global__ __launch_bounds__(NT) void zl_instance_general_kernel(
     __shared__ __align__(16) unsigned char smem[C::BYTES];
     const Smem sm = carve<NT, ITEMS>(smem);
     const int tid = threadIdx.x;
-    const i64 b = blockIdx.x;
-    if (wait[b] != DEFERRED) return;
-    const i64* __restrict__ inst = ts + b * (i64)P * R;
+    const u32 total = (u32)B;
+    const u32 share = (total + gridDim.x - 1) / gridDim.x;
+    const u32 first = blockIdx.x * share;
+    const u32 end = first + share < total ? first + share : total;
 
-    i64 mn = INT64_MAX, mxf = INT64_MIN, mxl = INT64_MIN;
-    for (int p = tid; p < P; p += NT) {
-        const i64 f = inst[(size_t)p * R], l = inst[(size_t)p * R + R - 1];
-        mn = f < mn ? f : mn;
-        mxf = f > mxf ? f : mxf;
-        mxl = l > mxl ? l : mxl;
-    }
-    const i64 base = block_reduce<i64, NT>(mn, (i64*)sm.red, OpMin());
-    const i64 first_max = block_reduce<i64, NT>(mxf, (i64*)sm.red, OpMax());
-    const i64 last_max = block_reduce<i64, NT>(mxl, (i64*)sm.red, OpMax());
-    const u64 range = (u64)last_max - (u64)base;
-    const u64 thr = (u64)first_max - (u64)base;
-    u32 flags = 0;
-    if (range > (u64)INT64_MAX / (u64)P) flags |= EBSP_STATUS_OVERFLOW;
+    for (u32 base0 = first; base0 < end; base0 += NT) {
+        const u32 idx = base0 + tid;
+        bool mine = idx < end && wait[idx] == DEFERRED;
+        for (;;) {
+            const u32 b = block_reduce<u32, NT>(mine ? idx : 0xffffffffu, (u32*)sm.red, OpMin());
+            if (b == 0xffffffffu) break;
+            if (b == idx) mine = false;
+            const i64* __restrict__ inst = ts + (i64)b * P * R;
+            i64 mn = INT64_MAX, mxf = INT64_MIN, mxl = INT64_MIN;
+            for (int p = tid; p < P; p += NT) {
+                const i64 f = inst[(size_t)p * R], l = inst[(size_t)p * R + R - 1];
+                mn = f < mn ? f : mn;
+                mxf = f > mxf ? f : mxf;
+                mxl = l > mxl ? l : mxl;
+            }
+            i64 base, first_max, last_max;
+            block_bounds<NT>(mn, mxf, mxl, (i64*)sm.red, base, first_max, last_max);
+            const u64 range = (u64)last_max - (u64)base;
+            const u64 thr = (u64)first_max - (u64)base;
+            u32 flags = 0;
+            if (range > (u64)INT64_MAX / (u64)P) flags |= EBSP_STATUS_OVERFLOW;
 
-    Rows rw;
-    rw.inst = inst; rw.P = P; rw.R = R; rw.base = (u64)base;
-    rw.cr = nullptr; rw.stride = 0; rw.k0 = rw.k1 = 0;
-    int bad = 0;
-    u64 best_wait = U64_MAX, best_rel = 0;
-    // the 64-bit-delta form serves every deferred instance, narrow ones included
-    zl_window<NT, ITEMS, true>(sm, rw, thr, 0ull, range, best_wait, best_rel, bad);
-    if (__syncthreads_or(bad)) flags |= EBSP_STATUS_UNSORTED;
-    const i64 bar = (i64)((u64)base + best_rel);
-    if (tid == 0) {
-        barrier[b] = bar;
-        wait[b] = (i64)best_wait;
-        if (status) status[b] = (int)flags;
+            Rows rw;
+            rw.inst = inst; rw.P = P; rw.R = R; rw.base = (u64)base;
+            rw.cr = nullptr; rw.stride = 0; rw.k0 = rw.k1 = 0;
+            int bad = 0;
+            u64 best_wait = U64_MAX, best_rel = 0;
+            // the 64-bit-delta form serves every deferred instance, narrow ones included
+            zl_window<NT, ITEMS, true>(sm, rw, thr, 0ull, range, best_wait, best_rel, bad);
+            if (__syncthreads_or(bad)) flags |= EBSP_STATUS_UNSORTED;
+            const i64 bar = (i64)((u64)base + best_rel);
+            if (tid == 0) {
+                barrier[b] = bar;
+                wait[b] = (i64)best_wait;
+                if (status) status[b] = (int)flags;
+            }
+            for (int p = tid; p < P; p += NT)
+                iters[(i64)b * P + p] = zl_iters(inst + (size_t)p * R, R, bar);
+        }
     }
-    for (int p = tid; p < P; p += NT)
-        iters[b * (i64)P + p] = zl_iters(inst + (size_t)p * R, R, bar);
 }
 
 // ---------------------------------------------------------------------------
@@ -914,12 +1081,12 @@ __global__ __launch_bounds__(256) void zl_bincount_kernel(
 }
 
 // zl_plan: windows of an instance.  Fine bin k belongs to group
-// below[k] >> GROUP_SHIFT; a window is a maximal run of bins of one group, so
-// it holds fewer than 2^GROUP_SHIFT keys plus its last bin's.
+// below[k] >> group_shift; a window is a maximal run of bins of one group, so
+// it holds fewer than 2^group_shift keys plus its last bin's.
 template <int NT>
 __global__ __launch_bounds__(NT) void zl_plan_kernel(
     InstInfo* __restrict__ info, const u32* __restrict__ below, int stride,
-    u32* __restrict__ winstart, int max_win)
+    u32* __restrict__ winstart, int max_win, int group_shift)
 {
     __shared__ u32 red[NT / WAVE];
     const int tid = threadIdx.x;
@@ -931,7 +1098,7 @@ __global__ __launch_bounds__(NT) void zl_plan_kernel(
     for (int k0 = 0; k0 < nb; k0 += NT) {
         const int k = k0 + tid;
         u32 flag = 0;
-        if (k < nb) flag = (k == 0) || ((bel[k] >> GROUP_SHIFT) != (bel[k - 1] >> GROUP_SHIFT));
+        if (k < nb) flag = (k == 0) || ((bel[k] >> group_shift) != (bel[k - 1] >> group_shift));
         u32 chunk;
         const u32 idx = found + block_excl_scan<u32, NT>(flag, red, chunk);
         if (flag && idx < (u32)max_win) ws[idx] = (u32)k;
@@ -954,15 +1121,11 @@ struct WinPos {
     u64 A, Elast;
 };
 
-__device__ __forceinline__ WinPos locate_window(const i64* ts, i64 B, int P, int R, const InstInfo* info,
-                                                const InstInfo& ii_unused, const u32* cross, int stride,
+__device__ __forceinline__ WinPos locate_window(u32 logical, const i64* ts, i64 B, int P, int R,
+                                                const InstInfo* info, const u32* cross, int stride,
                                                 const u32* winstart, int max_win, InstInfo& ii)
 {
     WinPos w;
-    // Consecutive windows share cache lines at their segment ends: give each
-    // XCD (workgroups are dealt round-robin to the 8 XCDs) a contiguous range.
-    const u32 per_xcd = gridDim.x / 8;
-    const u32 logical = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
     w.b = logical / (u32)max_win;
     w.j = (int)(logical % (u32)max_win);
     w.valid = false;
@@ -998,8 +1161,12 @@ __global__ __launch_bounds__(NT) void zl_window_kernel(
     using H = HotCfg<NT, ITEMS>;
     __shared__ __align__(16) unsigned char smem[H::BYTES];
     const Smem sm = carve_hot<NT, ITEMS>(smem);
+    // Consecutive windows share cache lines at their segment ends: give each
+    // XCD (workgroups are dealt round-robin to the 8 XCDs) a contiguous range.
+    const u32 per_xcd = gridDim.x / 8;
+    const u32 logical = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
     InstInfo ii;
-    const WinPos w = locate_window(ts, B, P, R, info, ii, cross, stride, winstart, max_win, ii);
+    const WinPos w = locate_window(logical, ts, B, P, R, info, cross, stride, winstart, max_win, ii);
     if (w.b >= B || w.j >= (int)ii.nwin) return;
 
     Partial r;
@@ -1011,13 +1178,13 @@ __global__ __launch_bounds__(NT) void zl_window_kernel(
         int total = 0;
         u64 w0 = 0;
         if (!defer) {
-            total = zl_delta<NT, false, false>(sm, w.rw, w.A, w.Elast, true, true, H::CAP, w0, bad);
+            total = zl_delta_rows<NT, ITEMS>(sm, w.rw, w.A, H::CAP, w0, bad);
             defer = total > H::CAP;
         }
         if (!defer && total > 0) {
             const u64 W0 = block_reduce<u64, NT>(w0, sm.red, OpAdd());   // also orders the record writes
             u32 key;
-            if (zl_bucket_search<NT, ITEMS>(sm, total, w.A, ii.thr, (u64)P, W0, w.Elast - w.A, r.wait, key))
+            if (zl_bucket_search<NT, ITEMS>(sm, total, w.A, ii.thr, (u64)P, W0, w.Elast - w.A, 0u, r.wait, key))
                 r.brel = w.A + key;
             else
                 defer = true;
@@ -1034,7 +1201,9 @@ __global__ __launch_bounds__(NT) void zl_window_kernel(
     }
 }
 
-// The windows zl_window_kernel deferred: the general window search.
+// The windows zl_window_kernel deferred: the general window search.  A small
+// fixed grid; every workgroup looks through its share of the window results for
+// deferred marks and handles the marked windows one after the other.
 template <int NT, int ITEMS>
 __global__ __launch_bounds__(NT) void zl_window_general_kernel(
     const i64* __restrict__ ts, i64 B, int P, int R,
@@ -1045,23 +1214,39 @@ __global__ __launch_bounds__(NT) void zl_window_general_kernel(
     using C = WinCfg<NT, ITEMS>;
     __shared__ __align__(16) unsigned char smem[C::BYTES];
     const Smem sm = carve<NT, ITEMS>(smem);
-    InstInfo ii;
-    const WinPos w = locate_window(ts, B, P, R, info, ii, cross, stride, winstart, max_win, ii);
-    if (w.b >= B || w.j >= (int)ii.nwin) return;
-    Partial* out = partial + w.b * (i64)max_win + w.j;
-    if (!(out->wait == U64_MAX && out->brel == DEFERRED_WINDOW)) return;
+    const u32 total = (u32)(B * (i64)max_win);
+    const u32 share = (total + gridDim.x - 1) / gridDim.x;
+    const u32 first = blockIdx.x * share;
+    const u32 end = first + share < total ? first + share : total;
 
-    u64 bw = U64_MAX, bb = 0;
-    int bad = 0;
-    if (ii.range >> 32) zl_window<NT, ITEMS, true>(sm, w.rw, ii.thr, w.A, w.Elast, bw, bb, bad);
-    else zl_window<NT, ITEMS, false>(sm, w.rw, ii.thr, w.A, w.Elast, bw, bb, bad);
-    bad = __syncthreads_or(bad);
-    if (threadIdx.x == 0) {
-        Partial r;
-        r.wait = bw;
-        r.brel = bb;
-        *out = r;
-        if (bad && status) atomicOr(status + w.b, (int)EBSP_STATUS_UNSORTED);
+    for (u32 base = first; base < end; base += NT) {
+        const u32 idx = base + threadIdx.x;
+        bool mine = false;
+        if (idx < end) {
+            const u32 b = idx / (u32)max_win, j = idx % (u32)max_win;
+            if (j < info[b].nwin) mine = partial[idx].wait == U64_MAX && partial[idx].brel == DEFERRED_WINDOW;
+        }
+        for (;;) {
+            const u32 pick = block_reduce<u32, NT>(mine ? idx : 0xffffffffu, (u32*)sm.red, OpMin());
+            if (pick == 0xffffffffu) break;
+            if (pick == idx) mine = false;
+            InstInfo ii;
+            const WinPos w = locate_window(pick, ts, B, P, R, info, cross, stride, winstart, max_win, ii);
+            u64 bw = U64_MAX, bb = 0;
+            int bad = 0;
+            if (w.valid) {
+                // the 64-bit-delta form serves every deferred window, narrow ones included
+                zl_window<NT, ITEMS, true>(sm, w.rw, ii.thr, w.A, w.Elast, bw, bb, bad);
+            }
+            bad = __syncthreads_or(bad);
+            if (threadIdx.x == 0) {
+                Partial r;
+                r.wait = bw;
+                r.brel = bb;
+                partial[pick] = r;
+                if (bad && status) atomicOr(status + w.b, (int)EBSP_STATUS_UNSORTED);
+            }
+        }
     }
 }
 
@@ -1135,8 +1320,16 @@ const char* const kKernelNames[K_COUNT] = {
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // Shape-dependent sizes of the multi-window path.
+struct Tuning {          // 0: choose by shape
+    int window_cap;
+    int single_max;
+};
+Tuning g_tune = {0, 0};
+
 struct Plan {
     bool multi;
+    int cap;           // records per window workgroup
+    int group_shift;   // log2(cap) - 1
     int bins;          // fine bins per instance
     int stride;        // bins + 1 crossing indices per row
     int max_win;       // windows per instance <= max_win
@@ -1149,11 +1342,16 @@ bool make_plan(i64 B, int P, int R, Plan& pl)
     const i64 n = (i64)P * (i64)R;
     if (n >= (1ll << 31)) return false;
     memset(&pl, 0, sizeof pl);
-    pl.multi = n > LARGE_CAP;
+    const int single_max = g_tune.single_max > 0 ? g_tune.single_max : SINGLE_MAX;
+    pl.multi = n > single_max;
     if (!pl.multi) return true;
-    pl.bins = (int)((n + (1 << FINE_SHIFT) - 1) >> FINE_SHIFT);
+    // the per-window cost has a term proportional to P: larger windows for more rows
+    pl.cap = g_tune.window_cap > 0 ? g_tune.window_cap : (P >= 512 ? 8192 : 4096);
+    pl.group_shift = pl.cap == 16384 ? 13 : (pl.cap == 8192 ? 12 : 11);
+    const int fine_shift = pl.group_shift - 2;
+    pl.bins = (int)((n + (1 << fine_shift) - 1) >> fine_shift);
     pl.stride = pl.bins + 1;
-    pl.max_win = (int)((n >> GROUP_SHIFT) + 2);
+    pl.max_win = (int)((n >> pl.group_shift) + 2);
     size_t o = 0;
     pl.off_info = o;     o = align_up(o + (size_t)B * sizeof(InstInfo), 256);
     pl.off_cross = o;    o = align_up(o + (size_t)B * P * pl.stride * sizeof(u32), 256);
@@ -1214,8 +1412,9 @@ int run_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters, i64*
             LAUNCH(K_INSTANCE, (zl_instance_kernel<512, 8>), grid, dim3(512), ts, P, R, rshift, barrier, iters, wait, status);
         else
             LAUNCH(K_INSTANCE, (zl_instance_kernel<1024, 16>), grid, dim3(1024), ts, P, R, rshift, barrier, iters, wait, status);
-        LAUNCH(K_INSTANCE_GENERAL, (zl_instance_general_kernel<LARGE_NT, LARGE_ITEMS>), grid, dim3(LARGE_NT),
-               ts, P, R, barrier, iters, wait, status);
+        LAUNCH(K_INSTANCE_GENERAL, (zl_instance_general_kernel<LARGE_NT, LARGE_ITEMS>),
+               dim3((unsigned)(B < GENERAL_GRID ? B : GENERAL_GRID)), dim3(LARGE_NT),
+               ts, B, P, R, barrier, iters, wait, status);
         return EBSP_OK;
     }
 
@@ -1240,11 +1439,20 @@ int run_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters, i64*
     if (kblocks * B > 0x7fffffffll || pblocks * B > 0x7fffffffll) return fail(EBSP_ERR_SHAPE, "batch too large for one call");
     LAUNCH(K_BINCOUNT, zl_bincount_kernel, dim3((unsigned)(kblocks * B)), dim3(256),
            cross, P, R, pl.stride, info, below);
-    LAUNCH(K_PLAN, (zl_plan_kernel<1024>), dim3((unsigned)B), dim3(1024), info, below, pl.stride, winstart, pl.max_win);
+    LAUNCH(K_PLAN, (zl_plan_kernel<1024>), dim3((unsigned)B), dim3(1024), info, below, pl.stride, winstart, pl.max_win,
+           pl.group_shift);
     const unsigned wgrid = (unsigned)((total_win + 7) / 8 * 8);
-    LAUNCH(K_WINDOW, (zl_window_kernel<LARGE_NT, LARGE_ITEMS>), dim3(wgrid), dim3(LARGE_NT),
-           ts, B, P, R, info, cross, pl.stride, winstart, pl.max_win, partial, status);
-    LAUNCH(K_WINDOW_GENERAL, (zl_window_general_kernel<LARGE_NT, LARGE_ITEMS>), dim3(wgrid), dim3(LARGE_NT),
+    if (pl.cap == 16384)
+        LAUNCH(K_WINDOW, (zl_window_kernel<1024, 16>), dim3(wgrid), dim3(1024),
+               ts, B, P, R, info, cross, pl.stride, winstart, pl.max_win, partial, status);
+    else if (pl.cap == 8192)
+        LAUNCH(K_WINDOW, (zl_window_kernel<512, 16>), dim3(wgrid), dim3(512),
+               ts, B, P, R, info, cross, pl.stride, winstart, pl.max_win, partial, status);
+    else
+        LAUNCH(K_WINDOW, (zl_window_kernel<256, 16>), dim3(wgrid), dim3(256),
+               ts, B, P, R, info, cross, pl.stride, winstart, pl.max_win, partial, status);
+    LAUNCH(K_WINDOW_GENERAL, (zl_window_general_kernel<LARGE_NT, LARGE_ITEMS>),
+           dim3((unsigned)(total_win < GENERAL_GRID ? total_win : GENERAL_GRID)), dim3(LARGE_NT),
            ts, B, P, R, info, cross, pl.stride, winstart, pl.max_win, partial, status);
     LAUNCH(K_FINISH, (zl_finish_kernel<256>), dim3((unsigned)(pblocks * B)), dim3(256),
            ts, P, R, info, partial, pl.max_win, barrier, iters, wait);
@@ -1270,6 +1478,17 @@ int ebsp_zipline_batch(const int64_t* ts, int64_t B, int32_t P, int32_t R,
                              workspace, workspace_bytes, (hipStream_t)stream);
     if (g_prof.on && rc == EBSP_OK && B > 0 && g_prof.calls < g_prof.max_calls) ++g_prof.calls;
     return rc;
+}
+
+int ebsp_zipline_tune(int32_t window_cap, int32_t single_max)
+{
+    if (window_cap != 0 && window_cap != 4096 && window_cap != 8192 && window_cap != 16384)
+        return fail(EBSP_ERR_SHAPE, "window_cap must be 0, 4096, 8192 or 16384");
+    if (single_max < 0 || single_max > SINGLE_MAX)
+        return fail(EBSP_ERR_SHAPE, "single_max must be in 0..16384");
+    g_tune.window_cap = window_cap;
+    g_tune.single_max = single_max;
+    return EBSP_OK;
 }
 
 int ebsp_zipline_copy_probe(const void* src, void* dst, size_t bytes, void* stream)
