@@ -545,7 +545,12 @@ struct HotCfg {
     static constexpr int RED_WORDS = 3 * NW + 8;
     static constexpr size_t BYTES = (size_t)CAP * 8 + (size_t)NB * 8 + (size_t)RED_WORDS * 8 + (size_t)NB * 4;
 };
+// One LDS word per bucket holds its entry count (upper bits) and the sum of its
+// deltas (lower SUM_BITS bits: at most 16384 deltas below 2^32 each).
+constexpr int SUM_BITS = 46;
+constexpr u64 SUM_MASK = (1ull << SUM_BITS) - 1;
 constexpr u32 BUCKET_LIMIT = 64;
+constexpr int GATHER_BATCH = 8;           // elements a thread loads before it uses any of them
 
 template <int NT, int ITEMS>
 __device__ __forceinline__ Smem carve_hot(unsigned char* smem)
@@ -575,7 +580,6 @@ __device__ __forceinline__ bool zl_bucket_search(const Smem& sm, int total, u64 
     const u64 qv = ((u64)H::NB << 32) / (span + 1);
     const u32 invb = qv >= 0xffffffffull ? 0xffffffffu : (qv ? (u32)qv : 1u);   // bucket = (key * invb) >> 32
 
-    cnt[tid] = 0; cnt[tid + NT] = 0;
     bsum[tid] = 0; bsum[tid + NT] = 0;
     __syncthreads();
     // zl_sort, step 1: histogram of bucket ids and of the deltas per bucket
@@ -588,20 +592,21 @@ __device__ __forceinline__ bool zl_bucket_search(const Smem& sm, int total, u64 
             key[j] = (u32)r + shift;
             dl[j] = (u32)(r >> 32);
             const u32 bid = (u32)(((u64)key[j] * invb) >> 32);
-            atomicAdd(&cnt[bid], 1u);
-            atomicAdd(&bsum[bid], (u64)dl[j]);
+            atomicAdd(&bsum[bid], (1ull << SUM_BITS) | (u64)dl[j]);
         }
     }
     __syncthreads();
     // step 2: exclusive scans over the buckets (two per thread)
-    const u32 c0 = cnt[2 * tid], c1 = cnt[2 * tid + 1];
-    const u64 s0 = bsum[2 * tid], s1 = bsum[2 * tid + 1];
+    const u64 h0 = bsum[2 * tid], h1 = bsum[2 * tid + 1];
+    const u32 c0 = (u32)(h0 >> SUM_BITS), c1 = (u32)(h1 >> SUM_BITS);
+    const u64 s0 = h0 & SUM_MASK, s1 = h1 & SUM_MASK;
     u32 cbase, biggest;
     u64 sbase;
     block_scan_pair<NT>(c0 + c1, s0 + s1, c0 > c1 ? c0 : c1, sm.red, cbase, sbase, biggest);
     if (biggest > BUCKET_LIMIT) return false;
     cnt[2 * tid] = cbase; cnt[2 * tid + 1] = cbase + c0;
-    bsum[2 * tid] = sbase; bsum[2 * tid + 1] = sbase + s0;
+    bsum[2 * tid] = sbase | ((u64)cbase << SUM_BITS);                 // BP(bucket) and the bucket's first slot
+    bsum[2 * tid + 1] = (sbase + s0) | ((u64)(cbase + c0) << SUM_BITS);
     __syncthreads();
     // step 3: scatter; afterwards cnt[b] is the end of bucket b
 #pragma unroll
@@ -621,8 +626,9 @@ __device__ __forceinline__ bool zl_bucket_search(const Smem& sm, int total, u64 
         const u32 k = (u32)recs[q];
         const u32 bid = (u32)(((u64)k * invb) >> 32);
         const u32 e = cnt[bid];
-        u32 x = bid ? cnt[bid - 1] : 0u;
-        u64 S = bsum[bid];
+        const u64 hb = bsum[bid];
+        u32 x = (u32)(hb >> SUM_BITS);
+        u64 S = hb & SUM_MASK;
         for (; x < e; x += 4) {                       // four entries per trip: one LDS round trip, not four
             const u32 last = e - 1;
             const u64 r0 = recs[x];
@@ -667,56 +673,91 @@ __device__ __forceinline__ bool zl_bucket_search(const Smem& sm, int total, u64 
 
 // zl_delta for the fast window path: the rows' index ranges are exactly the
 // window (no searching) and everything fits 32 bits.  Two sweeps:
-//   1. one thread per row: its segment length, its share of W0, a block scan for
-//      its first slot, and the source index of every element of the segment
-//      written into that element's slot;
-//   2. one thread per slot: read the source index, load the element and its
+//   1. one thread per row: its segment length, a block scan for its first slot,
+//      and a source word for every element of the segment written into that
+//      element's slot (index into the instance; FIRST_OF_ROW: the row's very
+//      first entry; FIRST_OF_SEGMENT: the entry whose predecessor lies before
+//      the window).  The crossing indices of up to 4*NT rows are fetched
+//      before any of them is used.
+//   2. one thread per slot: read the source word, load the element and its
 //      predecessor (all loads of a thread in flight together; consecutive slots
 //      are consecutive addresses within a segment), overwrite the slot with the
-//      (key, delta) record.
+//      (key, delta) record.  W0 = sum_p (a - last value of row p before the
+//      window) is collected from the segment-first entries; rows without any
+//      entry in the window add their share in sweep 1.
 // Returns the number of entries; nothing is loaded if it exceeds `cap`.
+constexpr u64 FIRST_OF_ROW = 1ull << 32, FIRST_OF_SEGMENT = 1ull << 33;
+
+template <int NT>
+__device__ __forceinline__ void place_row(u64* recs, const Rows& rw, int p, u32 lo, u32 hi, u32 slot, int cap)
+{
+    u64 src = (u64)((u32)p * (u32)rw.R + lo) | FIRST_OF_SEGMENT | (lo == 0 ? FIRST_OF_ROW : 0ull);
+    for (u32 i = lo; i < hi && slot < (u32)cap; ++i, ++slot) {
+        recs[slot] = src;
+        src = (u64)((u32)src + 1u);
+    }
+}
+
 template <int NT, int ITEMS>
 __device__ __forceinline__ int zl_delta_rows(const Smem& sm, const Rows& rw, u64 a, int cap, u64& w0, int& bad)
 {
     const int tid = threadIdx.x;
     u64* recs = sm.recs;
     int total = 0;
-    for (int p0 = 0; p0 < rw.P; p0 += NT) {
-        const int p = p0 + tid;
-        u32 lo = 0, hi = 0;
-        if (p < rw.P) {
-            rw.range(p, lo, hi);
-            if (lo > 0) w0 += a - rw.rel(p, lo - 1);
+    constexpr int MAXCH = 4;
+    if (rw.P <= MAXCH * NT) {
+        u32 lo[MAXCH], hi[MAXCH];
+#pragma unroll
+        for (int c = 0; c < MAXCH; ++c) {
+            const int p = c * NT + tid;
+            lo[c] = 0; hi[c] = 0;
+            if (p < rw.P) rw.range(p, lo[c], hi[c]);
         }
-        u32 chunk;
-        const u32 off = block_excl_scan<u32, NT>(hi - lo, (u32*)sm.red, chunk);
-        // source = index into the instance; bit 31 marks a row's very first entry
-        u32 src = (u32)p * (u32)rw.R + lo;
-        u32 slot = (u32)total + off;
-        for (u32 i = lo; i < hi && slot < (u32)cap; ++i, ++src, ++slot)
-            recs[slot] = i == 0 ? (src | 0x80000000u) : src;
-        total += (int)chunk;
+#pragma unroll
+        for (int c = 0; c < MAXCH; ++c) {
+            if (c * NT < rw.P) {
+                const int p = c * NT + tid;
+                if (p < rw.P && lo[c] == hi[c] && lo[c] > 0) w0 += a - rw.rel(p, lo[c] - 1);
+                u32 chunk;
+                const u32 off = block_excl_scan<u32, NT>(hi[c] - lo[c], (u32*)sm.red, chunk);
+                place_row<NT>(recs, rw, p, lo[c], hi[c], (u32)total + off, cap);
+                total += (int)chunk;
+            }
+        }
+    } else {
+        for (int p0 = 0; p0 < rw.P; p0 += NT) {
+            const int p = p0 + tid;
+            u32 lo = 0, hi = 0;
+            if (p < rw.P) {
+                rw.range(p, lo, hi);
+                if (lo == hi && lo > 0) w0 += a - rw.rel(p, lo - 1);
+            }
+            u32 chunk;
+            const u32 off = block_excl_scan<u32, NT>(hi - lo, (u32*)sm.red, chunk);
+            place_row<NT>(recs, rw, p, lo, hi, (u32)total + off, cap);
+            total += (int)chunk;
+        }
     }
     __syncthreads();
     if (total > cap) return total;
 
-    constexpr int G = ITEMS < 8 ? ITEMS : 8;              // loads in flight per thread and sweep
 #pragma unroll
-    for (int g = 0; g < ITEMS; g += G) {
+    for (int g = 0; g < ITEMS; g += GATHER_BATCH) {
         if (g * NT < total) {
-            u32 src[G];
+            constexpr int G = ITEMS < GATHER_BATCH ? ITEMS : GATHER_BATCH;
+            u64 src[G];
             i64 cur[G], prv[G];
 #pragma unroll
             for (int j = 0; j < G; ++j) {
                 const int q = (g + j) * NT + tid;
-                src[j] = q < total ? (u32)recs[q] : 0x80000000u;
+                src[j] = q < total ? recs[q] : FIRST_OF_ROW;
             }
 #pragma unroll
             for (int j = 0; j < G; ++j) {
                 const int q = (g + j) * NT + tid;
-                const u32 at = src[j] & 0x7fffffffu;
+                const u32 at = (u32)src[j];
                 cur[j] = q < total ? rw.inst[at] : 0;
-                prv[j] = (q < total && !(src[j] >> 31)) ? rw.inst[at - 1] : 0;
+                prv[j] = (q < total && !(src[j] & FIRST_OF_ROW)) ? rw.inst[at - 1] : 0;
             }
 #pragma unroll
             for (int j = 0; j < G; ++j) {
@@ -724,9 +765,10 @@ __device__ __forceinline__ int zl_delta_rows(const Smem& sm, const Rows& rw, u64
                 if (q < total) {
                     const u32 key = (u32)((u64)cur[j] - rw.base - a);
                     u32 dl = key;                              // first entry of its row: delta from the window start
-                    if (!(src[j] >> 31)) {
+                    if (!(src[j] & FIRST_OF_ROW)) {
                         dl = (u32)((u64)cur[j] - (u64)prv[j]);
                         bad |= (cur[j] < prv[j]);
+                        if (src[j] & FIRST_OF_SEGMENT) w0 += a - ((u64)prv[j] - rw.base);
                     }
                     recs[q] = (u64)key | ((u64)dl << 32);
                 }
@@ -1152,7 +1194,7 @@ __device__ __forceinline__ WinPos locate_window(u32 logical, const i64* ts, i64 
 // Handles the normal case (32-bit value spread, the window fits in LDS) and
 // marks every other window as deferred to zl_window_general_kernel.
 template <int NT, int ITEMS>
-__global__ __launch_bounds__(NT) void zl_window_kernel(
+__global__ __launch_bounds__(NT, 4) void zl_window_kernel(
     const i64* __restrict__ ts, i64 B, int P, int R,
     const InstInfo* __restrict__ info, const u32* __restrict__ cross, int stride,
     const u32* __restrict__ winstart, int max_win,
