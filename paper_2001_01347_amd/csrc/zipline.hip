@@ -503,10 +503,11 @@ __device__ __forceinline__ int zl_delta(const Smem& sm, const Rows& rw, u64 a, u
 // is <= its own; equal keys get equal values, so no run-end rule is needed.
 // The work is total + sum over buckets of size^2: a bucket with more than
 // BUCKET_LIMIT entries makes the caller fall back to the radix sort.
-// One exchange for three block-wide results: exclusive scans of c (u32) and s (u64)
-// and the maximum of m.  `red` holds 3*NT/64 u64 words.
-template <int NT>
-__device__ __forceinline__ void block_scan_pair(u32 c, u64 s, u32 m, u64* red, u32& cbase, u64& sbase, u32& mmax)
+// One exchange for four block-wide results: exclusive scans of c (u32) and s (u64),
+// the maximum of m and (WITH_X) the sum of x.  `red` holds 3*NT/64 u64 words.
+template <int NT, bool WITH_X>
+__device__ __forceinline__ void block_scan_pair(u32 c, u64 s, u32 m, u64 x, u64* red,
+                                                u32& cbase, u64& sbase, u32& mmax, u64& xsum)
 {
     constexpr int NW = NT / WAVE;
     const int lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x >> 6;
@@ -519,22 +520,32 @@ __device__ __forceinline__ void block_scan_pair(u32 c, u64 s, u32 m, u64* red, u
         if (lane >= d) { ci += oc; si += os; }
     }
 #pragma unroll
-    for (int d = WAVE / 2; d > 0; d >>= 1) { const u32 o = __shfl_xor(m, d, WAVE); m = o > m ? o : m; }
-    if (lane == WAVE - 1) { red[wave] = si; red[NW + wave] = ((u64)m << 32) | ci; }
+    for (int d = WAVE / 2; d > 0; d >>= 1) {
+        const u32 o = __shfl_xor(m, d, WAVE);
+        m = o > m ? o : m;
+        if (WITH_X) x += __shfl_xor(x, d, WAVE);
+    }
+    if (lane == WAVE - 1) {
+        red[wave] = si;
+        red[NW + wave] = ((u64)m << 32) | ci;
+        if (WITH_X) red[2 * NW + wave] = x;
+    }
     __syncthreads();
     u32 cb = 0, mm = 0;
-    u64 sb = 0;
+    u64 sb = 0, xx = 0;
 #pragma unroll
     for (int w = 0; w < NW; ++w) {
         const u64 xs = red[w], xc = red[NW + w];
         if (w < wave) { sb += xs; cb += (u32)xc; }
         const u32 xm = (u32)(xc >> 32);
         mm = xm > mm ? xm : mm;
+        if (WITH_X) xx += red[2 * NW + w];
     }
     __syncthreads();
     cbase = cb + ci - c;
     sbase = sb + si - s;
     mmax = mm;
+    xsum = xx;
 }
 
 template <int NT, int ITEMS>
@@ -564,45 +575,45 @@ __device__ __forceinline__ Smem carve_hot(unsigned char* smem)
     return s;
 }
 
-// Records [0, total) in any order -> first minimum (wait, key) of
-// P*key + W0 - S(key) over keys with a + key >= thr.  `span` = largest possible key;
-// `shift` is added (mod 2^32) to every stored key first.
+// bucket = (key * scale) >> 32 maps keys in [0, span] onto [0, NB) monotonically.
+__device__ __forceinline__ u32 bucket_scale(u64 span, u32 nb)
+{
+    const u64 q = ((u64)nb << 32) / (span + 1);
+    return q >= 0xffffffffull ? 0xffffffffu : (q ? (u32)q : 1u);
+}
+
+// The records of a window, held ITEMS per thread in registers (item j of thread t
+// is record j*NT + t, present if that is below `total`) -> first minimum
+// (wait, key) of P*key + W0 - S(key) over keys with a + key >= thr, W0 being the
+// block sum of `w0` (taken as 0 unless WITH_W0).
+// On entry the bucket words must be zero and a barrier must have passed since;
+// the record area may hold anything (it is overwritten).
 // Returns false (nothing computed) if some bucket is over the limit.
-template <int NT, int ITEMS>
-__device__ __forceinline__ bool zl_bucket_search(const Smem& sm, int total, u64 a, u64 thr, u64 P, u64 W0,
-                                                 u64 span, u32 shift, u64& best_wait, u32& best_key)
+template <int NT, int ITEMS, bool WITH_W0>
+__device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key)[ITEMS], const u32 (&dl)[ITEMS],
+                                                 u32 scale, int total, u64 a, u64 thr, u64 P, u64 w0,
+                                                 u64& best_wait, u32& best_key)
 {
     using H = HotCfg<NT, ITEMS>;
     u64* recs = sm.recs;
     u64* bsum = sm.recs + H::CAP;
     u32* cnt = sm.cnt;
     const int tid = threadIdx.x;
-    const u64 qv = ((u64)H::NB << 32) / (span + 1);
-    const u32 invb = qv >= 0xffffffffull ? 0xffffffffu : (qv ? (u32)qv : 1u);   // bucket = (key * invb) >> 32
-
-    bsum[tid] = 0; bsum[tid + NT] = 0;
-    __syncthreads();
-    // zl_sort, step 1: histogram of bucket ids and of the deltas per bucket
-    u32 key[ITEMS], dl[ITEMS];
+    // zl_sort, step 1: per bucket, entry count and sum of deltas in one word
 #pragma unroll
-    for (int j = 0; j < ITEMS; ++j) {
-        const int q = j * NT + tid;
-        if (q < total) {
-            const u64 r = recs[q];
-            key[j] = (u32)r + shift;
-            dl[j] = (u32)(r >> 32);
-            const u32 bid = (u32)(((u64)key[j] * invb) >> 32);
+    for (int j = 0; j < ITEMS; ++j)
+        if (j * NT + tid < total) {
+            const u32 bid = (u32)(((u64)key[j] * scale) >> 32);
             atomicAdd(&bsum[bid], (1ull << SUM_BITS) | (u64)dl[j]);
         }
-    }
     __syncthreads();
     // step 2: exclusive scans over the buckets (two per thread)
     const u64 h0 = bsum[2 * tid], h1 = bsum[2 * tid + 1];
     const u32 c0 = (u32)(h0 >> SUM_BITS), c1 = (u32)(h1 >> SUM_BITS);
     const u64 s0 = h0 & SUM_MASK, s1 = h1 & SUM_MASK;
     u32 cbase, biggest;
-    u64 sbase;
-    block_scan_pair<NT>(c0 + c1, s0 + s1, c0 > c1 ? c0 : c1, sm.red, cbase, sbase, biggest);
+    u64 sbase, W0;
+    block_scan_pair<NT, WITH_W0>(c0 + c1, s0 + s1, c0 > c1 ? c0 : c1, w0, sm.red, cbase, sbase, biggest, W0);
     if (biggest > BUCKET_LIMIT) return false;
     cnt[2 * tid] = cbase; cnt[2 * tid + 1] = cbase + c0;
     bsum[2 * tid] = sbase | ((u64)cbase << SUM_BITS);                 // BP(bucket) and the bucket's first slot
@@ -610,21 +621,19 @@ __device__ __forceinline__ bool zl_bucket_search(const Smem& sm, int total, u64 
     __syncthreads();
     // step 3: scatter; afterwards cnt[b] is the end of bucket b
 #pragma unroll
-    for (int j = 0; j < ITEMS; ++j) {
-        const int q = j * NT + tid;
-        if (q < total) {
-            const u32 bid = (u32)(((u64)key[j] * invb) >> 32);
+    for (int j = 0; j < ITEMS; ++j)
+        if (j * NT + tid < total) {
+            const u32 bid = (u32)(((u64)key[j] * scale) >> 32);
             const u32 slot = atomicAdd(&cnt[bid], 1u);
             recs[slot] = (u64)key[j] | ((u64)dl[j] << 32);
         }
-    }
     __syncthreads();
     // zl_scan + zl_argmin: every element evaluates its own candidate
     u64 bw = U64_MAX;
     u32 bk = 0xffffffffu;
     for (int q = tid; q < total; q += NT) {
         const u32 k = (u32)recs[q];
-        const u32 bid = (u32)(((u64)k * invb) >> 32);
+        const u32 bid = (u32)(((u64)k * scale) >> 32);
         const u32 e = cnt[bid];
         const u64 hb = bsum[bid];
         u32 x = (u32)(hb >> SUM_BITS);
@@ -673,70 +682,55 @@ __device__ __forceinline__ bool zl_bucket_search(const Smem& sm, int total, u64 
 
 // zl_delta for the fast window path: the rows' index ranges are exactly the
 // window (no searching) and everything fits 32 bits.  Two sweeps:
-//   1. one thread per row: its segment length, a block scan for its first slot,
-//      and a source word for every element of the segment written into that
-//      element's slot (index into the instance; FIRST_OF_ROW: the row's very
-//      first entry; FIRST_OF_SEGMENT: the entry whose predecessor lies before
-//      the window).  The crossing indices of up to 4*NT rows are fetched
-//      before any of them is used.
+//   1. one thread per row (up to four rows each per round): segment lengths, one
+//      block scan for the first slots, and a source word for every element of a
+//      segment written into that element's slot (index into the instance;
+//      FIRST_OF_ROW: the row's very first entry; FIRST_OF_SEGMENT: the entry whose
+//      predecessor lies before the window).  The crossing indices of a round
+//      are all fetched before any of them is used.
 //   2. one thread per slot: read the source word, load the element and its
-//      predecessor (all loads of a thread in flight together; consecutive slots
-//      are consecutive addresses within a segment), overwrite the slot with the
-//      (key, delta) record.  W0 = sum_p (a - last value of row p before the
-//      window) is collected from the segment-first entries; rows without any
-//      entry in the window add their share in sweep 1.
+//      predecessor (GATHER_BATCH elements of a thread in flight together;
+//      consecutive slots are consecutive addresses within a segment) and keep
+//      the (key, delta) records in registers: item j of thread t is slot
+//      j*NT + t.  W0 = sum_p (a - last value of row p before the window) is
+//      collected from the segment-first entries; rows without any entry in the
+//      window add their share in sweep 1.
 // Returns the number of entries; nothing is loaded if it exceeds `cap`.
 constexpr u64 FIRST_OF_ROW = 1ull << 32, FIRST_OF_SEGMENT = 1ull << 33;
 
-template <int NT>
-__device__ __forceinline__ void place_row(u64* recs, const Rows& rw, int p, u32 lo, u32 hi, u32 slot, int cap)
-{
-    u64 src = (u64)((u32)p * (u32)rw.R + lo) | FIRST_OF_SEGMENT | (lo == 0 ? FIRST_OF_ROW : 0ull);
-    for (u32 i = lo; i < hi && slot < (u32)cap; ++i, ++slot) {
-        recs[slot] = src;
-        src = (u64)((u32)src + 1u);
-    }
-}
-
 template <int NT, int ITEMS>
-__device__ __forceinline__ int zl_delta_rows(const Smem& sm, const Rows& rw, u64 a, int cap, u64& w0, int& bad)
+__device__ __forceinline__ int zl_delta_rows(const Smem& sm, const Rows& rw, u64 a, int cap,
+                                             u32 (&key)[ITEMS], u32 (&dl)[ITEMS], u64& w0, int& bad)
 {
     const int tid = threadIdx.x;
     u64* recs = sm.recs;
     int total = 0;
-    constexpr int MAXCH = 4;
-    if (rw.P <= MAXCH * NT) {
-        u32 lo[MAXCH], hi[MAXCH];
+    constexpr int RPT = 4;                                   // rows per thread and round
+    for (int p0 = 0; p0 < rw.P; p0 += RPT * NT) {
+        u32 lo[RPT], hi[RPT];
+        u32 mine = 0;
 #pragma unroll
-        for (int c = 0; c < MAXCH; ++c) {
-            const int p = c * NT + tid;
+        for (int c = 0; c < RPT; ++c) {
+            const int p = p0 + c * NT + tid;
             lo[c] = 0; hi[c] = 0;
             if (p < rw.P) rw.range(p, lo[c], hi[c]);
+            mine += hi[c] - lo[c];
         }
+        u32 round;
+        u32 slot = (u32)total + block_excl_scan<u32, NT>(mine, (u32*)sm.red, round);
 #pragma unroll
-        for (int c = 0; c < MAXCH; ++c) {
-            if (c * NT < rw.P) {
-                const int p = c * NT + tid;
-                if (p < rw.P && lo[c] == hi[c] && lo[c] > 0) w0 += a - rw.rel(p, lo[c] - 1);
-                u32 chunk;
-                const u32 off = block_excl_scan<u32, NT>(hi[c] - lo[c], (u32*)sm.red, chunk);
-                place_row<NT>(recs, rw, p, lo[c], hi[c], (u32)total + off, cap);
-                total += (int)chunk;
-            }
-        }
-    } else {
-        for (int p0 = 0; p0 < rw.P; p0 += NT) {
-            const int p = p0 + tid;
-            u32 lo = 0, hi = 0;
+        for (int c = 0; c < RPT; ++c) {
+            const int p = p0 + c * NT + tid;
             if (p < rw.P) {
-                rw.range(p, lo, hi);
-                if (lo == hi && lo > 0) w0 += a - rw.rel(p, lo - 1);
+                if (lo[c] == hi[c] && lo[c] > 0) w0 += a - rw.rel(p, lo[c] - 1);
+                u64 src = (u64)((u32)p * (u32)rw.R + lo[c]) | FIRST_OF_SEGMENT | (lo[c] == 0 ? FIRST_OF_ROW : 0ull);
+                for (u32 i = lo[c]; i < hi[c] && slot < (u32)cap; ++i, ++slot) {
+                    recs[slot] = src;
+                    src = (u64)((u32)src + 1u);
+                }
             }
-            u32 chunk;
-            const u32 off = block_excl_scan<u32, NT>(hi - lo, (u32*)sm.red, chunk);
-            place_row<NT>(recs, rw, p, lo, hi, (u32)total + off, cap);
-            total += (int)chunk;
         }
+        total += (int)round;
     }
     __syncthreads();
     if (total > cap) return total;
@@ -763,14 +757,15 @@ __device__ __forceinline__ int zl_delta_rows(const Smem& sm, const Rows& rw, u64
             for (int j = 0; j < G; ++j) {
                 const int q = (g + j) * NT + tid;
                 if (q < total) {
-                    const u32 key = (u32)((u64)cur[j] - rw.base - a);
-                    u32 dl = key;                              // first entry of its row: delta from the window start
+                    const u32 k = (u32)((u64)cur[j] - rw.base - a);
+                    u32 d = k;                                 // first entry of its row: delta from the window start
                     if (!(src[j] & FIRST_OF_ROW)) {
-                        dl = (u32)((u64)cur[j] - (u64)prv[j]);
+                        d = (u32)((u64)cur[j] - (u64)prv[j]);
                         bad |= (cur[j] < prv[j]);
                         if (src[j] & FIRST_OF_SEGMENT) w0 += a - ((u64)prv[j] - rw.base);
                     }
-                    recs[q] = (u64)key | ((u64)dl << 32);
+                    key[g + j] = k;
+                    dl[g + j] = d;
                 }
             }
         }
@@ -893,6 +888,10 @@ __global__ __launch_bounds__(NT) void zl_instance_kernel(
     // ones per round, so the previous element sits in the neighbouring lane.
     // The instance minimum is not known yet, so keys are first taken relative to
     // the instance's first element t00 (mod 2^32) and shifted afterwards.
+    {
+        u64* bsum = sm.recs + H::CAP;
+        bsum[tid] = 0; bsum[tid + NT] = 0;
+    }
     const int lane = tid & (WAVE - 1), wave = tid >> 6;
     const int items = (n + NT - 1) / NT;
     const int wbase = wave * WAVE * items;
@@ -942,13 +941,25 @@ __global__ __launch_bounds__(NT) void zl_instance_kernel(
         sm.recs[(size_t)p * R] = (u64)(u32)r | ((u64)((u32)(r >> 32) + shift) << 32);
     }
     if (__syncthreads_or(bad)) flags |= EBSP_STATUS_UNSORTED;
+    // the records go to registers for the bucket search (which reuses the record area)
+    u32 key[ITEMS], dl[ITEMS];
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        const int q = j * NT + tid;
+        if (q < n) {
+            const u64 r = sm.recs[q];
+            key[j] = (u32)r + shift;
+            dl[j] = (u32)(r >> 32);
+        }
+    }
     u64 best_wait;
-    u32 key;
-    if (!zl_bucket_search<NT, ITEMS>(sm, n, 0ull, thr, (u64)P, 0ull, range, shift, best_wait, key)) {
+    u32 bkey;
+    if (!zl_bucket_finish<NT, ITEMS, false>(sm, key, dl, bucket_scale(range, H::NB), n, 0ull, thr, (u64)P, 0ull,
+                                            best_wait, bkey)) {
         if (tid == 0) wait[b] = DEFERRED;      // clustered values: left to zl_instance_general_kernel
         return;
     }
-    const i64 bar = (i64)((u64)base + key);
+    const i64 bar = (i64)((u64)base + bkey);
     if (tid == 0) {
         barrier[b] = bar;
         wait[b] = (i64)best_wait;
@@ -1211,25 +1222,29 @@ __global__ __launch_bounds__(NT, 4) void zl_window_kernel(
     const WinPos w = locate_window(logical, ts, B, P, R, info, cross, stride, winstart, max_win, ii);
     if (w.b >= B || w.j >= (int)ii.nwin) return;
 
+    {
+        u64* bsum = sm.recs + H::CAP;
+        bsum[threadIdx.x] = 0; bsum[threadIdx.x + NT] = 0;
+    }
     Partial r;
     r.wait = U64_MAX;
     r.brel = 0;
     int bad = 0;
     if (w.valid) {
         bool defer = (ii.range >> 32) != 0;
-        int total = 0;
-        u64 w0 = 0;
         if (!defer) {
-            total = zl_delta_rows<NT, ITEMS>(sm, w.rw, w.A, H::CAP, w0, bad);
+            u32 key[ITEMS], dl[ITEMS];
+            u64 w0 = 0;
+            const int total = zl_delta_rows<NT, ITEMS>(sm, w.rw, w.A, H::CAP, key, dl, w0, bad);
             defer = total > H::CAP;
-        }
-        if (!defer && total > 0) {
-            const u64 W0 = block_reduce<u64, NT>(w0, sm.red, OpAdd());   // also orders the record writes
-            u32 key;
-            if (zl_bucket_search<NT, ITEMS>(sm, total, w.A, ii.thr, (u64)P, W0, w.Elast - w.A, 0u, r.wait, key))
-                r.brel = w.A + key;
-            else
-                defer = true;
+            if (!defer && total > 0) {
+                u32 bkey;
+                if (zl_bucket_finish<NT, ITEMS, true>(sm, key, dl, bucket_scale(w.Elast - w.A, H::NB), total, w.A,
+                                                      ii.thr, (u64)P, w0, r.wait, bkey))
+                    r.brel = w.A + bkey;
+                else
+                    defer = true;
+            }
         }
         if (defer) {
             r.wait = U64_MAX;
