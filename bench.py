@@ -125,8 +125,9 @@ def main() -> int:
         del dst
 
     # shape-dependent constants of the multi-window path (for the byte model only)
-    bins = (P * R + 2047) // 2048 if P * R > 16384 else 0
-    windows = B * ((P * R + 8191) // 8192) if P * R > 16384 else 0
+    shape = zipline.ebsp_zipline_shape_info(B, P, R)
+    bins = shape["bins"]
+    windows = B * ((2 * P * R + shape["window_cap"] - 1) // shape["window_cap"]) if shape["multi"] else 0
     per_kernel = {k: v / args.steps for k, v in kernel_ms.items() if v > 0.0}
     dom = max(per_kernel, key=per_kernel.get)
     dom_bytes = algorithmic_bytes(dom, B, P, R, bins, windows)

@@ -80,6 +80,14 @@ int ebsp_zipline_batch(const int64_t* ts, int64_t B, int32_t P, int32_t R,
                        void* stream);
 
 /*
+ * How a shape is handled (for benchmarks' byte models; HOST array of 4):
+ * info[0] = 1 if instances are cut into windows (0: one workgroup each),
+ * info[1] = records per window workgroup, info[2] = fine bins per instance,
+ * info[3] = upper bound of windows per instance (all 0 when info[0] is 0).
+ */
+int ebsp_zipline_shape_info(int64_t B, int32_t P, int32_t R, int64_t* info);
+
+/*
  * Tuning knobs (process-wide; call before ebsp_zipline_workspace_bytes, since
  * the workspace size depends on them; not thread-safe against running calls).
  *   window_cap  records one window workgroup holds on the multi-window path:

@@ -181,15 +181,21 @@ struct Rows {
     const i64* inst;
     int P, R;
     u64 base;
-    const u32* cr;      // crossing indices of this instance, or nullptr for whole rows
+    const void* cr;     // crossing indices of this instance (u16 if narrow, else u32), or nullptr for whole rows
+    bool narrow;
     int stride;
     u32 k0, k1;
 
     __device__ __forceinline__ void range(int p, u32& lo, u32& hi) const
     {
         if (!cr) { lo = 0; hi = (u32)R; return; }
-        lo = cr[(i64)p * stride + k0];
-        hi = cr[(i64)p * stride + k1];
+        if (narrow) {
+            const unsigned short* c = (const unsigned short*)cr + (i64)p * stride;
+            lo = c[k0]; hi = c[k1];
+        } else {
+            const u32* c = (const u32*)cr + (i64)p * stride;
+            lo = c[k0]; hi = c[k1];
+        }
         lo = lo < (u32)R ? lo : (u32)R;               // stale scratch (unsorted rows) cannot
         hi = hi < (u32)R ? hi : (u32)R;               // lead outside the row
         hi = hi > lo ? hi : lo;
@@ -1012,7 +1018,7 @@ __global__ __launch_bounds__(NT) void zl_instance_general_kernel(
 
             Rows rw;
             rw.inst = inst; rw.P = P; rw.R = R; rw.base = (u64)base;
-            rw.cr = nullptr; rw.stride = 0; rw.k0 = rw.k1 = 0;
+            rw.cr = nullptr; rw.narrow = false; rw.stride = 0; rw.k0 = rw.k1 = 0;
             int bad = 0;
             u64 best_wait = U64_MAX, best_rel = 0;
             // the 64-bit-delta form serves every deferred instance, narrow ones included
@@ -1077,10 +1083,10 @@ __global__ __launch_bounds__(NT) void zl_bounds_kernel(
 
 // zl_partition: one wave per row.  cross[row][k] = number of entries of the row
 // that fall in fine bins below k, for k = 0..nb.
-template <int NT>
+template <int NT, class CT>
 __global__ __launch_bounds__(NT) void zl_partition_kernel(
     const i64* __restrict__ ts, i64 nrows, int P, int R,
-    const InstInfo* __restrict__ info, u32* __restrict__ cross, int stride)
+    const InstInfo* __restrict__ info, CT* __restrict__ cross, int stride)
 {
     const int lane = threadIdx.x & (WAVE - 1);
     const i64 row_id = (i64)blockIdx.x * (NT / WAVE) + (threadIdx.x >> 6);
@@ -1088,7 +1094,7 @@ __global__ __launch_bounds__(NT) void zl_partition_kernel(
     const i64 b = row_id / P;
     const InstInfo ii = info[b];
     const i64* __restrict__ row = ts + row_id * (i64)R;
-    u32* __restrict__ out = cross + row_id * (i64)stride;
+    CT* __restrict__ out = cross + row_id * (i64)stride;
     const u64 base = (u64)ii.base;
 
     int carry = -1;                        // bin of the element before lane 0's
@@ -1099,17 +1105,20 @@ __global__ __launch_bounds__(NT) void zl_partition_kernel(
         int pb = __shfl_up(bin, 1, WAVE);
         if (lane == 0) pb = carry;
         if (i < R)
-            for (int k = pb + 1; k <= bin; ++k) out[k] = (u32)i;
+            for (int k = pb + 1; k <= bin; ++k) out[k] = (CT)i;
         carry = __shfl(bin, WAVE - 1, WAVE);
     }
     const int last_bin = (int)fine_bin((u64)row[R - 1] - base, ii);
-    for (int k = last_bin + 1 + lane; k <= (int)ii.nb; k += WAVE) out[k] = (u32)R;
+    for (int k = last_bin + 1 + lane; k <= (int)ii.nb; k += WAVE) out[k] = (CT)R;
 }
 
-// zl_bincount: below[b][k] = number of keys of instance b under fine bin k
-// (column sums of cross over the P rows), k = 0..nb.
+// zl_bincount: below[b][k] ~ number of keys of instance b under fine bin k, k = 0..nb:
+// the column sum of cross over every `step`-th row, scaled to all P rows.  The
+// counts only steer how bins are grouped into windows (a window's true size is
+// taken from cross itself), so an estimate from 256 or more rows is enough.
+template <class CT>
 __global__ __launch_bounds__(256) void zl_bincount_kernel(
-    const u32* __restrict__ cross, int P, int R, int stride,
+    const CT* __restrict__ cross, int P, int R, int stride, int step,
     const InstInfo* __restrict__ info, u32* __restrict__ below)
 {
     __shared__ u32 part[256];
@@ -1120,17 +1129,20 @@ __global__ __launch_bounds__(256) void zl_bincount_kernel(
     const u32 nb = info[b].nb;
     u32 s = 0;
     if (k <= (int)nb) {
-        const u32* col = cross + (b * (i64)P) * stride + k;
+        const CT* col = cross + (b * (i64)P) * stride + k;
 #pragma unroll 4
-        for (int p = pg; p < P; p += 4) {
+        for (int p = pg * step; p < P; p += 4 * step) {
             const u32 c = col[(i64)p * stride];
             s += c < (u32)R ? c : (u32)R;
         }
     }
     part[tid] = s;
     __syncthreads();
-    if (pg == 0 && k <= (int)nb)
-        below[b * (i64)stride + k] = part[kl] + part[64 + kl] + part[128 + kl] + part[192 + kl];
+    if (pg == 0 && k <= (int)nb) {
+        const u64 sum = (u64)part[kl] + part[64 + kl] + part[128 + kl] + part[192 + kl];
+        const u32 sampled = (u32)(P + step - 1) / (u32)step;
+        below[b * (i64)stride + k] = (u32)(sum * (u64)P / sampled);
+    }
 }
 
 // zl_plan: windows of an instance.  Fine bin k belongs to group
@@ -1175,7 +1187,7 @@ struct WinPos {
 };
 
 __device__ __forceinline__ WinPos locate_window(u32 logical, const i64* ts, i64 B, int P, int R,
-                                                const InstInfo* info, const u32* cross, int stride,
+                                                const InstInfo* info, const void* cross, bool narrow, int stride,
                                                 const u32* winstart, int max_win, InstInfo& ii)
 {
     WinPos w;
@@ -1188,7 +1200,9 @@ __device__ __forceinline__ WinPos locate_window(u32 logical, const i64* ts, i64 
     const u32* ws = winstart + w.b * (i64)(max_win + 1);
     w.rw.inst = ts + w.b * (i64)P * R;
     w.rw.P = P; w.rw.R = R; w.rw.base = (u64)ii.base;
-    w.rw.cr = cross + (w.b * (i64)P) * stride;
+    w.rw.cr = narrow ? (const void*)((const unsigned short*)cross + (w.b * (i64)P) * stride)
+                     : (const void*)((const u32*)cross + (w.b * (i64)P) * stride);
+    w.rw.narrow = narrow;
     w.rw.stride = stride;
     w.rw.k0 = ws[w.j];
     w.rw.k1 = ws[w.j + 1];
@@ -1207,7 +1221,7 @@ __device__ __forceinline__ WinPos locate_window(u32 logical, const i64* ts, i64 
 template <int NT, int ITEMS>
 __global__ __launch_bounds__(NT, 4) void zl_window_kernel(
     const i64* __restrict__ ts, i64 B, int P, int R,
-    const InstInfo* __restrict__ info, const u32* __restrict__ cross, int stride,
+    const InstInfo* __restrict__ info, const void* __restrict__ cross, bool narrow, int stride,
     const u32* __restrict__ winstart, int max_win,
     Partial* __restrict__ partial, int* __restrict__ status)
 {
@@ -1219,7 +1233,7 @@ __global__ __launch_bounds__(NT, 4) void zl_window_kernel(
     const u32 per_xcd = gridDim.x / 8;
     const u32 logical = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
     InstInfo ii;
-    const WinPos w = locate_window(logical, ts, B, P, R, info, cross, stride, winstart, max_win, ii);
+    const WinPos w = locate_window(logical, ts, B, P, R, info, cross, narrow, stride, winstart, max_win, ii);
     if (w.b >= B || w.j >= (int)ii.nwin) return;
 
     {
@@ -1264,7 +1278,7 @@ __global__ __launch_bounds__(NT, 4) void zl_window_kernel(
 template <int NT, int ITEMS>
 __global__ __launch_bounds__(NT) void zl_window_general_kernel(
     const i64* __restrict__ ts, i64 B, int P, int R,
-    const InstInfo* __restrict__ info, const u32* __restrict__ cross, int stride,
+    const InstInfo* __restrict__ info, const void* __restrict__ cross, bool narrow, int stride,
     const u32* __restrict__ winstart, int max_win,
     Partial* __restrict__ partial, int* __restrict__ status)
 {
@@ -1288,7 +1302,7 @@ __global__ __launch_bounds__(NT) void zl_window_general_kernel(
             if (pick == 0xffffffffu) break;
             if (pick == idx) mine = false;
             InstInfo ii;
-            const WinPos w = locate_window(pick, ts, B, P, R, info, cross, stride, winstart, max_win, ii);
+            const WinPos w = locate_window(pick, ts, B, P, R, info, cross, narrow, stride, winstart, max_win, ii);
             u64 bw = U64_MAX, bb = 0;
             int bad = 0;
             if (w.valid) {
@@ -1390,6 +1404,8 @@ struct Plan {
     int bins;          // fine bins per instance
     int stride;        // bins + 1 crossing indices per row
     int max_win;       // windows per instance <= max_win
+    bool narrow;       // crossing indices fit 16 bits
+    int step;          // zl_bincount looks at every step-th row
     size_t off_info, off_cross, off_below, off_winstart, off_partial, bytes;
 };
 
@@ -1408,10 +1424,12 @@ bool make_plan(i64 B, int P, int R, Plan& pl)
     const int fine_shift = pl.group_shift - 2;
     pl.bins = (int)((n + (1 << fine_shift) - 1) >> fine_shift);
     pl.stride = pl.bins + 1;
-    pl.max_win = (int)((n >> pl.group_shift) + 2);
+    pl.max_win = (int)(((n + n / 4) >> pl.group_shift) + 2);      // the counts behind the grouping are estimates
     size_t o = 0;
     pl.off_info = o;     o = align_up(o + (size_t)B * sizeof(InstInfo), 256);
-    pl.off_cross = o;    o = align_up(o + (size_t)B * P * pl.stride * sizeof(u32), 256);
+    pl.narrow = R < 65536;
+    pl.step = P / 256 > 1 ? P / 256 : 1;
+    pl.off_cross = o;    o = align_up(o + (size_t)B * P * pl.stride * (pl.narrow ? 2 : 4), 256);
     pl.off_below = o;    o = align_up(o + (size_t)B * pl.stride * sizeof(u32), 256);
     pl.off_winstart = o; o = align_up(o + (size_t)B * (pl.max_win + 1) * sizeof(u32), 256);
     pl.off_partial = o;  o = align_up(o + (size_t)B * pl.max_win * sizeof(Partial), 256);
@@ -1483,34 +1501,42 @@ int run_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters, i64*
 
     char* wsp = (char*)workspace;
     InstInfo* info = (InstInfo*)(wsp + pl.off_info);
-    u32* cross = (u32*)(wsp + pl.off_cross);
+    void* cross = (void*)(wsp + pl.off_cross);
     u32* below = (u32*)(wsp + pl.off_below);
     u32* winstart = (u32*)(wsp + pl.off_winstart);
     Partial* partial = (Partial*)(wsp + pl.off_partial);
 
     LAUNCH(K_BOUNDS, (zl_bounds_kernel<256>), dim3((unsigned)B), dim3(256), ts, P, R, pl.bins, info, status);
     const i64 nrows = B * (i64)P;
-    LAUNCH(K_PARTITION, (zl_partition_kernel<256>), dim3((unsigned)((nrows + 3) / 4)), dim3(256),
-           ts, nrows, P, R, info, cross, pl.stride);
+    if (pl.narrow)
+        LAUNCH(K_PARTITION, (zl_partition_kernel<256, unsigned short>), dim3((unsigned)((nrows + 3) / 4)), dim3(256),
+               ts, nrows, P, R, info, (unsigned short*)cross, pl.stride);
+    else
+        LAUNCH(K_PARTITION, (zl_partition_kernel<256, u32>), dim3((unsigned)((nrows + 3) / 4)), dim3(256),
+               ts, nrows, P, R, info, (u32*)cross, pl.stride);
     const i64 kblocks = (pl.stride + 63) / 64, pblocks = (P + 255) / 256;
     if (kblocks * B > 0x7fffffffll || pblocks * B > 0x7fffffffll) return fail(EBSP_ERR_SHAPE, "batch too large for one call");
-    LAUNCH(K_BINCOUNT, zl_bincount_kernel, dim3((unsigned)(kblocks * B)), dim3(256),
-           cross, P, R, pl.stride, info, below);
+    if (pl.narrow)
+        LAUNCH(K_BINCOUNT, zl_bincount_kernel<unsigned short>, dim3((unsigned)(kblocks * B)), dim3(256),
+               (const unsigned short*)cross, P, R, pl.stride, pl.step, info, below);
+    else
+        LAUNCH(K_BINCOUNT, zl_bincount_kernel<u32>, dim3((unsigned)(kblocks * B)), dim3(256),
+               (const u32*)cross, P, R, pl.stride, pl.step, info, below);
     LAUNCH(K_PLAN, (zl_plan_kernel<1024>), dim3((unsigned)B), dim3(1024), info, below, pl.stride, winstart, pl.max_win,
            pl.group_shift);
     const unsigned wgrid = (unsigned)((total_win + 7) / 8 * 8);
     if (pl.cap == 16384)
         LAUNCH(K_WINDOW, (zl_window_kernel<1024, 16>), dim3(wgrid), dim3(1024),
-               ts, B, P, R, info, cross, pl.stride, winstart, pl.max_win, partial, status);
+               ts, B, P, R, info, cross, pl.narrow, pl.stride, winstart, pl.max_win, partial, status);
     else if (pl.cap == 8192)
         LAUNCH(K_WINDOW, (zl_window_kernel<512, 16>), dim3(wgrid), dim3(512),
-               ts, B, P, R, info, cross, pl.stride, winstart, pl.max_win, partial, status);
+               ts, B, P, R, info, cross, pl.narrow, pl.stride, winstart, pl.max_win, partial, status);
     else
         LAUNCH(K_WINDOW, (zl_window_kernel<256, 16>), dim3(wgrid), dim3(256),
-               ts, B, P, R, info, cross, pl.stride, winstart, pl.max_win, partial, status);
+               ts, B, P, R, info, cross, pl.narrow, pl.stride, winstart, pl.max_win, partial, status);
     LAUNCH(K_WINDOW_GENERAL, (zl_window_general_kernel<LARGE_NT, LARGE_ITEMS>),
            dim3((unsigned)(total_win < GENERAL_GRID ? total_win : GENERAL_GRID)), dim3(LARGE_NT),
-           ts, B, P, R, info, cross, pl.stride, winstart, pl.max_win, partial, status);
+           ts, B, P, R, info, cross, pl.narrow, pl.stride, winstart, pl.max_win, partial, status);
     LAUNCH(K_FINISH, (zl_finish_kernel<256>), dim3((unsigned)(pblocks * B)), dim3(256),
            ts, P, R, info, partial, pl.max_win, barrier, iters, wait);
     return EBSP_OK;
@@ -1535,6 +1561,18 @@ int ebsp_zipline_batch(const int64_t* ts, int64_t B, int32_t P, int32_t R,
                              workspace, workspace_bytes, (hipStream_t)stream);
     if (g_prof.on && rc == EBSP_OK && B > 0 && g_prof.calls < g_prof.max_calls) ++g_prof.calls;
     return rc;
+}
+
+int ebsp_zipline_shape_info(int64_t B, int32_t P, int32_t R, int64_t* info)
+{
+    Plan pl;
+    if (!info) return fail(EBSP_ERR_NULL, "info must not be NULL");
+    if (!make_plan(B, P, R, pl)) return fail(EBSP_ERR_SHAPE, "invalid shape: need B >= 0, P >= 1, R >= 1, P*R < 2^31");
+    info[0] = pl.multi ? 1 : 0;
+    info[1] = pl.multi ? pl.cap : 0;
+    info[2] = pl.multi ? pl.bins : 0;
+    info[3] = pl.multi ? pl.max_win : 0;
+    return EBSP_OK;
 }
 
 int ebsp_zipline_tune(int32_t window_cap, int32_t single_max)

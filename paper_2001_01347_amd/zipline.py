@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libebsp_zipline.so")
 EBSP_OK = 0
 STATUS_OK, STATUS_UNSORTED, STATUS_OVERFLOW, STATUS_UNSUPPORTED = 0, 1, 2, 4
 
-EXPORTS = ("ebsp_zipline_workspace_bytes", "ebsp_zipline_batch", "ebsp_zipline_tune", "ebsp_zipline_profile_begin",
+EXPORTS = ("ebsp_zipline_workspace_bytes", "ebsp_zipline_batch", "ebsp_zipline_tune", "ebsp_zipline_shape_info", "ebsp_zipline_profile_begin",
            "ebsp_zipline_profile_end", "ebsp_zipline_copy_probe", "ebsp_zipline_kernel_count",
            "ebsp_zipline_kernel_name", "ebsp_last_error")
 
@@ -45,6 +45,8 @@ def load() -> ctypes.CDLL:
         common = [vp, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
         lib.ebsp_zipline_batch.restype = ctypes.c_int
         lib.ebsp_zipline_batch.argtypes = common
+        lib.ebsp_zipline_shape_info.restype = ctypes.c_int
+        lib.ebsp_zipline_shape_info.argtypes = [i64, i32, i32, ctypes.POINTER(ctypes.c_int64)]
         lib.ebsp_zipline_tune.restype = ctypes.c_int
         lib.ebsp_zipline_tune.argtypes = [i32, i32]
         lib.ebsp_zipline_profile_begin.restype = ctypes.c_int
@@ -69,6 +71,15 @@ def ebsp_last_error() -> str:
 
 def ebsp_zipline_workspace_bytes(B: int, P: int, R: int) -> int:
     return int(load().ebsp_zipline_workspace_bytes(B, P, R))
+
+
+def ebsp_zipline_shape_info(B: int, P: int, R: int) -> Dict[str, int]:
+    """How the library handles a shape: {'multi', 'window_cap', 'bins', 'max_windows'}."""
+    info = (ctypes.c_int64 * 4)()
+    rc = load().ebsp_zipline_shape_info(B, P, R, info)
+    if rc != EBSP_OK:
+        raise ZipLineError(f"ebsp_zipline_shape_info failed ({rc}): {ebsp_last_error()}")
+    return {"multi": int(info[0]), "window_cap": int(info[1]), "bins": int(info[2]), "max_windows": int(info[3])}
 
 
 def ebsp_zipline_tune(window_cap: int = 0, single_max: int = 0) -> None:
