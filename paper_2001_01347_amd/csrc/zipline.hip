@@ -703,25 +703,40 @@ __device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key
 //      window add their share in sweep 1.
 // Returns the number of entries; nothing is loaded if it exceeds `cap`.
 constexpr u64 FIRST_OF_ROW = 1ull << 32, FIRST_OF_SEGMENT = 1ull << 33;
+constexpr int ROWS_PER_THREAD = 4;        // rows a thread takes per round of sweep 1
+constexpr int WINDOWS_PER_BLOCK = 2;      // windows a workgroup handles, their index ranges fetched together
+
+template <int NT>
+__device__ __forceinline__ void load_ranges(const Rows& rw, int p0, u32 (&lo)[ROWS_PER_THREAD], u32 (&hi)[ROWS_PER_THREAD])
+{
+#pragma unroll
+    for (int c = 0; c < ROWS_PER_THREAD; ++c) {
+        const int p = p0 + c * NT + (int)threadIdx.x;
+        lo[c] = 0; hi[c] = 0;
+        if (p < rw.P) rw.range(p, lo[c], hi[c]);
+    }
+}
 
 template <int NT, int ITEMS>
 __device__ __forceinline__ int zl_delta_rows(const Smem& sm, const Rows& rw, u64 a, int cap,
+                                             const u32 (&lo0)[ROWS_PER_THREAD], const u32 (&hi0)[ROWS_PER_THREAD],
                                              u32 (&key)[ITEMS], u32 (&dl)[ITEMS], u64& w0, int& bad)
 {
     const int tid = threadIdx.x;
     u64* recs = sm.recs;
     int total = 0;
-    constexpr int RPT = 4;                                   // rows per thread and round
+    constexpr int RPT = ROWS_PER_THREAD;
     for (int p0 = 0; p0 < rw.P; p0 += RPT * NT) {
         u32 lo[RPT], hi[RPT];
+        if (p0 == 0) {                                       // the first round's ranges came with the call
+#pragma unroll
+            for (int c = 0; c < RPT; ++c) { lo[c] = lo0[c]; hi[c] = hi0[c]; }
+        } else {
+            load_ranges<NT>(rw, p0, lo, hi);
+        }
         u32 mine = 0;
 #pragma unroll
-        for (int c = 0; c < RPT; ++c) {
-            const int p = p0 + c * NT + tid;
-            lo[c] = 0; hi[c] = 0;
-            if (p < rw.P) rw.range(p, lo[c], hi[c]);
-            mine += hi[c] - lo[c];
-        }
+        for (int c = 0; c < RPT; ++c) mine += hi[c] - lo[c];
         u32 round;
         u32 slot = (u32)total + block_excl_scan<u32, NT>(mine, (u32*)sm.red, round);
 #pragma unroll
@@ -1215,6 +1230,51 @@ __device__ __forceinline__ WinPos locate_window(u32 logical, const i64* ts, i64 
     return w;
 }
 
+// The fast search of one window (see zl_window_kernel); lo/hi hold the index
+// ranges of the thread's first ROWS_PER_THREAD rows.
+template <int NT, int ITEMS>
+__device__ __forceinline__ void window_search(const Smem& sm, const WinPos& w, const InstInfo& ii,
+                                              const u32 (&lo)[ROWS_PER_THREAD], const u32 (&hi)[ROWS_PER_THREAD],
+                                              int P, int max_win, Partial* __restrict__ partial,
+                                              int* __restrict__ status)
+{
+    using H = HotCfg<NT, ITEMS>;
+    {
+        u64* bsum = sm.recs + H::CAP;
+        bsum[threadIdx.x] = 0; bsum[threadIdx.x + NT] = 0;
+    }
+    Partial r;
+    r.wait = U64_MAX;
+    r.brel = 0;
+    int bad = 0;
+    if (w.valid) {
+        bool defer = (ii.range >> 32) != 0;
+        if (!defer) {
+            u32 key[ITEMS], dl[ITEMS];
+            u64 w0 = 0;
+            const int total = zl_delta_rows<NT, ITEMS>(sm, w.rw, w.A, H::CAP, lo, hi, key, dl, w0, bad);
+            defer = total > H::CAP;
+            if (!defer && total > 0) {
+                u32 bkey;
+                if (zl_bucket_finish<NT, ITEMS, true>(sm, key, dl, bucket_scale(w.Elast - w.A, H::NB), total, w.A,
+                                                      ii.thr, (u64)P, w0, r.wait, bkey))
+                    r.brel = w.A + bkey;
+                else
+                    defer = true;
+            }
+        }
+        if (defer) {
+            r.wait = U64_MAX;
+            r.brel = DEFERRED_WINDOW;
+        }
+    }
+    bad = __syncthreads_or(bad);              // also: everyone is done with LDS before the next window
+    if (threadIdx.x == 0) {
+        partial[w.b * (i64)max_win + w.j] = r;
+        if (bad && status) atomicOr(status + w.b, (int)EBSP_STATUS_UNSORTED);
+    }
+}
+
 // One workgroup per window; the window's best candidate goes to `partial`.
 // Handles the normal case (32-bit value spread, the window fits in LDS) and
 // marks every other window as deferred to zl_window_general_kernel.
@@ -1231,45 +1291,21 @@ __global__ __launch_bounds__(NT, 4) void zl_window_kernel(
     // Consecutive windows share cache lines at their segment ends: give each
     // XCD (workgroups are dealt round-robin to the 8 XCDs) a contiguous range.
     const u32 per_xcd = gridDim.x / 8;
-    const u32 logical = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
-    InstInfo ii;
-    const WinPos w = locate_window(logical, ts, B, P, R, info, cross, narrow, stride, winstart, max_win, ii);
-    if (w.b >= B || w.j >= (int)ii.nwin) return;
-
-    {
-        u64* bsum = sm.recs + H::CAP;
-        bsum[threadIdx.x] = 0; bsum[threadIdx.x + NT] = 0;
-    }
-    Partial r;
-    r.wait = U64_MAX;
-    r.brel = 0;
-    int bad = 0;
-    if (w.valid) {
-        bool defer = (ii.range >> 32) != 0;
-        if (!defer) {
-            u32 key[ITEMS], dl[ITEMS];
-            u64 w0 = 0;
-            const int total = zl_delta_rows<NT, ITEMS>(sm, w.rw, w.A, H::CAP, key, dl, w0, bad);
-            defer = total > H::CAP;
-            if (!defer && total > 0) {
-                u32 bkey;
-                if (zl_bucket_finish<NT, ITEMS, true>(sm, key, dl, bucket_scale(w.Elast - w.A, H::NB), total, w.A,
-                                                      ii.thr, (u64)P, w0, r.wait, bkey))
-                    r.brel = w.A + bkey;
-                else
-                    defer = true;
-            }
-        }
-        if (defer) {
-            r.wait = U64_MAX;
-            r.brel = DEFERRED_WINDOW;
-        }
-    }
-    bad = __syncthreads_or(bad);
-    if (threadIdx.x == 0) {
-        partial[w.b * (i64)max_win + w.j] = r;
-        if (bad && status) atomicOr(status + w.b, (int)EBSP_STATUS_UNSORTED);
-    }
+    const u32 slot = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    // where the workgroup's two windows are, then the index ranges of both: the
+    // latency of these two dependent fetches is paid once per workgroup
+    static_assert(WINDOWS_PER_BLOCK == 2, "the kernel body is written out for two windows");
+    InstInfo iiA, iiB;
+    const WinPos wA = locate_window(slot * 2, ts, B, P, R, info, cross, narrow, stride, winstart, max_win, iiA);
+    const WinPos wB = locate_window(slot * 2 + 1, ts, B, P, R, info, cross, narrow, stride, winstart, max_win, iiB);
+    const bool liveA = wA.b < B && wA.j < (int)iiA.nwin, liveB = wB.b < B && wB.j < (int)iiB.nwin;
+    u32 loA[ROWS_PER_THREAD], hiA[ROWS_PER_THREAD], loB[ROWS_PER_THREAD], hiB[ROWS_PER_THREAD];
+#pragma unroll
+    for (int c = 0; c < ROWS_PER_THREAD; ++c) { loA[c] = hiA[c] = loB[c] = hiB[c] = 0; }
+    if (liveA && wA.valid && !(iiA.range >> 32)) load_ranges<NT>(wA.rw, 0, loA, hiA);
+    if (liveB && wB.valid && !(iiB.range >> 32)) load_ranges<NT>(wB.rw, 0, loB, hiB);
+    if (liveA) window_search<NT, ITEMS>(sm, wA, iiA, loA, hiA, P, max_win, partial, status);
+    if (liveB) window_search<NT, ITEMS>(sm, wB, iiB, loB, hiB, P, max_win, partial, status);
 }
 
 // The windows zl_window_kernel deferred: the general window search.  A small
@@ -1524,7 +1560,7 @@ int run_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters, i64*
                (const u32*)cross, P, R, pl.stride, pl.step, info, below);
     LAUNCH(K_PLAN, (zl_plan_kernel<1024>), dim3((unsigned)B), dim3(1024), info, below, pl.stride, winstart, pl.max_win,
            pl.group_shift);
-    const unsigned wgrid = (unsigned)((total_win + 7) / 8 * 8);
+    const unsigned wgrid = (unsigned)(((total_win + WINDOWS_PER_BLOCK - 1) / WINDOWS_PER_BLOCK + 7) / 8 * 8);
     if (pl.cap == 16384)
         LAUNCH(K_WINDOW, (zl_window_kernel<1024, 16>), dim3(wgrid), dim3(1024),
                ts, B, P, R, info, cross, pl.narrow, pl.stride, winstart, pl.max_win, partial, status);
