@@ -30,14 +30,16 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 def algorithmic_bytes(kernel: str, B: int, P: int, R: int, bins: int, windows: int) -> float:
     """Bytes a kernel must move per launch (inputs it has to read once + what it has to write)."""
     n = float(B) * P * R
+    cw = 2.0 if R < 65536 else 4.0          # bytes of one crossing index
+    step = max(1, P // 256)                 # zl_bincount looks at every step-th row
     if kernel == "zl_instance_kernel":      # every timestamp once, all three outputs
         return 8.0 * n + B * (16.0 + 4.0 * P)
     if kernel == "zl_window_kernel":        # every timestamp once, two crossing rows per window, one result
-        return 8.0 * n + windows * (8.0 * P + 16.0)
+        return 8.0 * n + windows * (2.0 * cw * P + 16.0)
     if kernel == "zl_partition_kernel":     # every timestamp once, one crossing index per (row, bin)
-        return 8.0 * n + 4.0 * B * P * (bins + 1)
+        return 8.0 * n + cw * B * P * (bins + 1)
     if kernel == "zl_bincount_kernel":      # the crossing indices once, one count per bin
-        return 4.0 * B * P * (bins + 1) + 4.0 * B * (bins + 1)
+        return cw * B * ((P + step - 1) // step) * (bins + 1) + 4.0 * B * (bins + 1)
     if kernel == "zl_bounds_kernel":        # first and last timestamp of every row (one 64-byte line each)
         return 128.0 * B * P
     if kernel == "zl_plan_kernel":
