@@ -560,7 +560,9 @@ struct HotCfg {
     static constexpr int CAP = NT * ITEMS;
     static constexpr int NB = 2 * NT;                     // value buckets; each thread scans two
     static constexpr int RED_WORDS = 3 * NW + 8;
-    static constexpr size_t BYTES = (size_t)CAP * 8 + (size_t)NB * 8 + (size_t)RED_WORDS * 8 + (size_t)NB * 4;
+    static constexpr int COARSE = 256;                    // coarse value bins behind an equalising bucket map
+    static constexpr size_t BYTES = (size_t)CAP * 8 + (size_t)NB * 8 + (size_t)RED_WORDS * 8 + (size_t)NB * 4 +
+                                    (size_t)COARSE * 8;
 };
 // One LDS word per bucket holds its entry count (upper bits) and the sum of its
 // deltas (lower SUM_BITS bits: at most 16384 deltas below 2^32 each).
@@ -581,12 +583,41 @@ __device__ __forceinline__ Smem carve_hot(unsigned char* smem)
     return s;
 }
 
-// bucket = (key * scale) >> 32 maps keys in [0, span] onto [0, NB) monotonically.
-__device__ __forceinline__ u32 bucket_scale(u64 span, u32 nb)
+// Monotone maps of keys onto value buckets [0, NB).
+// LinearMap: bucket = (key * scale) >> 32, equal slices of [0, span]; right when the
+// keys are spread evenly, as inside a window of the multi-window path.
+// (Keys beyond the span only occur in unsorted rows; the clamps keep those in bounds.)
+struct LinearMap {
+    u32 scale, top;
+    __device__ __forceinline__ u32 operator()(u32 key) const
+    {
+        const u32 b = (u32)(((u64)key * scale) >> 32);
+        return b < top ? b : top;
+    }
+};
+__device__ __forceinline__ LinearMap linear_map(u64 span, u32 nb)
 {
     const u64 q = ((u64)nb << 32) / (span + 1);
-    return q >= 0xffffffffull ? 0xffffffffu : (q ? (u32)q : 1u);
+    LinearMap m;
+    m.scale = q >= 0xffffffffull ? 0xffffffffu : (q ? (u32)q : 1u);
+    m.top = nb - 1;
+    return m;
 }
+// TableMap: piecewise linear through up to 256 coarse bins of width 2^cshift, each
+// given a share of the buckets in proportion to its key count, so that buckets
+// hold about the same number of keys even where the density of keys varies (a
+// whole instance: many workers early in the value range, few stragglers late).
+// tab[c] = first bucket of coarse bin c | (buckets of bin c scaled by 2^(32-cshift)) << 32.
+struct TableMap {
+    const u64* tab;
+    u32 cshift, cmask;
+    __device__ __forceinline__ u32 coarse(u32 key) const { const u32 c = key >> cshift; return c < 255u ? c : 255u; }
+    __device__ __forceinline__ u32 operator()(u32 key) const
+    {
+        const u64 e = tab[coarse(key)];
+        return (u32)e + (u32)(((u64)(key & cmask) * (e >> 32)) >> 32);
+    }
+};
 
 // The records of a window, held ITEMS per thread in registers (item j of thread t
 // is record j*NT + t, present if that is below `total`) -> first minimum
@@ -595,9 +626,9 @@ __device__ __forceinline__ u32 bucket_scale(u64 span, u32 nb)
 // On entry the bucket words must be zero and a barrier must have passed since;
 // the record area may hold anything (it is overwritten).
 // Returns false (nothing computed) if some bucket is over the limit.
-template <int NT, int ITEMS, bool WITH_W0>
+template <int NT, int ITEMS, bool WITH_W0, class Map>
 __device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key)[ITEMS], const u32 (&dl)[ITEMS],
-                                                 u32 scale, int total, u64 a, u64 thr, u64 P, u64 w0,
+                                                 const Map bucket, int total, u64 a, u64 thr, u64 P, u64 w0,
                                                  u64& best_wait, u32& best_key)
 {
     using H = HotCfg<NT, ITEMS>;
@@ -609,7 +640,7 @@ __device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key
 #pragma unroll
     for (int j = 0; j < ITEMS; ++j)
         if (j * NT + tid < total) {
-            const u32 bid = (u32)(((u64)key[j] * scale) >> 32);
+            const u32 bid = bucket(key[j]);
             atomicAdd(&bsum[bid], (1ull << SUM_BITS) | (u64)dl[j]);
         }
     __syncthreads();
@@ -629,7 +660,7 @@ __device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key
 #pragma unroll
     for (int j = 0; j < ITEMS; ++j)
         if (j * NT + tid < total) {
-            const u32 bid = (u32)(((u64)key[j] * scale) >> 32);
+            const u32 bid = bucket(key[j]);
             const u32 slot = atomicAdd(&cnt[bid], 1u);
             recs[slot] = (u64)key[j] | ((u64)dl[j] << 32);
         }
@@ -639,7 +670,7 @@ __device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key
     u32 bk = 0xffffffffu;
     for (int q = tid; q < total; q += NT) {
         const u32 k = (u32)recs[q];
-        const u32 bid = (u32)(((u64)k * scale) >> 32);
+        const u32 bid = bucket(k);
         const u32 e = cnt[bid];
         const u64 hb = bsum[bid];
         u32 x = (u32)(hb >> SUM_BITS);
@@ -973,10 +1004,48 @@ __global__ __launch_bounds__(NT) void zl_instance_kernel(
             dl[j] = (u32)(r >> 32);
         }
     }
+    // the equalising bucket map: key counts of up to 256 coarse bins -> buckets per bin
+    u32* coarse = sm.cnt;                                   // free until the bucket scan
+    u64* tab = (u64*)(sm.cnt + H::NB);
+    const int bl = bit_length(range);
+    TableMap bucket;
+    bucket.tab = tab;
+    bucket.cshift = bl > 8 ? (u32)(bl - 8) : 0u;
+    bucket.cmask = (1u << bucket.cshift) - 1u;
+    constexpr int CPT = H::COARSE / NT > 1 ? H::COARSE / NT : 1;      // coarse bins per thread
+    for (int c = tid; c < H::COARSE; c += NT) coarse[c] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j)
+        if (j * NT + tid < n) atomicAdd(&coarse[bucket.coarse(key[j])], 1u);
+    __syncthreads();
+    {
+        u32 c[CPT], mine = 0;
+#pragma unroll
+        for (int i = 0; i < CPT; ++i) {
+            c[i] = tid * CPT + i < H::COARSE ? coarse[tid * CPT + i] : 0u;
+            mine += c[i];
+        }
+        u32 all;
+        u32 below_c = block_excl_scan<u32, NT>(mine, (u32*)sm.red, all);
+#pragma unroll
+        for (int i = 0; i < CPT; ++i) {
+            if (tid * CPT + i < H::COARSE) {
+                const u32 first = (u32)((u64)below_c * H::NB / (u32)n);
+                u32 last = (u32)((u64)(below_c + c[i]) * H::NB / (u32)n);    // first bucket of the next coarse bin
+                if (last > (u32)H::NB - 1) last = H::NB - 1;
+                u32 nbk = last >= first ? last - first + 1 : 1;                // buckets this bin spreads over
+                if (bucket.cshift < 32 && nbk > (1u << bucket.cshift)) nbk = 1u << bucket.cshift;
+                const u64 mult = bucket.cshift ? ((u64)nbk << (32 - bucket.cshift)) - 1 : 0ull;
+                tab[tid * CPT + i] = (u64)(first < (u32)H::NB ? first : (u32)H::NB - 1) | (mult << 32);
+            }
+            below_c += c[i];
+        }
+    }
+    __syncthreads();
     u64 best_wait;
     u32 bkey;
-    if (!zl_bucket_finish<NT, ITEMS, false>(sm, key, dl, bucket_scale(range, H::NB), n, 0ull, thr, (u64)P, 0ull,
-                                            best_wait, bkey)) {
+    if (!zl_bucket_finish<NT, ITEMS, false>(sm, key, dl, bucket, n, 0ull, thr, (u64)P, 0ull, best_wait, bkey)) {
         if (tid == 0) wait[b] = DEFERRED;      // clustered values: left to zl_instance_general_kernel
         return;
     }
@@ -1256,7 +1325,7 @@ __device__ __forceinline__ void window_search(const Smem& sm, const WinPos& w, c
             defer = total > H::CAP;
             if (!defer && total > 0) {
                 u32 bkey;
-                if (zl_bucket_finish<NT, ITEMS, true>(sm, key, dl, bucket_scale(w.Elast - w.A, H::NB), total, w.A,
+                if (zl_bucket_finish<NT, ITEMS, true>(sm, key, dl, linear_map(w.Elast - w.A, H::NB), total, w.A,
                                                       ii.thr, (u64)P, w0, r.wait, bkey))
                     r.brel = w.A + bkey;
                 else
