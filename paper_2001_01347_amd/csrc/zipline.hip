@@ -561,7 +561,9 @@ struct HotCfg {
     static constexpr int NB = 2 * NT;                     // value buckets; each thread scans two
     static constexpr int RED_WORDS = 3 * NW + 8;
     static constexpr int COARSE = 256;                    // coarse value bins behind an equalising bucket map
-    static constexpr size_t BYTES = (size_t)CAP * 8 + (size_t)NB * 8 + (size_t)RED_WORDS * 8 + (size_t)NB * 4 +
+    static constexpr int PAD = 4;                         // record slots after the last one that a 4-wide read may touch
+    static constexpr int BSUM_AT = CAP + PAD;             // bucket words follow the records
+    static constexpr size_t BYTES = (size_t)BSUM_AT * 8 + (size_t)NB * 8 + (size_t)RED_WORDS * 8 + (size_t)NB * 4 +
                                     (size_t)COARSE * 8;
 };
 // One LDS word per bucket holds its entry count (upper bits) and the sum of its
@@ -578,7 +580,7 @@ __device__ __forceinline__ Smem carve_hot(unsigned char* smem)
     Smem s;
     s.recs = (u64*)smem;
     s.dhi = nullptr;
-    s.red = s.recs + H::CAP + H::NB;      // bucket sums sit between the records and the scratch
+    s.red = s.recs + H::BSUM_AT + H::NB;      // bucket sums sit between the records and the scratch
     s.cnt = (u32*)(s.red + H::RED_WORDS);
     return s;
 }
@@ -633,7 +635,7 @@ __device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key
 {
     using H = HotCfg<NT, ITEMS>;
     u64* recs = sm.recs;
-    u64* bsum = sm.recs + H::CAP;
+    u64* bsum = sm.recs + H::BSUM_AT;
     u32* cnt = sm.cnt;
     const int tid = threadIdx.x;
     // zl_sort, step 1: per bucket, entry count and sum of deltas in one word
@@ -664,8 +666,12 @@ __device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key
             const u32 slot = atomicAdd(&cnt[bid], 1u);
             recs[slot] = (u64)key[j] | ((u64)dl[j] << 32);
         }
+    // a 4-wide read of the last bucket may run past the end: entries that add nothing
+    if (tid < H::PAD - 1) recs[total + tid] = 0xffffffffull;
     __syncthreads();
-    // zl_scan + zl_argmin: every element evaluates its own candidate
+    // zl_scan + zl_argmin: every element evaluates its own candidate.  The bucket map
+    // is monotone, so whatever a 4-wide read picks up beyond the element's own bucket
+    // has a larger key and drops out by the same comparison.
     u64 bw = U64_MAX;
     u32 bk = 0xffffffffu;
     for (int q = tid; q < total; q += NT) {
@@ -676,15 +682,11 @@ __device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key
         u32 x = (u32)(hb >> SUM_BITS);
         u64 S = hb & SUM_MASK;
         for (; x < e; x += 4) {                       // four entries per trip: one LDS round trip, not four
-            const u32 last = e - 1;
-            const u64 r0 = recs[x];
-            const u64 r1 = recs[x + 1 < e ? x + 1 : last];
-            const u64 r2 = recs[x + 2 < e ? x + 2 : last];
-            const u64 r3 = recs[x + 3 < e ? x + 3 : last];
+            const u64 r0 = recs[x], r1 = recs[x + 1], r2 = recs[x + 2], r3 = recs[x + 3];
             S += ((u32)r0 <= k) ? r0 >> 32 : 0ull;
-            S += (x + 1 < e && (u32)r1 <= k) ? r1 >> 32 : 0ull;
-            S += (x + 2 < e && (u32)r2 <= k) ? r2 >> 32 : 0ull;
-            S += (x + 3 < e && (u32)r3 <= k) ? r3 >> 32 : 0ull;
+            S += ((u32)r1 <= k) ? r1 >> 32 : 0ull;
+            S += ((u32)r2 <= k) ? r2 >> 32 : 0ull;
+            S += ((u32)r3 <= k) ? r3 >> 32 : 0ull;
         }
         if (a + k >= thr) {
             const u64 w = P * (u64)k + W0 - S;
@@ -941,7 +943,7 @@ __global__ __launch_bounds__(NT) void zl_instance_kernel(
     // The instance minimum is not known yet, so keys are first taken relative to
     // the instance's first element t00 (mod 2^32) and shifted afterwards.
     {
-        u64* bsum = sm.recs + H::CAP;
+        u64* bsum = sm.recs + H::BSUM_AT;
         bsum[tid] = 0; bsum[tid + NT] = 0;
     }
     const int lane = tid & (WAVE - 1), wave = tid >> 6;
@@ -1309,7 +1311,7 @@ __device__ __forceinline__ void window_search(const Smem& sm, const WinPos& w, c
 {
     using H = HotCfg<NT, ITEMS>;
     {
-        u64* bsum = sm.recs + H::CAP;
+        u64* bsum = sm.recs + H::BSUM_AT;
         bsum[threadIdx.x] = 0; bsum[threadIdx.x + NT] = 0;
     }
     Partial r;
