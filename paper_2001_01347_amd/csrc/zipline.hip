@@ -572,6 +572,7 @@ constexpr int SUM_BITS = 46;
 constexpr u64 SUM_MASK = (1ull << SUM_BITS) - 1;
 constexpr u32 BUCKET_LIMIT = 64;
 constexpr int GATHER_BATCH = 8;           // elements a thread loads before it uses any of them
+constexpr int GATHER_TAIL = 4;            // the same beyond the first batch
 
 template <int NT, int ITEMS>
 __device__ __forceinline__ Smem carve_hot(unsigned char* smem)
@@ -720,45 +721,82 @@ __device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key
 }
 
 // zl_delta for the fast window path: the rows' index ranges are exactly the
-// window (no searching) and everything fits 32 bits.  Two sweeps:
-//   1. one thread per row (up to four rows each per round): segment lengths, one
-//      block scan for the first slots, and a source word for every element of a
+// window (no searching), every value of the instance fits 32 bits relative to
+// its base, and byte offsets into the instance fit 32 bits.  Two sweeps:
+//   1. one thread per row (a round covers 1024 rows): segment lengths, one block
+//      scan for the first slots, and a source word for every element of a
 //      segment written into that element's slot (index into the instance;
-//      FIRST_OF_ROW: the row's very first entry; FIRST_OF_SEGMENT: the entry whose
-//      predecessor lies before the window).  The crossing indices of a round
-//      are all fetched before any of them is used.
-//   2. one thread per slot: read the source word, load the element and its
-//      predecessor (GATHER_BATCH elements of a thread in flight together;
-//      consecutive slots are consecutive addresses within a segment) and keep
-//      the (key, delta) records in registers: item j of thread t is slot
-//      j*NT + t.  W0 = sum_p (a - last value of row p before the window) is
-//      collected from the segment-first entries; rows without any entry in the
-//      window add their share in sweep 1.
+//      FIRST_OF_ROW: the row's very first entry, which has no predecessor;
+//      FIRST_OF_SEGMENT: the entry whose predecessor lies before the window).
+//      The crossing indices of a round are all fetched before any is used.
+//   2. one thread per slot: read the source word, load the low words of the
+//      element and of its predecessor (GATHER_BATCH elements of a thread in
+//      flight together; consecutive slots are consecutive addresses within a
+//      segment) and keep the (key, delta) records in registers: item j of
+//      thread t is slot j*NT + t.  key = t - (base + a), delta = t - predecessor
+//      (the window start for a row's first entry).  W0 = sum_p (a - last value
+//      of row p before the window) is collected from the segment-first entries;
+//      rows without any entry in the window add their share in sweep 1.
 // Returns the number of entries; nothing is loaded if it exceeds `cap`.
 constexpr u64 FIRST_OF_ROW = 1ull << 32, FIRST_OF_SEGMENT = 1ull << 33;
-constexpr int ROWS_PER_THREAD = 4;        // rows a thread takes per round of sweep 1
+// rows a thread takes per round of sweep 1: one round covers 1024 rows
+template <int NT> constexpr int ROWS_PER_THREAD = NT >= 1024 ? 1 : 1024 / NT;
 constexpr int WINDOWS_PER_BLOCK = 2;      // windows a workgroup handles, their index ranges fetched together
+constexpr u64 HOT_MAX_ENTRIES = 1ull << 29;   // P*R below this: byte offsets into an instance fit 32 bits
 
 template <int NT>
-__device__ __forceinline__ void load_ranges(const Rows& rw, int p0, u32 (&lo)[ROWS_PER_THREAD], u32 (&hi)[ROWS_PER_THREAD])
+__device__ __forceinline__ void load_ranges(const Rows& rw, int p0, u32 (&lo)[ROWS_PER_THREAD<NT>], u32 (&hi)[ROWS_PER_THREAD<NT>])
 {
 #pragma unroll
-    for (int c = 0; c < ROWS_PER_THREAD; ++c) {
+    for (int c = 0; c < ROWS_PER_THREAD<NT>; ++c) {
         const int p = p0 + c * NT + (int)threadIdx.x;
         lo[c] = 0; hi[c] = 0;
         if (p < rw.P) rw.range(p, lo[c], hi[c]);
     }
 }
 
+// Sweep 2 for items [g, g + G) of every thread.  Only the low words of the
+// timestamps are loaded (rows were checked for order by zl_partition).
+template <int NT, int ITEMS, int G>
+__device__ __forceinline__ void gather_batch(const u64* recs, const char* bytes, int g, int total, u32 start,
+                                             u32 (&key)[ITEMS], u32 (&dl)[ITEMS], u64& w0)
+{
+    const int tid = threadIdx.x;
+    if (g * NT >= total) return;
+    u64 src[G];
+    u32 cur[G], prv[G];
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+        const int q = (g + j) * NT + tid;
+        src[j] = q < total ? recs[q] : FIRST_OF_ROW;               // beyond the end: entry 0, harmless
+    }
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+        const u32 at = (u32)src[j];
+        const u32 pat = at - (1u - ((u32)(src[j] >> 32) & 1u));    // a row's first entry stands in for its predecessor
+        cur[j] = *(const u32*)(bytes + (at << 3));
+        prv[j] = *(const u32*)(bytes + (pat << 3));
+    }
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+        const u32 from = (src[j] & FIRST_OF_ROW) ? start : prv[j];
+        key[g + j] = cur[j] - start;
+        dl[g + j] = cur[j] - from;
+        w0 += (src[j] & FIRST_OF_SEGMENT) ? (u64)(start - from) : 0ull;   // below 2^32 like every relative value
+    }
+}
+
 template <int NT, int ITEMS>
 __device__ __forceinline__ int zl_delta_rows(const Smem& sm, const Rows& rw, u64 a, int cap,
-                                             const u32 (&lo0)[ROWS_PER_THREAD], const u32 (&hi0)[ROWS_PER_THREAD],
-                                             u32 (&key)[ITEMS], u32 (&dl)[ITEMS], u64& w0, int& bad)
+                                             const u32 (&lo0)[ROWS_PER_THREAD<NT>], const u32 (&hi0)[ROWS_PER_THREAD<NT>],
+                                             u32 (&key)[ITEMS], u32 (&dl)[ITEMS], u64& w0)
 {
     const int tid = threadIdx.x;
     u64* recs = sm.recs;
+    const char* bytes = (const char*)rw.inst;
+    const u32 start = (u32)(rw.base + a);                    // low word of the window's first value
     int total = 0;
-    constexpr int RPT = ROWS_PER_THREAD;
+    constexpr int RPT = ROWS_PER_THREAD<NT>;
     for (int p0 = 0; p0 < rw.P; p0 += RPT * NT) {
         u32 lo[RPT], hi[RPT];
         if (p0 == 0) {                                       // the first round's ranges came with the call
@@ -789,41 +827,12 @@ __device__ __forceinline__ int zl_delta_rows(const Smem& sm, const Rows& rw, u64
     __syncthreads();
     if (total > cap) return total;
 
+    constexpr int G0 = ITEMS < GATHER_BATCH ? ITEMS : GATHER_BATCH;
+    gather_batch<NT, ITEMS, G0>(recs, bytes, 0, total, start, key, dl, w0);
+    static_assert((ITEMS - G0) % GATHER_TAIL == 0 || ITEMS < GATHER_BATCH, "tail batches must tile the items");
 #pragma unroll
-    for (int g = 0; g < ITEMS; g += GATHER_BATCH) {
-        if (g * NT < total) {
-            constexpr int G = ITEMS < GATHER_BATCH ? ITEMS : GATHER_BATCH;
-            u64 src[G];
-            i64 cur[G], prv[G];
-#pragma unroll
-            for (int j = 0; j < G; ++j) {
-                const int q = (g + j) * NT + tid;
-                src[j] = q < total ? recs[q] : FIRST_OF_ROW;
-            }
-#pragma unroll
-            for (int j = 0; j < G; ++j) {
-                const int q = (g + j) * NT + tid;
-                const u32 at = (u32)src[j];
-                cur[j] = q < total ? rw.inst[at] : 0;
-                prv[j] = (q < total && !(src[j] & FIRST_OF_ROW)) ? rw.inst[at - 1] : 0;
-            }
-#pragma unroll
-            for (int j = 0; j < G; ++j) {
-                const int q = (g + j) * NT + tid;
-                if (q < total) {
-                    const u32 k = (u32)((u64)cur[j] - rw.base - a);
-                    u32 d = k;                                 // first entry of its row: delta from the window start
-                    if (!(src[j] & FIRST_OF_ROW)) {
-                        d = (u32)((u64)cur[j] - (u64)prv[j]);
-                        bad |= (cur[j] < prv[j]);
-                        if (src[j] & FIRST_OF_SEGMENT) w0 += a - ((u64)prv[j] - rw.base);
-                    }
-                    key[g + j] = k;
-                    dl[g + j] = d;
-                }
-            }
-        }
-    }
+    for (int g = G0; g < ITEMS; g += GATHER_TAIL)           // a window seldom fills all items: smaller steps there
+        gather_batch<NT, ITEMS, GATHER_TAIL>(recs, bytes, g, total, start, key, dl, w0);
     return total;
 }
 
@@ -1172,7 +1181,7 @@ __global__ __launch_bounds__(NT) void zl_bounds_kernel(
 template <int NT, class CT>
 __global__ __launch_bounds__(NT) void zl_partition_kernel(
     const i64* __restrict__ ts, i64 nrows, int P, int R,
-    const InstInfo* __restrict__ info, CT* __restrict__ cross, int stride)
+    const InstInfo* __restrict__ info, CT* __restrict__ cross, int stride, int* __restrict__ status)
 {
     const int lane = threadIdx.x & (WAVE - 1);
     const i64 row_id = (i64)blockIdx.x * (NT / WAVE) + (threadIdx.x >> 6);
@@ -1184,16 +1193,23 @@ __global__ __launch_bounds__(NT) void zl_partition_kernel(
     const u64 base = (u64)ii.base;
 
     int carry = -1;                        // bin of the element before lane 0's
+    i64 carry_t = INT64_MIN;               // and its value
+    bool bad = false;
     for (int i0 = 0; i0 < R; i0 += WAVE) {
         const int i = i0 + lane;
         int bin = -1;
-        if (i < R) bin = (int)fine_bin((u64)row[i] - base, ii);
+        i64 t = INT64_MAX;
+        if (i < R) { t = row[i]; bin = (int)fine_bin((u64)t - base, ii); }
         int pb = __shfl_up(bin, 1, WAVE);
-        if (lane == 0) pb = carry;
+        i64 pt = __shfl_up(t, 1, WAVE);
+        if (lane == 0) { pb = carry; pt = carry_t; }
+        bad |= t < pt;                     // the only place the multi-window path checks every pair of neighbours
         if (i < R)
             for (int k = pb + 1; k <= bin; ++k) out[k] = (CT)i;
         carry = __shfl(bin, WAVE - 1, WAVE);
+        carry_t = __shfl(t, WAVE - 1, WAVE);
     }
+    if (__any(bad) && lane == 0 && status) atomicOr(status + b, (int)EBSP_STATUS_UNSORTED);
     const int last_bin = (int)fine_bin((u64)row[R - 1] - base, ii);
     for (int k = last_bin + 1 + lane; k <= (int)ii.nb; k += WAVE) out[k] = (CT)R;
 }
@@ -1302,10 +1318,10 @@ __device__ __forceinline__ WinPos locate_window(u32 logical, const i64* ts, i64 
 }
 
 // The fast search of one window (see zl_window_kernel); lo/hi hold the index
-// ranges of the thread's first ROWS_PER_THREAD rows.
+// ranges of the thread's first ROWS_PER_THREAD<NT> rows.
 template <int NT, int ITEMS>
 __device__ __forceinline__ void window_search(const Smem& sm, const WinPos& w, const InstInfo& ii,
-                                              const u32 (&lo)[ROWS_PER_THREAD], const u32 (&hi)[ROWS_PER_THREAD],
+                                              const u32 (&lo)[ROWS_PER_THREAD<NT>], const u32 (&hi)[ROWS_PER_THREAD<NT>],
                                               int P, int max_win, Partial* __restrict__ partial,
                                               int* __restrict__ status)
 {
@@ -1317,13 +1333,12 @@ __device__ __forceinline__ void window_search(const Smem& sm, const WinPos& w, c
     Partial r;
     r.wait = U64_MAX;
     r.brel = 0;
-    int bad = 0;
     if (w.valid) {
-        bool defer = (ii.range >> 32) != 0;
+        bool defer = (ii.range >> 32) != 0 || (u64)P * (u64)w.rw.R >= HOT_MAX_ENTRIES;
         if (!defer) {
             u32 key[ITEMS], dl[ITEMS];
             u64 w0 = 0;
-            const int total = zl_delta_rows<NT, ITEMS>(sm, w.rw, w.A, H::CAP, lo, hi, key, dl, w0, bad);
+            const int total = zl_delta_rows<NT, ITEMS>(sm, w.rw, w.A, H::CAP, lo, hi, key, dl, w0);
             defer = total > H::CAP;
             if (!defer && total > 0) {
                 u32 bkey;
@@ -1339,10 +1354,9 @@ __device__ __forceinline__ void window_search(const Smem& sm, const WinPos& w, c
             r.brel = DEFERRED_WINDOW;
         }
     }
-    bad = __syncthreads_or(bad);              // also: everyone is done with LDS before the next window
+    __syncthreads();                          // everyone is done with LDS before the next window
     if (threadIdx.x == 0) {
         partial[w.b * (i64)max_win + w.j] = r;
-        if (bad && status) atomicOr(status + w.b, (int)EBSP_STATUS_UNSORTED);
     }
 }
 
@@ -1370,11 +1384,11 @@ __global__ __launch_bounds__(NT, 4) void zl_window_kernel(
     const WinPos wA = locate_window(slot * 2, ts, B, P, R, info, cross, narrow, stride, winstart, max_win, iiA);
     const WinPos wB = locate_window(slot * 2 + 1, ts, B, P, R, info, cross, narrow, stride, winstart, max_win, iiB);
     const bool liveA = wA.b < B && wA.j < (int)iiA.nwin, liveB = wB.b < B && wB.j < (int)iiB.nwin;
-    u32 loA[ROWS_PER_THREAD], hiA[ROWS_PER_THREAD], loB[ROWS_PER_THREAD], hiB[ROWS_PER_THREAD];
+    u32 loA[ROWS_PER_THREAD<NT>], hiA[ROWS_PER_THREAD<NT>], loB[ROWS_PER_THREAD<NT>], hiB[ROWS_PER_THREAD<NT>];
 #pragma unroll
-    for (int c = 0; c < ROWS_PER_THREAD; ++c) { loA[c] = hiA[c] = loB[c] = hiB[c] = 0; }
-    if (liveA && wA.valid && !(iiA.range >> 32)) load_ranges<NT>(wA.rw, 0, loA, hiA);
-    if (liveB && wB.valid && !(iiB.range >> 32)) load_ranges<NT>(wB.rw, 0, loB, hiB);
+    for (int c = 0; c < ROWS_PER_THREAD<NT>; ++c) { loA[c] = hiA[c] = loB[c] = hiB[c] = 0; }
+    if (liveA && wA.valid && !(iiA.range >> 32) && (u64)P * (u64)R < HOT_MAX_ENTRIES) load_ranges<NT>(wA.rw, 0, loA, hiA);
+    if (liveB && wB.valid && !(iiB.range >> 32) && (u64)P * (u64)R < HOT_MAX_ENTRIES) load_ranges<NT>(wB.rw, 0, loB, hiB);
     if (liveA) window_search<NT, ITEMS>(sm, wA, iiA, loA, hiA, P, max_win, partial, status);
     if (liveB) window_search<NT, ITEMS>(sm, wB, iiB, loB, hiB, P, max_win, partial, status);
 }
@@ -1617,10 +1631,10 @@ int run_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters, i64*
     const i64 nrows = B * (i64)P;
     if (pl.narrow)
         LAUNCH(K_PARTITION, (zl_partition_kernel<256, unsigned short>), dim3((unsigned)((nrows + 3) / 4)), dim3(256),
-               ts, nrows, P, R, info, (unsigned short*)cross, pl.stride);
+               ts, nrows, P, R, info, (unsigned short*)cross, pl.stride, status);
     else
         LAUNCH(K_PARTITION, (zl_partition_kernel<256, u32>), dim3((unsigned)((nrows + 3) / 4)), dim3(256),
-               ts, nrows, P, R, info, (u32*)cross, pl.stride);
+               ts, nrows, P, R, info, (u32*)cross, pl.stride, status);
     const i64 kblocks = (pl.stride + 63) / 64, pblocks = (P + 255) / 256;
     if (kblocks * B > 0x7fffffffll || pblocks * B > 0x7fffffffll) return fail(EBSP_ERR_SHAPE, "batch too large for one call");
     if (pl.narrow)
