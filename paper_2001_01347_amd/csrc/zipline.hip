@@ -200,6 +200,16 @@ struct Rows {
         hi = hi < (u32)R ? hi : (u32)R;               // lead outside the row
         hi = hi > lo ? hi : lo;
     }
+    // the same when the caller knows the index type at compile time
+    template <class CT>
+    __device__ __forceinline__ void range_as(int p, u32& lo, u32& hi) const
+    {
+        const CT* c = (const CT*)cr + (i64)p * stride;
+        lo = c[k0]; hi = c[k1];
+        lo = lo < (u32)R ? lo : (u32)R;
+        hi = hi < (u32)R ? hi : (u32)R;
+        hi = hi > lo ? hi : lo;
+    }
     __device__ __forceinline__ u64 rel(int p, u32 i) const { return (u64)inst[(size_t)p * R + i] - base; }
 };
 
@@ -554,7 +564,7 @@ __device__ __forceinline__ void block_scan_pair(u32 c, u64 s, u32 m, u64 x, u64*
     xsum = xx;
 }
 
-template <int NT, int ITEMS>
+template <int NT, int ITEMS, bool TABLE = true>
 struct HotCfg {
     static constexpr int NW = NT / WAVE;
     static constexpr int CAP = NT * ITEMS;
@@ -564,7 +574,7 @@ struct HotCfg {
     static constexpr int PAD = 4;                         // record slots after the last one that a 4-wide read may touch
     static constexpr int BSUM_AT = CAP + PAD;             // bucket words follow the records
     static constexpr size_t BYTES = (size_t)BSUM_AT * 8 + (size_t)NB * 8 + (size_t)RED_WORDS * 8 + (size_t)NB * 4 +
-                                    (size_t)COARSE * 8;
+                                    (TABLE ? (size_t)COARSE * 8 : 0);   // the coarse table is the last area
 };
 // One LDS word per bucket holds its entry count (upper bits) and the sum of its
 // deltas (lower SUM_BITS bits: at most 16384 deltas below 2^32 each).
@@ -744,14 +754,14 @@ template <int NT> constexpr int ROWS_PER_THREAD = NT >= 1024 ? 1 : 1024 / NT;
 constexpr int WINDOWS_PER_BLOCK = 2;      // windows a workgroup handles, their index ranges fetched together
 constexpr u64 HOT_MAX_ENTRIES = 1ull << 29;   // P*R below this: byte offsets into an instance fit 32 bits
 
-template <int NT>
+template <int NT, class CT>
 __device__ __forceinline__ void load_ranges(const Rows& rw, int p0, u32 (&lo)[ROWS_PER_THREAD<NT>], u32 (&hi)[ROWS_PER_THREAD<NT>])
 {
 #pragma unroll
     for (int c = 0; c < ROWS_PER_THREAD<NT>; ++c) {
         const int p = p0 + c * NT + (int)threadIdx.x;
         lo[c] = 0; hi[c] = 0;
-        if (p < rw.P) rw.range(p, lo[c], hi[c]);
+        if (p < rw.P) rw.range_as<CT>(p, lo[c], hi[c]);
     }
 }
 
@@ -786,7 +796,7 @@ __device__ __forceinline__ void gather_batch(const u64* recs, const char* bytes,
     }
 }
 
-template <int NT, int ITEMS>
+template <int NT, int ITEMS, class CT>
 __device__ __forceinline__ int zl_delta_rows(const Smem& sm, const Rows& rw, u64 a, int cap,
                                              const u32 (&lo0)[ROWS_PER_THREAD<NT>], const u32 (&hi0)[ROWS_PER_THREAD<NT>],
                                              u32 (&key)[ITEMS], u32 (&dl)[ITEMS], u64& w0)
@@ -803,7 +813,7 @@ __device__ __forceinline__ int zl_delta_rows(const Smem& sm, const Rows& rw, u64
 #pragma unroll
             for (int c = 0; c < RPT; ++c) { lo[c] = lo0[c]; hi[c] = hi0[c]; }
         } else {
-            load_ranges<NT>(rw, p0, lo, hi);
+            load_ranges<NT, CT>(rw, p0, lo, hi);
         }
         u32 mine = 0;
 #pragma unroll
@@ -1249,18 +1259,23 @@ __global__ __launch_bounds__(256) void zl_bincount_kernel(
 
 // zl_plan: windows of an instance.  Fine bin k belongs to group
 // below[k] >> group_shift; a window is a maximal run of bins of one group, so
-// it holds fewer than 2^group_shift keys plus its last bin's.
+// it holds fewer than 2^group_shift keys plus its last bin's.  Per window: its
+// first fine bin (winstart) and its first and last value (winval).
+struct WinVal { u64 A, Elast; };
+
 template <int NT>
 __global__ __launch_bounds__(NT) void zl_plan_kernel(
     InstInfo* __restrict__ info, const u32* __restrict__ below, int stride,
-    u32* __restrict__ winstart, int max_win, int group_shift)
+    u32* __restrict__ winstart, WinVal* __restrict__ winval, int max_win, int group_shift)
 {
     __shared__ u32 red[NT / WAVE];
     const int tid = threadIdx.x;
     const i64 b = blockIdx.x;
     const u32* bel = below + b * (i64)stride;
     u32* ws = winstart + b * (i64)(max_win + 1);
-    const int nb = (int)info[b].nb;
+    WinVal* wv = winval + b * (i64)max_win;
+    const InstInfo ii = info[b];
+    const int nb = (int)ii.nb;
     u32 found = 0;
     for (int k0 = 0; k0 < nb; k0 += NT) {
         const int k = k0 + tid;
@@ -1268,13 +1283,19 @@ __global__ __launch_bounds__(NT) void zl_plan_kernel(
         if (k < nb) flag = (k == 0) || ((bel[k] >> group_shift) != (bel[k - 1] >> group_shift));
         u32 chunk;
         const u32 idx = found + block_excl_scan<u32, NT>(flag, red, chunk);
-        if (flag && idx < (u32)max_win) ws[idx] = (u32)k;
+        if (flag && idx < (u32)max_win) {
+            const u64 first = fine_bin_start((u32)k, ii);
+            ws[idx] = (u32)k;
+            wv[idx].A = first;
+            if (idx > 0) wv[idx - 1].Elast = first - 1;
+        }
         found += chunk;
     }
     if (tid == 0) {
         // more starts than max_win can only come from unsorted rows; the last window then runs to the end
         const u32 nwin = found < (u32)max_win ? found : (u32)max_win;
         ws[nwin] = (u32)nb;
+        if (nwin > 0) wv[nwin - 1].Elast = ii.range;
         info[b].nwin = nwin;
     }
 }
@@ -1288,42 +1309,41 @@ struct WinPos {
     u64 A, Elast;
 };
 
-__device__ __forceinline__ WinPos locate_window(u32 logical, const i64* ts, i64 B, int P, int R,
-                                                const InstInfo* info, const void* cross, bool narrow, int stride,
-                                                const u32* winstart, int max_win, InstInfo& ii)
+// Window j of instance b (b < B); `ii` must be info[b].
+__device__ __forceinline__ WinPos locate_window(i64 b, int j, const InstInfo& ii, const i64* ts, int P, int R,
+                                                const void* cross, bool narrow, int stride,
+                                                const u32* winstart, const WinVal* winval, int max_win)
 {
     WinPos w;
-    w.b = logical / (u32)max_win;
-    w.j = (int)(logical % (u32)max_win);
+    w.b = b;
+    w.j = j;
     w.valid = false;
-    if (w.b >= B) return w;
-    ii = info[w.b];
-    if (w.j >= (int)ii.nwin) return w;
-    const u32* ws = winstart + w.b * (i64)(max_win + 1);
-    w.rw.inst = ts + w.b * (i64)P * R;
+    if (j >= (int)ii.nwin) return w;
+    const u32* ws = winstart + b * (i64)(max_win + 1);
+    const WinVal wv = winval[b * (i64)max_win + j];
+    w.rw.inst = ts + b * (i64)P * R;
     w.rw.P = P; w.rw.R = R; w.rw.base = (u64)ii.base;
-    w.rw.cr = narrow ? (const void*)((const unsigned short*)cross + (w.b * (i64)P) * stride)
-                     : (const void*)((const u32*)cross + (w.b * (i64)P) * stride);
+    w.rw.cr = narrow ? (const void*)((const unsigned short*)cross + (b * (i64)P) * stride)
+                     : (const void*)((const u32*)cross + (b * (i64)P) * stride);
     w.rw.narrow = narrow;
     w.rw.stride = stride;
-    w.rw.k0 = ws[w.j];
-    w.rw.k1 = ws[w.j + 1];
+    w.rw.k0 = ws[j];
+    w.rw.k1 = ws[j + 1];
     if (w.rw.k0 > ii.nb) w.rw.k0 = ii.nb;              // stale scratch cannot index outside a row of cross
     if (w.rw.k1 > ii.nb) w.rw.k1 = ii.nb;
     if (w.rw.k1 <= w.rw.k0) w.rw.k1 = w.rw.k0 < ii.nb ? w.rw.k0 + 1 : w.rw.k0;
-    w.A = fine_bin_start(w.rw.k0, ii);                                            // first value of the window
-    w.Elast = w.rw.k1 >= ii.nb ? ii.range : fine_bin_start(w.rw.k1, ii) - 1;      // last value of the window
+    w.A = wv.A;                                         // first and last value of the window
+    w.Elast = wv.Elast;
     w.valid = w.Elast >= w.A;
     return w;
 }
 
 // The fast search of one window (see zl_window_kernel); lo/hi hold the index
 // ranges of the thread's first ROWS_PER_THREAD<NT> rows.
-template <int NT, int ITEMS>
+template <int NT, int ITEMS, class CT>
 __device__ __forceinline__ void window_search(const Smem& sm, const WinPos& w, const InstInfo& ii,
                                               const u32 (&lo)[ROWS_PER_THREAD<NT>], const u32 (&hi)[ROWS_PER_THREAD<NT>],
-                                              int P, int max_win, Partial* __restrict__ partial,
-                                              int* __restrict__ status)
+                                              int P, int max_win, Partial* __restrict__ partial)
 {
     using H = HotCfg<NT, ITEMS>;
     {
@@ -1338,7 +1358,7 @@ __device__ __forceinline__ void window_search(const Smem& sm, const WinPos& w, c
         if (!defer) {
             u32 key[ITEMS], dl[ITEMS];
             u64 w0 = 0;
-            const int total = zl_delta_rows<NT, ITEMS>(sm, w.rw, w.A, H::CAP, lo, hi, key, dl, w0);
+            const int total = zl_delta_rows<NT, ITEMS, CT>(sm, w.rw, w.A, H::CAP, lo, hi, key, dl, w0);
             defer = total > H::CAP;
             if (!defer && total > 0) {
                 u32 bkey;
@@ -1363,34 +1383,42 @@ __device__ __forceinline__ void window_search(const Smem& sm, const WinPos& w, c
 // One workgroup per window; the window's best candidate goes to `partial`.
 // Handles the normal case (32-bit value spread, the window fits in LDS) and
 // marks every other window as deferred to zl_window_general_kernel.
-template <int NT, int ITEMS>
+template <int NT, int ITEMS, class CT>
 __global__ __launch_bounds__(NT, 4) void zl_window_kernel(
     const i64* __restrict__ ts, i64 B, int P, int R,
-    const InstInfo* __restrict__ info, const void* __restrict__ cross, bool narrow, int stride,
-    const u32* __restrict__ winstart, int max_win,
-    Partial* __restrict__ partial, int* __restrict__ status)
+    const InstInfo* __restrict__ info, const CT* __restrict__ cross, int stride,
+    const u32* __restrict__ winstart, const WinVal* __restrict__ winval, int max_win, u32 pairs, u32 pairs_inv,
+    Partial* __restrict__ partial)
 {
-    using H = HotCfg<NT, ITEMS>;
+    using H = HotCfg<NT, ITEMS, false>;       // windows use the linear bucket map: no coarse table
     __shared__ __align__(16) unsigned char smem[H::BYTES];
     const Smem sm = carve_hot<NT, ITEMS>(smem);
+    constexpr bool narrow = sizeof(CT) == 2;
     // Consecutive windows share cache lines at their segment ends: give each
     // XCD (workgroups are dealt round-robin to the 8 XCDs) a contiguous range.
     const u32 per_xcd = gridDim.x / 8;
     const u32 slot = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    // slot = b * pairs + pair, with pairs_inv = floor(2^32 / pairs): the estimate is at most one short
+    u32 b = __umulhi(slot, pairs_inv);
+    u32 pair = slot - b * pairs;
+    if (pair >= pairs) { ++b; pair -= pairs; }
+    if ((i64)b >= B) return;
     // where the workgroup's two windows are, then the index ranges of both: the
     // latency of these two dependent fetches is paid once per workgroup
     static_assert(WINDOWS_PER_BLOCK == 2, "the kernel body is written out for two windows");
-    InstInfo iiA, iiB;
-    const WinPos wA = locate_window(slot * 2, ts, B, P, R, info, cross, narrow, stride, winstart, max_win, iiA);
-    const WinPos wB = locate_window(slot * 2 + 1, ts, B, P, R, info, cross, narrow, stride, winstart, max_win, iiB);
-    const bool liveA = wA.b < B && wA.j < (int)iiA.nwin, liveB = wB.b < B && wB.j < (int)iiB.nwin;
+    const InstInfo ii = info[b];
+    const int jA = (int)pair * 2, jB = jA + 1;
+    const WinPos wA = locate_window(b, jA, ii, ts, P, R, cross, narrow, stride, winstart, winval, max_win);
+    const WinPos wB = locate_window(b, jB, ii, ts, P, R, cross, narrow, stride, winstart, winval, max_win);
+    const bool liveA = jA < (int)ii.nwin, liveB = jB < (int)ii.nwin;
+    const bool hot = !(ii.range >> 32) && (u64)P * (u64)R < HOT_MAX_ENTRIES;
     u32 loA[ROWS_PER_THREAD<NT>], hiA[ROWS_PER_THREAD<NT>], loB[ROWS_PER_THREAD<NT>], hiB[ROWS_PER_THREAD<NT>];
 #pragma unroll
     for (int c = 0; c < ROWS_PER_THREAD<NT>; ++c) { loA[c] = hiA[c] = loB[c] = hiB[c] = 0; }
-    if (liveA && wA.valid && !(iiA.range >> 32) && (u64)P * (u64)R < HOT_MAX_ENTRIES) load_ranges<NT>(wA.rw, 0, loA, hiA);
-    if (liveB && wB.valid && !(iiB.range >> 32) && (u64)P * (u64)R < HOT_MAX_ENTRIES) load_ranges<NT>(wB.rw, 0, loB, hiB);
-    if (liveA) window_search<NT, ITEMS>(sm, wA, iiA, loA, hiA, P, max_win, partial, status);
-    if (liveB) window_search<NT, ITEMS>(sm, wB, iiB, loB, hiB, P, max_win, partial, status);
+    if (liveA && wA.valid && hot) load_ranges<NT, CT>(wA.rw, 0, loA, hiA);
+    if (liveB && wB.valid && hot) load_ranges<NT, CT>(wB.rw, 0, loB, hiB);
+    if (liveA) window_search<NT, ITEMS, CT>(sm, wA, ii, loA, hiA, P, max_win, partial);
+    if (liveB) window_search<NT, ITEMS, CT>(sm, wB, ii, loB, hiB, P, max_win, partial);
 }
 
 // The windows zl_window_kernel deferred: the general window search.  A small
@@ -1400,7 +1428,7 @@ template <int NT, int ITEMS>
 __global__ __launch_bounds__(NT) void zl_window_general_kernel(
     const i64* __restrict__ ts, i64 B, int P, int R,
     const InstInfo* __restrict__ info, const void* __restrict__ cross, bool narrow, int stride,
-    const u32* __restrict__ winstart, int max_win,
+    const u32* __restrict__ winstart, const WinVal* __restrict__ winval, int max_win,
     Partial* __restrict__ partial, int* __restrict__ status)
 {
     using C = WinCfg<NT, ITEMS>;
@@ -1422,8 +1450,10 @@ __global__ __launch_bounds__(NT) void zl_window_general_kernel(
             const u32 pick = block_reduce<u32, NT>(mine ? idx : 0xffffffffu, (u32*)sm.red, OpMin());
             if (pick == 0xffffffffu) break;
             if (pick == idx) mine = false;
-            InstInfo ii;
-            const WinPos w = locate_window(pick, ts, B, P, R, info, cross, narrow, stride, winstart, max_win, ii);
+            const i64 pb = pick / (u32)max_win;
+            const InstInfo ii = info[pb];
+            const WinPos w = locate_window(pb, (int)(pick % (u32)max_win), ii, ts, P, R, cross, narrow, stride,
+                                           winstart, winval, max_win);
             u64 bw = U64_MAX, bb = 0;
             int bad = 0;
             if (w.valid) {
@@ -1527,7 +1557,7 @@ struct Plan {
     int max_win;       // windows per instance <= max_win
     bool narrow;       // crossing indices fit 16 bits
     int step;          // zl_bincount looks at every step-th row
-    size_t off_info, off_cross, off_below, off_winstart, off_partial, bytes;
+    size_t off_info, off_cross, off_below, off_winstart, off_winval, off_partial, bytes;
 };
 
 bool make_plan(i64 B, int P, int R, Plan& pl)
@@ -1545,7 +1575,7 @@ bool make_plan(i64 B, int P, int R, Plan& pl)
     const int fine_shift = pl.group_shift - 2;
     pl.bins = (int)((n + (1 << fine_shift) - 1) >> fine_shift);
     pl.stride = pl.bins + 1;
-    pl.max_win = (int)(((n + n / 4) >> pl.group_shift) + 2);      // the counts behind the grouping are estimates
+    pl.max_win = (int)(((n + n / 4) >> pl.group_shift) + 3) & ~1;  // the counts behind the grouping are estimates; even
     size_t o = 0;
     pl.off_info = o;     o = align_up(o + (size_t)B * sizeof(InstInfo), 256);
     pl.narrow = R < 65536;
@@ -1553,6 +1583,7 @@ bool make_plan(i64 B, int P, int R, Plan& pl)
     pl.off_cross = o;    o = align_up(o + (size_t)B * P * pl.stride * (pl.narrow ? 2 : 4), 256);
     pl.off_below = o;    o = align_up(o + (size_t)B * pl.stride * sizeof(u32), 256);
     pl.off_winstart = o; o = align_up(o + (size_t)B * (pl.max_win + 1) * sizeof(u32), 256);
+    pl.off_winval = o;   o = align_up(o + (size_t)B * pl.max_win * sizeof(WinVal), 256);
     pl.off_partial = o;  o = align_up(o + (size_t)B * pl.max_win * sizeof(Partial), 256);
     pl.bytes = o;
     return true;
@@ -1625,6 +1656,7 @@ int run_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters, i64*
     void* cross = (void*)(wsp + pl.off_cross);
     u32* below = (u32*)(wsp + pl.off_below);
     u32* winstart = (u32*)(wsp + pl.off_winstart);
+    WinVal* winval = (WinVal*)(wsp + pl.off_winval);
     Partial* partial = (Partial*)(wsp + pl.off_partial);
 
     LAUNCH(K_BOUNDS, (zl_bounds_kernel<256>), dim3((unsigned)B), dim3(256), ts, P, R, pl.bins, info, status);
@@ -1643,21 +1675,25 @@ int run_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters, i64*
     else
         LAUNCH(K_BINCOUNT, zl_bincount_kernel<u32>, dim3((unsigned)(kblocks * B)), dim3(256),
                (const u32*)cross, P, R, pl.stride, pl.step, info, below);
-    LAUNCH(K_PLAN, (zl_plan_kernel<1024>), dim3((unsigned)B), dim3(1024), info, below, pl.stride, winstart, pl.max_win,
-           pl.group_shift);
-    const unsigned wgrid = (unsigned)(((total_win + WINDOWS_PER_BLOCK - 1) / WINDOWS_PER_BLOCK + 7) / 8 * 8);
-    if (pl.cap == 16384)
-        LAUNCH(K_WINDOW, (zl_window_kernel<1024, 16>), dim3(wgrid), dim3(1024),
-               ts, B, P, R, info, cross, pl.narrow, pl.stride, winstart, pl.max_win, partial, status);
-    else if (pl.cap == 8192)
-        LAUNCH(K_WINDOW, (zl_window_kernel<512, 16>), dim3(wgrid), dim3(512),
-               ts, B, P, R, info, cross, pl.narrow, pl.stride, winstart, pl.max_win, partial, status);
-    else
-        LAUNCH(K_WINDOW, (zl_window_kernel<256, 16>), dim3(wgrid), dim3(256),
-               ts, B, P, R, info, cross, pl.narrow, pl.stride, winstart, pl.max_win, partial, status);
+    LAUNCH(K_PLAN, (zl_plan_kernel<1024>), dim3((unsigned)B), dim3(1024), info, below, pl.stride, winstart, winval,
+           pl.max_win, pl.group_shift);
+    const u32 pairs = (u32)(pl.max_win / WINDOWS_PER_BLOCK);                 // max_win is even
+    const u32 pairs_inv = pairs > 1 ? (u32)((1ull << 32) / pairs) : 0xffffffffu;
+    const unsigned wgrid = (unsigned)((B * (i64)pairs + 7) / 8 * 8);
+#define LAUNCH_WINDOW(NT_, CT_)                                                                          \
+    LAUNCH(K_WINDOW, (zl_window_kernel<NT_, 16, CT_>), dim3(wgrid), dim3(NT_), ts, B, P, R, info,      \
+           (const CT_*)cross, pl.stride, winstart, winval, pl.max_win, pairs, pairs_inv, partial)
+    if (pl.cap == 16384) {
+        if (pl.narrow) LAUNCH_WINDOW(1024, unsigned short); else LAUNCH_WINDOW(1024, u32);
+    } else if (pl.cap == 8192) {
+        if (pl.narrow) LAUNCH_WINDOW(512, unsigned short); else LAUNCH_WINDOW(512, u32);
+    } else {
+        if (pl.narrow) LAUNCH_WINDOW(256, unsigned short); else LAUNCH_WINDOW(256, u32);
+    }
+#undef LAUNCH_WINDOW
     LAUNCH(K_WINDOW_GENERAL, (zl_window_general_kernel<LARGE_NT, LARGE_ITEMS>),
            dim3((unsigned)(total_win < GENERAL_GRID ? total_win : GENERAL_GRID)), dim3(LARGE_NT),
-           ts, B, P, R, info, cross, pl.narrow, pl.stride, winstart, pl.max_win, partial, status);
+           ts, B, P, R, info, cross, pl.narrow, pl.stride, winstart, winval, pl.max_win, partial, status);
     LAUNCH(K_FINISH, (zl_finish_kernel<256>), dim3((unsigned)(pblocks * B)), dim3(256),
            ts, P, R, info, partial, pl.max_win, barrier, iters, wait);
     return EBSP_OK;
