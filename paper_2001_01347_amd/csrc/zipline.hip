@@ -549,7 +549,7 @@ __device__ __forceinline__ void block_scan_pair(u32 c, u64 s, u32 m, u64 x, u64*
     __syncthreads();
     u32 cb = 0, mm = 0;
     u64 sb = 0, xx = 0;
-#pragma unroll
+#pragma unroll 2                       // more would hold all the partial results in registers at once
     for (int w = 0; w < NW; ++w) {
         const u64 xs = red[w], xc = red[NW + w];
         if (w < wave) { sb += xs; cb += (u32)xc; }
@@ -602,18 +602,37 @@ __device__ __forceinline__ Smem carve_hot(unsigned char* smem)
 // (Keys beyond the span only occur in unsorted rows; the clamps keep those in bounds.)
 struct LinearMap {
     u32 scale, top;
+    u32 span;      // largest key of sorted rows
+    u64 inv52;     // floor(2^52 / scale)
+    static constexpr bool HAS_BOUNDS = true;
     __device__ __forceinline__ u32 operator()(u32 key) const
     {
         const u32 b = (u32)(((u64)key * scale) >> 32);
         return b < top ? b : top;
     }
+    // lo <= every key of bucket b <= hi (for keys within [0, span]).  A key k of bucket
+    // b < top has b * 2^32 <= k * scale < (b + 1) * 2^32; inv52 is at most one short of
+    // 2^52 / scale, which costs less than 2 after the shift (b + 1 <= 2^11).
+    __device__ __forceinline__ void bounds(u32 b, u32& lo, u32& hi) const
+    {
+        const u64 l = ((u64)b * inv52) >> 20;
+        const u64 h = (((u64)(b + 1) * inv52) >> 20) + 2;
+        hi = (b >= top || h > span) ? span : (u32)h;
+        lo = l > hi ? hi : (u32)l;
+    }
 };
-__device__ __forceinline__ LinearMap linear_map(u64 span, u32 nb)
+__device__ __forceinline__ u32 linear_scale(u64 span, u32 nb)
 {
     const u64 q = ((u64)nb << 32) / (span + 1);
+    return q >= 0xffffffffull ? 0xffffffffu : (q ? (u32)q : 1u);
+}
+__device__ __forceinline__ LinearMap linear_map(u32 span, u32 nb, u32 scale, u64 inv52)
+{
     LinearMap m;
-    m.scale = q >= 0xffffffffull ? 0xffffffffu : (q ? (u32)q : 1u);
+    m.scale = scale;
     m.top = nb - 1;
+    m.span = span;
+    m.inv52 = inv52;
     return m;
 }
 // TableMap: piecewise linear through up to 256 coarse bins of width 2^cshift, each
@@ -624,6 +643,8 @@ __device__ __forceinline__ LinearMap linear_map(u64 span, u32 nb)
 struct TableMap {
     const u64* tab;
     u32 cshift, cmask;
+    static constexpr bool HAS_BOUNDS = false;
+    __device__ __forceinline__ void bounds(u32, u32& lo, u32& hi) const { lo = 0; hi = 0xffffffffu; }
     __device__ __forceinline__ u32 coarse(u32 key) const { const u32 c = key >> cshift; return c < 255u ? c : 255u; }
     __device__ __forceinline__ u32 operator()(u32 key) const
     {
@@ -665,6 +686,65 @@ __device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key
     u64 sbase, W0;
     block_scan_pair<NT, WITH_W0>(c0 + c1, s0 + s1, c0 > c1 ? c0 : c1, w0, sm.red, cbase, sbase, biggest, W0);
     if (biggest > BUCKET_LIMIT) return false;
+    u64 bw = U64_MAX;
+    u32 bk = 0xffffffffu;
+    if constexpr (Map::HAS_BOUNDS) {
+        // Most buckets cannot hold the minimum.  With E = the sum of deltas up to the end
+        // of bucket b and lo <= keys of b <= hi: the bucket's largest key kmax is a
+        // candidate with wait P*kmax + W0 - E <= P*hi + W0 - E =: ub(b) (if the whole
+        // bucket is admissible), and every key of b waits at least P*lo + W0 - E =: lb(b).
+        // Buckets with lb(b) above the smallest ub are dropped; the others get room in a
+        // compact list (in any order) and only their entries are scattered and evaluated.
+        constexpr u32 DROPPED = 0x80000000u;
+        u32* live_count = (u32*)(sm.red + H::RED_WORDS - 1);
+        if (tid == 0) *live_count = 0;
+        u32 lo0, hi0, lo1, hi1;
+        bucket.bounds(2 * tid, lo0, hi0);
+        bucket.bounds(2 * tid + 1, lo1, hi1);
+        const u64 need = thr > a ? thr - a : 0;                       // keys >= need are admissible
+        const u64 e0 = sbase + s0, e1 = e0 + s1;
+        const i64 ub0 = (i64)(P * (u64)hi0 + W0 - e0), ub1 = (i64)(P * (u64)hi1 + W0 - e1);
+        i64 ub = INT64_MAX;
+        if (c0 && lo0 >= need) ub = ub0;
+        if (c1 && lo1 >= need && ub1 < ub) ub = ub1;
+        const i64 ubmin = block_reduce<i64, NT>(ub, (i64*)sm.red, OpMin());
+        const bool live0 = c0 && ub0 - (i64)(P * (u64)(hi0 - lo0)) <= ubmin;
+        const bool live1 = c1 && ub1 - (i64)(P * (u64)(hi1 - lo1)) <= ubmin;
+        u32 at0 = DROPPED, at1 = DROPPED;
+        if (live0) at0 = atomicAdd(live_count, c0);
+        if (live1) at1 = atomicAdd(live_count, c1);
+        cnt[2 * tid] = at0; cnt[2 * tid + 1] = at1;
+        bsum[2 * tid] = sbase | ((u64)(at0 & (DROPPED - 1)) << SUM_BITS);     // BP(bucket) and the bucket's first slot
+        bsum[2 * tid + 1] = e0 | ((u64)(at1 & (DROPPED - 1)) << SUM_BITS);
+        __syncthreads();
+        // step 3: scatter the entries of the live buckets; afterwards cnt[b] is the end of bucket b
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j)
+            if (j * NT + tid < total) {
+                const u32 bid = bucket(key[j]);
+                const u32 slot = atomicAdd(&cnt[bid], 1u);
+                if (slot < DROPPED) recs[slot] = (u64)key[j] | ((u64)dl[j] << 32);
+            }
+        __syncthreads();
+        const int live = (int)*live_count;
+        // zl_scan + zl_argmin: every listed entry evaluates its own candidate
+        for (int q = tid; q < live; q += NT) {
+            const u32 k = (u32)recs[q];
+            const u32 bid = bucket(k);
+            const u32 e = cnt[bid];
+            const u64 hb = bsum[bid];
+            u32 x = (u32)(hb >> SUM_BITS);
+            u64 S = hb & SUM_MASK;
+            for (; x < e; ++x) {
+                const u64 r = recs[x];
+                S += ((u32)r <= k) ? r >> 32 : 0ull;
+            }
+            if ((u64)k >= need) {
+                const u64 w = P * (u64)k + W0 - S;
+                if (w < bw || (w == bw && k < bk)) { bw = w; bk = k; }
+            }
+        }
+    } else {
     cnt[2 * tid] = cbase; cnt[2 * tid + 1] = cbase + c0;
     bsum[2 * tid] = sbase | ((u64)cbase << SUM_BITS);                 // BP(bucket) and the bucket's first slot
     bsum[2 * tid + 1] = (sbase + s0) | ((u64)(cbase + c0) << SUM_BITS);
@@ -683,8 +763,6 @@ __device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key
     // zl_scan + zl_argmin: every element evaluates its own candidate.  The bucket map
     // is monotone, so whatever a 4-wide read picks up beyond the element's own bucket
     // has a larger key and drops out by the same comparison.
-    u64 bw = U64_MAX;
-    u32 bk = 0xffffffffu;
     for (int q = tid; q < total; q += NT) {
         const u32 k = (u32)recs[q];
         const u32 bid = bucket(k);
@@ -703,6 +781,7 @@ __device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key
             const u64 w = P * (u64)k + W0 - S;
             if (w < bw || (w == bw && k < bk)) { bw = w; bk = k; }
         }
+    }
     }
     // block arg-min over (wait, key): smaller wait, then smaller key
 #pragma unroll
@@ -1260,13 +1339,19 @@ __global__ __launch_bounds__(256) void zl_bincount_kernel(
 // zl_plan: windows of an instance.  Fine bin k belongs to group
 // below[k] >> group_shift; a window is a maximal run of bins of one group, so
 // it holds fewer than 2^group_shift keys plus its last bin's.  Per window: its
-// first fine bin (winstart) and its first and last value (winval).
-struct WinVal { u64 A, Elast; };
+// first fine bin (winstart), its first and last value and the constants of the
+// linear bucket map over that span (winval).
+struct WinVal {
+    u64 A, Elast;
+    u64 inv52;     // floor(2^52 / scale)
+    u32 scale;     // linear_scale(Elast - A, buckets), when the span fits 32 bits
+    u32 pad_;
+};
 
 template <int NT>
 __global__ __launch_bounds__(NT) void zl_plan_kernel(
     InstInfo* __restrict__ info, const u32* __restrict__ below, int stride,
-    u32* __restrict__ winstart, WinVal* __restrict__ winval, int max_win, int group_shift)
+    u32* __restrict__ winstart, WinVal* __restrict__ winval, int max_win, int group_shift, u32 buckets)
 {
     __shared__ u32 red[NT / WAVE];
     const int tid = threadIdx.x;
@@ -1298,6 +1383,17 @@ __global__ __launch_bounds__(NT) void zl_plan_kernel(
         if (nwin > 0) wv[nwin - 1].Elast = ii.range;
         info[b].nwin = nwin;
     }
+    // the windows' values are complete: their bucket maps
+    __threadfence_block();
+    __syncthreads();
+    const u32 nwin = found < (u32)max_win ? found : (u32)max_win;
+    for (u32 j = tid; j < nwin; j += NT) {
+        const u64 span = wv[j].Elast - wv[j].A;
+        const u32 scale = linear_scale(span <= 0xffffffffull ? span : 0xffffffffull, buckets);
+        wv[j].scale = scale;
+        wv[j].inv52 = (1ull << 52) / scale;
+        wv[j].pad_ = 0;
+    }
 }
 
 // Where a window sits: instance b, window j, fine bins [k0, k1), values [A, Elast].
@@ -1307,6 +1403,8 @@ struct WinPos {
     bool valid;
     Rows rw;
     u64 A, Elast;
+    u32 scale;      // of the linear bucket map over [A, Elast]
+    u64 inv52;
 };
 
 // Window j of instance b (b < B); `ii` must be info[b].
@@ -1334,6 +1432,8 @@ __device__ __forceinline__ WinPos locate_window(i64 b, int j, const InstInfo& ii
     if (w.rw.k1 <= w.rw.k0) w.rw.k1 = w.rw.k0 < ii.nb ? w.rw.k0 + 1 : w.rw.k0;
     w.A = wv.A;                                         // first and last value of the window
     w.Elast = wv.Elast;
+    w.scale = wv.scale ? wv.scale : 1u;
+    w.inv52 = wv.inv52;
     w.valid = w.Elast >= w.A;
     return w;
 }
@@ -1362,7 +1462,8 @@ __device__ __forceinline__ void window_search(const Smem& sm, const WinPos& w, c
             defer = total > H::CAP;
             if (!defer && total > 0) {
                 u32 bkey;
-                if (zl_bucket_finish<NT, ITEMS, true>(sm, key, dl, linear_map(w.Elast - w.A, H::NB), total, w.A,
+                if (zl_bucket_finish<NT, ITEMS, true>(sm, key, dl,
+                                                      linear_map((u32)(w.Elast - w.A), H::NB, w.scale, w.inv52), total, w.A,
                                                       ii.thr, (u64)P, w0, r.wait, bkey))
                     r.brel = w.A + bkey;
                 else
@@ -1676,7 +1777,7 @@ int run_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters, i64*
         LAUNCH(K_BINCOUNT, zl_bincount_kernel<u32>, dim3((unsigned)(kblocks * B)), dim3(256),
                (const u32*)cross, P, R, pl.stride, pl.step, info, below);
     LAUNCH(K_PLAN, (zl_plan_kernel<1024>), dim3((unsigned)B), dim3(1024), info, below, pl.stride, winstart, winval,
-           pl.max_win, pl.group_shift);
+           pl.max_win, pl.group_shift, (u32)(pl.cap / 8));
     const u32 pairs = (u32)(pl.max_win / WINDOWS_PER_BLOCK);                 // max_win is even
     const u32 pairs_inv = pairs > 1 ? (u32)((1ull << 32) / pairs) : 0xffffffffu;
     const unsigned wgrid = (unsigned)((B * (i64)pairs + 7) / 8 * 8);
