@@ -34,6 +34,7 @@
 #include <stdint.h>
 #include <stdio.h>
 #include <string.h>
+#include <limits>
 
 #include "ebsp_zipline.h"
 
@@ -78,16 +79,73 @@ struct Partial {  // best candidate of one window
 // ---------------------------------------------------------------------------
 // Wave and block primitives (wave64).
 
-template <class T>
-__device__ __forceinline__ T wave_incl_scan(T v)
+// Cross-lane moves inside the vector ALU (data-parallel primitives): no trip
+// through the LDS pipeline.  dpp_take<CTRL, ROWS>(fill, v) gives every lane the
+// value of the lane that CTRL selects; lanes in rows outside the ROWS mask and
+// lanes whose source does not exist get `fill`.
+template <int CTRL, int ROWS>
+__device__ __forceinline__ u32 dpp_word(u32 fill, u32 v)
 {
-    const int lane = threadIdx.x & (WAVE - 1);
-#pragma unroll
-    for (int d = 1; d < WAVE; d <<= 1) {
-        T o = __shfl_up(v, d, WAVE);
-        if (lane >= d) v += o;
+    return (u32)__builtin_amdgcn_update_dpp((int)fill, (int)v, CTRL, ROWS, 0xf, false);
+}
+template <int CTRL, int ROWS, class T>
+__device__ __forceinline__ T dpp_take(T fill, T v)
+{
+    static_assert(sizeof(T) == 4 || sizeof(T) == 8, "one or two words");
+    if constexpr (sizeof(T) == 4) {
+        return (T)dpp_word<CTRL, ROWS>((u32)fill, (u32)v);
+    } else {
+        const u64 f = (u64)fill, x = (u64)v;
+        return (T)((u64)dpp_word<CTRL, ROWS>((u32)f, (u32)x) |
+                   ((u64)dpp_word<CTRL, ROWS>((u32)(f >> 32), (u32)(x >> 32)) << 32));
     }
+}
+constexpr int DPP_ROW_SHR1 = 0x111, DPP_ROW_SHR2 = 0x112, DPP_ROW_SHR4 = 0x114, DPP_ROW_SHR8 = 0x118,
+              DPP_ROW_BCAST15 = 0x142, DPP_ROW_BCAST31 = 0x143;
+
+struct OpMin {
+    template <class T> __device__ T operator()(T a, T b) const { return a < b ? a : b; }
+    template <class T> static constexpr T identity() { return std::numeric_limits<T>::max(); }
+};
+struct OpMax {
+    template <class T> __device__ T operator()(T a, T b) const { return a > b ? a : b; }
+    template <class T> static constexpr T identity() { return std::numeric_limits<T>::lowest(); }
+};
+struct OpAdd {
+    template <class T> __device__ T operator()(T a, T b) const { return a + b; }
+    template <class T> static constexpr T identity() { return T(0); }
+};
+
+// Inclusive scan over the 64 lanes of a wave: four steps inside each row of 16
+// lanes, then the row totals are passed on (last lane of row 0 and 2 to rows 1
+// and 3, last lane of row 1 to rows 2 and 3).  Lane 63 ends with the reduction.
+template <class T, class Op>
+__device__ __forceinline__ T wave_scan(T v, Op op)
+{
+    constexpr T id = Op::template identity<T>();
+    v = op(v, dpp_take<DPP_ROW_SHR1, 0xf>(id, v));
+    v = op(v, dpp_take<DPP_ROW_SHR2, 0xf>(id, v));
+    v = op(v, dpp_take<DPP_ROW_SHR4, 0xf>(id, v));
+    v = op(v, dpp_take<DPP_ROW_SHR8, 0xf>(id, v));
+    v = op(v, dpp_take<DPP_ROW_BCAST15, 0xa>(id, v));
+    v = op(v, dpp_take<DPP_ROW_BCAST31, 0xc>(id, v));
     return v;
+}
+template <class T>
+__device__ __forceinline__ T wave_incl_scan(T v) { return wave_scan(v, OpAdd()); }
+
+// First minimum of (w, k) pairs over a wave (smaller w, then smaller k); lane 63 ends with it.
+template <class K>
+__device__ __forceinline__ void wave_argmin(u64& w, K& k)
+{
+    auto step = [&](u64 ow, K ok) { if (ow < w || (ow == w && ok < k)) { w = ow; k = ok; } };
+    constexpr K kmax = std::numeric_limits<K>::max();
+    step(dpp_take<DPP_ROW_SHR1, 0xf>(U64_MAX, w), dpp_take<DPP_ROW_SHR1, 0xf>(kmax, k));
+    step(dpp_take<DPP_ROW_SHR2, 0xf>(U64_MAX, w), dpp_take<DPP_ROW_SHR2, 0xf>(kmax, k));
+    step(dpp_take<DPP_ROW_SHR4, 0xf>(U64_MAX, w), dpp_take<DPP_ROW_SHR4, 0xf>(kmax, k));
+    step(dpp_take<DPP_ROW_SHR8, 0xf>(U64_MAX, w), dpp_take<DPP_ROW_SHR8, 0xf>(kmax, k));
+    step(dpp_take<DPP_ROW_BCAST15, 0xa>(U64_MAX, w), dpp_take<DPP_ROW_BCAST15, 0xa>(kmax, k));
+    step(dpp_take<DPP_ROW_BCAST31, 0xc>(U64_MAX, w), dpp_take<DPP_ROW_BCAST31, 0xc>(kmax, k));
 }
 
 // Exclusive block scan; `total` receives the block sum.  `red` holds NT/64 T's.
@@ -111,18 +169,13 @@ __device__ __forceinline__ T block_excl_scan(T v, T* red, T& total)
     return base + inc - v;
 }
 
-struct OpMin { template <class T> __device__ T operator()(T a, T b) const { return a < b ? a : b; } };
-struct OpMax { template <class T> __device__ T operator()(T a, T b) const { return a > b ? a : b; } };
-struct OpAdd { template <class T> __device__ T operator()(T a, T b) const { return a + b; } };
-
 template <class T, int NT, class Op>
 __device__ __forceinline__ T block_reduce(T v, T* red, Op op)
 {
     constexpr int NW = NT / WAVE;
     const int lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x >> 6;
-#pragma unroll
-    for (int d = WAVE / 2; d > 0; d >>= 1) v = op(v, __shfl_xor(v, d, WAVE));
-    if (lane == 0) red[wave] = v;
+    v = wave_scan(v, op);
+    if (lane == WAVE - 1) red[wave] = v;
     __syncthreads();
     T r = red[0];
 #pragma unroll
@@ -138,14 +191,10 @@ __device__ __forceinline__ void block_bounds(i64 a, i64 b, i64 c, i64* red, i64&
 {
     constexpr int NW = NT / WAVE;
     const int lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x >> 6;
-#pragma unroll
-    for (int d = WAVE / 2; d > 0; d >>= 1) {
-        const i64 oa = __shfl_xor(a, d, WAVE), ob = __shfl_xor(b, d, WAVE), oc = __shfl_xor(c, d, WAVE);
-        a = oa < a ? oa : a;
-        b = ob > b ? ob : b;
-        c = oc > c ? oc : c;
-    }
-    if (lane == 0) { red[wave] = a; red[NW + wave] = b; red[2 * NW + wave] = c; }
+    a = wave_scan(a, OpMin());
+    b = wave_scan(b, OpMax());
+    c = wave_scan(c, OpMax());
+    if (lane == WAVE - 1) { red[wave] = a; red[NW + wave] = b; red[2 * NW + wave] = c; }
     __syncthreads();
     a = red[0]; b = red[NW]; c = red[2 * NW];
 #pragma unroll
@@ -527,20 +576,10 @@ __device__ __forceinline__ void block_scan_pair(u32 c, u64 s, u32 m, u64 x, u64*
 {
     constexpr int NW = NT / WAVE;
     const int lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x >> 6;
-    u32 ci = c;
-    u64 si = s;
-#pragma unroll
-    for (int d = 1; d < WAVE; d <<= 1) {
-        const u32 oc = __shfl_up(ci, d, WAVE);
-        const u64 os = __shfl_up(si, d, WAVE);
-        if (lane >= d) { ci += oc; si += os; }
-    }
-#pragma unroll
-    for (int d = WAVE / 2; d > 0; d >>= 1) {
-        const u32 o = __shfl_xor(m, d, WAVE);
-        m = o > m ? o : m;
-        if (WITH_X) x += __shfl_xor(x, d, WAVE);
-    }
+    const u32 ci = wave_scan(c, OpAdd());
+    const u64 si = wave_scan(s, OpAdd());
+    m = wave_scan(m, OpMax());
+    if (WITH_X) x = wave_scan(x, OpAdd());
     if (lane == WAVE - 1) {
         red[wave] = si;
         red[NW + wave] = ((u64)m << 32) | ci;
@@ -784,16 +823,11 @@ __device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key
     }
     }
     // block arg-min over (wait, key): smaller wait, then smaller key
-#pragma unroll
-    for (int d = WAVE / 2; d > 0; d >>= 1) {
-        const u64 ow = __shfl_xor(bw, d, WAVE);
-        const u32 ok = __shfl_xor(bk, d, WAVE);
-        if (ow < bw || (ow == bw && ok < bk)) { bw = ow; bk = ok; }
-    }
+    wave_argmin(bw, bk);
     constexpr int NW = NT / WAVE;
     const int lane = tid & (WAVE - 1), wave = tid >> 6;
     u64* red = sm.red;
-    if (lane == 0) { red[wave] = bw; red[NW + wave] = bk; }
+    if (lane == WAVE - 1) { red[wave] = bw; red[NW + wave] = bk; }
     __syncthreads();
     bw = red[0];
     bk = (u32)red[NW];
@@ -1594,12 +1628,8 @@ __global__ __launch_bounds__(NT) void zl_finish_kernel(
         const Partial r = pp[j];
         if (r.wait < bw || (r.wait == bw && r.brel < bb)) { bw = r.wait; bb = r.brel; }
     }
-#pragma unroll
-    for (int d = WAVE / 2; d > 0; d >>= 1) {
-        const u64 ow = __shfl_xor(bw, d, WAVE), ob = __shfl_xor(bb, d, WAVE);
-        if (ow < bw || (ow == bw && ob < bb)) { bw = ow; bb = ob; }
-    }
-    if (lane == 0) { red[wave] = bw; red[NW + wave] = bb; }
+    wave_argmin(bw, bb);
+    if (lane == WAVE - 1) { red[wave] = bw; red[NW + wave] = bb; }
     __syncthreads();
     bw = red[0]; bb = red[NW];
 #pragma unroll
