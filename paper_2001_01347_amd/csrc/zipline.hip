@@ -864,7 +864,7 @@ __device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key
 constexpr u64 FIRST_OF_ROW = 1ull << 32, FIRST_OF_SEGMENT = 1ull << 33;
 // rows a thread takes per round of sweep 1: one round covers 1024 rows
 template <int NT> constexpr int ROWS_PER_THREAD = NT >= 1024 ? 1 : 1024 / NT;
-constexpr int WINDOWS_PER_BLOCK = 2;      // windows a workgroup handles, their index ranges fetched together
+constexpr int WINDOWS_PER_BLOCK = 2;      // consecutive windows a workgroup handles, one after the other
 constexpr u64 HOT_MAX_ENTRIES = 1ull << 29;   // P*R below this: byte offsets into an instance fit 32 bits
 
 template <int NT, class CT>
@@ -880,6 +880,18 @@ __device__ __forceinline__ void load_ranges(const Rows& rw, int p0, u32 (&lo)[RO
 
 // Sweep 2 for items [g, g + G) of every thread.  Only the low words of the
 // timestamps are loaded (rows were checked for order by zl_partition).
+// Crossing indices of the thread's rows of the first round at fine bin k (0 for rows beyond P).
+template <int NT, class CT>
+__device__ __forceinline__ void load_column(const Rows& rw, u32 k, u32 (&out)[ROWS_PER_THREAD<NT>])
+{
+#pragma unroll
+    for (int c = 0; c < ROWS_PER_THREAD<NT>; ++c) {
+        const int p = c * NT + (int)threadIdx.x;
+        out[c] = 0;
+        if (p < rw.P) out[c] = ((const CT*)rw.cr)[(i64)p * rw.stride + k];
+    }
+}
+
 template <int NT, int ITEMS, int G>
 __device__ __forceinline__ void gather_batch(const u64* recs, const char* bytes, int g, int total, u32 start,
                                              u32 (&key)[ITEMS], u32 (&dl)[ITEMS], u64& w0)
@@ -922,22 +934,32 @@ __device__ __forceinline__ int zl_delta_rows(const Smem& sm, const Rows& rw, u64
     constexpr int RPT = ROWS_PER_THREAD<NT>;
     for (int p0 = 0; p0 < rw.P; p0 += RPT * NT) {
         u32 lo[RPT], hi[RPT];
-        if (p0 == 0) {                                       // the first round's ranges came with the call
+        if (p0 == 0) {                                       // the first round's crossings came with the call
 #pragma unroll
-            for (int c = 0; c < RPT; ++c) { lo[c] = lo0[c]; hi[c] = hi0[c]; }
+            for (int c = 0; c < RPT; ++c) {                  // stale scratch (unsorted rows) cannot lead outside the row
+                lo[c] = lo0[c] < (u32)rw.R ? lo0[c] : (u32)rw.R;
+                hi[c] = hi0[c] < (u32)rw.R ? hi0[c] : (u32)rw.R;
+                hi[c] = hi[c] > lo[c] ? hi[c] : lo[c];
+            }
         } else {
             load_ranges<NT, CT>(rw, p0, lo, hi);
         }
         u32 mine = 0;
+        u32 before[RPT];                                     // rows with nothing in the window: their last entry before it
 #pragma unroll
-        for (int c = 0; c < RPT; ++c) mine += hi[c] - lo[c];
+        for (int c = 0; c < RPT; ++c) {
+            const int p = p0 + c * NT + tid;
+            mine += hi[c] - lo[c];
+            before[c] = start;
+            if (p < rw.P && lo[c] == hi[c] && lo[c] > 0)
+                before[c] = *(const u32*)(bytes + (((u32)p * (u32)rw.R + lo[c] - 1u) << 3));
+        }
         u32 round;
         u32 slot = (u32)total + block_excl_scan<u32, NT>(mine, (u32*)sm.red, round);
 #pragma unroll
         for (int c = 0; c < RPT; ++c) {
             const int p = p0 + c * NT + tid;
             if (p < rw.P) {
-                if (lo[c] == hi[c] && lo[c] > 0) w0 += a - rw.rel(p, lo[c] - 1);
                 u64 src = (u64)((u32)p * (u32)rw.R + lo[c]) | FIRST_OF_SEGMENT | (lo[c] == 0 ? FIRST_OF_ROW : 0ull);
                 for (u32 i = lo[c]; i < hi[c] && slot < (u32)cap; ++i, ++slot) {
                     recs[slot] = src;
@@ -945,6 +967,8 @@ __device__ __forceinline__ int zl_delta_rows(const Smem& sm, const Rows& rw, u64
                 }
             }
         }
+#pragma unroll
+        for (int c = 0; c < RPT; ++c) w0 += (u64)(start - before[c]);     // below 2^32 like every relative value
         total += (int)round;
     }
     __syncthreads();
@@ -1475,9 +1499,9 @@ __device__ __forceinline__ WinPos locate_window(i64 b, int j, const InstInfo& ii
 // The fast search of one window (see zl_window_kernel); lo/hi hold the index
 // ranges of the thread's first ROWS_PER_THREAD<NT> rows.
 template <int NT, int ITEMS, class CT>
-__device__ __forceinline__ void window_search(const Smem& sm, const WinPos& w, const InstInfo& ii,
+__device__ __forceinline__ void window_search(const Smem& sm, const Rows& rw, const WinVal& wv, const InstInfo& ii, bool hot,
                                               const u32 (&lo)[ROWS_PER_THREAD<NT>], const u32 (&hi)[ROWS_PER_THREAD<NT>],
-                                              int P, int max_win, Partial* __restrict__ partial)
+                                              Partial* __restrict__ out)
 {
     using H = HotCfg<NT, ITEMS>;
     {
@@ -1487,19 +1511,20 @@ __device__ __forceinline__ void window_search(const Smem& sm, const WinPos& w, c
     Partial r;
     r.wait = U64_MAX;
     r.brel = 0;
-    if (w.valid) {
-        bool defer = (ii.range >> 32) != 0 || (u64)P * (u64)w.rw.R >= HOT_MAX_ENTRIES;
+    if (wv.Elast >= wv.A) {
+        bool defer = !hot;
         if (!defer) {
             u32 key[ITEMS], dl[ITEMS];
             u64 w0 = 0;
-            const int total = zl_delta_rows<NT, ITEMS, CT>(sm, w.rw, w.A, H::CAP, lo, hi, key, dl, w0);
+            const int total = zl_delta_rows<NT, ITEMS, CT>(sm, rw, wv.A, H::CAP, lo, hi, key, dl, w0);
             defer = total > H::CAP;
             if (!defer && total > 0) {
                 u32 bkey;
                 if (zl_bucket_finish<NT, ITEMS, true>(sm, key, dl,
-                                                      linear_map((u32)(w.Elast - w.A), H::NB, w.scale, w.inv52), total, w.A,
-                                                      ii.thr, (u64)P, w0, r.wait, bkey))
-                    r.brel = w.A + bkey;
+                                                      linear_map((u32)(wv.Elast - wv.A), H::NB, wv.scale ? wv.scale : 1u,
+                                                                 wv.inv52),
+                                                      total, wv.A, ii.thr, (u64)rw.P, w0, r.wait, bkey))
+                    r.brel = wv.A + bkey;
                 else
                     defer = true;
             }
@@ -1510,50 +1535,81 @@ __device__ __forceinline__ void window_search(const Smem& sm, const WinPos& w, c
         }
     }
     __syncthreads();                          // everyone is done with LDS before the next window
-    if (threadIdx.x == 0) {
-        partial[w.b * (i64)max_win + w.j] = r;
-    }
+    if (threadIdx.x == 0) *out = r;
 }
 
-// One workgroup per window; the window's best candidate goes to `partial`.
-// Handles the normal case (32-bit value spread, the window fits in LDS) and
-// marks every other window as deferred to zl_window_general_kernel.
+// One workgroup per WINDOWS_PER_BLOCK consecutive windows of an instance; each
+// window's best candidate goes to `partial`.  Handles the normal case (32-bit
+// value spread, the window fits in LDS) and marks every other window as deferred
+// to zl_window_general_kernel.  A window's upper crossings are the next
+// window's lower ones, and those of the window after are fetched while the
+// current one is being searched.
 template <int NT, int ITEMS, class CT>
 __global__ __launch_bounds__(NT, 4) void zl_window_kernel(
     const i64* __restrict__ ts, i64 B, int P, int R,
     const InstInfo* __restrict__ info, const CT* __restrict__ cross, int stride,
-    const u32* __restrict__ winstart, const WinVal* __restrict__ winval, int max_win, u32 pairs, u32 pairs_inv,
+    const u32* __restrict__ winstart, const WinVal* __restrict__ winval, int max_win, u32 groups, u32 groups_inv,
     Partial* __restrict__ partial)
 {
     using H = HotCfg<NT, ITEMS, false>;       // windows use the linear bucket map: no coarse table
     __shared__ __align__(16) unsigned char smem[H::BYTES];
     const Smem sm = carve_hot<NT, ITEMS>(smem);
-    constexpr bool narrow = sizeof(CT) == 2;
+    constexpr int RPT = ROWS_PER_THREAD<NT>;
     // Consecutive windows share cache lines at their segment ends: give each
     // XCD (workgroups are dealt round-robin to the 8 XCDs) a contiguous range.
     const u32 per_xcd = gridDim.x / 8;
     const u32 slot = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
-    // slot = b * pairs + pair, with pairs_inv = floor(2^32 / pairs): the estimate is at most one short
-    u32 b = __umulhi(slot, pairs_inv);
-    u32 pair = slot - b * pairs;
-    if (pair >= pairs) { ++b; pair -= pairs; }
+    // slot = b * groups + group, with groups_inv = floor(2^32 / groups): the estimate is at most one short
+    u32 b = __umulhi(slot, groups_inv);
+    u32 group = slot - b * groups;
+    if (group >= groups) { ++b; group -= groups; }
     if ((i64)b >= B) return;
-    // where the workgroup's two windows are, then the index ranges of both: the
-    // latency of these two dependent fetches is paid once per workgroup
-    static_assert(WINDOWS_PER_BLOCK == 2, "the kernel body is written out for two windows");
     const InstInfo ii = info[b];
-    const int jA = (int)pair * 2, jB = jA + 1;
-    const WinPos wA = locate_window(b, jA, ii, ts, P, R, cross, narrow, stride, winstart, winval, max_win);
-    const WinPos wB = locate_window(b, jB, ii, ts, P, R, cross, narrow, stride, winstart, winval, max_win);
-    const bool liveA = jA < (int)ii.nwin, liveB = jB < (int)ii.nwin;
+    const int j0 = (int)group * WINDOWS_PER_BLOCK;
+    const int jend = j0 + WINDOWS_PER_BLOCK < (int)ii.nwin ? j0 + WINDOWS_PER_BLOCK : (int)ii.nwin;
+    if (j0 >= jend) return;
+    const u32* ws = winstart + b * (i64)(max_win + 1);       // max_win + 1 entries
+    const WinVal* wv = winval + b * (i64)max_win;
+    Partial* out = partial + b * (i64)max_win;
     const bool hot = !(ii.range >> 32) && (u64)P * (u64)R < HOT_MAX_ENTRIES;
-    u32 loA[ROWS_PER_THREAD<NT>], hiA[ROWS_PER_THREAD<NT>], loB[ROWS_PER_THREAD<NT>], hiB[ROWS_PER_THREAD<NT>];
+    Rows rw;
+    rw.inst = ts + b * (i64)P * R;
+    rw.P = P; rw.R = R; rw.base = (u64)ii.base;
+    rw.cr = (const void*)(cross + (b * (i64)P) * stride);
+    rw.narrow = sizeof(CT) == 2;
+    rw.stride = stride;
+    // fine bins where the current window starts and ends and where the next one ends
+    // (stale scratch cannot index outside a row of cross)
+    // fine bins where the windows start and end (stale scratch cannot index outside a
+    // row of cross) and the windows' values: all fetched before the first search
+    constexpr int W = WINDOWS_PER_BLOCK;
+    u32 bins[W + 1];
+    WinVal vals[W];
 #pragma unroll
-    for (int c = 0; c < ROWS_PER_THREAD<NT>; ++c) { loA[c] = hiA[c] = loB[c] = hiB[c] = 0; }
-    if (liveA && wA.valid && hot) load_ranges<NT, CT>(wA.rw, 0, loA, hiA);
-    if (liveB && wB.valid && hot) load_ranges<NT, CT>(wB.rw, 0, loB, hiB);
-    if (liveA) window_search<NT, ITEMS, CT>(sm, wA, ii, loA, hiA, P, max_win, partial);
-    if (liveB) window_search<NT, ITEMS, CT>(sm, wB, ii, loB, hiB, P, max_win, partial);
+    for (int i = 0; i <= W; ++i) {
+        const u32 k = ws[j0 + i];                            // j0 + W <= max_win
+        bins[i] = k < ii.nb ? k : ii.nb;
+    }
+#pragma unroll
+    for (int i = 0; i < W; ++i) vals[i] = wv[j0 + i];
+    u32 lo[RPT], hi[RPT], next[RPT];
+#pragma unroll
+    for (int c = 0; c < RPT; ++c) { lo[c] = hi[c] = next[c] = 0; }
+    if (hot) {
+        load_column<NT, CT>(rw, bins[0], lo);
+        load_column<NT, CT>(rw, bins[1], hi);
+    }
+#pragma unroll
+    for (int i = 0; i < W; ++i) {
+        if (j0 + i < jend) {
+            if (hot && i + 1 < W && j0 + i + 1 < jend) load_column<NT, CT>(rw, bins[i + 1 < W ? i + 2 : W], next);
+            rw.k0 = bins[i];
+            rw.k1 = bins[i + 1] > bins[i] ? bins[i + 1] : bins[i];
+            window_search<NT, ITEMS, CT>(sm, rw, vals[i], ii, hot, lo, hi, out + j0 + i);
+#pragma unroll
+            for (int c = 0; c < RPT; ++c) { lo[c] = hi[c]; hi[c] = next[c]; }
+        }
+    }
 }
 
 // The windows zl_window_kernel deferred: the general window search.  A small
@@ -1706,7 +1762,8 @@ bool make_plan(i64 B, int P, int R, Plan& pl)
     const int fine_shift = pl.group_shift - 2;
     pl.bins = (int)((n + (1 << fine_shift) - 1) >> fine_shift);
     pl.stride = pl.bins + 1;
-    pl.max_win = (int)(((n + n / 4) >> pl.group_shift) + 3) & ~1;  // the counts behind the grouping are estimates; even
+    // the counts behind the grouping are estimates; a whole number of workgroups per instance
+    pl.max_win = (int)((((n + n / 4) >> pl.group_shift) + 2 + WINDOWS_PER_BLOCK - 1) / WINDOWS_PER_BLOCK * WINDOWS_PER_BLOCK);
     size_t o = 0;
     pl.off_info = o;     o = align_up(o + (size_t)B * sizeof(InstInfo), 256);
     pl.narrow = R < 65536;
@@ -1808,12 +1865,12 @@ int run_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters, i64*
                (const u32*)cross, P, R, pl.stride, pl.step, info, below);
     LAUNCH(K_PLAN, (zl_plan_kernel<1024>), dim3((unsigned)B), dim3(1024), info, below, pl.stride, winstart, winval,
            pl.max_win, pl.group_shift, (u32)(pl.cap / 8));
-    const u32 pairs = (u32)(pl.max_win / WINDOWS_PER_BLOCK);                 // max_win is even
-    const u32 pairs_inv = pairs > 1 ? (u32)((1ull << 32) / pairs) : 0xffffffffu;
-    const unsigned wgrid = (unsigned)((B * (i64)pairs + 7) / 8 * 8);
+    const u32 groups = (u32)(pl.max_win / WINDOWS_PER_BLOCK);
+    const u32 groups_inv = groups > 1 ? (u32)((1ull << 32) / groups) : 0xffffffffu;
+    const unsigned wgrid = (unsigned)((B * (i64)groups + 7) / 8 * 8);
 #define LAUNCH_WINDOW(NT_, CT_)                                                                          \
     LAUNCH(K_WINDOW, (zl_window_kernel<NT_, 16, CT_>), dim3(wgrid), dim3(NT_), ts, B, P, R, info,      \
-           (const CT_*)cross, pl.stride, winstart, winval, pl.max_win, pairs, pairs_inv, partial)
+           (const CT_*)cross, pl.stride, winstart, winval, pl.max_win, groups, groups_inv, partial)
     if (pl.cap == 16384) {
         if (pl.narrow) LAUNCH_WINDOW(1024, unsigned short); else LAUNCH_WINDOW(1024, u32);
     } else if (pl.cap == 8192) {
