@@ -568,11 +568,15 @@ __device__ __forceinline__ int zl_delta(const Smem& sm, const Rows& rw, u64 a, u
 // is <= its own; equal keys get equal values, so no run-end rule is needed.
 // The work is total + sum over buckets of size^2: a bucket with more than
 // BUCKET_LIMIT entries makes the caller fall back to the radix sort.
-// One exchange for four block-wide results: exclusive scans of c (u32) and s (u64),
-// the maximum of m and (WITH_X) the sum of x.  `red` holds 3*NT/64 u64 words.
-template <int NT, bool WITH_X>
-__device__ __forceinline__ void block_scan_pair(u32 c, u64 s, u32 m, u64 x, u64* red,
-                                                u32& cbase, u64& sbase, u32& mmax, u64& xsum)
+// One exchange for five block-wide results: exclusive scans of c (u32) and s (u64),
+// the maximum of m, (WITH_X) the sum of x and (WITH_U) the minimum over all threads of
+// local(i) - (sum of s over the waves before the thread's), where i is the inclusive
+// scan of s inside the thread's wave; local(i) == INT64_MAX stands for "none".
+// `red` holds 4*NT/64 u64 words; the caller must pass a barrier before it
+// writes them again.
+template <int NT, bool WITH_X, bool WITH_U, class Local>
+__device__ __forceinline__ void block_scan_pair(u32 c, u64 s, u32 m, u64 x, Local local, u64* red,
+                                                u32& cbase, u64& sbase, u32& mmax, u64& xsum, i64& umin)
 {
     constexpr int NW = NT / WAVE;
     const int lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x >> 6;
@@ -580,14 +584,18 @@ __device__ __forceinline__ void block_scan_pair(u32 c, u64 s, u32 m, u64 x, u64*
     const u64 si = wave_scan(s, OpAdd());
     m = wave_scan(m, OpMax());
     if (WITH_X) x = wave_scan(x, OpAdd());
+    i64 u = INT64_MAX;
+    if (WITH_U) u = wave_scan((i64)local(si), OpMin());
     if (lane == WAVE - 1) {
         red[wave] = si;
         red[NW + wave] = ((u64)m << 32) | ci;
         if (WITH_X) red[2 * NW + wave] = x;
+        if (WITH_U) red[3 * NW + wave] = (u64)u;
     }
     __syncthreads();
     u32 cb = 0, mm = 0;
-    u64 sb = 0, xx = 0;
+    u64 sb = 0, xx = 0, run = 0;
+    i64 um = INT64_MAX;
 #pragma unroll 2                       // more would hold all the partial results in registers at once
     for (int w = 0; w < NW; ++w) {
         const u64 xs = red[w], xc = red[NW + w];
@@ -595,12 +603,18 @@ __device__ __forceinline__ void block_scan_pair(u32 c, u64 s, u32 m, u64 x, u64*
         const u32 xm = (u32)(xc >> 32);
         mm = xm > mm ? xm : mm;
         if (WITH_X) xx += red[2 * NW + w];
+        if (WITH_U) {
+            const i64 uw = (i64)red[3 * NW + w];
+            const i64 cand = uw == INT64_MAX ? uw : uw - (i64)run;
+            um = cand < um ? cand : um;
+            run += xs;
+        }
     }
-    __syncthreads();
     cbase = cb + ci - c;
     sbase = sb + si - s;
     mmax = mm;
     xsum = xx;
+    umin = um;
 }
 
 template <int NT, int ITEMS, bool TABLE = true>
@@ -608,7 +622,7 @@ struct HotCfg {
     static constexpr int NW = NT / WAVE;
     static constexpr int CAP = NT * ITEMS;
     static constexpr int NB = 2 * NT;                     // value buckets; each thread scans two
-    static constexpr int RED_WORDS = 3 * NW + 8;
+    static constexpr int RED_WORDS = 4 * NW + 8;
     static constexpr int COARSE = 256;                    // coarse value bins behind an equalising bucket map
     static constexpr int PAD = 4;                         // record slots after the last one that a 4-wide read may touch
     static constexpr int BSUM_AT = CAP + PAD;             // bucket words follow the records
@@ -697,7 +711,8 @@ struct TableMap {
 // (wait, key) of P*key + W0 - S(key) over keys with a + key >= thr, W0 being the
 // block sum of `w0` (taken as 0 unless WITH_W0).
 // On entry the bucket words must be zero and a barrier must have passed since;
-// the record area may hold anything (it is overwritten).
+// the record area may hold anything (it is overwritten).  On return some threads
+// may still be reading LDS: the caller passes a barrier before writing it again.
 // Returns false (nothing computed) if some bucket is over the limit.
 template <int NT, int ITEMS, bool WITH_W0, class Map>
 __device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key)[ITEMS], const u32 (&dl)[ITEMS],
@@ -721,32 +736,40 @@ __device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key
     const u64 h0 = bsum[2 * tid], h1 = bsum[2 * tid + 1];
     const u32 c0 = (u32)(h0 >> SUM_BITS), c1 = (u32)(h1 >> SUM_BITS);
     const u64 s0 = h0 & SUM_MASK, s1 = h1 & SUM_MASK;
+    constexpr bool PRUNE = Map::HAS_BOUNDS;
+    constexpr u32 DROPPED = 0x80000000u;
+    u32* live_count = (u32*)(sm.red + H::RED_WORDS - 1);
+    if (PRUNE && tid == 0) *live_count = 0;
+    // Most buckets cannot hold the minimum.  With E = the sum of deltas up to the end
+    // of bucket b and lo <= keys of b <= hi: the bucket's largest key kmax is a
+    // candidate with wait P*kmax + W0 - E <= P*hi + W0 - E =: ub(b) (if the whole
+    // bucket is admissible), and every key of b waits at least P*lo + W0 - E =: lb(b).
+    // Buckets with lb(b) above the smallest ub are dropped; the others get room in a
+    // compact list (in any order) and only their entries are scattered and evaluated.
+    u32 lo0 = 0, hi0 = 0, lo1 = 0, hi1 = 0;
+    const u64 need = thr > a ? thr - a : 0;                           // keys >= need are admissible
+    if (PRUNE) {
+        bucket.bounds(2 * tid, lo0, hi0);
+        bucket.bounds(2 * tid + 1, lo1, hi1);
+    }
+    // smallest P*hi - E over the thread's admissible buckets, E counted from the wave's first bucket
+    auto local_bound = [&](u64 incl) {
+        i64 u = INT64_MAX;
+        if (c0 && lo0 >= need) u = (i64)(P * (u64)hi0 - (incl - s1));
+        if (c1 && lo1 >= need) { const i64 u1 = (i64)(P * (u64)hi1 - incl); u = u1 < u ? u1 : u; }
+        return u;
+    };
     u32 cbase, biggest;
     u64 sbase, W0;
-    block_scan_pair<NT, WITH_W0>(c0 + c1, s0 + s1, c0 > c1 ? c0 : c1, w0, sm.red, cbase, sbase, biggest, W0);
+    i64 ubmin;
+    block_scan_pair<NT, WITH_W0, PRUNE>(c0 + c1, s0 + s1, c0 > c1 ? c0 : c1, w0, local_bound, sm.red,
+                                        cbase, sbase, biggest, W0, ubmin);
     if (biggest > BUCKET_LIMIT) return false;
     u64 bw = U64_MAX;
     u32 bk = 0xffffffffu;
-    if constexpr (Map::HAS_BOUNDS) {
-        // Most buckets cannot hold the minimum.  With E = the sum of deltas up to the end
-        // of bucket b and lo <= keys of b <= hi: the bucket's largest key kmax is a
-        // candidate with wait P*kmax + W0 - E <= P*hi + W0 - E =: ub(b) (if the whole
-        // bucket is admissible), and every key of b waits at least P*lo + W0 - E =: lb(b).
-        // Buckets with lb(b) above the smallest ub are dropped; the others get room in a
-        // compact list (in any order) and only their entries are scattered and evaluated.
-        constexpr u32 DROPPED = 0x80000000u;
-        u32* live_count = (u32*)(sm.red + H::RED_WORDS - 1);
-        if (tid == 0) *live_count = 0;
-        u32 lo0, hi0, lo1, hi1;
-        bucket.bounds(2 * tid, lo0, hi0);
-        bucket.bounds(2 * tid + 1, lo1, hi1);
-        const u64 need = thr > a ? thr - a : 0;                       // keys >= need are admissible
+    if constexpr (PRUNE) {
         const u64 e0 = sbase + s0, e1 = e0 + s1;
-        const i64 ub0 = (i64)(P * (u64)hi0 + W0 - e0), ub1 = (i64)(P * (u64)hi1 + W0 - e1);
-        i64 ub = INT64_MAX;
-        if (c0 && lo0 >= need) ub = ub0;
-        if (c1 && lo1 >= need && ub1 < ub) ub = ub1;
-        const i64 ubmin = block_reduce<i64, NT>(ub, (i64*)sm.red, OpMin());
+        const i64 ub0 = (i64)(P * (u64)hi0 - e0), ub1 = (i64)(P * (u64)hi1 - e1);       // both without W0, like ubmin
         const bool live0 = c0 && ub0 - (i64)(P * (u64)(hi0 - lo0)) <= ubmin;
         const bool live1 = c1 && ub1 - (i64)(P * (u64)(hi1 - lo1)) <= ubmin;
         u32 at0 = DROPPED, at1 = DROPPED;
@@ -837,8 +860,7 @@ __device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key
         const u32 ok = (u32)red[NW + w];
         if (ow < bw || (ow == bw && ok < bk)) { bw = ow; bk = ok; }
     }
-    __syncthreads();
-    best_wait = bw;
+    best_wait = bw;                       // the caller passes a barrier before LDS is written again
     best_key = bk;
     return true;
 }
