@@ -627,7 +627,7 @@ struct HotCfg {
     static constexpr int PAD = 4;                         // record slots after the last one that a 4-wide read may touch
     static constexpr int BSUM_AT = CAP + PAD;             // bucket words follow the records
     static constexpr size_t BYTES = (size_t)BSUM_AT * 8 + (size_t)NB * 8 + (size_t)RED_WORDS * 8 + (size_t)NB * 4 +
-                                    (TABLE ? (size_t)COARSE * 8 : 0);   // the coarse table is the last area
+                                    (TABLE ? (size_t)COARSE * 16 : 0);  // the coarse tables are the last area
 };
 // One LDS word per bucket holds its entry count (upper bits) and the sum of its
 // deltas (lower SUM_BITS bits: at most 16384 deltas below 2^32 each).
@@ -693,16 +693,45 @@ __device__ __forceinline__ LinearMap linear_map(u32 span, u32 nb, u32 scale, u64
 // hold about the same number of keys even where the density of keys varies (a
 // whole instance: many workers early in the value range, few stragglers late).
 // tab[c] = first bucket of coarse bin c | (buckets of bin c scaled by 2^(32-cshift)) << 32.
+template <bool BOUNDS>       // whether the caller wants to drop buckets by their bounds
 struct TableMap {
-    const u64* tab;
+    const u64* tab;     // 256 entries, followed by 256 of: buckets of the bin << 52 | floor(2^52 / multiplier)
     u32 cshift, cmask;
-    static constexpr bool HAS_BOUNDS = false;
-    __device__ __forceinline__ void bounds(u32, u32& lo, u32& hi) const { lo = 0; hi = 0xffffffffu; }
+    u32 span;           // largest key of sorted rows
+    static constexpr bool HAS_BOUNDS = BOUNDS;
     __device__ __forceinline__ u32 coarse(u32 key) const { const u32 c = key >> cshift; return c < 255u ? c : 255u; }
     __device__ __forceinline__ u32 operator()(u32 key) const
     {
         const u64 e = tab[coarse(key)];
         return (u32)e + (u32)(((u64)(key & cmask) * (e >> 32)) >> 32);
+    }
+    // lo <= every key of bucket b <= hi.  The bins that reach bucket b are consecutive:
+    // the lower bound comes from the first of them, the upper bound from the last; inside
+    // a bin the bucket is linear in the key's low bits, as for LinearMap.
+    __device__ __forceinline__ void bounds(u32 b, u32& lo, u32& hi) const
+    {
+        const u64* inv = tab + 256;
+        int l = 0, h = 255;
+        while (l < h) {                                    // last bin whose first bucket is <= b
+            const int m = (l + h + 1) >> 1;
+            if ((u32)tab[m] <= b) l = m; else h = m - 1;
+        }
+        const int chi = l;
+        l = 0; h = chi;
+        while (l < h) {                                    // first bin whose last bucket is >= b
+            const int m = (l + h) >> 1;
+            if ((u32)tab[m] + (u32)(inv[m] >> 52) > b) h = m; else l = m + 1;
+        }
+        const int clo = l;
+        const u64 ilo = inv[clo] & ((1ull << 52) - 1), ihi = inv[chi] & ((1ull << 52) - 1);
+        const u32 first_lo = (u32)tab[clo], first_hi = (u32)tab[chi];
+        const u32 rlo = b >= first_lo ? b - first_lo : 0u, rhi = b >= first_hi ? b - first_hi : 0u;   // below 2^11
+        u64 xl = ((u64)rlo * ilo) >> 20, xh = (((u64)(rhi + 1) * ihi) >> 20) + 2;
+        xl = xl > cmask ? cmask : xl;
+        xh = xh > cmask ? cmask : xh;
+        const u64 kh = ((u64)chi << cshift) + xh, kl = ((u64)clo << cshift) + xl;
+        hi = kh > span ? span : (u32)kh;
+        lo = kl > hi ? hi : (u32)kl;
     }
 };
 
@@ -1188,10 +1217,11 @@ __global__ __launch_bounds__(NT) void zl_instance_kernel(
     u32* coarse = sm.cnt;                                   // free until the bucket scan
     u64* tab = (u64*)(sm.cnt + H::NB);
     const int bl = bit_length(range);
-    TableMap bucket;
+    TableMap<(ITEMS >= 8)> bucket;                          // small instances: finding the bounds costs more than it saves
     bucket.tab = tab;
     bucket.cshift = bl > 8 ? (u32)(bl - 8) : 0u;
     bucket.cmask = (1u << bucket.cshift) - 1u;
+    bucket.span = (u32)range;
     constexpr int CPT = H::COARSE / NT > 1 ? H::COARSE / NT : 1;      // coarse bins per thread
     for (int c = tid; c < H::COARSE; c += NT) coarse[c] = 0;
     __syncthreads();
@@ -1218,6 +1248,7 @@ __global__ __launch_bounds__(NT) void zl_instance_kernel(
                 if (bucket.cshift < 32 && nbk > (1u << bucket.cshift)) nbk = 1u << bucket.cshift;
                 const u64 mult = bucket.cshift ? ((u64)nbk << (32 - bucket.cshift)) - 1 : 0ull;
                 tab[tid * CPT + i] = (u64)(first < (u32)H::NB ? first : (u32)H::NB - 1) | (mult << 32);
+                tab[H::COARSE + tid * CPT + i] = ((u64)nbk << 52) | (mult ? (1ull << 52) / mult : 0ull);
             }
             below_c += c[i];
         }
