@@ -568,51 +568,44 @@ __device__ __forceinline__ int zl_delta(const Smem& sm, const Rows& rw, u64 a, u
 // is <= its own; equal keys get equal values, so no run-end rule is needed.
 // The work is total + sum over buckets of size^2: a bucket with more than
 // BUCKET_LIMIT entries makes the caller fall back to the radix sort.
-// One exchange for five block-wide results: exclusive scans of c (u32) and s (u64),
-// the maximum of m, (WITH_X) the sum of x and (WITH_U) the minimum over all threads of
-// local(i) - (sum of s over the waves before the thread's), where i is the inclusive
-// scan of s inside the thread's wave; local(i) == INT64_MAX stands for "none".
-// `red` holds 4*NT/64 u64 words; the caller must pass a barrier before it
+// One exchange for three block-wide results: the exclusive scan of h (a packed
+// count and sum: the two fields must not overflow into each other), (WITH_X) the
+// sum of x and (WITH_U) the minimum over all threads of local(i) - (sum of h's low
+// SUM_BITS over the waves before the thread's), where i is the inclusive scan of
+// h inside the thread's wave; local(i) == INT64_MAX stands for "none".
+// `red` holds 3*NT/64 u64 words; the caller must pass a barrier before it
 // writes them again.
 template <int NT, bool WITH_X, bool WITH_U, class Local>
-__device__ __forceinline__ void block_scan_pair(u32 c, u64 s, u32 m, u64 x, Local local, u64* red,
-                                                u32& cbase, u64& sbase, u32& mmax, u64& xsum, i64& umin)
+__device__ __forceinline__ void block_scan_pair(u64 h, u64 x, Local local, u64* red, u64 low_mask,
+                                                u64& hbase, u64& xsum, i64& umin)
 {
     constexpr int NW = NT / WAVE;
     const int lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x >> 6;
-    const u32 ci = wave_scan(c, OpAdd());
-    const u64 si = wave_scan(s, OpAdd());
-    m = wave_scan(m, OpMax());
+    const u64 hi = wave_scan(h, OpAdd());
     if (WITH_X) x = wave_scan(x, OpAdd());
     i64 u = INT64_MAX;
-    if (WITH_U) u = wave_scan((i64)local(si), OpMin());
+    if (WITH_U) u = wave_scan((i64)local(hi), OpMin());
     if (lane == WAVE - 1) {
-        red[wave] = si;
-        red[NW + wave] = ((u64)m << 32) | ci;
-        if (WITH_X) red[2 * NW + wave] = x;
-        if (WITH_U) red[3 * NW + wave] = (u64)u;
+        red[wave] = hi;
+        if (WITH_X) red[NW + wave] = x;
+        if (WITH_U) red[2 * NW + wave] = (u64)u;
     }
     __syncthreads();
-    u32 cb = 0, mm = 0;
-    u64 sb = 0, xx = 0, run = 0;
+    u64 hb = 0, xx = 0, run = 0;
     i64 um = INT64_MAX;
 #pragma unroll 2                       // more would hold all the partial results in registers at once
     for (int w = 0; w < NW; ++w) {
-        const u64 xs = red[w], xc = red[NW + w];
-        if (w < wave) { sb += xs; cb += (u32)xc; }
-        const u32 xm = (u32)(xc >> 32);
-        mm = xm > mm ? xm : mm;
-        if (WITH_X) xx += red[2 * NW + w];
+        const u64 xh = red[w];
+        if (w < wave) hb += xh;
+        if (WITH_X) xx += red[NW + w];
         if (WITH_U) {
-            const i64 uw = (i64)red[3 * NW + w];
+            const i64 uw = (i64)red[2 * NW + w];
             const i64 cand = uw == INT64_MAX ? uw : uw - (i64)run;
             um = cand < um ? cand : um;
-            run += xs;
+            run += xh & low_mask;
         }
     }
-    cbase = cb + ci - c;
-    sbase = sb + si - s;
-    mmax = mm;
+    hbase = hb + hi - h;
     xsum = xx;
     umin = um;
 }
@@ -672,6 +665,18 @@ struct LinearMap {
         const u64 h = (((u64)(b + 1) * inv52) >> 20) + 2;
         hi = (b >= top || h > span) ? span : (u32)h;
         lo = l > hi ? hi : (u32)l;
+    }
+    // The same for buckets b and b + 1 with one product: floor((b + 1) * x) >= floor(b * x) +
+    // floor(x), and a bucket is less than floor(x) + 2 wide (x = inv52 / 2^20).
+    __device__ __forceinline__ void bounds_pair(u32 b, u32& lo0, u32& hi0, u32& lo1, u32& hi1) const
+    {
+        const u64 step = inv52 >> 20;
+        const u64 l0 = ((u64)b * inv52) >> 20, l1 = l0 + step;
+        const u64 h0 = l0 + step + 4, h1 = l1 + step + 4;
+        hi0 = h0 > span ? span : (u32)h0;
+        hi1 = (b + 1 >= top || h1 > span) ? span : (u32)h1;
+        lo0 = l0 > hi0 ? hi0 : (u32)l0;
+        lo1 = l1 > hi1 ? hi1 : (u32)l1;
     }
 };
 __device__ __forceinline__ u32 linear_scale(u64 span, u32 nb)
@@ -733,6 +738,11 @@ struct TableMap {
         hi = kh > span ? span : (u32)kh;
         lo = kl > hi ? hi : (u32)kl;
     }
+    __device__ __forceinline__ void bounds_pair(u32 b, u32& lo0, u32& hi0, u32& lo1, u32& hi1) const
+    {
+        bounds(b, lo0, hi0);
+        bounds(b + 1, lo1, hi1);
+    }
 };
 
 // The records of a window, held ITEMS per thread in registers (item j of thread t
@@ -745,7 +755,7 @@ struct TableMap {
 // Returns false (nothing computed) if some bucket is over the limit.
 template <int NT, int ITEMS, bool WITH_W0, class Map>
 __device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key)[ITEMS], const u32 (&dl)[ITEMS],
-                                                 const Map bucket, int total, u64 a, u64 thr, u64 P, u64 w0,
+                                                 const Map bucket, int total, u64 a, u64 thr, u32 P, u64 w0,
                                                  u64& best_wait, u32& best_key)
 {
     using H = HotCfg<NT, ITEMS>;
@@ -753,6 +763,9 @@ __device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key
     u64* bsum = sm.recs + H::BSUM_AT;
     u32* cnt = sm.cnt;
     const int tid = threadIdx.x;
+    u32* live_count = (u32*)(sm.red + H::RED_WORDS - 1);              // entries of the compact list
+    u32* deep = live_count + 1;                                       // set if some bucket is over the limit
+    if (tid == 0) { *live_count = 0; *deep = 0; }
     // zl_sort, step 1: per bucket, entry count and sum of deltas in one word
 #pragma unroll
     for (int j = 0; j < ITEMS; ++j)
@@ -767,8 +780,6 @@ __device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key
     const u64 s0 = h0 & SUM_MASK, s1 = h1 & SUM_MASK;
     constexpr bool PRUNE = Map::HAS_BOUNDS;
     constexpr u32 DROPPED = 0x80000000u;
-    u32* live_count = (u32*)(sm.red + H::RED_WORDS - 1);
-    if (PRUNE && tid == 0) *live_count = 0;
     // Most buckets cannot hold the minimum.  With E = the sum of deltas up to the end
     // of bucket b and lo <= keys of b <= hi: the bucket's largest key kmax is a
     // candidate with wait P*kmax + W0 - E <= P*hi + W0 - E =: ub(b) (if the whole
@@ -777,30 +788,29 @@ __device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key
     // compact list (in any order) and only their entries are scattered and evaluated.
     u32 lo0 = 0, hi0 = 0, lo1 = 0, hi1 = 0;
     const u64 need = thr > a ? thr - a : 0;                           // keys >= need are admissible
-    if (PRUNE) {
-        bucket.bounds(2 * tid, lo0, hi0);
-        bucket.bounds(2 * tid + 1, lo1, hi1);
-    }
+    if (PRUNE) bucket.bounds_pair(2 * tid, lo0, hi0, lo1, hi1);
     // smallest P*hi - E over the thread's admissible buckets, E counted from the wave's first bucket
     auto local_bound = [&](u64 incl) {
+        const u64 e1 = incl & SUM_MASK;
         i64 u = INT64_MAX;
-        if (c0 && lo0 >= need) u = (i64)(P * (u64)hi0 - (incl - s1));
-        if (c1 && lo1 >= need) { const i64 u1 = (i64)(P * (u64)hi1 - incl); u = u1 < u ? u1 : u; }
+        if (c0 && lo0 >= need) u = (i64)((u64)P * hi0 - (e1 - s1));
+        if (c1 && lo1 >= need) { const i64 u1 = (i64)((u64)P * hi1 - e1); u = u1 < u ? u1 : u; }
         return u;
     };
-    u32 cbase, biggest;
-    u64 sbase, W0;
+    u64 hbase, W0;
     i64 ubmin;
-    block_scan_pair<NT, WITH_W0, PRUNE>(c0 + c1, s0 + s1, c0 > c1 ? c0 : c1, w0, local_bound, sm.red,
-                                        cbase, sbase, biggest, W0, ubmin);
-    if (biggest > BUCKET_LIMIT) return false;
+    if ((c0 > c1 ? c0 : c1) > BUCKET_LIMIT) *deep = 1;
+    block_scan_pair<NT, WITH_W0, PRUNE>(h0 + h1, w0, local_bound, sm.red, SUM_MASK, hbase, W0, ubmin);
+    if (*deep) return false;
+    const u32 cbase = (u32)(hbase >> SUM_BITS);
+    const u64 sbase = hbase & SUM_MASK;
     u64 bw = U64_MAX;
     u32 bk = 0xffffffffu;
     if constexpr (PRUNE) {
         const u64 e0 = sbase + s0, e1 = e0 + s1;
-        const i64 ub0 = (i64)(P * (u64)hi0 - e0), ub1 = (i64)(P * (u64)hi1 - e1);       // both without W0, like ubmin
-        const bool live0 = c0 && ub0 - (i64)(P * (u64)(hi0 - lo0)) <= ubmin;
-        const bool live1 = c1 && ub1 - (i64)(P * (u64)(hi1 - lo1)) <= ubmin;
+        const i64 ub0 = (i64)((u64)P * hi0 - e0), ub1 = (i64)((u64)P * hi1 - e1);       // both without W0, like ubmin
+        const bool live0 = c0 && ub0 - (i64)((u64)P * (hi0 - lo0)) <= ubmin;
+        const bool live1 = c1 && ub1 - (i64)((u64)P * (hi1 - lo1)) <= ubmin;
         u32 at0 = DROPPED, at1 = DROPPED;
         if (live0) at0 = atomicAdd(live_count, c0);
         if (live1) at1 = atomicAdd(live_count, c1);
@@ -831,7 +841,7 @@ __device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key
                 S += ((u32)r <= k) ? r >> 32 : 0ull;
             }
             if ((u64)k >= need) {
-                const u64 w = P * (u64)k + W0 - S;
+                const u64 w = (u64)P * k + W0 - S;
                 if (w < bw || (w == bw && k < bk)) { bw = w; bk = k; }
             }
         }
@@ -869,7 +879,7 @@ __device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key
             S += ((u32)r3 <= k) ? r3 >> 32 : 0ull;
         }
         if (a + k >= thr) {
-            const u64 w = P * (u64)k + W0 - S;
+            const u64 w = (u64)P * k + W0 - S;
             if (w < bw || (w == bw && k < bk)) { bw = w; bk = k; }
         }
     }
@@ -1256,7 +1266,7 @@ __global__ __launch_bounds__(NT) void zl_instance_kernel(
     __syncthreads();
     u64 best_wait;
     u32 bkey;
-    if (!zl_bucket_finish<NT, ITEMS, false>(sm, key, dl, bucket, n, 0ull, thr, (u64)P, 0ull, best_wait, bkey)) {
+    if (!zl_bucket_finish<NT, ITEMS, false>(sm, key, dl, bucket, n, 0ull, thr, (u32)P, 0ull, best_wait, bkey)) {
         if (tid == 0) wait[b] = DEFERRED;      // clustered values: left to zl_instance_general_kernel
         return;
     }
@@ -1576,7 +1586,7 @@ __device__ __forceinline__ void window_search(const Smem& sm, const Rows& rw, co
                 if (zl_bucket_finish<NT, ITEMS, true>(sm, key, dl,
                                                       linear_map((u32)(wv.Elast - wv.A), H::NB, wv.scale ? wv.scale : 1u,
                                                                  wv.inv52),
-                                                      total, wv.A, ii.thr, (u64)rw.P, w0, r.wait, bkey))
+                                                      total, wv.A, ii.thr, (u32)rw.P, w0, r.wait, bkey))
                     r.brel = wv.A + bkey;
                 else
                     defer = true;
