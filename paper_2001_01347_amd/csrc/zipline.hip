@@ -809,8 +809,9 @@ __device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key
     if constexpr (PRUNE) {
         const u64 e0 = sbase + s0, e1 = e0 + s1;
         const i64 ub0 = (i64)((u64)P * hi0 - e0), ub1 = (i64)((u64)P * hi1 - e1);       // both without W0, like ubmin
-        const bool live0 = c0 && ub0 - (i64)((u64)P * (hi0 - lo0)) <= ubmin;
-        const bool live1 = c1 && ub1 - (i64)((u64)P * (hi1 - lo1)) <= ubmin;
+        // (a bucket whose keys are all below `need` holds no candidate at all)
+        const bool live0 = c0 && hi0 >= need && ub0 - (i64)((u64)P * (hi0 - lo0)) <= ubmin;
+        const bool live1 = c1 && hi1 >= need && ub1 - (i64)((u64)P * (hi1 - lo1)) <= ubmin;
         u32 at0 = DROPPED, at1 = DROPPED;
         if (live0) at0 = atomicAdd(live_count, c0);
         if (live1) at1 = atomicAdd(live_count, c1);
