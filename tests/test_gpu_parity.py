@@ -96,6 +96,25 @@ def test_degenerate_values(zl, oracle):
     assert_same(zl, oracle, t, "tie at the end")
 
 
+@pytest.mark.parametrize("P,R", [(8, 2048), (4, 1024), (16, 4096), (600, 64)])
+def test_equal_minima_far_apart(zl, oracle, P, R):
+    # workers of one period T, evenly staggered: after the first period every arrival gives
+    # the same wait g*P*(P-1)/2, so the minimum is attained in every bucket and every window;
+    # worker 0 joins k periods late, which makes all earlier candidates inadmissible.
+    # The earliest admissible minimum must win: the barrier is worker 0's first timestamp.
+    g, k = 7, R // 3
+    T = P * g
+    i = np.arange(R, dtype=np.int64)
+    t = np.stack([p * g + i * T for p in range(P)])
+    t[0] = (i + k) * T
+    ts = np.stack([t, t + 3, t * 1000 + EPOCH])          # the last one: spread >= 2^32 for the larger shapes
+    bar, it, w, st = gpu_run(zl, ts)
+    assert (st == 0).all()
+    assert list(bar) == [k * T, k * T + 3, k * T * 1000 + EPOCH]
+    assert list(w[:2]) == [g * P * (P - 1) // 2] * 2 and int(w[2]) == 1000 * g * P * (P - 1) // 2
+    assert_same(zl, oracle, ts, f"staggered P={P} R={R}")
+
+
 def test_wide_value_ranges(zl, oracle):
     # per-instance spread of 2^32 units or more (e.g. nanosecond timestamps): deltas need 64 bits
     rng = np.random.default_rng(8)
