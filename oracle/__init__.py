@@ -16,18 +16,21 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "zipline_oracle.c")
+_SRC_RANGE = os.path.join(_HERE, "zipline_range_oracle.c")      # the paper's formal objective max(Z) - min(Z)
 _LIB = os.path.join(_HERE, "libzipline_oracle.so")
 _lib = None
 
 METHODS = {"sweep": 0, "definition": 1, "naive": 2}
+RANGE_METHODS = {"sweep": 0, "definition": 1, "naive": 2, "zipline": 3}
 
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (host only). Returns the library path."""
-    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < max(os.path.getmtime(_SRC),
+                                                                        os.path.getmtime(_SRC_RANGE))
     if force or stale:
         cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-Wall", "-Wextra",
-               _SRC, "-o", _LIB]
+               _SRC, _SRC_RANGE, "-o", _LIB]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -43,8 +46,20 @@ def _load():
         lib.zl_oracle_batch.argtypes = [i64p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
                                         i64p, i32p, i64p, i32p, ctypes.c_int32, ctypes.c_int32,
                                         i32p]
+        lib.zl_range_batch.restype = ctypes.c_int
+        lib.zl_range_batch.argtypes = lib.zl_oracle_batch.argtypes
         _lib = lib
     return _lib
+
+
+def zipline_range(ts, method: str = "sweep", threads: int = 0):
+    """The search under the paper's formal objective d_Z = max(Z) - min(Z) (Section III).
+
+    Same conventions as :func:`zipline`; the third result is ``dmin[B]`` instead of
+    the summed wait.  Methods: "sweep", "definition", "naive", "zipline" (Algorithm 2
+    as the paper states it, looking through Z for its minimum).
+    """
+    return _run(ts, "zl_range_batch", RANGE_METHODS[method], threads)
 
 
 def zipline(ts, method: str = "sweep", threads: int = 0):
@@ -54,6 +69,10 @@ def zipline(ts, method: str = "sweep", threads: int = 0):
     threads_used)``.  ``rc`` is 0 for a valid instance and 1 where a row was
     not non-decreasing (that instance's outputs are left at zero).
     """
+    return _run(ts, "zl_oracle_batch", METHODS[method], threads)
+
+
+def _run(ts, entry: str, method: int, threads: int):
     a = np.ascontiguousarray(np.asarray(ts), dtype=np.int64)
     if a.ndim == 2:
         a = a[None]
@@ -70,10 +89,10 @@ def zipline(ts, method: str = "sweep", threads: int = 0):
     used = ctypes.c_int32(0)
     i64p = ctypes.POINTER(ctypes.c_int64)
     i32p = ctypes.POINTER(ctypes.c_int32)
-    r = lib.zl_oracle_batch(a.ctypes.data_as(i64p), B, P, R,
+    r = getattr(lib, entry)(a.ctypes.data_as(i64p), B, P, R,
                             barrier.ctypes.data_as(i64p), iters.ctypes.data_as(i32p),
                             wait.ctypes.data_as(i64p), rc.ctypes.data_as(i32p),
-                            METHODS[method], int(threads), ctypes.byref(used))
+                            int(method), int(threads), ctypes.byref(used))
     if r == 2:
         raise ValueError("oracle rejected its arguments")
     return barrier, iters, wait, rc, int(used.value)
