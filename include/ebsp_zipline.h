@@ -80,6 +80,30 @@ int ebsp_zipline_batch(const int64_t* ts, int64_t B, int32_t P, int32_t R,
                        void* stream);
 
 /*
+ * The same search under the paper's formal objective (Section III "The
+ * Problem": d_Z = max(Z) - min(Z), the waiting time of the fastest worker;
+ * Section IV, Algorithm 2, which sweeps the merged timestamps with a set Z of
+ * every worker's newest one; Fig. 3 caption for ties).  For a barrier c the
+ * tightest Z holds every worker's latest timestamp <= c, so
+ *
+ *     dmin    = min_c ( c - min_p last_p(c) )   over timestamps c >= max_p t[p][0],
+ *     barrier = the smallest c that attains it,
+ *     iters[p]= #{ i : t[p][i] <= barrier }.
+ *
+ * Arguments, layouts, ownership and return codes as for ebsp_zipline_batch,
+ * with dmin[B] (int64, device, >= 0) in place of wait[B] and a workspace of at
+ * least ebsp_zipline_range_workspace_bytes() bytes.  This build handles
+ * instances whose value spread (max t - min t) is below 2^32 - 1 and whose
+ * windows fit one workgroup; any other instance gets EBSP_STATUS_UNSUPPORTED in
+ * status[b] and unspecified outputs (other instances are unaffected).
+ */
+size_t ebsp_zipline_range_workspace_bytes(int64_t B, int32_t P, int32_t R);
+int ebsp_zipline_range_batch(const int64_t* ts, int64_t B, int32_t P, int32_t R,
+                             int64_t* barrier, int32_t* iters, int64_t* dmin,
+                             int32_t* status, void* workspace, size_t workspace_bytes,
+                             void* stream);
+
+/*
  * How a shape is handled (for benchmarks' byte models; HOST array of 4):
  * info[0] = 1 if instances are cut into windows (0: one workgroup each),
  * info[1] = records per window workgroup, info[2] = fine bins per instance,

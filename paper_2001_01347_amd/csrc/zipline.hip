@@ -101,7 +101,8 @@ __device__ __forceinline__ T dpp_take(T fill, T v)
     }
 }
 constexpr int DPP_ROW_SHR1 = 0x111, DPP_ROW_SHR2 = 0x112, DPP_ROW_SHR4 = 0x114, DPP_ROW_SHR8 = 0x118,
-              DPP_ROW_BCAST15 = 0x142, DPP_ROW_BCAST31 = 0x143;
+              DPP_ROW_BCAST15 = 0x142, DPP_ROW_BCAST31 = 0x143,
+              DPP_WAVE_SHR1 = 0x138;      // every lane takes the value of the lane before it (across rows)
 
 struct OpMin {
     template <class T> __device__ T operator()(T a, T b) const { return a < b ? a : b; }
@@ -1727,6 +1728,349 @@ __global__ __launch_bounds__(NT) void zl_window_general_kernel(
     }
 }
 
+// ---------------------------------------------------------------------------
+// The paper's formal objective (Section III): d_Z = max(Z) - min(Z).  For a barrier
+// c the tightest Z holds every worker's latest timestamp <= c, so
+// d(c) = c - min_p last_p(c); the search returns the first minimum over the
+// timestamps c >= max_p t[p][0] (Algorithm 2 evaluates exactly these states of Z).
+//
+// One value interval [a, el] of the rows in `rw` (all of an instance, or one window
+// of the multi-window path) is handled by one workgroup: the entries are gathered as
+// (key = value - a, next = the same worker's next value - a, or NEVER) plus, for the
+// first entry of a row inside the interval, gone = a - the worker's last value
+// before the interval (NEVER if the worker has none: it has not finished an
+// iteration yet), and sorted by key (zl_sort).  At sorted position k:
+//   * a worker whose first entry in the interval lies at a position > k (or that has
+//     no entry in it) still stands at its value before the interval: the largest
+//     `gone` over those workers, G(k), is a suffix maximum, and d = key_k + G(k);
+//   * if there is no such worker, min(Z) is the first entry j whose successor has
+//     not arrived yet (next_j > key_k): with M(j) the prefix maximum of next,
+//     j = #{ j' : M(j') <= key_k } (M is monotone: a binary search), d = key_k - key_j.
+// Entries equal to key_k at later positions are treated as not yet arrived; that can
+// only raise d at position k, and the last position of the run of equal keys sees
+// them all, so the minimum over all positions is the minimum over the timestamps.
+// Needs a value spread below 2^32 - 1 (keys and the NEVER mark share 32 bits).
+constexpr u32 NEVER = 0xffffffffu;
+
+template <class T, int NT, class Op>
+__device__ __forceinline__ T block_excl_scan_op(T v, T* red, Op op)      // `red` holds NT/64 T's
+{
+    constexpr int NW = NT / WAVE;
+    constexpr T id = Op::template identity<T>();
+    const int lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x >> 6;
+    const T inc = wave_scan(v, op);
+    if (lane == WAVE - 1) red[wave] = inc;
+    T before = dpp_take<DPP_WAVE_SHR1, 0xf>(id, inc);       // exclusive inside the wave
+    if (lane == 0) before = id;
+    __syncthreads();
+    T base = id;
+#pragma unroll 4
+    for (int w = 0; w < NW; ++w)
+        if (w < wave) base = op(base, red[w]);
+    __syncthreads();
+    return op(base, before);
+}
+
+// Gather for the range objective; returns the number of entries (nothing useful is
+// stored if it exceeds `cap`).  absent = the largest `gone` over the workers without
+// an entry in the interval (this thread's share).
+template <int NT>
+__device__ __forceinline__ int zl_range_gather(const Smem& sm, const Rows& rw, u64 a, u64 el, bool lx, bool rx,
+                                               int cap, u32& absent, int& bad)
+{
+    const int tid = threadIdx.x;
+    u32* rowoff = sm.cnt;
+    u32* rowlo = sm.cnt + NT;
+    int total = 0;
+    for (int p0 = 0; p0 < rw.P; p0 += NT) {
+        const int p = p0 + tid;
+        u32 lo = 0, hi = 0;
+        if (p < rw.P) {
+            sub_range(rw, p, a, el, lx, rx, lo, hi);
+            if (lo == hi) {
+                const u32 gone = lo > 0 ? (u32)(a - rw.rel(p, lo - 1)) : NEVER;
+                absent = gone > absent ? gone : absent;
+            }
+        }
+        u32 chunk;
+        const u32 off = block_excl_scan<u32, NT>(hi - lo, (u32*)sm.red, chunk);
+        rowoff[tid] = off;
+        rowlo[tid] = lo;
+        __syncthreads();
+        const int room = cap - total;
+        const int take = (int)chunk < room ? (int)chunk : room;
+        const int nrows = (rw.P - p0) < NT ? (rw.P - p0) : NT;
+        for (int e = tid; e < take; e += NT) {
+            int l = 0, h = nrows;                 // the last row r with rowoff[r] <= e
+            while (h - l > 1) {
+                const int m = (l + h) >> 1;
+                if (rowoff[m] <= (u32)e) l = m; else h = m;
+            }
+            const u32 i = rowlo[l] + ((u32)e - rowoff[l]);
+            const i64* src = rw.inst + (size_t)(p0 + l) * rw.R + i;
+            const i64 cur = src[0];
+            const u64 rel = (u64)cur - rw.base;
+            u32 next = NEVER, gone = 0;
+            if (i + 1 < (u32)rw.R) {
+                const i64 nxt = src[1];
+                bad |= (nxt < cur);
+                next = (u32)((u64)nxt - rw.base - a);
+            }
+            if (i == rowlo[l]) {                  // the row's first entry inside the interval
+                gone = NEVER;
+                if (i > 0) {
+                    const i64 prv = src[-1];
+                    bad |= (cur < prv);
+                    gone = (u32)(a - ((u64)prv - rw.base));
+                }
+            }
+            const int slot = phys(total + e);
+            sm.recs[slot] = (u64)(u32)(rel - a) | ((u64)next << 32);
+            sm.dhi[slot] = gone;
+        }
+        total += (int)chunk;
+        __syncthreads();
+    }
+    return total;
+}
+
+// The search over the sorted entries [0, total); thread t owns positions
+// [t*items, (t+1)*items).  Returns the first minimum (d, key); d == U64_MAX: none.
+template <int NT>
+__device__ __forceinline__ void zl_range_scan_argmin(const Smem& sm, int items, int total, u64 a, u64 thr,
+                                                     u32 absent_all, u64& best_d, u32& best_key)
+{
+    u64* recs = sm.recs;
+    u32* gone = sm.dhi;
+    u32* mirror = sm.cnt;                        // NT words
+    const int tid = threadIdx.x;
+    const int q0 = tid * items < total ? tid * items : total;
+    const int qe = q0 + items < total ? q0 + items : total;
+    // M: prefix maximum of `next`, written over `next`
+    u32 mine = 0;
+    for (int q = q0; q < qe; ++q) { const u32 nx = (u32)(recs[phys(q)] >> 32); mine = nx > mine ? nx : mine; }
+    u32 run = block_excl_scan_op<u32, NT>(mine, (u32*)sm.red, OpMax());
+    for (int q = q0; q < qe; ++q) {
+        const u64 r = recs[phys(q)];
+        const u32 nx = (u32)(r >> 32);
+        run = nx > run ? nx : run;
+        recs[phys(q)] = (u64)(u32)r | ((u64)run << 32);
+    }
+    // G: largest `gone` over the positions behind the thread's own (threads in mirrored order)
+    u32 far = 0;
+    for (int q = q0; q < qe; ++q) { const u32 g = gone[phys(q)]; far = g > far ? g : far; }
+    mirror[NT - 1 - tid] = far;
+    __syncthreads();
+    const u32 mv = mirror[tid];
+    __syncthreads();
+    const u32 behind_m = block_excl_scan_op<u32, NT>(mv, (u32*)sm.red, OpMax());   // for thread NT-1-tid
+    mirror[NT - 1 - tid] = behind_m;
+    __syncthreads();                              // also: every M is in place
+    u32 G = mirror[tid];
+    G = absent_all > G ? absent_all : G;
+
+    u64 bd = U64_MAX;
+    u32 bq = 0xffffffffu, bk = 0;
+    for (int q = qe - 1; q >= q0; --q) {          // right to left: G covers the positions behind q
+        const u32 key = (u32)recs[phys(q)];
+        if (a + key >= thr && G != NEVER) {
+            u64 d;
+            bool ok = true;
+            if (G > 0) {
+                d = (u64)key + G;
+            } else {
+                int l = 0, h = total;             // number of positions j with M(j) <= key
+                while (l < h) {
+                    const int m = (l + h) >> 1;
+                    if ((u32)(recs[phys(m)] >> 32) <= key) l = m + 1; else h = m;
+                }
+                ok = l < total;
+                d = ok ? (u64)(key - (u32)recs[phys(l)]) : 0;
+            }
+            if (ok && (d < bd || (d == bd && (u32)q < bq))) { bd = d; bq = (u32)q; bk = key; }
+        }
+        const u32 g = gone[phys(q)];
+        G = g > G ? g : G;
+    }
+    // block arg-min over (d, position): smaller d, then earlier position
+    u64 pk = ((u64)bq << 32) | bk;
+    wave_argmin(bd, pk);
+    constexpr int NW = NT / WAVE;
+    const int lane = tid & (WAVE - 1), wave = tid >> 6;
+    u64* red = sm.red;
+    __syncthreads();
+    if (lane == WAVE - 1) { red[wave] = bd; red[NW + wave] = pk; }
+    __syncthreads();
+    bd = red[0]; pk = red[NW];
+#pragma unroll 4
+    for (int w = 1; w < NW; ++w) {
+        const u64 od = red[w], ok = red[NW + w];
+        if (od < bd || (od == bd && ok < pk)) { bd = od; pk = ok; }
+    }
+    __syncthreads();
+    best_d = bd;
+    best_key = (u32)pk;
+}
+
+// One interval [A, Elast] (less than 2^32 - 1 wide): gather, sort, search.  An interval
+// with more than CAP_WIDE entries is walked in pieces that do fit, cut by bisection on
+// the value (every piece is searched on its own: what a piece needs from outside it
+// are the neighbouring entries of its rows, which the gather reads); a single value
+// that alone occurs more than CAP_WIDE times is one candidate and is evaluated
+// directly from the rows.  (bd, bb) is updated with the first minimum found.
+template <int NT, int ITEMS>
+__device__ __forceinline__ void zl_range_window(const Smem& sm, const Rows& rw, u64 thr, u64 A, u64 Elast,
+                                                u64& bd, u64& bb, int& bad)
+{
+    using C = WinCfg<NT, ITEMS>;
+    constexpr int CAPW = C::CAP_WIDE;
+    u64 a = A;
+    bool lx = true;
+    for (;;) {
+        u64 el = Elast;
+        bool rx = true;
+        u32 absent = 0;
+        int total = zl_range_gather<NT>(sm, rw, a, el, lx, rx, CAPW, absent, bad);
+        bool single = false;
+        if (total > CAPW) {
+            if (count_interval<NT>(sm, rw, a, a, lx) > (u32)CAPW) {
+                single = true;                     // the value `a` alone overflows a piece
+                el = a;
+            } else {
+                u64 l = a, h = el;                 // count(a, l) <= CAPW < count(a, h)
+                while (h - l > 1) {
+                    const u64 m = l + ((h - l) >> 1);
+                    if (count_interval<NT>(sm, rw, a, m, lx) <= (u32)CAPW) l = m; else h = m;
+                }
+                el = l;
+                absent = 0;
+                total = zl_range_gather<NT>(sm, rw, a, el, lx, false, CAPW, absent, bad);
+            }
+            rx = false;
+        }
+        if (single) {
+            // candidate c = a: every row stops at its last entry <= a
+            u64 far = 0;
+            int missing = 0;
+            for (int p = threadIdx.x; p < rw.P; p += NT) {
+                u32 lo, hi;
+                sub_range(rw, p, a, a, lx, false, lo, hi);
+                if (hi > 0) { const u64 g = a - rw.rel(p, hi - 1); far = g > far ? g : far; } else missing = 1;
+            }
+            const u64 d = block_reduce<u64, NT>(far, sm.red, OpMax());
+            missing = __syncthreads_or(missing);
+            if (!missing && a >= thr && (d < bd || (d == bd && a < bb))) { bd = d; bb = a; }
+        } else {
+            const u32 absent_all = block_reduce<u32, NT>(absent, (u32*)sm.red, OpMax());   // also orders the record writes
+            if (total > 0) {
+                const int items = (total + NT - 1) / NT;
+                fill_sentinels<NT>(sm.recs, total, items);
+                __syncthreads();
+                zl_sort<NT, ITEMS, true>(sm, items, bit_length(el - a));
+                u64 d;
+                u32 key;
+                zl_range_scan_argmin<NT>(sm, items, total, a, thr, absent_all, d, key);
+                if (d != U64_MAX && (d < bd || (d == bd && a + key < bb))) { bd = d; bb = a + key; }
+            }
+        }
+        if (rx) break;
+        // continue at the smallest entry above el, if any
+        u64 nxt = U64_MAX;
+        int have = 0;
+        for (int p = threadIdx.x; p < rw.P; p += NT) {
+            u32 lo, hi;
+            rw.range(p, lo, hi);
+            const u32 i = row_lower_bound(rw, p, lo, hi, el + 1);
+            if (i < hi) { const u64 v = rw.rel(p, i); nxt = v < nxt ? v : nxt; have = 1; }
+        }
+        nxt = block_reduce<u64, NT>(nxt, sm.red, OpMin());
+        have = __syncthreads_or(have);
+        if (!have || nxt > Elast || nxt <= el) break;
+        a = nxt;
+        lx = false;
+    }
+}
+
+// Instances of at most CAP_WIDE entries: one workgroup each.
+template <int NT, int ITEMS>
+__global__ __launch_bounds__(NT) void zl_range_instance_kernel(
+    const i64* __restrict__ ts, int P, int R,
+    i64* __restrict__ barrier, int* __restrict__ iters, i64* __restrict__ dmin,
+    int* __restrict__ status)
+{
+    using C = WinCfg<NT, ITEMS>;
+    __shared__ __align__(16) unsigned char smem[C::BYTES];
+    const Smem sm = carve<NT, ITEMS>(smem);
+    const int tid = threadIdx.x;
+    const i64 b = blockIdx.x;
+    const i64* __restrict__ inst = ts + b * (i64)P * R;
+    i64 mn = INT64_MAX, mxf = INT64_MIN, mxl = INT64_MIN;
+    for (int p = tid; p < P; p += NT) {
+        const i64 f = inst[(size_t)p * R], l = inst[(size_t)p * R + R - 1];
+        mn = f < mn ? f : mn;
+        mxf = f > mxf ? f : mxf;
+        mxl = l > mxl ? l : mxl;
+    }
+    i64 base, first_max, last_max;
+    block_bounds<NT>(mn, mxf, mxl, (i64*)sm.red, base, first_max, last_max);
+    const u64 range = (u64)last_max - (u64)base;
+    const u64 thr = (u64)first_max - (u64)base;
+    u32 flags = 0;
+    u64 best_d = U64_MAX, best_rel = 0;
+    int bad = 0;
+    if (range >= 0xffffffffull) {
+        flags |= EBSP_STATUS_UNSUPPORTED;
+    } else {
+        Rows rw;
+        rw.inst = inst; rw.P = P; rw.R = R; rw.base = (u64)base;
+        rw.cr = nullptr; rw.narrow = false; rw.stride = 0; rw.k0 = rw.k1 = 0;
+        zl_range_window<NT, ITEMS>(sm, rw, thr, 0ull, range, best_d, best_rel, bad);
+    }
+    if (__syncthreads_or(bad)) flags |= EBSP_STATUS_UNSORTED;
+    if (best_d == U64_MAX) { best_d = 0; best_rel = 0; }
+    const i64 bar = (i64)((u64)base + best_rel);
+    if (tid == 0) {
+        barrier[b] = bar;
+        dmin[b] = (i64)best_d;
+        if (status) status[b] = (int)flags;
+    }
+    for (int p = tid; p < P; p += NT)
+        iters[b * (i64)P + p] = zl_iters(inst + (size_t)p * R, R, bar);
+}
+
+// One workgroup per window of the multi-window path; results go to `partial`
+// (reduced by zl_finish_kernel like those of the summed-wait search).
+template <int NT, int ITEMS>
+__global__ __launch_bounds__(NT) void zl_range_window_kernel(
+    const i64* __restrict__ ts, i64 B, int P, int R,
+    const InstInfo* __restrict__ info, const void* __restrict__ cross, bool narrow, int stride,
+    const u32* __restrict__ winstart, const WinVal* __restrict__ winval, int max_win,
+    Partial* __restrict__ partial, int* __restrict__ status)
+{
+    using C = WinCfg<NT, ITEMS>;
+    __shared__ __align__(16) unsigned char smem[C::BYTES];
+    const Smem sm = carve<NT, ITEMS>(smem);
+    const i64 b = blockIdx.x / (u32)max_win;
+    const int j = (int)(blockIdx.x % (u32)max_win);
+    if (b >= B) return;
+    const InstInfo ii = info[b];
+    if (j >= (int)ii.nwin) return;
+    const WinPos w = locate_window(b, j, ii, ts, P, R, cross, narrow, stride, winstart, winval, max_win);
+    Partial r;
+    r.wait = U64_MAX;
+    r.brel = 0;
+    int bad = 0;
+    bool fits = true;
+    if (ii.range >= 0xffffffffull) fits = false;
+    else if (w.valid) zl_range_window<NT, ITEMS>(sm, w.rw, ii.thr, w.A, w.Elast, r.wait, r.brel, bad);
+    bad = __syncthreads_or(bad);
+    if (threadIdx.x == 0) {
+        partial[b * (i64)max_win + j] = r;
+        if (status && (bad || !fits))
+            atomicOr(status + b, (bad ? (int)EBSP_STATUS_UNSORTED : 0) | (fits ? 0 : (int)EBSP_STATUS_UNSUPPORTED));
+    }
+}
+
 // zl_iters for the multi-window path: reduce the instance's window results
 // (first minimum: smaller wait, then earlier barrier), then count iterations.
 template <int NT>
@@ -1784,11 +2128,11 @@ int fail(int code, const char* msg)
 }
 
 enum KernelId { K_INSTANCE = 0, K_INSTANCE_GENERAL, K_BOUNDS, K_PARTITION, K_BINCOUNT, K_PLAN, K_WINDOW,
-                K_WINDOW_GENERAL, K_FINISH, K_COPY, K_COUNT };
+                K_WINDOW_GENERAL, K_FINISH, K_COPY, K_RANGE_INSTANCE, K_RANGE_WINDOW, K_COUNT };
 const char* const kKernelNames[K_COUNT] = {
     "zl_instance_kernel", "zl_instance_general_kernel", "zl_bounds_kernel", "zl_partition_kernel",
     "zl_bincount_kernel", "zl_plan_kernel", "zl_window_kernel", "zl_window_general_kernel",
-    "zl_finish_kernel", "zl_copy_kernel"};
+    "zl_finish_kernel", "zl_copy_kernel", "zl_range_instance_kernel", "zl_range_window_kernel"};
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -1811,13 +2155,15 @@ struct Plan {
     size_t off_info, off_cross, off_below, off_winstart, off_winval, off_partial, bytes;
 };
 
-bool make_plan(i64 B, int P, int R, Plan& pl)
+// single_limit: the most entries one workgroup takes whole on the path the plan is for
+bool make_plan(i64 B, int P, int R, Plan& pl, int single_limit = SINGLE_MAX)
 {
     if (B < 0 || P < 1 || R < 1) return false;
     const i64 n = (i64)P * (i64)R;
     if (n >= (1ll << 31)) return false;
     memset(&pl, 0, sizeof pl);
-    const int single_max = g_tune.single_max > 0 ? g_tune.single_max : SINGLE_MAX;
+    int single_max = g_tune.single_max > 0 ? g_tune.single_max : SINGLE_MAX;
+    if (single_max > single_limit) single_max = single_limit;
     pl.multi = n > single_max;
     if (!pl.multi) return true;
     // the per-window cost has a term proportional to P: larger windows for more rows
@@ -1951,6 +2297,63 @@ int run_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters, i64*
     return EBSP_OK;
 }
 
+// The search under the paper's formal objective; the multi-window path shares the
+// kernels that cut an instance into windows.
+constexpr int RANGE_SINGLE_MAX = WinCfg<LARGE_NT, LARGE_ITEMS>::CAP_WIDE;
+
+int run_range_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters, i64* dmin, int* status,
+                    void* workspace, size_t workspace_bytes, hipStream_t st)
+{
+    Plan pl;
+    if (!make_plan(B, P, R, pl, RANGE_SINGLE_MAX))
+        return fail(EBSP_ERR_SHAPE, "invalid shape: need B >= 0, P >= 1, R >= 1, P*R < 2^31");
+    if (B == 0) return EBSP_OK;
+    if (!ts || !barrier || !iters || !dmin) return fail(EBSP_ERR_NULL, "ts, barrier, iters and dmin must not be NULL");
+    if (B > 0x7fffffffll) return fail(EBSP_ERR_SHAPE, "B must be below 2^31");
+    if (!pl.multi) {
+        LAUNCH(K_RANGE_INSTANCE, (zl_range_instance_kernel<LARGE_NT, LARGE_ITEMS>), dim3((unsigned)B), dim3(LARGE_NT),
+               ts, P, R, barrier, iters, dmin, status);
+        return EBSP_OK;
+    }
+    if (!workspace) return fail(EBSP_ERR_NULL, "this shape needs a workspace");
+    if (workspace_bytes < pl.bytes) return fail(EBSP_ERR_WORKSPACE, "workspace smaller than ebsp_zipline_range_workspace_bytes()");
+    if (((uintptr_t)workspace & 255u) != 0) return fail(EBSP_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    const i64 total_win = B * (i64)pl.max_win;
+    if (total_win + 8 > 0x7fffffffll || B * (i64)P > (0x7fffffffll * 4)) return fail(EBSP_ERR_SHAPE, "batch too large for one call");
+
+    char* wsp = (char*)workspace;
+    InstInfo* info = (InstInfo*)(wsp + pl.off_info);
+    void* cross = (void*)(wsp + pl.off_cross);
+    u32* below = (u32*)(wsp + pl.off_below);
+    u32* winstart = (u32*)(wsp + pl.off_winstart);
+    WinVal* winval = (WinVal*)(wsp + pl.off_winval);
+    Partial* partial = (Partial*)(wsp + pl.off_partial);
+
+    LAUNCH(K_BOUNDS, (zl_bounds_kernel<256>), dim3((unsigned)B), dim3(256), ts, P, R, pl.bins, info, status);
+    const i64 nrows = B * (i64)P;
+    if (pl.narrow)
+        LAUNCH(K_PARTITION, (zl_partition_kernel<256, unsigned short>), dim3((unsigned)((nrows + 3) / 4)), dim3(256),
+               ts, nrows, P, R, info, (unsigned short*)cross, pl.stride, status);
+    else
+        LAUNCH(K_PARTITION, (zl_partition_kernel<256, u32>), dim3((unsigned)((nrows + 3) / 4)), dim3(256),
+               ts, nrows, P, R, info, (u32*)cross, pl.stride, status);
+    const i64 kblocks = (pl.stride + 63) / 64, pblocks = (P + 255) / 256;
+    if (kblocks * B > 0x7fffffffll || pblocks * B > 0x7fffffffll) return fail(EBSP_ERR_SHAPE, "batch too large for one call");
+    if (pl.narrow)
+        LAUNCH(K_BINCOUNT, zl_bincount_kernel<unsigned short>, dim3((unsigned)(kblocks * B)), dim3(256),
+               (const unsigned short*)cross, P, R, pl.stride, pl.step, info, below);
+    else
+        LAUNCH(K_BINCOUNT, zl_bincount_kernel<u32>, dim3((unsigned)(kblocks * B)), dim3(256),
+               (const u32*)cross, P, R, pl.stride, pl.step, info, below);
+    LAUNCH(K_PLAN, (zl_plan_kernel<1024>), dim3((unsigned)B), dim3(1024), info, below, pl.stride, winstart, winval,
+           pl.max_win, pl.group_shift, (u32)(pl.cap / 8));
+    LAUNCH(K_RANGE_WINDOW, (zl_range_window_kernel<LARGE_NT, LARGE_ITEMS>), dim3((unsigned)total_win), dim3(LARGE_NT),
+           ts, B, P, R, info, cross, pl.narrow, pl.stride, winstart, winval, pl.max_win, partial, status);
+    LAUNCH(K_FINISH, (zl_finish_kernel<256>), dim3((unsigned)(pblocks * B)), dim3(256),
+           ts, P, R, info, partial, pl.max_win, barrier, iters, dmin);
+    return EBSP_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -1968,6 +2371,23 @@ int ebsp_zipline_batch(const int64_t* ts, int64_t B, int32_t P, int32_t R,
 {
     const int rc = run_batch((const i64*)ts, B, P, R, (i64*)barrier, iters, (i64*)wait, status,
                              workspace, workspace_bytes, (hipStream_t)stream);
+    if (g_prof.on && rc == EBSP_OK && B > 0 && g_prof.calls < g_prof.max_calls) ++g_prof.calls;
+    return rc;
+}
+
+size_t ebsp_zipline_range_workspace_bytes(int64_t B, int32_t P, int32_t R)
+{
+    Plan pl;
+    if (!make_plan(B, P, R, pl, RANGE_SINGLE_MAX)) return 0;
+    return pl.multi ? pl.bytes : 0;
+}
+
+int ebsp_zipline_range_batch(const int64_t* ts, int64_t B, int32_t P, int32_t R,
+                             int64_t* barrier, int32_t* iters, int64_t* dmin,
+                             int32_t* status, void* workspace, size_t workspace_bytes, void* stream)
+{
+    const int rc = run_range_batch((const i64*)ts, B, P, R, (i64*)barrier, iters, (i64*)dmin, status,
+                                   workspace, workspace_bytes, (hipStream_t)stream);
     if (g_prof.on && rc == EBSP_OK && B > 0 && g_prof.calls < g_prof.max_calls) ++g_prof.calls;
     return rc;
 }

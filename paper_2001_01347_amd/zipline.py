@@ -20,7 +20,8 @@ LIB_PATH = os.path.join(_HERE, "libebsp_zipline.so")
 EBSP_OK = 0
 STATUS_OK, STATUS_UNSORTED, STATUS_OVERFLOW, STATUS_UNSUPPORTED = 0, 1, 2, 4
 
-EXPORTS = ("ebsp_zipline_workspace_bytes", "ebsp_zipline_batch", "ebsp_zipline_tune", "ebsp_zipline_shape_info", "ebsp_zipline_profile_begin",
+EXPORTS = ("ebsp_zipline_workspace_bytes", "ebsp_zipline_batch", "ebsp_zipline_range_workspace_bytes",
+           "ebsp_zipline_range_batch", "ebsp_zipline_tune", "ebsp_zipline_shape_info", "ebsp_zipline_profile_begin",
            "ebsp_zipline_profile_end", "ebsp_zipline_copy_probe", "ebsp_zipline_kernel_count",
            "ebsp_zipline_kernel_name", "ebsp_last_error")
 
@@ -45,6 +46,10 @@ def load() -> ctypes.CDLL:
         common = [vp, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
         lib.ebsp_zipline_batch.restype = ctypes.c_int
         lib.ebsp_zipline_batch.argtypes = common
+        lib.ebsp_zipline_range_workspace_bytes.restype = sz
+        lib.ebsp_zipline_range_workspace_bytes.argtypes = [i64, i32, i32]
+        lib.ebsp_zipline_range_batch.restype = ctypes.c_int
+        lib.ebsp_zipline_range_batch.argtypes = common
         lib.ebsp_zipline_shape_info.restype = ctypes.c_int
         lib.ebsp_zipline_shape_info.argtypes = [i64, i32, i32, ctypes.POINTER(ctypes.c_int64)]
         lib.ebsp_zipline_tune.restype = ctypes.c_int
@@ -71,6 +76,10 @@ def ebsp_last_error() -> str:
 
 def ebsp_zipline_workspace_bytes(B: int, P: int, R: int) -> int:
     return int(load().ebsp_zipline_workspace_bytes(B, P, R))
+
+
+def ebsp_zipline_range_workspace_bytes(B: int, P: int, R: int) -> int:
+    return int(load().ebsp_zipline_range_workspace_bytes(B, P, R))
 
 
 def ebsp_zipline_shape_info(B: int, P: int, R: int) -> Dict[str, int]:
@@ -100,7 +109,7 @@ def _check(ts: torch.Tensor) -> Tuple[int, int, int]:
     return tuple(int(x) for x in ts.shape)
 
 
-def _prepare(ts, barrier, iters, wait, status, workspace):
+def _prepare(ts, barrier, iters, wait, status, workspace, workspace_bytes=None):
     B, P, R = _check(ts)
     dev = ts.device
     if barrier is None:
@@ -111,7 +120,7 @@ def _prepare(ts, barrier, iters, wait, status, workspace):
         wait = torch.empty(B, dtype=torch.int64, device=dev)
     if status is None:
         status = torch.empty(B, dtype=torch.int32, device=dev)
-    need = ebsp_zipline_workspace_bytes(B, P, R)
+    need = (workspace_bytes or ebsp_zipline_workspace_bytes)(B, P, R)
     if workspace is None and need:
         workspace = torch.empty(need, dtype=torch.uint8, device=dev)
     ws_ptr = workspace.data_ptr() if workspace is not None else None
@@ -136,6 +145,22 @@ def ebsp_zipline_batch(ts: torch.Tensor, barrier: Optional[torch.Tensor] = None,
         rc = load().ebsp_zipline_batch(*args)
     if rc != EBSP_OK:
         raise ZipLineError(f"ebsp_zipline_batch failed ({rc}): {ebsp_last_error()}")
+    return outs
+
+
+def ebsp_zipline_range_batch(ts: torch.Tensor, barrier: Optional[torch.Tensor] = None,
+                             iters: Optional[torch.Tensor] = None, dmin: Optional[torch.Tensor] = None,
+                             status: Optional[torch.Tensor] = None,
+                             workspace: Optional[torch.Tensor] = None):
+    """The search under the paper's formal objective max(Z) - min(Z); see the header.
+
+    Returns ``(barrier[B], iters[B, P], dmin[B], status[B])`` device tensors.  Does not synchronise.
+    """
+    args, outs = _prepare(ts, barrier, iters, dmin, status, workspace, ebsp_zipline_range_workspace_bytes)
+    with torch.cuda.device(ts.device):
+        rc = load().ebsp_zipline_range_batch(*args)
+    if rc != EBSP_OK:
+        raise ZipLineError(f"ebsp_zipline_range_batch failed ({rc}): {ebsp_last_error()}")
     return outs
 
 
