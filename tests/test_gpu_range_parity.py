@@ -129,3 +129,43 @@ def test_status_flags(zl, oracle):
     ms[1, 9, 100] = ms[1, 9, 99] - 5
     bar, it, dm, st = gpu_run(zl, ms)
     assert st[1] & zl.STATUS_UNSORTED and (np.delete(st, 1) == 0).all()
+
+
+def _properties_hold(ts, bar, it, dm):
+    """Checks that hold at any size (torch, on the GPU): each worker stops at its last timestamp
+    <= barrier, the barrier is some worker's stop, and dmin is the barrier minus the earliest stop."""
+    B, P, R = ts.shape
+    assert int(it.min()) >= 1 and int(it.max()) <= R
+    idx = (it.long() - 1).unsqueeze(-1)
+    stop = torch.gather(ts, 2, idx).squeeze(-1)                        # [B, P]
+    assert bool((stop <= bar.unsqueeze(-1)).all())
+    nxt = torch.gather(ts, 2, torch.clamp(idx + 1, max=R - 1)).squeeze(-1)
+    beyond = (it.long() == R) | (nxt > bar.unsqueeze(-1))
+    assert bool(beyond.all())
+    assert bool((stop.max(dim=1).values == bar).all())
+    assert bool((bar - stop.min(dim=1).values == dm).all())
+    first_all = ts[:, :, 0].max(dim=1).values
+    assert bool((bar >= first_all).all())
+    # never worse than the classic barrier after one iteration of every worker
+    lag = torch.searchsorted(ts.contiguous(), first_all.view(B, 1, 1).expand(B, P, 1).contiguous(), right=True).squeeze(-1)
+    classic = first_all - torch.gather(ts, 2, (lag - 1).unsqueeze(-1)).squeeze(-1).min(dim=1).values
+    assert bool((dm <= classic).all())
+
+
+@pytest.mark.parametrize("k,sample", [(3, 768), (4, 96), (5, 8)])
+def test_full_size_configs(zl, oracle, k, sample):
+    cfg = workloads.CONFIGS[k]
+    host = workloads.make(k, threads=16)
+    ts = torch.from_numpy(host).cuda()
+    bar, it, dm, st = zl.ebsp_zipline_range_batch(ts)
+    torch.cuda.synchronize()
+    assert int(st.max().item()) == 0
+    _properties_hold(ts, bar, it, dm)
+    rng = np.random.default_rng(100 + k)
+    ids = np.sort(rng.choice(cfg.B, size=sample, replace=False))
+    ob, oi, od, rc, _ = oracle.zipline_range(host[ids], "sweep", threads=16)
+    assert (rc == 0).all()
+    sel = torch.from_numpy(ids).cuda()
+    assert np.array_equal(bar[sel].cpu().numpy(), ob)
+    assert np.array_equal(dm[sel].cpu().numpy(), od)
+    assert np.array_equal(it[sel].cpu().numpy(), oi)
