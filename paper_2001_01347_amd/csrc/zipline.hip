@@ -2156,7 +2156,7 @@ struct Plan {
 };
 
 // single_limit: the most entries one workgroup takes whole on the path the plan is for
-bool make_plan(i64 B, int P, int R, Plan& pl, int single_limit = SINGLE_MAX)
+bool make_plan(i64 B, int P, int R, Plan& pl, int single_limit = SINGLE_MAX, int cap_override = 0)
 {
     if (B < 0 || P < 1 || R < 1) return false;
     const i64 n = (i64)P * (i64)R;
@@ -2167,7 +2167,7 @@ bool make_plan(i64 B, int P, int R, Plan& pl, int single_limit = SINGLE_MAX)
     pl.multi = n > single_max;
     if (!pl.multi) return true;
     // the per-window cost has a term proportional to P: larger windows for more rows
-    pl.cap = g_tune.window_cap > 0 ? g_tune.window_cap : (P >= 512 ? 8192 : 4096);
+    pl.cap = cap_override > 0 ? cap_override : (g_tune.window_cap > 0 ? g_tune.window_cap : (P >= 512 ? 8192 : 4096));
     pl.group_shift = pl.cap == 16384 ? 13 : (pl.cap == 8192 ? 12 : 11);
     const int fine_shift = pl.group_shift - 2;
     pl.bins = (int)((n + (1 << fine_shift) - 1) >> fine_shift);
@@ -2300,12 +2300,13 @@ int run_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters, i64*
 // The search under the paper's formal objective; the multi-window path shares the
 // kernels that cut an instance into windows.
 constexpr int RANGE_SINGLE_MAX = WinCfg<LARGE_NT, LARGE_ITEMS>::CAP_WIDE;
+constexpr int RANGE_WINDOW_CAP = 4096;      // windows of about 2048 entries: a 512-thread workgroup each, three per CU
 
 int run_range_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters, i64* dmin, int* status,
                     void* workspace, size_t workspace_bytes, hipStream_t st)
 {
     Plan pl;
-    if (!make_plan(B, P, R, pl, RANGE_SINGLE_MAX))
+    if (!make_plan(B, P, R, pl, RANGE_SINGLE_MAX, RANGE_WINDOW_CAP))
         return fail(EBSP_ERR_SHAPE, "invalid shape: need B >= 0, P >= 1, R >= 1, P*R < 2^31");
     if (B == 0) return EBSP_OK;
     if (!ts || !barrier || !iters || !dmin) return fail(EBSP_ERR_NULL, "ts, barrier, iters and dmin must not be NULL");
@@ -2347,7 +2348,7 @@ int run_range_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters
                (const u32*)cross, P, R, pl.stride, pl.step, info, below);
     LAUNCH(K_PLAN, (zl_plan_kernel<1024>), dim3((unsigned)B), dim3(1024), info, below, pl.stride, winstart, winval,
            pl.max_win, pl.group_shift, (u32)(pl.cap / 8));
-    LAUNCH(K_RANGE_WINDOW, (zl_range_window_kernel<LARGE_NT, LARGE_ITEMS>), dim3((unsigned)total_win), dim3(LARGE_NT),
+    LAUNCH(K_RANGE_WINDOW, (zl_range_window_kernel<512, 16>), dim3((unsigned)total_win), dim3(512),
            ts, B, P, R, info, cross, pl.narrow, pl.stride, winstart, winval, pl.max_win, partial, status);
     LAUNCH(K_FINISH, (zl_finish_kernel<256>), dim3((unsigned)(pblocks * B)), dim3(256),
            ts, P, R, info, partial, pl.max_win, barrier, iters, dmin);
@@ -2378,7 +2379,7 @@ int ebsp_zipline_batch(const int64_t* ts, int64_t B, int32_t P, int32_t R,
 size_t ebsp_zipline_range_workspace_bytes(int64_t B, int32_t P, int32_t R)
 {
     Plan pl;
-    if (!make_plan(B, P, R, pl, RANGE_SINGLE_MAX)) return 0;
+    if (!make_plan(B, P, R, pl, RANGE_SINGLE_MAX, RANGE_WINDOW_CAP)) return 0;
     return pl.multi ? pl.bytes : 0;
 }
 
