@@ -38,6 +38,8 @@ def algorithmic_bytes(kernel: str, B: int, P: int, R: int, bins: int, windows: i
         return 8.0 * n + windows * (2.0 * cw * P + 16.0)
     if kernel == "zl_partition_kernel":     # every timestamp once, one crossing index per (row, bin)
         return 8.0 * n + cw * B * P * (bins + 1)
+    if kernel == "zl_partition_pred_kernel":    # 16 bytes per worker, one crossing index per (row, bin)
+        return 16.0 * B * P + cw * B * P * (bins + 1)
     if kernel == "zl_bincount_kernel":      # the crossing indices once, one count per bin
         return cw * B * ((P + step - 1) // step) * (bins + 1) + 4.0 * B * (bins + 1)
     if kernel == "zl_bounds_kernel":        # first and last timestamp of every row (one 64-byte line each)
@@ -63,6 +65,9 @@ def main() -> int:
     ap.add_argument("--objective", default="sum", choices=["sum", "range"],
                     help="sum: the summed waiting time (ebsp_zipline_batch, the default); "
                          "range: the paper's formal objective max(Z) - min(Z) (ebsp_zipline_range_batch)")
+    ap.add_argument("--predicted", action="store_true",
+                    help="rows predicted inside the kernels from (last_end, interval) per worker "
+                         "(ebsp_predict_zipline_batch): nothing but 16 bytes per worker is read from HBM")
     ap.add_argument("--cpu-instances", type=int, default=-1,
                     help="instances in the CPU-oracle sample (default: sized for roughly 10-30 s of CPU work)")
     ap.add_argument("--copy-probe", type=int, default=3,
@@ -89,8 +94,16 @@ def main() -> int:
     torch.cuda.set_device(dev)
 
     t0 = time.time()
-    host = workloads.make(args.config, threads=16)
-    ts = torch.from_numpy(host).to(dev)
+    if args.predicted:
+        if args.objective != "sum":
+            print("bench.py: --predicted goes with the summed-wait objective only", file=sys.stderr)
+            return 2
+        le_host, iv_host = workloads.make_predicted(args.config)
+        le_dev, iv_dev = torch.from_numpy(le_host).to(dev), torch.from_numpy(iv_host).to(dev)
+        host = ts = None
+    else:
+        host = workloads.make(args.config, threads=16)
+        ts = torch.from_numpy(host).to(dev)
     gen_s = time.time() - t0
 
     barrier = torch.empty(B, dtype=torch.int64, device=dev)
@@ -102,7 +115,9 @@ def main() -> int:
     workspace = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
 
     def step():
-        if ranged:
+        if args.predicted:
+            zipline.ebsp_predict_zipline_batch(le_dev, iv_dev, R, barrier, iters, wait, status, workspace)
+        elif ranged:
             zipline.ebsp_zipline_range_batch(ts, barrier, iters, wait, status, workspace)
         else:
             zipline.ebsp_zipline_batch(ts, barrier, iters, wait, status, workspace)
@@ -126,7 +141,7 @@ def main() -> int:
 
     # yardstick: a plain streaming copy of the same 8 B/key input (reads and writes n_keys * 8 bytes)
     copy_gbs = None
-    if args.copy_probe > 0:
+    if args.copy_probe > 0 and ts is not None:
         dst = torch.empty_like(ts)
         zipline.ebsp_zipline_copy_probe(ts, dst)
         torch.cuda.synchronize()
@@ -160,7 +175,7 @@ def main() -> int:
         n_cpu = min(B, args.cpu_instances)
     else:
         n_cpu = max(1, min(B, int(1.7e7 * cores // (P * R)) or 1))
-    sample = host[:n_cpu]
+    sample = host[:n_cpu] if host is not None else workloads.predicted_rows(le_host[:n_cpu], iv_host[:n_cpu], R)
     cpu_search = oracle.zipline_range if ranged else oracle.zipline
     cpu_search(sample[:1], "sweep", threads=1)              # load the library, touch the pages
     c0 = time.perf_counter()
@@ -172,7 +187,8 @@ def main() -> int:
             and np.array_equal(oi, iters[:n_cpu].cpu().numpy()))
 
     out = {
-        "metric": "zipline_timestamps_per_sec" if not ranged else "zipline_range_timestamps_per_sec",
+        "metric": ("zipline_predicted_timestamps_per_sec" if args.predicted else
+                   "zipline_timestamps_per_sec" if not ranged else "zipline_range_timestamps_per_sec"),
         "value": n_keys / (ms_per_step * 1e-3),
         "unit": "timestamps/s",
         "instances_per_sec": B / (ms_per_step * 1e-3),
@@ -187,7 +203,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"config {cfg.k}: B={B} instances, P={P} workers, R={R} lookahead, "
                                f"{n_keys} int64 us timestamps resident in HBM",
-                   "B": B, "P": P, "R": R, "objective": args.objective},
+                   "B": B, "P": P, "R": R, "objective": args.objective, "predicted": bool(args.predicted)},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
                      "kernel_ms": per_kernel[dom], "algorithmic_bytes": dom_bytes},

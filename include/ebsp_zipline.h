@@ -80,6 +80,30 @@ int ebsp_zipline_batch(const int64_t* ts, int64_t B, int32_t P, int32_t R,
                        void* stream);
 
 /*
+ * The prediction folded in (Section III: a worker's iterations take similar
+ * time, so its next R end timestamps are predicted from its most recent ones;
+ * the paper gives no formula, the linear one is this build's reading):
+ *
+ *     t[p][i] = last_end[p] + (i + 1) * interval[p],   i = 0 .. R-1
+ *
+ * and then exactly the search of ebsp_zipline_batch over these rows, which are
+ * never stored: the kernels compute them where they would have loaded them.
+ *
+ *   last_end  in  [B][P] int64, device: end timestamp of each worker's last
+ *                 finished iteration (any fixed unit and epoch).
+ *   interval  in  [B][P] int64, device: predicted iteration time, >= 0
+ *                 (a negative one gives EBSP_STATUS_UNSORTED for the instance).
+ *   the other arguments, the workspace size (ebsp_zipline_workspace_bytes),
+ *   the status bits and the return codes: as for ebsp_zipline_batch.
+ * Precondition: last_end + R * interval does not overflow int64.
+ */
+int ebsp_predict_zipline_batch(const int64_t* last_end, const int64_t* interval,
+                               int64_t B, int32_t P, int32_t R,
+                               int64_t* barrier, int32_t* iters, int64_t* wait,
+                               int32_t* status, void* workspace, size_t workspace_bytes,
+                               void* stream);
+
+/*
  * The same search under the paper's formal objective (Section III "The
  * Problem": d_Z = max(Z) - min(Z), the waiting time of the fastest worker;
  * Section IV, Algorithm 2, which sweeps the merged timestamps with a set Z of

@@ -228,7 +228,10 @@ __device__ __forceinline__ u64 fine_bin_start(u32 k, const InstInfo& ii)
 // Rows of one instance and, per row, the index range under consideration:
 // the whole row, or [cross[p][k0], cross[p][k1]) from zl_partition.
 struct Rows {
-    const i64* inst;
+    const i64* inst;    // the instance's stored matrix, or nullptr for predicted rows:
+    const i64* le;      // t[p][i] = le[p] + (i + 1) * iv[p]   (Section III: iterations of a worker
+    const i64* iv;      // take similar time; its next R end timestamps from the last one and the interval)
+    const uint2* par;   // predicted rows on the fast window path: low words of (first value, interval) per row
     int P, R;
     u64 base;
     const void* cr;     // crossing indices of this instance (u16 if narrow, else u32), or nullptr for whole rows
@@ -260,7 +263,11 @@ struct Rows {
         hi = hi < (u32)R ? hi : (u32)R;
         hi = hi > lo ? hi : lo;
     }
-    __device__ __forceinline__ u64 rel(int p, u32 i) const { return (u64)inst[(size_t)p * R + i] - base; }
+    __device__ __forceinline__ i64 value(int p, u32 i) const
+    {
+        return inst ? inst[(size_t)p * R + i] : (i64)((u64)le[p] + (u64)(i + 1) * (u64)iv[p]);
+    }
+    __device__ __forceinline__ u64 rel(int p, u32 i) const { return (u64)value(p, i) - base; }
 };
 
 // First index in [lo, hi) of row p whose relative value is >= v (hi if none).
@@ -291,6 +298,19 @@ __device__ __forceinline__ int zl_iters(const i64* __restrict__ row, int R, i64 
     while (lo < hi) {
         int m = (lo + hi) >> 1;
         if (row[m] <= v) lo = m + 1; else hi = m;
+    }
+    return lo;
+}
+
+// The same for row p of stored (inst != nullptr) or predicted rows.
+__device__ __forceinline__ int zl_iters_of(const i64* inst, const i64* le, const i64* iv, int p, int R, i64 v)
+{
+    if (inst) return zl_iters(inst + (size_t)p * R, R, v);
+    const i64 l = le[p], s = iv[p];
+    int lo = 0, hi = R;
+    while (lo < hi) {
+        const int m = (lo + hi) >> 1;
+        if ((i64)((u64)l + (u64)(m + 1) * (u64)s) <= v) lo = m + 1; else hi = m;
     }
     return lo;
 }
@@ -540,12 +560,11 @@ __device__ __forceinline__ int zl_delta(const Smem& sm, const Rows& rw, u64 a, u
                 if (rowoff[m] <= (u32)e) l = m; else h = m;
             }
             const u32 i = rowlo[l] + ((u32)e - rowoff[l]);
-            const i64* src = rw.inst + (size_t)(p0 + l) * rw.R + i;
-            const i64 cur = src[0];
+            const i64 cur = rw.value(p0 + l, i);
             const u64 rel = (u64)cur - rw.base;
             u64 prel = a;
             if (i > 0) {
-                const i64 prv = src[-1];
+                const i64 prv = rw.value(p0 + l, i - 1);
                 prel = (u64)prv - rw.base;
                 bad |= (cur < prv);
             }
@@ -925,6 +944,7 @@ __device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key
 //      rows without any entry in the window add their share in sweep 1.
 // Returns the number of entries; nothing is loaded if it exceeds `cap`.
 constexpr u64 FIRST_OF_ROW = 1ull << 32, FIRST_OF_SEGMENT = 1ull << 33;
+constexpr int PRED_ROW_SHIFT = 34;        // predicted rows: the row number sits above the two flags
 // rows a thread takes per round of sweep 1: one round covers 1024 rows
 template <int NT> constexpr int ROWS_PER_THREAD = NT >= 1024 ? 1 : 1024 / NT;
 constexpr int WINDOWS_PER_BLOCK = 2;      // consecutive windows a workgroup handles, one after the other
@@ -955,9 +975,9 @@ __device__ __forceinline__ void load_column(const Rows& rw, u32 k, u32 (&out)[RO
     }
 }
 
-template <int NT, int ITEMS, int G>
-__device__ __forceinline__ void gather_batch(const u64* recs, const char* bytes, int g, int total, u32 start,
-                                             u32 (&key)[ITEMS], u32 (&dl)[ITEMS], u64& w0)
+template <int NT, int ITEMS, int G, bool PRED>
+__device__ __forceinline__ void gather_batch(const u64* recs, const char* bytes, const uint2* par, int g, int total,
+                                             u32 start, u32 (&key)[ITEMS], u32 (&dl)[ITEMS], u64& w0)
 {
     const int tid = threadIdx.x;
     if (g * NT >= total) return;
@@ -970,10 +990,17 @@ __device__ __forceinline__ void gather_batch(const u64* recs, const char* bytes,
     }
 #pragma unroll
     for (int j = 0; j < G; ++j) {
-        const u32 at = (u32)src[j];
-        const u32 pat = at - (1u - ((u32)(src[j] >> 32) & 1u));    // a row's first entry stands in for its predecessor
-        cur[j] = *(const u32*)(bytes + (at << 3));
-        prv[j] = *(const u32*)(bytes + (pat << 3));
+        if (PRED) {
+            // predicted rows: the source word holds the row (above the flags) and the index in it
+            const uint2 fs = par[(u32)(src[j] >> PRED_ROW_SHIFT)];  // first value of the row, interval
+            cur[j] = fs.x + (u32)src[j] * fs.y;
+            prv[j] = cur[j] - fs.y;
+        } else {
+            const u32 at = (u32)src[j];
+            const u32 pat = at - (1u - ((u32)(src[j] >> 32) & 1u));    // a row's first entry stands in for its predecessor
+            cur[j] = *(const u32*)(bytes + (at << 3));
+            prv[j] = *(const u32*)(bytes + (pat << 3));
+        }
     }
 #pragma unroll
     for (int j = 0; j < G; ++j) {
@@ -984,7 +1011,7 @@ __device__ __forceinline__ void gather_batch(const u64* recs, const char* bytes,
     }
 }
 
-template <int NT, int ITEMS, class CT>
+template <int NT, int ITEMS, class CT, bool PRED>
 __device__ __forceinline__ int zl_delta_rows(const Smem& sm, const Rows& rw, u64 a, int cap,
                                              const u32 (&lo0)[ROWS_PER_THREAD<NT>], const u32 (&hi0)[ROWS_PER_THREAD<NT>],
                                              u32 (&key)[ITEMS], u32 (&dl)[ITEMS], u64& w0)
@@ -1014,8 +1041,10 @@ __device__ __forceinline__ int zl_delta_rows(const Smem& sm, const Rows& rw, u64
             const int p = p0 + c * NT + tid;
             mine += hi[c] - lo[c];
             before[c] = start;
-            if (p < rw.P && lo[c] == hi[c] && lo[c] > 0)
-                before[c] = *(const u32*)(bytes + (((u32)p * (u32)rw.R + lo[c] - 1u) << 3));
+            if (p < rw.P && lo[c] == hi[c] && lo[c] > 0) {
+                if (PRED) { const uint2 fs = rw.par[p]; before[c] = fs.x + (lo[c] - 1u) * fs.y; }
+                else before[c] = *(const u32*)(bytes + (((u32)p * (u32)rw.R + lo[c] - 1u) << 3));
+            }
         }
         u32 round;
         u32 slot = (u32)total + block_excl_scan<u32, NT>(mine, (u32*)sm.red, round);
@@ -1023,10 +1052,12 @@ __device__ __forceinline__ int zl_delta_rows(const Smem& sm, const Rows& rw, u64
         for (int c = 0; c < RPT; ++c) {
             const int p = p0 + c * NT + tid;
             if (p < rw.P) {
-                u64 src = (u64)((u32)p * (u32)rw.R + lo[c]) | FIRST_OF_SEGMENT | (lo[c] == 0 ? FIRST_OF_ROW : 0ull);
+                const u64 row = PRED ? (u64)(u32)p << PRED_ROW_SHIFT : 0ull;
+                u64 src = row | (u64)(PRED ? lo[c] : (u32)p * (u32)rw.R + lo[c]) | FIRST_OF_SEGMENT |
+                          (lo[c] == 0 ? FIRST_OF_ROW : 0ull);
                 for (u32 i = lo[c]; i < hi[c] && slot < (u32)cap; ++i, ++slot) {
                     recs[slot] = src;
-                    src = (u64)((u32)src + 1u);
+                    src = row | (u64)((u32)src + 1u);
                 }
             }
         }
@@ -1038,11 +1069,11 @@ __device__ __forceinline__ int zl_delta_rows(const Smem& sm, const Rows& rw, u64
     if (total > cap) return total;
 
     constexpr int G0 = ITEMS < GATHER_BATCH ? ITEMS : GATHER_BATCH;
-    gather_batch<NT, ITEMS, G0>(recs, bytes, 0, total, start, key, dl, w0);
+    gather_batch<NT, ITEMS, G0, PRED>(recs, bytes, rw.par, 0, total, start, key, dl, w0);
     static_assert((ITEMS - G0) % GATHER_TAIL == 0 || ITEMS < GATHER_BATCH, "tail batches must tile the items");
 #pragma unroll
     for (int g = G0; g < ITEMS; g += GATHER_TAIL)           // a window seldom fills all items: smaller steps there
-        gather_batch<NT, ITEMS, GATHER_TAIL>(recs, bytes, g, total, start, key, dl, w0);
+        gather_batch<NT, ITEMS, GATHER_TAIL, PRED>(recs, bytes, rw.par, g, total, start, key, dl, w0);
     return total;
 }
 
@@ -1141,9 +1172,9 @@ __device__ __forceinline__ void zl_window(const Smem& sm, const Rows& rw, u64 th
 
 // ---------------------------------------------------------------------------
 // One workgroup per instance (P*R <= NT*ITEMS): the whole search in LDS.
-template <int NT, int ITEMS>
+template <int NT, int ITEMS, bool PRED>        // PRED: rows are le[p] + (i + 1) * iv[p] instead of stored
 __global__ __launch_bounds__(NT) void zl_instance_kernel(
-    const i64* __restrict__ ts, int P, int R, int rshift,
+    const i64* __restrict__ ts, const i64* __restrict__ le, const i64* __restrict__ iv, int P, int R, int rshift,
     i64* __restrict__ barrier, int* __restrict__ iters, i64* __restrict__ wait,
     int* __restrict__ status)
 {
@@ -1154,7 +1185,14 @@ __global__ __launch_bounds__(NT) void zl_instance_kernel(
     const int tid = threadIdx.x;
     const i64 b = blockIdx.x;
     const int n = P * R;
-    const i64* __restrict__ inst = ts + b * (i64)n;
+    const i64* __restrict__ inst = PRED ? nullptr : ts + b * (i64)n;
+    const i64* __restrict__ lep = PRED ? le + b * (i64)P : nullptr;
+    const i64* __restrict__ ivp = PRED ? iv + b * (i64)P : nullptr;
+    auto at = [&](int e) -> i64 {                       // element e of the instance
+        if (!PRED) return inst[e];
+        const int p = rshift >= 0 ? (e >> rshift) : (e / R);
+        return (i64)((u64)lep[p] + (u64)(e - p * R + 1) * (u64)ivp[p]);
+    };
 
     // zl_delta.  Every element is loaded once, all loads of a thread in flight
     // together: wave w takes elements [w*64*items, (w+1)*64*items), 64 consecutive
@@ -1168,14 +1206,14 @@ __global__ __launch_bounds__(NT) void zl_instance_kernel(
     const int lane = tid & (WAVE - 1), wave = tid >> 6;
     const int items = (n + NT - 1) / NT;
     const int wbase = wave * WAVE * items;
-    const i64 t00 = inst[0];
+    const i64 t00 = at(0);
     i64 v[ITEMS];
 #pragma unroll
     for (int j = 0; j < ITEMS; ++j) {
         const int e = wbase + j * WAVE + lane;
-        v[j] = (j < items && e < n) ? inst[e] : 0;
+        v[j] = (j < items && e < n) ? at(e) : 0;
     }
-    i64 carry = (wbase > 0 && wbase < n) ? inst[wbase - 1] : 0;   // element ahead of the wave's first
+    i64 carry = (wbase > 0 && wbase < n) ? at(wbase - 1) : 0;   // element ahead of the wave's first
     i64 mn = INT64_MAX, mxf = INT64_MIN, mxl = INT64_MIN;         // min first, max first, max last of the rows
     int bad = 0;
 #pragma unroll
@@ -1279,7 +1317,7 @@ __global__ __launch_bounds__(NT) void zl_instance_kernel(
         if (status) status[b] = (int)flags;
     }
     for (int p = tid; p < P; p += NT)
-        iters[b * (i64)P + p] = zl_iters(inst + (size_t)p * R, R, bar);
+        iters[b * (i64)P + p] = zl_iters_of(inst, lep, ivp, p, R, bar);
 }
 
 // The instances zl_instance_kernel deferred (value spread of 2^32 or more, or
@@ -1288,7 +1326,7 @@ __global__ __launch_bounds__(NT) void zl_instance_kernel(
 // wait[] for deferred marks and handles the marked instances one after the other.
 template <int NT, int ITEMS>
 __global__ __launch_bounds__(NT) void zl_instance_general_kernel(
-    const i64* __restrict__ ts, i64 B, int P, int R,
+    const i64* __restrict__ ts, const i64* __restrict__ le, const i64* __restrict__ iv, i64 B, int P, int R,
     i64* __restrict__ barrier, int* __restrict__ iters, i64* __restrict__ wait,
     int* __restrict__ status)
 {
@@ -1308,10 +1346,13 @@ __global__ __launch_bounds__(NT) void zl_instance_general_kernel(
             const u32 b = block_reduce<u32, NT>(mine ? idx : 0xffffffffu, (u32*)sm.red, OpMin());
             if (b == 0xffffffffu) break;
             if (b == idx) mine = false;
-            const i64* __restrict__ inst = ts + (i64)b * P * R;
+            const i64* __restrict__ inst = ts ? ts + (i64)b * P * R : nullptr;
+            Rows ends;                            // only to read the rows' first and last entries
+            ends.inst = inst; ends.le = le ? le + (i64)b * P : nullptr; ends.iv = iv ? iv + (i64)b * P : nullptr;
+            ends.R = R;
             i64 mn = INT64_MAX, mxf = INT64_MIN, mxl = INT64_MIN;
             for (int p = tid; p < P; p += NT) {
-                const i64 f = inst[(size_t)p * R], l = inst[(size_t)p * R + R - 1];
+                const i64 f = ends.value(p, 0), l = ends.value(p, (u32)R - 1);
                 mn = f < mn ? f : mn;
                 mxf = f > mxf ? f : mxf;
                 mxl = l > mxl ? l : mxl;
@@ -1324,7 +1365,8 @@ __global__ __launch_bounds__(NT) void zl_instance_general_kernel(
             if (range > (u64)INT64_MAX / (u64)P) flags |= EBSP_STATUS_OVERFLOW;
 
             Rows rw;
-            rw.inst = inst; rw.P = P; rw.R = R; rw.base = (u64)base;
+            rw.inst = inst; rw.le = le ? le + (i64)b * P : nullptr; rw.iv = iv ? iv + (i64)b * P : nullptr;
+            rw.P = P; rw.R = R; rw.base = (u64)base;
             rw.cr = nullptr; rw.narrow = false; rw.stride = 0; rw.k0 = rw.k1 = 0;
             int bad = 0;
             u64 best_wait = U64_MAX, best_rel = 0;
@@ -1338,7 +1380,7 @@ __global__ __launch_bounds__(NT) void zl_instance_general_kernel(
                 if (status) status[b] = (int)flags;
             }
             for (int p = tid; p < P; p += NT)
-                iters[(i64)b * P + p] = zl_iters(inst + (size_t)p * R, R, bar);
+                iters[(i64)b * P + p] = zl_iters_of(inst, ends.le, ends.iv, p, R, bar);
         }
     }
 }
@@ -1349,32 +1391,43 @@ __global__ __launch_bounds__(NT) void zl_instance_general_kernel(
 // zl_bounds: per-instance base, range, thr and the fine-bin grid.
 template <int NT>
 __global__ __launch_bounds__(NT) void zl_bounds_kernel(
-    const i64* __restrict__ ts, int P, int R, int bins,
-    InstInfo* __restrict__ info, int* __restrict__ status)
+    const i64* __restrict__ ts, const i64* __restrict__ le, const i64* __restrict__ iv, int P, int R, int bins,
+    InstInfo* __restrict__ info, uint2* __restrict__ rowpar, int* __restrict__ status)
 {
     __shared__ i64 red[NT / WAVE];
     const int tid = threadIdx.x;
     const i64 b = blockIdx.x;
-    const i64* __restrict__ inst = ts + b * (i64)P * R;
+    Rows ends;                                        // only to read the rows' first and last entries
+    ends.inst = ts ? ts + b * (i64)P * R : nullptr;
+    ends.le = le ? le + b * (i64)P : nullptr;
+    ends.iv = iv ? iv + b * (i64)P : nullptr;
+    ends.R = R;
     i64 mn = INT64_MAX, mxf = INT64_MIN, mxl = INT64_MIN;
+    int backwards = 0;
     for (int p = tid; p < P; p += NT) {
-        const i64 f = inst[(size_t)p * R], l = inst[(size_t)p * R + R - 1];
+        const i64 f = ends.value(p, 0), l = ends.value(p, (u32)R - 1);
         mn = f < mn ? f : mn;
         mxf = f > mxf ? f : mxf;
         mxl = l > mxl ? l : mxl;
+        if (!ends.inst && R > 1 && ends.iv[p] < 0) backwards = 1;     // predicted rows: a negative interval
     }
     const i64 base = block_reduce<i64, NT>(mn, red, OpMin());
     const i64 first_max = block_reduce<i64, NT>(mxf, red, OpMax());
     const i64 last_max = block_reduce<i64, NT>(mxl, red, OpMax());
+    backwards = __syncthreads_or(backwards);
+    if (rowpar)                                       // predicted rows, for the window gather: low words of the first value and the interval
+        for (int p = tid; p < P; p += NT)
+            rowpar[b * (i64)P + p] = make_uint2((u32)(u64)ends.value(p, 0), (u32)ends.iv[p]);
     if (tid == 0) {
         InstInfo ii;
         ii.base = base;
         ii.range = (u64)last_max - (u64)base;
         ii.thr = (u64)first_max - (u64)base;
         ii.nwin = 0;
-        ii.flags = 0;
+        ii.flags = backwards ? (u32)EBSP_STATUS_UNSORTED : 0u;
         ii.pad_ = 0;
         if (ii.range > (u64)INT64_MAX / (u64)P) ii.flags |= EBSP_STATUS_OVERFLOW;
+        if (backwards) ii.range = 0;                  // nothing downstream may rely on such rows
         // bins are equal slices of [0, range >> wshift]: inv = bins * 2^32 / (top + 1), capped to 32 bits
         const int bl = bit_length(ii.range);
         ii.wshift = bl > 32 ? (u32)(bl - 32) : 0u;
@@ -1424,6 +1477,40 @@ __global__ __launch_bounds__(NT) void zl_partition_kernel(
     if (__any(bad) && lane == 0 && status) atomicOr(status + b, (int)EBSP_STATUS_UNSORTED);
     const int last_bin = (int)fine_bin((u64)row[R - 1] - base, ii);
     for (int k = last_bin + 1 + lane; k <= (int)ii.nb; k += WAVE) out[k] = (CT)R;
+}
+
+// zl_partition for predicted rows: the same crossing indices from arithmetic.  Row p
+// holds first + i * step (i < R, relative to the instance's base); the entries in
+// fine bins below k are those below the first value of bin k.  One thread per bin
+// (consecutive threads write consecutive indices of a row), looping over the rows.
+template <class CT>
+__global__ __launch_bounds__(256) void zl_partition_pred_kernel(
+    const i64* __restrict__ le, const i64* __restrict__ iv, int P, int R,
+    const InstInfo* __restrict__ info, CT* __restrict__ cross, int stride)
+{
+    const u32 kblocks = (u32)(stride + 255) / 256;
+    const i64 b = blockIdx.x / kblocks;
+    const int k = (int)(blockIdx.x % kblocks) * 256 + (int)threadIdx.x;
+    const InstInfo ii = info[b];
+    if (k > (int)ii.nb) return;
+    const bool broken = (ii.flags & EBSP_STATUS_UNSORTED) != 0;      // a negative interval: indices stay zero
+    const u64 edge = k >= (int)ii.nb ? U64_MAX : fine_bin_start((u32)k, ii);   // bin nb: everything lies below
+    const i64* __restrict__ lep = le + b * (i64)P;
+    const i64* __restrict__ ivp = iv + b * (i64)P;
+    CT* __restrict__ out = cross + (b * (i64)P) * stride + k;
+    const bool narrow_values = (ii.range >> 32) == 0;
+    for (int p = 0; p < P; ++p) {
+        const u64 step = (u64)ivp[p];
+        const u64 first = (u64)lep[p] + step - (u64)ii.base;
+        u64 below;                                                   // entries with first + i * step < edge
+        if (broken) below = 0;
+        else if (edge == U64_MAX) below = (u64)R;
+        else if (edge <= first) below = 0;
+        else if (step == 0) below = (u64)R;
+        else if (narrow_values && (step >> 32) == 0) below = (u64)(((u32)(edge - first) - 1u) / (u32)step) + 1u;
+        else below = (edge - first - 1) / step + 1;
+        out[(i64)p * stride] = (CT)(below < (u64)R ? below : (u64)R);
+    }
 }
 
 // zl_bincount: below[b][k] ~ number of keys of instance b under fine bin k, k = 0..nb:
@@ -1531,7 +1618,8 @@ struct WinPos {
 };
 
 // Window j of instance b (b < B); `ii` must be info[b].
-__device__ __forceinline__ WinPos locate_window(i64 b, int j, const InstInfo& ii, const i64* ts, int P, int R,
+__device__ __forceinline__ WinPos locate_window(i64 b, int j, const InstInfo& ii, const i64* ts,
+                                                const i64* le, const i64* iv, int P, int R,
                                                 const void* cross, bool narrow, int stride,
                                                 const u32* winstart, const WinVal* winval, int max_win)
 {
@@ -1542,7 +1630,9 @@ __device__ __forceinline__ WinPos locate_window(i64 b, int j, const InstInfo& ii
     if (j >= (int)ii.nwin) return w;
     const u32* ws = winstart + b * (i64)(max_win + 1);
     const WinVal wv = winval[b * (i64)max_win + j];
-    w.rw.inst = ts + b * (i64)P * R;
+    w.rw.inst = ts ? ts + b * (i64)P * R : nullptr;
+    w.rw.le = le ? le + b * (i64)P : nullptr;
+    w.rw.iv = iv ? iv + b * (i64)P : nullptr;
     w.rw.P = P; w.rw.R = R; w.rw.base = (u64)ii.base;
     w.rw.cr = narrow ? (const void*)((const unsigned short*)cross + (b * (i64)P) * stride)
                      : (const void*)((const u32*)cross + (b * (i64)P) * stride);
@@ -1563,7 +1653,7 @@ __device__ __forceinline__ WinPos locate_window(i64 b, int j, const InstInfo& ii
 
 // The fast search of one window (see zl_window_kernel); lo/hi hold the index
 // ranges of the thread's first ROWS_PER_THREAD<NT> rows.
-template <int NT, int ITEMS, class CT>
+template <int NT, int ITEMS, class CT, bool PRED>
 __device__ __forceinline__ void window_search(const Smem& sm, const Rows& rw, const WinVal& wv, const InstInfo& ii, bool hot,
                                               const u32 (&lo)[ROWS_PER_THREAD<NT>], const u32 (&hi)[ROWS_PER_THREAD<NT>],
                                               Partial* __restrict__ out)
@@ -1581,7 +1671,7 @@ __device__ __forceinline__ void window_search(const Smem& sm, const Rows& rw, co
         if (!defer) {
             u32 key[ITEMS], dl[ITEMS];
             u64 w0 = 0;
-            const int total = zl_delta_rows<NT, ITEMS, CT>(sm, rw, wv.A, H::CAP, lo, hi, key, dl, w0);
+            const int total = zl_delta_rows<NT, ITEMS, CT, PRED>(sm, rw, wv.A, H::CAP, lo, hi, key, dl, w0);
             defer = total > H::CAP;
             if (!defer && total > 0) {
                 u32 bkey;
@@ -1609,9 +1699,9 @@ __device__ __forceinline__ void window_search(const Smem& sm, const Rows& rw, co
 // to zl_window_general_kernel.  A window's upper crossings are the next
 // window's lower ones, and those of the window after are fetched while the
 // current one is being searched.
-template <int NT, int ITEMS, class CT>
+template <int NT, int ITEMS, class CT, bool PRED>
 __global__ __launch_bounds__(NT, 4) void zl_window_kernel(
-    const i64* __restrict__ ts, i64 B, int P, int R,
+    const i64* __restrict__ ts, const uint2* __restrict__ rowpar, i64 B, int P, int R,
     const InstInfo* __restrict__ info, const CT* __restrict__ cross, int stride,
     const u32* __restrict__ winstart, const WinVal* __restrict__ winval, int max_win, u32 groups, u32 groups_inv,
     Partial* __restrict__ partial)
@@ -1638,7 +1728,9 @@ __global__ __launch_bounds__(NT, 4) void zl_window_kernel(
     Partial* out = partial + b * (i64)max_win;
     const bool hot = !(ii.range >> 32) && (u64)P * (u64)R < HOT_MAX_ENTRIES;
     Rows rw;
-    rw.inst = ts + b * (i64)P * R;
+    rw.inst = PRED ? nullptr : ts + b * (i64)P * R;
+    rw.le = nullptr; rw.iv = nullptr;
+    rw.par = PRED ? rowpar + b * (i64)P : nullptr;
     rw.P = P; rw.R = R; rw.base = (u64)ii.base;
     rw.cr = (const void*)(cross + (b * (i64)P) * stride);
     rw.narrow = sizeof(CT) == 2;
@@ -1670,7 +1762,7 @@ __global__ __launch_bounds__(NT, 4) void zl_window_kernel(
             if (hot && i + 1 < W && j0 + i + 1 < jend) load_column<NT, CT>(rw, bins[i + 1 < W ? i + 2 : W], next);
             rw.k0 = bins[i];
             rw.k1 = bins[i + 1] > bins[i] ? bins[i + 1] : bins[i];
-            window_search<NT, ITEMS, CT>(sm, rw, vals[i], ii, hot, lo, hi, out + j0 + i);
+            window_search<NT, ITEMS, CT, PRED>(sm, rw, vals[i], ii, hot, lo, hi, out + j0 + i);
 #pragma unroll
             for (int c = 0; c < RPT; ++c) { lo[c] = hi[c]; hi[c] = next[c]; }
         }
@@ -1682,7 +1774,7 @@ __global__ __launch_bounds__(NT, 4) void zl_window_kernel(
 // deferred marks and handles the marked windows one after the other.
 template <int NT, int ITEMS>
 __global__ __launch_bounds__(NT) void zl_window_general_kernel(
-    const i64* __restrict__ ts, i64 B, int P, int R,
+    const i64* __restrict__ ts, const i64* __restrict__ le, const i64* __restrict__ iv, i64 B, int P, int R,
     const InstInfo* __restrict__ info, const void* __restrict__ cross, bool narrow, int stride,
     const u32* __restrict__ winstart, const WinVal* __restrict__ winval, int max_win,
     Partial* __restrict__ partial, int* __restrict__ status)
@@ -1708,7 +1800,7 @@ __global__ __launch_bounds__(NT) void zl_window_general_kernel(
             if (pick == idx) mine = false;
             const i64 pb = pick / (u32)max_win;
             const InstInfo ii = info[pb];
-            const WinPos w = locate_window(pb, (int)(pick % (u32)max_win), ii, ts, P, R, cross, narrow, stride,
+            const WinPos w = locate_window(pb, (int)(pick % (u32)max_win), ii, ts, le, iv, P, R, cross, narrow, stride,
                                            winstart, winval, max_win);
             u64 bw = U64_MAX, bb = 0;
             int bad = 0;
@@ -2022,7 +2114,7 @@ __global__ __launch_bounds__(NT) void zl_range_instance_kernel(
         flags |= EBSP_STATUS_UNSUPPORTED;
     } else {
         Rows rw;
-        rw.inst = inst; rw.P = P; rw.R = R; rw.base = (u64)base;
+        rw.inst = inst; rw.le = nullptr; rw.iv = nullptr; rw.P = P; rw.R = R; rw.base = (u64)base;
         rw.cr = nullptr; rw.narrow = false; rw.stride = 0; rw.k0 = rw.k1 = 0;
         zl_range_window<NT, ITEMS>(sm, rw, thr, 0ull, range, best_d, best_rel, bad);
     }
@@ -2055,7 +2147,7 @@ __global__ __launch_bounds__(NT) void zl_range_window_kernel(
     if (b >= B) return;
     const InstInfo ii = info[b];
     if (j >= (int)ii.nwin) return;
-    const WinPos w = locate_window(b, j, ii, ts, P, R, cross, narrow, stride, winstart, winval, max_win);
+    const WinPos w = locate_window(b, j, ii, ts, nullptr, nullptr, P, R, cross, narrow, stride, winstart, winval, max_win);
     Partial r;
     r.wait = U64_MAX;
     r.brel = 0;
@@ -2075,7 +2167,7 @@ __global__ __launch_bounds__(NT) void zl_range_window_kernel(
 // (first minimum: smaller wait, then earlier barrier), then count iterations.
 template <int NT>
 __global__ __launch_bounds__(NT) void zl_finish_kernel(
-    const i64* __restrict__ ts, int P, int R,
+    const i64* __restrict__ ts, const i64* __restrict__ le, const i64* __restrict__ iv, int P, int R,
     const InstInfo* __restrict__ info, const Partial* __restrict__ partial, int max_win,
     i64* __restrict__ barrier, int* __restrict__ iters, i64* __restrict__ wait)
 {
@@ -2105,7 +2197,9 @@ __global__ __launch_bounds__(NT) void zl_finish_kernel(
     const i64 bar = (i64)((u64)ii.base + bb);
     if (pblk == 0 && tid == 0) { barrier[b] = bar; wait[b] = (i64)bw; }
     const int p = pblk * NT + tid;
-    if (p < P) iters[b * (i64)P + p] = zl_iters(ts + (b * (i64)P + p) * (i64)R, R, bar);
+    if (p < P)
+        iters[b * (i64)P + p] = zl_iters_of(ts ? ts + b * (i64)P * R : nullptr, le ? le + b * (i64)P : nullptr,
+                                            iv ? iv + b * (i64)P : nullptr, p, R, bar);
 }
 
 // Plain streaming copy of n 16-byte words: the yardstick that HBM byte counters
@@ -2128,11 +2222,12 @@ int fail(int code, const char* msg)
 }
 
 enum KernelId { K_INSTANCE = 0, K_INSTANCE_GENERAL, K_BOUNDS, K_PARTITION, K_BINCOUNT, K_PLAN, K_WINDOW,
-                K_WINDOW_GENERAL, K_FINISH, K_COPY, K_RANGE_INSTANCE, K_RANGE_WINDOW, K_COUNT };
+                K_WINDOW_GENERAL, K_FINISH, K_COPY, K_RANGE_INSTANCE, K_RANGE_WINDOW, K_PARTITION_PRED, K_COUNT };
 const char* const kKernelNames[K_COUNT] = {
     "zl_instance_kernel", "zl_instance_general_kernel", "zl_bounds_kernel", "zl_partition_kernel",
     "zl_bincount_kernel", "zl_plan_kernel", "zl_window_kernel", "zl_window_general_kernel",
-    "zl_finish_kernel", "zl_copy_kernel", "zl_range_instance_kernel", "zl_range_window_kernel"};
+    "zl_finish_kernel", "zl_copy_kernel", "zl_range_instance_kernel", "zl_range_window_kernel",
+    "zl_partition_pred_kernel"};
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -2152,7 +2247,7 @@ struct Plan {
     int max_win;       // windows per instance <= max_win
     bool narrow;       // crossing indices fit 16 bits
     int step;          // zl_bincount looks at every step-th row
-    size_t off_info, off_cross, off_below, off_winstart, off_winval, off_partial, bytes;
+    size_t off_info, off_cross, off_below, off_winstart, off_winval, off_partial, off_rowpar, bytes;
 };
 
 // single_limit: the most entries one workgroup takes whole on the path the plan is for
@@ -2183,6 +2278,7 @@ bool make_plan(i64 B, int P, int R, Plan& pl, int single_limit = SINGLE_MAX, int
     pl.off_winstart = o; o = align_up(o + (size_t)B * (pl.max_win + 1) * sizeof(u32), 256);
     pl.off_winval = o;   o = align_up(o + (size_t)B * pl.max_win * sizeof(WinVal), 256);
     pl.off_partial = o;  o = align_up(o + (size_t)B * pl.max_win * sizeof(Partial), 256);
+    pl.off_rowpar = o;   o = align_up(o + (size_t)B * P * sizeof(uint2), 256);      // predicted rows only
     pl.bytes = o;
     return true;
 }
@@ -2216,30 +2312,38 @@ hipEvent_t* prof_slot(int kid, int which)
         }                                                                                  \
     } while (0)
 
-int run_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters, i64* wait, int* status,
+// The rows are either stored (ts != nullptr) or predicted: t[p][i] = le[p] + (i + 1) * iv[p] (ts == nullptr).
+int run_batch(const i64* ts, const i64* le, const i64* iv, i64 B, int P, int R,
+              i64* barrier, int* iters, i64* wait, int* status,
               void* workspace, size_t workspace_bytes, hipStream_t st)
 {
     Plan pl;
     if (!make_plan(B, P, R, pl)) return fail(EBSP_ERR_SHAPE, "invalid shape: need B >= 0, P >= 1, R >= 1, P*R < 2^31");
     if (B == 0) return EBSP_OK;
-    if (!ts || !barrier || !iters || !wait) return fail(EBSP_ERR_NULL, "ts, barrier, iters and wait must not be NULL");
+    const bool pred = ts == nullptr;
+    if ((pred && (!le || !iv)) || !barrier || !iters || !wait)
+        return fail(EBSP_ERR_NULL, "the input arrays, barrier, iters and wait must not be NULL");
     if (B > 0x7fffffffll) return fail(EBSP_ERR_SHAPE, "B must be below 2^31");
     const int n = P * R;
 
     if (!pl.multi) {
         const int rshift = (R & (R - 1)) == 0 ? __builtin_ctz((unsigned)R) : -1;
         const dim3 grid((unsigned)B);
-        if (n <= 256)
-            LAUNCH(K_INSTANCE, (zl_instance_kernel<128, 2>), grid, dim3(128), ts, P, R, rshift, barrier, iters, wait, status);
-        else if (n <= 1024)
-            LAUNCH(K_INSTANCE, (zl_instance_kernel<256, 4>), grid, dim3(256), ts, P, R, rshift, barrier, iters, wait, status);
-        else if (n <= 4096)
-            LAUNCH(K_INSTANCE, (zl_instance_kernel<512, 8>), grid, dim3(512), ts, P, R, rshift, barrier, iters, wait, status);
-        else
-            LAUNCH(K_INSTANCE, (zl_instance_kernel<1024, 16>), grid, dim3(1024), ts, P, R, rshift, barrier, iters, wait, status);
+#define LAUNCH_INSTANCE(NT_, ITEMS_)                                                                        \
+    do {                                                                                                    \
+        if (pred) LAUNCH(K_INSTANCE, (zl_instance_kernel<NT_, ITEMS_, true>), grid, dim3(NT_), ts, le, iv, P, R, rshift, \
+                         barrier, iters, wait, status);                                                     \
+        else LAUNCH(K_INSTANCE, (zl_instance_kernel<NT_, ITEMS_, false>), grid, dim3(NT_), ts, le, iv, P, R, rshift, \
+                    barrier, iters, wait, status);                                                          \
+    } while (0)
+        if (n <= 256) LAUNCH_INSTANCE(128, 2);
+        else if (n <= 1024) LAUNCH_INSTANCE(256, 4);
+        else if (n <= 4096) LAUNCH_INSTANCE(512, 8);
+        else LAUNCH_INSTANCE(1024, 16);
+#undef LAUNCH_INSTANCE
         LAUNCH(K_INSTANCE_GENERAL, (zl_instance_general_kernel<LARGE_NT, LARGE_ITEMS>),
                dim3((unsigned)(B < GENERAL_GRID ? B : GENERAL_GRID)), dim3(LARGE_NT),
-               ts, B, P, R, barrier, iters, wait, status);
+               ts, le, iv, B, P, R, barrier, iters, wait, status);
         return EBSP_OK;
     }
 
@@ -2256,17 +2360,25 @@ int run_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters, i64*
     u32* winstart = (u32*)(wsp + pl.off_winstart);
     WinVal* winval = (WinVal*)(wsp + pl.off_winval);
     Partial* partial = (Partial*)(wsp + pl.off_partial);
+    uint2* rowpar = pred ? (uint2*)(wsp + pl.off_rowpar) : nullptr;
 
-    LAUNCH(K_BOUNDS, (zl_bounds_kernel<256>), dim3((unsigned)B), dim3(256), ts, P, R, pl.bins, info, status);
+    LAUNCH(K_BOUNDS, (zl_bounds_kernel<256>), dim3((unsigned)B), dim3(256), ts, le, iv, P, R, pl.bins, info, rowpar, status);
     const i64 nrows = B * (i64)P;
-    if (pl.narrow)
+    const i64 kblocks = (pl.stride + 63) / 64, pblocks = (P + 255) / 256, kblocks256 = (pl.stride + 255) / 256;
+    if (kblocks * B > 0x7fffffffll || pblocks * B > 0x7fffffffll) return fail(EBSP_ERR_SHAPE, "batch too large for one call");
+    if (pred) {
+        if (pl.narrow)
+            LAUNCH(K_PARTITION_PRED, zl_partition_pred_kernel<unsigned short>, dim3((unsigned)(kblocks256 * B)), dim3(256),
+                   le, iv, P, R, info, (unsigned short*)cross, pl.stride);
+        else
+            LAUNCH(K_PARTITION_PRED, zl_partition_pred_kernel<u32>, dim3((unsigned)(kblocks256 * B)), dim3(256),
+                   le, iv, P, R, info, (u32*)cross, pl.stride);
+    } else if (pl.narrow)
         LAUNCH(K_PARTITION, (zl_partition_kernel<256, unsigned short>), dim3((unsigned)((nrows + 3) / 4)), dim3(256),
                ts, nrows, P, R, info, (unsigned short*)cross, pl.stride, status);
     else
         LAUNCH(K_PARTITION, (zl_partition_kernel<256, u32>), dim3((unsigned)((nrows + 3) / 4)), dim3(256),
                ts, nrows, P, R, info, (u32*)cross, pl.stride, status);
-    const i64 kblocks = (pl.stride + 63) / 64, pblocks = (P + 255) / 256;
-    if (kblocks * B > 0x7fffffffll || pblocks * B > 0x7fffffffll) return fail(EBSP_ERR_SHAPE, "batch too large for one call");
     if (pl.narrow)
         LAUNCH(K_BINCOUNT, zl_bincount_kernel<unsigned short>, dim3((unsigned)(kblocks * B)), dim3(256),
                (const unsigned short*)cross, P, R, pl.stride, pl.step, info, below);
@@ -2278,9 +2390,13 @@ int run_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters, i64*
     const u32 groups = (u32)(pl.max_win / WINDOWS_PER_BLOCK);
     const u32 groups_inv = groups > 1 ? (u32)((1ull << 32) / groups) : 0xffffffffu;
     const unsigned wgrid = (unsigned)((B * (i64)groups + 7) / 8 * 8);
-#define LAUNCH_WINDOW(NT_, CT_)                                                                          \
-    LAUNCH(K_WINDOW, (zl_window_kernel<NT_, 16, CT_>), dim3(wgrid), dim3(NT_), ts, B, P, R, info,      \
-           (const CT_*)cross, pl.stride, winstart, winval, pl.max_win, groups, groups_inv, partial)
+#define LAUNCH_WINDOW(NT_, CT_)                                                                              \
+    do {                                                                                                     \
+        if (pred) LAUNCH(K_WINDOW, (zl_window_kernel<NT_, 16, CT_, true>), dim3(wgrid), dim3(NT_), ts, rowpar, B, P, R, info, \
+                         (const CT_*)cross, pl.stride, winstart, winval, pl.max_win, groups, groups_inv, partial); \
+        else LAUNCH(K_WINDOW, (zl_window_kernel<NT_, 16, CT_, false>), dim3(wgrid), dim3(NT_), ts, rowpar, B, P, R, info, \
+                    (const CT_*)cross, pl.stride, winstart, winval, pl.max_win, groups, groups_inv, partial);  \
+    } while (0)
     if (pl.cap == 16384) {
         if (pl.narrow) LAUNCH_WINDOW(1024, unsigned short); else LAUNCH_WINDOW(1024, u32);
     } else if (pl.cap == 8192) {
@@ -2291,9 +2407,9 @@ int run_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters, i64*
 #undef LAUNCH_WINDOW
     LAUNCH(K_WINDOW_GENERAL, (zl_window_general_kernel<LARGE_NT, LARGE_ITEMS>),
            dim3((unsigned)(total_win < GENERAL_GRID ? total_win : GENERAL_GRID)), dim3(LARGE_NT),
-           ts, B, P, R, info, cross, pl.narrow, pl.stride, winstart, winval, pl.max_win, partial, status);
+           ts, le, iv, B, P, R, info, cross, pl.narrow, pl.stride, winstart, winval, pl.max_win, partial, status);
     LAUNCH(K_FINISH, (zl_finish_kernel<256>), dim3((unsigned)(pblocks * B)), dim3(256),
-           ts, P, R, info, partial, pl.max_win, barrier, iters, wait);
+           ts, le, iv, P, R, info, partial, pl.max_win, barrier, iters, wait);
     return EBSP_OK;
 }
 
@@ -2330,7 +2446,8 @@ int run_range_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters
     WinVal* winval = (WinVal*)(wsp + pl.off_winval);
     Partial* partial = (Partial*)(wsp + pl.off_partial);
 
-    LAUNCH(K_BOUNDS, (zl_bounds_kernel<256>), dim3((unsigned)B), dim3(256), ts, P, R, pl.bins, info, status);
+    LAUNCH(K_BOUNDS, (zl_bounds_kernel<256>), dim3((unsigned)B), dim3(256), ts, nullptr, nullptr, P, R, pl.bins, info,
+           nullptr, status);
     const i64 nrows = B * (i64)P;
     if (pl.narrow)
         LAUNCH(K_PARTITION, (zl_partition_kernel<256, unsigned short>), dim3((unsigned)((nrows + 3) / 4)), dim3(256),
@@ -2351,7 +2468,7 @@ int run_range_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters
     LAUNCH(K_RANGE_WINDOW, (zl_range_window_kernel<512, 16>), dim3((unsigned)total_win), dim3(512),
            ts, B, P, R, info, cross, pl.narrow, pl.stride, winstart, winval, pl.max_win, partial, status);
     LAUNCH(K_FINISH, (zl_finish_kernel<256>), dim3((unsigned)(pblocks * B)), dim3(256),
-           ts, P, R, info, partial, pl.max_win, barrier, iters, dmin);
+           ts, nullptr, nullptr, P, R, info, partial, pl.max_win, barrier, iters, dmin);
     return EBSP_OK;
 }
 
@@ -2370,8 +2487,20 @@ int ebsp_zipline_batch(const int64_t* ts, int64_t B, int32_t P, int32_t R,
                        int64_t* barrier, int32_t* iters, int64_t* wait,
                        int32_t* status, void* workspace, size_t workspace_bytes, void* stream)
 {
-    const int rc = run_batch((const i64*)ts, B, P, R, (i64*)barrier, iters, (i64*)wait, status,
+    if (!ts && B > 0) return fail(EBSP_ERR_NULL, "ts must not be NULL");
+    const int rc = run_batch((const i64*)ts, nullptr, nullptr, B, P, R, (i64*)barrier, iters, (i64*)wait, status,
                              workspace, workspace_bytes, (hipStream_t)stream);
+    if (g_prof.on && rc == EBSP_OK && B > 0 && g_prof.calls < g_prof.max_calls) ++g_prof.calls;
+    return rc;
+}
+
+int ebsp_predict_zipline_batch(const int64_t* last_end, const int64_t* interval, int64_t B, int32_t P, int32_t R,
+                               int64_t* barrier, int32_t* iters, int64_t* wait,
+                               int32_t* status, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if ((!last_end || !interval) && B > 0) return fail(EBSP_ERR_NULL, "last_end and interval must not be NULL");
+    const int rc = run_batch(nullptr, (const i64*)last_end, (const i64*)interval, B, P, R, (i64*)barrier, iters,
+                             (i64*)wait, status, workspace, workspace_bytes, (hipStream_t)stream);
     if (g_prof.on && rc == EBSP_OK && B > 0 && g_prof.calls < g_prof.max_calls) ++g_prof.calls;
     return rc;
 }

@@ -119,6 +119,44 @@ def make(k: int, instances: Optional[Iterable[int]] = None, shift: int = 0,
     return out
 
 
+def make_predicted(k: int, instances: Optional[Iterable[int]] = None, shift: int = 0):
+    """Inputs of the fused prediction for configuration ``k``: ``(last_end[n, P], interval[n, P])`` int64.
+
+    Worker p's interval is its mean iteration time of the configuration (the same
+    distribution of means, stragglers and rounding as :func:`make`), its last end
+    timestamp the configuration's random offset; the predicted rows are
+    ``last_end + (i + 1) * interval``.  Instance ``b`` uses its own seeded stream.
+    """
+    cfg = CONFIGS[k]
+    ids = list(range(cfg.B)) if instances is None else [int(b) for b in instances]
+    le = np.empty((len(ids), cfg.P), dtype=np.int64)
+    iv = np.empty((len(ids), cfg.P), dtype=np.int64)
+    for j, b in enumerate(ids):
+        if not 0 <= b < cfg.B:
+            raise ValueError(f"instance {b} outside [0, {cfg.B})")
+        rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([SEED_BASE + 100 + cfg.k, b])))
+        P = cfg.P
+        if cfg.bimodal:
+            slow = rng.random(P) >= 0.8
+            mu = np.where(slow, rng.uniform(200.0, 300.0, P), rng.uniform(90.0, 110.0, P))
+        else:
+            mu = rng.uniform(cfg.mu_lo, cfg.mu_hi, P)
+        if cfg.stragglers:
+            who = rng.choice(P, size=cfg.stragglers, replace=False)
+            mu[who] *= rng.uniform(1.5, 3.0, cfg.stragglers)
+        off = rng.random(P) * (mu if cfg.offset_hi_ms is None else cfg.offset_hi_ms)
+        q = max(1, cfg.round_to_us)
+        iv[j] = np.maximum((np.rint(mu * 1000.0).astype(np.int64) + q // 2) // q * q, 1)
+        le[j] = (np.rint(off * 1000.0).astype(np.int64) + q // 2) // q * q + shift
+    return le, iv
+
+
+def predicted_rows(last_end: np.ndarray, interval: np.ndarray, R: int) -> np.ndarray:
+    """The rows the fused prediction stands for: t[b, p, i] = last_end[b, p] + (i + 1) * interval[b, p]."""
+    i = np.arange(1, R + 1, dtype=np.int64)
+    return last_end[..., None] + interval[..., None] * i
+
+
 def random_small(rng: np.random.Generator, P: int, R: int, lo: int = 1, hi: int = 20,
                  ties: bool = False) -> np.ndarray:
     """A small random instance [P, R]: cumulative sums of integer steps in [lo, hi].

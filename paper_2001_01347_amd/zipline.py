@@ -21,7 +21,7 @@ EBSP_OK = 0
 STATUS_OK, STATUS_UNSORTED, STATUS_OVERFLOW, STATUS_UNSUPPORTED = 0, 1, 2, 4
 
 EXPORTS = ("ebsp_zipline_workspace_bytes", "ebsp_zipline_batch", "ebsp_zipline_range_workspace_bytes",
-           "ebsp_zipline_range_batch", "ebsp_zipline_tune", "ebsp_zipline_shape_info", "ebsp_zipline_profile_begin",
+           "ebsp_zipline_range_batch", "ebsp_predict_zipline_batch", "ebsp_zipline_tune", "ebsp_zipline_shape_info", "ebsp_zipline_profile_begin",
            "ebsp_zipline_profile_end", "ebsp_zipline_copy_probe", "ebsp_zipline_kernel_count",
            "ebsp_zipline_kernel_name", "ebsp_last_error")
 
@@ -50,6 +50,8 @@ def load() -> ctypes.CDLL:
         lib.ebsp_zipline_range_workspace_bytes.argtypes = [i64, i32, i32]
         lib.ebsp_zipline_range_batch.restype = ctypes.c_int
         lib.ebsp_zipline_range_batch.argtypes = common
+        lib.ebsp_predict_zipline_batch.restype = ctypes.c_int
+        lib.ebsp_predict_zipline_batch.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
         lib.ebsp_zipline_shape_info.restype = ctypes.c_int
         lib.ebsp_zipline_shape_info.argtypes = [i64, i32, i32, ctypes.POINTER(ctypes.c_int64)]
         lib.ebsp_zipline_tune.restype = ctypes.c_int
@@ -162,6 +164,46 @@ def ebsp_zipline_range_batch(ts: torch.Tensor, barrier: Optional[torch.Tensor] =
     if rc != EBSP_OK:
         raise ZipLineError(f"ebsp_zipline_range_batch failed ({rc}): {ebsp_last_error()}")
     return outs
+
+
+def ebsp_predict_zipline_batch(last_end: torch.Tensor, interval: torch.Tensor, R: int,
+                               barrier: Optional[torch.Tensor] = None, iters: Optional[torch.Tensor] = None,
+                               wait: Optional[torch.Tensor] = None, status: Optional[torch.Tensor] = None,
+                               workspace: Optional[torch.Tensor] = None):
+    """The search over predicted rows ``last_end[b, p] + (i + 1) * interval[b, p]``, i < R; see the header.
+
+    ``last_end`` and ``interval`` are contiguous int64 CUDA tensors of shape [B, P].
+    Returns ``(barrier[B], iters[B, P], wait[B], status[B])`` device tensors.  Does not synchronise.
+    """
+    for t in (last_end, interval):
+        if t.dim() != 2 or t.dtype != torch.int64 or not t.is_cuda or not t.is_contiguous():
+            raise ValueError("last_end and interval must be contiguous int64 CUDA tensors of shape [B, P]")
+    if last_end.shape != interval.shape or last_end.device != interval.device:
+        raise ValueError("last_end and interval must have the same shape and device")
+    B, P = (int(x) for x in last_end.shape)
+    R = int(R)
+    dev = last_end.device
+    if barrier is None:
+        barrier = torch.empty(B, dtype=torch.int64, device=dev)
+    if iters is None:
+        iters = torch.empty((B, P), dtype=torch.int32, device=dev)
+    if wait is None:
+        wait = torch.empty(B, dtype=torch.int64, device=dev)
+    if status is None:
+        status = torch.empty(B, dtype=torch.int32, device=dev)
+    need = ebsp_zipline_workspace_bytes(B, P, R)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    with torch.cuda.device(dev):
+        rc = load().ebsp_predict_zipline_batch(last_end.data_ptr(), interval.data_ptr(), B, P, R,
+                                               barrier.data_ptr(), iters.data_ptr(), wait.data_ptr(),
+                                               status.data_ptr(), ws_ptr, ws_len,
+                                               torch.cuda.current_stream(dev).cuda_stream)
+    if rc != EBSP_OK:
+        raise ZipLineError(f"ebsp_predict_zipline_batch failed ({rc}): {ebsp_last_error()}")
+    return barrier, iters, wait, status
 
 
 def ebsp_zipline_copy_probe(src: torch.Tensor, dst: torch.Tensor) -> None:
