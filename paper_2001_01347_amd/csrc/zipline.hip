@@ -1483,6 +1483,7 @@ __global__ __launch_bounds__(NT) void zl_partition_kernel(
 // holds first + i * step (i < R, relative to the instance's base); the entries in
 // fine bins below k are those below the first value of bin k.  One thread per bin
 // (consecutive threads write consecutive indices of a row), looping over the rows.
+constexpr int PRED_ROWS_PER_BLOCK = 64;
 template <class CT>
 __global__ __launch_bounds__(256) void zl_partition_pred_kernel(
     const i64* __restrict__ le, const i64* __restrict__ iv, int P, int R,
@@ -1491,6 +1492,8 @@ __global__ __launch_bounds__(256) void zl_partition_pred_kernel(
     const u32 kblocks = (u32)(stride + 255) / 256;
     const i64 b = blockIdx.x / kblocks;
     const int k = (int)(blockIdx.x % kblocks) * 256 + (int)threadIdx.x;
+    const int p_begin = (int)blockIdx.y * PRED_ROWS_PER_BLOCK;           // a slice of the rows per workgroup
+    const int p_end = p_begin + PRED_ROWS_PER_BLOCK < P ? p_begin + PRED_ROWS_PER_BLOCK : P;
     const InstInfo ii = info[b];
     if (k > (int)ii.nb) return;
     const bool broken = (ii.flags & EBSP_STATUS_UNSORTED) != 0;      // a negative interval: indices stay zero
@@ -1499,7 +1502,7 @@ __global__ __launch_bounds__(256) void zl_partition_pred_kernel(
     const i64* __restrict__ ivp = iv + b * (i64)P;
     CT* __restrict__ out = cross + (b * (i64)P) * stride + k;
     const bool narrow_values = (ii.range >> 32) == 0;
-    for (int p = 0; p < P; ++p) {
+    for (int p = p_begin; p < p_end; ++p) {
         const u64 step = (u64)ivp[p];
         const u64 first = (u64)lep[p] + step - (u64)ii.base;
         u64 below;                                                   // entries with first + i * step < edge
@@ -2368,10 +2371,12 @@ int run_batch(const i64* ts, const i64* le, const i64* iv, i64 B, int P, int R,
     if (kblocks * B > 0x7fffffffll || pblocks * B > 0x7fffffffll) return fail(EBSP_ERR_SHAPE, "batch too large for one call");
     if (pred) {
         if (pl.narrow)
-            LAUNCH(K_PARTITION_PRED, zl_partition_pred_kernel<unsigned short>, dim3((unsigned)(kblocks256 * B)), dim3(256),
+            LAUNCH(K_PARTITION_PRED, zl_partition_pred_kernel<unsigned short>,
+                   dim3((unsigned)(kblocks256 * B), (unsigned)((P + PRED_ROWS_PER_BLOCK - 1) / PRED_ROWS_PER_BLOCK)), dim3(256),
                    le, iv, P, R, info, (unsigned short*)cross, pl.stride);
         else
-            LAUNCH(K_PARTITION_PRED, zl_partition_pred_kernel<u32>, dim3((unsigned)(kblocks256 * B)), dim3(256),
+            LAUNCH(K_PARTITION_PRED, zl_partition_pred_kernel<u32>,
+                   dim3((unsigned)(kblocks256 * B), (unsigned)((P + PRED_ROWS_PER_BLOCK - 1) / PRED_ROWS_PER_BLOCK)), dim3(256),
                    le, iv, P, R, info, (u32*)cross, pl.stride);
     } else if (pl.narrow)
         LAUNCH(K_PARTITION, (zl_partition_kernel<256, unsigned short>), dim3((unsigned)((nrows + 3) / 4)), dim3(256),
