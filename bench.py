@@ -46,7 +46,9 @@ def algorithmic_bytes(kernel: str, B: int, P: int, R: int, bins: int, windows: i
         return 128.0 * B * P
     if kernel == "zl_plan_kernel":
         return 4.0 * B * (bins + 1) + 4.0 * windows
-    if kernel == "zl_range_window_kernel":  # every timestamp once (a neighbour comes in the same line), crossing rows, one result
+    if kernel in ("zl_range_fast_kernel", "zl_range_window_kernel"):
+        # every timestamp once (a neighbour comes in the same line), crossing rows, one result.  The sort-based
+        # kernel only takes the windows the fast one leaves to it: priced at the whole input, its figure is a ceiling.
         return 8.0 * n + windows * (2.0 * cw * P + 16.0)
     if kernel == "zl_range_instance_kernel":
         return 8.0 * n + B * (16.0 + 4.0 * P)

@@ -1011,15 +1011,21 @@ __device__ __forceinline__ void gather_batch(const u64* recs, const char* bytes,
     }
 }
 
-template <int NT, int ITEMS, class CT, bool PRED>
-__device__ __forceinline__ int zl_delta_rows(const Smem& sm, const Rows& rw, u64 a, int cap,
+// Sweep 1 of the window gather (see above): a source word for every entry of the window in
+// its slot.  Returns the number of entries (slots beyond `cap` are not written).  For the rows
+// without an entry in the window the distances from their last value before it to the window
+// start are summed into before_sum and their maximum goes to before_max.  WITH_LAST marks a
+// row's very last entry too (stored rows only: the mark shares its bit with the row number).
+constexpr u64 LAST_OF_ROW = 1ull << 34;
+template <int NT, class CT, bool PRED, bool WITH_LAST>
+__device__ __forceinline__ int zl_place_rows(const Smem& sm, const Rows& rw, u32 start, int cap,
                                              const u32 (&lo0)[ROWS_PER_THREAD<NT>], const u32 (&hi0)[ROWS_PER_THREAD<NT>],
-                                             u32 (&key)[ITEMS], u32 (&dl)[ITEMS], u64& w0)
+                                             u64& before_sum, u32& before_max)
 {
+    static_assert(!(PRED && WITH_LAST), "the last-of-row mark is for stored rows");
     const int tid = threadIdx.x;
     u64* recs = sm.recs;
     const char* bytes = (const char*)rw.inst;
-    const u32 start = (u32)(rw.base + a);                    // low word of the window's first value
     int total = 0;
     constexpr int RPT = ROWS_PER_THREAD<NT>;
     for (int p0 = 0; p0 < rw.P; p0 += RPT * NT) {
@@ -1056,16 +1062,33 @@ __device__ __forceinline__ int zl_delta_rows(const Smem& sm, const Rows& rw, u64
                 u64 src = row | (u64)(PRED ? lo[c] : (u32)p * (u32)rw.R + lo[c]) | FIRST_OF_SEGMENT |
                           (lo[c] == 0 ? FIRST_OF_ROW : 0ull);
                 for (u32 i = lo[c]; i < hi[c] && slot < (u32)cap; ++i, ++slot) {
-                    recs[slot] = src;
+                    recs[slot] = (WITH_LAST && i + 1 == (u32)rw.R) ? (src | LAST_OF_ROW) : src;
                     src = row | (u64)((u32)src + 1u);
                 }
             }
         }
 #pragma unroll
-        for (int c = 0; c < RPT; ++c) w0 += (u64)(start - before[c]);     // below 2^32 like every relative value
+        for (int c = 0; c < RPT; ++c) {                      // below 2^32 like every relative value
+            const u32 gone = start - before[c];
+            before_sum += (u64)gone;
+            before_max = gone > before_max ? gone : before_max;
+        }
         total += (int)round;
     }
     __syncthreads();
+    return total;
+}
+
+template <int NT, int ITEMS, class CT, bool PRED>
+__device__ __forceinline__ int zl_delta_rows(const Smem& sm, const Rows& rw, u64 a, int cap,
+                                             const u32 (&lo0)[ROWS_PER_THREAD<NT>], const u32 (&hi0)[ROWS_PER_THREAD<NT>],
+                                             u32 (&key)[ITEMS], u32 (&dl)[ITEMS], u64& w0)
+{
+    const u64* recs = sm.recs;
+    const char* bytes = (const char*)rw.inst;
+    const u32 start = (u32)(rw.base + a);                    // low word of the window's first value
+    u32 unused = 0;
+    const int total = zl_place_rows<NT, CT, PRED, false>(sm, rw, start, cap, lo0, hi0, w0, unused);
     if (total > cap) return total;
 
     constexpr int G0 = ITEMS < GATHER_BATCH ? ITEMS : GATHER_BATCH;
@@ -1696,22 +1719,32 @@ __device__ __forceinline__ void window_search(const Smem& sm, const Rows& rw, co
     if (threadIdx.x == 0) *out = r;
 }
 
+// The summed-wait search of one window for window_pairs().
+template <int NT, int ITEMS, class CT, bool PRED>
+struct SumSearch {
+    static constexpr bool PREDICTED = PRED;
+    __device__ __forceinline__ static void run(const Smem& sm, const Rows& rw, const WinVal& wv, const InstInfo& ii, bool hot,
+                                               const u32 (&lo)[ROWS_PER_THREAD<NT>], const u32 (&hi)[ROWS_PER_THREAD<NT>],
+                                               Partial* __restrict__ out)
+    {
+        window_search<NT, ITEMS, CT, PRED>(sm, rw, wv, ii, hot, lo, hi, out);
+    }
+};
+
 // One workgroup per WINDOWS_PER_BLOCK consecutive windows of an instance; each
 // window's best candidate goes to `partial`.  Handles the normal case (32-bit
 // value spread, the window fits in LDS) and marks every other window as deferred
-// to zl_window_general_kernel.  A window's upper crossings are the next
-// window's lower ones, and those of the window after are fetched while the
-// current one is being searched.
-template <int NT, int ITEMS, class CT, bool PRED>
-__global__ __launch_bounds__(NT, 4) void zl_window_kernel(
-    const i64* __restrict__ ts, const uint2* __restrict__ rowpar, i64 B, int P, int R,
+// to the general kernel.  A window's upper crossings are the next window's lower
+// ones, and those of the window after are fetched while the current one is
+// being searched.  `Search` does one window.
+template <int NT, int ITEMS, class CT, class Search>
+__device__ __forceinline__ void window_pairs(
+    const Smem& sm, const i64* __restrict__ ts, const uint2* __restrict__ rowpar, i64 B, int P, int R,
     const InstInfo* __restrict__ info, const CT* __restrict__ cross, int stride,
     const u32* __restrict__ winstart, const WinVal* __restrict__ winval, int max_win, u32 groups, u32 groups_inv,
     Partial* __restrict__ partial)
 {
-    using H = HotCfg<NT, ITEMS, false>;       // windows use the linear bucket map: no coarse table
-    __shared__ __align__(16) unsigned char smem[H::BYTES];
-    const Smem sm = carve_hot<NT, ITEMS>(smem);
+    constexpr bool PRED = Search::PREDICTED;
     constexpr int RPT = ROWS_PER_THREAD<NT>;
     // Consecutive windows share cache lines at their segment ends: give each
     // XCD (workgroups are dealt round-robin to the 8 XCDs) a contiguous range.
@@ -1738,8 +1771,6 @@ __global__ __launch_bounds__(NT, 4) void zl_window_kernel(
     rw.cr = (const void*)(cross + (b * (i64)P) * stride);
     rw.narrow = sizeof(CT) == 2;
     rw.stride = stride;
-    // fine bins where the current window starts and ends and where the next one ends
-    // (stale scratch cannot index outside a row of cross)
     // fine bins where the windows start and end (stale scratch cannot index outside a
     // row of cross) and the windows' values: all fetched before the first search
     constexpr int W = WINDOWS_PER_BLOCK;
@@ -1765,11 +1796,25 @@ __global__ __launch_bounds__(NT, 4) void zl_window_kernel(
             if (hot && i + 1 < W && j0 + i + 1 < jend) load_column<NT, CT>(rw, bins[i + 1 < W ? i + 2 : W], next);
             rw.k0 = bins[i];
             rw.k1 = bins[i + 1] > bins[i] ? bins[i + 1] : bins[i];
-            window_search<NT, ITEMS, CT, PRED>(sm, rw, vals[i], ii, hot, lo, hi, out + j0 + i);
+            Search::run(sm, rw, vals[i], ii, hot, lo, hi, out + j0 + i);
 #pragma unroll
             for (int c = 0; c < RPT; ++c) { lo[c] = hi[c]; hi[c] = next[c]; }
         }
     }
+}
+
+template <int NT, int ITEMS, class CT, bool PRED>
+__global__ __launch_bounds__(NT, 4) void zl_window_kernel(
+    const i64* __restrict__ ts, const uint2* __restrict__ rowpar, i64 B, int P, int R,
+    const InstInfo* __restrict__ info, const CT* __restrict__ cross, int stride,
+    const u32* __restrict__ winstart, const WinVal* __restrict__ winval, int max_win, u32 groups, u32 groups_inv,
+    Partial* __restrict__ partial)
+{
+    using H = HotCfg<NT, ITEMS, false>;       // windows use the linear bucket map: no coarse table
+    __shared__ __align__(16) unsigned char smem[H::BYTES];
+    const Smem sm = carve_hot<NT, ITEMS>(smem);
+    window_pairs<NT, ITEMS, CT, SumSearch<NT, ITEMS, CT, PRED>>(sm, ts, rowpar, B, P, R, info, cross, stride, winstart,
+                                                               winval, max_win, groups, groups_inv, partial);
 }
 
 // The windows zl_window_kernel deferred: the general window search.  A small
@@ -2086,6 +2131,279 @@ __device__ __forceinline__ void zl_range_window(const Smem& sm, const Rows& rw, 
     }
 }
 
+// ---------------------------------------------------------------------------
+// The fast form of the range search for one window of the multi-window path:
+// value buckets instead of a sort, as for the summed wait.  With next(x) = the same
+// worker's next value and gone(x) = how far the worker's previous value lies
+// before the window (for a row's first entry in it; 0 otherwise),
+//   min(Z) at time c  =  - max{ gone(x) : x > c }              if that is positive
+//                        (some worker still stands before the window), else
+//                     =  min{ x <= c : next(x) > c }.
+// Per bucket b: reach(b) = max next, far(b) = max gone, both by LDS atomics while the
+// entries are gathered.  M = prefix maximum of reach, F = suffix maximum of far.  The
+// entry that is min(Z) at time c lies in the first bucket with M > c, so for every c
+// of bucket b: lo(first bucket with M > lo(b)) <= min(Z) <= hi(first bucket with M >
+// hi(b)) (or -F on either side while F > 0): an upper bound of d for some candidate of
+// the bucket and a lower bound for all of them.  Buckets whose lower bound exceeds the
+// smallest upper bound are dropped.  For the candidates that remain, and for the
+// entries of the buckets that can hold their min(Z) (buckets where M rises, between
+// the bounds of the remaining candidates), key, next and gone are read again through
+// the source words and d is evaluated exactly from that short list.
+// Returns false if the window has to be left to the sort-based search (too many
+// entries for the list to fit behind them, or too many listed).
+
+// Fine bins per group of the range plan.  Windows must leave room for the short list, and
+// with few rows (windows of 4096 slots) a fine bin of a quarter group often takes them past it.
+inline int range_fine_log2(int P) { return P >= 512 ? 2 : 3; }
+
+template <int NT, int ITEMS, class CT>
+__device__ __forceinline__ bool zl_range_bucket_search(const Smem& sm, const Rows& rw, const WinVal& wv, u64 thr,
+                                                       const u32 (&lo)[ROWS_PER_THREAD<NT>],
+                                                       const u32 (&hi)[ROWS_PER_THREAD<NT>],
+                                                       u64& best_d, u32& best_key)
+{
+    using H = HotCfg<NT, ITEMS, false>;
+    constexpr int NB = H::NB;
+    constexpr int NW = NT / WAVE;
+    static_assert(NB == 2 * NT, "two buckets per thread");
+    constexpr int RANGE_LIST_CAP = 2 * NT;                  // entries of the short list (four words each, behind the source words)
+    const int tid = threadIdx.x;
+    u64* recs = sm.recs;
+    u32* reach = (u32*)(sm.recs + H::BSUM_AT);              // NB words, later M
+    u32* far = reach + NB;                                  // NB words, later F (exclusive)
+    u32* flag = sm.cnt;                                     // NB words: entry counts, later what a bucket is kept for
+    u32* misc = (u32*)(sm.red + H::RED_WORDS - 3);          // listed holders, lowest and highest kept value, absent rows, listed others
+    reach[tid] = 0; reach[tid + NT] = 0;
+    far[tid] = 0; far[tid + NT] = 0;
+    flag[tid] = 0; flag[tid + NT] = 0;
+    if (tid == 0) { misc[0] = 0; misc[1] = 0xffffffffu; misc[2] = 0; misc[3] = 0; misc[4] = 0; }
+    const char* bytes = (const char*)rw.inst;
+    const u64 a = wv.A;
+    const u32 start = (u32)(rw.base + a);                   // low word of the window's first value
+    u64 unused = 0;
+    u32 absent = 0;
+    const int total = zl_place_rows<NT, CT, false, true>(sm, rw, start, H::CAP, lo, hi, unused, absent);
+    best_d = U64_MAX;
+    best_key = 0;
+    if (total > H::CAP - 2 * RANGE_LIST_CAP) return false;
+    if (total == 0) return true;
+    const LinearMap bucket = linear_map((u32)(wv.Elast - a), NB, wv.scale ? wv.scale : 1u, wv.inv52);
+    auto read_entry = [&](u64 src, u32& key, u32& next, u32& gone) {     // an entry through its source word
+        const u32 at = (u32)src;
+        const bool inner = (src & FIRST_OF_SEGMENT) && !(src & FIRST_OF_ROW);   // has a predecessor before the window
+        const bool last = (src & LAST_OF_ROW) != 0;
+        const u32 cur = *(const u32*)(bytes + (at << 3));
+        const u32 nxt = *(const u32*)(bytes + ((at + (last ? 0u : 1u)) << 3));
+        const u32 prv = *(const u32*)(bytes + ((at - (inner ? 1u : 0u)) << 3));
+        key = cur - start;
+        next = last ? NEVER : nxt - start;
+        gone = inner ? start - prv : 0u;
+    };
+    // sweep 2: reach, far and the entry count of every bucket; the keys stay in registers
+    u32 key[ITEMS];
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        const int q = j * NT + tid;
+        key[j] = 0;
+        if (j * NT < total) {
+            u32 next, gone;
+            read_entry(q < total ? recs[q] : (FIRST_OF_ROW | LAST_OF_ROW), key[j], next, gone);
+            if (q < total) {
+                const u32 b = bucket(key[j]);
+                atomicAdd(&flag[b], 1u);
+                atomicMax(&reach[b], next);
+                if (gone) atomicMax(&far[b], gone);
+            }
+        }
+    }
+    if (absent) atomicMax(&misc[3], absent);
+    __syncthreads();
+    const u32 absent_all = misc[3];
+    const u32 c0 = flag[2 * tid], c1 = flag[2 * tid + 1];
+    const u32 r0 = reach[2 * tid], r1 = reach[2 * tid + 1];
+    const u32 g0 = far[2 * tid], g1 = far[2 * tid + 1];
+    // M: prefix maximum of reach (inclusive), F: maximum of far over the buckets behind (and the absent rows)
+    const u32 m_before = block_excl_scan_op<u32, NT>(r0 > r1 ? r0 : r1, (u32*)sm.red, OpMax());
+    const u32 M0 = m_before > r0 ? m_before : r0, M1 = M0 > r1 ? M0 : r1;
+    u32* mirror = (u32*)(recs + ((total + 1) & ~1));        // NT words behind the source words
+    mirror[NT - 1 - tid] = g0 > g1 ? g0 : g1;
+    __syncthreads();
+    const u32 mv = mirror[tid];
+    __syncthreads();
+    const u32 behind_m = block_excl_scan_op<u32, NT>(mv, (u32*)sm.red, OpMax());
+    mirror[NT - 1 - tid] = behind_m;
+    __syncthreads();
+    u32 F1 = mirror[tid];                                   // buckets behind 2*tid + 1
+    F1 = absent_all > F1 ? absent_all : F1;
+    const u32 F0 = g1 > F1 ? g1 : F1;                       // buckets behind 2*tid
+    reach[2 * tid] = M0; reach[2 * tid + 1] = M1;
+    far[2 * tid] = g0 > F0 ? g0 : F0;                       // from here on: the bucket itself included
+    far[2 * tid + 1] = g1 > F1 ? g1 : F1;
+    __syncthreads();
+    // bounds of d over each bucket
+    const u64 need = thr > a ? thr - a : 0;                 // keys >= need are admissible
+    u32 lo0, hi0, lo1, hi1;
+    bucket.bounds_pair(2 * tid, lo0, hi0, lo1, hi1);
+    auto first_above = [&](u32 v) {                          // first bucket with M > v (NB if none)
+        int l = 0, h = NB;
+        while (l < h) { const int m = (l + h) >> 1; if (reach[m] > v) h = m; else l = m + 1; }
+        return l;
+    };
+    auto bounds_of = [&](u32 k, u32 c, u32 g, u32 F, u32 lok, u32 hik, i64& ub, i64& lb) {
+        ub = INT64_MAX; lb = INT64_MAX;
+        if (!c) return;
+        const u32 Fin = g > F ? g : F;                       // workers that may still stand before the window
+        i64 zlow, zhigh;                                     // min(Z) over the bucket lies in [zlow, zhigh]
+        if (Fin) zlow = -(i64)Fin;
+        else {
+            u32 jl = (u32)first_above(lok);
+            jl = jl < k ? jl : k;
+            u32 l2, h2;
+            bucket.bounds(jl, l2, h2);
+            zlow = (i64)l2;
+        }
+        if (F) zhigh = -(i64)F;
+        else {
+            const u32 jh = (u32)first_above(hik);
+            u32 l2, h2 = hik;
+            if (jh < k) bucket.bounds(jh, l2, h2);
+            zhigh = (i64)(h2 < hik ? h2 : hik);
+        }
+        lb = (i64)lok - zhigh;
+        if ((u64)lok >= need) ub = (i64)hik - zlow;
+    };
+    i64 ub0, lb0, ub1, lb1;
+    bounds_of(2 * tid, c0, g0, F0, lo0, hi0, ub0, lb0);
+    bounds_of(2 * tid + 1, c1, g1, F1, lo1, hi1, ub1, lb1);
+    const i64 ubmin = block_reduce<i64, NT>(ub0 < ub1 ? ub0 : ub1, (i64*)sm.red, OpMin());
+    const bool live0 = c0 && (u64)hi0 >= need && lb0 <= ubmin;
+    const bool live1 = c1 && (u64)hi1 >= need && lb1 <= ubmin;
+    if (live0 || live1) {
+        atomicMin(&misc[1], live0 ? lo0 : lo1);
+        atomicMax(&misc[2], live1 ? hi1 : hi0);
+    }
+    __syncthreads();
+    const u32 clo = misc[1], chi = misc[2];                 // all remaining candidates lie in [clo, chi]
+    // buckets where M rises hold the entries that are min(Z) at some time: those between clo and chi
+    const bool holds0 = r0 > m_before && M0 > clo && m_before <= chi;
+    const bool holds1 = r1 > M0 && M1 > clo && M0 <= chi;
+    flag[2 * tid] = (live0 ? 1u : 0u) | (holds0 ? 2u : 0u);
+    flag[2 * tid + 1] = (live1 ? 1u : 0u) | (holds1 ? 2u : 0u);
+    __syncthreads();
+    // the short list: slot and purpose first, then the entries themselves.  Entries of the
+    // buckets that can hold min(Z) fill it from the front, mere candidates from the back.
+    u32* lslot = mirror;                                    // RANGE_LIST_CAP words each
+    u32* lkey = lslot + RANGE_LIST_CAP;
+    u32* lnext = lkey + RANGE_LIST_CAP;
+    u32* lgone = lnext + RANGE_LIST_CAP;
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        const int q = j * NT + tid;
+        if (q < total) {
+            const u32 f = flag[bucket(key[j])];
+            if (f & 2u) {
+                const u32 at = atomicAdd(&misc[0], 1u);
+                if (at < (u32)RANGE_LIST_CAP) lslot[at] = (u32)q | (f << 16);
+            } else if (f) {
+                const u32 at = atomicAdd(&misc[4], 1u);
+                if (at < (u32)RANGE_LIST_CAP) lslot[RANGE_LIST_CAP - 1 - at] = (u32)q | (f << 16);
+            }
+        }
+    }
+    __syncthreads();
+    const int holders = (int)misc[0], others = (int)misc[4];
+    if (holders + others > RANGE_LIST_CAP) return false;
+    const int back = RANGE_LIST_CAP - others;               // the list is [0, holders) and [back, RANGE_LIST_CAP)
+    for (int i = tid; i < holders + others; i += NT) {
+        const int e = i < holders ? i : back + (i - holders);
+        read_entry(recs[lslot[e] & 0xffffu], lkey[e], lnext[e], lgone[e]);
+    }
+    __syncthreads();
+    u64 bd = U64_MAX;
+    u32 bk = 0xffffffffu;
+    for (int i = tid; i < holders + others; i += NT) {
+        const int me = i < holders ? i : back + (i - holders);
+        if (!(lslot[me] & 0x10000u)) continue;              // not a candidate, only a possible min(Z)
+        const u32 c = lkey[me];
+        if ((u64)c < need) continue;
+        const u32 b = bucket(c);
+        u32 out = 0;                                         // how far back the workers stand whose first entry lies behind c
+        if (far[b]) {
+            out = b + 1 < (u32)NB ? far[b + 1] : absent_all;
+            for (int e = 0; e < holders; ++e)
+                if (lkey[e] > c && lgone[e] > out) out = lgone[e];
+            for (int e = back; e < RANGE_LIST_CAP; ++e)
+                if (lkey[e] > c && lgone[e] > out) out = lgone[e];
+        }
+        u64 d;
+        if (out) {
+            d = (u64)c + out;
+        } else {
+            u32 z = c;                                       // the candidate itself is in Z unless its successor is equal
+            for (int e = 0; e < holders; ++e)
+                if (lkey[e] <= c && lnext[e] > c && lkey[e] < z) z = lkey[e];
+            d = (u64)(c - z);
+        }
+        if (d < bd || (d == bd && c < bk)) { bd = d; bk = c; }
+    }
+    wave_argmin(bd, bk);
+    const int lane = tid & (WAVE - 1), wave = tid >> 6;
+    u64* red = sm.red;
+    if (lane == WAVE - 1) { red[wave] = bd; red[NW + wave] = bk; }
+    __syncthreads();
+    bd = red[0];
+    bk = (u32)red[NW];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) {
+        const u64 od = red[w];
+        const u32 ok = (u32)red[NW + w];
+        if (od < bd || (od == bd && ok < bk)) { bd = od; bk = ok; }
+    }
+    best_d = bd;
+    best_key = bk;
+    return true;
+}
+
+template <int NT, int ITEMS, class CT>
+struct RangeSearch {
+    static constexpr bool PREDICTED = false;
+    __device__ __forceinline__ static void run(const Smem& sm, const Rows& rw, const WinVal& wv, const InstInfo& ii, bool hot,
+                                               const u32 (&lo)[ROWS_PER_THREAD<NT>], const u32 (&hi)[ROWS_PER_THREAD<NT>],
+                                               Partial* __restrict__ out)
+    {
+        Partial r;
+        r.wait = U64_MAX;
+        r.brel = 0;
+        if (wv.Elast >= wv.A) {
+            bool done = false;
+            if (hot && !(ii.range >> 31)) {                  // `gone` and `next` as positive 32-bit numbers
+                u32 key;
+                done = zl_range_bucket_search<NT, ITEMS, CT>(sm, rw, wv, ii.thr, lo, hi, r.wait, key);
+                if (done) r.brel = r.wait == U64_MAX ? 0 : wv.A + key;
+            }
+            if (!done) { r.wait = U64_MAX; r.brel = DEFERRED_WINDOW; }
+        }
+        __syncthreads();                          // everyone is done with LDS before the next window
+        if (threadIdx.x == 0) *out = r;
+    }
+};
+
+// The fast range search over all windows; windows it cannot take are marked for
+// zl_range_window_kernel.
+template <int NT, int ITEMS, class CT>
+__global__ __launch_bounds__(NT, 4) void zl_range_fast_kernel(
+    const i64* __restrict__ ts, i64 B, int P, int R,
+    const InstInfo* __restrict__ info, const CT* __restrict__ cross, int stride,
+    const u32* __restrict__ winstart, const WinVal* __restrict__ winval, int max_win, u32 groups, u32 groups_inv,
+    Partial* __restrict__ partial)
+{
+    using H = HotCfg<NT, ITEMS, false>;
+    __shared__ __align__(16) unsigned char smem[H::BYTES];
+    const Smem sm = carve_hot<NT, ITEMS>(smem);
+    window_pairs<NT, ITEMS, CT, RangeSearch<NT, ITEMS, CT>>(sm, ts, nullptr, B, P, R, info, cross, stride, winstart,
+                                                           winval, max_win, groups, groups_inv, partial);
+}
+
 // Instances of at most CAP_WIDE entries: one workgroup each.
 template <int NT, int ITEMS>
 __global__ __launch_bounds__(NT) void zl_range_instance_kernel(
@@ -2139,7 +2457,7 @@ template <int NT, int ITEMS>
 __global__ __launch_bounds__(NT) void zl_range_window_kernel(
     const i64* __restrict__ ts, i64 B, int P, int R,
     const InstInfo* __restrict__ info, const void* __restrict__ cross, bool narrow, int stride,
-    const u32* __restrict__ winstart, const WinVal* __restrict__ winval, int max_win,
+    const u32* __restrict__ winstart, const WinVal* __restrict__ winval, int max_win, bool only_marked,
     Partial* __restrict__ partial, int* __restrict__ status)
 {
     using C = WinCfg<NT, ITEMS>;
@@ -2150,6 +2468,10 @@ __global__ __launch_bounds__(NT) void zl_range_window_kernel(
     if (b >= B) return;
     const InstInfo ii = info[b];
     if (j >= (int)ii.nwin) return;
+    if (only_marked) {                            // the fast kernel ran first: only what it left
+        const Partial seen = partial[b * (i64)max_win + j];
+        if (!(seen.wait == U64_MAX && seen.brel == DEFERRED_WINDOW)) return;
+    }
     const WinPos w = locate_window(b, j, ii, ts, nullptr, nullptr, P, R, cross, narrow, stride, winstart, winval, max_win);
     Partial r;
     r.wait = U64_MAX;
@@ -2225,12 +2547,12 @@ int fail(int code, const char* msg)
 }
 
 enum KernelId { K_INSTANCE = 0, K_INSTANCE_GENERAL, K_BOUNDS, K_PARTITION, K_BINCOUNT, K_PLAN, K_WINDOW,
-                K_WINDOW_GENERAL, K_FINISH, K_COPY, K_RANGE_INSTANCE, K_RANGE_WINDOW, K_PARTITION_PRED, K_COUNT };
+                K_WINDOW_GENERAL, K_FINISH, K_COPY, K_RANGE_INSTANCE, K_RANGE_WINDOW, K_PARTITION_PRED, K_RANGE_FAST, K_COUNT };
 const char* const kKernelNames[K_COUNT] = {
     "zl_instance_kernel", "zl_instance_general_kernel", "zl_bounds_kernel", "zl_partition_kernel",
     "zl_bincount_kernel", "zl_plan_kernel", "zl_window_kernel", "zl_window_general_kernel",
     "zl_finish_kernel", "zl_copy_kernel", "zl_range_instance_kernel", "zl_range_window_kernel",
-    "zl_partition_pred_kernel"};
+    "zl_partition_pred_kernel", "zl_range_fast_kernel"};
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -2254,7 +2576,7 @@ struct Plan {
 };
 
 // single_limit: the most entries one workgroup takes whole on the path the plan is for
-bool make_plan(i64 B, int P, int R, Plan& pl, int single_limit = SINGLE_MAX, int cap_override = 0)
+bool make_plan(i64 B, int P, int R, Plan& pl, int single_limit = SINGLE_MAX, int fine_per_group_log2 = 2)
 {
     if (B < 0 || P < 1 || R < 1) return false;
     const i64 n = (i64)P * (i64)R;
@@ -2265,9 +2587,9 @@ bool make_plan(i64 B, int P, int R, Plan& pl, int single_limit = SINGLE_MAX, int
     pl.multi = n > single_max;
     if (!pl.multi) return true;
     // the per-window cost has a term proportional to P: larger windows for more rows
-    pl.cap = cap_override > 0 ? cap_override : (g_tune.window_cap > 0 ? g_tune.window_cap : (P >= 512 ? 8192 : 4096));
+    pl.cap = g_tune.window_cap > 0 ? g_tune.window_cap : (P >= 512 ? 8192 : 4096);
     pl.group_shift = pl.cap == 16384 ? 13 : (pl.cap == 8192 ? 12 : 11);
-    const int fine_shift = pl.group_shift - 2;
+    const int fine_shift = pl.group_shift - fine_per_group_log2;      // a window exceeds its group's 2^group_shift keys by at most one fine bin
     pl.bins = (int)((n + (1 << fine_shift) - 1) >> fine_shift);
     pl.stride = pl.bins + 1;
     // the counts behind the grouping are estimates; a whole number of workgroups per instance
@@ -2421,13 +2743,12 @@ int run_batch(const i64* ts, const i64* le, const i64* iv, i64 B, int P, int R,
 // The search under the paper's formal objective; the multi-window path shares the
 // kernels that cut an instance into windows.
 constexpr int RANGE_SINGLE_MAX = WinCfg<LARGE_NT, LARGE_ITEMS>::CAP_WIDE;
-constexpr int RANGE_WINDOW_CAP = 4096;      // windows of about 2048 entries: a 512-thread workgroup each, three per CU
 
 int run_range_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters, i64* dmin, int* status,
                     void* workspace, size_t workspace_bytes, hipStream_t st)
 {
     Plan pl;
-    if (!make_plan(B, P, R, pl, RANGE_SINGLE_MAX, RANGE_WINDOW_CAP))
+    if (!make_plan(B, P, R, pl, RANGE_SINGLE_MAX, range_fine_log2(P)))
         return fail(EBSP_ERR_SHAPE, "invalid shape: need B >= 0, P >= 1, R >= 1, P*R < 2^31");
     if (B == 0) return EBSP_OK;
     if (!ts || !barrier || !iters || !dmin) return fail(EBSP_ERR_NULL, "ts, barrier, iters and dmin must not be NULL");
@@ -2470,8 +2791,27 @@ int run_range_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters
                (const u32*)cross, P, R, pl.stride, pl.step, info, below);
     LAUNCH(K_PLAN, (zl_plan_kernel<1024>), dim3((unsigned)B), dim3(1024), info, below, pl.stride, winstart, winval,
            pl.max_win, pl.group_shift, (u32)(pl.cap / 8));
-    LAUNCH(K_RANGE_WINDOW, (zl_range_window_kernel<512, 16>), dim3((unsigned)total_win), dim3(512),
-           ts, B, P, R, info, cross, pl.narrow, pl.stride, winstart, winval, pl.max_win, partial, status);
+    const u32 groups = (u32)(pl.max_win / WINDOWS_PER_BLOCK);
+    const u32 groups_inv = groups > 1 ? (u32)((1ull << 32) / groups) : 0xffffffffu;
+    const unsigned wgrid = (unsigned)((B * (i64)groups + 7) / 8 * 8);
+#define LAUNCH_RANGE(NT_, CT_)                                                                               \
+    LAUNCH(K_RANGE_FAST, (zl_range_fast_kernel<NT_, 16, CT_>), dim3(wgrid), dim3(NT_), ts, B, P, R, info,   \
+           (const CT_*)cross, pl.stride, winstart, winval, pl.max_win, groups, groups_inv, partial)
+    if (pl.cap == 16384) {
+        if (pl.narrow) LAUNCH_RANGE(1024, unsigned short); else LAUNCH_RANGE(1024, u32);
+    } else if (pl.cap == 8192) {
+        if (pl.narrow) LAUNCH_RANGE(512, unsigned short); else LAUNCH_RANGE(512, u32);
+    } else {
+        if (pl.narrow) LAUNCH_RANGE(256, unsigned short); else LAUNCH_RANGE(256, u32);
+    }
+#undef LAUNCH_RANGE
+    // what the fast kernel left: the sort-based search, one workgroup per marked window
+    if (pl.cap <= 4096)       // windows of about 2048 entries fit a 512-thread workgroup's sort (three workgroups per CU)
+        LAUNCH(K_RANGE_WINDOW, (zl_range_window_kernel<512, 16>), dim3((unsigned)total_win), dim3(512),
+               ts, B, P, R, info, cross, pl.narrow, pl.stride, winstart, winval, pl.max_win, true, partial, status);
+    else
+        LAUNCH(K_RANGE_WINDOW, (zl_range_window_kernel<LARGE_NT, LARGE_ITEMS>), dim3((unsigned)total_win), dim3(LARGE_NT),
+               ts, B, P, R, info, cross, pl.narrow, pl.stride, winstart, winval, pl.max_win, true, partial, status);
     LAUNCH(K_FINISH, (zl_finish_kernel<256>), dim3((unsigned)(pblocks * B)), dim3(256),
            ts, nullptr, nullptr, P, R, info, partial, pl.max_win, barrier, iters, dmin);
     return EBSP_OK;
@@ -2513,7 +2853,7 @@ int ebsp_predict_zipline_batch(const int64_t* last_end, const int64_t* interval,
 size_t ebsp_zipline_range_workspace_bytes(int64_t B, int32_t P, int32_t R)
 {
     Plan pl;
-    if (!make_plan(B, P, R, pl, RANGE_SINGLE_MAX, RANGE_WINDOW_CAP)) return 0;
+    if (!make_plan(B, P, R, pl, RANGE_SINGLE_MAX, range_fine_log2(P))) return 0;
     return pl.multi ? pl.bytes : 0;
 }
 
