@@ -31,7 +31,6 @@ def algorithmic_bytes(kernel: str, B: int, P: int, R: int, bins: int, windows: i
     """Bytes a kernel must move per launch (inputs it has to read once + what it has to write)."""
     n = float(B) * P * R
     cw = 2.0 if R < 65536 else 4.0          # bytes of one crossing index
-    step = max(1, P // 256)                 # zl_bincount looks at every step-th row
     if kernel == "zl_instance_kernel":      # every timestamp once, all three outputs
         return 8.0 * n + B * (16.0 + 4.0 * P)
     if kernel == "zl_window_kernel":        # every timestamp once, two crossing rows per window, one result
@@ -41,7 +40,7 @@ def algorithmic_bytes(kernel: str, B: int, P: int, R: int, bins: int, windows: i
     if kernel == "zl_partition_pred_kernel":    # 16 bytes per worker, one crossing index per (row, bin)
         return 16.0 * B * P + cw * B * P * (bins + 1)
     if kernel == "zl_bincount_kernel":      # the crossing indices once, one count per bin
-        return cw * B * ((P + step - 1) // step) * (bins + 1) + 4.0 * B * (bins + 1)
+        return cw * B * P * (bins + 1) + 4.0 * B * (bins + 1)
     if kernel == "zl_bounds_kernel":        # first and last timestamp of every row (one 64-byte line each)
         return 128.0 * B * P
     if kernel == "zl_plan_kernel":
@@ -76,6 +75,7 @@ def main() -> int:
                     help="launches of the plain copy kernel (the input's size) after the timed region; "
                          "its bandwidth and byte counters are the yardstick for the others (0: skip)")
     ap.add_argument("--window-cap", type=int, default=0, help="tuning: records per window workgroup (0: default)")
+    ap.add_argument("--window-fill", type=int, default=0, help="tuning: entries a window is filled to (0: default)")
     ap.add_argument("--single-max", type=int, default=0, help="tuning: largest P*R taken by one workgroup (0: default)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -88,7 +88,7 @@ def main() -> int:
     import torch
     from paper_2001_01347_amd import workloads, zipline
 
-    zipline.ebsp_zipline_tune(args.window_cap, args.single_max)
+    zipline.ebsp_zipline_tune(args.window_cap, args.single_max, args.window_fill)
     cfg = workloads.CONFIGS[args.config]
     B, P, R = cfg.B, cfg.P, cfg.R
     n_keys = cfg.n_keys
@@ -159,10 +159,10 @@ def main() -> int:
     bins = shape["bins"]
     if ranged and P * R > 8192 and not shape["multi"]:
         # this objective cuts instances of more than 8192 entries into windows: the shape as the library plans it
-        zipline.ebsp_zipline_tune(args.window_cap, 8192)
+        zipline.ebsp_zipline_tune(args.window_cap, 8192, args.window_fill)
         shape = zipline.ebsp_zipline_shape_info(B, P, R)
-        zipline.ebsp_zipline_tune(args.window_cap, args.single_max)
-    windows = B * ((2 * P * R + shape["window_cap"] - 1) // shape["window_cap"]) if shape["multi"] else 0
+        zipline.ebsp_zipline_tune(args.window_cap, args.single_max, args.window_fill)
+    windows = B * ((P * R + shape["window_fill"] - 1) // shape["window_fill"]) if shape["multi"] else 0
     per_kernel = {k: v / args.steps for k, v in kernel_ms.items() if v > 0.0}
     dom = max(per_kernel, key=per_kernel.get)
     dom_bytes = algorithmic_bytes(dom, B, P, R, bins, windows)

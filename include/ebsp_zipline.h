@@ -128,10 +128,11 @@ int ebsp_zipline_range_batch(const int64_t* ts, int64_t B, int32_t P, int32_t R,
                              void* stream);
 
 /*
- * How a shape is handled (for benchmarks' byte models; HOST array of 4):
+ * How a shape is handled (for benchmarks' byte models; HOST array of 5):
  * info[0] = 1 if instances are cut into windows (0: one workgroup each),
  * info[1] = records per window workgroup, info[2] = fine bins per instance,
- * info[3] = upper bound of windows per instance (all 0 when info[0] is 0).
+ * info[3] = upper bound of windows per instance, info[4] = entries a window
+ * holds at most (all 0 when info[0] is 0).
  */
 int ebsp_zipline_shape_info(int64_t B, int32_t P, int32_t R, int64_t* info);
 
@@ -143,9 +144,11 @@ int ebsp_zipline_shape_info(int64_t B, int32_t P, int32_t R, int64_t* info);
  *   single_max  largest P*R that one workgroup handles whole (1..16384);
  *               0 = 16384 (the default).  Larger instances take the
  *               multi-window path.
- * Results do not depend on either.  Returns EBSP_OK or EBSP_ERR_SHAPE.
+ *   window_fill most entries of a window (at least 512); 0 = window_cap (the
+ *               default: windows are packed as full as a workgroup can hold).
+ * Results do not depend on any of them.  Returns EBSP_OK or EBSP_ERR_SHAPE.
  */
-int ebsp_zipline_tune(int32_t window_cap, int32_t single_max);
+int ebsp_zipline_tune(int32_t window_cap, int32_t single_max, int32_t window_fill);
 
 /*
  * Per-kernel timing for benchmarks.  Between ebsp_zipline_profile_begin() and

@@ -40,6 +40,7 @@
 
 typedef unsigned long long u64;
 typedef unsigned int u32;
+typedef unsigned short u16;
 typedef long long i64;
 
 namespace {
@@ -63,7 +64,7 @@ struct InstInfo {
     i64 base;    // min_p t[p][0]; all other values are relative to it
     u64 range;   // max_p t[p][R-1] - base
     u64 thr;     // max_p t[p][0] - base: earliest admissible barrier
-    u32 inv;     // fine bin of relative value v is ((v >> wshift) * inv) >> 32
+    u32 segshift; // segment of the fine-bin map that (v >> wshift) falls in: (v >> wshift) >> segshift
     u32 wshift;  // 0 unless the range needs more than 32 bits
     u32 nb;      // number of fine bins, bin(range) + 1
     u32 nwin;    // number of windows (set by zl_plan)
@@ -212,16 +213,42 @@ __device__ __forceinline__ void block_bounds(i64 a, i64 b, i64 c, i64* red, i64&
 __device__ __forceinline__ int bit_length(u64 x) { return x ? 64 - __clzll((long long)x) : 0; }
 
 // Fine-bin grid of an instance: a monotone map of relative values onto [0, nb).
-__device__ __forceinline__ u32 fine_bin(u64 rel, const InstInfo& ii)
+// x = v >> wshift runs over SEGS segments of 2^segshift values each; within segment s
+// the bin is (G[s] + offset * slope[s]) >> 32 with G[s + 1] = G[s] + 2^segshift *
+// slope[s] (32.32 fixed point), so the map is continuous and never decreases.
+// zl_bounds sets the slopes from an estimate of how many entries each segment holds
+// (rows taken as evenly spaced between their first and last value), so that bins
+// hold about the same number of entries wherever the rows are dense or sparse.
+constexpr int SEGS = 64;
+struct SegEntry {        // one segment of an instance's map
+    u64 G;
+    u32 slope;
+    u32 pad_;
+};
+__device__ __forceinline__ u32 fine_bin(u64 rel, const InstInfo& ii, const SegEntry* tab)
 {
     if (rel > ii.range) rel = ii.range;              // only reachable for unsorted rows
-    const u32 k = (u32)(((rel >> ii.wshift) * (u64)ii.inv) >> 32);
+    const u32 x = (u32)(rel >> ii.wshift);
+    const u32 s = x >> ii.segshift;
+    const SegEntry e = tab[s];
+    const u32 k = (u32)((e.G + (u64)(x - (s << ii.segshift)) * e.slope) >> 32);
     return k < ii.nb ? k : ii.nb - 1;
 }
-// Smallest relative value that falls in bin k or later.
-__device__ __forceinline__ u64 fine_bin_start(u32 k, const InstInfo& ii)
+// Smallest relative value that falls in bin k or later (k < nb).
+__device__ __forceinline__ u64 fine_bin_start(u32 k, const InstInfo& ii, const SegEntry* tab)
 {
-    return ((((u64)k << 32) + ii.inv - 1) / ii.inv) << ii.wshift;
+    const u64 wmax = (1ull << ii.segshift) - 1;
+    const u64 want = (u64)k << 32;
+    int lo = 0, hi = SEGS - 1;                       // first segment whose last value reaches bin k
+    while (lo < hi) {
+        const int m = (lo + hi) >> 1;
+        const SegEntry e = tab[m];
+        if (((e.G + wmax * e.slope) >> 32) >= k) hi = m; else lo = m + 1;
+    }
+    const SegEntry e = tab[lo];
+    u64 off = 0;
+    if (want > e.G && e.slope) off = (want - e.G + e.slope - 1) / e.slope;
+    return (((u64)lo << ii.segshift) + off) << ii.wshift;
 }
 
 // ---------------------------------------------------------------------------
@@ -1415,9 +1442,15 @@ __global__ __launch_bounds__(NT) void zl_instance_general_kernel(
 template <int NT>
 __global__ __launch_bounds__(NT) void zl_bounds_kernel(
     const i64* __restrict__ ts, const i64* __restrict__ le, const i64* __restrict__ iv, int P, int R, int bins,
-    InstInfo* __restrict__ info, uint2* __restrict__ rowpar, int* __restrict__ status)
+    InstInfo* __restrict__ info, SegEntry* __restrict__ segtab, uint2* __restrict__ rowpar, int* __restrict__ status)
 {
+    static_assert(NT >= SEGS, "one thread per segment");
     __shared__ i64 red[NT / WAVE];
+    __shared__ u64 seg_part[SEGS];        // entries of rows that begin or end in a segment (x 2^16)
+    __shared__ u64 seg_diff[SEGS + 1];    // difference array: entries per segment of the rows that cover it whole (x 2^16)
+    __shared__ u64 seg_est[SEGS];
+    __shared__ u64 seg_step[SEGS];
+    __shared__ u32 seg_slope[SEGS];
     const int tid = threadIdx.x;
     const i64 b = blockIdx.x;
     Rows ends;                                        // only to read the rows' first and last entries
@@ -1434,6 +1467,8 @@ __global__ __launch_bounds__(NT) void zl_bounds_kernel(
         mxl = l > mxl ? l : mxl;
         if (!ends.inst && R > 1 && ends.iv[p] < 0) backwards = 1;     // predicted rows: a negative interval
     }
+    if (tid < SEGS) { seg_part[tid] = 0; seg_diff[tid] = 0; }
+    if (tid == 0) seg_diff[SEGS] = 0;
     const i64 base = block_reduce<i64, NT>(mn, red, OpMin());
     const i64 first_max = block_reduce<i64, NT>(mxf, red, OpMax());
     const i64 last_max = block_reduce<i64, NT>(mxl, red, OpMax());
@@ -1441,26 +1476,80 @@ __global__ __launch_bounds__(NT) void zl_bounds_kernel(
     if (rowpar)                                       // predicted rows, for the window gather: low words of the first value and the interval
         for (int p = tid; p < P; p += NT)
             rowpar[b * (i64)P + p] = make_uint2((u32)(u64)ends.value(p, 0), (u32)ends.iv[p]);
-    if (tid == 0) {
-        InstInfo ii;
-        ii.base = base;
-        ii.range = (u64)last_max - (u64)base;
-        ii.thr = (u64)first_max - (u64)base;
-        ii.nwin = 0;
-        ii.flags = backwards ? (u32)EBSP_STATUS_UNSORTED : 0u;
-        ii.pad_ = 0;
-        if (ii.range > (u64)INT64_MAX / (u64)P) ii.flags |= EBSP_STATUS_OVERFLOW;
-        if (backwards) ii.range = 0;                  // nothing downstream may rely on such rows
-        // bins are equal slices of [0, range >> wshift]: inv = bins * 2^32 / (top + 1), capped to 32 bits
-        const int bl = bit_length(ii.range);
-        ii.wshift = bl > 32 ? (u32)(bl - 32) : 0u;
-        const u64 top = ii.range >> ii.wshift;
-        const u64 q = ((u64)bins << 32) / (top + 1);
-        ii.inv = q < 0xffffffffull ? (u32)q : 0xffffffffu;
-        if (ii.inv == 0) ii.inv = 1;
-        ii.nb = (u32)((top * (u64)ii.inv) >> 32) + 1u;
-        info[b] = ii;
-        if (status) status[b] = (int)ii.flags;
+    InstInfo ii;
+    ii.base = base;
+    ii.range = (u64)last_max - (u64)base;
+    ii.thr = (u64)first_max - (u64)base;
+    ii.nwin = 0;
+    ii.flags = backwards ? (u32)EBSP_STATUS_UNSORTED : 0u;
+    ii.pad_ = 0;
+    if (ii.range > (u64)INT64_MAX / (u64)P) ii.flags |= EBSP_STATUS_OVERFLOW;
+    if (backwards) ii.range = 0;                      // nothing downstream may rely on such rows
+    const int bl = bit_length(ii.range);
+    ii.wshift = bl > 32 ? (u32)(bl - 32) : 0u;
+    const u64 top = ii.range >> ii.wshift;            // x = v >> wshift runs over [0, top], top < 2^32
+    const int tl = bit_length(top);
+    ii.segshift = tl > 6 ? (u32)(tl - 6) : 0u;        // top >> segshift < SEGS
+    const u64 W = 1ull << ii.segshift;
+    const int nseg = (int)(top >> ii.segshift) + 1;
+    // how many entries each segment holds if every row's R entries are evenly spaced from its first to its last value
+    constexpr double FIX = 65536.0;
+    for (int p = tid; p < P; p += NT) {
+        const u64 f = (u64)ends.value(p, 0) - (u64)base, l = (u64)ends.value(p, (u32)R - 1) - (u64)base;
+        if (l < f || l > ii.range) continue;          // not a sorted row: the status says so elsewhere
+        const u64 xf = f >> ii.wshift, xl = l >> ii.wshift;
+        const u32 sf = (u32)(xf >> ii.segshift), sl = (u32)(xl >> ii.segshift);
+        if (sf == sl) {
+            atomicAdd(&seg_part[sf], (u64)((double)R * FIX));
+        } else {
+            const double rate = (double)R * FIX / (double)(xl - xf + 1);          // per unit of x
+            atomicAdd(&seg_part[sf], (u64)(rate * (double)((((u64)sf + 1) << ii.segshift) - xf)));
+            atomicAdd(&seg_part[sl], (u64)(rate * (double)(xl - ((u64)sl << ii.segshift) + 1)));
+            if (sl > sf + 1) {
+                const u64 whole = (u64)(rate * (double)W);
+                atomicAdd(&seg_diff[sf + 1], whole);
+                atomicAdd(&seg_diff[sl], 0ull - whole);
+            }
+        }
+    }
+    __syncthreads();
+    if (tid < SEGS) {
+        u64 cover = 0;
+        for (int j = 0; j <= tid; ++j) cover += seg_diff[j];
+        seg_est[tid] = tid < nseg ? seg_part[tid] + cover : 0;
+    }
+    __syncthreads();
+    if (tid < SEGS) {
+        u64 total = 0;
+        for (int j = 0; j < nseg; ++j) total += seg_est[j];
+        // an eighth of the bins is spread evenly, in case the rows are far from evenly spaced
+        const u64 even = total / (8ull * (u64)nseg) + 1;
+        const u64 total2 = total + even * (u64)nseg;
+        u32 slope = 0;
+        if (tid < nseg) {
+            const u64 len = tid == nseg - 1 ? top - ((u64)tid << ii.segshift) + 1 : W;       // values of the segment in use
+            const double share = (double)(seg_est[tid] + even) / (double)total2 * (double)(bins - 1);
+            const double sl = share * 4294967296.0 / (double)len;
+            slope = sl < 4294967295.0 ? (u32)sl : 0xffffffffu;
+        }
+        seg_step[tid] = W * (u64)slope;
+        seg_slope[tid] = slope;
+    }
+    __syncthreads();
+    if (tid < SEGS) {
+        const u32 slope = seg_slope[tid];
+        u64 G = 0;
+        for (int j = 0; j < tid; ++j) G += seg_step[j];
+        SegEntry e;
+        e.G = G;
+        e.slope = slope;
+        e.pad_ = 0;
+        segtab[b * (i64)SEGS + tid] = e;
+        if (tid == nseg - 1) {
+            ii.nb = (u32)((G + (top - ((u64)tid << ii.segshift)) * (u64)slope) >> 32) + 1u;
+            info[b] = ii;
+            if (status) status[b] = (int)ii.flags;
+        }
     }
 }
 
@@ -1469,13 +1558,21 @@ __global__ __launch_bounds__(NT) void zl_bounds_kernel(
 template <int NT, class CT>
 __global__ __launch_bounds__(NT) void zl_partition_kernel(
     const i64* __restrict__ ts, i64 nrows, int P, int R,
-    const InstInfo* __restrict__ info, CT* __restrict__ cross, int stride, int* __restrict__ status)
+    const InstInfo* __restrict__ info, const SegEntry* __restrict__ segtab, CT* __restrict__ cross, int stride,
+    int* __restrict__ status)
 {
+    __shared__ SegEntry tabs[NT / WAVE][SEGS];         // each wave's copy of its instance's fine-bin map
     const int lane = threadIdx.x & (WAVE - 1);
     const i64 row_id = (i64)blockIdx.x * (NT / WAVE) + (threadIdx.x >> 6);
     if (row_id >= nrows) return;
     const i64 b = row_id / P;
     const InstInfo ii = info[b];
+    SegEntry* tab = tabs[threadIdx.x >> 6];
+    static_assert(SEGS == WAVE, "one entry per lane");
+    tab[lane] = segtab[b * (i64)SEGS + lane];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");     // the wave's own stores, read by its other lanes below
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     const i64* __restrict__ row = ts + row_id * (i64)R;
     CT* __restrict__ out = cross + row_id * (i64)stride;
     const u64 base = (u64)ii.base;
@@ -1487,7 +1584,7 @@ __global__ __launch_bounds__(NT) void zl_partition_kernel(
         const int i = i0 + lane;
         int bin = -1;
         i64 t = INT64_MAX;
-        if (i < R) { t = row[i]; bin = (int)fine_bin((u64)t - base, ii); }
+        if (i < R) { t = row[i]; bin = (int)fine_bin((u64)t - base, ii, tab); }
         int pb = __shfl_up(bin, 1, WAVE);
         i64 pt = __shfl_up(t, 1, WAVE);
         if (lane == 0) { pb = carry; pt = carry_t; }
@@ -1498,7 +1595,7 @@ __global__ __launch_bounds__(NT) void zl_partition_kernel(
         carry_t = __shfl(t, WAVE - 1, WAVE);
     }
     if (__any(bad) && lane == 0 && status) atomicOr(status + b, (int)EBSP_STATUS_UNSORTED);
-    const int last_bin = (int)fine_bin((u64)row[R - 1] - base, ii);
+    const int last_bin = (int)fine_bin((u64)row[R - 1] - base, ii, tab);
     for (int k = last_bin + 1 + lane; k <= (int)ii.nb; k += WAVE) out[k] = (CT)R;
 }
 
@@ -1510,7 +1607,7 @@ constexpr int PRED_ROWS_PER_BLOCK = 64;
 template <class CT>
 __global__ __launch_bounds__(256) void zl_partition_pred_kernel(
     const i64* __restrict__ le, const i64* __restrict__ iv, int P, int R,
-    const InstInfo* __restrict__ info, CT* __restrict__ cross, int stride)
+    const InstInfo* __restrict__ info, const SegEntry* __restrict__ segtab, CT* __restrict__ cross, int stride)
 {
     const u32 kblocks = (u32)(stride + 255) / 256;
     const i64 b = blockIdx.x / kblocks;
@@ -1520,7 +1617,7 @@ __global__ __launch_bounds__(256) void zl_partition_pred_kernel(
     const InstInfo ii = info[b];
     if (k > (int)ii.nb) return;
     const bool broken = (ii.flags & EBSP_STATUS_UNSORTED) != 0;      // a negative interval: indices stay zero
-    const u64 edge = k >= (int)ii.nb ? U64_MAX : fine_bin_start((u32)k, ii);   // bin nb: everything lies below
+    const u64 edge = k >= (int)ii.nb ? U64_MAX : fine_bin_start((u32)k, ii, segtab + b * (i64)SEGS);   // bin nb: everything lies below
     const i64* __restrict__ lep = le + b * (i64)P;
     const i64* __restrict__ ivp = iv + b * (i64)P;
     CT* __restrict__ out = cross + (b * (i64)P) * stride + k;
@@ -1539,13 +1636,11 @@ __global__ __launch_bounds__(256) void zl_partition_pred_kernel(
     }
 }
 
-// zl_bincount: below[b][k] ~ number of keys of instance b under fine bin k, k = 0..nb:
-// the column sum of cross over every `step`-th row, scaled to all P rows.  The
-// counts only steer how bins are grouped into windows (a window's true size is
-// taken from cross itself), so an estimate from 256 or more rows is enough.
+// zl_bincount: below[b][k] = number of keys of instance b under fine bin k, k = 0..nb:
+// the column sums of cross.  Exact, so that zl_plan can fill windows to the brim.
 template <class CT>
 __global__ __launch_bounds__(256) void zl_bincount_kernel(
-    const CT* __restrict__ cross, int P, int R, int stride, int step,
+    const CT* __restrict__ cross, int P, int R, int stride,
     const InstInfo* __restrict__ info, u32* __restrict__ below)
 {
     __shared__ u32 part[256];
@@ -1557,26 +1652,26 @@ __global__ __launch_bounds__(256) void zl_bincount_kernel(
     u32 s = 0;
     if (k <= (int)nb) {
         const CT* col = cross + (b * (i64)P) * stride + k;
-#pragma unroll 4
-        for (int p = pg * step; p < P; p += 4 * step) {
+#pragma unroll 8
+        for (int p = pg; p < P; p += 4) {
             const u32 c = col[(i64)p * stride];
             s += c < (u32)R ? c : (u32)R;
         }
     }
     part[tid] = s;
     __syncthreads();
-    if (pg == 0 && k <= (int)nb) {
-        const u64 sum = (u64)part[kl] + part[64 + kl] + part[128 + kl] + part[192 + kl];
-        const u32 sampled = (u32)(P + step - 1) / (u32)step;
-        below[b * (i64)stride + k] = (u32)(sum * (u64)P / sampled);
-    }
+    if (pg == 0 && k <= (int)nb)
+        below[b * (i64)stride + k] = part[kl] + part[64 + kl] + part[128 + kl] + part[192 + kl];
 }
 
-// zl_plan: windows of an instance.  Fine bin k belongs to group
-// below[k] >> group_shift; a window is a maximal run of bins of one group, so
-// it holds fewer than 2^group_shift keys plus its last bin's.  Per window: its
-// first fine bin (winstart), its first and last value and the constants of the
-// linear bucket map over that span (winval).
+// zl_plan: windows of an instance.  below[] holds the exact number of keys under
+// every fine bin, so the windows are packed greedily: a window takes fine bins while
+// its entries stay within `fill` (a bin larger than that becomes a window of its own,
+// which the window kernel leaves to the general search).  The packing is a sequential
+// walk over the bins by one wave (64 bins at a time, one ballot per window), fed from
+// LDS in slices the workgroup loads together; the per-window values follow in parallel.  Per window: its first fine bin
+// (winstart), its first and last value and the constants of the linear bucket map
+// over that span (winval).
 struct WinVal {
     u64 A, Elast;
     u64 inv52;     // floor(2^52 / scale)
@@ -1584,12 +1679,15 @@ struct WinVal {
     u32 pad_;
 };
 
-template <int NT>
+template <int NT, int PLAN_SLICE>       // PLAN_SLICE: fine bins held in LDS at a time
 __global__ __launch_bounds__(NT) void zl_plan_kernel(
-    InstInfo* __restrict__ info, const u32* __restrict__ below, int stride,
-    u32* __restrict__ winstart, WinVal* __restrict__ winval, int max_win, int group_shift, u32 buckets)
+    InstInfo* __restrict__ info, const SegEntry* __restrict__ segtab, const u32* __restrict__ below, int stride,
+    u32* __restrict__ winstart, WinVal* __restrict__ winval, int max_win, u32 fill, u32 buckets)
 {
-    __shared__ u32 red[NT / WAVE];
+    __shared__ u32 ends[PLAN_SLICE + 1];   // ends[i + 1] = keys under bin k0 + i + 1 = where bin k0 + i ends
+    __shared__ u32 found_all;
+    __shared__ SegEntry tab[SEGS];         // the instance's fine-bin map
+    __shared__ u16 hop[2][PLAN_SLICE + 1];
     const int tid = threadIdx.x;
     const i64 b = blockIdx.x;
     const u32* bel = below + b * (i64)stride;
@@ -1597,38 +1695,100 @@ __global__ __launch_bounds__(NT) void zl_plan_kernel(
     WinVal* wv = winval + b * (i64)max_win;
     const InstInfo ii = info[b];
     const int nb = (int)ii.nb;
-    u32 found = 0;
-    for (int k0 = 0; k0 < nb; k0 += NT) {
-        const int k = k0 + tid;
-        u32 flag = 0;
-        if (k < nb) flag = (k == 0) || ((bel[k] >> group_shift) != (bel[k - 1] >> group_shift));
-        u32 chunk;
-        const u32 idx = found + block_excl_scan<u32, NT>(flag, red, chunk);
-        if (flag && idx < (u32)max_win) {
-            const u64 first = fine_bin_start((u32)k, ii);
-            ws[idx] = (u32)k;
-            wv[idx].A = first;
-            if (idx > 0) wv[idx - 1].Elast = first - 1;
+    if (tid == 0) found_all = 0;
+    if (nb <= PLAN_SLICE) {
+        // All bins fit in LDS.  jump[k] = the bin that opens the next window if one opens at bin k
+        // (nb: none); the windows open at 0, jump[0], jump[jump[0]], ...  Thread r finds the r-th
+        // of them by squaring the jump table: level l applies jump^(2^l) to the ranks with bit l set.
+        static_assert(PLAN_SLICE % NT == 0, "whole ranks per thread");
+        constexpr int RANKS = PLAN_SLICE / NT;          // ranks per thread: every window holds at least one bin
+        u16* jump = hop[0];
+        u16* other = hop[1];
+        for (int i = tid; i <= nb; i += NT) ends[i] = bel[i];
+        __syncthreads();
+        for (int k = tid; k <= nb; k += NT) {
+            int lo = k + 1, hi = nb;                      // first bin j > k whose end lies more than `fill` past the start of bin k
+            if (k < nb) {
+                const u32 limit = ends[k] + fill;         // no overflow: fill and the key count are both below 2^31
+                while (lo < hi) { const int m = (lo + hi) >> 1; if (ends[m + 1] > limit) hi = m; else lo = m + 1; }
+            } else lo = nb;
+            jump[k] = (u16)lo;
         }
-        found += chunk;
+        u32 pos[RANKS];
+#pragma unroll
+        for (int q = 0; q < RANKS; ++q) pos[q] = 0;
+        const u32 top_rank = (u32)nb < (u32)max_win ? (u32)nb : (u32)max_win;
+        for (int level = 0; (1u << level) <= top_rank; ++level) {
+            __syncthreads();
+#pragma unroll
+            for (int q = 0; q < RANKS; ++q)
+                if (((u32)(q * NT + tid) >> level) & 1u) pos[q] = jump[pos[q]];
+            for (int k = tid; k <= nb; k += NT) other[k] = jump[jump[k]];
+            u16* t = jump; jump = other; other = t;
+        }
+#pragma unroll
+        for (int q = 0; q < RANKS; ++q) {
+            const u32 r = (u32)(q * NT + tid);
+            if (pos[q] < (u32)nb && r < (u32)max_win) {
+                ws[r] = pos[q];
+                atomicMax(&found_all, r + 1);
+            }
+        }
+        __syncthreads();
+        if (tid == 0) { ws[found_all] = (u32)nb; info[b].nwin = found_all; }
+    } else {
+    // wave 0 walks the bins, 64 at a time: one step per window, not per bin
+    u32 found = 0, first_key = 0;          // windows so far, keys under the open window's first bin
+    for (int k0 = 0; k0 < nb; k0 += PLAN_SLICE) {
+        const int cnt = nb - k0 < PLAN_SLICE ? nb - k0 : PLAN_SLICE;
+        __syncthreads();
+#pragma unroll 4
+        for (int i = tid; i <= cnt; i += NT) ends[i] = bel[k0 + i];
+        __syncthreads();
+        if (tid < WAVE) {
+            for (int i0 = 0; i0 < cnt; i0 += WAVE) {
+                const int i = i0 + tid;
+                const bool valid = i < cnt;
+                const u32 e = valid ? ends[i + 1] : 0u;
+                const u32 before = valid ? ends[i] : 0u;            // where the bin before this one ends
+                int from = 0;
+                for (;;) {
+                    const bool opens = valid && tid >= from && (k0 + i == 0 || e - first_key > fill);
+                    const unsigned long long m = __ballot(opens);
+                    if (!m) break;
+                    const int at = __builtin_amdgcn_readfirstlane(__ffsll((long long)m) - 1);   // bin k0 + i0 + at opens a window
+                    if (tid == at && found < (u32)max_win) ws[found] = (u32)(k0 + i);
+                    ++found;
+                    first_key = (u32)__builtin_amdgcn_readlane((int)before, at);
+                    from = at + 1;
+                }
+            }
+        }
     }
     if (tid == 0) {
-        // more starts than max_win can only come from unsorted rows; the last window then runs to the end
+        // more starts than max_win cannot come from sorted rows; the last window then runs to the end
         const u32 nwin = found < (u32)max_win ? found : (u32)max_win;
         ws[nwin] = (u32)nb;
-        if (nwin > 0) wv[nwin - 1].Elast = ii.range;
         info[b].nwin = nwin;
+        found_all = nwin;
     }
-    // the windows' values are complete: their bucket maps
+    }
+    if (tid < SEGS) tab[tid] = segtab[b * (i64)SEGS + tid];
     __threadfence_block();
     __syncthreads();
-    const u32 nwin = found < (u32)max_win ? found : (u32)max_win;
+    const u32 nwin = found_all;
     for (u32 j = tid; j < nwin; j += NT) {
-        const u64 span = wv[j].Elast - wv[j].A;
+        const u64 first = fine_bin_start(ws[j], ii, tab);
+        const u64 last = j + 1 < nwin ? fine_bin_start(ws[j + 1], ii, tab) - 1 : ii.range;
+        const u64 span = last - first;
         const u32 scale = linear_scale(span <= 0xffffffffull ? span : 0xffffffffull, buckets);
-        wv[j].scale = scale;
-        wv[j].inv52 = (1ull << 52) / scale;
-        wv[j].pad_ = 0;
+        WinVal v;
+        v.A = first;
+        v.Elast = last;
+        v.scale = scale;
+        v.inv52 = (1ull << 52) / scale;
+        v.pad_ = 0;
+        wv[j] = v;
     }
 }
 
@@ -2152,9 +2312,6 @@ __device__ __forceinline__ void zl_range_window(const Smem& sm, const Rows& rw, 
 // Returns false if the window has to be left to the sort-based search (too many
 // entries for the list to fit behind them, or too many listed).
 
-// Fine bins per group of the range plan.  Windows must leave room for the short list, and
-// with few rows (windows of 4096 slots) a fine bin of a quarter group often takes them past it.
-inline int range_fine_log2(int P) { return P >= 512 ? 2 : 3; }
 
 template <int NT, int ITEMS, class CT>
 __device__ __forceinline__ bool zl_range_bucket_search(const Smem& sm, const Rows& rw, const WinVal& wv, u64 thr,
@@ -2451,40 +2608,54 @@ __global__ __launch_bounds__(NT) void zl_range_instance_kernel(
         iters[b * (i64)P + p] = zl_iters(inst + (size_t)p * R, R, bar);
 }
 
-// One workgroup per window of the multi-window path; results go to `partial`
-// (reduced by zl_finish_kernel like those of the summed-wait search).
+// The windows zl_range_fast_kernel marked: the sort-based search.  A fixed grid; every
+// workgroup looks through its share of the window results for the marks and handles the
+// marked windows one after the other.  Results go to `partial` (reduced by
+// zl_finish_kernel like those of the summed-wait search).
 template <int NT, int ITEMS>
 __global__ __launch_bounds__(NT) void zl_range_window_kernel(
     const i64* __restrict__ ts, i64 B, int P, int R,
     const InstInfo* __restrict__ info, const void* __restrict__ cross, bool narrow, int stride,
-    const u32* __restrict__ winstart, const WinVal* __restrict__ winval, int max_win, bool only_marked,
+    const u32* __restrict__ winstart, const WinVal* __restrict__ winval, int max_win,
     Partial* __restrict__ partial, int* __restrict__ status)
 {
     using C = WinCfg<NT, ITEMS>;
     __shared__ __align__(16) unsigned char smem[C::BYTES];
     const Smem sm = carve<NT, ITEMS>(smem);
-    const i64 b = blockIdx.x / (u32)max_win;
-    const int j = (int)(blockIdx.x % (u32)max_win);
-    if (b >= B) return;
-    const InstInfo ii = info[b];
-    if (j >= (int)ii.nwin) return;
-    if (only_marked) {                            // the fast kernel ran first: only what it left
-        const Partial seen = partial[b * (i64)max_win + j];
-        if (!(seen.wait == U64_MAX && seen.brel == DEFERRED_WINDOW)) return;
-    }
-    const WinPos w = locate_window(b, j, ii, ts, nullptr, nullptr, P, R, cross, narrow, stride, winstart, winval, max_win);
-    Partial r;
-    r.wait = U64_MAX;
-    r.brel = 0;
-    int bad = 0;
-    bool fits = true;
-    if (ii.range >= 0xffffffffull) fits = false;
-    else if (w.valid) zl_range_window<NT, ITEMS>(sm, w.rw, ii.thr, w.A, w.Elast, r.wait, r.brel, bad);
-    bad = __syncthreads_or(bad);
-    if (threadIdx.x == 0) {
-        partial[b * (i64)max_win + j] = r;
-        if (status && (bad || !fits))
-            atomicOr(status + b, (bad ? (int)EBSP_STATUS_UNSORTED : 0) | (fits ? 0 : (int)EBSP_STATUS_UNSUPPORTED));
+    const u32 total = (u32)(B * (i64)max_win);
+    const u32 share = (total + gridDim.x - 1) / gridDim.x;
+    const u32 first = blockIdx.x * share;
+    const u32 end = first + share < total ? first + share : total;
+
+    for (u32 base = first; base < end; base += NT) {
+        const u32 idx = base + threadIdx.x;
+        bool mine = false;
+        if (idx < end) {
+            const u32 b = idx / (u32)max_win, j = idx % (u32)max_win;
+            if (j < info[b].nwin) mine = partial[idx].wait == U64_MAX && partial[idx].brel == DEFERRED_WINDOW;
+        }
+        for (;;) {
+            const u32 pick = block_reduce<u32, NT>(mine ? idx : 0xffffffffu, (u32*)sm.red, OpMin());
+            if (pick == 0xffffffffu) break;
+            if (pick == idx) mine = false;
+            const i64 b = pick / (u32)max_win;
+            const InstInfo ii = info[b];
+            const WinPos w = locate_window(b, (int)(pick % (u32)max_win), ii, ts, nullptr, nullptr, P, R, cross, narrow,
+                                           stride, winstart, winval, max_win);
+            Partial r;
+            r.wait = U64_MAX;
+            r.brel = 0;
+            int bad = 0;
+            bool fits = true;
+            if (ii.range >= 0xffffffffull) fits = false;
+            else if (w.valid) zl_range_window<NT, ITEMS>(sm, w.rw, ii.thr, w.A, w.Elast, r.wait, r.brel, bad);
+            bad = __syncthreads_or(bad);
+            if (threadIdx.x == 0) {
+                partial[pick] = r;
+                if (status && (bad || !fits))
+                    atomicOr(status + b, (bad ? (int)EBSP_STATUS_UNSORTED : 0) | (fits ? 0 : (int)EBSP_STATUS_UNSUPPORTED));
+            }
+        }
     }
 }
 
@@ -2560,23 +2731,24 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 struct Tuning {          // 0: choose by shape
     int window_cap;
     int single_max;
+    int window_fill;
 };
-Tuning g_tune = {0, 0};
+Tuning g_tune = {0, 0, 0};
 
 struct Plan {
     bool multi;
     int cap;           // records per window workgroup
-    int group_shift;   // log2(cap) - 1
+    int fill;          // most entries of a window (unless a single fine bin holds more)
     int bins;          // fine bins per instance
     int stride;        // bins + 1 crossing indices per row
     int max_win;       // windows per instance <= max_win
     bool narrow;       // crossing indices fit 16 bits
-    int step;          // zl_bincount looks at every step-th row
-    size_t off_info, off_cross, off_below, off_winstart, off_winval, off_partial, off_rowpar, bytes;
+    size_t off_info, off_seg, off_cross, off_below, off_winstart, off_winval, off_partial, off_rowpar, bytes;
 };
 
-// single_limit: the most entries one workgroup takes whole on the path the plan is for
-bool make_plan(i64 B, int P, int R, Plan& pl, int single_limit = SINGLE_MAX, int fine_per_group_log2 = 2)
+// single_limit: the most entries one workgroup takes whole on the path the plan is for;
+// list_room: windows leave a quarter or more of the workgroup's records free (the fast range search keeps its short list there)
+bool make_plan(i64 B, int P, int R, Plan& pl, int single_limit = SINGLE_MAX, bool list_room = false)
 {
     if (B < 0 || P < 1 || R < 1) return false;
     const i64 n = (i64)P * (i64)R;
@@ -2588,16 +2760,21 @@ bool make_plan(i64 B, int P, int R, Plan& pl, int single_limit = SINGLE_MAX, int
     if (!pl.multi) return true;
     // the per-window cost has a term proportional to P: larger windows for more rows
     pl.cap = g_tune.window_cap > 0 ? g_tune.window_cap : (P >= 512 ? 8192 : 4096);
-    pl.group_shift = pl.cap == 16384 ? 13 : (pl.cap == 8192 ? 12 : 11);
-    const int fine_shift = pl.group_shift - fine_per_group_log2;      // a window exceeds its group's 2^group_shift keys by at most one fine bin
+    const int fine_shift = (pl.cap == 16384 ? 14 : (pl.cap == 8192 ? 13 : 12)) - 3;       // fine bins of cap/8 keys on average
+    pl.fill = g_tune.window_fill > 0 && g_tune.window_fill < pl.cap ? g_tune.window_fill : pl.cap;
+    if (list_room) {
+        // with few workers a larger share of a window's entries is min(Z) at some time and has to be listed
+        const int room = P < 128 ? pl.cap / 2 : pl.cap / 4;
+        if (pl.fill > pl.cap - room) pl.fill = pl.cap - room;
+    }
     pl.bins = (int)((n + (1 << fine_shift) - 1) >> fine_shift);
     pl.stride = pl.bins + 1;
-    // the counts behind the grouping are estimates; a whole number of workgroups per instance
-    pl.max_win = (int)((((n + n / 4) >> pl.group_shift) + 2 + WINDOWS_PER_BLOCK - 1) / WINDOWS_PER_BLOCK * WINDOWS_PER_BLOCK);
+    // two windows in a row hold more than `fill` keys, or they would be one; a whole number of workgroups per instance
+    pl.max_win = (int)((2 * n / pl.fill + 3 + WINDOWS_PER_BLOCK - 1) / WINDOWS_PER_BLOCK * WINDOWS_PER_BLOCK);
     size_t o = 0;
     pl.off_info = o;     o = align_up(o + (size_t)B * sizeof(InstInfo), 256);
+    pl.off_seg = o;      o = align_up(o + (size_t)B * SEGS * sizeof(SegEntry), 256);
     pl.narrow = R < 65536;
-    pl.step = P / 256 > 1 ? P / 256 : 1;
     pl.off_cross = o;    o = align_up(o + (size_t)B * P * pl.stride * (pl.narrow ? 2 : 4), 256);
     pl.off_below = o;    o = align_up(o + (size_t)B * pl.stride * sizeof(u32), 256);
     pl.off_winstart = o; o = align_up(o + (size_t)B * (pl.max_win + 1) * sizeof(u32), 256);
@@ -2680,6 +2857,7 @@ int run_batch(const i64* ts, const i64* le, const i64* iv, i64 B, int P, int R,
 
     char* wsp = (char*)workspace;
     InstInfo* info = (InstInfo*)(wsp + pl.off_info);
+    SegEntry* segtab = (SegEntry*)(wsp + pl.off_seg);
     void* cross = (void*)(wsp + pl.off_cross);
     u32* below = (u32*)(wsp + pl.off_below);
     u32* winstart = (u32*)(wsp + pl.off_winstart);
@@ -2687,7 +2865,7 @@ int run_batch(const i64* ts, const i64* le, const i64* iv, i64 B, int P, int R,
     Partial* partial = (Partial*)(wsp + pl.off_partial);
     uint2* rowpar = pred ? (uint2*)(wsp + pl.off_rowpar) : nullptr;
 
-    LAUNCH(K_BOUNDS, (zl_bounds_kernel<256>), dim3((unsigned)B), dim3(256), ts, le, iv, P, R, pl.bins, info, rowpar, status);
+    LAUNCH(K_BOUNDS, (zl_bounds_kernel<256>), dim3((unsigned)B), dim3(256), ts, le, iv, P, R, pl.bins, info, segtab, rowpar, status);
     const i64 nrows = B * (i64)P;
     const i64 kblocks = (pl.stride + 63) / 64, pblocks = (P + 255) / 256, kblocks256 = (pl.stride + 255) / 256;
     if (kblocks * B > 0x7fffffffll || pblocks * B > 0x7fffffffll) return fail(EBSP_ERR_SHAPE, "batch too large for one call");
@@ -2695,25 +2873,29 @@ int run_batch(const i64* ts, const i64* le, const i64* iv, i64 B, int P, int R,
         if (pl.narrow)
             LAUNCH(K_PARTITION_PRED, zl_partition_pred_kernel<unsigned short>,
                    dim3((unsigned)(kblocks256 * B), (unsigned)((P + PRED_ROWS_PER_BLOCK - 1) / PRED_ROWS_PER_BLOCK)), dim3(256),
-                   le, iv, P, R, info, (unsigned short*)cross, pl.stride);
+                   le, iv, P, R, info, segtab, (unsigned short*)cross, pl.stride);
         else
             LAUNCH(K_PARTITION_PRED, zl_partition_pred_kernel<u32>,
                    dim3((unsigned)(kblocks256 * B), (unsigned)((P + PRED_ROWS_PER_BLOCK - 1) / PRED_ROWS_PER_BLOCK)), dim3(256),
-                   le, iv, P, R, info, (u32*)cross, pl.stride);
+                   le, iv, P, R, info, segtab, (u32*)cross, pl.stride);
     } else if (pl.narrow)
         LAUNCH(K_PARTITION, (zl_partition_kernel<256, unsigned short>), dim3((unsigned)((nrows + 3) / 4)), dim3(256),
-               ts, nrows, P, R, info, (unsigned short*)cross, pl.stride, status);
+               ts, nrows, P, R, info, segtab, (unsigned short*)cross, pl.stride, status);
     else
         LAUNCH(K_PARTITION, (zl_partition_kernel<256, u32>), dim3((unsigned)((nrows + 3) / 4)), dim3(256),
-               ts, nrows, P, R, info, (u32*)cross, pl.stride, status);
+               ts, nrows, P, R, info, segtab, (u32*)cross, pl.stride, status);
     if (pl.narrow)
         LAUNCH(K_BINCOUNT, zl_bincount_kernel<unsigned short>, dim3((unsigned)(kblocks * B)), dim3(256),
-               (const unsigned short*)cross, P, R, pl.stride, pl.step, info, below);
+               (const unsigned short*)cross, P, R, pl.stride, info, below);
     else
         LAUNCH(K_BINCOUNT, zl_bincount_kernel<u32>, dim3((unsigned)(kblocks * B)), dim3(256),
-               (const u32*)cross, P, R, pl.stride, pl.step, info, below);
-    LAUNCH(K_PLAN, (zl_plan_kernel<1024>), dim3((unsigned)B), dim3(1024), info, below, pl.stride, winstart, winval,
-           pl.max_win, pl.group_shift, (u32)(pl.cap / 8));
+               (const u32*)cross, P, R, pl.stride, info, below);
+    if (pl.bins <= 1024)      // small instances, many of them: small workgroups
+        LAUNCH(K_PLAN, (zl_plan_kernel<256, 1024>), dim3((unsigned)B), dim3(256), info, segtab, below, pl.stride, winstart, winval,
+               pl.max_win, (u32)pl.fill, (u32)(pl.cap / 8));
+    else
+        LAUNCH(K_PLAN, (zl_plan_kernel<1024, 4096>), dim3((unsigned)B), dim3(1024), info, segtab, below, pl.stride, winstart, winval,
+               pl.max_win, (u32)pl.fill, (u32)(pl.cap / 8));
     const u32 groups = (u32)(pl.max_win / WINDOWS_PER_BLOCK);
     const u32 groups_inv = groups > 1 ? (u32)((1ull << 32) / groups) : 0xffffffffu;
     const unsigned wgrid = (unsigned)((B * (i64)groups + 7) / 8 * 8);
@@ -2744,11 +2926,12 @@ int run_batch(const i64* ts, const i64* le, const i64* iv, i64 B, int P, int R,
 // kernels that cut an instance into windows.
 constexpr int RANGE_SINGLE_MAX = WinCfg<LARGE_NT, LARGE_ITEMS>::CAP_WIDE;
 
+
 int run_range_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters, i64* dmin, int* status,
                     void* workspace, size_t workspace_bytes, hipStream_t st)
 {
     Plan pl;
-    if (!make_plan(B, P, R, pl, RANGE_SINGLE_MAX, range_fine_log2(P)))
+    if (!make_plan(B, P, R, pl, RANGE_SINGLE_MAX, true))
         return fail(EBSP_ERR_SHAPE, "invalid shape: need B >= 0, P >= 1, R >= 1, P*R < 2^31");
     if (B == 0) return EBSP_OK;
     if (!ts || !barrier || !iters || !dmin) return fail(EBSP_ERR_NULL, "ts, barrier, iters and dmin must not be NULL");
@@ -2766,6 +2949,7 @@ int run_range_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters
 
     char* wsp = (char*)workspace;
     InstInfo* info = (InstInfo*)(wsp + pl.off_info);
+    SegEntry* segtab = (SegEntry*)(wsp + pl.off_seg);
     void* cross = (void*)(wsp + pl.off_cross);
     u32* below = (u32*)(wsp + pl.off_below);
     u32* winstart = (u32*)(wsp + pl.off_winstart);
@@ -2773,24 +2957,28 @@ int run_range_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters
     Partial* partial = (Partial*)(wsp + pl.off_partial);
 
     LAUNCH(K_BOUNDS, (zl_bounds_kernel<256>), dim3((unsigned)B), dim3(256), ts, nullptr, nullptr, P, R, pl.bins, info,
-           nullptr, status);
+           segtab, nullptr, status);
     const i64 nrows = B * (i64)P;
     if (pl.narrow)
         LAUNCH(K_PARTITION, (zl_partition_kernel<256, unsigned short>), dim3((unsigned)((nrows + 3) / 4)), dim3(256),
-               ts, nrows, P, R, info, (unsigned short*)cross, pl.stride, status);
+               ts, nrows, P, R, info, segtab, (unsigned short*)cross, pl.stride, status);
     else
         LAUNCH(K_PARTITION, (zl_partition_kernel<256, u32>), dim3((unsigned)((nrows + 3) / 4)), dim3(256),
-               ts, nrows, P, R, info, (u32*)cross, pl.stride, status);
+               ts, nrows, P, R, info, segtab, (u32*)cross, pl.stride, status);
     const i64 kblocks = (pl.stride + 63) / 64, pblocks = (P + 255) / 256;
     if (kblocks * B > 0x7fffffffll || pblocks * B > 0x7fffffffll) return fail(EBSP_ERR_SHAPE, "batch too large for one call");
     if (pl.narrow)
         LAUNCH(K_BINCOUNT, zl_bincount_kernel<unsigned short>, dim3((unsigned)(kblocks * B)), dim3(256),
-               (const unsigned short*)cross, P, R, pl.stride, pl.step, info, below);
+               (const unsigned short*)cross, P, R, pl.stride, info, below);
     else
         LAUNCH(K_BINCOUNT, zl_bincount_kernel<u32>, dim3((unsigned)(kblocks * B)), dim3(256),
-               (const u32*)cross, P, R, pl.stride, pl.step, info, below);
-    LAUNCH(K_PLAN, (zl_plan_kernel<1024>), dim3((unsigned)B), dim3(1024), info, below, pl.stride, winstart, winval,
-           pl.max_win, pl.group_shift, (u32)(pl.cap / 8));
+               (const u32*)cross, P, R, pl.stride, info, below);
+    if (pl.bins <= 1024)      // small instances, many of them: small workgroups
+        LAUNCH(K_PLAN, (zl_plan_kernel<256, 1024>), dim3((unsigned)B), dim3(256), info, segtab, below, pl.stride, winstart, winval,
+               pl.max_win, (u32)pl.fill, (u32)(pl.cap / 8));
+    else
+        LAUNCH(K_PLAN, (zl_plan_kernel<1024, 4096>), dim3((unsigned)B), dim3(1024), info, segtab, below, pl.stride, winstart, winval,
+               pl.max_win, (u32)pl.fill, (u32)(pl.cap / 8));
     const u32 groups = (u32)(pl.max_win / WINDOWS_PER_BLOCK);
     const u32 groups_inv = groups > 1 ? (u32)((1ull << 32) / groups) : 0xffffffffu;
     const unsigned wgrid = (unsigned)((B * (i64)groups + 7) / 8 * 8);
@@ -2806,12 +2994,13 @@ int run_range_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters
     }
 #undef LAUNCH_RANGE
     // what the fast kernel left: the sort-based search, one workgroup per marked window
-    if (pl.cap <= 4096)       // windows of about 2048 entries fit a 512-thread workgroup's sort (three workgroups per CU)
-        LAUNCH(K_RANGE_WINDOW, (zl_range_window_kernel<512, 16>), dim3((unsigned)total_win), dim3(512),
-               ts, B, P, R, info, cross, pl.narrow, pl.stride, winstart, winval, pl.max_win, true, partial, status);
+    // the windows the fast kernel marked; more workgroups than fit at once, so that uneven shares even out
+    if (pl.cap <= 4096)       // such windows fit a 512-thread workgroup's sort (three workgroups per CU)
+        LAUNCH(K_RANGE_WINDOW, (zl_range_window_kernel<512, 16>), dim3(8 * GENERAL_GRID), dim3(512),
+               ts, B, P, R, info, cross, pl.narrow, pl.stride, winstart, winval, pl.max_win, partial, status);
     else
-        LAUNCH(K_RANGE_WINDOW, (zl_range_window_kernel<LARGE_NT, LARGE_ITEMS>), dim3((unsigned)total_win), dim3(LARGE_NT),
-               ts, B, P, R, info, cross, pl.narrow, pl.stride, winstart, winval, pl.max_win, true, partial, status);
+        LAUNCH(K_RANGE_WINDOW, (zl_range_window_kernel<LARGE_NT, LARGE_ITEMS>), dim3(4 * GENERAL_GRID), dim3(LARGE_NT),
+               ts, B, P, R, info, cross, pl.narrow, pl.stride, winstart, winval, pl.max_win, partial, status);
     LAUNCH(K_FINISH, (zl_finish_kernel<256>), dim3((unsigned)(pblocks * B)), dim3(256),
            ts, nullptr, nullptr, P, R, info, partial, pl.max_win, barrier, iters, dmin);
     return EBSP_OK;
@@ -2853,7 +3042,7 @@ int ebsp_predict_zipline_batch(const int64_t* last_end, const int64_t* interval,
 size_t ebsp_zipline_range_workspace_bytes(int64_t B, int32_t P, int32_t R)
 {
     Plan pl;
-    if (!make_plan(B, P, R, pl, RANGE_SINGLE_MAX, range_fine_log2(P))) return 0;
+    if (!make_plan(B, P, R, pl, RANGE_SINGLE_MAX, true)) return 0;
     return pl.multi ? pl.bytes : 0;
 }
 
@@ -2876,17 +3065,21 @@ int ebsp_zipline_shape_info(int64_t B, int32_t P, int32_t R, int64_t* info)
     info[1] = pl.multi ? pl.cap : 0;
     info[2] = pl.multi ? pl.bins : 0;
     info[3] = pl.multi ? pl.max_win : 0;
+    info[4] = pl.multi ? pl.fill : 0;
     return EBSP_OK;
 }
 
-int ebsp_zipline_tune(int32_t window_cap, int32_t single_max)
+int ebsp_zipline_tune(int32_t window_cap, int32_t single_max, int32_t window_fill)
 {
+    if (window_fill < 0 || (window_fill > 0 && window_fill < 512))
+        return fail(EBSP_ERR_SHAPE, "window_fill must be 0 or at least 512");
     if (window_cap != 0 && window_cap != 4096 && window_cap != 8192 && window_cap != 16384)
         return fail(EBSP_ERR_SHAPE, "window_cap must be 0, 4096, 8192 or 16384");
     if (single_max < 0 || single_max > SINGLE_MAX)
         return fail(EBSP_ERR_SHAPE, "single_max must be in 0..16384");
     g_tune.window_cap = window_cap;
     g_tune.single_max = single_max;
+    g_tune.window_fill = window_fill;
     return EBSP_OK;
 }
 

@@ -55,7 +55,7 @@ def load() -> ctypes.CDLL:
         lib.ebsp_zipline_shape_info.restype = ctypes.c_int
         lib.ebsp_zipline_shape_info.argtypes = [i64, i32, i32, ctypes.POINTER(ctypes.c_int64)]
         lib.ebsp_zipline_tune.restype = ctypes.c_int
-        lib.ebsp_zipline_tune.argtypes = [i32, i32]
+        lib.ebsp_zipline_tune.argtypes = [i32, i32, i32]
         lib.ebsp_zipline_profile_begin.restype = ctypes.c_int
         lib.ebsp_zipline_profile_begin.argtypes = [i32]
         lib.ebsp_zipline_profile_end.restype = ctypes.c_int
@@ -85,17 +85,18 @@ def ebsp_zipline_range_workspace_bytes(B: int, P: int, R: int) -> int:
 
 
 def ebsp_zipline_shape_info(B: int, P: int, R: int) -> Dict[str, int]:
-    """How the library handles a shape: {'multi', 'window_cap', 'bins', 'max_windows'}."""
-    info = (ctypes.c_int64 * 4)()
+    """How the library handles a shape: {'multi', 'window_cap', 'bins', 'max_windows', 'window_fill'}."""
+    info = (ctypes.c_int64 * 5)()
     rc = load().ebsp_zipline_shape_info(B, P, R, info)
     if rc != EBSP_OK:
         raise ZipLineError(f"ebsp_zipline_shape_info failed ({rc}): {ebsp_last_error()}")
-    return {"multi": int(info[0]), "window_cap": int(info[1]), "bins": int(info[2]), "max_windows": int(info[3])}
+    return {"multi": int(info[0]), "window_cap": int(info[1]), "bins": int(info[2]), "max_windows": int(info[3]),
+            "window_fill": int(info[4])}
 
 
-def ebsp_zipline_tune(window_cap: int = 0, single_max: int = 0) -> None:
+def ebsp_zipline_tune(window_cap: int = 0, single_max: int = 0, window_fill: int = 0) -> None:
     """Set the process-wide tuning knobs (0 = default); see the header."""
-    rc = load().ebsp_zipline_tune(int(window_cap), int(single_max))
+    rc = load().ebsp_zipline_tune(int(window_cap), int(single_max), int(window_fill))
     if rc != EBSP_OK:
         raise ZipLineError(f"ebsp_zipline_tune failed ({rc}): {ebsp_last_error()}")
 

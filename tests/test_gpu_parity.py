@@ -85,6 +85,27 @@ def test_multi_window_shapes(zl, oracle, P, R):
     assert_same(zl, oracle, ts + EPOCH, f"P={P} R={R} shifted")
 
 
+@pytest.mark.parametrize("P,R", [(40, 60000), (600, 7100)])
+def test_more_fine_bins_than_the_plan_holds_in_lds(zl, oracle, P, R):
+    # above 4096 fine bins per instance the windows are packed by the sequential walk
+    assert zl.ebsp_zipline_shape_info(2, P, R)["bins"] > 4096
+    rng = np.random.default_rng(P + R)
+    ts = np.stack([workloads.random_small(rng, P, R, 1, 1000, ties=(i == 1)) for i in range(2)])
+    assert_same(zl, oracle, ts, f"P={P} R={R}")
+
+
+def test_results_do_not_depend_on_the_tuning_knobs(zl, oracle):
+    ts = workloads.make(4, instances=range(4))
+    try:
+        for cap, single, fill in [(0, 0, 0), (0, 0, 700), (8192, 0, 5000), (16384, 0, 0), (4096, 4096, 3000)]:
+            zl.ebsp_zipline_tune(cap, single, fill)
+            assert_same(zl, oracle, ts, f"tune {cap} {single} {fill}")
+            small = workloads.make(3, instances=range(8))
+            assert_same(zl, oracle, small, f"tune {cap} {single} {fill} config 3")
+    finally:
+        zl.ebsp_zipline_tune(0, 0, 0)
+
+
 def test_degenerate_values(zl, oracle):
     # all timestamps equal; all workers identical; one giant tie at the optimum
     assert_same(zl, oracle, np.full((3, 8, 16), 42, dtype=np.int64), "all equal")
