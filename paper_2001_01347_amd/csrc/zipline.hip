@@ -1638,30 +1638,38 @@ __global__ __launch_bounds__(256) void zl_partition_pred_kernel(
 
 // zl_bincount: below[b][k] = number of keys of instance b under fine bin k, k = 0..nb:
 // the column sums of cross.  Exact, so that zl_plan can fill windows to the brim.
+// A thread sums four neighbouring columns (one 8- or 16-byte load per row; `stride`
+// is a multiple of 8), the four waves of a workgroup take every fourth row each.
 template <class CT>
 __global__ __launch_bounds__(256) void zl_bincount_kernel(
     const CT* __restrict__ cross, int P, int R, int stride,
     const InstInfo* __restrict__ info, u32* __restrict__ below)
 {
-    __shared__ u32 part[256];
+    struct alignas(4 * sizeof(CT)) Four { CT v[4]; };
+    __shared__ u32 part[4][256];
     const int tid = threadIdx.x, kl = tid & 63, pg = tid >> 6;
-    const u32 kblocks = (u32)(stride + 63) / 64;
+    const u32 kblocks = (u32)(stride + 255) / 256;
     const i64 b = blockIdx.x / kblocks;
-    const int k = (int)(blockIdx.x % kblocks) * 64 + kl;
+    const int k = (int)(blockIdx.x % kblocks) * 256 + 4 * kl;          // k .. k + 3, all below stride or none
     const u32 nb = info[b].nb;
-    u32 s = 0;
+    u32 s0 = 0, s1 = 0, s2 = 0, s3 = 0;
     if (k <= (int)nb) {
         const CT* col = cross + (b * (i64)P) * stride + k;
 #pragma unroll 8
         for (int p = pg; p < P; p += 4) {
-            const u32 c = col[(i64)p * stride];
-            s += c < (u32)R ? c : (u32)R;
+            const Four c = *(const Four*)(col + (i64)p * stride);
+            s0 += c.v[0] < (u32)R ? (u32)c.v[0] : (u32)R;
+            s1 += c.v[1] < (u32)R ? (u32)c.v[1] : (u32)R;
+            s2 += c.v[2] < (u32)R ? (u32)c.v[2] : (u32)R;
+            s3 += c.v[3] < (u32)R ? (u32)c.v[3] : (u32)R;
         }
     }
-    part[tid] = s;
+    part[0][tid] = s0; part[1][tid] = s1; part[2][tid] = s2; part[3][tid] = s3;
     __syncthreads();
-    if (pg == 0 && k <= (int)nb)
-        below[b * (i64)stride + k] = part[kl] + part[64 + kl] + part[128 + kl] + part[192 + kl];
+    if (pg == 0)
+        for (int c = 0; c < 4; ++c)
+            if (k + c <= (int)nb)
+                below[b * (i64)stride + k + c] = part[c][kl] + part[c][64 + kl] + part[c][128 + kl] + part[c][192 + kl];
 }
 
 // zl_plan: windows of an instance.  below[] holds the exact number of keys under
@@ -2768,7 +2776,7 @@ bool make_plan(i64 B, int P, int R, Plan& pl, int single_limit = SINGLE_MAX, boo
         if (pl.fill > pl.cap - room) pl.fill = pl.cap - room;
     }
     pl.bins = (int)((n + (1 << fine_shift) - 1) >> fine_shift);
-    pl.stride = pl.bins + 1;
+    pl.stride = (pl.bins + 1 + 7) / 8 * 8;              // rows of cross start on 16-byte boundaries
     // two windows in a row hold more than `fill` keys, or they would be one; a whole number of workgroups per instance
     pl.max_win = (int)((2 * n / pl.fill + 3 + WINDOWS_PER_BLOCK - 1) / WINDOWS_PER_BLOCK * WINDOWS_PER_BLOCK);
     size_t o = 0;
@@ -2867,7 +2875,7 @@ int run_batch(const i64* ts, const i64* le, const i64* iv, i64 B, int P, int R,
 
     LAUNCH(K_BOUNDS, (zl_bounds_kernel<256>), dim3((unsigned)B), dim3(256), ts, le, iv, P, R, pl.bins, info, segtab, rowpar, status);
     const i64 nrows = B * (i64)P;
-    const i64 kblocks = (pl.stride + 63) / 64, pblocks = (P + 255) / 256, kblocks256 = (pl.stride + 255) / 256;
+    const i64 kblocks = (pl.stride + 255) / 256, pblocks = (P + 255) / 256, kblocks256 = (pl.stride + 255) / 256;
     if (kblocks * B > 0x7fffffffll || pblocks * B > 0x7fffffffll) return fail(EBSP_ERR_SHAPE, "batch too large for one call");
     if (pred) {
         if (pl.narrow)
@@ -2965,7 +2973,7 @@ int run_range_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters
     else
         LAUNCH(K_PARTITION, (zl_partition_kernel<256, u32>), dim3((unsigned)((nrows + 3) / 4)), dim3(256),
                ts, nrows, P, R, info, segtab, (u32*)cross, pl.stride, status);
-    const i64 kblocks = (pl.stride + 63) / 64, pblocks = (P + 255) / 256;
+    const i64 kblocks = (pl.stride + 255) / 256, pblocks = (P + 255) / 256;
     if (kblocks * B > 0x7fffffffll || pblocks * B > 0x7fffffffll) return fail(EBSP_ERR_SHAPE, "batch too large for one call");
     if (pl.narrow)
         LAUNCH(K_BINCOUNT, zl_bincount_kernel<unsigned short>, dim3((unsigned)(kblocks * B)), dim3(256),
