@@ -675,7 +675,7 @@ constexpr int SUM_BITS = 46;
 constexpr u64 SUM_MASK = (1ull << SUM_BITS) - 1;
 constexpr u32 BUCKET_LIMIT = 64;
 constexpr int GATHER_BATCH = 8;           // elements a thread loads before it uses any of them
-constexpr int GATHER_TAIL = 4;            // the same beyond the first batch
+constexpr int GATHER_TAIL = 8;            // the same beyond the first batch
 
 template <int NT, int ITEMS>
 __device__ __forceinline__ Smem carve_hot(unsigned char* smem)
@@ -1122,7 +1122,7 @@ __device__ __forceinline__ int zl_delta_rows(const Smem& sm, const Rows& rw, u64
     gather_batch<NT, ITEMS, G0, PRED>(recs, bytes, rw.par, 0, total, start, key, dl, w0);
     static_assert((ITEMS - G0) % GATHER_TAIL == 0 || ITEMS < GATHER_BATCH, "tail batches must tile the items");
 #pragma unroll
-    for (int g = G0; g < ITEMS; g += GATHER_TAIL)           // a window seldom fills all items: smaller steps there
+    for (int g = G0; g < ITEMS; g += GATHER_TAIL)
         gather_batch<NT, ITEMS, GATHER_TAIL, PRED>(recs, bytes, rw.par, g, total, start, key, dl, w0);
     return total;
 }
@@ -1923,12 +1923,22 @@ __device__ __forceinline__ void window_pairs(
     u32 group = slot - b * groups;
     if (group >= groups) { ++b; group -= groups; }
     if ((i64)b >= B) return;
-    const InstInfo ii = info[b];
     const int j0 = (int)group * WINDOWS_PER_BLOCK;
-    const int jend = j0 + WINDOWS_PER_BLOCK < (int)ii.nwin ? j0 + WINDOWS_PER_BLOCK : (int)ii.nwin;
-    if (j0 >= jend) return;
     const u32* ws = winstart + b * (i64)(max_win + 1);       // max_win + 1 entries
     const WinVal* wv = winval + b * (i64)max_win;
+    // fine bins where the windows start and end and the windows' values: asked for together
+    // with the instance's facts, before anything depends on those (j0 + W <= max_win, so the
+    // addresses are valid even where the instance has fewer windows)
+    constexpr int W = WINDOWS_PER_BLOCK;
+    u32 bins[W + 1];
+    WinVal vals[W];
+#pragma unroll
+    for (int i = 0; i <= W; ++i) bins[i] = ws[j0 + i];
+#pragma unroll
+    for (int i = 0; i < W; ++i) vals[i] = wv[j0 + i];
+    const InstInfo ii = info[b];
+    const int jend = j0 + WINDOWS_PER_BLOCK < (int)ii.nwin ? j0 + WINDOWS_PER_BLOCK : (int)ii.nwin;
+    if (j0 >= jend) return;
     Partial* out = partial + b * (i64)max_win;
     const bool hot = !(ii.range >> 32) && (u64)P * (u64)R < HOT_MAX_ENTRIES;
     Rows rw;
@@ -1939,18 +1949,9 @@ __device__ __forceinline__ void window_pairs(
     rw.cr = (const void*)(cross + (b * (i64)P) * stride);
     rw.narrow = sizeof(CT) == 2;
     rw.stride = stride;
-    // fine bins where the windows start and end (stale scratch cannot index outside a
-    // row of cross) and the windows' values: all fetched before the first search
-    constexpr int W = WINDOWS_PER_BLOCK;
-    u32 bins[W + 1];
-    WinVal vals[W];
 #pragma unroll
-    for (int i = 0; i <= W; ++i) {
-        const u32 k = ws[j0 + i];                            // j0 + W <= max_win
-        bins[i] = k < ii.nb ? k : ii.nb;
-    }
-#pragma unroll
-    for (int i = 0; i < W; ++i) vals[i] = wv[j0 + i];
+    for (int i = 0; i <= W; ++i)                             // stale scratch cannot index outside a row of cross
+        bins[i] = bins[i] < ii.nb ? bins[i] : ii.nb;
     u32 lo[RPT], hi[RPT], next[RPT];
 #pragma unroll
     for (int c = 0; c < RPT; ++c) { lo[c] = hi[c] = next[c] = 0; }
