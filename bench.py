@@ -35,12 +35,13 @@ def algorithmic_bytes(kernel: str, B: int, P: int, R: int, bins: int, windows: i
         return 8.0 * n + B * (16.0 + 4.0 * P)
     if kernel == "zl_window_kernel":        # every timestamp once, two crossing rows per window, one result
         return 8.0 * n + windows * (2.0 * cw * P + 16.0)
-    if kernel == "zl_partition_kernel":     # every timestamp once, one crossing index per (row, bin)
-        return 8.0 * n + cw * B * P * (bins + 1)
-    if kernel == "zl_partition_pred_kernel":    # 16 bytes per worker, one crossing index per (row, bin)
-        return 16.0 * B * P + cw * B * P * (bins + 1)
-    if kernel == "zl_bincount_kernel":      # the crossing indices once, one count per bin
-        return cw * B * P * (bins + 1) + 4.0 * B * (bins + 1)
+    groups = (P + 15) // 16                 # rows of partial column sums per instance, when the bins fit LDS
+    if kernel == "zl_partition_kernel":     # every timestamp once, one crossing index per (row, bin), partial column sums
+        return 8.0 * n + cw * B * P * (bins + 1) + (4.0 * B * groups * (bins + 1) if bins + 1 <= 8200 else 0.0)
+    if kernel == "zl_partition_pred_kernel":    # 16 bytes per worker, one crossing index per (row, bin), partial column sums
+        return 16.0 * B * P + cw * B * P * (bins + 1) + 4.0 * B * ((P + 63) // 64) * (bins + 1)
+    if kernel == "zl_bincount_kernel":      # the partial column sums once (else the crossing indices), one count per bin
+        return (4.0 * B * groups if bins + 1 <= 8200 else cw * B * P) * (bins + 1) + 4.0 * B * (bins + 1)
     if kernel == "zl_bounds_kernel":        # first and last timestamp of every row (one 64-byte line each)
         return 128.0 * B * P
     if kernel == "zl_plan_kernel":

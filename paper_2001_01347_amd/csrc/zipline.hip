@@ -1599,6 +1599,61 @@ __global__ __launch_bounds__(NT) void zl_partition_kernel(
     for (int k = last_bin + 1 + lane; k <= (int)ii.nb; k += WAVE) out[k] = (CT)R;
 }
 
+// The same with the column sums on the way: a workgroup takes PART_ROWS consecutive rows of
+// one instance (one wave each), adds every crossing index it writes to an LDS array over
+// the fine bins and stores that array as part[b][g][k] = sum of cross[p][k] over the rows p
+// of group g.  zl_bincount then adds up P / PART_ROWS partial rows instead of P rows of
+// cross.  For instances whose fine bins fit the LDS array (stride <= PART_MAX_STRIDE).
+constexpr int PART_ROWS = 16;
+constexpr int PART_MAX_STRIDE = 8200;
+template <class CT>
+__global__ __launch_bounds__(PART_ROWS * WAVE) void zl_partition_sum_kernel(
+    const i64* __restrict__ ts, int P, int R, int groups,
+    const InstInfo* __restrict__ info, const SegEntry* __restrict__ segtab, CT* __restrict__ cross, int stride,
+    u32* __restrict__ part, int* __restrict__ status)
+{
+    constexpr int NT = PART_ROWS * WAVE;
+    __shared__ SegEntry tab[SEGS];
+    __shared__ u32 sums[PART_MAX_STRIDE];
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1);
+    const i64 b = blockIdx.x / (u32)groups;
+    const int g = (int)(blockIdx.x % (u32)groups);
+    const int p = g * PART_ROWS + (tid >> 6);
+    const InstInfo ii = info[b];
+    if (tid < SEGS) tab[tid] = segtab[b * (i64)SEGS + tid];
+    for (int k = tid; k <= (int)ii.nb; k += NT) sums[k] = 0;
+    __syncthreads();
+    if (p < P) {
+        const i64 row_id = b * (i64)P + p;
+        const i64* __restrict__ row = ts + row_id * (i64)R;
+        CT* __restrict__ out = cross + row_id * (i64)stride;
+        const u64 base = (u64)ii.base;
+        int carry = -1;                        // bin of the element before lane 0's
+        i64 carry_t = INT64_MIN;               // and its value
+        bool bad = false;
+        for (int i0 = 0; i0 < R; i0 += WAVE) {
+            const int i = i0 + lane;
+            int bin = -1;
+            i64 t = INT64_MAX;
+            if (i < R) { t = row[i]; bin = (int)fine_bin((u64)t - base, ii, tab); }
+            int pb = __shfl_up(bin, 1, WAVE);
+            i64 pt = __shfl_up(t, 1, WAVE);
+            if (lane == 0) { pb = carry; pt = carry_t; }
+            bad |= t < pt;                     // the only place the multi-window path checks every pair of neighbours
+            if (i < R)
+                for (int k = pb + 1; k <= bin; ++k) { out[k] = (CT)i; atomicAdd(&sums[k], (u32)i); }
+            carry = __shfl(bin, WAVE - 1, WAVE);
+            carry_t = __shfl(t, WAVE - 1, WAVE);
+        }
+        if (__any(bad) && lane == 0 && status) atomicOr(status + b, (int)EBSP_STATUS_UNSORTED);
+        const int last_bin = (int)fine_bin((u64)row[R - 1] - base, ii, tab);
+        for (int k = last_bin + 1 + lane; k <= (int)ii.nb; k += WAVE) { out[k] = (CT)R; atomicAdd(&sums[k], (u32)R); }
+    }
+    __syncthreads();
+    u32* __restrict__ mine = part + (b * (i64)groups + g) * stride;
+    for (int k = tid; k <= (int)ii.nb; k += NT) mine[k] = sums[k];
+}
+
 // zl_partition for predicted rows: the same crossing indices from arithmetic.  Row p
 // holds first + i * step (i < R, relative to the instance's base); the entries in
 // fine bins below k are those below the first value of bin k.  One thread per bin
@@ -1607,7 +1662,8 @@ constexpr int PRED_ROWS_PER_BLOCK = 64;
 template <class CT>
 __global__ __launch_bounds__(256) void zl_partition_pred_kernel(
     const i64* __restrict__ le, const i64* __restrict__ iv, int P, int R,
-    const InstInfo* __restrict__ info, const SegEntry* __restrict__ segtab, CT* __restrict__ cross, int stride)
+    const InstInfo* __restrict__ info, const SegEntry* __restrict__ segtab, CT* __restrict__ cross, int stride,
+    u32* __restrict__ part)
 {
     const u32 kblocks = (u32)(stride + 255) / 256;
     const i64 b = blockIdx.x / kblocks;
@@ -1622,6 +1678,7 @@ __global__ __launch_bounds__(256) void zl_partition_pred_kernel(
     const i64* __restrict__ ivp = iv + b * (i64)P;
     CT* __restrict__ out = cross + (b * (i64)P) * stride + k;
     const bool narrow_values = (ii.range >> 32) == 0;
+    u32 sum = 0;
     for (int p = p_begin; p < p_end; ++p) {
         const u64 step = (u64)ivp[p];
         const u64 first = (u64)lep[p] + step - (u64)ii.base;
@@ -1632,8 +1689,11 @@ __global__ __launch_bounds__(256) void zl_partition_pred_kernel(
         else if (step == 0) below = (u64)R;
         else if (narrow_values && (step >> 32) == 0) below = (u64)(((u32)(edge - first) - 1u) / (u32)step) + 1u;
         else below = (edge - first - 1) / step + 1;
-        out[(i64)p * stride] = (CT)(below < (u64)R ? below : (u64)R);
+        const u32 c = (u32)(below < (u64)R ? below : (u64)R);
+        out[(i64)p * stride] = (CT)c;
+        sum += c;
     }
+    part[(b * (i64)gridDim.y + blockIdx.y) * stride + k] = sum;      // this slice's share of the column sum
 }
 
 // zl_bincount: below[b][k] = number of keys of instance b under fine bin k, k = 0..nb:
@@ -2748,11 +2808,12 @@ struct Plan {
     bool multi;
     int cap;           // records per window workgroup
     int fill;          // most entries of a window (unless a single fine bin holds more)
+    int part_stored, part_pred;   // groups of rows whose column sums the partition kernels write (stored / predicted rows)
     int bins;          // fine bins per instance
     int stride;        // bins + 1 crossing indices per row
     int max_win;       // windows per instance <= max_win
     bool narrow;       // crossing indices fit 16 bits
-    size_t off_info, off_seg, off_cross, off_below, off_winstart, off_winval, off_partial, off_rowpar, bytes;
+    size_t off_info, off_seg, off_cross, off_part, off_below, off_winstart, off_winval, off_partial, off_rowpar, bytes;
 };
 
 // single_limit: the most entries one workgroup takes whole on the path the plan is for;
@@ -2785,6 +2846,10 @@ bool make_plan(i64 B, int P, int R, Plan& pl, int single_limit = SINGLE_MAX, boo
     pl.off_seg = o;      o = align_up(o + (size_t)B * SEGS * sizeof(SegEntry), 256);
     pl.narrow = R < 65536;
     pl.off_cross = o;    o = align_up(o + (size_t)B * P * pl.stride * (pl.narrow ? 2 : 4), 256);
+    pl.part_stored = pl.stride <= PART_MAX_STRIDE ? (P + PART_ROWS - 1) / PART_ROWS : 0;     // 0: zl_bincount reads cross itself
+    pl.part_pred = (P + PRED_ROWS_PER_BLOCK - 1) / PRED_ROWS_PER_BLOCK;
+    const int part_rows = pl.part_stored > pl.part_pred ? pl.part_stored : pl.part_pred;
+    pl.off_part = o;     o = align_up(o + (size_t)B * part_rows * pl.stride * sizeof(u32), 256);
     pl.off_below = o;    o = align_up(o + (size_t)B * pl.stride * sizeof(u32), 256);
     pl.off_winstart = o; o = align_up(o + (size_t)B * (pl.max_win + 1) * sizeof(u32), 256);
     pl.off_winval = o;   o = align_up(o + (size_t)B * pl.max_win * sizeof(WinVal), 256);
@@ -2822,6 +2887,69 @@ hipEvent_t* prof_slot(int kid, int which)
             return EBSP_ERR_LAUNCH;                                                        \
         }                                                                                  \
     } while (0)
+
+// The front of the multi-window path, shared by the objectives: per-instance facts and
+// fine-bin map, crossing indices, exact bin counts, windows.
+int plan_windows(const Plan& pl, const i64* ts, const i64* le, const i64* iv, i64 B, int P, int R,
+                 char* wsp, int* status, hipStream_t st)
+{
+    const bool pred = ts == nullptr;
+    InstInfo* info = (InstInfo*)(wsp + pl.off_info);
+    SegEntry* segtab = (SegEntry*)(wsp + pl.off_seg);
+    void* cross = (void*)(wsp + pl.off_cross);
+    u32* part = (u32*)(wsp + pl.off_part);
+    u32* below = (u32*)(wsp + pl.off_below);
+    u32* winstart = (u32*)(wsp + pl.off_winstart);
+    WinVal* winval = (WinVal*)(wsp + pl.off_winval);
+    uint2* rowpar = pred ? (uint2*)(wsp + pl.off_rowpar) : nullptr;
+    const i64 nrows = B * (i64)P;
+    const i64 kblocks = (pl.stride + 255) / 256;
+    const i64 widest = pl.part_stored > pl.part_pred ? pl.part_stored : pl.part_pred;
+    if (kblocks * B > 0x7fffffffll || widest * B > 0x7fffffffll) return fail(EBSP_ERR_SHAPE, "batch too large for one call");
+    LAUNCH(K_BOUNDS, (zl_bounds_kernel<256>), dim3((unsigned)B), dim3(256), ts, le, iv, P, R, pl.bins, info, segtab, rowpar, status);
+    int part_rows;                                    // rows of partial column sums per instance (0: none, count from cross)
+    if (pred) {
+        part_rows = pl.part_pred;
+        if (pl.narrow)
+            LAUNCH(K_PARTITION_PRED, zl_partition_pred_kernel<unsigned short>, dim3((unsigned)(kblocks * B), (unsigned)part_rows),
+                   dim3(256), le, iv, P, R, info, segtab, (unsigned short*)cross, pl.stride, part);
+        else
+            LAUNCH(K_PARTITION_PRED, zl_partition_pred_kernel<u32>, dim3((unsigned)(kblocks * B), (unsigned)part_rows),
+                   dim3(256), le, iv, P, R, info, segtab, (u32*)cross, pl.stride, part);
+    } else if (pl.part_stored > 0) {
+        part_rows = pl.part_stored;
+        if (pl.narrow)
+            LAUNCH(K_PARTITION, zl_partition_sum_kernel<unsigned short>, dim3((unsigned)(B * part_rows)), dim3(PART_ROWS * WAVE),
+                   ts, P, R, part_rows, info, segtab, (unsigned short*)cross, pl.stride, part, status);
+        else
+            LAUNCH(K_PARTITION, zl_partition_sum_kernel<u32>, dim3((unsigned)(B * part_rows)), dim3(PART_ROWS * WAVE),
+                   ts, P, R, part_rows, info, segtab, (u32*)cross, pl.stride, part, status);
+    } else {
+        part_rows = 0;
+        if (pl.narrow)
+            LAUNCH(K_PARTITION, (zl_partition_kernel<256, unsigned short>), dim3((unsigned)((nrows + 3) / 4)), dim3(256),
+                   ts, nrows, P, R, info, segtab, (unsigned short*)cross, pl.stride, status);
+        else
+            LAUNCH(K_PARTITION, (zl_partition_kernel<256, u32>), dim3((unsigned)((nrows + 3) / 4)), dim3(256),
+                   ts, nrows, P, R, info, segtab, (u32*)cross, pl.stride, status);
+    }
+    if (part_rows > 0)        // the partial sums are exact counts already: nothing to clamp
+        LAUNCH(K_BINCOUNT, zl_bincount_kernel<u32>, dim3((unsigned)(kblocks * B)), dim3(256),
+               (const u32*)part, part_rows, 0x7fffffff, pl.stride, info, below);
+    else if (pl.narrow)
+        LAUNCH(K_BINCOUNT, zl_bincount_kernel<unsigned short>, dim3((unsigned)(kblocks * B)), dim3(256),
+               (const unsigned short*)cross, P, R, pl.stride, info, below);
+    else
+        LAUNCH(K_BINCOUNT, zl_bincount_kernel<u32>, dim3((unsigned)(kblocks * B)), dim3(256),
+               (const u32*)cross, P, R, pl.stride, info, below);
+    if (pl.bins <= 1024)      // small instances, many of them: small workgroups
+        LAUNCH(K_PLAN, (zl_plan_kernel<256, 1024>), dim3((unsigned)B), dim3(256), info, segtab, below, pl.stride, winstart, winval,
+               pl.max_win, (u32)pl.fill, (u32)(pl.cap / 8));
+    else
+        LAUNCH(K_PLAN, (zl_plan_kernel<1024, 4096>), dim3((unsigned)B), dim3(1024), info, segtab, below, pl.stride, winstart, winval,
+               pl.max_win, (u32)pl.fill, (u32)(pl.cap / 8));
+    return EBSP_OK;
+}
 
 // The rows are either stored (ts != nullptr) or predicted: t[p][i] = le[p] + (i + 1) * iv[p] (ts == nullptr).
 int run_batch(const i64* ts, const i64* le, const i64* iv, i64 B, int P, int R,
@@ -2866,45 +2994,15 @@ int run_batch(const i64* ts, const i64* le, const i64* iv, i64 B, int P, int R,
 
     char* wsp = (char*)workspace;
     InstInfo* info = (InstInfo*)(wsp + pl.off_info);
-    SegEntry* segtab = (SegEntry*)(wsp + pl.off_seg);
     void* cross = (void*)(wsp + pl.off_cross);
-    u32* below = (u32*)(wsp + pl.off_below);
     u32* winstart = (u32*)(wsp + pl.off_winstart);
     WinVal* winval = (WinVal*)(wsp + pl.off_winval);
     Partial* partial = (Partial*)(wsp + pl.off_partial);
     uint2* rowpar = pred ? (uint2*)(wsp + pl.off_rowpar) : nullptr;
 
-    LAUNCH(K_BOUNDS, (zl_bounds_kernel<256>), dim3((unsigned)B), dim3(256), ts, le, iv, P, R, pl.bins, info, segtab, rowpar, status);
-    const i64 nrows = B * (i64)P;
-    const i64 kblocks = (pl.stride + 255) / 256, pblocks = (P + 255) / 256, kblocks256 = (pl.stride + 255) / 256;
-    if (kblocks * B > 0x7fffffffll || pblocks * B > 0x7fffffffll) return fail(EBSP_ERR_SHAPE, "batch too large for one call");
-    if (pred) {
-        if (pl.narrow)
-            LAUNCH(K_PARTITION_PRED, zl_partition_pred_kernel<unsigned short>,
-                   dim3((unsigned)(kblocks256 * B), (unsigned)((P + PRED_ROWS_PER_BLOCK - 1) / PRED_ROWS_PER_BLOCK)), dim3(256),
-                   le, iv, P, R, info, segtab, (unsigned short*)cross, pl.stride);
-        else
-            LAUNCH(K_PARTITION_PRED, zl_partition_pred_kernel<u32>,
-                   dim3((unsigned)(kblocks256 * B), (unsigned)((P + PRED_ROWS_PER_BLOCK - 1) / PRED_ROWS_PER_BLOCK)), dim3(256),
-                   le, iv, P, R, info, segtab, (u32*)cross, pl.stride);
-    } else if (pl.narrow)
-        LAUNCH(K_PARTITION, (zl_partition_kernel<256, unsigned short>), dim3((unsigned)((nrows + 3) / 4)), dim3(256),
-               ts, nrows, P, R, info, segtab, (unsigned short*)cross, pl.stride, status);
-    else
-        LAUNCH(K_PARTITION, (zl_partition_kernel<256, u32>), dim3((unsigned)((nrows + 3) / 4)), dim3(256),
-               ts, nrows, P, R, info, segtab, (u32*)cross, pl.stride, status);
-    if (pl.narrow)
-        LAUNCH(K_BINCOUNT, zl_bincount_kernel<unsigned short>, dim3((unsigned)(kblocks * B)), dim3(256),
-               (const unsigned short*)cross, P, R, pl.stride, info, below);
-    else
-        LAUNCH(K_BINCOUNT, zl_bincount_kernel<u32>, dim3((unsigned)(kblocks * B)), dim3(256),
-               (const u32*)cross, P, R, pl.stride, info, below);
-    if (pl.bins <= 1024)      // small instances, many of them: small workgroups
-        LAUNCH(K_PLAN, (zl_plan_kernel<256, 1024>), dim3((unsigned)B), dim3(256), info, segtab, below, pl.stride, winstart, winval,
-               pl.max_win, (u32)pl.fill, (u32)(pl.cap / 8));
-    else
-        LAUNCH(K_PLAN, (zl_plan_kernel<1024, 4096>), dim3((unsigned)B), dim3(1024), info, segtab, below, pl.stride, winstart, winval,
-               pl.max_win, (u32)pl.fill, (u32)(pl.cap / 8));
+    if (int rc = plan_windows(pl, ts, le, iv, B, P, R, wsp, status, st)) return rc;
+    const i64 pblocks = (P + 255) / 256;
+    if (pblocks * B > 0x7fffffffll) return fail(EBSP_ERR_SHAPE, "batch too large for one call");
     const u32 groups = (u32)(pl.max_win / WINDOWS_PER_BLOCK);
     const u32 groups_inv = groups > 1 ? (u32)((1ull << 32) / groups) : 0xffffffffu;
     const unsigned wgrid = (unsigned)((B * (i64)groups + 7) / 8 * 8);
@@ -2958,36 +3056,14 @@ int run_range_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters
 
     char* wsp = (char*)workspace;
     InstInfo* info = (InstInfo*)(wsp + pl.off_info);
-    SegEntry* segtab = (SegEntry*)(wsp + pl.off_seg);
     void* cross = (void*)(wsp + pl.off_cross);
-    u32* below = (u32*)(wsp + pl.off_below);
     u32* winstart = (u32*)(wsp + pl.off_winstart);
     WinVal* winval = (WinVal*)(wsp + pl.off_winval);
     Partial* partial = (Partial*)(wsp + pl.off_partial);
 
-    LAUNCH(K_BOUNDS, (zl_bounds_kernel<256>), dim3((unsigned)B), dim3(256), ts, nullptr, nullptr, P, R, pl.bins, info,
-           segtab, nullptr, status);
-    const i64 nrows = B * (i64)P;
-    if (pl.narrow)
-        LAUNCH(K_PARTITION, (zl_partition_kernel<256, unsigned short>), dim3((unsigned)((nrows + 3) / 4)), dim3(256),
-               ts, nrows, P, R, info, segtab, (unsigned short*)cross, pl.stride, status);
-    else
-        LAUNCH(K_PARTITION, (zl_partition_kernel<256, u32>), dim3((unsigned)((nrows + 3) / 4)), dim3(256),
-               ts, nrows, P, R, info, segtab, (u32*)cross, pl.stride, status);
-    const i64 kblocks = (pl.stride + 255) / 256, pblocks = (P + 255) / 256;
-    if (kblocks * B > 0x7fffffffll || pblocks * B > 0x7fffffffll) return fail(EBSP_ERR_SHAPE, "batch too large for one call");
-    if (pl.narrow)
-        LAUNCH(K_BINCOUNT, zl_bincount_kernel<unsigned short>, dim3((unsigned)(kblocks * B)), dim3(256),
-               (const unsigned short*)cross, P, R, pl.stride, info, below);
-    else
-        LAUNCH(K_BINCOUNT, zl_bincount_kernel<u32>, dim3((unsigned)(kblocks * B)), dim3(256),
-               (const u32*)cross, P, R, pl.stride, info, below);
-    if (pl.bins <= 1024)      // small instances, many of them: small workgroups
-        LAUNCH(K_PLAN, (zl_plan_kernel<256, 1024>), dim3((unsigned)B), dim3(256), info, segtab, below, pl.stride, winstart, winval,
-               pl.max_win, (u32)pl.fill, (u32)(pl.cap / 8));
-    else
-        LAUNCH(K_PLAN, (zl_plan_kernel<1024, 4096>), dim3((unsigned)B), dim3(1024), info, segtab, below, pl.stride, winstart, winval,
-               pl.max_win, (u32)pl.fill, (u32)(pl.cap / 8));
+    if (int rc = plan_windows(pl, ts, nullptr, nullptr, B, P, R, wsp, status, st)) return rc;
+    const i64 pblocks = (P + 255) / 256;
+    if (pblocks * B > 0x7fffffffll) return fail(EBSP_ERR_SHAPE, "batch too large for one call");
     const u32 groups = (u32)(pl.max_win / WINDOWS_PER_BLOCK);
     const u32 groups_inv = groups > 1 ? (u32)((1ull << 32) / groups) : 0xffffffffu;
     const unsigned wgrid = (unsigned)((B * (i64)groups + 7) / 8 * 8);

@@ -85,10 +85,11 @@ def test_multi_window_shapes(zl, oracle, P, R):
     assert_same(zl, oracle, ts + EPOCH, f"P={P} R={R} shifted")
 
 
-@pytest.mark.parametrize("P,R", [(40, 60000), (600, 7100)])
+@pytest.mark.parametrize("P,R", [(40, 60000), (600, 7100), (64, 70000)])
 def test_more_fine_bins_than_the_plan_holds_in_lds(zl, oracle, P, R):
-    # above 4096 fine bins per instance the windows are packed by the sequential walk
-    assert zl.ebsp_zipline_shape_info(2, P, R)["bins"] > 4096
+    # above 4096 fine bins per instance the windows are packed by the sequential walk; above 8200
+    # (the last shape, which also needs 32-bit crossing indices) the bins are counted from the whole table
+    assert zl.ebsp_zipline_shape_info(2, P, R)["bins"] > (8200 if R > 65535 else 4096)
     rng = np.random.default_rng(P + R)
     ts = np.stack([workloads.random_small(rng, P, R, 1, 1000, ties=(i == 1)) for i in range(2)])
     assert_same(zl, oracle, ts, f"P={P} R={R}")
