@@ -1,0 +1,55 @@
+// Reduction of the window results, iteration counts; the copy kernel used as a yardstick.
+// Part of the ZipLine library (see zipline.hip); device code for gfx950.
+#pragma once
+#include "zl_range.h"
+
+namespace {
+
+// zl_iters for the multi-window path: reduce the instance's window results
+// (first minimum: smaller wait, then earlier barrier), then count iterations.
+template <int NT>
+__global__ __launch_bounds__(NT) void zl_finish_kernel(
+    const i64* __restrict__ ts, const i64* __restrict__ le, const i64* __restrict__ iv, int P, int R,
+    const InstInfo* __restrict__ info, const Partial* __restrict__ partial, int max_win,
+    i64* __restrict__ barrier, int* __restrict__ iters, i64* __restrict__ wait)
+{
+    __shared__ u64 red[2 * (NT / WAVE)];
+    constexpr int NW = NT / WAVE;
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid >> 6;
+    const u32 pblocks = (u32)(P + NT - 1) / NT;
+    const i64 b = blockIdx.x / pblocks;
+    const int pblk = (int)(blockIdx.x % pblocks);
+    const InstInfo ii = info[b];
+    u64 bw = U64_MAX, bb = U64_MAX;
+    const Partial* pp = partial + b * (i64)max_win;
+    for (int j = tid; j < (int)ii.nwin; j += NT) {
+        const Partial r = pp[j];
+        if (r.wait < bw || (r.wait == bw && r.brel < bb)) { bw = r.wait; bb = r.brel; }
+    }
+    wave_argmin(bw, bb);
+    if (lane == WAVE - 1) { red[wave] = bw; red[NW + wave] = bb; }
+    __syncthreads();
+    bw = red[0]; bb = red[NW];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) {
+        const u64 ow = red[w], ob = red[NW + w];
+        if (ow < bw || (ow == bw && ob < bb)) { bw = ow; bb = ob; }
+    }
+    if (bw == U64_MAX) bb = 0;
+    const i64 bar = (i64)((u64)ii.base + bb);
+    if (pblk == 0 && tid == 0) { barrier[b] = bar; wait[b] = (i64)bw; }
+    const int p = pblk * NT + tid;
+    if (p < P)
+        iters[b * (i64)P + p] = zl_iters_of(ts ? ts + b * (i64)P * R : nullptr, le ? le + b * (i64)P : nullptr,
+                                            iv ? iv + b * (i64)P : nullptr, p, R, bar);
+}
+
+// Plain streaming copy of n 16-byte words: the yardstick that HBM byte counters
+// and achieved bandwidth of the other kernels are read against.
+__global__ __launch_bounds__(256) void zl_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, i64 n)
+{
+    const i64 stride = (i64)gridDim.x * blockDim.x;
+    for (i64 i = (i64)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+}
+
+}  // namespace

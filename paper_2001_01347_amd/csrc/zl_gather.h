@@ -1,0 +1,183 @@
+// Row segments of a window into (key, delta) records held in registers.
+// Part of the ZipLine library (see zipline.hip); device code for gfx950.
+#pragma once
+#include "zl_bucket.h"
+
+namespace {
+
+// zl_delta for the fast window path: the rows' index ranges are exactly the
+// window (no searching), every value of the instance fits 32 bits relative to
+// its base, and byte offsets into the instance fit 32 bits.  Two sweeps:
+//   1. one thread per row (a round covers 1024 rows): segment lengths, one block
+//      scan for the first slots, and a source word for every element of a
+//      segment written into that element's slot (index into the instance;
+//      FIRST_OF_ROW: the row's very first entry, which has no predecessor;
+//      FIRST_OF_SEGMENT: the entry whose predecessor lies before the window).
+//      The crossing indices of a round are all fetched before any is used.
+//   2. one thread per slot: read the source word, load the low words of the
+//      element and of its predecessor (GATHER_BATCH elements of a thread in
+//      flight together; consecutive slots are consecutive addresses within a
+//      segment) and keep the (key, delta) records in registers: item j of
+//      thread t is slot j*NT + t.  key = t - (base + a), delta = t - predecessor
+//      (the window start for a row's first entry).  W0 = sum_p (a - last value
+//      of row p before the window) is collected from the segment-first entries;
+//      rows without any entry in the window add their share in sweep 1.
+// Returns the number of entries; nothing is loaded if it exceeds `cap`.
+constexpr u64 FIRST_OF_ROW = 1ull << 32, FIRST_OF_SEGMENT = 1ull << 33;
+constexpr int PRED_ROW_SHIFT = 34;        // predicted rows: the row number sits above the two flags
+// rows a thread takes per round of sweep 1: one round covers 1024 rows
+template <int NT> constexpr int ROWS_PER_THREAD = NT >= 1024 ? 1 : 1024 / NT;
+constexpr int WINDOWS_PER_BLOCK = 2;      // consecutive windows a workgroup handles, one after the other
+constexpr u64 HOT_MAX_ENTRIES = 1ull << 29;   // P*R below this: byte offsets into an instance fit 32 bits
+
+template <int NT, class CT>
+__device__ __forceinline__ void load_ranges(const Rows& rw, int p0, u32 (&lo)[ROWS_PER_THREAD<NT>], u32 (&hi)[ROWS_PER_THREAD<NT>])
+{
+#pragma unroll
+    for (int c = 0; c < ROWS_PER_THREAD<NT>; ++c) {
+        const int p = p0 + c * NT + (int)threadIdx.x;
+        lo[c] = 0; hi[c] = 0;
+        if (p < rw.P) rw.range_as<CT>(p, lo[c], hi[c]);
+    }
+}
+
+// Sweep 2 for items [g, g + G) of every thread.  Only the low words of the
+// timestamps are loaded (rows were checked for order by zl_partition).
+// Crossing indices of the thread's rows of the first round at fine bin k (0 for rows beyond P).
+template <int NT, class CT>
+__device__ __forceinline__ void load_column(const Rows& rw, u32 k, u32 (&out)[ROWS_PER_THREAD<NT>])
+{
+#pragma unroll
+    for (int c = 0; c < ROWS_PER_THREAD<NT>; ++c) {
+        const int p = c * NT + (int)threadIdx.x;
+        out[c] = 0;
+        if (p < rw.P) out[c] = ((const CT*)rw.cr)[(i64)p * rw.stride + k];
+    }
+}
+
+template <int NT, int ITEMS, int G, bool PRED>
+__device__ __forceinline__ void gather_batch(const u64* recs, const char* bytes, const uint2* par, int g, int total,
+                                             u32 start, u32 (&key)[ITEMS], u32 (&dl)[ITEMS], u64& w0)
+{
+    const int tid = threadIdx.x;
+    if (g * NT >= total) return;
+    u64 src[G];
+    u32 cur[G], prv[G];
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+        const int q = (g + j) * NT + tid;
+        src[j] = q < total ? recs[q] : FIRST_OF_ROW;               // beyond the end: entry 0, harmless
+    }
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+        if (PRED) {
+            // predicted rows: the source word holds the row (above the flags) and the index in it
+            const uint2 fs = par[(u32)(src[j] >> PRED_ROW_SHIFT)];  // first value of the row, interval
+            cur[j] = fs.x + (u32)src[j] * fs.y;
+            prv[j] = cur[j] - fs.y;
+        } else {
+            const u32 at = (u32)src[j];
+            const u32 pat = at - (1u - ((u32)(src[j] >> 32) & 1u));    // a row's first entry stands in for its predecessor
+            cur[j] = *(const u32*)(bytes + (at << 3));
+            prv[j] = *(const u32*)(bytes + (pat << 3));
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+        const u32 from = (src[j] & FIRST_OF_ROW) ? start : prv[j];
+        key[g + j] = cur[j] - start;
+        dl[g + j] = cur[j] - from;
+        w0 += (src[j] & FIRST_OF_SEGMENT) ? (u64)(start - from) : 0ull;   // below 2^32 like every relative value
+    }
+}
+
+// Sweep 1 of the window gather (see above): a source word for every entry of the window in
+// its slot.  Returns the number of entries (slots beyond `cap` are not written).  For the rows
+// without an entry in the window the distances from their last value before it to the window
+// start are summed into before_sum and their maximum goes to before_max.  WITH_LAST marks a
+// row's very last entry too (stored rows only: the mark shares its bit with the row number).
+constexpr u64 LAST_OF_ROW = 1ull << 34;
+template <int NT, class CT, bool PRED, bool WITH_LAST>
+__device__ __forceinline__ int zl_place_rows(const Smem& sm, const Rows& rw, u32 start, int cap,
+                                             const u32 (&lo0)[ROWS_PER_THREAD<NT>], const u32 (&hi0)[ROWS_PER_THREAD<NT>],
+                                             u64& before_sum, u32& before_max)
+{
+    static_assert(!(PRED && WITH_LAST), "the last-of-row mark is for stored rows");
+    const int tid = threadIdx.x;
+    u64* recs = sm.recs;
+    const char* bytes = (const char*)rw.inst;
+    int total = 0;
+    constexpr int RPT = ROWS_PER_THREAD<NT>;
+    for (int p0 = 0; p0 < rw.P; p0 += RPT * NT) {
+        u32 lo[RPT], hi[RPT];
+        if (p0 == 0) {                                       // the first round's crossings came with the call
+#pragma unroll
+            for (int c = 0; c < RPT; ++c) {                  // stale scratch (unsorted rows) cannot lead outside the row
+                lo[c] = lo0[c] < (u32)rw.R ? lo0[c] : (u32)rw.R;
+                hi[c] = hi0[c] < (u32)rw.R ? hi0[c] : (u32)rw.R;
+                hi[c] = hi[c] > lo[c] ? hi[c] : lo[c];
+            }
+        } else {
+            load_ranges<NT, CT>(rw, p0, lo, hi);
+        }
+        u32 mine = 0;
+        u32 before[RPT];                                     // rows with nothing in the window: their last entry before it
+#pragma unroll
+        for (int c = 0; c < RPT; ++c) {
+            const int p = p0 + c * NT + tid;
+            mine += hi[c] - lo[c];
+            before[c] = start;
+            if (p < rw.P && lo[c] == hi[c] && lo[c] > 0) {
+                if (PRED) { const uint2 fs = rw.par[p]; before[c] = fs.x + (lo[c] - 1u) * fs.y; }
+                else before[c] = *(const u32*)(bytes + (((u32)p * (u32)rw.R + lo[c] - 1u) << 3));
+            }
+        }
+        u32 round;
+        u32 slot = (u32)total + block_excl_scan<u32, NT>(mine, (u32*)sm.red, round);
+#pragma unroll
+        for (int c = 0; c < RPT; ++c) {
+            const int p = p0 + c * NT + tid;
+            if (p < rw.P) {
+                const u64 row = PRED ? (u64)(u32)p << PRED_ROW_SHIFT : 0ull;
+                u64 src = row | (u64)(PRED ? lo[c] : (u32)p * (u32)rw.R + lo[c]) | FIRST_OF_SEGMENT |
+                          (lo[c] == 0 ? FIRST_OF_ROW : 0ull);
+                for (u32 i = lo[c]; i < hi[c] && slot < (u32)cap; ++i, ++slot) {
+                    recs[slot] = (WITH_LAST && i + 1 == (u32)rw.R) ? (src | LAST_OF_ROW) : src;
+                    src = row | (u64)((u32)src + 1u);
+                }
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < RPT; ++c) {                      // below 2^32 like every relative value
+            const u32 gone = start - before[c];
+            before_sum += (u64)gone;
+            before_max = gone > before_max ? gone : before_max;
+        }
+        total += (int)round;
+    }
+    __syncthreads();
+    return total;
+}
+
+template <int NT, int ITEMS, class CT, bool PRED>
+__device__ __forceinline__ int zl_delta_rows(const Smem& sm, const Rows& rw, u64 a, int cap,
+                                             const u32 (&lo0)[ROWS_PER_THREAD<NT>], const u32 (&hi0)[ROWS_PER_THREAD<NT>],
+                                             u32 (&key)[ITEMS], u32 (&dl)[ITEMS], u64& w0)
+{
+    const u64* recs = sm.recs;
+    const char* bytes = (const char*)rw.inst;
+    const u32 start = (u32)(rw.base + a);                    // low word of the window's first value
+    u32 unused = 0;
+    const int total = zl_place_rows<NT, CT, PRED, false>(sm, rw, start, cap, lo0, hi0, w0, unused);
+    if (total > cap) return total;
+
+    constexpr int G0 = ITEMS < GATHER_BATCH ? ITEMS : GATHER_BATCH;
+    gather_batch<NT, ITEMS, G0, PRED>(recs, bytes, rw.par, 0, total, start, key, dl, w0);
+    static_assert((ITEMS - G0) % GATHER_TAIL == 0 || ITEMS < GATHER_BATCH, "tail batches must tile the items");
+#pragma unroll
+    for (int g = G0; g < ITEMS; g += GATHER_TAIL)
+        gather_batch<NT, ITEMS, GATHER_TAIL, PRED>(recs, bytes, rw.par, g, total, start, key, dl, w0);
+    return total;
+}
+
+}  // namespace
