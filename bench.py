@@ -27,21 +27,48 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 
 
-def algorithmic_bytes(kernel: str, B: int, P: int, R: int, bins: int, windows: int) -> float:
+# HBM bytes per launch of the dominant kernel, from `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE` runs of
+# this program (their summaries, with the commands, are under profiles/), each scaled by what the same counter
+# reads for the plain copy kernel of known size (FETCH_SIZE x 2048 B, WRITE_SIZE x 1024 B per count).  They
+# hold only for the kernel sources they were taken from: `traffic` is null once those have changed.
+COUNTED_SOURCES_SHA256 = "ac62091366b56ef04163710cf959e2cddadad5ad5b1e26fb89b7838acd088962"
+COUNTED_TRAFFIC = {     # (objective, predicted, config) -> (kernel, bytes)
+    ("sum", False, 5): ("zl_window_kernel", 2253500 * 2048 + 1229 * 1024),
+    ("sum", False, 3): ("zl_instance_kernel", 1189600 * 2048 + 5654 * 1024),
+    ("range", False, 5): ("zl_range_fast_kernel", 2236400 * 2048 + 1675 * 1024),
+    ("sum", True, 5): ("zl_window_kernel", 267400 * 2048 + 560 * 1024),
+}
+
+
+def kernel_sources_sha256() -> str:
+    """Hash of the HIP sources the library is built from (file names and contents, in name order)."""
+    import hashlib
+    d = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2001_01347_amd", "csrc")
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            with open(os.path.join(d, name), "rb") as f:
+                h.update(f.read())
+    return h.hexdigest()
+
+
+def algorithmic_bytes(kernel: str, B: int, P: int, R: int, bins: int, windows: int, predicted: bool = False) -> float:
     """Bytes a kernel must move per launch (inputs it has to read once + what it has to write)."""
     n = float(B) * P * R
     cw = 2.0 if R < 65536 else 4.0          # bytes of one crossing index
+    rows = 16.0 * B * P if predicted else 8.0 * n       # predicted rows: 16 bytes per worker stand for R timestamps
     if kernel == "zl_instance_kernel":      # every timestamp once, all three outputs
-        return 8.0 * n + B * (16.0 + 4.0 * P)
+        return rows + B * (16.0 + 4.0 * P)
     if kernel == "zl_window_kernel":        # every timestamp once, two crossing rows per window, one result
-        return 8.0 * n + windows * (2.0 * cw * P + 16.0)
-    groups = (P + 15) // 16                 # rows of partial column sums per instance, when the bins fit LDS
+        return rows + windows * (2.0 * cw * P + 16.0)
+    groups = (P + 63) // 64 if predicted else (P + 15) // 16    # rows of partial column sums per instance (stored rows: when the bins fit LDS)
     if kernel == "zl_partition_kernel":     # every timestamp once, one crossing index per (row, bin), partial column sums
         return 8.0 * n + cw * B * P * (bins + 1) + (4.0 * B * groups * (bins + 1) if bins + 1 <= 8200 else 0.0)
     if kernel == "zl_partition_pred_kernel":    # 16 bytes per worker, one crossing index per (row, bin), partial column sums
         return 16.0 * B * P + cw * B * P * (bins + 1) + 4.0 * B * ((P + 63) // 64) * (bins + 1)
     if kernel == "zl_bincount_kernel":      # the partial column sums once (else the crossing indices), one count per bin
-        return (4.0 * B * groups if bins + 1 <= 8200 else cw * B * P) * (bins + 1) + 4.0 * B * (bins + 1)
+        return (4.0 * B * groups if predicted or bins + 1 <= 8200 else cw * B * P) * (bins + 1) + 4.0 * B * (bins + 1)
     if kernel == "zl_bounds_kernel":        # first and last timestamp of every row (one 64-byte line each)
         return 128.0 * B * P
     if kernel == "zl_plan_kernel":
@@ -166,9 +193,14 @@ def main() -> int:
     windows = B * ((P * R + shape["window_fill"] - 1) // shape["window_fill"]) if shape["multi"] else 0
     per_kernel = {k: v / args.steps for k, v in kernel_ms.items() if v > 0.0}
     dom = max(per_kernel, key=per_kernel.get)
-    dom_bytes = algorithmic_bytes(dom, B, P, R, bins, windows)
+    dom_bytes = algorithmic_bytes(dom, B, P, R, bins, windows, args.predicted)
     achieved = dom_bytes / (per_kernel[dom] * 1e-3) / 1e9
-    total_bytes = sum(algorithmic_bytes(k, B, P, R, bins, windows) for k in per_kernel)
+    counted = COUNTED_TRAFFIC.get((args.objective, bool(args.predicted), args.config))
+    tuned = bool(args.window_cap or args.single_max or args.window_fill)
+    traffic = None
+    if counted and counted[0] == dom and not tuned and kernel_sources_sha256() == COUNTED_SOURCES_SHA256:
+        traffic = float(counted[1])
+    total_bytes = sum(algorithmic_bytes(k, B, P, R, bins, windows, args.predicted) for k in per_kernel)
 
     # CPU oracle on a bounded sample of the same workload (baseline, not a target)
     import oracle
@@ -208,7 +240,7 @@ def main() -> int:
                                f"{n_keys} int64 us timestamps resident in HBM",
                    "B": B, "P": P, "R": R, "objective": args.objective, "predicted": bool(args.predicted)},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "kernel_ms": per_kernel[dom], "algorithmic_bytes": dom_bytes},
         "whole_call": {"algorithmic_bytes": total_bytes,
                        "achieved_GBs": total_bytes / (ms_per_step * 1e-3) / 1e9,
