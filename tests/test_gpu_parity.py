@@ -171,6 +171,23 @@ def test_skewed_and_clustered_values(zl, oracle):
     assert_same(zl, oracle, c, "cluster and outlier")
 
 
+def test_rows_far_from_evenly_spaced(zl, oracle):
+    # the fine bins are laid out as if every row were evenly spaced between its first and last value:
+    # rows that are not only make the bins uneven (oversize windows go to the general search)
+    rng = np.random.default_rng(5)
+    t = workloads.make(4, instances=range(2)).copy()
+    t[:, :, 512:] += 3_000_000_000                          # every worker pauses for 50 minutes half way
+    assert_same(zl, oracle, t, "a long pause")
+    u = workloads.make(4, instances=range(2)).copy()
+    u[:, ::2, 100:] += 500_000_000                          # half of the workers pause early
+    u[:, 1::2, 900:] += 900_000_000                         # the others late
+    assert_same(zl, oracle, u, "staggered pauses")
+    # quadratic rows: iterations slow down steadily
+    i = np.arange(700, dtype=np.int64)
+    q = (rng.integers(0, 1000, size=(2, 300, 1)) + i * 1000 + (i * i) * rng.integers(1, 40, size=(2, 300, 1))).astype(np.int64)
+    assert_same(zl, oracle, q, "slowing workers")
+
+
 def test_status_flags(zl, oracle):
     ts = workloads.make(2, instances=range(8)).copy()
     ts[3, 5, 10] = ts[3, 5, 9] - 1                      # one row of one instance goes backwards
