@@ -190,7 +190,10 @@ def main() -> int:
         zipline.ebsp_zipline_tune(args.window_cap, 8192, args.window_fill)
         shape = zipline.ebsp_zipline_shape_info(B, P, R)
         zipline.ebsp_zipline_tune(args.window_cap, args.single_max, args.window_fill)
-    windows = B * ((P * R + shape["window_fill"] - 1) // shape["window_fill"]) if shape["multi"] else 0
+    fill = shape["window_fill"]
+    if ranged and shape["multi"]:           # this objective leaves room for its short list behind a window's entries
+        fill -= shape["window_cap"] // (2 if P < 128 else 4)
+    windows = B * ((P * R + fill - 1) // fill) if shape["multi"] else 0
     per_kernel = {k: v / args.steps for k, v in kernel_ms.items() if v > 0.0}
     dom = max(per_kernel, key=per_kernel.get)
     dom_bytes = algorithmic_bytes(dom, B, P, R, bins, windows, args.predicted)
@@ -217,6 +220,16 @@ def main() -> int:
     ob, oi, ow, rc, used = cpu_search(sample, "sweep", threads=cores)
     c1 = time.perf_counter()
     cpu_rate = n_cpu * P * R / (c1 - c0)
+    n_one = max(1, n_cpu // cores)                          # the same oracle on one thread, a sixteenth of the sample
+    c2 = time.perf_counter()
+    cpu_search(sample[:n_one], "sweep", threads=1)
+    cpu_rate_one = n_one * P * R / (time.perf_counter() - c2)
+    cpu_model = ""
+    try:
+        with open("/proc/cpuinfo") as f:
+            cpu_model = next((l.split(":", 1)[1].strip() for l in f if l.startswith("model name")), "")
+    except OSError:
+        pass
     same = (np.array_equal(ob, barrier[:n_cpu].cpu().numpy())
             and np.array_equal(ow, wait[:n_cpu].cpu().numpy())
             and np.array_equal(oi, iters[:n_cpu].cpu().numpy()))
@@ -250,7 +263,7 @@ def main() -> int:
         "cpu_baseline": {"value": cpu_rate, "unit": "timestamps/s", "cores": used, "kind": "oracle",
                          "sample": f"sweep oracle on the first {n_cpu} of {B} instances "
                                    f"({n_cpu * P * R} timestamps), {c1 - c0:.2f} s wall",
-                         "matches_gpu": bool(same)},
+                         "matches_gpu": bool(same), "one_thread_value": cpu_rate_one, "cpu_model": cpu_model},
         "copy_probe_GBs": copy_gbs,
         "setup_s": gen_s,
     }
