@@ -92,7 +92,7 @@ __device__ __forceinline__ void gather_batch(const u64* recs, const char* bytes,
 }
 
 // Sweep 1 of the window gather (see above): a source word for every entry of the window in
-// its slot.  Returns the number of entries (slots beyond `cap` are not written).  For the rows
+// its slot.  Returns the number of entries (none is written if they exceed `cap`).  For the rows
 // without an entry in the window the distances from their last value before it to the window
 // start are summed into before_sum and their maximum goes to before_max.  WITH_LAST marks a
 // row's very last entry too (stored rows only: the mark shares its bit with the row number).
@@ -134,17 +134,30 @@ __device__ __forceinline__ int zl_place_rows(const Smem& sm, const Rows& rw, u32
         }
         u32 round;
         u32 slot = (u32)total + block_excl_scan<u32, NT>(mine, (u32*)sm.red, round);
+        total += (int)round;
+        if (total > cap) return total;                       // the same for every thread: nothing is written
+        // The source words of a row's segment: (index, flags) pairs, two per trip.  This loop runs as
+        // long as the longest segment among a wave's rows, so it is kept to a store and two additions.
+        constexpr u32 SEGMENT_BIT = (u32)(FIRST_OF_SEGMENT >> 32), ROW_BIT = (u32)(FIRST_OF_ROW >> 32),
+                      LAST_BIT = (u32)(LAST_OF_ROW >> 32);
 #pragma unroll
         for (int c = 0; c < RPT; ++c) {
             const int p = p0 + c * NT + tid;
-            if (p < rw.P) {
-                const u64 row = PRED ? (u64)(u32)p << PRED_ROW_SHIFT : 0ull;
-                u64 src = row | (u64)(PRED ? lo[c] : (u32)p * (u32)rw.R + lo[c]) | FIRST_OF_SEGMENT |
-                          (lo[c] == 0 ? FIRST_OF_ROW : 0ull);
-                for (u32 i = lo[c]; i < hi[c] && slot < (u32)cap; ++i, ++slot) {
-                    recs[slot] = (WITH_LAST && i + 1 == (u32)rw.R) ? (src | LAST_OF_ROW) : src;
-                    src = row | (u64)((u32)src + 1u);
+            const u32 n = hi[c] - lo[c];
+            if (p < rw.P && n > 0) {
+                const u32 rest = PRED ? (u32)p << (PRED_ROW_SHIFT - 32) : 0u;       // upper word of every entry but the first
+                const u32 first = PRED ? lo[c] : (u32)p * (u32)rw.R + lo[c];
+                uint2* dst = (uint2*)recs + slot;
+                dst[0] = make_uint2(first, rest | SEGMENT_BIT | (lo[c] == 0 ? ROW_BIT : 0u));
+                u32 i = 1;
+                for (; i + 1 < n; i += 2) {
+                    dst[i] = make_uint2(first + i, rest);
+                    dst[i + 1] = make_uint2(first + i + 1, rest);
                 }
+                if (i < n) dst[i] = make_uint2(first + i, rest);
+                if (WITH_LAST && hi[c] == (u32)rw.R)             // the row's very last entry (after the stores above, same thread)
+                    dst[n - 1].y = (n == 1 ? rest | SEGMENT_BIT | (lo[c] == 0 ? ROW_BIT : 0u) : rest) | LAST_BIT;
+                slot += n;
             }
         }
 #pragma unroll
@@ -153,7 +166,6 @@ __device__ __forceinline__ int zl_place_rows(const Smem& sm, const Rows& rw, u32
             before_sum += (u64)gone;
             before_max = gone > before_max ? gone : before_max;
         }
-        total += (int)round;
     }
     __syncthreads();
     return total;
