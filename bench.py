@@ -32,11 +32,11 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 # reads for the plain copy kernel of known size (FETCH_SIZE x 2048 B, WRITE_SIZE x 1024 B per count).  They
 # hold only for the kernel sources they were taken from: `traffic` is null once those have changed.
 COUNTED_SOURCES_SHA256 = "5bef337ff8fd377794641addd4cdcb6350d57a86019d4fea24dd2ba990d5ace2"
-COUNTED_TRAFFIC = {     # (objective, predicted, config) -> (kernel, bytes)
-    ("sum", False, 5): ("zl_window_kernel", 2254300 * 2048 + 1230 * 1024),
-    ("sum", False, 3): ("zl_instance_kernel", 1189500 * 2048 + 5653 * 1024),
-    ("range", False, 5): ("zl_range_fast_kernel", 2233900 * 2048 + 1680 * 1024),
-    ("sum", True, 5): ("zl_window_kernel", 267400 * 2048 + 560 * 1024),
+COUNTED_TRAFFIC = {     # (objective, predicted, config) -> (dominant kernel, its bytes, bytes of all kernels of a call)
+    ("sum", False, 5): ("zl_window_kernel", 2254300 * 2048 + 1230 * 1024, 7580975883),
+    ("sum", False, 3): ("zl_instance_kernel", 1189500 * 2048 + 5653 * 1024, 2453610240),
+    ("range", False, 5): ("zl_range_fast_kernel", 2233900 * 2048 + 1680 * 1024, 7539880000),
+    ("sum", True, 5): ("zl_window_kernel", 267400 * 2048 + 560 * 1024, 1175839691),
 }
 
 
@@ -200,9 +200,9 @@ def main() -> int:
     achieved = dom_bytes / (per_kernel[dom] * 1e-3) / 1e9
     counted = COUNTED_TRAFFIC.get((args.objective, bool(args.predicted), args.config))
     tuned = bool(args.window_cap or args.single_max or args.window_fill)
-    traffic = None
+    traffic = call_traffic = None
     if counted and counted[0] == dom and not tuned and kernel_sources_sha256() == COUNTED_SOURCES_SHA256:
-        traffic = float(counted[1])
+        traffic, call_traffic = float(counted[1]), float(counted[2])
     total_bytes = sum(algorithmic_bytes(k, B, P, R, bins, windows, args.predicted) for k in per_kernel)
 
     # CPU oracle on a bounded sample of the same workload (baseline, not a target)
@@ -259,6 +259,11 @@ def main() -> int:
                        "achieved_GBs": total_bytes / (ms_per_step * 1e-3) / 1e9,
                        "floor_bytes": 8.0 * n_keys,
                        "floor_GBs": 8.0 * n_keys / (ms_per_step * 1e-3) / 1e9,
+                       # HBM bytes the counters saw over all kernels of a call (null under the same conditions as
+                       # roofline.traffic) against the call's duration: the traffic-based fraction of the HBM peak
+                       "counted_bytes": call_traffic,
+                       "counted_GBs": call_traffic / (ms_per_step * 1e-3) / 1e9 if call_traffic else None,
+                       "counted_frac_of_peak": call_traffic / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS if call_traffic else None,
                        "kernel_ms": per_kernel},
         "cpu_baseline": {"value": cpu_rate, "unit": "timestamps/s", "cores": used, "kind": "oracle",
                          "sample": f"sweep oracle on the first {n_cpu} of {B} instances "
