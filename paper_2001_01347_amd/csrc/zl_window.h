@@ -157,35 +157,23 @@ __device__ __forceinline__ void window_pairs(
 #pragma unroll
     for (int i = 0; i <= W; ++i)                             // stale scratch cannot index outside a row of cross
         bins[i] = bins[i] < ii.nb ? bins[i] : ii.nb;
-    // Neighbouring workgroups share the cache lines at the ends of their row segments.  Every other
-    // workgroup takes its windows from the last to the first, so that two neighbours reach a shared
-    // line at the same stage of their work (both early or both late) and the second finds it in L2.
-    static_assert(W == 2, "written for pairs of windows");
-    const bool both = j0 + 1 < jend;
-    const bool backwards = (group & 1u) != 0 && both;
-    const int first = backwards ? 1 : 0;                     // the window taken first; the other one follows
-    u32 lo[RPT], hi[RPT], other[RPT];                        // crossings: below and above the first window, and the pair's far end
+    u32 lo[RPT], hi[RPT], next[RPT];
 #pragma unroll
-    for (int c = 0; c < RPT; ++c) { lo[c] = hi[c] = other[c] = 0; }
+    for (int c = 0; c < RPT; ++c) { lo[c] = hi[c] = next[c] = 0; }
     if (hot) {
-        load_column<NT, CT>(rw, bins[first], lo);
-        load_column<NT, CT>(rw, bins[first + 1], hi);
-        if (both) load_column<NT, CT>(rw, backwards ? bins[0] : bins[2], other);   // in flight while the first window is searched
+        load_column<NT, CT>(rw, bins[0], lo);
+        load_column<NT, CT>(rw, bins[1], hi);
     }
-    rw.k0 = bins[first];
-    rw.k1 = bins[first + 1] > bins[first] ? bins[first + 1] : bins[first];
-    Search::run(sm, rw, vals[first], ii, hot, lo, hi, out + j0 + first);
-    if (both) {
-        u32 lo2[RPT], hi2[RPT];
 #pragma unroll
-        for (int c = 0; c < RPT; ++c) {
-            lo2[c] = backwards ? other[c] : hi[c];
-            hi2[c] = backwards ? lo[c] : other[c];
+    for (int i = 0; i < W; ++i) {
+        if (j0 + i < jend) {
+            if (hot && i + 1 < W && j0 + i + 1 < jend) load_column<NT, CT>(rw, bins[i + 1 < W ? i + 2 : W], next);
+            rw.k0 = bins[i];
+            rw.k1 = bins[i + 1] > bins[i] ? bins[i + 1] : bins[i];
+            Search::run(sm, rw, vals[i], ii, hot, lo, hi, out + j0 + i);
+#pragma unroll
+            for (int c = 0; c < RPT; ++c) { lo[c] = hi[c]; hi[c] = next[c]; }
         }
-        const int second = 1 - first;
-        rw.k0 = bins[second];
-        rw.k1 = bins[second + 1] > bins[second] ? bins[second + 1] : bins[second];
-        Search::run(sm, rw, vals[second], ii, hot, lo2, hi2, out + j0 + second);
     }
 }
 
