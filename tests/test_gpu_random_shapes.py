@@ -1,0 +1,86 @@
+"""Seeded random shapes and value distributions: all three entry points against the oracle, bit for bit."""
+import numpy as np
+import pytest
+
+from paper_2001_01347_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def zl():
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    from paper_2001_01347_amd import zipline
+    zipline.load()
+    return zipline
+
+
+@pytest.fixture(scope="module")
+def oracle():
+    import oracle as o
+    return o
+
+
+def _instances(rng):
+    P = int(rng.choice([1, 2, 3, 5, 8, 16, 33, 64, 100, 256, 300, 512, 1000, 1024, 1500, 2048]))
+    R = int(rng.choice([1, 2, 7, 16, 64, 100, 256, 1000, 1024, 4096, 5000]))
+    n = P * R
+    if n > 2_000_000:
+        return None
+    B = int(rng.integers(1, 4)) if n > 100_000 else int(rng.integers(1, 30))
+    kind = int(rng.integers(0, 5))
+    lo, hi = (1, 1000) if kind < 2 else ((0, 3) if kind == 2 else ((1, 50_000) if kind == 3 else (1, 5)))
+    steps = rng.integers(lo, hi + 1, size=(B, P, R)).astype(np.int64)
+    if kind == 1:                                   # workers of very different speed
+        steps *= rng.integers(1, 2000, size=(B, P, 1))
+    if kind == 4:                                   # long pauses now and then
+        every = max(1, R // 3)
+        steps[:, :, ::every] += rng.integers(0, 10_000_000, size=steps[:, :, ::every].shape)
+    epoch = int(rng.choice([0, 1_700_000_000_000_000]))
+    return np.cumsum(steps, axis=2) + rng.integers(-10 ** 6, 10 ** 6, size=(B, P, 1)) + epoch
+
+
+@pytest.mark.parametrize("seed", [101, 102, 103])
+def test_random_stored_rows_both_objectives(zl, oracle, seed):
+    rng = np.random.default_rng(seed)
+    done = 0
+    while done < 40:
+        ts = _instances(rng)
+        if ts is None:
+            continue
+        done += 1
+        label = f"seed {seed} case {done} shape {ts.shape}"
+        t = torch.from_numpy(ts).cuda()
+        bar, it, w, st = (x.cpu().numpy() for x in zl.ebsp_zipline_batch(t))
+        ob, oi, ow, rc, _ = oracle.zipline(ts, "sweep", threads=16)
+        assert (rc == 0).all() and (st == 0).all(), label
+        assert np.array_equal(bar, ob) and np.array_equal(w, ow) and np.array_equal(it, oi), label
+        rbar, rit, rd, rst = (x.cpu().numpy() for x in zl.ebsp_zipline_range_batch(t))
+        spread = ts.max(axis=(1, 2)) - ts.min(axis=(1, 2))
+        assert set(np.unique(rst)) <= {0, zl.STATUS_UNSUPPORTED}, label
+        assert (rst[spread < 2 ** 32 - 1] == 0).all(), label          # only wider instances may be refused
+        qb, qi, qd, _, _ = oracle.zipline_range(ts, "sweep", threads=16)
+        ok = rst == 0
+        assert np.array_equal(rbar[ok], qb[ok]) and np.array_equal(rd[ok], qd[ok]) and np.array_equal(rit[ok], qi[ok]), label
+
+
+@pytest.mark.parametrize("seed", [201, 202])
+def test_random_predicted_rows(zl, oracle, seed):
+    rng = np.random.default_rng(seed)
+    for case in range(40):
+        P = int(rng.choice([1, 2, 7, 16, 64, 256, 600, 1024, 2048]))
+        R = int(rng.choice([1, 3, 16, 64, 256, 1000, 4096]))
+        if P * R > 2_000_000:
+            continue
+        B = int(rng.integers(1, 4)) if P * R > 100_000 else int(rng.integers(1, 30))
+        iv = rng.integers(0 if case % 7 == 0 else 1, int(rng.choice([5, 1000, 300_000])), size=(B, P)).astype(np.int64)
+        le = rng.integers(-10 ** 6, 10 ** 7, size=(B, P)).astype(np.int64) + int(rng.choice([0, 1_700_000_000_000_000]))
+        label = f"seed {seed} case {case} B={B} P={P} R={R}"
+        bar, it, w, st = (x.cpu().numpy() for x in zl.ebsp_predict_zipline_batch(torch.from_numpy(le).cuda(),
+                                                                                 torch.from_numpy(iv).cuda(), R))
+        ob, oi, ow, rc, _ = oracle.zipline(workloads.predicted_rows(le, iv, R), "sweep", threads=16)
+        assert (rc == 0).all() and (st == 0).all(), label
+        assert np.array_equal(bar, ob) and np.array_equal(w, ow) and np.array_equal(it, oi), label
