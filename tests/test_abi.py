@@ -88,3 +88,44 @@ def test_binding_refuses_cpu_tensors():
     from paper_2001_01347_amd import zipline
     with pytest.raises(ValueError):
         zipline.ebsp_zipline_batch(torch.zeros((1, 2, 3), dtype=torch.int64))
+
+
+def test_plan_of_a_shape_and_the_tuning_knobs(lib):
+    """Host logic of the multi-window plan: shape_info, the knobs' limits and their effect on the sizes."""
+    from paper_2001_01347_amd import zipline
+    info = zipline.ebsp_zipline_shape_info
+    tune = zipline.ebsp_zipline_tune
+    try:
+        tune(0, 0, 0)
+        assert info(4096, 16, 64) == {"multi": 0, "window_cap": 0, "bins": 0, "max_windows": 0, "window_fill": 0}
+        big = info(64, 1024, 4096)              # many workers: 8192-record windows, filled to the brim
+        assert big["multi"] == 1 and big["window_cap"] == 8192 and big["window_fill"] == 8192
+        assert big["bins"] == 1024 * 4096 // 1024            # fine bins of window_cap / 8 keys on average
+        # any two neighbouring windows hold more than window_fill keys: at most 2n/fill + 3 windows, an even number
+        assert big["max_windows"] % 2 == 0 and 2 * 1024 * 4096 // 8192 + 3 <= big["max_windows"] <= 2 * 1024 * 4096 // 8192 + 4
+        few = info(1024, 256, 1024)             # fewer than 512 workers: 4096-record windows
+        assert few["window_cap"] == 4096 and few["window_fill"] == 4096 and few["bins"] == 256 * 1024 // 512
+        # the knobs: limits
+        for bad in [(1000, 0, 0), (0, -1, 0), (0, 16385, 0), (0, 0, 100), (0, 0, -5)]:
+            with pytest.raises(zipline.ZipLineError):
+                tune(*bad)
+        # a smaller fill means more windows and more scratch; a fill above the capacity is capped
+        base = zipline.ebsp_zipline_workspace_bytes(64, 1024, 4096)
+        tune(0, 0, 2048)
+        half = info(64, 1024, 4096)
+        assert half["window_fill"] == 2048 and half["max_windows"] > big["max_windows"]
+        assert zipline.ebsp_zipline_workspace_bytes(64, 1024, 4096) > base
+        tune(0, 0, 1 << 20)
+        assert info(64, 1024, 4096)["window_fill"] == 8192
+        # the capacity and the single-workgroup limit
+        tune(16384, 0, 0)
+        assert info(64, 1024, 4096)["window_cap"] == 16384
+        tune(0, 4096, 0)
+        assert info(16384, 64, 256)["multi"] == 1 and zipline.ebsp_zipline_workspace_bytes(16384, 64, 256) > 0
+        # the range objective leaves room for its short list and cuts instances above 8192 entries
+        tune(0, 0, 0)
+        assert zipline.ebsp_zipline_range_workspace_bytes(16384, 64, 256) > 0
+        assert zipline.ebsp_zipline_range_workspace_bytes(4096, 16, 64) == 0
+        assert zipline.ebsp_zipline_range_workspace_bytes(64, 1024, 4096) > base     # more, smaller windows
+    finally:
+        tune(0, 0, 0)
