@@ -101,7 +101,7 @@ bool make_plan(i64 B, int P, int R, Plan& pl, int single_limit = SINGLE_MAX, boo
     pl.multi = n > single_max;
     if (!pl.multi) return true;
     // the per-window cost has a term proportional to P: larger windows for more rows
-    pl.cap = g_tune.window_cap > 0 ? g_tune.window_cap : (P >= 512 ? 8192 : 4096);
+    pl.cap = g_tune.window_cap > 0 ? g_tune.window_cap : (P >= 1536 ? 16384 : (P >= 512 ? 8192 : 4096));
     const int fine_shift = (pl.cap == 16384 ? 14 : (pl.cap == 8192 ? 13 : 12)) - 3;       // fine bins of cap/8 keys on average
     pl.fill = g_tune.window_fill > 0 && g_tune.window_fill < pl.cap ? g_tune.window_fill : pl.cap;
     if (list_room) {
