@@ -97,6 +97,10 @@ def main() -> int:
     ap.add_argument("--predicted", action="store_true",
                     help="rows predicted inside the kernels from (last_end, interval) per worker "
                          "(ebsp_predict_zipline_batch): nothing but 16 bytes per worker is read from HBM")
+    ap.add_argument("--supersteps", type=int, default=0,
+                    help="S > 0: a step is one ebsp_simulate_supersteps call, S supersteps of predict -> search -> "
+                         "resume at the barrier on the device (implies --predicted)")
+    ap.add_argument("--sync-cost", type=int, default=2000, help="with --supersteps: time from a barrier to the restart (us)")
     ap.add_argument("--cpu-instances", type=int, default=-1,
                     help="instances in the CPU-oracle sample (default: sized for roughly 10-30 s of CPU work)")
     ap.add_argument("--copy-probe", type=int, default=3,
@@ -123,8 +127,18 @@ def main() -> int:
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
+    S = max(0, args.supersteps)
+    if S:
+        args.predicted = True
     t0 = time.time()
-    if args.predicted:
+    if S:
+        if args.objective != "sum":
+            print("bench.py: --supersteps goes with the summed-wait objective only", file=sys.stderr)
+            return 2
+        le_host, iv_host = workloads.make_supersteps(args.config, S)
+        le_dev, iv_dev = torch.from_numpy(le_host).to(dev), torch.from_numpy(iv_host).to(dev)
+        host = ts = None
+    elif args.predicted:
         if args.objective != "sum":
             print("bench.py: --predicted goes with the summed-wait objective only", file=sys.stderr)
             return 2
@@ -136,16 +150,20 @@ def main() -> int:
         ts = torch.from_numpy(host).to(dev)
     gen_s = time.time() - t0
 
-    barrier = torch.empty(B, dtype=torch.int64, device=dev)
-    iters = torch.empty((B, P), dtype=torch.int32, device=dev)
-    wait = torch.empty(B, dtype=torch.int64, device=dev)
-    status = torch.empty(B, dtype=torch.int32, device=dev)
+    lead = (S,) if S else ()
+    barrier = torch.empty(lead + (B,), dtype=torch.int64, device=dev)
+    iters = torch.empty(lead + (B, P), dtype=torch.int32, device=dev)
+    wait = torch.empty(lead + (B,), dtype=torch.int64, device=dev)
+    status = torch.empty(lead + (B,), dtype=torch.int32, device=dev)
     ranged = args.objective == "range"
-    ws_bytes = (zipline.ebsp_zipline_range_workspace_bytes if ranged else zipline.ebsp_zipline_workspace_bytes)(B, P, R)
+    ws_bytes = (zipline.ebsp_simulate_workspace_bytes if S else zipline.ebsp_zipline_range_workspace_bytes if ranged
+                else zipline.ebsp_zipline_workspace_bytes)(B, P, R)
     workspace = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
 
     def step():
-        if args.predicted:
+        if S:
+            zipline.ebsp_simulate_supersteps(le_dev, iv_dev, R, args.sync_cost, barrier, iters, wait, status, workspace)
+        elif args.predicted:
             zipline.ebsp_predict_zipline_batch(le_dev, iv_dev, R, barrier, iters, wait, status, workspace)
         elif ranged:
             zipline.ebsp_zipline_range_batch(ts, barrier, iters, wait, status, workspace)
@@ -157,7 +175,9 @@ def main() -> int:
     torch.cuda.synchronize()
 
     # timed region: K steps, per-kernel HIP events recorded inside the library on the launch stream
-    zipline.ebsp_zipline_profile_begin(args.steps)
+    searches = max(1, S)                    # searches (launches of every kernel of the search) per step
+    n_keys *= searches                      # timestamps a step looks through
+    zipline.ebsp_zipline_profile_begin(args.steps * searches)
     torch.cuda.synchronize()
     w0 = time.perf_counter()
     for _ in range(args.steps):
@@ -165,7 +185,7 @@ def main() -> int:
     torch.cuda.synchronize()
     w1 = time.perf_counter()
     kernel_ms, calls = zipline.ebsp_zipline_profile_end()
-    assert calls == args.steps
+    assert calls == args.steps * searches
     ms_per_step = (w1 - w0) * 1e3 / args.steps
     assert int(status.max().item()) == 0, "the search flagged a data error on synthetic input"
 
@@ -194,16 +214,16 @@ def main() -> int:
     if ranged and shape["multi"]:           # this objective leaves room for its short list behind a window's entries
         fill -= shape["window_cap"] // (2 if P < 128 else 4)
     windows = B * ((P * R + fill - 1) // fill) if shape["multi"] else 0
-    per_kernel = {k: v / args.steps for k, v in kernel_ms.items() if v > 0.0}
+    per_kernel = {k: v / calls for k, v in kernel_ms.items() if v > 0.0}      # per launch
     dom = max(per_kernel, key=per_kernel.get)
     dom_bytes = algorithmic_bytes(dom, B, P, R, bins, windows, args.predicted)
     achieved = dom_bytes / (per_kernel[dom] * 1e-3) / 1e9
     counted = COUNTED_TRAFFIC.get((args.objective, bool(args.predicted), args.config))
     tuned = bool(args.window_cap or args.single_max or args.window_fill)
     traffic = call_traffic = None
-    if counted and counted[0] == dom and not tuned and kernel_sources_sha256() == COUNTED_SOURCES_SHA256:
+    if counted and counted[0] == dom and not tuned and not S and kernel_sources_sha256() == COUNTED_SOURCES_SHA256:
         traffic, call_traffic = float(counted[1]), float(counted[2])
-    total_bytes = sum(algorithmic_bytes(k, B, P, R, bins, windows, args.predicted) for k in per_kernel)
+    total_bytes = searches * sum(algorithmic_bytes(k, B, P, R, bins, windows, args.predicted) for k in per_kernel)
 
     # CPU oracle on a bounded sample of the same workload (baseline, not a target)
     import oracle
@@ -212,30 +232,41 @@ def main() -> int:
     if args.cpu_instances > 0:
         n_cpu = min(B, args.cpu_instances)
     else:
-        n_cpu = max(1, min(B, int(1.7e7 * cores // (P * R)) or 1))
-    sample = host[:n_cpu] if host is not None else workloads.predicted_rows(le_host[:n_cpu], iv_host[:n_cpu], R)
-    cpu_search = oracle.zipline_range if ranged else oracle.zipline
-    cpu_search(sample[:1], "sweep", threads=1)              # load the library, touch the pages
-    c0 = time.perf_counter()
-    ob, oi, ow, rc, used = cpu_search(sample, "sweep", threads=cores)
-    c1 = time.perf_counter()
-    cpu_rate = n_cpu * P * R / (c1 - c0)
+        n_cpu = max(1, min(B, int(1.7e7 * cores // (P * R * searches)) or 1))
     n_one = max(1, n_cpu // cores)                          # the same oracle on one thread, a sixteenth of the sample
-    c2 = time.perf_counter()
-    cpu_search(sample[:n_one], "sweep", threads=1)
-    cpu_rate_one = n_one * P * R / (time.perf_counter() - c2)
+    if S:
+        oracle.simulate(le_host[:1], iv_host[:1, :1], R, args.sync_cost, threads=1)     # load the library
+        c0 = time.perf_counter()
+        ob, oi, ow, rc, used = oracle.simulate(le_host[:n_cpu], iv_host[:, :n_cpu], R, args.sync_cost, threads=cores)
+        c1 = time.perf_counter()
+        c2 = time.perf_counter()
+        oracle.simulate(le_host[:n_one], iv_host[:, :n_one], R, args.sync_cost, threads=1)
+        one_s = time.perf_counter() - c2
+    else:
+        sample = host[:n_cpu] if host is not None else oracle.predicted_rows(le_host[:n_cpu], iv_host[:n_cpu], R)
+        cpu_search = oracle.zipline_range if ranged else oracle.zipline
+        cpu_search(sample[:1], "sweep", threads=1)          # load the library, touch the pages
+        c0 = time.perf_counter()
+        ob, oi, ow, rc, used = cpu_search(sample, "sweep", threads=cores)
+        c1 = time.perf_counter()
+        c2 = time.perf_counter()
+        cpu_search(sample[:n_one], "sweep", threads=1)
+        one_s = time.perf_counter() - c2
+    cpu_rate = n_cpu * P * R * searches / (c1 - c0)
+    cpu_rate_one = n_one * P * R * searches / one_s
     cpu_model = ""
     try:
         with open("/proc/cpuinfo") as f:
             cpu_model = next((l.split(":", 1)[1].strip() for l in f if l.startswith("model name")), "")
     except OSError:
         pass
-    same = (np.array_equal(ob, barrier[:n_cpu].cpu().numpy())
-            and np.array_equal(ow, wait[:n_cpu].cpu().numpy())
-            and np.array_equal(oi, iters[:n_cpu].cpu().numpy()))
+    same = (np.array_equal(ob, barrier[..., :n_cpu].cpu().numpy())
+            and np.array_equal(ow, wait[..., :n_cpu].cpu().numpy())
+            and np.array_equal(oi, (iters[:, :n_cpu] if S else iters[:n_cpu]).cpu().numpy()))
 
     out = {
-        "metric": ("zipline_predicted_timestamps_per_sec" if args.predicted else
+        "metric": ("elasticbsp_simulated_timestamps_per_sec" if S else
+                   "zipline_predicted_timestamps_per_sec" if args.predicted else
                    "zipline_timestamps_per_sec" if not ranged else "zipline_range_timestamps_per_sec"),
         "value": n_keys / (ms_per_step * 1e-3),
         "unit": "timestamps/s",
@@ -250,8 +281,10 @@ def main() -> int:
         "dtype": "int64",
         "data": "synthetic",
         "config": {"workload": f"config {cfg.k}: B={B} instances, P={P} workers, R={R} lookahead, "
-                               f"{n_keys} int64 us timestamps resident in HBM",
-                   "B": B, "P": P, "R": R, "objective": args.objective, "predicted": bool(args.predicted)},
+                               f"{n_keys} int64 us timestamps " +
+                               (f"predicted on the device over {S} supersteps" if S else "resident in HBM"),
+                   "B": B, "P": P, "R": R, "objective": args.objective, "predicted": bool(args.predicted),
+                   "supersteps": S},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "kernel_ms": per_kernel[dom], "algorithmic_bytes": dom_bytes},
@@ -267,7 +300,7 @@ def main() -> int:
                        "kernel_ms": per_kernel},
         "cpu_baseline": {"value": cpu_rate, "unit": "timestamps/s", "cores": used, "kind": "oracle",
                          "sample": f"sweep oracle on the first {n_cpu} of {B} instances "
-                                   f"({n_cpu * P * R} timestamps), {c1 - c0:.2f} s wall",
+                                   f"({n_cpu * P * R * searches} timestamps), {c1 - c0:.2f} s wall",
                          "matches_gpu": bool(same), "one_thread_value": cpu_rate_one, "cpu_model": cpu_model},
         "copy_probe_GBs": copy_gbs,
         "setup_s": gen_s,

@@ -104,6 +104,51 @@ int ebsp_predict_zipline_batch(const int64_t* last_end, const int64_t* interval,
                                void* stream);
 
 /*
+ * A run of S supersteps (Fig. 1: a superstep is the time between two barriers;
+ * Section III: the server decides barrier after barrier, each time from the
+ * workers' most recent iteration times).  Superstep s predicts every worker's
+ * next R end timestamps from the time it starts the superstep at and from its
+ * iteration time in that superstep, searches them as
+ * ebsp_predict_zipline_batch does, and lets all workers of the instance start
+ * the next superstep together once the barrier and the synchronisation are
+ * over:
+ *
+ *     start[0][b][p]  = last_end0[b][p]
+ *     (barrier, iters, wait)[s][b] = search over start[s][b][p] + (i+1) * interval[s][b][p], i < R
+ *     start[s+1][b][p] = barrier[s][b] + sync_cost           for every p
+ *
+ * The paper's training runs are not reproduced; this is the part of its
+ * comparison that needs only iteration times: R = 1 is BSP with one iteration
+ * per superstep (barrier = the slowest worker's end), larger R is ElasticBSP.
+ * That workers run exactly as predicted within a superstep, that they all
+ * resume at the same time and that a synchronisation takes a fixed time are
+ * this build's readings (the paper states none of the three).
+ *
+ *   last_end0  in  [B][P] int64, device: each worker's start time of the run.
+ *   interval   in  [S][B][P] int64, device: iteration time of worker p of
+ *                  instance b during superstep s, >= 0.
+ *   sync_cost      time from a barrier to the start of the next superstep, >= 0.
+ *   barrier    out [S][B] int64; iters out [S][B][P] int32; wait out [S][B]
+ *              int64; status out [S][B] int32 or NULL: per superstep as for
+ *              ebsp_predict_zipline_batch.  An instance that raises a status
+ *              bit in a superstep keeps its start times for the next one (when
+ *              status is NULL this cannot be seen and its later results are
+ *              undefined).
+ *   workspace      at least ebsp_simulate_workspace_bytes(B, P, R) bytes (never
+ *                  0 for a valid shape: it holds the start times), 256-byte
+ *                  aligned.
+ * The supersteps are enqueued one after the other on `stream`; nothing is
+ * copied to the host in between.  S == 0 or B == 0 is a valid no-op.
+ * Precondition: no start + R * interval overflows int64.  Return codes as above
+ * (EBSP_ERR_SHAPE also for S < 0 or sync_cost < 0).
+ */
+size_t ebsp_simulate_workspace_bytes(int64_t B, int32_t P, int32_t R);
+int ebsp_simulate_supersteps(const int64_t* last_end0, const int64_t* interval, int64_t sync_cost,
+                             int64_t S, int64_t B, int32_t P, int32_t R,
+                             int64_t* barrier, int32_t* iters, int64_t* wait, int32_t* status,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * The same search under the paper's formal objective (Section III "The
  * Problem": d_Z = max(Z) - min(Z), the waiting time of the fastest worker;
  * Section IV, Algorithm 2, which sweeps the merged timestamps with a set Z of

@@ -2,9 +2,14 @@
 
 Thin ctypes wrapper over ``zipline_oracle.c`` (plain host C, no GPU code).
 Nothing in the product package imports this module; only the tests, the smoke
-check and the benchmark's CPU-baseline leg do.  The arithmetic lives entirely
-in the C file, whose header states the definition it follows (Section III
-"The Problem", Section IV "Naive search" and Algorithm 2 of the paper).
+check and the benchmark's CPU-baseline leg do.  The arithmetic of the search
+lives entirely in the C files, whose headers state the definition they follow
+(Section III "The Problem", Section IV "Naive search" and Algorithm 2 of the
+paper).  Two small steps around the search are written out here in numpy:
+the linear prediction of a worker's next R end timestamps (:func:`predicted_rows`)
+and the run of supersteps that resumes every worker at the barrier
+(:func:`simulate`); the paper describes both only in words (Section I, Section
+III, Fig. 1), so both are readings, stated in their docstrings.
 """
 from __future__ import annotations
 
@@ -70,6 +75,54 @@ def zipline(ts, method: str = "sweep", threads: int = 0):
     not non-decreasing (that instance's outputs are left at zero).
     """
     return _run(ts, "zl_oracle_batch", METHODS[method], threads)
+
+
+def predicted_rows(last_end, interval, R: int) -> np.ndarray:
+    """The prediction phase (Section I and Section III: a worker's coming iterations are taken to last
+    as long as its most recent one): worker p's i-th coming iteration ends at
+
+        t[..., p, i] = last_end[..., p] + (i + 1) * interval[..., p],   i = 0 .. R-1.
+
+    The paper gives no formula; this linear one is the reading.  int64 in, int64 out, one more axis.
+    """
+    le = np.asarray(last_end, dtype=np.int64)
+    iv = np.asarray(interval, dtype=np.int64)
+    out = np.empty(le.shape + (int(R),), dtype=np.int64)
+    for i in range(int(R)):
+        out[..., i] = le + (i + 1) * iv
+    return out
+
+
+def simulate(last_end0, interval, R: int, sync_cost: int = 0, method: str = "sweep", threads: int = 0):
+    """A run of S supersteps (Fig. 1: a superstep is the time between two barriers; Section III: the
+    server decides one barrier after the other from the workers' most recent iteration times).
+
+    ``last_end0[B, P]``: the time every worker starts the run at; ``interval[S, B, P]``: worker p's
+    iteration time during superstep s.  Superstep s predicts R end timestamps per worker from its
+    start time and interval, runs the search over them, and every worker of the instance starts
+    superstep s + 1 at ``barrier + sync_cost``.  Readings (the paper states none of them): workers
+    run exactly as predicted up to the barrier, all of them resume together, and a synchronisation
+    takes a fixed time.  With R = 1 this is BSP with one iteration per superstep.  An instance
+    whose rows the search rejects (rc != 0) keeps its start times.
+
+    Returns ``(barrier[S, B], iters[S, B, P], wait[S, B], rc[S, B], threads_used)``.
+    """
+    start = np.array(last_end0, dtype=np.int64)
+    iv = np.asarray(interval, dtype=np.int64)
+    if start.ndim != 2 or iv.ndim != 3 or iv.shape[1:] != start.shape:
+        raise ValueError("last_end0 must have shape [B, P] and interval [S, B, P]")
+    S, B, P = iv.shape
+    barrier = np.zeros((S, B), dtype=np.int64)
+    iters = np.zeros((S, B, P), dtype=np.int32)
+    wait = np.zeros((S, B), dtype=np.int64)
+    rc = np.zeros((S, B), dtype=np.int32)
+    used = 0
+    for s in range(S):
+        barrier[s], iters[s], wait[s], rc[s], used = zipline(predicted_rows(start, iv[s], R), method, threads)
+        for b in range(B):
+            if rc[s, b] == 0:
+                start[b, :] = barrier[s, b] + int(sync_cost)
+    return barrier, iters, wait, rc, used
 
 
 def _run(ts, entry: str, method: int, threads: int):

@@ -59,12 +59,12 @@ int fail(int code, const char* msg)
 }
 
 enum KernelId { K_INSTANCE = 0, K_INSTANCE_GENERAL, K_BOUNDS, K_PARTITION, K_BINCOUNT, K_PLAN, K_WINDOW,
-                K_WINDOW_GENERAL, K_FINISH, K_COPY, K_RANGE_INSTANCE, K_RANGE_WINDOW, K_PARTITION_PRED, K_RANGE_FAST, K_COUNT };
+                K_WINDOW_GENERAL, K_FINISH, K_COPY, K_RANGE_INSTANCE, K_RANGE_WINDOW, K_PARTITION_PRED, K_RANGE_FAST, K_ADVANCE, K_COUNT };
 const char* const kKernelNames[K_COUNT] = {
     "zl_instance_kernel", "zl_instance_general_kernel", "zl_bounds_kernel", "zl_partition_kernel",
     "zl_bincount_kernel", "zl_plan_kernel", "zl_window_kernel", "zl_window_general_kernel",
     "zl_finish_kernel", "zl_copy_kernel", "zl_range_instance_kernel", "zl_range_window_kernel",
-    "zl_partition_pred_kernel", "zl_range_fast_kernel"};
+    "zl_partition_pred_kernel", "zl_range_fast_kernel", "zl_advance_kernel"};
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -394,6 +394,46 @@ int ebsp_predict_zipline_batch(const int64_t* last_end, const int64_t* interval,
                              (i64*)wait, status, workspace, workspace_bytes, (hipStream_t)stream);
     if (g_prof.on && rc == EBSP_OK && B > 0 && g_prof.calls < g_prof.max_calls) ++g_prof.calls;
     return rc;
+}
+
+size_t ebsp_simulate_workspace_bytes(int64_t B, int32_t P, int32_t R)
+{
+    Plan pl;
+    if (!make_plan(B, P, R, pl)) return 0;
+    return align_up(pl.multi ? pl.bytes : 0, 256) + align_up((size_t)B * P * sizeof(i64), 256);   // + the workers' current start times
+}
+
+int ebsp_simulate_supersteps(const int64_t* last_end0, const int64_t* interval, int64_t sync_cost,
+                             int64_t S, int64_t B, int32_t P, int32_t R, int64_t* barrier, int32_t* iters, int64_t* wait, int32_t* status,
+                             void* workspace, size_t workspace_bytes, void* stream)
+{
+    Plan pl;
+    if (S < 0 || sync_cost < 0 || !make_plan(B, P, R, pl))
+        return fail(EBSP_ERR_SHAPE, "invalid shape: need S >= 0, sync_cost >= 0, B >= 0, P >= 1, R >= 1, P*R < 2^31");
+    if (S == 0 || B == 0) return EBSP_OK;
+    if (!last_end0 || !interval) return fail(EBSP_ERR_NULL, "last_end0 and interval must not be NULL");
+    if (!barrier || !iters || !wait) return fail(EBSP_ERR_NULL, "barrier, iters and wait must not be NULL");
+    if (!workspace) return fail(EBSP_ERR_NULL, "the simulation needs a workspace");
+    if (((uintptr_t)workspace & 255u) != 0) return fail(EBSP_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    const size_t search_bytes = align_up(pl.multi ? pl.bytes : 0, 256);
+    if (workspace_bytes < search_bytes + (size_t)B * P * sizeof(i64))
+        return fail(EBSP_ERR_WORKSPACE, "workspace smaller than ebsp_simulate_workspace_bytes()");
+    if ((B * (i64)P + 255) / 256 > 0x7fffffffll) return fail(EBSP_ERR_SHAPE, "batch too large for one call");
+    hipStream_t st = (hipStream_t)stream;
+    i64* start = (i64*)((char*)workspace + search_bytes);
+    const i64 per = B * (i64)P;
+    for (i64 s = 0; s < S; ++s) {
+        const i64* from = s == 0 ? (const i64*)last_end0 : start;
+        int* flags = status ? status + s * B : nullptr;
+        const int rc = run_batch(nullptr, from, (const i64*)interval + s * per, B, P, R, (i64*)barrier + s * B, iters + s * per,
+                                 (i64*)wait + s * B, flags, workspace, search_bytes, st);
+        if (rc != EBSP_OK) return rc;
+        if (s + 1 < S)       // the workers' start times of the next superstep (after the last one barrier[S-1] says it all)
+            LAUNCH(K_ADVANCE, zl_advance_kernel, dim3((unsigned)((per + 255) / 256)), dim3(256),
+                   (const i64*)barrier + s * B, (const int*)flags, from, start, (i64)sync_cost, B, P);
+        if (g_prof.on && g_prof.calls < g_prof.max_calls) ++g_prof.calls;
+    }
+    return EBSP_OK;
 }
 
 size_t ebsp_zipline_range_workspace_bytes(int64_t B, int32_t P, int32_t R)

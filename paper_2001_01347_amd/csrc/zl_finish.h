@@ -44,6 +44,20 @@ __global__ __launch_bounds__(NT) void zl_finish_kernel(
                                             iv ? iv + b * (i64)P : nullptr, p, R, bar);
 }
 
+// Superstep simulation: after a barrier (and the synchronisation, which takes sync_cost) every
+// worker of an instance starts its next iteration together.  start[b][p] = barrier[b] + sync_cost;
+// an instance whose search raised a status bit has no barrier: its workers keep `from`, the times
+// they started the superstep at.
+__global__ __launch_bounds__(256) void zl_advance_kernel(const i64* __restrict__ barrier, const int* __restrict__ status,
+                                                         const i64* from, i64* start,
+                                                         i64 sync_cost, i64 B, int P)
+{
+    const i64 at = (i64)blockIdx.x * 256 + threadIdx.x;
+    if (at >= B * (i64)P) return;
+    const i64 b = at / P;
+    start[at] = (!status || status[b] == 0) ? barrier[b] + sync_cost : from[at];
+}
+
 // Plain streaming copy of n 16-byte words: the yardstick that HBM byte counters
 // and achieved bandwidth of the other kernels are read against.
 __global__ __launch_bounds__(256) void zl_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, i64 n)

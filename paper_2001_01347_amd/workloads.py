@@ -151,10 +151,24 @@ def make_predicted(k: int, instances: Optional[Iterable[int]] = None, shift: int
     return le, iv
 
 
-def predicted_rows(last_end: np.ndarray, interval: np.ndarray, R: int) -> np.ndarray:
-    """The rows the fused prediction stands for: t[b, p, i] = last_end[b, p] + (i + 1) * interval[b, p]."""
-    i = np.arange(1, R + 1, dtype=np.int64)
-    return last_end[..., None] + interval[..., None] * i
+def make_supersteps(k: int, S: int, instances: Optional[Iterable[int]] = None, jitter: float = 0.02,
+                    shift: int = 0):
+    """Inputs of a run of ``S`` supersteps for configuration ``k``: ``(last_end0[n, P], interval[S, n, P])`` int64.
+
+    The workers start at the configuration's random offsets and have its mean iteration times (as
+    :func:`make_predicted`); in superstep s a worker's iteration time is its mean times
+    ``1 + jitter * N(0, 1)`` (at least 1), drawn per (superstep, worker) from the instance's own
+    seeded stream: iteration times of one worker stay similar from one superstep to the next.
+    """
+    cfg = CONFIGS[k]
+    ids = list(range(cfg.B)) if instances is None else [int(b) for b in instances]
+    le, mean = make_predicted(k, ids, shift)
+    iv = np.empty((int(S), len(ids), cfg.P), dtype=np.int64)
+    for j, b in enumerate(ids):
+        rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([SEED_BASE + 200 + cfg.k, b])))
+        f = 1.0 + float(jitter) * rng.standard_normal((int(S), cfg.P))
+        iv[:, j, :] = np.maximum(np.rint(mean[j][None, :] * f).astype(np.int64), 1)
+    return le, iv
 
 
 def random_small(rng: np.random.Generator, P: int, R: int, lo: int = 1, hi: int = 20,

@@ -21,7 +21,8 @@ EBSP_OK = 0
 STATUS_OK, STATUS_UNSORTED, STATUS_OVERFLOW, STATUS_UNSUPPORTED = 0, 1, 2, 4
 
 EXPORTS = ("ebsp_zipline_workspace_bytes", "ebsp_zipline_batch", "ebsp_zipline_range_workspace_bytes",
-           "ebsp_zipline_range_batch", "ebsp_predict_zipline_batch", "ebsp_zipline_tune", "ebsp_zipline_shape_info", "ebsp_zipline_profile_begin",
+           "ebsp_zipline_range_batch", "ebsp_predict_zipline_batch", "ebsp_simulate_workspace_bytes",
+           "ebsp_simulate_supersteps", "ebsp_zipline_tune", "ebsp_zipline_shape_info", "ebsp_zipline_profile_begin",
            "ebsp_zipline_profile_end", "ebsp_zipline_copy_probe", "ebsp_zipline_kernel_count",
            "ebsp_zipline_kernel_name", "ebsp_last_error")
 
@@ -52,6 +53,10 @@ def load() -> ctypes.CDLL:
         lib.ebsp_zipline_range_batch.argtypes = common
         lib.ebsp_predict_zipline_batch.restype = ctypes.c_int
         lib.ebsp_predict_zipline_batch.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+        lib.ebsp_simulate_workspace_bytes.restype = sz
+        lib.ebsp_simulate_workspace_bytes.argtypes = [i64, i32, i32]
+        lib.ebsp_simulate_supersteps.restype = ctypes.c_int
+        lib.ebsp_simulate_supersteps.argtypes = [vp, vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
         lib.ebsp_zipline_shape_info.restype = ctypes.c_int
         lib.ebsp_zipline_shape_info.argtypes = [i64, i32, i32, ctypes.POINTER(ctypes.c_int64)]
         lib.ebsp_zipline_tune.restype = ctypes.c_int
@@ -204,6 +209,51 @@ def ebsp_predict_zipline_batch(last_end: torch.Tensor, interval: torch.Tensor, R
                                                torch.cuda.current_stream(dev).cuda_stream)
     if rc != EBSP_OK:
         raise ZipLineError(f"ebsp_predict_zipline_batch failed ({rc}): {ebsp_last_error()}")
+    return barrier, iters, wait, status
+
+
+def ebsp_simulate_workspace_bytes(B: int, P: int, R: int) -> int:
+    return int(load().ebsp_simulate_workspace_bytes(B, P, R))
+
+
+def ebsp_simulate_supersteps(last_end0: torch.Tensor, interval: torch.Tensor, R: int, sync_cost: int = 0,
+                             barrier: Optional[torch.Tensor] = None, iters: Optional[torch.Tensor] = None,
+                             wait: Optional[torch.Tensor] = None, status: Optional[torch.Tensor] = None,
+                             workspace: Optional[torch.Tensor] = None):
+    """S supersteps of predict -> search -> resume at the barrier; see the header.
+
+    ``last_end0`` is a contiguous int64 CUDA tensor [B, P], ``interval`` one of shape [S, B, P].
+    Returns ``(barrier[S, B], iters[S, B, P], wait[S, B], status[S, B])`` device tensors.  Does not synchronise.
+    """
+    for t in (last_end0, interval):
+        if t.dtype != torch.int64 or not t.is_cuda or not t.is_contiguous():
+            raise ValueError("last_end0 and interval must be contiguous int64 CUDA tensors")
+    if last_end0.dim() != 2 or interval.dim() != 3 or interval.shape[1:] != last_end0.shape \
+            or interval.device != last_end0.device:
+        raise ValueError("last_end0 must have shape [B, P] and interval [S, B, P], on one device")
+    S, B, P = (int(x) for x in interval.shape)
+    R = int(R)
+    dev = last_end0.device
+    if barrier is None:
+        barrier = torch.empty((S, B), dtype=torch.int64, device=dev)
+    if iters is None:
+        iters = torch.empty((S, B, P), dtype=torch.int32, device=dev)
+    if wait is None:
+        wait = torch.empty((S, B), dtype=torch.int64, device=dev)
+    if status is None:
+        status = torch.empty((S, B), dtype=torch.int32, device=dev)
+    need = ebsp_simulate_workspace_bytes(B, P, R)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    with torch.cuda.device(dev):
+        rc = load().ebsp_simulate_supersteps(last_end0.data_ptr(), interval.data_ptr(), int(sync_cost), S, B, P, R,
+                                             barrier.data_ptr(), iters.data_ptr(), wait.data_ptr(),
+                                             status.data_ptr(), ws_ptr, ws_len,
+                                             torch.cuda.current_stream(dev).cuda_stream)
+    if rc != EBSP_OK:
+        raise ZipLineError(f"ebsp_simulate_supersteps failed ({rc}): {ebsp_last_error()}")
     return barrier, iters, wait, status
 
 

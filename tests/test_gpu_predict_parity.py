@@ -31,7 +31,7 @@ def gpu_run(zl, le, iv, R):
 
 def assert_same(zl, oracle, le, iv, R, label=""):
     bar, it, w, st = gpu_run(zl, le, iv, R)
-    ob, oi, ow, rc, _ = oracle.zipline(workloads.predicted_rows(le, iv, R), "sweep", threads=16)
+    ob, oi, ow, rc, _ = oracle.zipline(oracle.predicted_rows(le, iv, R), "sweep", threads=16)
     assert (rc == 0).all()
     assert (st == 0).all(), f"{label}: status {np.unique(st)}"
     assert np.array_equal(w, ow), f"{label}: wait differs at {np.nonzero(w != ow)[0][:5]}"
@@ -82,7 +82,7 @@ def test_same_as_the_stored_path(zl):
         le, iv = workloads.make_predicted(k, instances=ids)
         R = workloads.CONFIGS[k].R
         bar, it, w, st = gpu_run(zl, le, iv, R)
-        ts = torch.from_numpy(workloads.predicted_rows(le, iv, R)).cuda()
+        ts = torch.from_numpy(oracle.predicted_rows(le, iv, R)).cuda()
         sb, si, sw, ss = zl.ebsp_zipline_batch(ts)
         torch.cuda.synchronize()
         assert np.array_equal(bar, sb.cpu().numpy()) and np.array_equal(w, sw.cpu().numpy())
@@ -114,7 +114,7 @@ def test_negative_interval_is_flagged(zl, oracle):
         bar, it, w, st = gpu_run(zl, le, iv, R)
         assert st[2] & zl.STATUS_UNSORTED and (np.delete(st, 2) == 0).all()
         keep = np.delete(np.arange(6), 2)
-        ob, oi, ow, rc, _ = oracle.zipline(workloads.predicted_rows(le[keep], iv[keep], R), "sweep", threads=8)
+        ob, oi, ow, rc, _ = oracle.zipline(oracle.predicted_rows(le[keep], iv[keep], R), "sweep", threads=8)
         assert np.array_equal(bar[keep], ob) and np.array_equal(w[keep], ow) and np.array_equal(it[keep], oi)
 
 
@@ -126,7 +126,7 @@ def test_full_size_configs(zl, oracle, k, sample):
     assert (st == 0).all()
     rng = np.random.default_rng(200 + k)
     ids = np.sort(rng.choice(cfg.B, size=sample, replace=False))
-    ob, oi, ow, rc, _ = oracle.zipline(workloads.predicted_rows(le[ids], iv[ids], cfg.R), "sweep", threads=16)
+    ob, oi, ow, rc, _ = oracle.zipline(oracle.predicted_rows(le[ids], iv[ids], cfg.R), "sweep", threads=16)
     assert (rc == 0).all()
     assert np.array_equal(bar[ids], ob) and np.array_equal(w[ids], ow) and np.array_equal(it[ids], oi)
     # properties that hold for every instance: each worker stops at its last predicted timestamp <= barrier,

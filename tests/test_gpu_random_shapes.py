@@ -81,6 +81,6 @@ def test_random_predicted_rows(zl, oracle, seed):
         label = f"seed {seed} case {case} B={B} P={P} R={R}"
         bar, it, w, st = (x.cpu().numpy() for x in zl.ebsp_predict_zipline_batch(torch.from_numpy(le).cuda(),
                                                                                  torch.from_numpy(iv).cuda(), R))
-        ob, oi, ow, rc, _ = oracle.zipline(workloads.predicted_rows(le, iv, R), "sweep", threads=16)
+        ob, oi, ow, rc, _ = oracle.zipline(oracle.predicted_rows(le, iv, R), "sweep", threads=16)
         assert (rc == 0).all() and (st == 0).all(), label
         assert np.array_equal(bar, ob) and np.array_equal(w, ow) and np.array_equal(it, oi), label

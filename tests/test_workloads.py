@@ -45,16 +45,27 @@ def test_key_ranges_fit_the_documented_bit_budget():
         assert (spread < 2 ** 32).all()
 
 
-def test_predicted_inputs_are_reproducible_and_rows_follow_the_rule():
+def test_predicted_inputs_are_reproducible():
     le, iv = workloads.make_predicted(3, instances=[5, 9])
     le2, iv2 = workloads.make_predicted(3, instances=[9])
     assert le.shape == iv.shape == (2, 64) and le.dtype == iv.dtype == np.int64
     assert np.array_equal(le[1], le2[0]) and np.array_equal(iv[1], iv2[0])
     assert (iv >= 1).all() and (le >= 0).all()
-    rows = workloads.predicted_rows(le, iv, 7)
-    assert rows.shape == (2, 64, 7)
-    assert np.array_equal(rows[..., 0], le + iv) and np.array_equal(np.diff(rows, axis=-1), np.broadcast_to(iv[..., None], (2, 64, 6)))
     shifted, _ = workloads.make_predicted(3, instances=[5], shift=10**15)
     assert np.array_equal(shifted[0], le[0] + 10**15)
     le4, iv4 = workloads.make_predicted(4, instances=[0])
     assert (le4 % 1000 == 0).all() and (iv4 % 1000 == 0).all()      # config 4 rounds to 1 ms
+
+
+def test_superstep_inputs_are_reproducible_and_stay_near_the_workers_means():
+    le, iv = workloads.make_supersteps(3, 6, instances=[5, 9])
+    le2, iv2 = workloads.make_supersteps(3, 6, instances=[9])
+    base_le, mean = workloads.make_predicted(3, instances=[5, 9])
+    assert le.shape == (2, 64) and iv.shape == (6, 2, 64) and iv.dtype == np.int64
+    assert np.array_equal(le, base_le)
+    assert np.array_equal(le[1], le2[0]) and np.array_equal(iv[:, 1], iv2[:, 0])
+    assert (iv >= 1).all()
+    assert (np.abs(iv - mean[None]) <= 0.12 * mean[None] + 1).all()          # 2 % jitter: six sigma
+    assert not np.array_equal(iv[0], iv[1])                                   # a fresh draw per superstep
+    _, flat = workloads.make_supersteps(3, 3, instances=[5], jitter=0.0)
+    assert np.array_equal(flat, np.broadcast_to(mean[None, :1], (3, 1, 64)))
