@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 # this program (their summaries, with the commands, are under profiles/), each scaled by what the same counter
 # reads for the plain copy kernel of known size (FETCH_SIZE x 2048 B, WRITE_SIZE x 1024 B per count).  They
 # hold only for the kernel sources they were taken from: `traffic` is null once those have changed.
-COUNTED_SOURCES_SHA256 = "5dce7b647329d6614e633fc561194ef8a04528e8d0fb1c1d457dd2dd4e36df32"
+COUNTED_SOURCES_SHA256 = "16ae33c291dc9a826277e5e1a8ad1a81489a7ea16b91a9133cdacf49bcaea6de"
 COUNTED_TRAFFIC = {     # (objective, predicted, config) -> (dominant kernel, its bytes, bytes of all kernels of a call)
     ("sum", False, 5): ("zl_window_kernel", 2254300 * 2048 + 1230 * 1024, 7580975883),
     ("sum", False, 3): ("zl_instance_kernel", 1189500 * 2048 + 5653 * 1024, 2453610240),
