@@ -76,7 +76,7 @@ def test_all_configurations(zl, oracle):
         assert_same(zl, oracle, le, iv, workloads.CONFIGS[k].R, f"config {k}")
 
 
-def test_same_as_the_stored_path(zl):
+def test_same_as_the_stored_path(zl, oracle):
     # the stored-rows entry point on the rows written out must give the very same outputs
     for k, ids in ((2, range(128)), (4, range(4))):
         le, iv = workloads.make_predicted(k, instances=ids)
