@@ -46,7 +46,8 @@ extern "C" {
 #define EBSP_STATUS_UNSORTED   1   /* some row is not non-decreasing (Section III: rows  */
                                    /* are iteration sequences)                            */
 #define EBSP_STATUS_OVERFLOW   2   /* P * (max t - min t) does not fit in int64          */
-#define EBSP_STATUS_UNSUPPORTED 4  /* the instance needs a code path this build lacks    */
+#define EBSP_STATUS_UNSUPPORTED 4  /* reserved: no entry point raises it any more (every */
+                                   /* instance has a code path)                           */
 
 /*
  * Bytes of device scratch that ebsp_zipline_batch needs for this shape.
@@ -161,10 +162,10 @@ int ebsp_simulate_supersteps(const int64_t* last_end0, const int64_t* interval, 
  *
  * Arguments, layouts, ownership and return codes as for ebsp_zipline_batch,
  * with dmin[B] (int64, device, >= 0) in place of wait[B] and a workspace of at
- * least ebsp_zipline_range_workspace_bytes() bytes.  This build handles
- * instances whose value spread (max t - min t) is below 2^32 - 1 and whose
- * windows fit one workgroup; any other instance gets EBSP_STATUS_UNSUPPORTED in
- * status[b] and unspecified outputs (other instances are unaffected).
+ * least ebsp_zipline_range_workspace_bytes() bytes.  No instance is refused
+ * for its values: only EBSP_STATUS_UNSORTED can be raised (nothing is summed
+ * over the workers, so there is no overflow precondition beyond max t - min t
+ * fitting int64).
  */
 size_t ebsp_zipline_range_workspace_bytes(int64_t B, int32_t P, int32_t R);
 int ebsp_zipline_range_batch(const int64_t* ts, int64_t B, int32_t P, int32_t R,

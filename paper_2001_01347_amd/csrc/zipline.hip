@@ -163,7 +163,7 @@ hipEvent_t* prof_slot(int kid, int which)
 // The front of the multi-window path, shared by the objectives: per-instance facts and
 // fine-bin map, crossing indices, exact bin counts, windows.
 int plan_windows(const Plan& pl, const i64* ts, const i64* le, const i64* iv, i64 B, int P, int R,
-                 char* wsp, int* status, hipStream_t st)
+                 char* wsp, int* status, bool summed, hipStream_t st)
 {
     const bool pred = ts == nullptr;
     InstInfo* info = (InstInfo*)(wsp + pl.off_info);
@@ -178,7 +178,7 @@ int plan_windows(const Plan& pl, const i64* ts, const i64* le, const i64* iv, i6
     const i64 kblocks = (pl.stride + 255) / 256;
     const i64 widest = pl.part_stored > pl.part_pred ? pl.part_stored : pl.part_pred;
     if (kblocks * B > 0x7fffffffll || widest * B > 0x7fffffffll) return fail(EBSP_ERR_SHAPE, "batch too large for one call");
-    LAUNCH(K_BOUNDS, (zl_bounds_kernel<256>), dim3((unsigned)B), dim3(256), ts, le, iv, P, R, pl.bins, info, segtab, rowpar, status);
+    LAUNCH(K_BOUNDS, (zl_bounds_kernel<256>), dim3((unsigned)B), dim3(256), ts, le, iv, P, R, pl.bins, info, segtab, rowpar, status, summed);
     int part_rows;                                    // rows of partial column sums per instance (0: none, count from cross)
     if (pred) {
         part_rows = pl.part_pred;
@@ -272,7 +272,7 @@ int run_batch(const i64* ts, const i64* le, const i64* iv, i64 B, int P, int R,
     Partial* partial = (Partial*)(wsp + pl.off_partial);
     uint2* rowpar = pred ? (uint2*)(wsp + pl.off_rowpar) : nullptr;
 
-    if (int rc = plan_windows(pl, ts, le, iv, B, P, R, wsp, status, st)) return rc;
+    if (int rc = plan_windows(pl, ts, le, iv, B, P, R, wsp, status, true, st)) return rc;
     const i64 pblocks = (P + 255) / 256;
     if (pblocks * B > 0x7fffffffll) return fail(EBSP_ERR_SHAPE, "batch too large for one call");
     const u32 groups = (u32)(pl.max_win / WINDOWS_PER_BLOCK);
@@ -333,7 +333,7 @@ int run_range_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters
     WinVal* winval = (WinVal*)(wsp + pl.off_winval);
     Partial* partial = (Partial*)(wsp + pl.off_partial);
 
-    if (int rc = plan_windows(pl, ts, nullptr, nullptr, B, P, R, wsp, status, st)) return rc;
+    if (int rc = plan_windows(pl, ts, nullptr, nullptr, B, P, R, wsp, status, false, st)) return rc;
     const i64 pblocks = (P + 255) / 256;
     if (pblocks * B > 0x7fffffffll) return fail(EBSP_ERR_SHAPE, "batch too large for one call");
     const u32 groups = (u32)(pl.max_win / WINDOWS_PER_BLOCK);

@@ -11,7 +11,8 @@ namespace {
 template <int NT>
 __global__ __launch_bounds__(NT) void zl_bounds_kernel(
     const i64* __restrict__ ts, const i64* __restrict__ le, const i64* __restrict__ iv, int P, int R, int bins,
-    InstInfo* __restrict__ info, SegEntry* __restrict__ segtab, uint2* __restrict__ rowpar, int* __restrict__ status)
+    InstInfo* __restrict__ info, SegEntry* __restrict__ segtab, uint2* __restrict__ rowpar, int* __restrict__ status,
+    bool summed)
 {
     static_assert(NT >= SEGS, "one thread per segment");
     __shared__ i64 red[NT / WAVE];
@@ -52,7 +53,7 @@ __global__ __launch_bounds__(NT) void zl_bounds_kernel(
     ii.nwin = 0;
     ii.flags = backwards ? (u32)EBSP_STATUS_UNSORTED : 0u;
     ii.pad_ = 0;
-    if (ii.range > (u64)INT64_MAX / (u64)P) ii.flags |= EBSP_STATUS_OVERFLOW;
+    if (summed && ii.range > (u64)INT64_MAX / (u64)P) ii.flags |= EBSP_STATUS_OVERFLOW;    // P waits are summed
     if (backwards) ii.range = 0;                      // nothing downstream may rely on such rows
     const int bl = bit_length(ii.range);
     ii.wshift = bl > 32 ? (u32)(bl - 32) : 0u;

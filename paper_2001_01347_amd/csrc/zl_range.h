@@ -25,8 +25,15 @@ namespace {
 // Entries equal to key_k at later positions are treated as not yet arrived; that can
 // only raise d at position k, and the last position of the run of equal keys sees
 // them all, so the minimum over all positions is the minimum over the timestamps.
-// Needs a value spread below 2^32 - 1 (keys and the NEVER mark share 32 bits).
+// An interval is at most 2^32 - 2 wide (keys and the NEVER mark share 32 bits); a `next`
+// beyond the interval is as good as NEVER inside it.  `gone` reaches back before the
+// interval: it fits 32 bits when the instance's value spread does (below 2^32 - 1);
+// otherwise (FAR) it is kept in 64 bits, its upper half in a third plane.
 constexpr u32 NEVER = 0xffffffffu;
+constexpr u64 RANGE_PIECE_MAX = 0xfffffffeull;          // widest interval searched in one go
+
+template <bool FAR> struct Gone { using type = u32; static constexpr u32 never = NEVER; };
+template <> struct Gone<true> { using type = u64; static constexpr u64 never = U64_MAX; };
 
 template <class T, int NT, class Op>
 __device__ __forceinline__ T block_excl_scan_op(T v, T* red, Op op)      // `red` holds NT/64 T's
@@ -50,10 +57,12 @@ __device__ __forceinline__ T block_excl_scan_op(T v, T* red, Op op)      // `red
 // Gather for the range objective; returns the number of entries (nothing useful is
 // stored if it exceeds `cap`).  absent = the largest `gone` over the workers without
 // an entry in the interval (this thread's share).
-template <int NT>
+template <int NT, bool FAR>
 __device__ __forceinline__ int zl_range_gather(const Smem& sm, const Rows& rw, u64 a, u64 el, bool lx, bool rx,
-                                               int cap, u32& absent, int& bad)
+                                               int cap, typename Gone<FAR>::type& absent, int& bad)
 {
+    using G = typename Gone<FAR>::type;
+    const u64 width = el - a;
     const int tid = threadIdx.x;
     u32* rowoff = sm.cnt;
     u32* rowlo = sm.cnt + NT;
@@ -64,7 +73,7 @@ __device__ __forceinline__ int zl_range_gather(const Smem& sm, const Rows& rw, u
         if (p < rw.P) {
             sub_range(rw, p, a, el, lx, rx, lo, hi);
             if (lo == hi) {
-                const u32 gone = lo > 0 ? (u32)(a - rw.rel(p, lo - 1)) : NEVER;
+                const G gone = lo > 0 ? (G)(a - rw.rel(p, lo - 1)) : Gone<FAR>::never;
                 absent = gone > absent ? gone : absent;
             }
         }
@@ -86,23 +95,26 @@ __device__ __forceinline__ int zl_range_gather(const Smem& sm, const Rows& rw, u
             const i64* src = rw.inst + (size_t)(p0 + l) * rw.R + i;
             const i64 cur = src[0];
             const u64 rel = (u64)cur - rw.base;
-            u32 next = NEVER, gone = 0;
+            u32 next = NEVER;
+            G gone = 0;
             if (i + 1 < (u32)rw.R) {
                 const i64 nxt = src[1];
                 bad |= (nxt < cur);
-                next = (u32)((u64)nxt - rw.base - a);
+                const u64 nrel = (u64)nxt - rw.base - a;
+                next = FAR && nrel > width ? NEVER : (u32)nrel;
             }
             if (i == rowlo[l]) {                  // the row's first entry inside the interval
-                gone = NEVER;
+                gone = Gone<FAR>::never;
                 if (i > 0) {
                     const i64 prv = src[-1];
                     bad |= (cur < prv);
-                    gone = (u32)(a - ((u64)prv - rw.base));
+                    gone = (G)(a - ((u64)prv - rw.base));
                 }
             }
             const int slot = phys(total + e);
             sm.recs[slot] = (u64)(u32)(rel - a) | ((u64)next << 32);
-            sm.dhi[slot] = gone;
+            sm.dhi[slot] = (u32)gone;
+            if (FAR) sm.ext[slot] = (u32)((u64)gone >> 32);
         }
         total += (int)chunk;
         __syncthreads();
@@ -112,13 +124,14 @@ __device__ __forceinline__ int zl_range_gather(const Smem& sm, const Rows& rw, u
 
 // The search over the sorted entries [0, total); thread t owns positions
 // [t*items, (t+1)*items).  Returns the first minimum (d, key); d == U64_MAX: none.
-template <int NT>
+template <int NT, bool FAR>
 __device__ __forceinline__ void zl_range_scan_argmin(const Smem& sm, int items, int total, u64 a, u64 thr,
-                                                     u32 absent_all, u64& best_d, u32& best_key)
+                                                     typename Gone<FAR>::type absent_all, u64& best_d, u32& best_key)
 {
+    using GT = typename Gone<FAR>::type;
     u64* recs = sm.recs;
-    u32* gone = sm.dhi;
-    u32* mirror = sm.cnt;                        // NT words
+    auto gone = [&](int slot) -> GT { return FAR ? (GT)(((u64)sm.ext[slot] << 32) | sm.dhi[slot]) : (GT)sm.dhi[slot]; };
+    GT* mirror = (GT*)sm.cnt;                    // NT of them (the counter plane holds 2*NT words at least)
     const int tid = threadIdx.x;
     const int q0 = tid * items < total ? tid * items : total;
     const int qe = q0 + items < total ? q0 + items : total;
@@ -133,23 +146,23 @@ __device__ __forceinline__ void zl_range_scan_argmin(const Smem& sm, int items, 
         recs[phys(q)] = (u64)(u32)r | ((u64)run << 32);
     }
     // G: largest `gone` over the positions behind the thread's own (threads in mirrored order)
-    u32 far = 0;
-    for (int q = q0; q < qe; ++q) { const u32 g = gone[phys(q)]; far = g > far ? g : far; }
+    GT far = 0;
+    for (int q = q0; q < qe; ++q) { const GT g = gone(phys(q)); far = g > far ? g : far; }
     mirror[NT - 1 - tid] = far;
     __syncthreads();
-    const u32 mv = mirror[tid];
+    const GT mv = mirror[tid];
     __syncthreads();
-    const u32 behind_m = block_excl_scan_op<u32, NT>(mv, (u32*)sm.red, OpMax());   // for thread NT-1-tid
+    const GT behind_m = block_excl_scan_op<GT, NT>(mv, (GT*)sm.red, OpMax());   // for thread NT-1-tid
     mirror[NT - 1 - tid] = behind_m;
     __syncthreads();                              // also: every M is in place
-    u32 G = mirror[tid];
+    GT G = mirror[tid];
     G = absent_all > G ? absent_all : G;
 
     u64 bd = U64_MAX;
     u32 bq = 0xffffffffu, bk = 0;
     for (int q = qe - 1; q >= q0; --q) {          // right to left: G covers the positions behind q
         const u32 key = (u32)recs[phys(q)];
-        if (a + key >= thr && G != NEVER) {
+        if (a + key >= thr && G != Gone<FAR>::never) {
             u64 d;
             bool ok = true;
             if (G > 0) {
@@ -165,7 +178,7 @@ __device__ __forceinline__ void zl_range_scan_argmin(const Smem& sm, int items, 
             }
             if (ok && (d < bd || (d == bd && (u32)q < bq))) { bd = d; bq = (u32)q; bk = key; }
         }
-        const u32 g = gone[phys(q)];
+        const GT g = gone(phys(q));
         G = g > G ? g : G;
     }
     // block arg-min over (d, position): smaller d, then earlier position
@@ -188,25 +201,27 @@ __device__ __forceinline__ void zl_range_scan_argmin(const Smem& sm, int items, 
     best_key = (u32)pk;
 }
 
-// One interval [A, Elast] (less than 2^32 - 1 wide): gather, sort, search.  An interval
-// with more than CAP_WIDE entries is walked in pieces that do fit, cut by bisection on
-// the value (every piece is searched on its own: what a piece needs from outside it
+// One interval [A, Elast]: gather, sort, search.  An interval wider than RANGE_PIECE_MAX
+// (FAR only) or with more than CAP_WIDE entries is walked in pieces that do fit, the latter
+// cut by bisection on the value (every piece is searched on its own: what a piece needs from outside it
 // are the neighbouring entries of its rows, which the gather reads); a single value
 // that alone occurs more than CAP_WIDE times is one candidate and is evaluated
 // directly from the rows.  (bd, bb) is updated with the first minimum found.
-template <int NT, int ITEMS>
+template <int NT, int ITEMS, bool FAR>
 __device__ __forceinline__ void zl_range_window(const Smem& sm, const Rows& rw, u64 thr, u64 A, u64 Elast,
                                                 u64& bd, u64& bb, int& bad)
 {
     using C = WinCfg<NT, ITEMS>;
+    using GT = typename Gone<FAR>::type;
     constexpr int CAPW = C::CAP_WIDE;
     u64 a = A;
     bool lx = true;
     for (;;) {
         u64 el = Elast;
         bool rx = true;
-        u32 absent = 0;
-        int total = zl_range_gather<NT>(sm, rw, a, el, lx, rx, CAPW, absent, bad);
+        if (FAR && el - a > RANGE_PIECE_MAX) { el = a + RANGE_PIECE_MAX; rx = false; }
+        GT absent = 0;
+        int total = zl_range_gather<NT, FAR>(sm, rw, a, el, lx, rx, CAPW, absent, bad);
         bool single = false;
         if (total > CAPW) {
             if (count_interval<NT>(sm, rw, a, a, lx) > (u32)CAPW) {
@@ -220,7 +235,7 @@ __device__ __forceinline__ void zl_range_window(const Smem& sm, const Rows& rw, 
                 }
                 el = l;
                 absent = 0;
-                total = zl_range_gather<NT>(sm, rw, a, el, lx, false, CAPW, absent, bad);
+                total = zl_range_gather<NT, FAR>(sm, rw, a, el, lx, false, CAPW, absent, bad);
             }
             rx = false;
         }
@@ -237,15 +252,15 @@ __device__ __forceinline__ void zl_range_window(const Smem& sm, const Rows& rw, 
             missing = __syncthreads_or(missing);
             if (!missing && a >= thr && (d < bd || (d == bd && a < bb))) { bd = d; bb = a; }
         } else {
-            const u32 absent_all = block_reduce<u32, NT>(absent, (u32*)sm.red, OpMax());   // also orders the record writes
+            const GT absent_all = block_reduce<GT, NT>(absent, (GT*)sm.red, OpMax());   // also orders the record writes
             if (total > 0) {
                 const int items = (total + NT - 1) / NT;
                 fill_sentinels<NT>(sm.recs, total, items);
                 __syncthreads();
-                zl_sort<NT, ITEMS, true>(sm, items, bit_length(el - a));
+                zl_sort<NT, ITEMS, true, FAR>(sm, items, bit_length(el - a));
                 u64 d;
                 u32 key;
-                zl_range_scan_argmin<NT>(sm, items, total, a, thr, absent_all, d, key);
+                zl_range_scan_argmin<NT, FAR>(sm, items, total, a, thr, absent_all, d, key);
                 if (d != U64_MAX && (d < bd || (d == bd && a + key < bb))) { bd = d; bb = a + key; }
             }
         }
@@ -564,14 +579,11 @@ __global__ __launch_bounds__(NT) void zl_range_instance_kernel(
     u32 flags = 0;
     u64 best_d = U64_MAX, best_rel = 0;
     int bad = 0;
-    if (range >= 0xffffffffull) {
-        flags |= EBSP_STATUS_UNSUPPORTED;
-    } else {
-        Rows rw;
-        rw.inst = inst; rw.le = nullptr; rw.iv = nullptr; rw.P = P; rw.R = R; rw.base = (u64)base;
-        rw.cr = nullptr; rw.narrow = false; rw.stride = 0; rw.k0 = rw.k1 = 0;
-        zl_range_window<NT, ITEMS>(sm, rw, thr, 0ull, range, best_d, best_rel, bad);
-    }
+    Rows rw;
+    rw.inst = inst; rw.le = nullptr; rw.iv = nullptr; rw.P = P; rw.R = R; rw.base = (u64)base;
+    rw.cr = nullptr; rw.narrow = false; rw.stride = 0; rw.k0 = rw.k1 = 0;
+    if (range > RANGE_PIECE_MAX) zl_range_window<NT, ITEMS, true>(sm, rw, thr, 0ull, range, best_d, best_rel, bad);
+    else zl_range_window<NT, ITEMS, false>(sm, rw, thr, 0ull, range, best_d, best_rel, bad);
     if (__syncthreads_or(bad)) flags |= EBSP_STATUS_UNSORTED;
     if (best_d == U64_MAX) { best_d = 0; best_rel = 0; }
     const i64 bar = (i64)((u64)base + best_rel);
@@ -622,14 +634,14 @@ __global__ __launch_bounds__(NT) void zl_range_window_kernel(
             r.wait = U64_MAX;
             r.brel = 0;
             int bad = 0;
-            bool fits = true;
-            if (ii.range >= 0xffffffffull) fits = false;
-            else if (w.valid) zl_range_window<NT, ITEMS>(sm, w.rw, ii.thr, w.A, w.Elast, r.wait, r.brel, bad);
+            if (w.valid) {
+                if (ii.range > RANGE_PIECE_MAX) zl_range_window<NT, ITEMS, true>(sm, w.rw, ii.thr, w.A, w.Elast, r.wait, r.brel, bad);
+                else zl_range_window<NT, ITEMS, false>(sm, w.rw, ii.thr, w.A, w.Elast, r.wait, r.brel, bad);
+            }
             bad = __syncthreads_or(bad);
             if (threadIdx.x == 0) {
                 partial[pick] = r;
-                if (status && (bad || !fits))
-                    atomicOr(status + b, (bad ? (int)EBSP_STATUS_UNSORTED : 0) | (fits ? 0 : (int)EBSP_STATUS_UNSUPPORTED));
+                if (status && bad) atomicOr(status + b, (int)EBSP_STATUS_UNSORTED);
             }
         }
     }

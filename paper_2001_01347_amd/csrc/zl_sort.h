@@ -10,7 +10,9 @@ namespace {
 // A record is (key: low 32 bits, delta: high 32 bits).  Keys are relative to
 // the window start and windows are at most 2^32 wide.  Deltas fit 32 bits when
 // the instance's range does; otherwise (WIDE) the upper half of each delta
-// lives in a second plane and a window holds half as many records.  Record q
+// lives in a second plane and a window holds half as many records (a third
+// plane of the same size carries one more payload word for the searches that
+// need it).  Record q
 // lives at slot q + (q >> 4): one pad slot per 16 records keeps both the
 // wave-striped access of the sort and the blocked access of the scan free of
 // bank conflicts.
@@ -24,7 +26,7 @@ struct WinCfg {
     static constexpr int CAP_WIDE = CAP / 2 > 0 ? CAP / 2 : 1;
     static constexpr int ITEMS_WIDE = ITEMS / 2 > 0 ? ITEMS / 2 : 1;
     static constexpr int RECS_WIDE = NT * ITEMS_WIDE + NT * ITEMS_WIDE / 16 + 2;
-    static constexpr size_t REC_BYTES = (size_t)RECS * 8 > (size_t)RECS_WIDE * 12 ? (size_t)RECS * 8 : (size_t)RECS_WIDE * 12;
+    static constexpr size_t REC_BYTES = (size_t)RECS * 8 > (size_t)RECS_WIDE * 16 ? (size_t)RECS * 8 : (size_t)RECS_WIDE * 16;
     static constexpr int CNT_WORDS = (NW * RADIX_MAX > 2 * NT) ? NW * RADIX_MAX : 2 * NT;
     static constexpr int RED_WORDS = 3 * NW + 8;          // u64 scratch for scans and reductions
     static constexpr size_t BYTES = (REC_BYTES + 15) / 16 * 16 + (size_t)RED_WORDS * 8 + (size_t)CNT_WORDS * 4;
@@ -33,6 +35,7 @@ struct WinCfg {
 struct Smem {       // carved from one static LDS array
     u64* recs;      // record plane
     u32* dhi;       // upper halves of the deltas (WIDE only)
+    u32* ext;       // one more payload word per record (WIDE with EXTRA only)
     u64* red;       // reduction scratch
     u32* cnt;       // per-wave digit counters; row offsets while loading
 };
@@ -44,6 +47,7 @@ __device__ __forceinline__ Smem carve(unsigned char* smem)
     Smem s;
     s.recs = (u64*)smem;
     s.dhi = (u32*)(s.recs + C::RECS_WIDE);
+    s.ext = s.dhi + C::RECS_WIDE;
     s.red = (u64*)(smem + (C::REC_BYTES + 15) / 16 * 16);
     s.cnt = (u32*)(s.red + C::RED_WORDS);
     return s;
@@ -71,9 +75,10 @@ __device__ __forceinline__ u64 match_digit(u32 d, int dbits)
 // round j lane l holds position w*64*items + j*64 + l.  Ranks within a wave
 // come from ballots, per-wave digit counts live in cnt[w][digit]; a digit-major
 // scan of those counts gives every (wave, digit) its first output position.
-template <int NT, int ITEMS, bool WIDE>
+template <int NT, int ITEMS, bool WIDE, bool EXTRA = false>
 __device__ __forceinline__ void zl_sort(const Smem& sm, int items, int kbits)
 {
+    static_assert(WIDE || !EXTRA, "the third plane goes with the WIDE layout");
     using C = WinCfg<NT, ITEMS>;
     constexpr int IT = WIDE ? C::ITEMS_WIDE : ITEMS;
     u64* recs = sm.recs;
@@ -90,7 +95,7 @@ __device__ __forceinline__ void zl_sort(const Smem& sm, int items, int kbits)
     for (int pass = 0; pass < npass; ++pass) {
         const int sh = pass * dbits;
         for (u32 d = lane; d < radix; d += WAVE) mycnt[d] = 0;
-        u32 key[IT], dl[IT], dh[WIDE ? IT : 1], rank[IT];
+        u32 key[IT], dl[IT], dh[WIDE ? IT : 1], ex[EXTRA ? IT : 1], rank[IT];
 #pragma unroll
         for (int j = 0; j < IT; ++j) {
             if (j < items) {
@@ -98,6 +103,7 @@ __device__ __forceinline__ void zl_sort(const Smem& sm, int items, int kbits)
                 key[j] = (u32)r;
                 dl[j] = (u32)(r >> 32);
                 if (WIDE) dh[j] = sm.dhi[phys(wbase + j * WAVE)];
+                if (EXTRA) ex[j] = sm.ext[phys(wbase + j * WAVE)];
                 const u32 d = (key[j] >> sh) & dmask;
                 const u64 peers = match_digit(d, dbits);
                 const u32 below = __popcll(peers & lt);
@@ -131,6 +137,7 @@ __device__ __forceinline__ void zl_sort(const Smem& sm, int items, int kbits)
                 const int pos = (int)(mycnt[d] + rank[j]);
                 recs[phys(pos)] = (u64)key[j] | ((u64)dl[j] << 32);
                 if (WIDE) sm.dhi[phys(pos)] = dh[j];
+                if (EXTRA) sm.ext[phys(pos)] = ex[j];
             }
         }
         __syncthreads();

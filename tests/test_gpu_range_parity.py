@@ -2,8 +2,7 @@
 d_Z = max(Z) - min(Z) (``ebsp_zipline_range_batch``), through the C ABI (needs an MI355X).
 
 Bar: bit-exact on barrier (int64), dmin (int64) and iters (int32); the result is unique
-(first minimum).  Instances the build does not handle (value spread of 2^32 - 1 or more)
-must be flagged, not answered wrongly.
+(first minimum), also for instances whose value spread does not fit 32 bits.
 """
 import json
 import os
@@ -120,11 +119,11 @@ def test_status_flags(zl, oracle):
     assert st[3] & zl.STATUS_UNSORTED and (np.delete(st, 3) == 0).all()
     ob, oi, od, rc, _ = oracle.zipline_range(np.delete(ts, 3, axis=0), "sweep", threads=8)
     assert np.array_equal(np.delete(bar, 3), ob) and np.array_equal(np.delete(dm, 3), od)
-    # spread of 2^32 or more: not handled by this build, and said so
+    # a spread of 2^32 or more is no reason for a flag
     wide = workloads.make(2, instances=range(4)).copy()
     wide[2] *= 1 << 20
     bar, it, dm, st = gpu_run(zl, wide)
-    assert st[2] & zl.STATUS_UNSUPPORTED and (np.delete(st, 2) == 0).all()
+    assert (st == 0).all()
     ms = workloads.make(3, instances=range(4)).copy()
     ms[1, 9, 100] = ms[1, 9, 99] - 5
     bar, it, dm, st = gpu_run(zl, ms)
@@ -169,3 +168,31 @@ def test_full_size_configs(zl, oracle, k, sample):
     assert np.array_equal(bar[sel].cpu().numpy(), ob)
     assert np.array_equal(dm[sel].cpu().numpy(), od)
     assert np.array_equal(it[sel].cpu().numpy(), oi)
+
+
+def test_value_spread_beyond_32_bits(zl, oracle):
+    # keys, successors and the distance back to a worker's previous value no longer fit 32 bits:
+    # one workgroup per instance (config 2), windows (configs 3 to 5), a mix of both kinds in one batch
+    assert_same(zl, oracle, workloads.make(2, instances=range(64)) * 1000 + EPOCH, "config 2 in ns")
+    mixed = workloads.make(2, instances=range(16)).copy()
+    mixed[::2] *= 1 << 20
+    assert_same(zl, oracle, mixed, "config 2, every other instance x 2^20")
+    assert_same(zl, oracle, workloads.make(3, instances=range(6)) * 1000, "config 3 in ns")
+    assert_same(zl, oracle, workloads.make(4, instances=range(2)) * 1000, "config 4 in ns")
+    assert_same(zl, oracle, workloads.make(5, instances=[0]) * 1000, "config 5 in ns")
+    rng = np.random.default_rng(5)
+    # every waiting time itself is beyond 2^32: two to five workers with iteration times near 2^33
+    for P, R in ((2, 3), (3, 40), (5, 700), (2, 5000)):
+        steps = rng.integers(2 ** 33, 2 ** 33 + 2 ** 31, size=(7, P, R), dtype=np.int64)
+        assert_same(zl, oracle, np.cumsum(steps, axis=2), f"steps near 2^33, P={P} R={R}")
+    # dense stretches far apart: most pieces of 2^32 are empty, some hold more than a workgroup takes
+    for P, R in ((8, 600), (64, 512), (300, 100)):
+        steps = rng.integers(1, 50, size=(3, P, R), dtype=np.int64)
+        steps[:, :, R // 3] += 2 ** 40
+        steps[:, :, 2 * R // 3] += 2 ** 34
+        steps[:, ::3, R // 2] += 2 ** 36
+        assert_same(zl, oracle, np.cumsum(steps, axis=2) - 2 ** 41, f"clusters far apart, P={P} R={R}")
+    # the widest values the precondition allows for two workers
+    big = np.array([[[0, 2 ** 61, 2 ** 62 - 1], [5, 2 ** 61 + 7, 2 ** 62 - 3]]], dtype=np.int64)
+    assert_same(zl, oracle, big, "values up to 2^62")
+    assert_same(zl, oracle, big - 2 ** 61, "values from -2^61")
