@@ -32,13 +32,14 @@
 extern "C" {
 #endif
 
-/* Return codes (host-detectable errors; nothing is enqueued when one is returned). */
+/* Return codes.  Nothing is enqueued when an error is returned, except for
+ * EBSP_ERR_LAUNCH, which may follow earlier launches of the same call. */
 #define EBSP_OK                0
 #define EBSP_ERR_NULL         -1   /* a required pointer is NULL                         */
 #define EBSP_ERR_SHAPE        -2   /* B < 0, P < 1, R < 1, or P*R >= 2^31                */
 #define EBSP_ERR_WORKSPACE    -3   /* workspace_bytes < ebsp_zipline_workspace_bytes()   */
 #define EBSP_ERR_LAUNCH       -4   /* the HIP runtime refused a launch; see last_error   */
-#define EBSP_ERR_DEVICE       -5   /* not a gfx950 device / LDS too small                */
+#define EBSP_ERR_DEVICE       -5   /* the current HIP device is not a gfx950             */
 
 /* Per-instance status bits written to status[b] (data errors; that instance's
  * outputs are then unspecified, other instances are unaffected). */

@@ -38,6 +38,7 @@
 //   zl_finish.h    reduction over windows, zl_iters; the copy yardstick
 // This file: the host side (plans, launches, the C entry points).
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <stdint.h>
 #include <stdio.h>
 #include <string.h>
@@ -56,6 +57,25 @@ int fail(int code, const char* msg)
 {
     snprintf(g_err, sizeof g_err, "%s", msg);
     return code;
+}
+
+// The kernels are built for gfx950 only: refuse any other device by name instead of
+// letting a launch fail.  Asked once per device; the answer is kept.
+int check_device()
+{
+    constexpr int KNOWN = 64;
+    static std::atomic<signed char> seen[KNOWN];       // 0: not asked yet, 1: gfx950, -1: something else
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return fail(EBSP_ERR_DEVICE, "no current HIP device");
+    signed char state = dev >= 0 && dev < KNOWN ? seen[dev].load(std::memory_order_relaxed) : 0;
+    if (state == 0) {
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return fail(EBSP_ERR_DEVICE, "hipGetDeviceProperties failed");
+        state = strncmp(prop.gcnArchName, "gfx950", 6) == 0 ? 1 : -1;
+        if (dev >= 0 && dev < KNOWN) seen[dev].store(state, std::memory_order_relaxed);
+    }
+    if (state < 0) return fail(EBSP_ERR_DEVICE, "the current device is not a gfx950 (MI355X): this library has code for nothing else");
+    return EBSP_OK;
 }
 
 enum KernelId { K_INSTANCE = 0, K_INSTANCE_GENERAL, K_BOUNDS, K_PARTITION, K_BINCOUNT, K_PLAN, K_WINDOW,
@@ -238,6 +258,7 @@ int run_batch(const i64* ts, const i64* le, const i64* iv, i64 B, int P, int R,
     const int n = P * R;
 
     if (!pl.multi) {
+        if (int rc = check_device()) return rc;
         const int rshift = (R & (R - 1)) == 0 ? __builtin_ctz((unsigned)R) : -1;
         const dim3 grid((unsigned)B);
 #define LAUNCH_INSTANCE(NT_, ITEMS_)                                                                        \
@@ -272,9 +293,10 @@ int run_batch(const i64* ts, const i64* le, const i64* iv, i64 B, int P, int R,
     Partial* partial = (Partial*)(wsp + pl.off_partial);
     uint2* rowpar = pred ? (uint2*)(wsp + pl.off_rowpar) : nullptr;
 
-    if (int rc = plan_windows(pl, ts, le, iv, B, P, R, wsp, status, true, st)) return rc;
     const i64 pblocks = (P + 255) / 256;
     if (pblocks * B > 0x7fffffffll) return fail(EBSP_ERR_SHAPE, "batch too large for one call");
+    if (int rc = check_device()) return rc;
+    if (int rc = plan_windows(pl, ts, le, iv, B, P, R, wsp, status, true, st)) return rc;
     const u32 groups = (u32)(pl.max_win / WINDOWS_PER_BLOCK);
     const u32 groups_inv = groups > 1 ? (u32)((1ull << 32) / groups) : 0xffffffffu;
     const unsigned wgrid = (unsigned)((B * (i64)groups + 7) / 8 * 8);
@@ -316,6 +338,7 @@ int run_range_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters
     if (!ts || !barrier || !iters || !dmin) return fail(EBSP_ERR_NULL, "ts, barrier, iters and dmin must not be NULL");
     if (B > 0x7fffffffll) return fail(EBSP_ERR_SHAPE, "B must be below 2^31");
     if (!pl.multi) {
+        if (int rc = check_device()) return rc;
         LAUNCH(K_RANGE_INSTANCE, (zl_range_instance_kernel<LARGE_NT, LARGE_ITEMS>), dim3((unsigned)B), dim3(LARGE_NT),
                ts, P, R, barrier, iters, dmin, status);
         return EBSP_OK;
@@ -333,9 +356,10 @@ int run_range_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters
     WinVal* winval = (WinVal*)(wsp + pl.off_winval);
     Partial* partial = (Partial*)(wsp + pl.off_partial);
 
-    if (int rc = plan_windows(pl, ts, nullptr, nullptr, B, P, R, wsp, status, false, st)) return rc;
     const i64 pblocks = (P + 255) / 256;
     if (pblocks * B > 0x7fffffffll) return fail(EBSP_ERR_SHAPE, "batch too large for one call");
+    if (int rc = check_device()) return rc;
+    if (int rc = plan_windows(pl, ts, nullptr, nullptr, B, P, R, wsp, status, false, st)) return rc;
     const u32 groups = (u32)(pl.max_win / WINDOWS_PER_BLOCK);
     const u32 groups_inv = groups > 1 ? (u32)((1ull << 32) / groups) : 0xffffffffu;
     const unsigned wgrid = (unsigned)((B * (i64)groups + 7) / 8 * 8);
@@ -485,6 +509,7 @@ int ebsp_zipline_copy_probe(const void* src, void* dst, size_t bytes, void* stre
     if (!src || !dst) return fail(EBSP_ERR_NULL, "src and dst must not be NULL");
     if (bytes == 0 || bytes % 16 != 0 || (((uintptr_t)src | (uintptr_t)dst) & 15u))
         return fail(EBSP_ERR_SHAPE, "copy probe needs a positive multiple of 16 bytes and 16-byte aligned pointers");
+    if (int rc = check_device()) return rc;
     hipStream_t st = (hipStream_t)stream;
     const i64 n = (i64)(bytes / 16);
     i64 blocks = (n + 255) / 256;

@@ -83,6 +83,43 @@ def test_argument_errors_are_reported_without_a_device(lib):
     assert lib.ebsp_zipline_profile_begin(0) == -2
 
 
+def test_simulation_argument_errors(lib):
+    from paper_2001_01347_amd import zipline
+    null = ctypes.c_void_p(0)
+    one = ctypes.c_void_p(256)   # never dereferenced: every call below fails validation first
+    sim = lib.ebsp_simulate_supersteps
+    # (last_end0, interval, sync_cost, S, B, P, R, barrier, iters, wait, status, workspace, bytes, stream)
+    assert sim(one, one, 0, -1, 1, 4, 8, one, one, one, null, one, 1 << 20, null) == -2
+    assert sim(one, one, -1, 2, 1, 4, 8, one, one, one, null, one, 1 << 20, null) == -2
+    assert "sync_cost" in zipline.ebsp_last_error()
+    assert sim(one, one, 0, 2, 1, 0, 8, one, one, one, null, one, 1 << 20, null) == -2
+    assert sim(null, one, 0, 2, 1, 4, 8, one, one, one, null, one, 1 << 20, null) == -1
+    assert sim(one, null, 0, 2, 1, 4, 8, one, one, one, null, one, 1 << 20, null) == -1
+    assert sim(one, one, 0, 2, 1, 4, 8, one, null, one, null, one, 1 << 20, null) == -1
+    assert sim(one, one, 0, 2, 1, 4, 8, one, one, one, null, null, 0, null) == -1       # the start times need a workspace
+    assert sim(one, one, 0, 2, 1, 4, 8, one, one, one, null, ctypes.c_void_p(264), 1 << 20, null) == -3
+    need = zipline.ebsp_simulate_workspace_bytes(3, 600, 240)
+    assert need >= zipline.ebsp_zipline_workspace_bytes(3, 600, 240) + 3 * 600 * 8
+    assert zipline.ebsp_simulate_workspace_bytes(5, 16, 64) == 5 * 16 * 8 + (-5 * 16 * 8) % 256
+    assert sim(one, one, 0, 2, 3, 600, 240, one, one, one, null, one, need - 256, null) == -3
+    # no supersteps or no instances: nothing to do, whatever the pointers
+    assert sim(null, null, 0, 0, 3, 4, 8, null, null, null, null, null, 0, null) == 0
+    assert sim(null, null, 0, 5, 0, 4, 8, null, null, null, null, null, 0, null) == 0
+
+
+def test_a_valid_call_without_a_gfx950_fails_loudly(lib):
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    from paper_2001_01347_amd import zipline
+    null = ctypes.c_void_p(0)
+    one = ctypes.c_void_p(256)   # never dereferenced: the device check comes before any launch
+    assert lib.ebsp_zipline_batch(one, 1, 4, 8, one, one, one, null, null, 0, null) == -5
+    assert "device" in zipline.ebsp_last_error()
+    assert lib.ebsp_zipline_range_batch(one, 1, 4, 8, one, one, one, null, null, 0, null) == -5
+    assert lib.ebsp_predict_zipline_batch(one, one, 1, 4, 8, one, one, one, null, null, 0, null) == -5
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     from paper_2001_01347_amd import zipline
