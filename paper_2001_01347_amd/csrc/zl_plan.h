@@ -150,16 +150,16 @@ __global__ __launch_bounds__(NT) void zl_partition_kernel(
     int carry = -1;                        // bin of the element before lane 0's
     i64 carry_t = INT64_MIN;               // and its value
     bool bad = false;
-    for (int i0 = 0; i0 < R; i0 += WAVE) {
-        const int i = i0 + lane;
+    for (u32 i0 = 0; i0 < (u32)R; i0 += WAVE) {       // unsigned: R may be within a wave's width of 2^31
+        const u32 i = i0 + (u32)lane;
         int bin = -1;
         i64 t = INT64_MAX;
-        if (i < R) { t = row[i]; bin = (int)fine_bin((u64)t - base, ii, tab); }
+        if (i < (u32)R) { t = row[i]; bin = (int)fine_bin((u64)t - base, ii, tab); }
         int pb = __shfl_up(bin, 1, WAVE);
         i64 pt = __shfl_up(t, 1, WAVE);
         if (lane == 0) { pb = carry; pt = carry_t; }
         bad |= t < pt;                     // the only place the multi-window path checks every pair of neighbours
-        if (i < R)
+        if (i < (u32)R)
             for (int k = pb + 1; k <= bin; ++k) out[k] = (CT)i;
         carry = __shfl(bin, WAVE - 1, WAVE);
         carry_t = __shfl(t, WAVE - 1, WAVE);
@@ -201,17 +201,17 @@ __global__ __launch_bounds__(PART_ROWS * WAVE) void zl_partition_sum_kernel(
         int carry = -1;                        // bin of the element before lane 0's
         i64 carry_t = INT64_MIN;               // and its value
         bool bad = false;
-        for (int i0 = 0; i0 < R; i0 += WAVE) {
-            const int i = i0 + lane;
+        for (u32 i0 = 0; i0 < (u32)R; i0 += WAVE) {   // unsigned: R may be within a wave's width of 2^31
+            const u32 i = i0 + (u32)lane;
             int bin = -1;
             i64 t = INT64_MAX;
-            if (i < R) { t = row[i]; bin = (int)fine_bin((u64)t - base, ii, tab); }
+            if (i < (u32)R) { t = row[i]; bin = (int)fine_bin((u64)t - base, ii, tab); }
             int pb = __shfl_up(bin, 1, WAVE);
             i64 pt = __shfl_up(t, 1, WAVE);
             if (lane == 0) { pb = carry; pt = carry_t; }
             bad |= t < pt;                     // the only place the multi-window path checks every pair of neighbours
-            if (i < R)
-                for (int k = pb + 1; k <= bin; ++k) { out[k] = (CT)i; atomicAdd(&sums[k], (u32)i); }
+            if (i < (u32)R)
+                for (int k = pb + 1; k <= bin; ++k) { out[k] = (CT)i; atomicAdd(&sums[k], i); }
             carry = __shfl(bin, WAVE - 1, WAVE);
             carry_t = __shfl(t, WAVE - 1, WAVE);
         }

@@ -74,12 +74,12 @@ __device__ __forceinline__ void sub_range(const Rows& rw, int p, u64 a, u64 el, 
 // zl_iters: number of entries of a sorted row that are <= v.
 __device__ __forceinline__ int zl_iters(const i64* __restrict__ row, int R, i64 v)
 {
-    int lo = 0, hi = R;
+    u32 lo = 0, hi = (u32)R;               // unsigned: lo + hi may pass 2^31
     while (lo < hi) {
-        int m = (lo + hi) >> 1;
+        const u32 m = (lo + hi) >> 1;
         if (row[m] <= v) lo = m + 1; else hi = m;
     }
-    return lo;
+    return (int)lo;
 }
 
 // The same for row p of stored (inst != nullptr) or predicted rows.
@@ -87,12 +87,12 @@ __device__ __forceinline__ int zl_iters_of(const i64* inst, const i64* le, const
 {
     if (inst) return zl_iters(inst + (size_t)p * R, R, v);
     const i64 l = le[p], s = iv[p];
-    int lo = 0, hi = R;
+    u32 lo = 0, hi = (u32)R;
     while (lo < hi) {
-        const int m = (lo + hi) >> 1;
+        const u32 m = (lo + hi) >> 1;
         if ((i64)((u64)l + (u64)(m + 1) * (u64)s) <= v) lo = m + 1; else hi = m;
     }
-    return lo;
+    return (int)lo;
 }
 
 }  // namespace

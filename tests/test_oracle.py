@@ -182,3 +182,19 @@ def test_batch_and_threads(oracle):
     for j in (0, 17, 63):
         s = oracle.zipline(ts[j], "sweep")
         assert s[0][0] == one[0][j] and s[2][0] == one[2][j] and np.array_equal(s[1][0], one[1][j])
+
+
+def test_workers_with_one_common_interval_closed_form(oracle):
+    # the closed form the large-instance GPU tests rely on, against every route of both oracles
+    from closed_forms import same_interval_workers
+    rng = np.random.default_rng(31)
+    for P, R, D, distinct in [(2, 3, 10, True), (5, 4, 50, True), (7, 9, 13, False), (40, 6, 1000, True), (64, 12, 37, False)]:
+        for _ in range(20):
+            off = rng.choice(D, size=P, replace=False) if distinct else rng.integers(0, D, size=P)
+            t = (off[:, None] + np.arange(R)[None, :] * D).astype(np.int64)
+            want = same_interval_workers(off, D, R)
+            for m in ("sweep", "definition"):
+                b, it, w, rc, _ = oracle.zipline(t, m)
+                assert (int(b[0]), int(w[0])) == want["sum"][:2] and np.array_equal(it[0], want["sum"][2]), (P, R, D, off)
+                b, it, d, rc, _ = oracle.zipline_range(t, m)
+                assert (int(b[0]), int(d[0])) == want["range"][:2] and np.array_equal(it[0], want["range"][2]), (P, R, D, off)
