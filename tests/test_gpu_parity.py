@@ -283,3 +283,41 @@ def test_shifted_epoch_multi_window(zl, oracle):
     assert_same(zl, oracle, workloads.make(5, instances=[0, 63], shift=EPOCH), "config 5 shifted")
     assert_same(zl, oracle, workloads.make(4, instances=range(16), shift=EPOCH), "config 4 shifted")
     assert_same(zl, oracle, workloads.make(3, instances=range(64), shift=-EPOCH), "config 3 shifted")
+
+
+def all_three(zl, oracle, ts, label):
+    """Summed wait and max(Z) - min(Z) on stored rows against their oracles."""
+    assert_same(zl, oracle, ts, label)
+    d = torch.from_numpy(np.ascontiguousarray(ts)).cuda()
+    bar, it, dm, st = (x.cpu().numpy() for x in zl.ebsp_zipline_range_batch(d))
+    ob, oi, od, rc, _ = oracle.zipline_range(ts, "sweep", threads=16)
+    assert (rc == 0).all() and (st == 0).all(), label
+    assert np.array_equal(bar, ob) and np.array_equal(dm, od) and np.array_equal(it, oi), f"{label}: range objective"
+
+
+def test_values_at_the_ends_of_int64(zl, oracle):
+    # all arithmetic is relative to the instance's smallest value, modulo 2^64: the epoch may sit anywhere
+    rng = np.random.default_rng(64)
+    lo, hi = np.iinfo(np.int64).min, np.iinfo(np.int64).max
+    for P, R in [(3, 5), (16, 64), (100, 163), (64, 257), (300, 100)]:
+        ts = np.stack([workloads.random_small(rng, P, R, 1, 1000, ties=(i % 2 == 0)) for i in range(3)])
+        ts -= ts.min()
+        all_three(zl, oracle, ts + lo, f"from INT64_MIN, P={P} R={R}")
+        all_three(zl, oracle, ts + (hi - ts.max()), f"up to INT64_MAX, P={P} R={R}")
+        all_three(zl, oracle, ts - ts.max() // 2, f"around zero, P={P} R={R}")
+        # predicted rows ending exactly at INT64_MAX
+        iv = rng.integers(1, 1000, size=(3, P)).astype(np.int64)
+        le = hi - R * iv - rng.integers(0, 3, size=(3, P)) * (iv != iv.max(axis=1, keepdims=True))
+        got = tuple(x.cpu().numpy() for x in zl.ebsp_predict_zipline_batch(torch.from_numpy(le).cuda(), torch.from_numpy(iv).cuda(), R))
+        ob, oi, ow, rc, _ = oracle.zipline(oracle.predicted_rows(le, iv, R), "sweep", threads=8)
+        assert (got[3] == 0).all() and (rc == 0).all()
+        assert np.array_equal(got[0], ob) and np.array_equal(got[2], ow) and np.array_equal(got[1], oi), f"predicted up to INT64_MAX, P={P} R={R}"
+
+
+def test_very_many_instances(zl, oracle):
+    # a million tiny instances (one workgroup each) and twelve thousand that are cut into windows
+    rng = np.random.default_rng(1_000_000)
+    steps = rng.integers(1, 50, size=(1_000_000, 3, 5), dtype=np.int64)
+    all_three(zl, oracle, np.cumsum(steps, axis=2) + rng.integers(0, 50, size=(1_000_000, 3, 1)), "B = 10^6, P=3 R=5")
+    steps = rng.integers(1, 2000, size=(12_000, 300, 100), dtype=np.int64)
+    all_three(zl, oracle, np.cumsum(steps, axis=2) + rng.integers(0, 2000, size=(12_000, 300, 1)), "B = 12000, P=300 R=100")
