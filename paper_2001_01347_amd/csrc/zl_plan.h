@@ -305,10 +305,10 @@ __global__ __launch_bounds__(256) void zl_bincount_kernel(
 // zl_plan: windows of an instance.  below[] holds the exact number of keys under
 // every fine bin, so the windows are packed greedily: a window takes fine bins while
 // its entries stay within `fill` (a bin larger than that becomes a window of its own,
-// which the window kernel leaves to the general search).  The packing is a sequential
-// walk over the bins by one wave (64 bins at a time, one ballot per window), fed from
-// LDS in slices the workgroup loads together; the per-window values follow in parallel.  Per window: its first fine bin
-// (winstart), its first and last value and the constants of the linear bucket map
+// which the window kernel leaves to the general search).  The greedy chain of window
+// starts is followed by pointer doubling over the bins held in LDS, a slice of them at a
+// time (see the kernel); the per-window values follow in parallel.  Per window: its first
+// fine bin (winstart), its first and last value and the constants of the linear bucket map
 // over that span (winval).
 struct WinVal {
     u64 A, Elast;
@@ -323,7 +323,7 @@ __global__ __launch_bounds__(NT) void zl_plan_kernel(
     u32* __restrict__ winstart, WinVal* __restrict__ winval, int max_win, u32 fill, u32 buckets)
 {
     __shared__ u32 ends[PLAN_SLICE + 1];   // ends[i + 1] = keys under bin k0 + i + 1 = where bin k0 + i ends
-    __shared__ u32 found_all;
+    __shared__ u32 found_all, slice_cnt, slice_last;
     __shared__ SegEntry tab[SEGS];         // the instance's fine-bin map
     __shared__ u16 hop[2][PLAN_SLICE + 1];
     const int tid = threadIdx.x;
@@ -333,83 +333,77 @@ __global__ __launch_bounds__(NT) void zl_plan_kernel(
     WinVal* wv = winval + b * (i64)max_win;
     const InstInfo ii = info[b];
     const int nb = (int)ii.nb;
-    if (tid == 0) found_all = 0;
-    if (nb <= PLAN_SLICE) {
-        // All bins fit in LDS.  jump[k] = the bin that opens the next window if one opens at bin k
-        // (nb: none); the windows open at 0, jump[0], jump[jump[0]], ...  Thread r finds the r-th
-        // of them by squaring the jump table: level l applies jump^(2^l) to the ranks with bit l set.
-        static_assert(PLAN_SLICE % NT == 0, "whole ranks per thread");
-        constexpr int RANKS = PLAN_SLICE / NT;          // ranks per thread: every window holds at least one bin
-        u16* jump = hop[0];
-        u16* other = hop[1];
-        for (int i = tid; i <= nb; i += NT) ends[i] = bel[i];
+    static_assert(PLAN_SLICE % NT == 0, "whole ranks per thread");
+    constexpr int RANKS = PLAN_SLICE / NT;              // ranks per thread: every window holds at least one bin
+    // The bins are taken a slice at a time.  Inside a slice, jump[k] = the bin that opens the next
+    // window if one opens at bin k (cnt: none in this slice); the windows open at s0, jump[s0],
+    // jump[jump[s0]], ...  Thread r finds the r-th of them by squaring the jump table: level l applies
+    // jump^(2^l) to the ranks with bit l set.  The window that is open at the end of a slice goes on
+    // into the next one, whose s0 is the first bin that no longer fits it.
+    u32 found = 0, open_key = 0;           // windows so far; keys under the first bin of the window that is open
+    bool have_open = false;
+    u16* jump = hop[0];
+    u16* other = hop[1];
+    for (int k0 = 0; k0 < nb; k0 += PLAN_SLICE) {
+        const int cnt = nb - k0 < PLAN_SLICE ? nb - k0 : PLAN_SLICE;
+        __syncthreads();                                  // the slice before is done with
+#pragma unroll 4
+        for (int i = tid; i <= cnt; i += NT) ends[i] = bel[k0 + i];
+        if (tid == 0) { slice_cnt = 0; slice_last = 0; }
         __syncthreads();
-        for (int k = tid; k <= nb; k += NT) {
-            int lo = k + 1, hi = nb;                      // first bin j > k whose end lies more than `fill` past the start of bin k
-            if (k < nb) {
-                const u32 limit = ends[k] + fill;         // no overflow: fill and the key count are both below 2^31
+        int s0 = 0;
+        if (have_open) {                                  // first bin whose end lies more than `fill` past the open window's start
+            const u32 limit = open_key + fill;            // no overflow: fill and the key count are both below 2^31
+            int lo = 0, hi = cnt;
+            while (lo < hi) { const int m = (lo + hi) >> 1; if (ends[m + 1] > limit) hi = m; else lo = m + 1; }
+            s0 = lo;
+        }
+        if (s0 >= cnt) continue;                          // the same for every thread: the open window takes the whole slice
+        for (int k = tid; k <= cnt; k += NT) {
+            int lo = k + 1, hi = cnt;                     // first bin j > k whose end lies more than `fill` past the start of bin k
+            if (k < cnt) {
+                const u32 limit = ends[k] + fill;
                 while (lo < hi) { const int m = (lo + hi) >> 1; if (ends[m + 1] > limit) hi = m; else lo = m + 1; }
-            } else lo = nb;
+            } else lo = cnt;
             jump[k] = (u16)lo;
         }
         u32 pos[RANKS];
 #pragma unroll
-        for (int q = 0; q < RANKS; ++q) pos[q] = 0;
-        const u32 top_rank = (u32)nb < (u32)max_win ? (u32)nb : (u32)max_win;
-        for (int level = 0; (1u << level) <= top_rank; ++level) {
+        for (int q = 0; q < RANKS; ++q) pos[q] = (u32)s0;
+        const u32 top_rank = (u32)cnt < (u32)max_win ? (u32)cnt : (u32)max_win;
+        int level = 0;
+        for (; (1u << level) <= top_rank; ++level) {
             __syncthreads();
 #pragma unroll
             for (int q = 0; q < RANKS; ++q)
                 if (((u32)(q * NT + tid) >> level) & 1u) pos[q] = jump[pos[q]];
-            for (int k = tid; k <= nb; k += NT) other[k] = jump[jump[k]];
+            for (int k = tid; k <= cnt; k += NT) other[k] = jump[jump[k]];
             u16* t = jump; jump = other; other = t;
         }
+        const u32 rank_end = 1u << level;                 // ranks from here on had their upper bits ignored: not windows
 #pragma unroll
         for (int q = 0; q < RANKS; ++q) {
             const u32 r = (u32)(q * NT + tid);
-            if (pos[q] < (u32)nb && r < (u32)max_win) {
-                ws[r] = pos[q];
-                atomicMax(&found_all, r + 1);
+            if (pos[q] < (u32)cnt && r < rank_end) {
+                // more starts than max_win cannot come from sorted rows; the last window then runs to the end
+                if (found + r < (u32)max_win) ws[found + r] = (u32)k0 + pos[q];
+                atomicMax(&slice_cnt, r + 1);
             }
         }
         __syncthreads();
-        if (tid == 0) { ws[found_all] = (u32)nb; info[b].nwin = found_all; }
-    } else {
-    // wave 0 walks the bins, 64 at a time: one step per window, not per bin
-    u32 found = 0, first_key = 0;          // windows so far, keys under the open window's first bin
-    for (int k0 = 0; k0 < nb; k0 += PLAN_SLICE) {
-        const int cnt = nb - k0 < PLAN_SLICE ? nb - k0 : PLAN_SLICE;
+#pragma unroll
+        for (int q = 0; q < RANKS; ++q)
+            if (pos[q] < (u32)cnt && (u32)(q * NT + tid) + 1 == slice_cnt) slice_last = pos[q];   // the slice's last window stays open
         __syncthreads();
-#pragma unroll 4
-        for (int i = tid; i <= cnt; i += NT) ends[i] = bel[k0 + i];
-        __syncthreads();
-        if (tid < WAVE) {
-            for (int i0 = 0; i0 < cnt; i0 += WAVE) {
-                const int i = i0 + tid;
-                const bool valid = i < cnt;
-                const u32 e = valid ? ends[i + 1] : 0u;
-                const u32 before = valid ? ends[i] : 0u;            // where the bin before this one ends
-                int from = 0;
-                for (;;) {
-                    const bool opens = valid && tid >= from && (k0 + i == 0 || e - first_key > fill);
-                    const unsigned long long m = __ballot(opens);
-                    if (!m) break;
-                    const int at = __builtin_amdgcn_readfirstlane(__ffsll((long long)m) - 1);   // bin k0 + i0 + at opens a window
-                    if (tid == at && found < (u32)max_win) ws[found] = (u32)(k0 + i);
-                    ++found;
-                    first_key = (u32)__builtin_amdgcn_readlane((int)before, at);
-                    from = at + 1;
-                }
-            }
-        }
+        open_key = ends[slice_last];
+        have_open = true;
+        found += slice_cnt;
     }
     if (tid == 0) {
-        // more starts than max_win cannot come from sorted rows; the last window then runs to the end
         const u32 nwin = found < (u32)max_win ? found : (u32)max_win;
         ws[nwin] = (u32)nb;
         info[b].nwin = nwin;
         found_all = nwin;
-    }
     }
     if (tid < SEGS) tab[tid] = segtab[b * (i64)SEGS + tid];
     __threadfence_block();

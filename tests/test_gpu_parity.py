@@ -321,3 +321,21 @@ def test_very_many_instances(zl, oracle):
     all_three(zl, oracle, np.cumsum(steps, axis=2) + rng.integers(0, 50, size=(1_000_000, 3, 1)), "B = 10^6, P=3 R=5")
     steps = rng.integers(1, 2000, size=(12_000, 300, 100), dtype=np.int64)
     all_three(zl, oracle, np.cumsum(steps, axis=2) + rng.integers(0, 2000, size=(12_000, 300, 1)), "B = 12000, P=300 R=100")
+
+
+@pytest.mark.parametrize("k,n", [(4, 64), (5, 4)])
+def test_the_fast_kernels_take_the_configurations(zl, k, n):
+    # On the synthetic configurations next to nothing is left to the general (sort-based) kernels.
+    # They are correct too, so only their share of the time shows whether the windows are planned
+    # as intended: a plan with surplus or oversize windows would still pass every parity test.
+    ts = torch.from_numpy(workloads.make(k, instances=range(n))).cuda()
+    for call, fast, general in ((zl.ebsp_zipline_batch, "zl_window_kernel", "zl_window_general_kernel"),
+                                (zl.ebsp_zipline_range_batch, "zl_range_fast_kernel", "zl_range_window_kernel")):
+        call(ts)
+        torch.cuda.synchronize()
+        zl.ebsp_zipline_profile_begin(3)
+        for _ in range(3):
+            out = call(ts)
+        ms, calls = zl.ebsp_zipline_profile_end()
+        assert calls == 3 and int(out[3].max().item()) == 0
+        assert ms[general] < 0.5 * ms[fast], f"config {k}: {general} {ms[general]:.3f} ms against {fast} {ms[fast]:.3f} ms"
