@@ -3,7 +3,9 @@
 The oracle would take minutes for one such instance, so the inputs are workers with one common
 iteration time, whose answer has a closed form (``closed_forms.same_interval_workers``, itself
 checked against every route of the oracle at small sizes in ``test_oracle.py``).  The rows are
-built on the device.  Bar: bit-exact on all three outputs of all three entry points.
+built on the device.  Shapes with extreme aspect ratios (a million workers with one iteration, two
+workers with a million) are small enough for the oracle and are compared with it.
+Bar: bit-exact on all three outputs of all three entry points.
 """
 import numpy as np
 import pytest
@@ -66,3 +68,24 @@ def test_shapes_beyond_the_limit_are_refused(zl):
     assert lib.ebsp_zipline_batch(p, 1, 1 << 16, 1 << 15, p, p, p, None, None, 0, None) == -2
     assert lib.ebsp_zipline_range_batch(p, 1, 1 << 16, 1 << 15, p, p, p, None, None, 0, None) == -2
     assert zl.ebsp_zipline_workspace_bytes(1, 1 << 16, 1 << 15) == 0
+
+
+@pytest.mark.parametrize("B,P,R", [(1, 1 << 20, 1), (1, 1 << 20, 2), (2, 300000, 3), (1, 65537, 16), (3, 17, 65535),
+                                   (3, 17, 65536), (3, 17, 65537), (1, 2, 1 << 20), (5, 1, 100000), (1, 40000, 40)])
+def test_extreme_aspect_ratios(zl, oracle, B, P, R):
+    # a million workers with one or two iterations each, two workers with a million, R on both sides of
+    # the switch from 16- to 32-bit crossing indices: all three entry points against the oracle
+    rng = np.random.default_rng(P + R)
+    ts = np.cumsum(rng.integers(1, 1000, size=(B, P, R), dtype=np.int64), axis=2) + rng.integers(0, 1000, size=(B, P, 1))
+    dev = torch.from_numpy(ts).cuda()
+    ob, oi, ow, rc, _ = oracle.zipline(ts, "sweep", threads=16)
+    bar, it, w, st = (x.cpu().numpy() for x in zl.ebsp_zipline_batch(dev))
+    assert (st == 0).all() and np.array_equal(bar, ob) and np.array_equal(w, ow) and np.array_equal(it, oi)
+    ob, oi, od, rc, _ = oracle.zipline_range(ts, "sweep", threads=16)
+    bar, it, dm, st = (x.cpu().numpy() for x in zl.ebsp_zipline_range_batch(dev))
+    assert (st == 0).all() and np.array_equal(bar, ob) and np.array_equal(dm, od) and np.array_equal(it, oi)
+    iv = rng.integers(0, 1000, size=(B, P)).astype(np.int64)
+    le = rng.integers(0, 1000, size=(B, P)).astype(np.int64)
+    ob, oi, ow, rc, _ = oracle.zipline(oracle.predicted_rows(le, iv, R), "sweep", threads=16)
+    bar, it, w, st = (x.cpu().numpy() for x in zl.ebsp_predict_zipline_batch(torch.from_numpy(le).cuda(), torch.from_numpy(iv).cuda(), R))
+    assert (st == 0).all() and np.array_equal(bar, ob) and np.array_equal(w, ow) and np.array_equal(it, oi)
