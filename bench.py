@@ -31,12 +31,12 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 # this program (their summaries, with the commands, are under profiles/), each scaled by what the same counter
 # reads for the plain copy kernel of known size (FETCH_SIZE x 2048 B, WRITE_SIZE x 1024 B per count).  They
 # hold only for the kernel sources they were taken from: `traffic` is null once those have changed.
-COUNTED_SOURCES_SHA256 = "16ae33c291dc9a826277e5e1a8ad1a81489a7ea16b91a9133cdacf49bcaea6de"
+COUNTED_SOURCES_SHA256 = "b1b4571e26c87fb1e2d982c73b8147577755d63f06ab68e4738a2cc96e5d7a85"
 COUNTED_TRAFFIC = {     # (objective, predicted, config) -> (dominant kernel, its bytes, bytes of all kernels of a call)
-    ("sum", False, 5): ("zl_window_kernel", 2254300 * 2048 + 1230 * 1024, 7580975883),
-    ("sum", False, 3): ("zl_instance_kernel", 1189500 * 2048 + 5653 * 1024, 2453610240),
-    ("range", False, 5): ("zl_range_fast_kernel", 2233900 * 2048 + 1680 * 1024, 7539880000),
-    ("sum", True, 5): ("zl_window_kernel", 267400 * 2048 + 560 * 1024, 1175839691),
+    ("sum", False, 5): ("zl_window_kernel", 2255091 * 2048 + 1231 * 1024, 7583295744),
+    ("sum", False, 3): ("zl_instance_kernel", 1189698 * 2048 + 5654 * 1024, 2454008736),
+    ("range", False, 5): ("zl_range_fast_kernel", 2234303 * 2048 + 1680 * 1024, 7550361824),
+    ("sum", True, 5): ("zl_window_kernel", 267418 * 2048 + 560 * 1024, 1175819243),
 }
 
 
