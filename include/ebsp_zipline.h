@@ -199,10 +199,12 @@ int ebsp_zipline_tune(int32_t window_cap, int32_t single_max, int32_t window_fil
 
 /*
  * Per-kernel timing for benchmarks.  Between ebsp_zipline_profile_begin() and
- * ebsp_zipline_profile_end() every ebsp_zipline_batch call made by the calling
- * thread records a pair of HIP events around each kernel it launches, on the
- * call's own stream, without synchronising (events are created up front, for
- * at most max_calls calls; further calls run untimed).
+ * ebsp_zipline_profile_end() every search call made by the calling thread
+ * (any of the batch entry points; every superstep of ebsp_simulate_supersteps
+ * counts as a call of its own) records a pair of HIP events around each kernel
+ * it launches, on the call's own stream, without synchronising (events are
+ * created up front, for at most max_calls calls; further calls run untimed).
+ * Do not capture a stream into a HIP graph while a profile is open.
  * ebsp_zipline_profile_end() synchronises the device, writes to kernel_ms
  * (HOST array of ebsp_zipline_kernel_count() floats, may be NULL) the summed
  * duration in milliseconds of each kernel over the profiled calls and to
