@@ -339,3 +339,42 @@ def test_the_fast_kernels_take_the_configurations(zl, k, n):
         ms, calls = zl.ebsp_zipline_profile_end()
         assert calls == 3 and int(out[3].max().item()) == 0
         assert ms[general] < 0.5 * ms[fast], f"config {k}: {general} {ms[general]:.3f} ms against {fast} {ms[fast]:.3f} ms"
+
+
+def test_host_threads_with_their_own_streams_and_workspaces(zl, oracle):
+    # the header's promise: calls on different streams may overlap if they use different workspaces.
+    # Four host threads, each with a stream, a workspace and a workload of its own (two of them
+    # multi-window), call all three entry points twenty times over while the others do the same.
+    import threading
+    jobs = []
+    for k, n in ((2, 256), (3, 24), (4, 6), (5, 1)):
+        cfg = workloads.CONFIGS[k]
+        ts = workloads.make(k, instances=range(n))
+        le, iv = workloads.make_predicted(k, instances=range(n))
+        want = (oracle.zipline(ts, "sweep", threads=16)[:3], oracle.zipline_range(ts, "sweep", threads=16)[:3],
+                oracle.zipline(oracle.predicted_rows(le, iv, cfg.R), "sweep", threads=16)[:3])
+        jobs.append((cfg, torch.from_numpy(ts).cuda(), torch.from_numpy(le).cuda(), torch.from_numpy(iv).cuda(), want))
+    torch.cuda.synchronize()
+    errors = []
+
+    def work(job):
+        cfg, ts, le, iv, want = job
+        try:
+            stream = torch.cuda.Stream()
+            with torch.cuda.stream(stream):
+                for rep in range(20):
+                    got = (zl.ebsp_zipline_batch(ts), zl.ebsp_zipline_range_batch(ts), zl.ebsp_predict_zipline_batch(le, iv, cfg.R))
+                    stream.synchronize()
+                    for (bar, it, val, st), (ob, oi, ov) in zip(got, want):
+                        if not ((st == 0).all().item() and np.array_equal(bar.cpu().numpy(), ob)
+                                and np.array_equal(val.cpu().numpy(), ov) and np.array_equal(it.cpu().numpy(), oi)):
+                            errors.append(f"config {cfg.k}, repetition {rep}")
+        except Exception as e:          # noqa: BLE001
+            errors.append(f"config {cfg.k}: {e!r}")
+
+    threads = [threading.Thread(target=work, args=(j,)) for j in jobs]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors[:5]
