@@ -378,3 +378,39 @@ def test_host_threads_with_their_own_streams_and_workspaces(zl, oracle):
     for t in threads:
         t.join()
     assert not errors, errors[:5]
+
+
+def test_status_may_be_null(zl, oracle):
+    # the C ABI takes NULL for status on every entry point (the binding always passes an array)
+    lib = zl.load()
+    for k, n in ((2, 64), (4, 3)):                       # one workgroup per instance; windows
+        cfg = workloads.CONFIGS[k]
+        host = workloads.make(k, instances=range(n))
+        le_h, iv_h = workloads.make_predicted(k, instances=range(n))
+        ts, le, iv = (torch.from_numpy(x).cuda() for x in (host, le_h, iv_h))
+        bar = torch.empty(n, dtype=torch.int64, device="cuda")
+        it = torch.empty((n, cfg.P), dtype=torch.int32, device="cuda")
+        val = torch.empty(n, dtype=torch.int64, device="cuda")
+        need = max(zl.ebsp_zipline_workspace_bytes(n, cfg.P, cfg.R), zl.ebsp_zipline_range_workspace_bytes(n, cfg.P, cfg.R),
+                   zl.ebsp_simulate_workspace_bytes(n, cfg.P, cfg.R))
+        ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+        stream = torch.cuda.current_stream().cuda_stream
+
+        def same(want):
+            torch.cuda.synchronize()
+            return (np.array_equal(bar.cpu().numpy(), want[0]) and np.array_equal(it.cpu().numpy(), want[1])
+                    and np.array_equal(val.cpu().numpy(), want[2]))
+
+        assert lib.ebsp_zipline_batch(ts.data_ptr(), n, cfg.P, cfg.R, bar.data_ptr(), it.data_ptr(), val.data_ptr(), None,
+                                      ws.data_ptr(), need, stream) == 0
+        assert same(oracle.zipline(host, "sweep", threads=8))
+        assert lib.ebsp_zipline_range_batch(ts.data_ptr(), n, cfg.P, cfg.R, bar.data_ptr(), it.data_ptr(), val.data_ptr(), None,
+                                            ws.data_ptr(), need, stream) == 0
+        assert same(oracle.zipline_range(host, "sweep", threads=8))
+        assert lib.ebsp_predict_zipline_batch(le.data_ptr(), iv.data_ptr(), n, cfg.P, cfg.R, bar.data_ptr(), it.data_ptr(),
+                                              val.data_ptr(), None, ws.data_ptr(), need, stream) == 0
+        want = oracle.zipline(oracle.predicted_rows(le_h, iv_h, cfg.R), "sweep", threads=8)
+        assert same(want)
+        assert lib.ebsp_simulate_supersteps(le.data_ptr(), iv.data_ptr(), 0, 1, n, cfg.P, cfg.R, bar.data_ptr(), it.data_ptr(),
+                                            val.data_ptr(), None, ws.data_ptr(), need, stream) == 0
+        assert same(want)                                  # one superstep is one predicted search
