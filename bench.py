@@ -111,7 +111,7 @@ def main() -> int:
     ap.add_argument("--single-max", type=int, default=0, help="tuning: largest P*R taken by one workgroup (0: default)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on exactly one GPU (instances are independent and would "
+        print("bench.py: this library runs on exactly one GPU (instances are independent and would "
               "shard over B with no exchange, but no multi-GPU path is part of it); use --gpus 1",
               file=sys.stderr)
         return 2

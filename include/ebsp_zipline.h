@@ -84,7 +84,7 @@ int ebsp_zipline_batch(const int64_t* ts, int64_t B, int32_t P, int32_t R,
 /*
  * The prediction folded in (Section III: a worker's iterations take similar
  * time, so its next R end timestamps are predicted from its most recent ones;
- * the paper gives no formula, the linear one is this build's reading):
+ * the paper gives no formula, the linear one is this library's reading):
  *
  *     t[p][i] = last_end[p] + (i + 1) * interval[p],   i = 0 .. R-1
  *
@@ -124,7 +124,7 @@ int ebsp_predict_zipline_batch(const int64_t* last_end, const int64_t* interval,
  * per superstep (barrier = the slowest worker's end), larger R is ElasticBSP.
  * That workers run exactly as predicted within a superstep, that they all
  * resume at the same time and that a synchronisation takes a fixed time are
- * this build's readings (the paper states none of the three).
+ * this library's readings (the paper states none of the three).
  *
  *   last_end0  in  [B][P] int64, device: each worker's start time of the run.
  *   interval   in  [S][B][P] int64, device: iteration time of worker p of
