@@ -20,7 +20,10 @@
  * enqueue work on `stream` (a hipStream_t passed as void*); they never
  * synchronise it, never allocate and never free.  The caller keeps every
  * buffer alive until the stream has passed the call.  Calls on different
- * streams may overlap if they use different workspaces.
+ * streams may overlap if they use different workspaces.  A call records
+ * kernel launches only (no memory set or copy nodes), so a stream may be
+ * captured into a HIP graph around it; the first call on a device also asks the
+ * runtime for the device's name, so make one call before capturing.
  */
 #ifndef EBSP_ZIPLINE_H
 #define EBSP_ZIPLINE_H
