@@ -339,8 +339,21 @@ int run_range_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters
     if (B > 0x7fffffffll) return fail(EBSP_ERR_SHAPE, "B must be below 2^31");
     if (!pl.multi) {
         if (int rc = check_device()) return rc;
-        LAUNCH(K_RANGE_INSTANCE, (zl_range_instance_kernel<LARGE_NT, LARGE_ITEMS>), dim3((unsigned)B), dim3(LARGE_NT),
-               ts, P, R, barrier, iters, dmin, status);
+        // the smallest workgroup whose records hold the instance (half of NT * ITEMS in the 12-byte form):
+        // several small instances share a CU
+        const i64 n = (i64)P * R;
+        if (n <= 1024)
+            LAUNCH(K_RANGE_INSTANCE, (zl_range_instance_kernel<256, 8>), dim3((unsigned)B), dim3(256),
+                   ts, P, R, barrier, iters, dmin, status);
+        else if (n <= 2048)
+            LAUNCH(K_RANGE_INSTANCE, (zl_range_instance_kernel<256, 16>), dim3((unsigned)B), dim3(256),
+                   ts, P, R, barrier, iters, dmin, status);
+        else if (n <= 4096)
+            LAUNCH(K_RANGE_INSTANCE, (zl_range_instance_kernel<512, 16>), dim3((unsigned)B), dim3(512),
+                   ts, P, R, barrier, iters, dmin, status);
+        else
+            LAUNCH(K_RANGE_INSTANCE, (zl_range_instance_kernel<LARGE_NT, LARGE_ITEMS>), dim3((unsigned)B), dim3(LARGE_NT),
+                   ts, P, R, barrier, iters, dmin, status);
         return EBSP_OK;
     }
     if (!workspace) return fail(EBSP_ERR_NULL, "this shape needs a workspace");

@@ -58,7 +58,8 @@ def test_config1_and_config2_full(zl, oracle):
 
 
 @pytest.mark.parametrize("P,R", [(1, 1), (1, 9), (6, 1), (2, 3), (3, 5), (7, 9), (4, 16), (13, 19), (64, 64),
-                                 (8, 1024), (8192, 1), (100, 81)])
+                                 (8, 1024), (8192, 1), (100, 81), (16, 64), (1, 1024), (1025, 1), (30, 60), (2, 1024),
+                                 (2049, 1), (33, 100), (64, 64), (4097, 1), (90, 90)])
 def test_single_workgroup_shapes(zl, oracle, P, R):
     rng = np.random.default_rng(1000 * P + R)
     ts = np.stack([workloads.random_small(rng, P, R, 1, 1000, ties=(i % 2 == 0)) for i in range(6)])
