@@ -273,9 +273,17 @@ int run_batch(const i64* ts, const i64* le, const i64* iv, i64 B, int P, int R,
         else if (n <= 4096) LAUNCH_INSTANCE(512, 8);
         else LAUNCH_INSTANCE(1024, 16);
 #undef LAUNCH_INSTANCE
-        LAUNCH(K_INSTANCE_GENERAL, (zl_instance_general_kernel<LARGE_NT, LARGE_ITEMS>),
-               dim3((unsigned)(B < GENERAL_GRID ? B : GENERAL_GRID)), dim3(LARGE_NT),
-               ts, le, iv, B, P, R, barrier, iters, wait, status);
+        // what the kernel above left: the general search in the smallest workgroup whose records hold an
+        // instance (half of NT * ITEMS with 64-bit deltas), as many workgroups as fit the chip at once
+#define LAUNCH_GENERAL(NT_, ITEMS_, PER_CU_)                                                                 \
+    LAUNCH(K_INSTANCE_GENERAL, (zl_instance_general_kernel<NT_, ITEMS_>),                                    \
+           dim3((unsigned)(B < PER_CU_ * GENERAL_GRID ? B : PER_CU_ * GENERAL_GRID)), dim3(NT_),            \
+           ts, le, iv, B, P, R, barrier, iters, wait, status)
+        if (n <= 1024) LAUNCH_GENERAL(256, 8, 7);
+        else if (n <= 2048) LAUNCH_GENERAL(256, 16, 4);
+        else if (n <= 4096) LAUNCH_GENERAL(512, 16, 2);
+        else LAUNCH_GENERAL(LARGE_NT, LARGE_ITEMS, 1);
+#undef LAUNCH_GENERAL
         return EBSP_OK;
     }
 
@@ -315,9 +323,14 @@ int run_batch(const i64* ts, const i64* le, const i64* iv, i64 B, int P, int R,
         if (pl.narrow) LAUNCH_WINDOW(256, unsigned short); else LAUNCH_WINDOW(256, u32);
     }
 #undef LAUNCH_WINDOW
-    LAUNCH(K_WINDOW_GENERAL, (zl_window_general_kernel<LARGE_NT, LARGE_ITEMS>),
-           dim3((unsigned)(total_win < GENERAL_GRID ? total_win : GENERAL_GRID)), dim3(LARGE_NT),
-           ts, le, iv, B, P, R, info, cross, pl.narrow, pl.stride, winstart, winval, pl.max_win, partial, status);
+    if (pl.cap <= 4096)       // such windows fit a 512-thread workgroup's general search: two workgroups per CU
+        LAUNCH(K_WINDOW_GENERAL, (zl_window_general_kernel<512, 16>),
+               dim3((unsigned)(total_win < 2 * GENERAL_GRID ? total_win : 2 * GENERAL_GRID)), dim3(512),
+               ts, le, iv, B, P, R, info, cross, pl.narrow, pl.stride, winstart, winval, pl.max_win, partial, status);
+    else
+        LAUNCH(K_WINDOW_GENERAL, (zl_window_general_kernel<LARGE_NT, LARGE_ITEMS>),
+               dim3((unsigned)(total_win < GENERAL_GRID ? total_win : GENERAL_GRID)), dim3(LARGE_NT),
+               ts, le, iv, B, P, R, info, cross, pl.narrow, pl.stride, winstart, winval, pl.max_win, partial, status);
     LAUNCH(K_FINISH, (zl_finish_kernel<256>), dim3((unsigned)(pblocks * B)), dim3(256),
            ts, le, iv, P, R, info, partial, pl.max_win, barrier, iters, wait);
     return EBSP_OK;
