@@ -205,7 +205,8 @@ __global__ __launch_bounds__(NT) void zl_instance_general_kernel(
             int bad = 0;
             u64 best_wait = U64_MAX, best_rel = 0;
             // the 64-bit-delta form serves every deferred instance, narrow ones included
-            zl_window<NT, ITEMS, true>(sm, rw, thr, 0ull, range, best_wait, best_rel, bad);
+            // 64-bit keys: an instance of any value spread in one piece (or as few as its entries need)
+            zl_window<NT, ITEMS, true, true>(sm, rw, thr, 0ull, range, best_wait, best_rel, bad);
             if (__syncthreads_or(bad)) flags |= EBSP_STATUS_UNSORTED;
             const i64 bar = (i64)((u64)base + best_rel);
             if (tid == 0) {

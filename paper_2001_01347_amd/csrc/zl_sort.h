@@ -75,10 +75,13 @@ __device__ __forceinline__ u64 match_digit(u32 d, int dbits)
 // round j lane l holds position w*64*items + j*64 + l.  Ranks within a wave
 // come from ballots, per-wave digit counts live in cnt[w][digit]; a digit-major
 // scan of those counts gives every (wave, digit) its first output position.
-template <int NT, int ITEMS, bool WIDE, bool EXTRA = false>
+// KEYHI: the third plane holds the upper halves of 64-bit keys and takes part in the order
+// (kbits up to 64); otherwise it is payload.
+template <int NT, int ITEMS, bool WIDE, bool EXTRA = false, bool KEYHI = false>
 __device__ __forceinline__ void zl_sort(const Smem& sm, int items, int kbits)
 {
     static_assert(WIDE || !EXTRA, "the third plane goes with the WIDE layout");
+    static_assert(EXTRA || !KEYHI, "upper key halves live in the third plane");
     using C = WinCfg<NT, ITEMS>;
     constexpr int IT = WIDE ? C::ITEMS_WIDE : ITEMS;
     u64* recs = sm.recs;
@@ -104,7 +107,7 @@ __device__ __forceinline__ void zl_sort(const Smem& sm, int items, int kbits)
                 dl[j] = (u32)(r >> 32);
                 if (WIDE) dh[j] = sm.dhi[phys(wbase + j * WAVE)];
                 if (EXTRA) ex[j] = sm.ext[phys(wbase + j * WAVE)];
-                const u32 d = (key[j] >> sh) & dmask;
+                const u32 d = KEYHI ? (u32)(((u64)key[j] | ((u64)ex[j] << 32)) >> sh) & dmask : (key[j] >> sh) & dmask;
                 const u64 peers = match_digit(d, dbits);
                 const u32 below = __popcll(peers & lt);
                 const u32 old = mycnt[d];
@@ -133,7 +136,7 @@ __device__ __forceinline__ void zl_sort(const Smem& sm, int items, int kbits)
 #pragma unroll
         for (int j = 0; j < IT; ++j) {
             if (j < items) {
-                const u32 d = (key[j] >> sh) & dmask;
+                const u32 d = KEYHI ? (u32)(((u64)key[j] | ((u64)ex[j] << 32)) >> sh) & dmask : (key[j] >> sh) & dmask;
                 const int pos = (int)(mycnt[d] + rank[j]);
                 recs[phys(pos)] = (u64)key[j] | ((u64)dl[j] << 32);
                 if (WIDE) sm.dhi[phys(pos)] = dh[j];
@@ -151,10 +154,11 @@ __device__ __forceinline__ void zl_sort(const Smem& sm, int items, int kbits)
 // true value is in [0, 2^63) by the caller's precondition).
 // Returns the block-wide first minimum: (wait, key) with wait == U64_MAX if
 // there is no candidate.
-template <int NT, bool WIDE>
+// KEY64: keys are 64 bits wide, their upper halves in the third plane.
+template <int NT, bool WIDE, bool KEY64 = false>
 __device__ __forceinline__ void zl_scan_argmin(const Smem& sm, int items, int total,
                                                u64 a, u64 thr, u64 P, u64 W0,
-                                               u64& best_wait, u32& best_key)
+                                               u64& best_wait, u64& best_key)
 {
     const u64* recs = sm.recs;
     u64* red = sm.red;
@@ -171,44 +175,50 @@ __device__ __forceinline__ void zl_scan_argmin(const Smem& sm, int items, int to
     u64 S = block_excl_scan<u64, NT>(local, red, sum_all);
 
     u64 bw = U64_MAX;
-    u32 bq = 0xffffffffu, bk = 0;
+    u32 bq = 0xffffffffu;
+    u64 bk = 0;
     u64 r = (q0 < qe) ? recs[phys(q0)] : 0ull;
+    u32 rh = (KEY64 && q0 < qe) ? sm.ext[phys(q0)] : 0u;
     for (int q = q0; q < qe; ++q) {
-        const u32 key = (u32)r;
+        const u64 key = (u64)(u32)r | ((u64)rh << 32);
         S += r >> 32;
         if (WIDE) S += (u64)sm.dhi[phys(q)] << 32;
         const bool has_next = q + 1 < total;
         const u64 rn = has_next ? recs[phys(q + 1)] : 0ull;
-        const bool run_end = !has_next || (u32)rn != key;
+        const u32 rnh = (KEY64 && has_next) ? sm.ext[phys(q + 1)] : 0u;
+        const bool run_end = !has_next || ((u64)(u32)rn | ((u64)rnh << 32)) != key;
         const bool admissible = a + key >= thr;
         if (run_end && admissible) {
-            const u64 w = P * (u64)key + W0 - S;
+            const u64 w = P * key + W0 - S;
             if (w < bw) { bw = w; bq = (u32)q; bk = key; }
         }
         r = rn;
+        rh = rnh;
     }
     // block arg-min over (wait, position): smaller wait, then earlier position
 #pragma unroll
     for (int d = WAVE / 2; d > 0; d >>= 1) {
         const u64 ow = __shfl_xor(bw, d, WAVE);
         const u32 oq = __shfl_xor(bq, d, WAVE);
-        const u32 ok = __shfl_xor(bk, d, WAVE);
+        const u64 ok = __shfl_xor(bk, d, WAVE);
         if (ow < bw || (ow == bw && oq < bq)) { bw = ow; bq = oq; bk = ok; }
     }
     constexpr int NW = NT / WAVE;
     const int lane = tid & (WAVE - 1), wave = tid >> 6;
-    if (lane == 0) { red[wave] = bw; red[NW + wave] = ((u64)bq << 32) | bk; }
+    if (lane == 0) { red[wave] = bw; red[NW + wave] = bq; red[2 * NW + wave] = bk; }
     __syncthreads();
     bw = red[0];
-    u64 bqk = red[NW];
+    bq = (u32)red[NW];
+    bk = red[2 * NW];
 #pragma unroll
     for (int w = 1; w < NW; ++w) {
-        const u64 ow = red[w], oqk = red[NW + w];
-        if (ow < bw || (ow == bw && (u32)(oqk >> 32) < (u32)(bqk >> 32))) { bw = ow; bqk = oqk; }
+        const u64 ow = red[w];
+        const u32 oq = (u32)red[NW + w];
+        if (ow < bw || (ow == bw && oq < bq)) { bw = ow; bq = oq; bk = red[2 * NW + w]; }
     }
     __syncthreads();
     best_wait = bw;
-    best_key = (u32)bqk;
+    best_key = bk;
 }
 
 // Sentinels behind the last record, so that whole rounds of 64 can be sorted.
@@ -218,7 +228,15 @@ __device__ __forceinline__ void fill_sentinels(u64* recs, int total, int items)
     for (int q = total + threadIdx.x; q < NT * items; q += NT) recs[phys(q)] = 0x00000000ffffffffull;
 }
 
-// zl_delta for a value interval [a, el] (el - a < 2^32) of the rows in `rw`:
+// The same for the plane of upper key halves.
+template <int NT>
+__device__ __forceinline__ void fill_sentinels_hi(u32* ext, int total, int items)
+{
+    for (int q = total + threadIdx.x; q < NT * items; q += NT) ext[phys(q)] = 0xffffffffu;
+}
+
+// zl_delta for a value interval [a, el] (el - a < 2^32, or any width with KEY64: the upper
+// halves of the keys then go to the third plane) of the rows in `rw`:
 // gathers every row's segment into records (key = value - a, delta = value -
 // the row's previous value, or value - a for a row's very first entry) in
 // slots [0, total).  At most `cap` records are stored; the true total is
@@ -226,10 +244,11 @@ __device__ __forceinline__ void fill_sentinels(u64* recs, int total, int items)
 // of row p before the interval).  Rows are taken NT at a time: a block scan of
 // the segment lengths gives every row its first slot, then consecutive threads
 // take consecutive slots, so reads within a segment coalesce.
-template <int NT, bool WIDE, bool PAD>
+template <int NT, bool WIDE, bool PAD, bool KEY64 = false>
 __device__ __forceinline__ int zl_delta(const Smem& sm, const Rows& rw, u64 a, u64 el, bool lx, bool rx,
                                         int cap, u64& w0, int& bad)
 {
+    static_assert(WIDE || !KEY64, "64-bit keys go with the three-plane layout");
     const int tid = threadIdx.x;
     u32* rowoff = sm.cnt;
     u32* rowlo = sm.cnt + NT;
@@ -268,6 +287,7 @@ __device__ __forceinline__ int zl_delta(const Smem& sm, const Rows& rw, u64 a, u
             const int slot = PAD ? phys(total + e) : total + e;
             sm.recs[slot] = (u64)(u32)(rel - a) | (dl << 32);
             if (WIDE) sm.dhi[slot] = (u32)(dl >> 32);
+            if (KEY64) sm.ext[slot] = (u32)((rel - a) >> 32);
         }
         total += (int)chunk;
         __syncthreads();

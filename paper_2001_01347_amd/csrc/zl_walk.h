@@ -20,12 +20,13 @@ __device__ __forceinline__ u32 count_interval(const Smem& sm, const Rows& rw, u6
 
 // Search one value interval [A, Elast] of the rows in `rw`: the general form of
 // zl_delta -> zl_sort -> zl_scan -> zl_argmin.  Normally the interval is at
-// most 2^32 wide and holds at most `cap` entries and is handled in one go.
+// most 2^32 wide (any width with KEY64: 64-bit keys, their upper halves in a third
+// plane) and holds at most `cap` entries and is handled in one go.
 // Otherwise it is walked in pieces that do fit, cut by bisection on the value;
 // a single value that alone occurs more than `cap` times is one candidate and
 // is evaluated directly from the rows.  (bw, bb) is updated with the first
 // minimum found: smaller wait, then smaller barrier (relative to base).
-template <int NT, int ITEMS, bool WIDE>
+template <int NT, int ITEMS, bool WIDE, bool KEY64 = false>
 __device__ __forceinline__ void zl_window(const Smem& sm, const Rows& rw, u64 thr, u64 A, u64 Elast,
                                           u64& bw, u64& bb, int& bad)
 {
@@ -36,9 +37,9 @@ __device__ __forceinline__ void zl_window(const Smem& sm, const Rows& rw, u64 th
     for (;;) {
         u64 el = Elast;
         bool rx = true;
-        if (el - a > 0xffffffffull) { el = a + 0xffffffffull; rx = false; }
+        if (!KEY64 && el - a > 0xffffffffull) { el = a + 0xffffffffull; rx = false; }
         u64 w0 = 0;
-        int total = zl_delta<NT, WIDE, true>(sm, rw, a, el, lx, rx, CAPW, w0, bad);
+        int total = zl_delta<NT, WIDE, true, KEY64>(sm, rw, a, el, lx, rx, CAPW, w0, bad);
         bool single = false;
         if (total > CAPW) {
             if (count_interval<NT>(sm, rw, a, a, lx) > (u32)CAPW) {
@@ -52,7 +53,7 @@ __device__ __forceinline__ void zl_window(const Smem& sm, const Rows& rw, u64 th
                 }
                 el = l;
                 w0 = 0;
-                total = zl_delta<NT, WIDE, true>(sm, rw, a, el, lx, false, CAPW, w0, bad);
+                total = zl_delta<NT, WIDE, true, KEY64>(sm, rw, a, el, lx, false, CAPW, w0, bad);
             }
             rx = false;
         }
@@ -71,11 +72,11 @@ __device__ __forceinline__ void zl_window(const Smem& sm, const Rows& rw, u64 th
         } else if (total > 0) {
             const int items = (total + NT - 1) / NT;
             fill_sentinels<NT>(sm.recs, total, items);
+            if (KEY64) fill_sentinels_hi<NT>(sm.ext, total, items);
             const u64 W0 = block_reduce<u64, NT>(w0, sm.red, OpAdd());   // also orders the record writes
-            zl_sort<NT, ITEMS, WIDE>(sm, items, bit_length(el - a));
-            u64 w;
-            u32 key;
-            zl_scan_argmin<NT, WIDE>(sm, items, total, a, thr, (u64)rw.P, W0, w, key);
+            zl_sort<NT, ITEMS, WIDE, KEY64, KEY64>(sm, items, bit_length(el - a));
+            u64 w, key;
+            zl_scan_argmin<NT, WIDE, KEY64>(sm, items, total, a, thr, (u64)rw.P, W0, w, key);
             if (w != U64_MAX && (w < bw || (w == bw && a + key < bb))) { bw = w; bb = a + key; }
         }
         if (rx) break;
