@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 # this program (their summaries, with the commands, are under profiles/), each scaled by what the same counter
 # reads for the plain copy kernel of known size (FETCH_SIZE x 2048 B, WRITE_SIZE x 1024 B per count).  They
 # hold only for the kernel sources they were taken from: `traffic` is null once those have changed.
-COUNTED_SOURCES_SHA256 = "1e4dbbabacbae53b6e5e6d47544a42d529c380c5ceed3ce04b170bad00226eba"
+COUNTED_SOURCES_SHA256 = "f640d1433a3ca048b255b49967498b2a3e29a7e5831e24f858ac5f67f005f1ce"
 COUNTED_TRAFFIC = {     # (objective, predicted, config) -> (dominant kernel, its bytes, bytes of all kernels of a call)
     ("sum", False, 5): ("zl_window_kernel", 2255091 * 2048 + 1231 * 1024, 7583295744),
     ("sum", False, 3): ("zl_instance_kernel", 1189698 * 2048 + 5654 * 1024, 2454008736),

@@ -38,7 +38,7 @@ struct InstInfo {
     u32 nb;      // number of fine bins, bin(range) + 1
     u32 nwin;    // number of windows (set by zl_plan)
     u32 flags;   // EBSP_STATUS_* bits found so far
-    u32 pad_;
+    u32 wide_steps; // nonzero: some row has two neighbouring entries 2^32 or more apart (set by zl_partition)
 };
 
 struct Partial {  // best candidate of one window

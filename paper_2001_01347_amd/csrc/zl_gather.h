@@ -98,11 +98,13 @@ __device__ __forceinline__ void gather_batch(const u64* recs, const char* bytes,
 // row's very last entry too (stored rows only: the mark shares its bit with the row number).
 constexpr u64 LAST_OF_ROW = 1ull << 34;
 template <int NT, class CT, bool PRED, bool WITH_LAST>
-__device__ __forceinline__ int zl_place_rows(const Smem& sm, const Rows& rw, u32 start, int cap,
+__device__ __forceinline__ int zl_place_rows(const Smem& sm, const Rows& rw, u64 start64, int cap,
                                              const u32 (&lo0)[ROWS_PER_THREAD<NT>], const u32 (&hi0)[ROWS_PER_THREAD<NT>],
                                              u64& before_sum, u32& before_max)
 {
     static_assert(!(PRED && WITH_LAST), "the last-of-row mark is for stored rows");
+    const u32 start = (u32)start64;                          // low word of the window's first value (absolute)
+    const bool wide = rw.wide;                               // the instance's value spread needs more than 32 bits
     const int tid = threadIdx.x;
     u64* recs = sm.recs;
     const char* bytes = (const char*)rw.inst;
@@ -129,7 +131,9 @@ __device__ __forceinline__ int zl_place_rows(const Smem& sm, const Rows& rw, u32
             before[c] = start;
             if (p < rw.P && lo[c] == hi[c] && lo[c] > 0) {
                 if (PRED) { const uint2 fs = rw.par[p]; before[c] = fs.x + (lo[c] - 1u) * fs.y; }
-                else before[c] = *(const u32*)(bytes + (((u32)p * (u32)rw.R + lo[c] - 1u) << 3));
+                else if (!wide) before[c] = *(const u32*)(bytes + (((u32)p * (u32)rw.R + lo[c] - 1u) << 3));
+                else       // a worker that finished long ago may stand 2^32 or more before the window: the whole value
+                    before_sum += start64 - (u64)*(const i64*)(bytes + (((u32)p * (u32)rw.R + lo[c] - 1u) << 3));
             }
         }
         u32 round;
@@ -161,10 +165,10 @@ __device__ __forceinline__ int zl_place_rows(const Smem& sm, const Rows& rw, u32
             }
         }
 #pragma unroll
-        for (int c = 0; c < RPT; ++c) {                      // below 2^32 like every relative value
+        for (int c = 0; c < RPT; ++c) {                      // below 2^32 in an instance whose value spread is (the others: above)
             const u32 gone = start - before[c];
             before_sum += (u64)gone;
-            before_max = gone > before_max ? gone : before_max;
+            before_max = gone > before_max ? gone : before_max;   // (only searches of such instances use the maximum)
         }
     }
     __syncthreads();
@@ -180,7 +184,7 @@ __device__ __forceinline__ int zl_delta_rows(const Smem& sm, const Rows& rw, u64
     const char* bytes = (const char*)rw.inst;
     const u32 start = (u32)(rw.base + a);                    // low word of the window's first value
     u32 unused = 0;
-    const int total = zl_place_rows<NT, CT, PRED, false>(sm, rw, start, cap, lo0, hi0, w0, unused);
+    const int total = zl_place_rows<NT, CT, PRED, false>(sm, rw, rw.base + a, cap, lo0, hi0, w0, unused);
     if (total > cap) return total;
 
     constexpr int G0 = ITEMS < GATHER_BATCH ? ITEMS : GATHER_BATCH;

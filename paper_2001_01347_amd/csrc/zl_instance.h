@@ -201,7 +201,7 @@ __global__ __launch_bounds__(NT) void zl_instance_general_kernel(
             Rows rw;
             rw.inst = inst; rw.le = le ? le + (i64)b * P : nullptr; rw.iv = iv ? iv + (i64)b * P : nullptr;
             rw.P = P; rw.R = R; rw.base = (u64)base;
-            rw.cr = nullptr; rw.narrow = false; rw.stride = 0; rw.k0 = rw.k1 = 0;
+            rw.cr = nullptr; rw.narrow = false; rw.wide = false; rw.stride = 0; rw.k0 = rw.k1 = 0;
             int bad = 0;
             u64 best_wait = U64_MAX, best_rel = 0;
             // the 64-bit-delta form serves every deferred instance, narrow ones included

@@ -52,7 +52,7 @@ __global__ __launch_bounds__(NT) void zl_bounds_kernel(
     ii.thr = (u64)first_max - (u64)base;
     ii.nwin = 0;
     ii.flags = backwards ? (u32)EBSP_STATUS_UNSORTED : 0u;
-    ii.pad_ = 0;
+    ii.wide_steps = 0;
     if (summed && ii.range > (u64)INT64_MAX / (u64)P) ii.flags |= EBSP_STATUS_OVERFLOW;    // P waits are summed
     if (backwards) ii.range = 0;                      // nothing downstream may rely on such rows
     const int bl = bit_length(ii.range);
@@ -128,7 +128,7 @@ __global__ __launch_bounds__(NT) void zl_bounds_kernel(
 template <int NT, class CT>
 __global__ __launch_bounds__(NT) void zl_partition_kernel(
     const i64* __restrict__ ts, i64 nrows, int P, int R,
-    const InstInfo* __restrict__ info, const SegEntry* __restrict__ segtab, CT* __restrict__ cross, int stride,
+    InstInfo* info, const SegEntry* __restrict__ segtab, CT* __restrict__ cross, int stride,
     int* __restrict__ status)
 {
     __shared__ SegEntry tabs[NT / WAVE][SEGS];         // each wave's copy of its instance's fine-bin map
@@ -149,7 +149,8 @@ __global__ __launch_bounds__(NT) void zl_partition_kernel(
 
     int carry = -1;                        // bin of the element before lane 0's
     i64 carry_t = INT64_MIN;               // and its value
-    bool bad = false;
+    bool bad = false, far = false;         // far: two neighbours 2^32 or more apart (the window kernels' 32-bit deltas)
+    const bool wide = (ii.range >> 32) != 0;          // only then can there be such neighbours
     for (u32 i0 = 0; i0 < (u32)R; i0 += WAVE) {       // unsigned: R may be within a wave's width of 2^31
         const u32 i = i0 + (u32)lane;
         int bin = -1;
@@ -159,12 +160,14 @@ __global__ __launch_bounds__(NT) void zl_partition_kernel(
         i64 pt = __shfl_up(t, 1, WAVE);
         if (lane == 0) { pb = carry; pt = carry_t; }
         bad |= t < pt;                     // the only place the multi-window path checks every pair of neighbours
+        if (wide) far |= i > 0 && i < (u32)R && (((u64)t - (u64)pt) >> 32) != 0;
         if (i < (u32)R)
             for (int k = pb + 1; k <= bin; ++k) out[k] = (CT)i;
         carry = __shfl(bin, WAVE - 1, WAVE);
         carry_t = __shfl(t, WAVE - 1, WAVE);
     }
     if (__any(bad) && lane == 0 && status) atomicOr(status + b, (int)EBSP_STATUS_UNSORTED);
+    if (__any(far) && lane == 0) atomicOr(&info[b].wide_steps, 1u);
     const int last_bin = (int)fine_bin((u64)row[R - 1] - base, ii, tab);
     for (int k = last_bin + 1 + lane; k <= (int)ii.nb; k += WAVE) out[k] = (CT)R;
 }
@@ -179,7 +182,7 @@ constexpr int PART_MAX_STRIDE = 8200;
 template <class CT>
 __global__ __launch_bounds__(PART_ROWS * WAVE) void zl_partition_sum_kernel(
     const i64* __restrict__ ts, int P, int R, int groups,
-    const InstInfo* __restrict__ info, const SegEntry* __restrict__ segtab, CT* __restrict__ cross, int stride,
+    InstInfo* info, const SegEntry* __restrict__ segtab, CT* __restrict__ cross, int stride,
     u32* __restrict__ part, int* __restrict__ status)
 {
     constexpr int NT = PART_ROWS * WAVE;
@@ -200,7 +203,8 @@ __global__ __launch_bounds__(PART_ROWS * WAVE) void zl_partition_sum_kernel(
         const u64 base = (u64)ii.base;
         int carry = -1;                        // bin of the element before lane 0's
         i64 carry_t = INT64_MIN;               // and its value
-        bool bad = false;
+        bool bad = false, far = false;         // far: two neighbours 2^32 or more apart (the window kernels' 32-bit deltas)
+        const bool wide = (ii.range >> 32) != 0;      // only then can there be such neighbours
         for (u32 i0 = 0; i0 < (u32)R; i0 += WAVE) {   // unsigned: R may be within a wave's width of 2^31
             const u32 i = i0 + (u32)lane;
             int bin = -1;
@@ -210,12 +214,14 @@ __global__ __launch_bounds__(PART_ROWS * WAVE) void zl_partition_sum_kernel(
             i64 pt = __shfl_up(t, 1, WAVE);
             if (lane == 0) { pb = carry; pt = carry_t; }
             bad |= t < pt;                     // the only place the multi-window path checks every pair of neighbours
+            if (wide) far |= i > 0 && i < (u32)R && (((u64)t - (u64)pt) >> 32) != 0;
             if (i < (u32)R)
                 for (int k = pb + 1; k <= bin; ++k) { out[k] = (CT)i; atomicAdd(&sums[k], i); }
             carry = __shfl(bin, WAVE - 1, WAVE);
             carry_t = __shfl(t, WAVE - 1, WAVE);
         }
         if (__any(bad) && lane == 0 && status) atomicOr(status + b, (int)EBSP_STATUS_UNSORTED);
+        if (__any(far) && lane == 0) atomicOr(&info[b].wide_steps, 1u);
         const int last_bin = (int)fine_bin((u64)row[R - 1] - base, ii, tab);
         for (int k = last_bin + 1 + lane; k <= (int)ii.nb; k += WAVE) { out[k] = (CT)R; atomicAdd(&sums[k], (u32)R); }
     }

@@ -330,7 +330,7 @@ __device__ __forceinline__ bool zl_range_bucket_search(const Smem& sm, const Row
     const u32 start = (u32)(rw.base + a);                   // low word of the window's first value
     u64 unused = 0;
     u32 absent = 0;
-    const int total = zl_place_rows<NT, CT, false, true>(sm, rw, start, H::CAP, lo, hi, unused, absent);
+    const int total = zl_place_rows<NT, CT, false, true>(sm, rw, rw.base + a, H::CAP, lo, hi, unused, absent);
     best_d = U64_MAX;
     best_key = 0;
     if (total > H::CAP - 2 * RANGE_LIST_CAP) return false;
@@ -581,7 +581,7 @@ __global__ __launch_bounds__(NT) void zl_range_instance_kernel(
     int bad = 0;
     Rows rw;
     rw.inst = inst; rw.le = nullptr; rw.iv = nullptr; rw.P = P; rw.R = R; rw.base = (u64)base;
-    rw.cr = nullptr; rw.narrow = false; rw.stride = 0; rw.k0 = rw.k1 = 0;
+    rw.cr = nullptr; rw.narrow = false; rw.wide = false; rw.stride = 0; rw.k0 = rw.k1 = 0;
     if (range > RANGE_PIECE_MAX) zl_range_window<NT, ITEMS, true>(sm, rw, thr, 0ull, range, best_d, best_rel, bad);
     else zl_range_window<NT, ITEMS, false>(sm, rw, thr, 0ull, range, best_d, best_rel, bad);
     if (__syncthreads_or(bad)) flags |= EBSP_STATUS_UNSORTED;

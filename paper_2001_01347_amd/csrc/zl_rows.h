@@ -16,6 +16,7 @@ struct Rows {
     u64 base;
     const void* cr;     // crossing indices of this instance (u16 if narrow, else u32), or nullptr for whole rows
     bool narrow;
+    bool wide;          // fast window path: the instance's value spread is 2^32 or more
     int stride;
     u32 k0, k1;
 

@@ -36,6 +36,7 @@ __device__ __forceinline__ WinPos locate_window(i64 b, int j, const InstInfo& ii
     w.rw.cr = narrow ? (const void*)((const unsigned short*)cross + (b * (i64)P) * stride)
                      : (const void*)((const u32*)cross + (b * (i64)P) * stride);
     w.rw.narrow = narrow;
+    w.rw.wide = false;          // (only the fast window search looks at it)
     w.rw.stride = stride;
     w.rw.k0 = ws[j];
     w.rw.k1 = ws[j + 1];
@@ -66,7 +67,7 @@ __device__ __forceinline__ void window_search(const Smem& sm, const Rows& rw, co
     r.wait = U64_MAX;
     r.brel = 0;
     if (wv.Elast >= wv.A) {
-        bool defer = !hot;
+        bool defer = !hot || ((wv.Elast - wv.A) >> 32) != 0;   // keys are 32 bits wide
         if (!defer) {
             u32 key[ITEMS], dl[ITEMS];
             u64 w0 = 0;
@@ -145,7 +146,9 @@ __device__ __forceinline__ void window_pairs(
     const int jend = j0 + WINDOWS_PER_BLOCK < (int)ii.nwin ? j0 + WINDOWS_PER_BLOCK : (int)ii.nwin;
     if (j0 >= jend) return;
     Partial* out = partial + b * (i64)max_win;
-    const bool hot = !(ii.range >> 32) && (u64)P * (u64)R < HOT_MAX_ENTRIES;
+    // the fast search holds keys relative to its window and deltas between neighbours in 32 bits: every
+    // instance whose spread fits, and (stored rows) any other whose rows step by less than 2^32
+    const bool hot = (!(ii.range >> 32) || (!PRED && ii.wide_steps == 0)) && (u64)P * (u64)R < HOT_MAX_ENTRIES;
     Rows rw;
     rw.inst = PRED ? nullptr : ts + b * (i64)P * R;
     rw.le = nullptr; rw.iv = nullptr;
@@ -153,6 +156,7 @@ __device__ __forceinline__ void window_pairs(
     rw.P = P; rw.R = R; rw.base = (u64)ii.base;
     rw.cr = (const void*)(cross + (b * (i64)P) * stride);
     rw.narrow = sizeof(CT) == 2;
+    rw.wide = (ii.range >> 32) != 0;
     rw.stride = stride;
 #pragma unroll
     for (int i = 0; i <= W; ++i)                             // stale scratch cannot index outside a row of cross
