@@ -414,3 +414,18 @@ def test_status_may_be_null(zl, oracle):
         assert lib.ebsp_simulate_supersteps(le.data_ptr(), iv.data_ptr(), 0, 1, n, cfg.P, cfg.R, bar.data_ptr(), it.data_ptr(),
                                             val.data_ptr(), None, ws.data_ptr(), need, stream) == 0
         assert same(want)                                  # one superstep is one predicted search
+
+
+@pytest.mark.parametrize("P,R", [(256, 240), (1024, 240)])
+def test_nanosecond_timestamps_at_the_papers_scales(zl, oracle, P, R):
+    # iteration times of 80-120 ms in nanoseconds: the instance's spread passes 2^32, its windows and the
+    # steps of its rows do not, so the fast window search takes all but the last windows, where only the
+    # slowest workers are left and a window is itself wider than 2^32 ns
+    rng = np.random.default_rng(P)
+    B = 6
+    mean = rng.integers(80_000_000, 120_000_000, size=(B, P, 1))
+    steps = (mean * (1.0 + 0.05 * rng.standard_normal((B, P, R)))).astype(np.int64)
+    ts = np.cumsum(steps, axis=2) + rng.integers(0, 100_000_000, size=(B, P, 1)) + EPOCH * 1000
+    assert ((ts.max(axis=(1, 2)) - ts.min(axis=(1, 2))) >> 32).all()
+    assert_same(zl, oracle, ts, f"ns, P={P} R={R}")
+    all_three(zl, oracle, ts[:2], f"ns, P={P} R={R}, both objectives")
