@@ -33,10 +33,10 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 # hold only for the kernel sources they were taken from: `traffic` is null once those have changed.
 COUNTED_SOURCES_SHA256 = "f640d1433a3ca048b255b49967498b2a3e29a7e5831e24f858ac5f67f005f1ce"
 COUNTED_TRAFFIC = {     # (objective, predicted, config) -> (dominant kernel, its bytes, bytes of all kernels of a call)
-    ("sum", False, 5): ("zl_window_kernel", 2255091 * 2048 + 1231 * 1024, 7583295744),
-    ("sum", False, 3): ("zl_instance_kernel", 1189698 * 2048 + 5654 * 1024, 2454008736),
-    ("range", False, 5): ("zl_range_fast_kernel", 2234303 * 2048 + 1680 * 1024, 7550361824),
-    ("sum", True, 5): ("zl_window_kernel", 267418 * 2048 + 560 * 1024, 1175819243),
+    ("sum", False, 5): ("zl_window_kernel", 2255624 * 2048 + 1231 * 1024, 7584808405),
+    ("sum", False, 3): ("zl_instance_kernel", 1189523 * 2048 + 5654 * 1024, 2458897803),
+    ("range", False, 5): ("zl_range_fast_kernel", 2232300 * 2048 + 1677 * 1024, 7546093472),
+    ("sum", True, 5): ("zl_window_kernel", 267418 * 2048 + 560 * 1024, 1176883819),
 }
 
 
