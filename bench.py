@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 # this program (their summaries, with the commands, are under profiles/), each scaled by what the same counter
 # reads for the plain copy kernel of known size (FETCH_SIZE x 2048 B, WRITE_SIZE x 1024 B per count).  They
 # hold only for the kernel sources they were taken from: `traffic` is null once those have changed.
-COUNTED_SOURCES_SHA256 = "f640d1433a3ca048b255b49967498b2a3e29a7e5831e24f858ac5f67f005f1ce"
+COUNTED_SOURCES_SHA256 = "3107a7598c595dc6acddd7b342400c6ac553097eb3f0e7e0ffcb4d21c5564962"
 COUNTED_TRAFFIC = {     # (objective, predicted, config) -> (dominant kernel, its bytes, bytes of all kernels of a call)
     ("sum", False, 5): ("zl_window_kernel", 2255624 * 2048 + 1231 * 1024, 7584808405),
     ("sum", False, 3): ("zl_instance_kernel", 1189523 * 2048 + 5654 * 1024, 2458897803),
@@ -79,9 +79,10 @@ def algorithmic_bytes(kernel: str, B: int, P: int, R: int, bins: int, windows: i
         return 8.0 * n + windows * (2.0 * cw * P + 16.0)
     if kernel == "zl_range_instance_kernel":
         return 8.0 * n + B * (16.0 + 4.0 * P)
-    if kernel == "zl_finish_kernel":        # window results, log2(R) probes per row, outputs
-        import math
-        return 16.0 * windows + B * P * (64.0 * max(1, math.ceil(math.log2(max(R, 2)))) + 4.0) + 16.0 * B
+    if kernel == "zl_finish_kernel":        # window results; per row its crossing indices at the barrier's bin and two probes
+        import math                         # (predicted rows: nothing is probed), outputs
+        probes = 0.0 if predicted else 64.0 * 3.0
+        return 16.0 * windows + B * P * (probes + 4.0) + 16.0 * B
     return 0.0
 
 

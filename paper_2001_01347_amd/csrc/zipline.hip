@@ -332,7 +332,8 @@ int run_batch(const i64* ts, const i64* le, const i64* iv, i64 B, int P, int R,
                dim3((unsigned)(total_win < GENERAL_GRID ? total_win : GENERAL_GRID)), dim3(LARGE_NT),
                ts, le, iv, B, P, R, info, cross, pl.narrow, pl.stride, winstart, winval, pl.max_win, partial, status);
     LAUNCH(K_FINISH, (zl_finish_kernel<256>), dim3((unsigned)(pblocks * B)), dim3(256),
-           ts, le, iv, P, R, info, partial, pl.max_win, barrier, iters, wait);
+           ts, le, iv, P, R, info, (const SegEntry*)(wsp + pl.off_seg), (const void*)cross, pl.narrow, pl.stride,
+           partial, pl.max_win, barrier, iters, wait);
     return EBSP_OK;
 }
 
@@ -409,7 +410,8 @@ int run_range_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters
         LAUNCH(K_RANGE_WINDOW, (zl_range_window_kernel<LARGE_NT, LARGE_ITEMS>), dim3(4 * GENERAL_GRID), dim3(LARGE_NT),
                ts, B, P, R, info, cross, pl.narrow, pl.stride, winstart, winval, pl.max_win, partial, status);
     LAUNCH(K_FINISH, (zl_finish_kernel<256>), dim3((unsigned)(pblocks * B)), dim3(256),
-           ts, nullptr, nullptr, P, R, info, partial, pl.max_win, barrier, iters, dmin);
+           ts, nullptr, nullptr, P, R, info, (const SegEntry*)(wsp + pl.off_seg), (const void*)cross, pl.narrow, pl.stride,
+           partial, pl.max_win, barrier, iters, dmin);
     return EBSP_OK;
 }
 

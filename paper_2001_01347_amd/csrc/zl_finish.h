@@ -6,11 +6,14 @@
 namespace {
 
 // zl_iters for the multi-window path: reduce the instance's window results
-// (first minimum: smaller wait, then earlier barrier), then count iterations.
+// (first minimum: smaller wait, then earlier barrier), then count iterations.  For stored
+// rows the crossing indices of the barrier's fine bin bracket the count, so the binary
+// search runs over the row's few entries of that bin instead of the whole row.
 template <int NT>
 __global__ __launch_bounds__(NT) void zl_finish_kernel(
     const i64* __restrict__ ts, const i64* __restrict__ le, const i64* __restrict__ iv, int P, int R,
-    const InstInfo* __restrict__ info, const Partial* __restrict__ partial, int max_win,
+    const InstInfo* __restrict__ info, const SegEntry* __restrict__ segtab, const void* __restrict__ cross, bool narrow,
+    int stride, const Partial* __restrict__ partial, int max_win,
     i64* __restrict__ barrier, int* __restrict__ iters, i64* __restrict__ wait)
 {
     __shared__ u64 red[2 * (NT / WAVE)];
@@ -39,9 +42,27 @@ __global__ __launch_bounds__(NT) void zl_finish_kernel(
     const i64 bar = (i64)((u64)ii.base + bb);
     if (pblk == 0 && tid == 0) { barrier[b] = bar; wait[b] = (i64)bw; }
     const int p = pblk * NT + tid;
-    if (p < P)
-        iters[b * (i64)P + p] = zl_iters_of(ts ? ts + b * (i64)P * R : nullptr, le ? le + b * (i64)P : nullptr,
-                                            iv ? iv + b * (i64)P : nullptr, p, R, bar);
+    if (p >= P) return;
+    if (!ts) {
+        iters[b * (i64)P + p] = zl_iters_of(nullptr, le + b * (i64)P, iv + b * (i64)P, p, R, bar);
+        return;
+    }
+    Rows rw;                                     // only for the index range of row p inside the barrier's fine bin
+    rw.R = R;
+    rw.cr = narrow ? (const void*)((const unsigned short*)cross + (b * (i64)P) * stride)
+                   : (const void*)((const u32*)cross + (b * (i64)P) * stride);
+    rw.narrow = narrow;
+    rw.stride = stride;
+    rw.k0 = fine_bin(bb, ii, segtab + b * (i64)SEGS);
+    rw.k1 = rw.k0 + 1;                           // k0 < nb, and a row of cross holds nb + 1 indices
+    u32 lo, hi;
+    rw.range(p, lo, hi);                         // entries before lo lie in lower bins (<= barrier), from hi on in higher ones
+    const i64* __restrict__ row = ts + (b * (i64)P + p) * (i64)R;
+    while (lo < hi) {
+        const u32 m = (lo + hi) >> 1;
+        if (row[m] <= bar) lo = m + 1; else hi = m;
+    }
+    iters[b * (i64)P + p] = (int)lo;
 }
 
 // Superstep simulation: after a barrier (and the synchronisation, which takes sync_cost) every
