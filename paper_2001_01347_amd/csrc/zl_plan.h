@@ -332,6 +332,7 @@ __global__ __launch_bounds__(NT) void zl_plan_kernel(
     __shared__ u32 found_all, slice_cnt, slice_last;
     __shared__ SegEntry tab[SEGS];         // the instance's fine-bin map
     __shared__ u16 hop[2][PLAN_SLICE + 1];
+    __shared__ u64 vstart[PLAN_SLICE + 1]; // wide instances: the first value of bin k0 + i (range + 1 for bin nb)
     const int tid = threadIdx.x;
     const i64 b = blockIdx.x;
     const u32* bel = below + b * (i64)stride;
@@ -346,7 +347,13 @@ __global__ __launch_bounds__(NT) void zl_plan_kernel(
     // jump[jump[s0]], ...  Thread r finds the r-th of them by squaring the jump table: level l applies
     // jump^(2^l) to the ranks with bit l set.  The window that is open at the end of a slice goes on
     // into the next one, whose s0 is the first bin that no longer fits it.
+    // In an instance whose value spread is 2^32 or more a window also ends where it would get wider
+    // than that: the fast window search holds keys relative to the window's first value in 32 bits.
+    const bool wide = (ii.range >> 32) != 0;
+    constexpr u64 SPAN_MAX = 1ull << 32;   // first value of the bin behind a window - first value of the window
+    if (tid < SEGS) tab[tid] = segtab[b * (i64)SEGS + tid];
     u32 found = 0, open_key = 0;           // windows so far; keys under the first bin of the window that is open
+    u64 open_start = 0;                    // wide: that bin's first value
     bool have_open = false;
     u16* jump = hop[0];
     u16* other = hop[1];
@@ -356,12 +363,20 @@ __global__ __launch_bounds__(NT) void zl_plan_kernel(
 #pragma unroll 4
         for (int i = tid; i <= cnt; i += NT) ends[i] = bel[k0 + i];
         if (tid == 0) { slice_cnt = 0; slice_last = 0; }
-        __syncthreads();
+        __syncthreads();                                  // (the first time round also: tab is there)
+        if (wide) {
+            for (int i = tid; i <= cnt; i += NT)
+                vstart[i] = k0 + i < nb ? fine_bin_start((u32)(k0 + i), ii, tab) : ii.range + 1;
+            __syncthreads();
+        }
         int s0 = 0;
         if (have_open) {                                  // first bin whose end lies more than `fill` past the open window's start
             const u32 limit = open_key + fill;            // no overflow: fill and the key count are both below 2^31
             int lo = 0, hi = cnt;
-            while (lo < hi) { const int m = (lo + hi) >> 1; if (ends[m + 1] > limit) hi = m; else lo = m + 1; }
+            while (lo < hi) {
+                const int m = (lo + hi) >> 1;
+                if (ends[m + 1] > limit || (wide && vstart[m + 1] - open_start > SPAN_MAX)) hi = m; else lo = m + 1;
+            }
             s0 = lo;
         }
         if (s0 >= cnt) continue;                          // the same for every thread: the open window takes the whole slice
@@ -369,7 +384,11 @@ __global__ __launch_bounds__(NT) void zl_plan_kernel(
             int lo = k + 1, hi = cnt;                     // first bin j > k whose end lies more than `fill` past the start of bin k
             if (k < cnt) {
                 const u32 limit = ends[k] + fill;
-                while (lo < hi) { const int m = (lo + hi) >> 1; if (ends[m + 1] > limit) hi = m; else lo = m + 1; }
+                const u64 from = wide ? vstart[k] : 0ull;
+                while (lo < hi) {
+                    const int m = (lo + hi) >> 1;
+                    if (ends[m + 1] > limit || (wide && vstart[m + 1] - from > SPAN_MAX)) hi = m; else lo = m + 1;
+                }
             } else lo = cnt;
             jump[k] = (u16)lo;
         }
@@ -402,6 +421,7 @@ __global__ __launch_bounds__(NT) void zl_plan_kernel(
             if (pos[q] < (u32)cnt && (u32)(q * NT + tid) + 1 == slice_cnt) slice_last = pos[q];   // the slice's last window stays open
         __syncthreads();
         open_key = ends[slice_last];
+        if (wide) open_start = vstart[slice_last];
         have_open = true;
         found += slice_cnt;
     }
@@ -411,7 +431,6 @@ __global__ __launch_bounds__(NT) void zl_plan_kernel(
         info[b].nwin = nwin;
         found_all = nwin;
     }
-    if (tid < SEGS) tab[tid] = segtab[b * (i64)SEGS + tid];
     __threadfence_block();
     __syncthreads();
     const u32 nwin = found_all;
