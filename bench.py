@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 # this program (their summaries, with the commands, are under profiles/), each scaled by what the same counter
 # reads for the plain copy kernel of known size (FETCH_SIZE x 2048 B, WRITE_SIZE x 1024 B per count).  They
 # hold only for the kernel sources they were taken from: `traffic` is null once those have changed.
-COUNTED_SOURCES_SHA256 = "8626dc537f834ade0f602fbacd6e7b866fd19e89419c7b2a892d67698815eeb9"
+COUNTED_SOURCES_SHA256 = "f835e57ff9849d4afdfdffc2214efd5caabfed39a751a349f7489bac15061102"
 COUNTED_TRAFFIC = {     # (objective, predicted, config) -> (dominant kernel, its bytes, bytes of all kernels of a call)
     ("sum", False, 5): ("zl_window_kernel", 2256604 * 2048 + 1237 * 1024, 7533185099),
     ("sum", False, 3): ("zl_instance_kernel", 1189523 * 2048 + 5654 * 1024, 2458897803),

@@ -105,7 +105,7 @@ struct Plan {
     int stride;        // bins + 1 crossing indices per row
     int max_win;       // windows per instance <= max_win
     bool narrow;       // crossing indices fit 16 bits
-    size_t off_info, off_seg, off_cross, off_part, off_below, off_winstart, off_winval, off_partial, off_rowpar, bytes;
+    size_t off_info, off_seg, off_cross, off_part, off_below, off_winstart, off_winval, off_partial, off_rowpar, off_wide, bytes;
 };
 
 // single_limit: the most entries one workgroup takes whole on the path the plan is for;
@@ -147,6 +147,7 @@ bool make_plan(i64 B, int P, int R, Plan& pl, int single_limit = SINGLE_MAX, boo
     pl.off_winval = o;   o = align_up(o + (size_t)B * pl.max_win * sizeof(WinVal), 256);
     pl.off_partial = o;  o = align_up(o + (size_t)B * pl.max_win * sizeof(Partial), 256);
     pl.off_rowpar = o;   o = align_up(o + (size_t)B * P * sizeof(uint2), 256);      // predicted rows only
+    pl.off_wide = o;     o = align_up(o + (size_t)B * WIDE_MARKS * sizeof(u32), 256);
     pl.bytes = o;
     return true;
 }
@@ -194,6 +195,7 @@ int plan_windows(const Plan& pl, const i64* ts, const i64* le, const i64* iv, i6
     u32* winstart = (u32*)(wsp + pl.off_winstart);
     WinVal* winval = (WinVal*)(wsp + pl.off_winval);
     uint2* rowpar = pred ? (uint2*)(wsp + pl.off_rowpar) : nullptr;
+    u32* widebin = (u32*)(wsp + pl.off_wide);
     const i64 nrows = B * (i64)P;
     const i64 kblocks = (pl.stride + 255) / 256;
     const i64 widest = pl.part_stored > pl.part_pred ? pl.part_stored : pl.part_pred;
@@ -212,18 +214,18 @@ int plan_windows(const Plan& pl, const i64* ts, const i64* le, const i64* iv, i6
         part_rows = pl.part_stored;
         if (pl.narrow)
             LAUNCH(K_PARTITION, zl_partition_sum_kernel<unsigned short>, dim3((unsigned)(B * part_rows)), dim3(PART_ROWS * WAVE),
-                   ts, P, R, part_rows, info, segtab, (unsigned short*)cross, pl.stride, part, status);
+                   ts, P, R, part_rows, info, widebin, segtab, (unsigned short*)cross, pl.stride, part, status);
         else
             LAUNCH(K_PARTITION, zl_partition_sum_kernel<u32>, dim3((unsigned)(B * part_rows)), dim3(PART_ROWS * WAVE),
-                   ts, P, R, part_rows, info, segtab, (u32*)cross, pl.stride, part, status);
+                   ts, P, R, part_rows, info, widebin, segtab, (u32*)cross, pl.stride, part, status);
     } else {
         part_rows = 0;
         if (pl.narrow)
             LAUNCH(K_PARTITION, (zl_partition_kernel<256, unsigned short>), dim3((unsigned)((nrows + 3) / 4)), dim3(256),
-                   ts, nrows, P, R, info, segtab, (unsigned short*)cross, pl.stride, status);
+                   ts, nrows, P, R, info, widebin, segtab, (unsigned short*)cross, pl.stride, status);
         else
             LAUNCH(K_PARTITION, (zl_partition_kernel<256, u32>), dim3((unsigned)((nrows + 3) / 4)), dim3(256),
-                   ts, nrows, P, R, info, segtab, (u32*)cross, pl.stride, status);
+                   ts, nrows, P, R, info, widebin, segtab, (u32*)cross, pl.stride, status);
     }
     if (part_rows > 0)        // the partial sums are exact counts already: nothing to clamp
         LAUNCH(K_BINCOUNT, zl_bincount_kernel<u32>, dim3((unsigned)(kblocks * B)), dim3(256),
@@ -235,10 +237,10 @@ int plan_windows(const Plan& pl, const i64* ts, const i64* le, const i64* iv, i6
         LAUNCH(K_BINCOUNT, zl_bincount_kernel<u32>, dim3((unsigned)(kblocks * B)), dim3(256),
                (const u32*)cross, P, R, pl.stride, info, below);
     if (pl.bins <= 1024)      // small instances, many of them: small workgroups
-        LAUNCH(K_PLAN, (zl_plan_kernel<256, 1024>), dim3((unsigned)B), dim3(256), info, segtab, below, pl.stride, winstart, winval,
+        LAUNCH(K_PLAN, (zl_plan_kernel<256, 1024>), dim3((unsigned)B), dim3(256), info, segtab, below, pl.stride, widebin, pred, winstart, winval,
                pl.max_win, (u32)pl.fill, (u32)(pl.cap / 8));
     else
-        LAUNCH(K_PLAN, (zl_plan_kernel<1024, 4096>), dim3((unsigned)B), dim3(1024), info, segtab, below, pl.stride, winstart, winval,
+        LAUNCH(K_PLAN, (zl_plan_kernel<1024, 4096>), dim3((unsigned)B), dim3(1024), info, segtab, below, pl.stride, widebin, pred, winstart, winval,
                pl.max_win, (u32)pl.fill, (u32)(pl.cap / 8));
     return EBSP_OK;
 }

@@ -38,8 +38,9 @@ struct InstInfo {
     u32 nb;      // number of fine bins, bin(range) + 1
     u32 nwin;    // number of windows (set by zl_plan)
     u32 flags;   // EBSP_STATUS_* bits found so far
-    u32 wide_steps; // nonzero: some row has two neighbouring entries 2^32 or more apart (set by zl_partition)
+    u32 wide_steps; // how often a row steps by 2^32 or more from one entry to the next (counted by zl_partition)
 };
+constexpr u32 WIDE_MARKS = 15;   // of those steps, as many are remembered per instance by the fine bin they end in
 
 struct Partial {  // best candidate of one window
     u64 wait;     // U64_MAX: the window has no admissible candidate

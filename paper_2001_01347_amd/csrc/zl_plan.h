@@ -128,7 +128,7 @@ __global__ __launch_bounds__(NT) void zl_bounds_kernel(
 template <int NT, class CT>
 __global__ __launch_bounds__(NT) void zl_partition_kernel(
     const i64* __restrict__ ts, i64 nrows, int P, int R,
-    InstInfo* info, const SegEntry* __restrict__ segtab, CT* __restrict__ cross, int stride,
+    InstInfo* info, u32* __restrict__ widebin, const SegEntry* __restrict__ segtab, CT* __restrict__ cross, int stride,
     int* __restrict__ status)
 {
     __shared__ SegEntry tabs[NT / WAVE][SEGS];         // each wave's copy of its instance's fine-bin map
@@ -149,8 +149,10 @@ __global__ __launch_bounds__(NT) void zl_partition_kernel(
 
     int carry = -1;                        // bin of the element before lane 0's
     i64 carry_t = INT64_MIN;               // and its value
-    bool bad = false, far = false;         // far: two neighbours 2^32 or more apart (the window kernels' 32-bit deltas)
-    const bool wide = (ii.range >> 32) != 0;          // only then can there be such neighbours
+    bool bad = false;
+    const bool wide = (ii.range >> 32) != 0;          // only then can two neighbours be 2^32 or more apart
+    int farbin = 0;                                   // the window kernels hold deltas in 32 bits: the bin such a
+    u32 far = 0;                                      // step ends in is remembered (this lane's last one, and how many)
     for (u32 i0 = 0; i0 < (u32)R; i0 += WAVE) {       // unsigned: R may be within a wave's width of 2^31
         const u32 i = i0 + (u32)lane;
         int bin = -1;
@@ -160,14 +162,17 @@ __global__ __launch_bounds__(NT) void zl_partition_kernel(
         i64 pt = __shfl_up(t, 1, WAVE);
         if (lane == 0) { pb = carry; pt = carry_t; }
         bad |= t < pt;                     // the only place the multi-window path checks every pair of neighbours
-        if (wide) far |= i > 0 && i < (u32)R && (((u64)t - (u64)pt) >> 32) != 0;
+        if (wide && i > 0 && i < (u32)R && (((u64)t - (u64)pt) >> 32) != 0) { farbin = bin; ++far; }
         if (i < (u32)R)
             for (int k = pb + 1; k <= bin; ++k) out[k] = (CT)i;
         carry = __shfl(bin, WAVE - 1, WAVE);
         carry_t = __shfl(t, WAVE - 1, WAVE);
     }
     if (__any(bad) && lane == 0 && status) atomicOr(status + b, (int)EBSP_STATUS_UNSORTED);
-    if (__any(far) && lane == 0) atomicOr(&info[b].wide_steps, 1u);
+    if (far) {                                        // (a lane with several such steps: more than the list takes)
+        const u32 slot = atomicAdd(&info[b].wide_steps, far == 1 ? 1u : WIDE_MARKS + 1u);
+        if (far == 1 && slot < WIDE_MARKS) widebin[b * (i64)WIDE_MARKS + slot] = (u32)farbin;
+    }
     const int last_bin = (int)fine_bin((u64)row[R - 1] - base, ii, tab);
     for (int k = last_bin + 1 + lane; k <= (int)ii.nb; k += WAVE) out[k] = (CT)R;
 }
@@ -182,7 +187,7 @@ constexpr int PART_MAX_STRIDE = 8200;
 template <class CT>
 __global__ __launch_bounds__(PART_ROWS * WAVE) void zl_partition_sum_kernel(
     const i64* __restrict__ ts, int P, int R, int groups,
-    InstInfo* info, const SegEntry* __restrict__ segtab, CT* __restrict__ cross, int stride,
+    InstInfo* info, u32* __restrict__ widebin, const SegEntry* __restrict__ segtab, CT* __restrict__ cross, int stride,
     u32* __restrict__ part, int* __restrict__ status)
 {
     constexpr int NT = PART_ROWS * WAVE;
@@ -203,8 +208,10 @@ __global__ __launch_bounds__(PART_ROWS * WAVE) void zl_partition_sum_kernel(
         const u64 base = (u64)ii.base;
         int carry = -1;                        // bin of the element before lane 0's
         i64 carry_t = INT64_MIN;               // and its value
-        bool bad = false, far = false;         // far: two neighbours 2^32 or more apart (the window kernels' 32-bit deltas)
-        const bool wide = (ii.range >> 32) != 0;      // only then can there be such neighbours
+        bool bad = false;
+        const bool wide = (ii.range >> 32) != 0;      // only then can two neighbours be 2^32 or more apart
+        int farbin = 0;                               // the window kernels hold deltas in 32 bits: the bin such a
+        u32 far = 0;                                  // step ends in is remembered (this lane's last one, and how many)
         for (u32 i0 = 0; i0 < (u32)R; i0 += WAVE) {   // unsigned: R may be within a wave's width of 2^31
             const u32 i = i0 + (u32)lane;
             int bin = -1;
@@ -214,14 +221,17 @@ __global__ __launch_bounds__(PART_ROWS * WAVE) void zl_partition_sum_kernel(
             i64 pt = __shfl_up(t, 1, WAVE);
             if (lane == 0) { pb = carry; pt = carry_t; }
             bad |= t < pt;                     // the only place the multi-window path checks every pair of neighbours
-            if (wide) far |= i > 0 && i < (u32)R && (((u64)t - (u64)pt) >> 32) != 0;
+            if (wide && i > 0 && i < (u32)R && (((u64)t - (u64)pt) >> 32) != 0) { farbin = bin; ++far; }
             if (i < (u32)R)
                 for (int k = pb + 1; k <= bin; ++k) { out[k] = (CT)i; atomicAdd(&sums[k], i); }
             carry = __shfl(bin, WAVE - 1, WAVE);
             carry_t = __shfl(t, WAVE - 1, WAVE);
         }
         if (__any(bad) && lane == 0 && status) atomicOr(status + b, (int)EBSP_STATUS_UNSORTED);
-        if (__any(far) && lane == 0) atomicOr(&info[b].wide_steps, 1u);
+        if (far) {                                    // (a lane with several such steps: more than the list takes)
+            const u32 slot = atomicAdd(&info[b].wide_steps, far == 1 ? 1u : WIDE_MARKS + 1u);
+            if (far == 1 && slot < WIDE_MARKS) widebin[b * (i64)WIDE_MARKS + slot] = (u32)farbin;
+        }
         const int last_bin = (int)fine_bin((u64)row[R - 1] - base, ii, tab);
         for (int k = last_bin + 1 + lane; k <= (int)ii.nb; k += WAVE) { out[k] = (CT)R; atomicAdd(&sums[k], (u32)R); }
     }
@@ -319,14 +329,16 @@ __global__ __launch_bounds__(256) void zl_bincount_kernel(
 struct WinVal {
     u64 A, Elast;
     u64 inv52;     // floor(2^52 / scale)
-    u32 scale;     // linear_scale(Elast - A, buckets), when the span fits 32 bits
+    u32 scale;     // linear_scale(Elast - A, buckets); 0: not for the fast search (the window is 2^32 or more
+                   // wide, or a row steps by 2^32 or more into it)
     u32 pad_;
 };
 
 template <int NT, int PLAN_SLICE>       // PLAN_SLICE: fine bins held in LDS at a time
 __global__ __launch_bounds__(NT) void zl_plan_kernel(
     InstInfo* __restrict__ info, const SegEntry* __restrict__ segtab, const u32* __restrict__ below, int stride,
-    u32* __restrict__ winstart, WinVal* __restrict__ winval, int max_win, u32 fill, u32 buckets)
+    const u32* __restrict__ widebin, bool pred, u32* __restrict__ winstart, WinVal* __restrict__ winval, int max_win,
+    u32 fill, u32 buckets)
 {
     __shared__ u32 ends[PLAN_SLICE + 1];   // ends[i + 1] = keys under bin k0 + i + 1 = where bin k0 + i ends
     __shared__ u32 found_all, slice_cnt, slice_last;
@@ -445,6 +457,21 @@ __global__ __launch_bounds__(NT) void zl_plan_kernel(
         v.scale = scale;
         v.inv52 = (1ull << 52) / scale;
         v.pad_ = 0;
+        bool slow = (span >> 32) != 0;
+        if (wide) {
+            // predicted rows of such an instance are not for the fast search (their first values and intervals
+            // are kept as 32-bit words); nor is an instance with more steps of 2^32 or more than the list of
+            // the bins they end in holds (zl_partition's); else the windows with such a bin
+            const u32 steps = ii.wide_steps;
+            slow |= pred || steps > WIDE_MARKS;
+            const u32 marks = steps <= WIDE_MARKS ? steps : 0u;
+            const u32 k_lo = ws[j], k_hi = j + 1 < nwin ? ws[j + 1] : (u32)nb;
+            for (u32 m = 0; m < marks; ++m) {
+                const u32 kb = widebin[b * (i64)WIDE_MARKS + m];
+                if (kb >= k_lo && kb < k_hi) slow = true;
+            }
+        }
+        if (slow) v.scale = 0;
         wv[j] = v;
     }
 }

@@ -67,7 +67,8 @@ __device__ __forceinline__ void window_search(const Smem& sm, const Rows& rw, co
     r.wait = U64_MAX;
     r.brel = 0;
     if (wv.Elast >= wv.A) {
-        bool defer = !hot || ((wv.Elast - wv.A) >> 32) != 0;   // keys are 32 bits wide
+        // scale 0: zl_plan found the window unfit for 32-bit keys and deltas (a window that wide is among them)
+        bool defer = !hot || ((wv.Elast - wv.A) >> 32) != 0 || wv.scale == 0;
         if (!defer) {
             u32 key[ITEMS], dl[ITEMS];
             u64 w0 = 0;
@@ -146,9 +147,10 @@ __device__ __forceinline__ void window_pairs(
     const int jend = j0 + WINDOWS_PER_BLOCK < (int)ii.nwin ? j0 + WINDOWS_PER_BLOCK : (int)ii.nwin;
     if (j0 >= jend) return;
     Partial* out = partial + b * (i64)max_win;
-    // the fast search holds keys relative to its window and deltas between neighbours in 32 bits: every
-    // instance whose spread fits, and (stored rows) any other whose rows step by less than 2^32
-    const bool hot = (!(ii.range >> 32) || (!PRED && ii.wide_steps == 0)) && (u64)P * (u64)R < HOT_MAX_ENTRIES;
+    // The fast search holds keys relative to its window and deltas between neighbours in 32 bits.  That
+    // fits every window of an instance whose value spread does; in the others zl_plan has marked the
+    // windows it does not fit (WinVal::scale == 0).
+    const bool hot = (!(ii.range >> 32) || !PRED) && (u64)P * (u64)R < HOT_MAX_ENTRIES;
     Rows rw;
     rw.inst = PRED ? nullptr : ts + b * (i64)P * R;
     rw.le = nullptr; rw.iv = nullptr;
