@@ -429,3 +429,21 @@ def test_nanosecond_timestamps_at_the_papers_scales(zl, oracle, P, R):
     assert ((ts.max(axis=(1, 2)) - ts.min(axis=(1, 2))) >> 32).all()
     assert_same(zl, oracle, ts, f"ns, P={P} R={R}")
     all_three(zl, oracle, ts[:2], f"ns, P={P} R={R}, both objectives")
+
+
+@pytest.mark.parametrize("pauses", [1, 3, 15, 16, 40])
+def test_a_few_long_pauses_in_nanosecond_rows(zl, oracle, pauses):
+    # an instance in nanoseconds whose rows step by less than 2^32 except for a few pauses of 2^33 and more:
+    # only the windows such a step ends in are left to the general search (up to 15 of them are remembered
+    # per instance; with more the whole instance is), and the result must not change either way
+    rng = np.random.default_rng(pauses)
+    B, P, R = 3, 600, 400
+    steps = rng.integers(80_000_000, 120_000_000, size=(B, P, R)).astype(np.int64)
+    for b in range(B):
+        for _ in range(pauses):
+            steps[b, rng.integers(0, P), rng.integers(1, R)] += int(rng.integers(2 ** 33, 2 ** 34))
+    ts = np.cumsum(steps, axis=2) + rng.integers(0, 100_000_000, size=(B, P, 1))
+    all_three(zl, oracle, ts, f"{pauses} pauses")
+    # the same pauses at the very first step of a row (its first entry stays early, the second comes late)
+    steps[:, :4, 1] += 2 ** 35
+    all_three(zl, oracle, np.cumsum(steps, axis=2), f"{pauses} pauses and four early ones")
