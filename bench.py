@@ -33,10 +33,10 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 # hold only for the kernel sources they were taken from: `traffic` is null once those have changed.
 COUNTED_SOURCES_SHA256 = "f835e57ff9849d4afdfdffc2214efd5caabfed39a751a349f7489bac15061102"
 COUNTED_TRAFFIC = {     # (objective, predicted, config) -> (dominant kernel, its bytes, bytes of all kernels of a call)
-    ("sum", False, 5): ("zl_window_kernel", 2256604 * 2048 + 1237 * 1024, 7533185099),
-    ("sum", False, 3): ("zl_instance_kernel", 1189523 * 2048 + 5654 * 1024, 2458897803),
-    ("range", False, 5): ("zl_range_fast_kernel", 2233410 * 2048 + 1678 * 1024, 7494517845),
-    ("sum", True, 5): ("zl_window_kernel", 267420 * 2048 + 559 * 1024, 1176887904),
+    ("sum", False, 5): ("zl_window_kernel", 2260923 * 2048 + 1223 * 1024, 7542405397),
+    ("sum", False, 3): ("zl_instance_kernel", 1189601 * 2048 + 5655 * 1024, 2459061408),
+    ("range", False, 5): ("zl_range_fast_kernel", 2233769 * 2048 + 1684 * 1024, 7495621707),
+    ("sum", True, 5): ("zl_window_kernel", 267418 * 2048 + 562 * 1024, 1176893707),
 }
 
 
