@@ -198,3 +198,14 @@ def test_run_replays_from_a_hip_graph(zl, oracle, B, P, R):
         assert np.array_equal(outs[1].cpu().numpy(), oi), rep
         eager = zl.ebsp_simulate_supersteps(le_dev, iv_dev, R, sync)
         assert all(torch.equal(a, b) for a, b in zip(eager, outs)), rep
+
+
+def test_hand_worked_fixture(zl):
+    import json
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "worked_examples_supersteps.json")
+    for c in json.load(open(path))["cases"]:
+        bar, it, w, st = gpu_run(zl, np.array(c["last_end0"], dtype=np.int64), np.array(c["interval"], dtype=np.int64),
+                                 c["R"], c["sync_cost"])
+        assert (st == 0).all(), c["name"]
+        assert bar.tolist() == c["barrier"] and w.tolist() == c["wait"] and it.tolist() == c["iters"], c["name"]

@@ -131,3 +131,15 @@ def test_superstep_workload_runs_and_lookahead_reduces_waiting(oracle):
         assert (rc == 0).all()
         per_iter.append(w.sum() / it.sum())
     assert per_iter[0] > per_iter[1] > per_iter[2]
+
+
+def test_hand_worked_fixture(oracle):
+    import json
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "worked_examples_supersteps.json")
+    cases = json.load(open(path))["cases"]
+    assert len(cases) >= 6
+    for c in cases:
+        b, it, w, rc, _ = oracle.simulate(c["last_end0"], c["interval"], c["R"], c["sync_cost"])
+        assert (rc == 0).all(), c["name"]
+        assert b.tolist() == c["barrier"] and w.tolist() == c["wait"] and it.tolist() == c["iters"], c["name"]
