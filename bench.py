@@ -307,6 +307,9 @@ def main() -> int:
         "setup_s": gen_s,
     }
     print(json.dumps(out))
+    if not same:
+        print("bench.py: the GPU results differ from the CPU oracle on the sampled instances", file=sys.stderr)
+        return 1
     return 0
 
 

@@ -4,11 +4,10 @@ Bar: bit-exact on barrier (int64), wait (int64) and iters (int32) -- the
 search is integer work and its result is unique (first minimum, upper-bound
 iteration counts), so every output is compared element by element.
 
-Small and medium cases are compared in full.  The three 2 GiB configurations
-are run at full size in the launch configuration the benchmark times and are
-checked two ways: instances drawn at random are compared with the oracle, and
-on every instance the three outputs are checked against properties that hold
-at any size (each worker stops at its last timestamp <= barrier, the stops sum
+Every case is compared in full, the three 2 GiB configurations included: they
+are run at full size in the launch configuration the benchmark times, every
+instance is compared with the oracle, and on every instance the three outputs
+are also checked against properties that hold at any size (each worker stops at its last timestamp <= barrier, the stops sum
 to the reported wait, some worker stops exactly at the barrier, and the wait
 does not exceed the classic-BSP wait of one iteration per worker).
 """
@@ -260,23 +259,20 @@ def _properties_hold(ts_dev, bar, it, w):
     assert bool((w >= 0).all())
 
 
-@pytest.mark.parametrize("k,sample", [(3, 768), (4, 96), (5, 8)])
-def test_full_size_configs(zl, oracle, k, sample):
-    cfg = workloads.CONFIGS[k]
+@pytest.mark.parametrize("k", [3, 4, 5])
+def test_full_size_configs(zl, oracle, k):
+    # every instance of the 2 GiB configurations against the oracle, in the launch configuration the benchmark times
     host = workloads.make(k, threads=16)
     ts = torch.from_numpy(host).cuda()
     bar, it, w, st = zl.ebsp_zipline_batch(ts)
     torch.cuda.synchronize()
     assert int(st.max().item()) == 0
     _properties_hold(ts, bar, it, w)
-    rng = np.random.default_rng(k)
-    ids = np.sort(rng.choice(cfg.B, size=sample, replace=False))
-    ob, oi, ow, rc, _ = oracle.zipline(host[ids], "sweep", threads=16)
+    ob, oi, ow, rc, _ = oracle.zipline(host, "sweep", threads=16)
     assert (rc == 0).all()
-    sel = torch.from_numpy(ids).cuda()
-    assert np.array_equal(bar[sel].cpu().numpy(), ob)
-    assert np.array_equal(w[sel].cpu().numpy(), ow)
-    assert np.array_equal(it[sel].cpu().numpy(), oi)
+    assert np.array_equal(bar.cpu().numpy(), ob), f"barrier differs at {np.nonzero(bar.cpu().numpy() != ob)[0][:5]}"
+    assert np.array_equal(w.cpu().numpy(), ow), f"wait differs at {np.nonzero(w.cpu().numpy() != ow)[0][:5]}"
+    assert np.array_equal(it.cpu().numpy(), oi)
 
 
 def test_shifted_epoch_multi_window(zl, oracle):

@@ -152,23 +152,20 @@ def _properties_hold(ts, bar, it, dm):
     assert bool((dm <= classic).all())
 
 
-@pytest.mark.parametrize("k,sample", [(3, 768), (4, 96), (5, 8)])
-def test_full_size_configs(zl, oracle, k, sample):
-    cfg = workloads.CONFIGS[k]
+@pytest.mark.parametrize("k", [3, 4, 5])
+def test_full_size_configs(zl, oracle, k):
+    # every instance of the 2 GiB configurations against the oracle
     host = workloads.make(k, threads=16)
     ts = torch.from_numpy(host).cuda()
     bar, it, dm, st = zl.ebsp_zipline_range_batch(ts)
     torch.cuda.synchronize()
     assert int(st.max().item()) == 0
     _properties_hold(ts, bar, it, dm)
-    rng = np.random.default_rng(100 + k)
-    ids = np.sort(rng.choice(cfg.B, size=sample, replace=False))
-    ob, oi, od, rc, _ = oracle.zipline_range(host[ids], "sweep", threads=16)
+    ob, oi, od, rc, _ = oracle.zipline_range(host, "sweep", threads=16)
     assert (rc == 0).all()
-    sel = torch.from_numpy(ids).cuda()
-    assert np.array_equal(bar[sel].cpu().numpy(), ob)
-    assert np.array_equal(dm[sel].cpu().numpy(), od)
-    assert np.array_equal(it[sel].cpu().numpy(), oi)
+    assert np.array_equal(bar.cpu().numpy(), ob), f"barrier differs at {np.nonzero(bar.cpu().numpy() != ob)[0][:5]}"
+    assert np.array_equal(dm.cpu().numpy(), od), f"dmin differs at {np.nonzero(dm.cpu().numpy() != od)[0][:5]}"
+    assert np.array_equal(it.cpu().numpy(), oi)
 
 
 def test_value_spread_beyond_32_bits(zl, oracle):
