@@ -85,6 +85,29 @@ int ebsp_zipline_batch(const int64_t* ts, int64_t B, int32_t P, int32_t R,
                        void* stream);
 
 /*
+ * ebsp_zipline_batch for callers that cannot allocate device memory or pass a
+ * workspace (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc): the same search, the same arguments without the
+ * workspace, the same results.  The scratch is a device array of
+ * EBSP_STATIC_SCRATCH_BYTES bytes inside the library, held by every GPU the
+ * library runs on until the process ends; its address on the current device
+ * is looked up on the first call there and kept.  The call allocates and frees
+ * nothing and only enqueues kernels on `stream`.
+ * A batch whose ebsp_zipline_workspace_bytes() exceeds the array is refused
+ * with EBSP_ERR_WORKSPACE (nothing enqueued; ebsp_last_error() says how much
+ * it needs): split it over several calls.  All calls on one GPU share the one
+ * array, so calls that overlap on a GPU (different streams, or threads) race:
+ * keep them on one stream, or use ebsp_zipline_batch with workspaces of your
+ * own.  No kernel expects the array to be cleared; it keeps the last call's
+ * contents.
+ */
+#define EBSP_STATIC_SCRATCH_BYTES (32u << 20)
+size_t ebsp_zipline_static_scratch_bytes(void);
+int ebsp_zipline_batch_static(const int64_t* ts, int64_t B, int32_t P, int32_t R,
+                              int64_t* barrier, int32_t* iters, int64_t* wait,
+                              int32_t* status, void* stream);
+
+/*
  * The prediction folded in (Section III: a worker's iterations take similar
  * time, so its next R end timestamps are predicted from its most recent ones;
  * the paper gives no formula, the linear one is this library's reading):

@@ -417,9 +417,56 @@ int run_range_batch(const i64* ts, i64 B, int P, int R, i64* barrier, int* iters
     return EBSP_OK;
 }
 
+// Scratch of the entry point that allocates nothing: a file-scope device array that every GPU the
+// library runs on holds until the process ends.  In host code the array's name is only a handle
+// for hipGetSymbolAddress; its device address is asked for once per device and kept.
+static __device__ __align__(256) unsigned char scratch[EBSP_STATIC_SCRATCH_BYTES];
+
+int static_scratch(void** out)
+{
+    constexpr int KNOWN = 64;
+    static std::atomic<void*> base[KNOWN];             // per device: where that GPU's copy of the array lives
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return fail(EBSP_ERR_DEVICE, "no current HIP device");
+    if (dev < 0 || dev >= KNOWN) return fail(EBSP_ERR_DEVICE, "device ordinal beyond what the static scratch table holds");
+    void* ptr = base[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) {
+            snprintf(g_err, sizeof g_err, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+            return EBSP_ERR_DEVICE;
+        }
+        base[dev].store(ptr, std::memory_order_release);
+    }
+    *out = ptr;
+    return EBSP_OK;
+}
+
 }  // namespace
 
 extern "C" {
+
+size_t ebsp_zipline_static_scratch_bytes(void) { return (size_t)EBSP_STATIC_SCRATCH_BYTES; }
+
+int ebsp_zipline_batch_static(const int64_t* ts, int64_t B, int32_t P, int32_t R,
+                              int64_t* barrier, int32_t* iters, int64_t* wait, int32_t* status, void* stream)
+{
+    if (!ts && B > 0) return fail(EBSP_ERR_NULL, "ts must not be NULL");
+    Plan pl;
+    if (!make_plan(B, P, R, pl)) return fail(EBSP_ERR_SHAPE, "invalid shape: need B >= 0, P >= 1, R >= 1, P*R < 2^31");
+    if (pl.multi && pl.bytes > (size_t)EBSP_STATIC_SCRATCH_BYTES) {
+        snprintf(g_err, sizeof g_err, "this batch needs %zu bytes of scratch, the static scratch holds %zu: "
+                 "use fewer instances per call or ebsp_zipline_batch with a workspace", pl.bytes, (size_t)EBSP_STATIC_SCRATCH_BYTES);
+        return EBSP_ERR_WORKSPACE;
+    }
+    void* ptr = nullptr;
+    if (B > 0)
+        if (int rc = static_scratch(&ptr)) return rc;
+    const int rc = run_batch((const i64*)ts, nullptr, nullptr, B, P, R, (i64*)barrier, iters, (i64*)wait, status,
+                             ptr, (size_t)EBSP_STATIC_SCRATCH_BYTES, (hipStream_t)stream);
+    if (g_prof.on && rc == EBSP_OK && B > 0 && g_prof.calls < g_prof.max_calls) ++g_prof.calls;
+    return rc;
+}
 
 size_t ebsp_zipline_workspace_bytes(int64_t B, int32_t P, int32_t R)
 {

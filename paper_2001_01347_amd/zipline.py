@@ -20,7 +20,8 @@ LIB_PATH = os.path.join(_HERE, "libebsp_zipline.so")
 EBSP_OK = 0
 STATUS_OK, STATUS_UNSORTED, STATUS_OVERFLOW, STATUS_UNSUPPORTED = 0, 1, 2, 4
 
-EXPORTS = ("ebsp_zipline_workspace_bytes", "ebsp_zipline_batch", "ebsp_zipline_range_workspace_bytes",
+EXPORTS = ("ebsp_zipline_workspace_bytes", "ebsp_zipline_batch", "ebsp_zipline_batch_static",
+           "ebsp_zipline_static_scratch_bytes", "ebsp_zipline_range_workspace_bytes",
            "ebsp_zipline_range_batch", "ebsp_predict_zipline_batch", "ebsp_simulate_workspace_bytes",
            "ebsp_simulate_supersteps", "ebsp_zipline_tune", "ebsp_zipline_shape_info", "ebsp_zipline_profile_begin",
            "ebsp_zipline_profile_end", "ebsp_zipline_copy_probe", "ebsp_zipline_kernel_count",
@@ -47,6 +48,10 @@ def load() -> ctypes.CDLL:
         common = [vp, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
         lib.ebsp_zipline_batch.restype = ctypes.c_int
         lib.ebsp_zipline_batch.argtypes = common
+        lib.ebsp_zipline_batch_static.restype = ctypes.c_int
+        lib.ebsp_zipline_batch_static.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp, vp]
+        lib.ebsp_zipline_static_scratch_bytes.restype = sz
+        lib.ebsp_zipline_static_scratch_bytes.argtypes = []
         lib.ebsp_zipline_range_workspace_bytes.restype = sz
         lib.ebsp_zipline_range_workspace_bytes.argtypes = [i64, i32, i32]
         lib.ebsp_zipline_range_batch.restype = ctypes.c_int
@@ -154,6 +159,23 @@ def ebsp_zipline_batch(ts: torch.Tensor, barrier: Optional[torch.Tensor] = None,
     if rc != EBSP_OK:
         raise ZipLineError(f"ebsp_zipline_batch failed ({rc}): {ebsp_last_error()}")
     return outs
+
+
+def ebsp_zipline_static_scratch_bytes() -> int:
+    return int(load().ebsp_zipline_static_scratch_bytes())
+
+
+def ebsp_zipline_batch_static(ts: torch.Tensor, barrier: torch.Tensor, iters: torch.Tensor, wait: torch.Tensor,
+                              status: torch.Tensor):
+    """``ebsp_zipline_batch`` on the library's own static scratch: nothing is allocated, here or in the library,
+    so the caller passes every output.  Returns ``(barrier, iters, wait, status)``.  Does not synchronise."""
+    B, P, R = _check(ts)
+    with torch.cuda.device(ts.device):
+        rc = load().ebsp_zipline_batch_static(ts.data_ptr(), B, P, R, barrier.data_ptr(), iters.data_ptr(), wait.data_ptr(),
+                                              status.data_ptr(), torch.cuda.current_stream(ts.device).cuda_stream)
+    if rc != EBSP_OK:
+        raise ZipLineError(f"ebsp_zipline_batch_static failed ({rc}): {ebsp_last_error()}")
+    return barrier, iters, wait, status
 
 
 def ebsp_zipline_range_batch(ts: torch.Tensor, barrier: Optional[torch.Tensor] = None,
