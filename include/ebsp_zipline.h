@@ -57,8 +57,12 @@ extern "C" {
  * Bytes of device scratch that ebsp_zipline_batch needs for this shape.
  * Returns 0 for invalid shapes and for shapes that need no scratch (small
  * instances are handled by one workgroup each, entirely in LDS).
+ * ebsp_predict_zipline_workspace_bytes is the same for
+ * ebsp_predict_zipline_batch (predicted rows take other kernels, which need
+ * more scratch).
  */
 size_t ebsp_zipline_workspace_bytes(int64_t B, int32_t P, int32_t R);
+size_t ebsp_predict_zipline_workspace_bytes(int64_t B, int32_t P, int32_t R);
 
 /*
  * Batched ZipLine search: B independent instances.
@@ -121,8 +125,9 @@ int ebsp_zipline_batch_static(const int64_t* ts, int64_t B, int32_t P, int32_t R
  *                 finished iteration (any fixed unit and epoch).
  *   interval  in  [B][P] int64, device: predicted iteration time, >= 0
  *                 (a negative one gives EBSP_STATUS_UNSORTED for the instance).
- *   the other arguments, the workspace size (ebsp_zipline_workspace_bytes),
- *   the status bits and the return codes: as for ebsp_zipline_batch.
+ *   workspace at least ebsp_predict_zipline_workspace_bytes(B, P, R) bytes;
+ *   the other arguments, the status bits and the return codes: as for
+ *   ebsp_zipline_batch.
  * Precondition: last_end + R * interval does not overflow int64.
  */
 int ebsp_predict_zipline_batch(const int64_t* last_end, const int64_t* interval,
@@ -222,6 +227,18 @@ int ebsp_zipline_shape_info(int64_t B, int32_t P, int32_t R, int64_t* info);
  * Results do not depend on any of them.  Returns EBSP_OK or EBSP_ERR_SHAPE.
  */
 int ebsp_zipline_tune(int32_t window_cap, int32_t single_max, int32_t window_fill);
+
+/*
+ * Which stored-row batches ebsp_zipline_batch searches in one pass (the frontier
+ * sweep) and how it slices them; process-wide, same rules as ebsp_zipline_tune.
+ *   sweep_min   smallest P*R that takes the sweep; 0 = the default, negative =
+ *               never (every batch takes the kernels that predicted rows and
+ *               the range objective use).
+ *   slice_keys  entries per slice of an instance's value range (at least 256);
+ *               0 = chosen from the batch.
+ * Results do not depend on either.  Returns EBSP_OK or EBSP_ERR_SHAPE.
+ */
+int ebsp_zipline_tune_sweep(int32_t sweep_min, int32_t slice_keys);
 
 /*
  * Per-kernel timing for benchmarks.  Between ebsp_zipline_profile_begin() and

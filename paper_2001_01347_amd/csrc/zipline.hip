@@ -36,6 +36,7 @@
 //   zl_window.h    window kernels of the summed-wait search
 //   zl_range.h     the objective max(Z) - min(Z)
 //   zl_finish.h    reduction over windows, zl_iters; the copy yardstick
+//   zl_sweep.h     the frontier sweep: stored rows searched in one pass, no crossing table
 // This file: the host side (plans, launches, the C entry points).
 #include <hip/hip_runtime.h>
 #include <atomic>
@@ -44,7 +45,7 @@
 #include <string.h>
 
 #include "ebsp_zipline.h"
-#include "zl_finish.h"      // pulls in the other device headers, in dependency order
+#include "zl_sweep.h"       // pulls in the other device headers, in dependency order
 
 namespace {
 
@@ -79,12 +80,12 @@ int check_device()
 }
 
 enum KernelId { K_INSTANCE = 0, K_INSTANCE_GENERAL, K_BOUNDS, K_PARTITION, K_BINCOUNT, K_PLAN, K_WINDOW,
-                K_WINDOW_GENERAL, K_FINISH, K_COPY, K_RANGE_INSTANCE, K_RANGE_WINDOW, K_PARTITION_PRED, K_RANGE_FAST, K_ADVANCE, K_COUNT };
+                K_WINDOW_GENERAL, K_FINISH, K_COPY, K_RANGE_INSTANCE, K_RANGE_WINDOW, K_PARTITION_PRED, K_RANGE_FAST, K_ADVANCE, K_SWEEP, K_SWEEP_FINISH, K_COUNT };
 const char* const kKernelNames[K_COUNT] = {
     "zl_instance_kernel", "zl_instance_general_kernel", "zl_bounds_kernel", "zl_partition_kernel",
     "zl_bincount_kernel", "zl_plan_kernel", "zl_window_kernel", "zl_window_general_kernel",
     "zl_finish_kernel", "zl_copy_kernel", "zl_range_instance_kernel", "zl_range_window_kernel",
-    "zl_partition_pred_kernel", "zl_range_fast_kernel", "zl_advance_kernel"};
+    "zl_partition_pred_kernel", "zl_range_fast_kernel", "zl_advance_kernel", "zl_sweep_kernel", "zl_sweep_finish_kernel"};
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -93,10 +94,31 @@ struct Tuning {          // 0: choose by shape
     int window_cap;
     int single_max;
     int window_fill;
+    int sweep_min;       // smallest P*R that takes the frontier sweep (0: the default, < 0: never)
+    int slice_keys;      // entries per slice of the sweep (0: chosen from the batch)
 };
-Tuning g_tune = {0, 0, 0};
+// Set before any thread calls a search (the header says so); read once per call, word by word.
+std::atomic<int> g_tune_window_cap{0}, g_tune_single_max{0}, g_tune_window_fill{0}, g_tune_sweep_min{0}, g_tune_slice_keys{0};
+Tuning tuning()
+{
+    Tuning t;
+    t.window_cap = g_tune_window_cap.load(std::memory_order_relaxed);
+    t.single_max = g_tune_single_max.load(std::memory_order_relaxed);
+    t.window_fill = g_tune_window_fill.load(std::memory_order_relaxed);
+    t.sweep_min = g_tune_sweep_min.load(std::memory_order_relaxed);
+    t.slice_keys = g_tune_slice_keys.load(std::memory_order_relaxed);
+    return t;
+}
+
+// The frontier sweep (zl_sweep.h) takes stored rows of these shapes under the summed-wait objective.
+constexpr int SWEEP_NT = 512, SWEEP_ITEMS = 16;
+constexpr int SWEEP_MIN_DEFAULT = 8192;          // instances of fewer entries: one workgroup of zl_instance_kernel each
+constexpr int SWEEP_PMAX = 2048;                 // every row with entries left needs a slot, and a quarter of the slots is the most they may take
 
 struct Plan {
+    bool sweep;        // stored rows go through the frontier sweep
+    int nslices;       // slices per instance there
+    size_t off_spartial, sweep_bytes;
     bool multi;
     int cap;           // records per window workgroup
     int fill;          // most entries of a window (unless a single fine bin holds more)
@@ -110,12 +132,35 @@ struct Plan {
 
 // single_limit: the most entries one workgroup takes whole on the path the plan is for;
 // list_room: windows leave a quarter or more of the workgroup's records free (the fast range search keeps its short list there)
-bool make_plan(i64 B, int P, int R, Plan& pl, int single_limit = SINGLE_MAX, bool list_room = false)
+bool make_plan(i64 B, int P, int R, Plan& pl, int single_limit = SINGLE_MAX, bool list_room = false, bool stored_sum = false)
 {
     if (B < 0 || P < 1 || R < 1) return false;
     const i64 n = (i64)P * (i64)R;
     if (n >= (1ll << 31)) return false;
     memset(&pl, 0, sizeof pl);
+    const Tuning g_tune = tuning();
+    {
+        const i64 sweep_min = g_tune.sweep_min > 0 ? g_tune.sweep_min : SWEEP_MIN_DEFAULT;
+        pl.sweep = stored_sum && g_tune.sweep_min >= 0 && n >= sweep_min && n < (1ll << 29) && P <= SWEEP_PMAX && B > 0;
+        if (pl.sweep) {
+            // about 2048 slices per batch (four rounds of two workgroups per CU), each long enough to pay for the
+            // searches that open it (64 entries per row or more) and short enough to spread an instance over the chip
+            i64 keys = g_tune.slice_keys > 0 ? g_tune.slice_keys : B * n / 2048;
+            if (g_tune.slice_keys <= 0) {
+                if (keys < 32768) keys = 32768;
+                if (keys > 262144) keys = 262144;
+                if (keys < 64ll * P) keys = 64ll * P;
+            }
+            i64 ns = (n + keys - 1) / keys;
+            if (ns > 4096) ns = 4096;
+            pl.nslices = (int)(ns < 1 ? 1 : ns);
+            size_t o = 0;                                       // (the first two as in the other layout below)
+            pl.off_info = o;     o = align_up(o + (size_t)B * sizeof(InstInfo), 256);
+            pl.off_seg = o;      o = align_up(o + (size_t)B * SEGS * sizeof(SegEntry), 256);
+            pl.off_spartial = o; o = align_up(o + (size_t)B * pl.nslices * sizeof(Partial), 256);
+            pl.sweep_bytes = o;
+        }
+    }
     int single_max = g_tune.single_max > 0 ? g_tune.single_max : SINGLE_MAX;
     if (single_max > single_limit) single_max = single_limit;
     pl.multi = n > single_max;
@@ -251,13 +296,39 @@ int run_batch(const i64* ts, const i64* le, const i64* iv, i64 B, int P, int R,
               void* workspace, size_t workspace_bytes, hipStream_t st)
 {
     Plan pl;
-    if (!make_plan(B, P, R, pl)) return fail(EBSP_ERR_SHAPE, "invalid shape: need B >= 0, P >= 1, R >= 1, P*R < 2^31");
-    if (B == 0) return EBSP_OK;
     const bool pred = ts == nullptr;
+    if (!make_plan(B, P, R, pl, SINGLE_MAX, false, !pred)) return fail(EBSP_ERR_SHAPE, "invalid shape: need B >= 0, P >= 1, R >= 1, P*R < 2^31");
+    if (B == 0) return EBSP_OK;
     if ((pred && (!le || !iv)) || !barrier || !iters || !wait)
         return fail(EBSP_ERR_NULL, "the input arrays, barrier, iters and wait must not be NULL");
     if (B > 0x7fffffffll) return fail(EBSP_ERR_SHAPE, "B must be below 2^31");
     const int n = P * R;
+
+    if (pl.sweep) {
+        // stored rows in one pass: instance facts and slices, the sweep, the reduction over slices with zl_iters
+        if (!workspace) return fail(EBSP_ERR_NULL, "this shape needs a workspace");
+        if (workspace_bytes < pl.sweep_bytes) return fail(EBSP_ERR_WORKSPACE, "workspace smaller than ebsp_zipline_workspace_bytes()");
+        if (((uintptr_t)workspace & 255u) != 0) return fail(EBSP_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+        const i64 pblocks = (P + 255) / 256;
+        if (B * (i64)pl.nslices > 0x7fffffffll || pblocks * B > 0x7fffffffll) return fail(EBSP_ERR_SHAPE, "batch too large for one call");
+        if (int rc = check_device()) return rc;
+        char* wsp = (char*)workspace;
+        InstInfo* info = (InstInfo*)(wsp + pl.off_info);
+        SegEntry* segtab = (SegEntry*)(wsp + pl.off_seg);
+        Partial* spartial = (Partial*)(wsp + pl.off_spartial);
+        LAUNCH(K_BOUNDS, (zl_bounds_kernel<256>), dim3((unsigned)B), dim3(256), ts, le, iv, P, R, pl.nslices, info, segtab,
+               (uint2*)nullptr, status, true);
+        const dim3 sgrid((unsigned)(B * (i64)pl.nslices));
+        if (P <= 1024)
+            LAUNCH(K_SWEEP, (zl_sweep_kernel<SWEEP_NT, SWEEP_ITEMS, 1024>), sgrid, dim3(SWEEP_NT), ts, B, P, R, pl.nslices,
+                   info, segtab, spartial, status);
+        else
+            LAUNCH(K_SWEEP, (zl_sweep_kernel<SWEEP_NT, SWEEP_ITEMS, SWEEP_PMAX>), sgrid, dim3(SWEEP_NT), ts, B, P, R, pl.nslices,
+                   info, segtab, spartial, status);
+        LAUNCH(K_SWEEP_FINISH, (zl_sweep_finish_kernel<256>), dim3((unsigned)(pblocks * B)), dim3(256),
+               ts, P, R, pl.nslices, info, spartial, barrier, iters, wait);
+        return EBSP_OK;
+    }
 
     if (!pl.multi) {
         if (int rc = check_device()) return rc;
@@ -453,10 +524,11 @@ int ebsp_zipline_batch_static(const int64_t* ts, int64_t B, int32_t P, int32_t R
 {
     if (!ts && B > 0) return fail(EBSP_ERR_NULL, "ts must not be NULL");
     Plan pl;
-    if (!make_plan(B, P, R, pl)) return fail(EBSP_ERR_SHAPE, "invalid shape: need B >= 0, P >= 1, R >= 1, P*R < 2^31");
-    if (pl.multi && pl.bytes > (size_t)EBSP_STATIC_SCRATCH_BYTES) {
+    if (!make_plan(B, P, R, pl, SINGLE_MAX, false, true)) return fail(EBSP_ERR_SHAPE, "invalid shape: need B >= 0, P >= 1, R >= 1, P*R < 2^31");
+    const size_t need = pl.sweep ? pl.sweep_bytes : (pl.multi ? pl.bytes : 0);
+    if (need > (size_t)EBSP_STATIC_SCRATCH_BYTES) {
         snprintf(g_err, sizeof g_err, "this batch needs %zu bytes of scratch, the static scratch holds %zu: "
-                 "use fewer instances per call or ebsp_zipline_batch with a workspace", pl.bytes, (size_t)EBSP_STATIC_SCRATCH_BYTES);
+                 "use fewer instances per call or ebsp_zipline_batch with a workspace", need, (size_t)EBSP_STATIC_SCRATCH_BYTES);
         return EBSP_ERR_WORKSPACE;
     }
     void* ptr = nullptr;
@@ -469,6 +541,14 @@ int ebsp_zipline_batch_static(const int64_t* ts, int64_t B, int32_t P, int32_t R
 }
 
 size_t ebsp_zipline_workspace_bytes(int64_t B, int32_t P, int32_t R)
+{
+    Plan pl;
+    if (!make_plan(B, P, R, pl, SINGLE_MAX, false, true)) return 0;
+    if (pl.sweep) return pl.sweep_bytes;
+    return pl.multi ? pl.bytes : 0;
+}
+
+size_t ebsp_predict_zipline_workspace_bytes(int64_t B, int32_t P, int32_t R)
 {
     Plan pl;
     if (!make_plan(B, P, R, pl)) return 0;
@@ -575,9 +655,17 @@ int ebsp_zipline_tune(int32_t window_cap, int32_t single_max, int32_t window_fil
         return fail(EBSP_ERR_SHAPE, "window_cap must be 0, 4096, 8192 or 16384");
     if (single_max < 0 || single_max > SINGLE_MAX)
         return fail(EBSP_ERR_SHAPE, "single_max must be in 0..16384");
-    g_tune.window_cap = window_cap;
-    g_tune.single_max = single_max;
-    g_tune.window_fill = window_fill;
+    g_tune_window_cap.store(window_cap, std::memory_order_relaxed);
+    g_tune_single_max.store(single_max, std::memory_order_relaxed);
+    g_tune_window_fill.store(window_fill, std::memory_order_relaxed);
+    return EBSP_OK;
+}
+
+int ebsp_zipline_tune_sweep(int32_t sweep_min, int32_t slice_keys)
+{
+    if (slice_keys < 0 || (slice_keys > 0 && slice_keys < 256)) return fail(EBSP_ERR_SHAPE, "slice_keys must be 0 or at least 256");
+    g_tune_sweep_min.store(sweep_min, std::memory_order_relaxed);
+    g_tune_slice_keys.store(slice_keys, std::memory_order_relaxed);
     return EBSP_OK;
 }
 

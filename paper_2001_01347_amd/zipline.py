@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libebsp_zipline.so")
 EBSP_OK = 0
 STATUS_OK, STATUS_UNSORTED, STATUS_OVERFLOW, STATUS_UNSUPPORTED = 0, 1, 2, 4
 
-EXPORTS = ("ebsp_zipline_workspace_bytes", "ebsp_zipline_batch", "ebsp_zipline_batch_static",
+EXPORTS = ("ebsp_zipline_workspace_bytes", "ebsp_predict_zipline_workspace_bytes", "ebsp_zipline_tune_sweep", "ebsp_zipline_batch", "ebsp_zipline_batch_static",
            "ebsp_zipline_static_scratch_bytes", "ebsp_zipline_range_workspace_bytes",
            "ebsp_zipline_range_batch", "ebsp_predict_zipline_batch", "ebsp_simulate_workspace_bytes",
            "ebsp_simulate_supersteps", "ebsp_zipline_tune", "ebsp_zipline_shape_info", "ebsp_zipline_profile_begin",
@@ -45,6 +45,10 @@ def load() -> ctypes.CDLL:
         vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
         lib.ebsp_zipline_workspace_bytes.restype = sz
         lib.ebsp_zipline_workspace_bytes.argtypes = [i64, i32, i32]
+        lib.ebsp_predict_zipline_workspace_bytes.restype = sz
+        lib.ebsp_predict_zipline_workspace_bytes.argtypes = [i64, i32, i32]
+        lib.ebsp_zipline_tune_sweep.restype = ctypes.c_int
+        lib.ebsp_zipline_tune_sweep.argtypes = [i32, i32]
         common = [vp, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
         lib.ebsp_zipline_batch.restype = ctypes.c_int
         lib.ebsp_zipline_batch.argtypes = common
@@ -88,6 +92,17 @@ def ebsp_last_error() -> str:
 
 def ebsp_zipline_workspace_bytes(B: int, P: int, R: int) -> int:
     return int(load().ebsp_zipline_workspace_bytes(B, P, R))
+
+
+def ebsp_predict_zipline_workspace_bytes(B: int, P: int, R: int) -> int:
+    return int(load().ebsp_predict_zipline_workspace_bytes(B, P, R))
+
+
+def ebsp_zipline_tune_sweep(sweep_min: int = 0, slice_keys: int = 0) -> None:
+    """Which stored-row batches take the one-pass sweep, and its slice length (0 = default); see the header."""
+    rc = load().ebsp_zipline_tune_sweep(int(sweep_min), int(slice_keys))
+    if rc != EBSP_OK:
+        raise ZipLineError(f"ebsp_zipline_tune_sweep failed ({rc}): {ebsp_last_error()}")
 
 
 def ebsp_zipline_range_workspace_bytes(B: int, P: int, R: int) -> int:
@@ -219,7 +234,7 @@ def ebsp_predict_zipline_batch(last_end: torch.Tensor, interval: torch.Tensor, R
         wait = torch.empty(B, dtype=torch.int64, device=dev)
     if status is None:
         status = torch.empty(B, dtype=torch.int32, device=dev)
-    need = ebsp_zipline_workspace_bytes(B, P, R)
+    need = ebsp_predict_zipline_workspace_bytes(B, P, R)
     if workspace is None and need:
         workspace = torch.empty(need, dtype=torch.uint8, device=dev)
     ws_ptr = workspace.data_ptr() if workspace is not None else None
