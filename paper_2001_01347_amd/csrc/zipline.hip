@@ -112,6 +112,7 @@ Tuning tuning()
 
 // The frontier sweep (zl_sweep.h) takes stored rows of these shapes under the summed-wait objective.
 constexpr int SWEEP_NT = 512, SWEEP_ITEMS = 16;
+constexpr int SWEEP_DEFAULT_ON = 1;              // 0: the sweep is the default for its shapes; 1: only where ebsp_zipline_tune_sweep asks for it
 constexpr int SWEEP_MIN_DEFAULT = 8192;          // instances of fewer entries: one workgroup of zl_instance_kernel each
 constexpr int SWEEP_PMAX = 2048;                 // every row with entries left needs a slot, and a quarter of the slots is the most they may take
 
@@ -141,7 +142,7 @@ bool make_plan(i64 B, int P, int R, Plan& pl, int single_limit = SINGLE_MAX, boo
     const Tuning g_tune = tuning();
     {
         const i64 sweep_min = g_tune.sweep_min > 0 ? g_tune.sweep_min : SWEEP_MIN_DEFAULT;
-        pl.sweep = stored_sum && g_tune.sweep_min >= 0 && n >= sweep_min && n < (1ll << 29) && P <= SWEEP_PMAX && B > 0;
+        pl.sweep = stored_sum && g_tune.sweep_min >= SWEEP_DEFAULT_ON && n >= sweep_min && n < (1ll << 29) && P <= SWEEP_PMAX && B > 0;
         if (pl.sweep) {
             // about 2048 slices per batch (four rounds of two workgroups per CU), each long enough to pay for the
             // searches that open it (64 entries per row or more) and short enough to spread an instance over the chip
