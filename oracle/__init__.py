@@ -22,6 +22,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "zipline_oracle.c")
 _SRC_RANGE = os.path.join(_HERE, "zipline_range_oracle.c")      # the paper's formal objective max(Z) - min(Z)
+_SRC_GRID = os.path.join(_HERE, "gridscan_oracle.c")            # GridScan and FullGridScan (Section IV, Algorithm 1)
 _LIB = os.path.join(_HERE, "libzipline_oracle.so")
 _lib = None
 
@@ -31,11 +32,11 @@ RANGE_METHODS = {"sweep": 0, "definition": 1, "naive": 2, "zipline": 3}
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (host only). Returns the library path."""
-    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < max(os.path.getmtime(_SRC),
-                                                                        os.path.getmtime(_SRC_RANGE))
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_RANGE),
+                                                                        os.path.getmtime(_SRC_GRID))
     if force or stale:
         cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-Wall", "-Wextra",
-               _SRC, _SRC_RANGE, "-o", _LIB]
+               _SRC, _SRC_RANGE, _SRC_GRID, "-o", _LIB]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -53,6 +54,11 @@ def _load():
                                         i32p]
         lib.zl_range_batch.restype = ctypes.c_int
         lib.zl_range_batch.argtypes = lib.zl_oracle_batch.argtypes
+        lib.gs_batch.restype = ctypes.c_int
+        lib.gs_batch.argtypes = [i64p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                 i64p, i32p, i64p, i32p, ctypes.c_int32, i32p]
+        lib.ebsp_zipline_oracle.restype = ctypes.c_int
+        lib.ebsp_zipline_oracle.argtypes = [i64p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, i64p, i32p, i64p, ctypes.c_int32]
         _lib = lib
     return _lib
 
@@ -75,6 +81,56 @@ def zipline(ts, method: str = "sweep", threads: int = 0):
     not non-decreasing (that instance's outputs are left at zero).
     """
     return _run(ts, "zl_oracle_batch", METHODS[method], threads)
+
+
+GRID_METHODS = {"scan": 0, "bisect": 1}
+
+
+def gridscan(ts, full: bool = False, method: str = "scan", threads: int = 0):
+    """GridScan (``full=False``) or FullGridScan (``full=True``) of Section IV, Algorithm 1, on ``ts`` [B, P, R] (or [P, R]).
+
+    Returns ``(barrier[B] int64, iters[B, P] int32, dz[B] int64, rc[B] int32, threads_used)``: ``dz`` is the smallest
+    ``max(Z) - min(Z)`` the heuristic finds, ``barrier = max(Z*)``, ``iters[p]`` = 1 + the index of worker p's point in Z*.
+    Methods: "scan" looks at every point of every other row (the order of work of Algorithm 1), "bisect" finds the
+    nearest point by bisection (for larger inputs).
+    """
+    a = np.ascontiguousarray(np.asarray(ts), dtype=np.int64)
+    if a.ndim == 2:
+        a = a[None]
+    if a.ndim != 3:
+        raise ValueError("ts must have shape [B, P, R] or [P, R]")
+    B, P, R = a.shape
+    lib = _load()
+    barrier = np.zeros(B, dtype=np.int64)
+    iters = np.zeros((B, P), dtype=np.int32)
+    dz = np.zeros(B, dtype=np.int64)
+    rc = np.zeros(B, dtype=np.int32)
+    used = ctypes.c_int32(0)
+    i64p = ctypes.POINTER(ctypes.c_int64)
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    r = lib.gs_batch(a.ctypes.data_as(i64p), B, P, R, 1 if full else 0, GRID_METHODS[method],
+                     barrier.ctypes.data_as(i64p), iters.ctypes.data_as(i32p), dz.ctypes.data_as(i64p),
+                     rc.ctypes.data_as(i32p), int(threads), ctypes.byref(used))
+    if r == 2:
+        raise ValueError("oracle rejected its arguments")
+    return barrier, iters, dz, rc, int(used.value)
+
+
+def zipline_c_abi(ts, threads: int = 0):
+    """The summed-wait search through the oracle library's C entry point ``ebsp_zipline_oracle``
+    (``include/ebsp_zipline_oracle.h``): the sweep route, host pointers.  Returns ``(barrier, iters, wait, rc)``."""
+    a = np.ascontiguousarray(np.asarray(ts), dtype=np.int64)
+    if a.ndim != 3:
+        raise ValueError("ts must have shape [B, P, R]")
+    B, P, R = a.shape
+    barrier = np.zeros(B, dtype=np.int64)
+    iters = np.zeros((B, P), dtype=np.int32)
+    wait = np.zeros(B, dtype=np.int64)
+    i64p = ctypes.POINTER(ctypes.c_int64)
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    rc = _load().ebsp_zipline_oracle(a.ctypes.data_as(i64p), B, P, R, barrier.ctypes.data_as(i64p),
+                                     iters.ctypes.data_as(i32p), wait.ctypes.data_as(i64p), int(threads))
+    return barrier, iters, wait, int(rc)
 
 
 def predicted_rows(last_end, interval, R: int) -> np.ndarray:

@@ -291,3 +291,15 @@ int zl_oracle_batch(const int64_t *ts, int64_t B, int32_t P, int32_t R,
         *threads_used = used;
     return worst;
 }
+
+/* ------------------------------------------------------------------ */
+/* The entry point declared in include/ebsp_zipline_oracle.h: the sweep
+ * route over a batch, host pointers, `threads` worker threads (<= 0: the
+ * library default).  Returns 0, or the largest per-instance code (1: some
+ * row of some instance is not non-decreasing, its outputs stay untouched;
+ * 2: invalid arguments). */
+int ebsp_zipline_oracle(const int64_t *ts, int64_t B, int32_t P, int32_t R,
+                        int64_t *barrier, int32_t *iters, int64_t *wait, int32_t threads)
+{
+    return zl_oracle_batch(ts, B, P, R, barrier, iters, wait, NULL, 0, threads, NULL);
+}
