@@ -206,6 +206,35 @@ int ebsp_zipline_range_batch(const int64_t* ts, int64_t B, int32_t P, int32_t R,
                              void* stream);
 
 /*
+ * GridScan and FullGridScan, the paper's own comparators of the search (Section
+ * IV: "GridScan", Algorithm 1, and the paragraph "FullGridScan"; Table I for
+ * their cost, Table II for the comparison with ZipLine).  For a designated
+ * point e of a designated row, Z holds e and every other row's point at the
+ * shortest distance to e, and d_Z = max(Z) - min(Z) as in Section III.
+ * full == 0 (GridScan): the row with the smallest first timestamp is
+ * designated and the smallest d_Z over its R points is kept.  full != 0
+ * (FullGridScan): every row is designated in turn (n*R sets).  Both are
+ * heuristics for ebsp_zipline_range_batch's exact dmin: dz >= dmin always.
+ *
+ *   ts       in   [B][P][R] int64 device, every row non-decreasing; not modified
+ *   barrier  out  [B] int64: max(Z*);  dz out [B] int64: d_Z* (>= 0)
+ *   iters    out  [B][P] int32: 1 + the index in row p of the point Z* holds
+ *   status   out  [B] int32 or NULL: EBSP_STATUS_UNSORTED if a row is not
+ *                 non-decreasing (outputs then unspecified), else 0
+ *   workspace     at least ebsp_gridscan_workspace_bytes(B, P, R, full) bytes,
+ *                 256-byte aligned
+ * Readings where the paper is silent: of two points of a row equally near to e
+ * (and of equal timestamps) the earlier one is taken; of rows with the same
+ * smallest first timestamp the first is designated; of equal d_Z the set met
+ * first in (row, point) order is kept.  Precondition: max t - min t fits int64.
+ * Asynchronous on `stream`, allocates nothing; return codes as above.
+ */
+size_t ebsp_gridscan_workspace_bytes(int64_t B, int32_t P, int32_t R, int32_t full);
+int ebsp_gridscan_batch(const int64_t* ts, int64_t B, int32_t P, int32_t R, int32_t full,
+                        int64_t* barrier, int32_t* iters, int64_t* dz, int32_t* status,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * How a shape is handled (for benchmarks' byte models; HOST array of 5):
  * info[0] = 1 if instances are cut into windows (0: one workgroup each),
  * info[1] = records per window workgroup, info[2] = fine bins per instance,

@@ -37,6 +37,7 @@
 //   zl_range.h     the objective max(Z) - min(Z)
 //   zl_finish.h    reduction over windows, zl_iters; the copy yardstick
 //   zl_sweep.h     the frontier sweep: stored rows searched in one pass, no crossing table
+//   zl_gridscan.h  GridScan and FullGridScan, the paper's comparators
 // This file: the host side (plans, launches, the C entry points).
 #include <hip/hip_runtime.h>
 #include <atomic>
@@ -45,7 +46,7 @@
 #include <string.h>
 
 #include "ebsp_zipline.h"
-#include "zl_sweep.h"       // pulls in the other device headers, in dependency order
+#include "zl_gridscan.h"    // pulls in the other device headers, in dependency order
 
 namespace {
 
@@ -80,12 +81,13 @@ int check_device()
 }
 
 enum KernelId { K_INSTANCE = 0, K_INSTANCE_GENERAL, K_BOUNDS, K_PARTITION, K_BINCOUNT, K_PLAN, K_WINDOW,
-                K_WINDOW_GENERAL, K_FINISH, K_COPY, K_RANGE_INSTANCE, K_RANGE_WINDOW, K_PARTITION_PRED, K_RANGE_FAST, K_ADVANCE, K_SWEEP, K_SWEEP_FINISH, K_COUNT };
+                K_WINDOW_GENERAL, K_FINISH, K_COPY, K_RANGE_INSTANCE, K_RANGE_WINDOW, K_PARTITION_PRED, K_RANGE_FAST, K_ADVANCE, K_SWEEP, K_SWEEP_FINISH, K_GRIDSCAN, K_GRIDSCAN_FINISH, K_COUNT };
 const char* const kKernelNames[K_COUNT] = {
     "zl_instance_kernel", "zl_instance_general_kernel", "zl_bounds_kernel", "zl_partition_kernel",
     "zl_bincount_kernel", "zl_plan_kernel", "zl_window_kernel", "zl_window_general_kernel",
     "zl_finish_kernel", "zl_copy_kernel", "zl_range_instance_kernel", "zl_range_window_kernel",
-    "zl_partition_pred_kernel", "zl_range_fast_kernel", "zl_advance_kernel", "zl_sweep_kernel", "zl_sweep_finish_kernel"};
+    "zl_partition_pred_kernel", "zl_range_fast_kernel", "zl_advance_kernel", "zl_sweep_kernel", "zl_sweep_finish_kernel", "zl_gridscan_kernel",
+    "zl_gridscan_finish_kernel"};
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -615,6 +617,36 @@ int ebsp_simulate_supersteps(const int64_t* last_end0, const int64_t* interval, 
                    (const i64*)barrier + s * B, (const int*)flags, from, start, (i64)sync_cost, B, P);
         if (g_prof.on && g_prof.calls < g_prof.max_calls) ++g_prof.calls;
     }
+    return EBSP_OK;
+}
+
+size_t ebsp_gridscan_workspace_bytes(int64_t B, int32_t P, int32_t R, int32_t full)
+{
+    if (B < 0 || P < 1 || R < 1 || (i64)P * R >= (1ll << 31)) return 0;
+    return align_up((size_t)B * (full ? (size_t)P : 1) * sizeof(GridBest), 256);
+}
+
+int ebsp_gridscan_batch(const int64_t* ts, int64_t B, int32_t P, int32_t R, int32_t full,
+                        int64_t* barrier, int32_t* iters, int64_t* dz, int32_t* status,
+                        void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (B < 0 || P < 1 || R < 1 || (i64)P * R >= (1ll << 31))
+        return fail(EBSP_ERR_SHAPE, "invalid shape: need B >= 0, P >= 1, R >= 1, P*R < 2^31");
+    if (B == 0) return EBSP_OK;
+    if (!ts || !barrier || !iters || !dz) return fail(EBSP_ERR_NULL, "ts, barrier, iters and dz must not be NULL");
+    const i64 blocks = B * (full ? (i64)P : 1);
+    if (blocks > 0x7fffffffll) return fail(EBSP_ERR_SHAPE, "batch too large for one call");
+    if (!workspace) return fail(EBSP_ERR_NULL, "the scans need a workspace");
+    if (workspace_bytes < ebsp_gridscan_workspace_bytes(B, P, R, full))
+        return fail(EBSP_ERR_WORKSPACE, "workspace smaller than ebsp_gridscan_workspace_bytes()");
+    if (((uintptr_t)workspace & 255u) != 0) return fail(EBSP_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    if (int rc = check_device()) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    GridBest* best = (GridBest*)workspace;
+    LAUNCH(K_GRIDSCAN, zl_gridscan_kernel, dim3((unsigned)blocks), dim3(GRID_NT), (const i64*)ts, P, R, full ? 1 : 0, best, status);
+    LAUNCH(K_GRIDSCAN_FINISH, zl_gridscan_finish_kernel, dim3((unsigned)B), dim3(GRID_NT), (const i64*)ts, P, R, full ? 1 : 0,
+           (const GridBest*)best, (i64*)barrier, iters, (i64*)dz);
+    if (g_prof.on && g_prof.calls < g_prof.max_calls) ++g_prof.calls;
     return EBSP_OK;
 }
 

@@ -171,6 +171,23 @@ def make_supersteps(k: int, S: int, instances: Optional[Iterable[int]] = None, j
     return le, iv
 
 
+def make_workers(P: int, R: int, n: int, tag: int = 0) -> np.ndarray:
+    """``n`` instances [n, P, R] of any shape, workers as in configuration 2 without its stragglers (mean iteration
+    time U[80, 120] ms, durations mu * LogNormal(0, 0.1), start offset U[0, mu)): the shapes of the paper's Table II
+    (10 to 1000 workers, 15 and 150 predicted iterations).  Instance b draws from
+    ``SeedSequence([SEED_BASE + 300 + tag, P, R, b])``."""
+    cfg = Config(0, int(n), int(P), int(R), 80.0, 120.0, "lognormal", 0.1, 0)
+    out = np.empty((int(n), int(P), int(R)), dtype=np.int64)
+    for b in range(int(n)):
+        rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([SEED_BASE + 300 + int(tag), int(P), int(R), b])))
+        mu = rng.uniform(cfg.mu_lo, cfg.mu_hi, cfg.P)
+        d = mu[:, None] * rng.lognormal(0.0, cfg.sigma, (cfg.P, cfg.R))
+        off = rng.random(cfg.P) * mu
+        d_us = np.maximum(np.rint(d * 1000.0), 1.0).astype(np.int64)
+        out[b] = np.rint(off * 1000.0).astype(np.int64)[:, None] + np.cumsum(d_us, axis=1)
+    return out
+
+
 def random_small(rng: np.random.Generator, P: int, R: int, lo: int = 1, hi: int = 20,
                  ties: bool = False) -> np.ndarray:
     """A small random instance [P, R]: cumulative sums of integer steps in [lo, hi].

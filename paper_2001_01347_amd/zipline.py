@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libebsp_zipline.so")
 EBSP_OK = 0
 STATUS_OK, STATUS_UNSORTED, STATUS_OVERFLOW, STATUS_UNSUPPORTED = 0, 1, 2, 4
 
-EXPORTS = ("ebsp_zipline_workspace_bytes", "ebsp_predict_zipline_workspace_bytes", "ebsp_zipline_tune_sweep", "ebsp_zipline_batch", "ebsp_zipline_batch_static",
+EXPORTS = ("ebsp_gridscan_workspace_bytes", "ebsp_gridscan_batch", "ebsp_zipline_workspace_bytes", "ebsp_predict_zipline_workspace_bytes", "ebsp_zipline_tune_sweep", "ebsp_zipline_batch", "ebsp_zipline_batch_static",
            "ebsp_zipline_static_scratch_bytes", "ebsp_zipline_range_workspace_bytes",
            "ebsp_zipline_range_batch", "ebsp_predict_zipline_batch", "ebsp_simulate_workspace_bytes",
            "ebsp_simulate_supersteps", "ebsp_zipline_tune", "ebsp_zipline_shape_info", "ebsp_zipline_profile_begin",
@@ -45,6 +45,10 @@ def load() -> ctypes.CDLL:
         vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
         lib.ebsp_zipline_workspace_bytes.restype = sz
         lib.ebsp_zipline_workspace_bytes.argtypes = [i64, i32, i32]
+        lib.ebsp_gridscan_workspace_bytes.restype = sz
+        lib.ebsp_gridscan_workspace_bytes.argtypes = [i64, i32, i32, i32]
+        lib.ebsp_gridscan_batch.restype = ctypes.c_int
+        lib.ebsp_gridscan_batch.argtypes = [vp, i64, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
         lib.ebsp_predict_zipline_workspace_bytes.restype = sz
         lib.ebsp_predict_zipline_workspace_bytes.argtypes = [i64, i32, i32]
         lib.ebsp_zipline_tune_sweep.restype = ctypes.c_int
@@ -207,6 +211,40 @@ def ebsp_zipline_range_batch(ts: torch.Tensor, barrier: Optional[torch.Tensor] =
     if rc != EBSP_OK:
         raise ZipLineError(f"ebsp_zipline_range_batch failed ({rc}): {ebsp_last_error()}")
     return outs
+
+
+def ebsp_gridscan_workspace_bytes(B: int, P: int, R: int, full: bool) -> int:
+    return int(load().ebsp_gridscan_workspace_bytes(B, P, R, 1 if full else 0))
+
+
+def ebsp_gridscan_batch(ts: torch.Tensor, full: bool = False, barrier: Optional[torch.Tensor] = None,
+                        iters: Optional[torch.Tensor] = None, dz: Optional[torch.Tensor] = None,
+                        status: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None):
+    """GridScan (``full=False``) or FullGridScan (``full=True``), the paper's comparators; see the header.
+
+    Returns ``(barrier[B], iters[B, P], dz[B], status[B])`` device tensors.  Does not synchronise.
+    """
+    B, P, R = _check(ts)
+    dev = ts.device
+    if barrier is None:
+        barrier = torch.empty(B, dtype=torch.int64, device=dev)
+    if iters is None:
+        iters = torch.empty((B, P), dtype=torch.int32, device=dev)
+    if dz is None:
+        dz = torch.empty(B, dtype=torch.int64, device=dev)
+    if status is None:
+        status = torch.empty(B, dtype=torch.int32, device=dev)
+    need = ebsp_gridscan_workspace_bytes(B, P, R, full)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    with torch.cuda.device(dev):
+        rc = load().ebsp_gridscan_batch(ts.data_ptr(), B, P, R, 1 if full else 0, barrier.data_ptr(), iters.data_ptr(),
+                                        dz.data_ptr(), status.data_ptr(), workspace.data_ptr(),
+                                        workspace.numel() * workspace.element_size(),
+                                        torch.cuda.current_stream(dev).cuda_stream)
+    if rc != EBSP_OK:
+        raise ZipLineError(f"ebsp_gridscan_batch failed ({rc}): {ebsp_last_error()}")
+    return barrier, iters, dz, status
 
 
 def ebsp_predict_zipline_batch(last_end: torch.Tensor, interval: torch.Tensor, R: int,
