@@ -46,6 +46,7 @@
 #include <string.h>
 
 #include "ebsp_zipline.h"
+#include "ebsp_zipline_bench.h"
 #include "zl_gridscan.h"    // pulls in the other device headers, in dependency order
 
 namespace {

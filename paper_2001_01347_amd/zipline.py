@@ -1,4 +1,4 @@
-"""ctypes binding of libebsp_zipline.so (see include/ebsp_zipline.h).
+"""ctypes binding of libebsp_zipline.so (see include/ebsp_zipline.h and include/ebsp_zipline_bench.h).
 
 Argument marshalling only: every step of the search runs in the HIP kernels.
 PyTorch supplies device memory (``torch.empty``) and the current stream.  The
@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libebsp_zipline.so")
 
 EBSP_OK = 0
-STATUS_OK, STATUS_UNSORTED, STATUS_OVERFLOW, STATUS_UNSUPPORTED = 0, 1, 2, 4
+STATUS_OK, STATUS_UNSORTED, STATUS_OVERFLOW = 0, 1, 2
 
 EXPORTS = ("ebsp_gridscan_workspace_bytes", "ebsp_gridscan_batch", "ebsp_zipline_workspace_bytes", "ebsp_predict_zipline_workspace_bytes", "ebsp_zipline_tune_sweep", "ebsp_zipline_batch", "ebsp_zipline_batch_static",
            "ebsp_zipline_static_scratch_bytes", "ebsp_zipline_range_workspace_bytes",
@@ -135,6 +135,41 @@ def ebsp_zipline_kernel_names() -> Tuple[str, ...]:
     return tuple(lib.ebsp_zipline_kernel_name(i).decode() for i in range(lib.ebsp_zipline_kernel_count()))
 
 
+def _check_buffer(name: str, t: torch.Tensor, dev: torch.device, dtype: torch.dtype, shape) -> None:
+    """A caller-supplied output must be exactly what the kernels will write: anything else would be written out of
+    bounds, or at a host address."""
+    if not isinstance(t, torch.Tensor) or t.device != dev or t.dtype != dtype or tuple(t.shape) != tuple(shape) \
+            or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous {dtype} tensor of shape {tuple(shape)} on {dev}")
+
+
+def _check_workspace(ws: Optional[torch.Tensor], dev: torch.device, need: int) -> None:
+    if ws is None:
+        if need:
+            raise ValueError(f"this shape needs a workspace of {need} bytes")
+        return
+    if not isinstance(ws, torch.Tensor) or ws.device != dev or ws.dtype != torch.uint8 or ws.dim() != 1 \
+            or not ws.is_contiguous() or ws.numel() < need:
+        raise ValueError(f"workspace must be a contiguous 1-D uint8 tensor of at least {need} bytes on {dev}")
+    if ws.data_ptr() % 256:
+        raise ValueError("workspace must be 256-byte aligned")
+
+
+def _outputs(dev, B, P, barrier, iters, third, status, lead=()):
+    """The four outputs: new tensors where none is given, checked ones where the caller supplies them."""
+    shapes = (lead + (B,), lead + (B, P), lead + (B,), lead + (B,))
+    dtypes = (torch.int64, torch.int32, torch.int64, torch.int32)
+    names = ("barrier", "iters", "wait", "status")
+    out = []
+    for name, t, shape, dtype in zip(names, (barrier, iters, third, status), shapes, dtypes):
+        if t is None:
+            t = torch.empty(shape, dtype=dtype, device=dev)
+        else:
+            _check_buffer(name, t, dev, dtype, shape)
+        out.append(t)
+    return out
+
+
 def _check(ts: torch.Tensor) -> Tuple[int, int, int]:
     if ts.dim() != 3 or ts.dtype != torch.int64 or not ts.is_cuda or not ts.is_contiguous():
         raise ValueError("ts must be a contiguous int64 CUDA tensor of shape [B, P, R]")
@@ -144,17 +179,11 @@ def _check(ts: torch.Tensor) -> Tuple[int, int, int]:
 def _prepare(ts, barrier, iters, wait, status, workspace, workspace_bytes=None):
     B, P, R = _check(ts)
     dev = ts.device
-    if barrier is None:
-        barrier = torch.empty(B, dtype=torch.int64, device=dev)
-    if iters is None:
-        iters = torch.empty((B, P), dtype=torch.int32, device=dev)
-    if wait is None:
-        wait = torch.empty(B, dtype=torch.int64, device=dev)
-    if status is None:
-        status = torch.empty(B, dtype=torch.int32, device=dev)
+    barrier, iters, wait, status = _outputs(dev, B, P, barrier, iters, wait, status)
     need = (workspace_bytes or ebsp_zipline_workspace_bytes)(B, P, R)
     if workspace is None and need:
         workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    _check_workspace(workspace, dev, need)
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
     stream = torch.cuda.current_stream(dev).cuda_stream
@@ -189,6 +218,7 @@ def ebsp_zipline_batch_static(ts: torch.Tensor, barrier: torch.Tensor, iters: to
     """``ebsp_zipline_batch`` on the library's own static scratch: nothing is allocated, here or in the library,
     so the caller passes every output.  Returns ``(barrier, iters, wait, status)``.  Does not synchronise."""
     B, P, R = _check(ts)
+    barrier, iters, wait, status = _outputs(ts.device, B, P, barrier, iters, wait, status)
     with torch.cuda.device(ts.device):
         rc = load().ebsp_zipline_batch_static(ts.data_ptr(), B, P, R, barrier.data_ptr(), iters.data_ptr(), wait.data_ptr(),
                                               status.data_ptr(), torch.cuda.current_stream(ts.device).cuda_stream)
@@ -226,17 +256,11 @@ def ebsp_gridscan_batch(ts: torch.Tensor, full: bool = False, barrier: Optional[
     """
     B, P, R = _check(ts)
     dev = ts.device
-    if barrier is None:
-        barrier = torch.empty(B, dtype=torch.int64, device=dev)
-    if iters is None:
-        iters = torch.empty((B, P), dtype=torch.int32, device=dev)
-    if dz is None:
-        dz = torch.empty(B, dtype=torch.int64, device=dev)
-    if status is None:
-        status = torch.empty(B, dtype=torch.int32, device=dev)
+    barrier, iters, dz, status = _outputs(dev, B, P, barrier, iters, dz, status)
     need = ebsp_gridscan_workspace_bytes(B, P, R, full)
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    _check_workspace(workspace, dev, need)
     with torch.cuda.device(dev):
         rc = load().ebsp_gridscan_batch(ts.data_ptr(), B, P, R, 1 if full else 0, barrier.data_ptr(), iters.data_ptr(),
                                         dz.data_ptr(), status.data_ptr(), workspace.data_ptr(),
@@ -264,17 +288,11 @@ def ebsp_predict_zipline_batch(last_end: torch.Tensor, interval: torch.Tensor, R
     B, P = (int(x) for x in last_end.shape)
     R = int(R)
     dev = last_end.device
-    if barrier is None:
-        barrier = torch.empty(B, dtype=torch.int64, device=dev)
-    if iters is None:
-        iters = torch.empty((B, P), dtype=torch.int32, device=dev)
-    if wait is None:
-        wait = torch.empty(B, dtype=torch.int64, device=dev)
-    if status is None:
-        status = torch.empty(B, dtype=torch.int32, device=dev)
+    barrier, iters, wait, status = _outputs(dev, B, P, barrier, iters, wait, status)
     need = ebsp_predict_zipline_workspace_bytes(B, P, R)
     if workspace is None and need:
         workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    _check_workspace(workspace, dev, need)
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
     with torch.cuda.device(dev):
@@ -309,17 +327,11 @@ def ebsp_simulate_supersteps(last_end0: torch.Tensor, interval: torch.Tensor, R:
     S, B, P = (int(x) for x in interval.shape)
     R = int(R)
     dev = last_end0.device
-    if barrier is None:
-        barrier = torch.empty((S, B), dtype=torch.int64, device=dev)
-    if iters is None:
-        iters = torch.empty((S, B, P), dtype=torch.int32, device=dev)
-    if wait is None:
-        wait = torch.empty((S, B), dtype=torch.int64, device=dev)
-    if status is None:
-        status = torch.empty((S, B), dtype=torch.int32, device=dev)
+    barrier, iters, wait, status = _outputs(dev, B, P, barrier, iters, wait, status, lead=(S,))
     need = ebsp_simulate_workspace_bytes(B, P, R)
     if workspace is None and need:
         workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    _check_workspace(workspace, dev, need)
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
     with torch.cuda.device(dev):

@@ -8,7 +8,8 @@ import re
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "ebsp_zipline.h")
+HEADERS = [os.path.join(ROOT, "include", "ebsp_zipline.h"), os.path.join(ROOT, "include", "ebsp_zipline_bench.h")]
+ORACLE_HEADER = os.path.join(ROOT, "include", "ebsp_zipline_oracle.h")
 
 
 @pytest.fixture(scope="module")
@@ -20,7 +21,7 @@ def lib():
 
 
 def declared_functions():
-    text = open(HEADER).read()
+    text = "".join(open(h).read() for h in HEADERS)
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(ebsp_[a-z_]+)\s*\(", text)))
 
@@ -32,6 +33,42 @@ def test_header_symbols_are_exported(lib):
     for n in names:
         assert hasattr(lib, n), f"{n} declared in the header but not exported"
     assert sorted(zipline.EXPORTS) == names
+
+
+def test_headers_are_plain_c(tmp_path):
+    # the boundary is a C ABI: every header must compile as C11 on its own, and a C program that uses it must link
+    import subprocess
+    for h in HEADERS + [ORACLE_HEADER]:
+        src = tmp_path / (os.path.basename(h) + ".c")
+        src.write_text(f'#include "{h}"\nint main(void) {{ return 0; }}\n')
+        subprocess.run(["gcc", "-std=c11", "-Wall", "-Wextra", "-Wpedantic", "-Werror", "-fsyntax-only", str(src)], check=True)
+    # a C caller of the oracle's entry point, linked against the oracle library
+    import oracle
+    lib_path = oracle.build()
+    prog = tmp_path / "call_oracle.c"
+    prog.write_text(f"""#include "{ORACLE_HEADER}"
+#include <stdio.h>
+int main(void) {{
+    const int64_t ts[2 * 3] = {{10, 20, 30, 14, 29, 44}};
+    int64_t barrier = 0, wait = 0; int32_t iters[2] = {{0, 0}};
+    int rc = ebsp_zipline_oracle(ts, 1, 2, 3, &barrier, iters, &wait, 1);
+    printf("%d %lld %lld %d %d\\n", rc, (long long)barrier, (long long)wait, iters[0], iters[1]);
+    return 0;
+}}
+""")
+    exe = tmp_path / "call_oracle"
+    subprocess.run(["gcc", "-std=c11", "-Wall", "-Werror", str(prog), lib_path, "-fopenmp", f"-Wl,-rpath,{os.path.dirname(lib_path)}",
+                    "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    assert out == ["0", "30", "1", "3", "2"]        # the two-worker example worked by hand in tests/golden/worked_examples.json
+
+
+def test_oracle_library_exports_its_header(oracle):
+    text = re.sub(r"/\*.*?\*/", "", open(ORACLE_HEADER).read(), flags=re.S)
+    names = sorted(set(re.findall(r"\b(ebsp_[a-z_]+)\s*\(", text)))
+    assert names == ["ebsp_zipline_oracle"]
+    lib = ctypes.CDLL(oracle.build())
+    assert hasattr(lib, "ebsp_zipline_oracle")
 
 
 def test_kernel_names(lib):
@@ -125,6 +162,34 @@ def test_binding_refuses_cpu_tensors():
     from paper_2001_01347_amd import zipline
     with pytest.raises(ValueError):
         zipline.ebsp_zipline_batch(torch.zeros((1, 2, 3), dtype=torch.int64))
+
+
+def test_binding_checks_the_buffers_it_is_given():
+    # device, dtype, shape and contiguity of every caller-supplied output, and the workspace, are checked before
+    # their addresses go to the library (a wrong buffer would be written out of bounds by a kernel)
+    import torch
+    from paper_2001_01347_amd import zipline
+    check = zipline._check_buffer
+    dev = torch.device("cpu")
+    good = torch.zeros((3, 4), dtype=torch.int32)
+    check("iters", good, dev, torch.int32, (3, 4))
+    for bad in (torch.zeros((3, 4), dtype=torch.int64), torch.zeros((4, 3), dtype=torch.int32),
+                torch.zeros((3, 8), dtype=torch.int32)[:, ::2], torch.zeros(12, dtype=torch.int32)):
+        with pytest.raises(ValueError):
+            check("iters", bad, dev, torch.int32, (3, 4))
+    with pytest.raises(ValueError):
+        check("iters", good, torch.device("meta"), torch.int32, (3, 4))
+    ws = zipline._check_workspace
+    raw = torch.zeros(2048, dtype=torch.uint8)
+    skew = (-raw.data_ptr()) % 256
+    ws(raw[skew:skew + 1024], dev, 1000)
+    with pytest.raises(ValueError):
+        ws(raw[skew + 8:skew + 1032], dev, 1000)        # not 256-byte aligned
+    ws(None, dev, 0)
+    for bad, need in ((raw[skew:skew + 512], 1000), (torch.zeros(1024, dtype=torch.int32), 16),
+                      (None, 1), (torch.zeros(2048, dtype=torch.uint8)[::2], 16)):
+        with pytest.raises(ValueError):
+            ws(bad, dev, need)
 
 
 def test_plan_of_a_shape_and_the_tuning_knobs(lib):
