@@ -87,109 +87,6 @@ __device__ __forceinline__ Smem carve_hot(unsigned char* smem)
     return s;
 }
 
-// Monotone maps of keys onto value buckets [0, NB).
-// LinearMap: bucket = (key * scale) >> 32, equal slices of [0, span]; right when the
-// keys are spread evenly, as inside a window of the multi-window path.
-// (Keys beyond the span only occur in unsorted rows; the clamps keep those in bounds.)
-struct LinearMap {
-    u32 scale, top;
-    u32 span;      // largest key of sorted rows
-    u64 inv52;     // floor(2^52 / scale)
-    static constexpr bool HAS_BOUNDS = true;
-    __device__ __forceinline__ u32 operator()(u32 key) const
-    {
-        const u32 b = (u32)(((u64)key * scale) >> 32);
-        return b < top ? b : top;
-    }
-    // lo <= every key of bucket b <= hi (for keys within [0, span]).  A key k of bucket
-    // b < top has b * 2^32 <= k * scale < (b + 1) * 2^32; inv52 is at most one short of
-    // 2^52 / scale, which costs less than 2 after the shift (b + 1 <= 2^11).
-    __device__ __forceinline__ void bounds(u32 b, u32& lo, u32& hi) const
-    {
-        const u64 l = ((u64)b * inv52) >> 20;
-        const u64 h = (((u64)(b + 1) * inv52) >> 20) + 2;
-        hi = (b >= top || h > span) ? span : (u32)h;
-        lo = l > hi ? hi : (u32)l;
-    }
-    // The same for buckets b and b + 1 with one product: floor((b + 1) * x) >= floor(b * x) +
-    // floor(x), and a bucket is less than floor(x) + 2 wide (x = inv52 / 2^20).
-    __device__ __forceinline__ void bounds_pair(u32 b, u32& lo0, u32& hi0, u32& lo1, u32& hi1) const
-    {
-        const u64 step = inv52 >> 20;
-        const u64 l0 = ((u64)b * inv52) >> 20, l1 = l0 + step;
-        const u64 h0 = l0 + step + 4, h1 = l1 + step + 4;
-        hi0 = h0 > span ? span : (u32)h0;
-        hi1 = (b + 1 >= top || h1 > span) ? span : (u32)h1;
-        lo0 = l0 > hi0 ? hi0 : (u32)l0;
-        lo1 = l1 > hi1 ? hi1 : (u32)l1;
-    }
-};
-__device__ __forceinline__ u32 linear_scale(u64 span, u32 nb)
-{
-    const u64 q = ((u64)nb << 32) / (span + 1);
-    return q >= 0xffffffffull ? 0xffffffffu : (q ? (u32)q : 1u);
-}
-__device__ __forceinline__ LinearMap linear_map(u32 span, u32 nb, u32 scale, u64 inv52)
-{
-    LinearMap m;
-    m.scale = scale;
-    m.top = nb - 1;
-    m.span = span;
-    m.inv52 = inv52;
-    return m;
-}
-// TableMap: piecewise linear through up to 256 coarse bins of width 2^cshift, each
-// given a share of the buckets in proportion to its key count, so that buckets
-// hold about the same number of keys even where the density of keys varies (a
-// whole instance: many workers early in the value range, few stragglers late).
-// tab[c] = first bucket of coarse bin c | (buckets of bin c scaled by 2^(32-cshift)) << 32.
-template <bool BOUNDS>       // whether the caller wants to drop buckets by their bounds
-struct TableMap {
-    const u64* tab;     // 256 entries, followed by 256 of: buckets of the bin << 52 | floor(2^52 / multiplier)
-    u32 cshift, cmask;
-    u32 span;           // largest key of sorted rows
-    static constexpr bool HAS_BOUNDS = BOUNDS;
-    __device__ __forceinline__ u32 coarse(u32 key) const { const u32 c = key >> cshift; return c < 255u ? c : 255u; }
-    __device__ __forceinline__ u32 operator()(u32 key) const
-    {
-        const u64 e = tab[coarse(key)];
-        return (u32)e + (u32)(((u64)(key & cmask) * (e >> 32)) >> 32);
-    }
-    // lo <= every key of bucket b <= hi.  The bins that reach bucket b are consecutive:
-    // the lower bound comes from the first of them, the upper bound from the last; inside
-    // a bin the bucket is linear in the key's low bits, as for LinearMap.
-    __device__ __forceinline__ void bounds(u32 b, u32& lo, u32& hi) const
-    {
-        const u64* inv = tab + 256;
-        int l = 0, h = 255;
-        while (l < h) {                                    // last bin whose first bucket is <= b
-            const int m = (l + h + 1) >> 1;
-            if ((u32)tab[m] <= b) l = m; else h = m - 1;
-        }
-        const int chi = l;
-        l = 0; h = chi;
-        while (l < h) {                                    // first bin whose last bucket is >= b
-            const int m = (l + h) >> 1;
-            if ((u32)tab[m] + (u32)(inv[m] >> 52) > b) h = m; else l = m + 1;
-        }
-        const int clo = l;
-        const u64 ilo = inv[clo] & ((1ull << 52) - 1), ihi = inv[chi] & ((1ull << 52) - 1);
-        const u32 first_lo = (u32)tab[clo], first_hi = (u32)tab[chi];
-        const u32 rlo = b >= first_lo ? b - first_lo : 0u, rhi = b >= first_hi ? b - first_hi : 0u;   // below 2^11
-        u64 xl = ((u64)rlo * ilo) >> 20, xh = (((u64)(rhi + 1) * ihi) >> 20) + 2;
-        xl = xl > cmask ? cmask : xl;
-        xh = xh > cmask ? cmask : xh;
-        const u64 kh = ((u64)chi << cshift) + xh, kl = ((u64)clo << cshift) + xl;
-        hi = kh > span ? span : (u32)kh;
-        lo = kl > hi ? hi : (u32)kl;
-    }
-    __device__ __forceinline__ void bounds_pair(u32 b, u32& lo0, u32& hi0, u32& lo1, u32& hi1) const
-    {
-        bounds(b, lo0, hi0);
-        bounds(b + 1, lo1, hi1);
-    }
-};
-
 // The records of a window, held ITEMS per thread in registers (item j of thread t
 // is record j*NT + t, present if that is below `total`) -> first minimum
 // (wait, key) of P*key + W0 - S(key) over keys with a + key >= thr, W0 being the

@@ -7,10 +7,9 @@
 
 #include "ebsp_zipline.h"
 
-typedef unsigned long long u64;
-typedef unsigned int u32;
-typedef unsigned short u16;
-typedef long long i64;
+#define ZL_FN __host__ __device__ __forceinline__
+#include "zl_maps.h"
+
 
 namespace {
 
@@ -27,20 +26,6 @@ constexpr int SINGLE_MAX = LARGE_NT * LARGE_ITEMS;  // largest P*R one workgroup
 constexpr int GENERAL_GRID = 256;            // workgroups of a general-path kernel (one per CU)
 // A window workgroup holds up to `cap` records (4096, 8192 or 16384).  Windows are
 // packed, as full as that allows, out of fine bins that hold about cap/8 keys each.
-
-// Per-instance facts shared by the kernels of the multi-window path.
-struct InstInfo {
-    i64 base;    // min_p t[p][0]; all other values are relative to it
-    u64 range;   // max_p t[p][R-1] - base
-    u64 thr;     // max_p t[p][0] - base: earliest admissible barrier
-    u32 segshift; // segment of the fine-bin map that (v >> wshift) falls in: (v >> wshift) >> segshift
-    u32 wshift;  // 0 unless the range needs more than 32 bits
-    u32 nb;      // number of fine bins, bin(range) + 1
-    u32 nwin;    // number of windows (set by zl_plan)
-    u32 flags;   // EBSP_STATUS_* bits found so far
-    u32 wide_steps; // how often a row steps by 2^32 or more from one entry to the next (counted by zl_partition)
-};
-constexpr u32 WIDE_MARKS = 15;   // of those steps, as many are remembered per instance by the fine bin they end in
 
 struct Partial {  // best candidate of one window
     u64 wait;     // U64_MAX: the window has no admissible candidate
@@ -178,47 +163,6 @@ __device__ __forceinline__ void block_bounds(i64 a, i64 b, i64 c, i64* red, i64&
     }
     __syncthreads();
     amin = a; bmax = b; cmax = c;
-}
-
-__device__ __forceinline__ int bit_length(u64 x) { return x ? 64 - __clzll((long long)x) : 0; }
-
-// Fine-bin grid of an instance: a monotone map of relative values onto [0, nb).
-// x = v >> wshift runs over SEGS segments of 2^segshift values each; within segment s
-// the bin is (G[s] + offset * slope[s]) >> 32 with G[s + 1] = G[s] + 2^segshift *
-// slope[s] (32.32 fixed point), so the map is continuous and never decreases.
-// zl_bounds sets the slopes from an estimate of how many entries each segment holds
-// (rows taken as evenly spaced between their first and last value), so that bins
-// hold about the same number of entries wherever the rows are dense or sparse.
-constexpr int SEGS = 64;
-struct SegEntry {        // one segment of an instance's map
-    u64 G;
-    u32 slope;
-    u32 pad_;
-};
-__device__ __forceinline__ u32 fine_bin(u64 rel, const InstInfo& ii, const SegEntry* tab)
-{
-    if (rel > ii.range) rel = ii.range;              // only reachable for unsorted rows
-    const u32 x = (u32)(rel >> ii.wshift);
-    const u32 s = x >> ii.segshift;
-    const SegEntry e = tab[s];
-    const u32 k = (u32)((e.G + (u64)(x - (s << ii.segshift)) * e.slope) >> 32);
-    return k < ii.nb ? k : ii.nb - 1;
-}
-// Smallest relative value that falls in bin k or later (k < nb).
-__device__ __forceinline__ u64 fine_bin_start(u32 k, const InstInfo& ii, const SegEntry* tab)
-{
-    const u64 wmax = (1ull << ii.segshift) - 1;
-    const u64 want = (u64)k << 32;
-    int lo = 0, hi = SEGS - 1;                       // first segment whose last value reaches bin k
-    while (lo < hi) {
-        const int m = (lo + hi) >> 1;
-        const SegEntry e = tab[m];
-        if (((e.G + wmax * e.slope) >> 32) >= k) hi = m; else lo = m + 1;
-    }
-    const SegEntry e = tab[lo];
-    u64 off = 0;
-    if (want > e.G && e.slope) off = (want - e.G + e.slope - 1) / e.slope;
-    return (((u64)lo << ii.segshift) + off) << ii.wshift;
 }
 
 }  // namespace

@@ -125,14 +125,10 @@ __global__ __launch_bounds__(NT) void zl_instance_kernel(
 #pragma unroll
         for (int i = 0; i < CPT; ++i) {
             if (tid * CPT + i < H::COARSE) {
-                const u32 first = (u32)((u64)below_c * H::NB / (u32)n);
-                u32 last = (u32)((u64)(below_c + c[i]) * H::NB / (u32)n);    // first bucket of the next coarse bin
-                if (last > (u32)H::NB - 1) last = H::NB - 1;
-                u32 nbk = last >= first ? last - first + 1 : 1;                // buckets this bin spreads over
-                if (bucket.cshift < 32 && nbk > (1u << bucket.cshift)) nbk = 1u << bucket.cshift;
-                const u64 mult = bucket.cshift ? ((u64)nbk << (32 - bucket.cshift)) - 1 : 0ull;
-                tab[tid * CPT + i] = (u64)(first < (u32)H::NB ? first : (u32)H::NB - 1) | (mult << 32);
-                tab[H::COARSE + tid * CPT + i] = ((u64)nbk << 52) | (mult ? (1ull << 52) / mult : 0ull);
+                u64 tw, iw;
+                table_entry(below_c, c[i], (u32)n, (u32)H::NB, bucket.cshift, tw, iw);
+                tab[tid * CPT + i] = tw;
+                tab[H::COARSE + tid * CPT + i] = iw;
             }
             below_c += c[i];
         }

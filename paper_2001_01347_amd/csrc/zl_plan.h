@@ -98,9 +98,7 @@ __global__ __launch_bounds__(NT) void zl_bounds_kernel(
         u32 slope = 0;
         if (tid < nseg) {
             const u64 len = tid == nseg - 1 ? top - ((u64)tid << ii.segshift) + 1 : W;       // values of the segment in use
-            const double share = (double)(seg_est[tid] + even) / (double)total2 * (double)(bins - 1);
-            const double sl = share * 4294967296.0 / (double)len;
-            slope = sl < 4294967295.0 ? (u32)sl : 0xffffffffu;
+            slope = seg_slope_of(seg_est[tid], even, total2, bins, len);
         }
         seg_step[tid] = W * (u64)slope;
         seg_slope[tid] = slope;
