@@ -8,9 +8,19 @@ one synthetic batch that is already resident in HBM.  The default workload is
 the largest configuration (B=64 instances, P=1024 workers, R=4096 lookahead,
 268 435 456 int64 timestamps, 2 GiB).  Prints ONE JSON line with the
 throughput in timestamps/s (and instances/s), the roofline figures of the
-kernel that takes the most time (measured live with HIP events recorded around
-every kernel launch on the stream the kernels run on), and the CPU oracle
-timed on the host cores over a bounded sample of the same workload.
+kernel that takes the most time, and the CPU oracle timed on the host cores
+over a bounded sample of the same workload.
+
+Two passes over the same K steps: the first is the headline (wall clock around
+all K calls, plus one HIP event pair around every call on the launch stream:
+median and mean), with nothing recorded inside the library; the second repeats
+the K calls with a HIP event pair around every kernel launch and gives the
+per-kernel durations that the roofline figures use.
+
+``--table2`` runs the shapes of the paper's Table II instead (10, 100, 1000
+workers; 15 and 150 predicted iterations): ZipLine against GridScan and
+FullGridScan, their run times and how far the heuristics' d_Z is from the
+optimum.
 """
 from __future__ import annotations
 
@@ -79,11 +89,98 @@ def algorithmic_bytes(kernel: str, B: int, P: int, R: int, bins: int, windows: i
         return 8.0 * n + windows * (2.0 * cw * P + 16.0)
     if kernel == "zl_range_instance_kernel":
         return 8.0 * n + B * (16.0 + 4.0 * P)
+    if kernel == "zl_sweep_kernel":         # every timestamp once, one partial result per slice
+        return rows + 16.0 * windows
+    if kernel == "zl_sweep_finish_kernel":  # partial results; per row two probes of its entries, outputs
+        return 16.0 * windows + B * P * (64.0 * 2.0 + 4.0) + 16.0 * B
     if kernel == "zl_finish_kernel":        # window results; per row its crossing indices at the barrier's bin and two probes
         import math                         # (predicted rows: nothing is probed), outputs
         probes = 0.0 if predicted else 64.0 * 3.0
         return 16.0 * windows + B * P * (probes + 4.0) + 16.0 * B
     return 0.0
+
+
+# Table II of the paper (run time in microseconds on its 24-core Xeon server, mean of 10 trials): context only.
+PAPER_TABLE2_US = {   # (workers, R) -> (ZipLine, FullGridScan, GridScan)
+    (10, 15): (1.49e2, 1.54e3, 1.68e2), (10, 150): (1.32e3, 4.67e4, 5.50e3),
+    (100, 15): (6.37e3, 8.13e4, 1.11e3), (100, 150): (4.99e4, 2.15e6, 4.38e4),
+    (1000, 15): (2.53e5, 4.04e6, 7.45e3), (1000, 150): (2.38e6, 2.07e8, 2.57e5),
+}
+
+
+def table2(args) -> int:
+    """The comparison of Section V-A (Table II) on synthetic workers: per shape, a batch of instances searched by
+    ZipLine (the paper's objective max(Z) - min(Z), and the summed wait), GridScan and FullGridScan on the GPU."""
+    import numpy as np
+    import torch
+    import oracle
+    from paper_2001_01347_amd import workloads, zipline
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    rows, ok = [], True
+    n_inst = max(1, args.table2_instances)
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        ms = []
+        for _ in range(max(10, args.steps)):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            e1.synchronize()
+            ms.append(e0.elapsed_time(e1))
+        return float(np.median(ms)), float(np.mean(ms))
+
+    for P in (10, 100, 1000):
+        for R in (15, 150):
+            host = workloads.make_workers(P, R, n_inst)
+            ts = torch.from_numpy(host).to(dev)
+            res, times = {}, {}
+            for name, fn in (("zipline_range", lambda: zipline.ebsp_zipline_range_batch(ts)),
+                             ("zipline_sum", lambda: zipline.ebsp_zipline_batch(ts)),
+                             ("gridscan", lambda: zipline.ebsp_gridscan_batch(ts, False)),
+                             ("fullgridscan", lambda: zipline.ebsp_gridscan_batch(ts, True))):
+                out = fn()
+                torch.cuda.synchronize()
+                assert int(out[3].max().item()) == 0
+                res[name] = [t.cpu().numpy() for t in out[:3]]
+                times[name] = timed(fn)
+            opt, gs, fgs = res["zipline_range"][2], res["gridscan"][2], res["fullgridscan"][2]
+            # the oracle on a bounded sample (FullGridScan costs P^2 R log R per instance on the CPU)
+            n_cpu = max(1, min(n_inst, int(2e9 // (P * P * R * 8)) or 1))
+            c0 = time.perf_counter()
+            o_gs = oracle.gridscan(host[:n_cpu], False, "bisect")
+            o_fgs = oracle.gridscan(host[:n_cpu], True, "bisect")
+            o_opt = oracle.zipline_range(host[:n_cpu])
+            cpu_s = time.perf_counter() - c0
+            same = all(np.array_equal(a[i][:n_cpu], o[i]) for a, o in ((res["gridscan"], o_gs), (res["fullgridscan"], o_fgs),
+                                                                       (res["zipline_range"], o_opt)) for i in range(3))
+            ok &= bool(same) and bool((fgs <= gs).all()) and bool((opt <= fgs).all())
+            paper = PAPER_TABLE2_US[(P, R)]
+            rows.append({
+                "workers": P, "R": R, "instances": n_inst,
+                "us_per_instance": {k: v[0] * 1e3 / n_inst for k, v in times.items()},
+                "batch_ms_median": {k: v[0] for k, v in times.items()},
+                "batch_ms_mean": {k: v[1] for k, v in times.items()},
+                "d_Z_mean": {"zipline": float(opt.mean()), "gridscan": float(gs.mean()), "fullgridscan": float(fgs.mean())},
+                "d_Z_over_optimum_mean": {"gridscan": float((gs / np.maximum(opt, 1)).mean()),
+                                          "fullgridscan": float((fgs / np.maximum(opt, 1)).mean())},
+                "finds_optimum_frac": {"gridscan": float((gs == opt).mean()), "fullgridscan": float((fgs == opt).mean())},
+                "oracle": {"instances": n_cpu, "matches_gpu": bool(same), "seconds": cpu_s},
+                "paper_us_xeon": {"zipline": paper[0], "fullgridscan": paper[1], "gridscan": paper[2]},
+            })
+    print(json.dumps({"metric": "table2_search_time", "unit": "us/instance", "n_gpus": 1, "dtype": "int64", "data": "synthetic",
+                      "config": {"workload": f"Table II shapes, {n_inst} instances per shape in one batch, "
+                                             "workers with mean iteration time U[80,120] ms, LogNormal(0, 0.1) jitter"},
+                      "rows": rows}))
+    if not ok:
+        print("bench.py: a GPU result differs from the CPU oracle, or the heuristics beat the optimum", file=sys.stderr)
+        return 1
+    return 0
 
 
 def main() -> int:
@@ -107,6 +204,12 @@ def main() -> int:
     ap.add_argument("--copy-probe", type=int, default=3,
                     help="launches of the plain copy kernel (the input's size) after the timed region; "
                          "its bandwidth and byte counters are the yardstick for the others (0: skip)")
+    ap.add_argument("--table2", action="store_true",
+                    help="the shapes of the paper's Table II instead: ZipLine, GridScan and FullGridScan, times and d_Z")
+    ap.add_argument("--table2-instances", type=int, default=64, help="with --table2: instances per shape")
+    ap.add_argument("--sweep-min", type=int, default=0,
+                    help="tuning: smallest P*R searched by the frontier sweep (0: default, negative: never)")
+    ap.add_argument("--slice-keys", type=int, default=0, help="tuning: entries per slice of the frontier sweep (0: default)")
     ap.add_argument("--window-cap", type=int, default=0, help="tuning: records per window workgroup (0: default)")
     ap.add_argument("--window-fill", type=int, default=0, help="tuning: entries a window is filled to (0: default)")
     ap.add_argument("--single-max", type=int, default=0, help="tuning: largest P*R taken by one workgroup (0: default)")
@@ -117,11 +220,18 @@ def main() -> int:
               file=sys.stderr)
         return 2
 
+    if args.steps < 1 or args.warmup < 0:
+        print("bench.py: --steps must be at least 1 and --warmup at least 0", file=sys.stderr)
+        return 2
+    if args.table2:
+        return table2(args)
+
     import numpy as np
     import torch
     from paper_2001_01347_amd import workloads, zipline
 
     zipline.ebsp_zipline_tune(args.window_cap, args.single_max, args.window_fill)
+    zipline.ebsp_zipline_tune_sweep(args.sweep_min, args.slice_keys)
     cfg = workloads.CONFIGS[args.config]
     B, P, R = cfg.B, cfg.P, cfg.R
     n_keys = cfg.n_keys
@@ -158,6 +268,7 @@ def main() -> int:
     status = torch.empty(lead + (B,), dtype=torch.int32, device=dev)
     ranged = args.objective == "range"
     ws_bytes = (zipline.ebsp_simulate_workspace_bytes if S else zipline.ebsp_zipline_range_workspace_bytes if ranged
+                else zipline.ebsp_predict_zipline_workspace_bytes if args.predicted
                 else zipline.ebsp_zipline_workspace_bytes)(B, P, R)
     workspace = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
 
@@ -175,33 +286,54 @@ def main() -> int:
         step()
     torch.cuda.synchronize()
 
-    # timed region: K steps, per-kernel HIP events recorded inside the library on the launch stream
+    # pass 1, the headline: K steps with nothing recorded inside the library.  Wall clock around all of them
+    # (ms_per_step) and one HIP event pair per call on the launch stream (torch's current stream, the one the
+    # binding hands to the library): median and mean.
     searches = max(1, S)                    # searches (launches of every kernel of the search) per step
     n_keys *= searches                      # timestamps a step looks through
-    zipline.ebsp_zipline_profile_begin(args.steps * searches)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     torch.cuda.synchronize()
     w0 = time.perf_counter()
-    for _ in range(args.steps):
+    for e0, e1 in ev:
+        e0.record()
         step()
+        e1.record()
     torch.cuda.synchronize()
     w1 = time.perf_counter()
-    kernel_ms, calls = zipline.ebsp_zipline_profile_end()
-    assert calls == args.steps * searches
     ms_per_step = (w1 - w0) * 1e3 / args.steps
+    call_ms = sorted(e0.elapsed_time(e1) for e0, e1 in ev)
+    call_ms_median = call_ms[len(call_ms) // 2] if len(call_ms) % 2 else 0.5 * (call_ms[len(call_ms) // 2 - 1] + call_ms[len(call_ms) // 2])
+    call_ms_mean = sum(call_ms) / len(call_ms)
     assert int(status.max().item()) == 0, "the search flagged a data error on synthetic input"
 
-    # yardstick: a plain streaming copy of the same 8 B/key input (reads and writes n_keys * 8 bytes)
-    copy_gbs = None
+    # pass 2: the same K steps with a HIP event pair around every kernel launch (recorded inside the library on
+    # the launch stream): per-kernel durations for the roofline figures
+    zipline.ebsp_zipline_profile_begin(args.steps * searches)
+    for _ in range(args.steps):
+        step()
+    kernel_ms, calls = zipline.ebsp_zipline_profile_end()
+    assert calls == args.steps * searches
+
+    # yardsticks over the same 8 B/key input: a plain streaming copy (reads and writes n bytes) and a plain
+    # streaming read; and the peak that the device's own memory clock and bus width imply
+    copy_gbs = read_gbs = None
     if args.copy_probe > 0 and ts is not None:
+        nbytes = ts.numel() * 8
         dst = torch.empty_like(ts)
+        sink = torch.zeros(1, dtype=torch.int64, device=dev)
         zipline.ebsp_zipline_copy_probe(ts, dst)
+        zipline.ebsp_zipline_read_probe(ts, sink)
         torch.cuda.synchronize()
-        zipline.ebsp_zipline_profile_begin(args.copy_probe)
+        zipline.ebsp_zipline_profile_begin(2 * args.copy_probe)
         for _ in range(args.copy_probe):
             zipline.ebsp_zipline_copy_probe(ts, dst)
-        copy_ms, ncopy = zipline.ebsp_zipline_profile_end()
-        copy_gbs = 2.0 * 8.0 * n_keys / (copy_ms["zl_copy_kernel"] / ncopy * 1e-3) / 1e9
+            zipline.ebsp_zipline_read_probe(ts, sink)
+        probe_ms, nprobe = zipline.ebsp_zipline_profile_end()
+        copy_gbs = 2.0 * nbytes / (probe_ms["zl_copy_kernel"] / args.copy_probe * 1e-3) / 1e9
+        read_gbs = 1.0 * nbytes / (probe_ms["zl_read_kernel"] / args.copy_probe * 1e-3) / 1e9
         del dst
+    mem_khz, mem_bits = zipline.ebsp_zipline_memory_info()
+    device_peak_gbs = 2.0 * mem_khz * 1e3 * mem_bits / 8.0 / 1e9       # double data rate
 
     # shape-dependent constants of the multi-window path (for the byte model only)
     shape = zipline.ebsp_zipline_shape_info(B, P, R)
@@ -216,11 +348,13 @@ def main() -> int:
         fill -= shape["window_cap"] // (2 if P < 128 else 4)
     windows = B * ((P * R + fill - 1) // fill) if shape["multi"] else 0
     per_kernel = {k: v / calls for k, v in kernel_ms.items() if v > 0.0}      # per launch
+    if "zl_sweep_kernel" in per_kernel:     # the frontier sweep: one partial result per slice, no windows
+        windows = B * shape["slices"]
     dom = max(per_kernel, key=per_kernel.get)
     dom_bytes = algorithmic_bytes(dom, B, P, R, bins, windows, args.predicted)
     achieved = dom_bytes / (per_kernel[dom] * 1e-3) / 1e9
     counted = COUNTED_TRAFFIC.get((args.objective, bool(args.predicted), args.config))
-    tuned = bool(args.window_cap or args.single_max or args.window_fill)
+    tuned = bool(args.window_cap or args.single_max or args.window_fill or args.sweep_min or args.slice_keys)
     traffic = call_traffic = None
     if counted and counted[0] == dom and not tuned and not S and kernel_sources_sha256() == COUNTED_SOURCES_SHA256:
         traffic, call_traffic = float(counted[1]), float(counted[2])
@@ -234,7 +368,8 @@ def main() -> int:
         n_cpu = min(B, args.cpu_instances)
     else:
         n_cpu = max(1, min(B, int(1.7e7 * cores // (P * R * searches)) or 1))
-    n_one = max(1, n_cpu // cores)                          # the same oracle on one thread, a sixteenth of the sample
+    # the same oracle on one thread: the first min(B, 64) instances, fewer where those would take over ~20 s
+    n_one = max(1, min(B, 64, int(3.0e8 // (P * R * searches)) or 1))
     if S:
         oracle.simulate(le_host[:1], iv_host[:1, :1], R, args.sync_cost, threads=1)     # load the library
         c0 = time.perf_counter()
@@ -276,6 +411,9 @@ def main() -> int:
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": ms_per_step,
+        "call_ms_median": call_ms_median,
+        "call_ms_mean": call_ms_mean,
+        "call_ms_min": call_ms[0],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -302,8 +440,11 @@ def main() -> int:
         "cpu_baseline": {"value": cpu_rate, "unit": "timestamps/s", "cores": used, "kind": "oracle",
                          "sample": f"sweep oracle on the first {n_cpu} of {B} instances "
                                    f"({n_cpu * P * R * searches} timestamps), {c1 - c0:.2f} s wall",
-                         "matches_gpu": bool(same), "one_thread_value": cpu_rate_one, "cpu_model": cpu_model},
+                         "matches_gpu": bool(same), "one_thread_value": cpu_rate_one,
+                         "one_thread_sample": f"the first {n_one} instances, {one_s:.2f} s", "cpu_model": cpu_model},
         "copy_probe_GBs": copy_gbs,
+        "read_probe_GBs": read_gbs,
+        "device_memory": {"clock_khz": mem_khz, "bus_bits": mem_bits, "implied_peak_GBs": device_peak_gbs},
         "setup_s": gen_s,
     }
     print(json.dumps(out))

@@ -20,11 +20,13 @@ extern "C" {
 #endif
 
 /*
- * How a shape is handled (for benchmarks' byte models; HOST array of 5):
+ * How a shape is handled (for benchmarks' byte models; HOST array of 6):
  * info[0] = 1 if instances are cut into windows (0: one workgroup each),
  * info[1] = records per window workgroup, info[2] = fine bins per instance,
  * info[3] = upper bound of windows per instance, info[4] = entries a window
- * holds at most (all 0 when info[0] is 0).
+ * holds at most (all 0 when info[0] is 0); info[5] = slices per instance if
+ * ebsp_zipline_batch searches stored rows of this shape with the frontier
+ * sweep (0: it takes the path that info[0..4] describe).
  */
 int ebsp_zipline_shape_info(int64_t B, int32_t P, int32_t R, int64_t* info);
 
@@ -79,6 +81,21 @@ int ebsp_zipline_profile_end(float* kernel_ms, int32_t* calls);
  * Counts as one call of an open profile.
  */
 int ebsp_zipline_copy_probe(const void* src, void* dst, size_t bytes, void* stream);
+
+/*
+ * The same for kernels that mostly read: streams `bytes` (a positive multiple
+ * of 16; src 16-byte aligned device memory) through a sum and adds the sum of
+ * all 32-bit words to *sink (DEVICE, 8-byte aligned; the caller sets it to
+ * zero if the value matters).  Counts as one call of an open profile.
+ */
+int ebsp_zipline_read_probe(const void* src, size_t bytes, uint64_t* sink, void* stream);
+
+/*
+ * What the current device reports of its memory (HOST pointers): the memory
+ * clock in kHz and the bus width in bits, as hipDeviceGetAttribute gives them.
+ * With double data rate the peak they imply is 2 * clock * bus / 8 bytes/s.
+ */
+int ebsp_zipline_memory_info(int32_t* clock_khz, int32_t* bus_bits);
 
 /* Number of distinct kernels the library may launch, and their names
  * (static storage; NULL if i is out of range). */

@@ -82,13 +82,13 @@ int check_device()
 }
 
 enum KernelId { K_INSTANCE = 0, K_INSTANCE_GENERAL, K_BOUNDS, K_PARTITION, K_BINCOUNT, K_PLAN, K_WINDOW,
-                K_WINDOW_GENERAL, K_FINISH, K_COPY, K_RANGE_INSTANCE, K_RANGE_WINDOW, K_PARTITION_PRED, K_RANGE_FAST, K_ADVANCE, K_SWEEP, K_SWEEP_FINISH, K_GRIDSCAN, K_GRIDSCAN_FINISH, K_COUNT };
+                K_WINDOW_GENERAL, K_FINISH, K_COPY, K_RANGE_INSTANCE, K_RANGE_WINDOW, K_PARTITION_PRED, K_RANGE_FAST, K_ADVANCE, K_SWEEP, K_SWEEP_FINISH, K_GRIDSCAN, K_GRIDSCAN_FINISH, K_READ, K_COUNT };
 const char* const kKernelNames[K_COUNT] = {
     "zl_instance_kernel", "zl_instance_general_kernel", "zl_bounds_kernel", "zl_partition_kernel",
     "zl_bincount_kernel", "zl_plan_kernel", "zl_window_kernel", "zl_window_general_kernel",
     "zl_finish_kernel", "zl_copy_kernel", "zl_range_instance_kernel", "zl_range_window_kernel",
     "zl_partition_pred_kernel", "zl_range_fast_kernel", "zl_advance_kernel", "zl_sweep_kernel", "zl_sweep_finish_kernel", "zl_gridscan_kernel",
-    "zl_gridscan_finish_kernel"};
+    "zl_gridscan_finish_kernel", "zl_read_kernel"};
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -678,6 +678,8 @@ int ebsp_zipline_shape_info(int64_t B, int32_t P, int32_t R, int64_t* info)
     info[2] = pl.multi ? pl.bins : 0;
     info[3] = pl.multi ? pl.max_win : 0;
     info[4] = pl.multi ? pl.fill : 0;
+    Plan stored;
+    info[5] = make_plan(B, P, R, stored, SINGLE_MAX, false, true) && stored.sweep ? stored.nslices : 0;
     return EBSP_OK;
 }
 
@@ -715,6 +717,34 @@ int ebsp_zipline_copy_probe(const void* src, void* dst, size_t bytes, void* stre
     if (blocks > 256 * 32) blocks = 256 * 32;
     LAUNCH(K_COPY, zl_copy_kernel, dim3((unsigned)blocks), dim3(256), (const uint4*)src, (uint4*)dst, n);
     if (g_prof.on && g_prof.calls < g_prof.max_calls) ++g_prof.calls;
+    return EBSP_OK;
+}
+
+int ebsp_zipline_read_probe(const void* src, size_t bytes, uint64_t* sink, void* stream)
+{
+    if (!src || !sink) return fail(EBSP_ERR_NULL, "src and sink must not be NULL");
+    if (bytes == 0 || bytes % 16 != 0 || ((uintptr_t)src & 15u) || ((uintptr_t)sink & 7u))
+        return fail(EBSP_ERR_SHAPE, "read probe needs a positive multiple of 16 bytes, a 16-byte aligned source and an 8-byte aligned sink");
+    if (int rc = check_device()) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    const i64 n = (i64)(bytes / 16);
+    i64 blocks = (n + 255) / 256;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    LAUNCH(K_READ, zl_read_kernel, dim3((unsigned)blocks), dim3(256), (const uint4*)src, n, (u64*)sink);
+    if (g_prof.on && g_prof.calls < g_prof.max_calls) ++g_prof.calls;
+    return EBSP_OK;
+}
+
+int ebsp_zipline_memory_info(int32_t* clock_khz, int32_t* bus_bits)
+{
+    if (!clock_khz || !bus_bits) return fail(EBSP_ERR_NULL, "clock_khz and bus_bits must not be NULL");
+    int dev = 0, clk = 0, bus = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return fail(EBSP_ERR_DEVICE, "no current HIP device");
+    if (hipDeviceGetAttribute(&clk, hipDeviceAttributeMemoryClockRate, dev) != hipSuccess ||
+        hipDeviceGetAttribute(&bus, hipDeviceAttributeMemoryBusWidth, dev) != hipSuccess)
+        return fail(EBSP_ERR_DEVICE, "hipDeviceGetAttribute failed");
+    *clock_khz = clk;
+    *bus_bits = bus;
     return EBSP_OK;
 }
 

@@ -87,4 +87,25 @@ __global__ __launch_bounds__(256) void zl_copy_kernel(const uint4* __restrict__ 
     for (i64 i = (i64)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
 }
 
+// Plain streaming read of n 16-byte words, four loads in flight per lane; every workgroup
+// adds the sum of its words to *sink so that no load can be dropped.  The yardstick for
+// kernels that read far more than they write.
+__global__ __launch_bounds__(256) void zl_read_kernel(const uint4* __restrict__ src, i64 n, u64* __restrict__ sink)
+{
+    __shared__ u64 red[4];
+    const i64 stride = (i64)gridDim.x * blockDim.x;
+    i64 i = (i64)blockIdx.x * blockDim.x + threadIdx.x;
+    u64 acc = 0;
+    for (; i + 3 * stride < n; i += 4 * stride) {
+        const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+        acc += (u64)a.x + a.y + a.z + a.w + b.x + b.y + b.z + b.w + c.x + c.y + c.z + c.w + d.x + d.y + d.z + d.w;
+    }
+    for (; i < n; i += stride) {
+        const uint4 a = src[i];
+        acc += (u64)a.x + a.y + a.z + a.w;
+    }
+    acc = block_reduce<u64, 256>(acc, red, OpAdd());
+    if (threadIdx.x == 0) atomicAdd(sink, acc);
+}
+
 }  // namespace

@@ -24,7 +24,8 @@ EXPORTS = ("ebsp_gridscan_workspace_bytes", "ebsp_gridscan_batch", "ebsp_zipline
            "ebsp_zipline_static_scratch_bytes", "ebsp_zipline_range_workspace_bytes",
            "ebsp_zipline_range_batch", "ebsp_predict_zipline_batch", "ebsp_simulate_workspace_bytes",
            "ebsp_simulate_supersteps", "ebsp_zipline_tune", "ebsp_zipline_shape_info", "ebsp_zipline_profile_begin",
-           "ebsp_zipline_profile_end", "ebsp_zipline_copy_probe", "ebsp_zipline_kernel_count",
+           "ebsp_zipline_profile_end", "ebsp_zipline_copy_probe", "ebsp_zipline_read_probe", "ebsp_zipline_memory_info",
+           "ebsp_zipline_kernel_count",
            "ebsp_zipline_kernel_name", "ebsp_last_error")
 
 _lib = None
@@ -80,6 +81,10 @@ def load() -> ctypes.CDLL:
         lib.ebsp_zipline_profile_end.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
         lib.ebsp_zipline_copy_probe.restype = ctypes.c_int
         lib.ebsp_zipline_copy_probe.argtypes = [vp, vp, sz, vp]
+        lib.ebsp_zipline_read_probe.restype = ctypes.c_int
+        lib.ebsp_zipline_read_probe.argtypes = [vp, sz, vp, vp]
+        lib.ebsp_zipline_memory_info.restype = ctypes.c_int
+        lib.ebsp_zipline_memory_info.argtypes = [ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]
         lib.ebsp_zipline_kernel_count.restype = ctypes.c_int
         lib.ebsp_zipline_kernel_count.argtypes = []
         lib.ebsp_zipline_kernel_name.restype = ctypes.c_char_p
@@ -114,13 +119,13 @@ def ebsp_zipline_range_workspace_bytes(B: int, P: int, R: int) -> int:
 
 
 def ebsp_zipline_shape_info(B: int, P: int, R: int) -> Dict[str, int]:
-    """How the library handles a shape: {'multi', 'window_cap', 'bins', 'max_windows', 'window_fill'}."""
-    info = (ctypes.c_int64 * 5)()
+    """How the library handles a shape: {'multi', 'window_cap', 'bins', 'max_windows', 'window_fill', 'slices'}."""
+    info = (ctypes.c_int64 * 6)()
     rc = load().ebsp_zipline_shape_info(B, P, R, info)
     if rc != EBSP_OK:
         raise ZipLineError(f"ebsp_zipline_shape_info failed ({rc}): {ebsp_last_error()}")
     return {"multi": int(info[0]), "window_cap": int(info[1]), "bins": int(info[2]), "max_windows": int(info[3]),
-            "window_fill": int(info[4])}
+            "window_fill": int(info[4]), "slices": int(info[5])}
 
 
 def ebsp_zipline_tune(window_cap: int = 0, single_max: int = 0, window_fill: int = 0) -> None:
@@ -355,6 +360,27 @@ def ebsp_zipline_copy_probe(src: torch.Tensor, dst: torch.Tensor) -> None:
                                             torch.cuda.current_stream(src.device).cuda_stream)
     if rc != EBSP_OK:
         raise ZipLineError(f"ebsp_zipline_copy_probe failed ({rc}): {ebsp_last_error()}")
+
+
+def ebsp_zipline_read_probe(src: torch.Tensor, sink: torch.Tensor) -> None:
+    """Plain streaming device read of src on the current stream, summed into sink (one int64 on the device)."""
+    if not (src.is_cuda and src.is_contiguous() and sink.is_cuda and sink.dtype == torch.int64 and sink.numel() == 1
+            and sink.device == src.device):
+        raise ValueError("src must be a contiguous CUDA tensor and sink one int64 on the same device")
+    with torch.cuda.device(src.device):
+        rc = load().ebsp_zipline_read_probe(src.data_ptr(), src.numel() * src.element_size(), sink.data_ptr(),
+                                            torch.cuda.current_stream(src.device).cuda_stream)
+    if rc != EBSP_OK:
+        raise ZipLineError(f"ebsp_zipline_read_probe failed ({rc}): {ebsp_last_error()}")
+
+
+def ebsp_zipline_memory_info() -> Tuple[int, int]:
+    """(memory clock in kHz, memory bus width in bits) of the current device, as HIP reports them."""
+    clk, bus = ctypes.c_int32(0), ctypes.c_int32(0)
+    rc = load().ebsp_zipline_memory_info(ctypes.byref(clk), ctypes.byref(bus))
+    if rc != EBSP_OK:
+        raise ZipLineError(f"ebsp_zipline_memory_info failed ({rc}): {ebsp_last_error()}")
+    return int(clk.value), int(bus.value)
 
 
 def ebsp_zipline_profile_begin(max_calls: int) -> None:

@@ -199,7 +199,7 @@ def test_plan_of_a_shape_and_the_tuning_knobs(lib):
     tune = zipline.ebsp_zipline_tune
     try:
         tune(0, 0, 0)
-        assert info(4096, 16, 64) == {"multi": 0, "window_cap": 0, "bins": 0, "max_windows": 0, "window_fill": 0}
+        assert info(4096, 16, 64) == {"multi": 0, "window_cap": 0, "bins": 0, "max_windows": 0, "window_fill": 0, "slices": 0}
         big = info(64, 1024, 4096)              # many workers: 8192-record windows, filled to the brim
         assert big["multi"] == 1 and big["window_cap"] == 8192 and big["window_fill"] == 8192
         assert big["bins"] == 1024 * 4096 // 1024            # fine bins of window_cap / 8 keys on average

@@ -131,9 +131,16 @@ def test_outputs_and_workspace_passed_in_are_used(zl, oracle):
     ob, oi, ow, rc, _ = oracle.simulate(le, iv, R, 10, threads=16)
     assert np.array_equal(outs[0].cpu().numpy(), ob) and np.array_equal(outs[1].cpu().numpy(), oi)
     assert np.array_equal(outs[2].cpu().numpy(), ow) and (outs[3].cpu().numpy() == 0).all()
-    # a workspace that is too small, a negative synchronisation time: refused on the host, nothing runs
-    with pytest.raises(zl.ZipLineError):
+    # a workspace that is too small, outputs of the wrong type or shape (refused by the binding, before any address
+    # reaches the library), a negative synchronisation time (refused by the library): nothing runs
+    with pytest.raises(ValueError):
         zl.ebsp_simulate_supersteps(torch.from_numpy(le).cuda(), torch.from_numpy(iv).cuda(), R, 10, workspace=ws[:need - 256])
+    with pytest.raises(ValueError):
+        zl.ebsp_simulate_supersteps(torch.from_numpy(le).cuda(), torch.from_numpy(iv).cuda(), R, 10, outs[0].to(torch.int32))
+    with pytest.raises(ValueError):
+        zl.ebsp_simulate_supersteps(torch.from_numpy(le).cuda(), torch.from_numpy(iv).cuda(), R, 10, outs[0], outs[1][:, :, :P - 1])
+    with pytest.raises(ValueError):
+        zl.ebsp_simulate_supersteps(torch.from_numpy(le).cuda(), torch.from_numpy(iv).cuda(), R, 10, outs[0].cpu())
     with pytest.raises(zl.ZipLineError):
         zl.ebsp_simulate_supersteps(torch.from_numpy(le).cuda(), torch.from_numpy(iv).cuda(), R, -1)
 
