@@ -210,6 +210,7 @@ def main() -> int:
     ap.add_argument("--sweep-min", type=int, default=0,
                     help="tuning: smallest P*R searched by the frontier sweep (0: default, negative: never)")
     ap.add_argument("--slice-keys", type=int, default=0, help="tuning: entries per slice of the frontier sweep (0: default)")
+    ap.add_argument("--sweep-lines", type=int, default=0, help="tuning: 128-byte lines a window of the frontier sweep asks for (0: default)")
     ap.add_argument("--window-cap", type=int, default=0, help="tuning: records per window workgroup (0: default)")
     ap.add_argument("--window-fill", type=int, default=0, help="tuning: entries a window is filled to (0: default)")
     ap.add_argument("--single-max", type=int, default=0, help="tuning: largest P*R taken by one workgroup (0: default)")
@@ -231,7 +232,7 @@ def main() -> int:
     from paper_2001_01347_amd import workloads, zipline
 
     zipline.ebsp_zipline_tune(args.window_cap, args.single_max, args.window_fill)
-    zipline.ebsp_zipline_tune_sweep(args.sweep_min, args.slice_keys)
+    zipline.ebsp_zipline_tune_sweep(args.sweep_min, args.slice_keys, args.sweep_lines)
     cfg = workloads.CONFIGS[args.config]
     B, P, R = cfg.B, cfg.P, cfg.R
     n_keys = cfg.n_keys
@@ -354,7 +355,7 @@ def main() -> int:
     dom_bytes = algorithmic_bytes(dom, B, P, R, bins, windows, args.predicted)
     achieved = dom_bytes / (per_kernel[dom] * 1e-3) / 1e9
     counted = COUNTED_TRAFFIC.get((args.objective, bool(args.predicted), args.config))
-    tuned = bool(args.window_cap or args.single_max or args.window_fill or args.sweep_min or args.slice_keys)
+    tuned = bool(args.window_cap or args.single_max or args.window_fill or args.sweep_min or args.slice_keys or args.sweep_lines)
     traffic = call_traffic = None
     if counted and counted[0] == dom and not tuned and not S and kernel_sources_sha256() == COUNTED_SOURCES_SHA256:
         traffic, call_traffic = float(counted[1]), float(counted[2])

@@ -52,9 +52,12 @@ int ebsp_zipline_tune(int32_t window_cap, int32_t single_max, int32_t window_fil
  *               the range objective use).
  *   slice_keys  entries per slice of an instance's value range (at least 256);
  *               0 = chosen from the batch.
- * Results do not depend on either.  Returns EBSP_OK or EBSP_ERR_SHAPE.
+ *   lines       128-byte lines of the input that one window of the sweep may
+ *               ask for (at most 4096; raised to two per worker where it is
+ *               less); 0 = chosen from P.
+ * Results do not depend on any of them.  Returns EBSP_OK or EBSP_ERR_SHAPE.
  */
-int ebsp_zipline_tune_sweep(int32_t sweep_min, int32_t slice_keys);
+int ebsp_zipline_tune_sweep(int32_t sweep_min, int32_t slice_keys, int32_t lines);
 
 /*
  * Per-kernel timing for benchmarks.  Between ebsp_zipline_profile_begin() and

@@ -99,9 +99,10 @@ struct Tuning {          // 0: choose by shape
     int window_fill;
     int sweep_min;       // smallest P*R that takes the frontier sweep (0: the default, < 0: never)
     int slice_keys;      // entries per slice of the sweep (0: chosen from the batch)
+    int sweep_lines;     // lines of a plan of the sweep (0: chosen from P)
 };
 // Set before any thread calls a search (the header says so); read once per call, word by word.
-std::atomic<int> g_tune_window_cap{0}, g_tune_single_max{0}, g_tune_window_fill{0}, g_tune_sweep_min{0}, g_tune_slice_keys{0};
+std::atomic<int> g_tune_window_cap{0}, g_tune_single_max{0}, g_tune_window_fill{0}, g_tune_sweep_min{0}, g_tune_slice_keys{0}, g_tune_sweep_lines{0};
 Tuning tuning()
 {
     Tuning t;
@@ -110,18 +111,20 @@ Tuning tuning()
     t.window_fill = g_tune_window_fill.load(std::memory_order_relaxed);
     t.sweep_min = g_tune_sweep_min.load(std::memory_order_relaxed);
     t.slice_keys = g_tune_slice_keys.load(std::memory_order_relaxed);
+    t.sweep_lines = g_tune_sweep_lines.load(std::memory_order_relaxed);
     return t;
 }
 
 // The frontier sweep (zl_sweep.h) takes stored rows of these shapes under the summed-wait objective.
-constexpr int SWEEP_NT = 512, SWEEP_ITEMS = 16;
+constexpr int SWEEP_NT = 512, SWEEP_LINES = 4096, SWEEP_BUCKETS = 4096, SWEEP_LIST = 2048;
 constexpr int SWEEP_DEFAULT_ON = 1;              // 0: the sweep is the default for its shapes; 1: only where ebsp_zipline_tune_sweep asks for it
 constexpr int SWEEP_MIN_DEFAULT = 8192;          // instances of fewer entries: one workgroup of zl_instance_kernel each
-constexpr int SWEEP_PMAX = 2048;                 // every row with entries left needs a slot, and a quarter of the slots is the most they may take
+constexpr int SWEEP_PMAX = 1024;                 // every row with entries left needs a line of its own and one to spare
 
 struct Plan {
     bool sweep;        // stored rows go through the frontier sweep
     int nslices;       // slices per instance there
+    int lines;         // lines of a plan there
     size_t off_spartial, sweep_bytes;
     bool multi;
     int cap;           // records per window workgroup
@@ -158,6 +161,13 @@ bool make_plan(i64 B, int P, int R, Plan& pl, int single_limit = SINGLE_MAX, boo
             i64 ns = (n + keys - 1) / keys;
             if (ns > 4096) ns = 4096;
             pl.nslices = (int)(ns < 1 ? 1 : ns);
+            // four lines a row: a window then takes about forty entries of every row, most of what is loaded
+            int lines = g_tune.sweep_lines > 0 ? g_tune.sweep_lines : 4 * P;
+            lines = (lines + 31) / 32 * 32;
+            if (lines < 2 * P) lines = (2 * P + 31) / 32 * 32;
+            if (lines < 128) lines = 128;
+            if (lines > SWEEP_LINES) lines = SWEEP_LINES;
+            pl.lines = lines;
             size_t o = 0;                                       // (the first two as in the other layout below)
             pl.off_info = o;     o = align_up(o + (size_t)B * sizeof(InstInfo), 256);
             pl.off_seg = o;      o = align_up(o + (size_t)B * SEGS * sizeof(SegEntry), 256);
@@ -323,12 +333,8 @@ int run_batch(const i64* ts, const i64* le, const i64* iv, i64 B, int P, int R,
         LAUNCH(K_BOUNDS, (zl_bounds_kernel<256>), dim3((unsigned)B), dim3(256), ts, le, iv, P, R, pl.nslices, info, segtab,
                (uint2*)nullptr, status, true);
         const dim3 sgrid((unsigned)(B * (i64)pl.nslices));
-        if (P <= 1024)
-            LAUNCH(K_SWEEP, (zl_sweep_kernel<SWEEP_NT, SWEEP_ITEMS, 1024>), sgrid, dim3(SWEEP_NT), ts, B, P, R, pl.nslices,
-                   info, segtab, spartial, status);
-        else
-            LAUNCH(K_SWEEP, (zl_sweep_kernel<SWEEP_NT, SWEEP_ITEMS, SWEEP_PMAX>), sgrid, dim3(SWEEP_NT), ts, B, P, R, pl.nslices,
-                   info, segtab, spartial, status);
+        LAUNCH(K_SWEEP, (zl_sweep_kernel<SWEEP_NT, SWEEP_LINES, SWEEP_BUCKETS, SWEEP_LIST, SWEEP_PMAX>), sgrid, dim3(SWEEP_NT),
+               ts, B, P, R, pl.nslices, pl.lines, info, segtab, spartial, status);
         LAUNCH(K_SWEEP_FINISH, (zl_sweep_finish_kernel<256>), dim3((unsigned)(pblocks * B)), dim3(256),
                ts, P, R, pl.nslices, info, spartial, barrier, iters, wait);
         return EBSP_OK;
@@ -697,10 +703,12 @@ int ebsp_zipline_tune(int32_t window_cap, int32_t single_max, int32_t window_fil
     return EBSP_OK;
 }
 
-int ebsp_zipline_tune_sweep(int32_t sweep_min, int32_t slice_keys)
+int ebsp_zipline_tune_sweep(int32_t sweep_min, int32_t slice_keys, int32_t lines)
 {
+    if (lines < 0 || lines > SWEEP_LINES) return fail(EBSP_ERR_SHAPE, "lines must be in 0..4096");
     if (slice_keys < 0 || (slice_keys > 0 && slice_keys < 256)) return fail(EBSP_ERR_SHAPE, "slice_keys must be 0 or at least 256");
     g_tune_sweep_min.store(sweep_min, std::memory_order_relaxed);
+    g_tune_sweep_lines.store(lines, std::memory_order_relaxed);
     g_tune_slice_keys.store(slice_keys, std::memory_order_relaxed);
     return EBSP_OK;
 }

@@ -53,7 +53,7 @@ def load() -> ctypes.CDLL:
         lib.ebsp_predict_zipline_workspace_bytes.restype = sz
         lib.ebsp_predict_zipline_workspace_bytes.argtypes = [i64, i32, i32]
         lib.ebsp_zipline_tune_sweep.restype = ctypes.c_int
-        lib.ebsp_zipline_tune_sweep.argtypes = [i32, i32]
+        lib.ebsp_zipline_tune_sweep.argtypes = [i32, i32, i32]
         common = [vp, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
         lib.ebsp_zipline_batch.restype = ctypes.c_int
         lib.ebsp_zipline_batch.argtypes = common
@@ -107,9 +107,9 @@ def ebsp_predict_zipline_workspace_bytes(B: int, P: int, R: int) -> int:
     return int(load().ebsp_predict_zipline_workspace_bytes(B, P, R))
 
 
-def ebsp_zipline_tune_sweep(sweep_min: int = 0, slice_keys: int = 0) -> None:
-    """Which stored-row batches take the one-pass sweep, and its slice length (0 = default); see the header."""
-    rc = load().ebsp_zipline_tune_sweep(int(sweep_min), int(slice_keys))
+def ebsp_zipline_tune_sweep(sweep_min: int = 0, slice_keys: int = 0, lines: int = 0) -> None:
+    """Which stored-row batches take the one-pass sweep, its slice length and the lines of a window (0 = default); see the header."""
+    rc = load().ebsp_zipline_tune_sweep(int(sweep_min), int(slice_keys), int(lines))
     if rc != EBSP_OK:
         raise ZipLineError(f"ebsp_zipline_tune_sweep failed ({rc}): {ebsp_last_error()}")
 
