@@ -27,7 +27,7 @@ _LIB = os.path.join(_HERE, "libzipline_oracle.so")
 _lib = None
 
 METHODS = {"sweep": 0, "definition": 1, "naive": 2}
-RANGE_METHODS = {"sweep": 0, "definition": 1, "naive": 2, "zipline": 3}
+RANGE_METHODS = {"sweep": 0, "definition": 1, "naive": 2, "latest": 3}
 
 
 def build(force: bool = False) -> str:
@@ -67,8 +67,8 @@ def zipline_range(ts, method: str = "sweep", threads: int = 0):
     """The search under the paper's formal objective d_Z = max(Z) - min(Z) (Section III).
 
     Same conventions as :func:`zipline`; the third result is ``dmin[B]`` instead of
-    the summed wait.  Methods: "sweep", "definition", "naive", "zipline" (Algorithm 2
-    as the paper states it, looking through Z for its minimum).
+    the summed wait.  Methods: "sweep", "definition", "naive", "latest" (the sweep with a
+    table of every worker's latest timestamp, searched for its minimum).
     """
     return _run(ts, "zl_range_batch", RANGE_METHODS[method], threads)
 

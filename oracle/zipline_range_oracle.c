@@ -25,23 +25,24 @@
  *   zl_range_naive       Section IV "Naive search": all R^P choices Z, value
  *                        max(Z) - min(Z), ties to the smaller max(Z).
  *   zl_range_definition  the formulas above written out.
- *   zl_range_zipline     Algorithm 2 in the paper's order: sort the merged set
- *                        Omega; fill Z from the left until all n workers are
- *                        present (an element replaces its worker's older one);
- *                        then repeatedly remove min(Z), refill Z from the left
- *                        of Omega until it is complete again, compute d_Z and
- *                        keep it if strictly smaller.  min(Z) is found by
- *                        looking through Z, as the paper describes.
- *   zl_range_sweep       the same sweep with the oldest timestamp still in Z
- *                        kept at the head of a queue (elements enter Z in
- *                        ascending order, so Z in entry order is sorted);
+ *   zl_range_latest      the sweep of Algorithm 2 with a table of every worker's
+ *                        latest timestamp: the merged timestamps are visited in
+ *                        ascending order, equal values together; after the
+ *                        group at value c the table holds last_p(c), and once
+ *                        every worker has an entry d(c) = c - (smallest entry)
+ *                        is a candidate.  The smallest entry is found by
+ *                        looking through the table, O(n) per candidate as in
+ *                        the paper's complexity count (Table I).
+ *   zl_range_sweep       the same sweep with the oldest of the latest timestamps
+ *                        kept at the head of a queue (timestamps enter the table in
+ *                        ascending order, so its entries in order of arrival are sorted);
  *                        O(n log n) for the sort, used for large instances.
  *
- * Readings where the paper is silent: d_Z is evaluated only while Z holds all
- * n workers (Fig. 3 caption), so when Omega runs out during a refill nothing
- * more is evaluated; elements with equal timestamps may enter in any order
- * (the result does not depend on it: a later evaluation at the same time can
- * only be smaller and is then taken by the strict comparison).
+ * Readings where the paper is silent: a barrier time is a candidate only once
+ * every worker has a timestamp at or before it (Fig. 3 caption: the set must
+ * hold all n workers); timestamps that are equal count together, in whatever
+ * order they are stored (the value at such a time is the one with all of them
+ * taken in).
  *
  * Return value of every routine: 0 on success, 1 if a row is not
  * non-decreasing (outputs untouched), 2 on invalid arguments.
@@ -187,10 +188,10 @@ static relem_t *merged_sorted(const int64_t *t, int32_t P, int32_t R)
     return om;
 }
 
-/* Algorithm 2 in the paper's order. Z[p] is worker p's element in Z (inZ[p]
- * says whether there is one); min(Z) and max(Z) are found by looking through Z. */
-int zl_range_zipline(const int64_t *t, int32_t P, int32_t R,
-                     int64_t *barrier, int32_t *iters, int64_t *dmin)
+/* The sweep with an explicit table of the workers' latest timestamps (Algorithm 2; of several equal
+ * minima the first, Fig. 3 caption). */
+int zl_range_latest(const int64_t *t, int32_t P, int32_t R,
+                    int64_t *barrier, int32_t *iters, int64_t *dmin)
 {
     if (!t || P < 1 || R < 1 || !barrier || !iters || !dmin)
         return 2;
@@ -198,60 +199,51 @@ int zl_range_zipline(const int64_t *t, int32_t P, int32_t R,
         return 1;
     const size_t n = (size_t)P * R;
     relem_t *om = merged_sorted(t, P, R);
-    int64_t *Z = (int64_t *)malloc((size_t)P * sizeof(int64_t));
-    char *inZ = (char *)calloc((size_t)P, 1);
-    if (!om || !Z || !inZ) {
-        free(om); free(Z); free(inZ);
+    int64_t *latest = (int64_t *)malloc((size_t)P * sizeof(int64_t));
+    char *started = (char *)calloc((size_t)P, 1);
+    if (!om || !latest || !started) {
+        free(om); free(latest); free(started);
         return 2;
     }
-    size_t next = 0;                        /* the very left element of Omega */
-    int32_t size = 0;                       /* |Z| */
-    while (size < P && next < n) {          /* initial fill */
-        const relem_t w = om[next++];
-        if (!inZ[w.p]) { inZ[w.p] = 1; ++size; }
-        Z[w.p] = w.v;                       /* replaces the worker's older element */
-    }
+    int32_t nstarted = 0;                   /* workers that have a timestamp <= c */
     int have = 0;
     uint64_t best_d = 0;
-    int64_t best_max = 0;
-    while (size == P) {
-        int64_t mx = Z[0], mn = Z[0];
-        int32_t pmin = 0;
-        for (int32_t p = 1; p < P; ++p) {
-            if (Z[p] > mx) mx = Z[p];
-            if (Z[p] < mn) { mn = Z[p]; pmin = p; }
+    int64_t best_c = 0;
+    size_t i = 0;
+    while (i < n) {
+        const int64_t c = om[i].v;
+        for (; i < n && om[i].v == c; ++i) {            /* every timestamp equal to c */
+            const int32_t p = om[i].p;
+            if (!started[p]) { started[p] = 1; ++nstarted; }
+            latest[p] = c;
         }
-        const uint64_t d = span_of(mx, mn);
-        if (!have || d < best_d) {
+        if (nstarted < P)
+            continue;                                   /* c lies before some worker's first timestamp */
+        int64_t oldest = latest[0];
+        for (int32_t p = 1; p < P; ++p)
+            if (latest[p] < oldest) oldest = latest[p];
+        const uint64_t d = span_of(c, oldest);
+        if (!have || d < best_d) {                      /* candidates come in ascending order: the first minimum stays */
             have = 1;
             best_d = d;
-            best_max = mx;
-        }
-        if (next >= n)
-            break;                          /* Omega is empty */
-        inZ[pmin] = 0;                      /* Z <- Z - min(Z) */
-        --size;
-        while (size < P && next < n) {      /* refill from the left of Omega */
-            const relem_t w = om[next++];
-            if (!inZ[w.p]) { inZ[w.p] = 1; ++size; }
-            Z[w.p] = w.v;
+            best_c = c;
         }
     }
-    free(om); free(Z); free(inZ);
+    free(om); free(latest); free(started);
     if (!have)
         return 2;
-    *barrier = best_max;
+    *barrier = best_c;
     *dmin = (int64_t)best_d;
-    range_count_iters(t, P, R, best_max, iters);
+    range_count_iters(t, P, R, best_c, iters);
     return 0;
 }
 
-/* The same sweep for large instances.  Elements enter Z in ascending order, so
- * the elements of Z in entry order are sorted and min(Z) is the oldest entry
- * that has not been replaced: a queue of entries with a "replaced" mark.
- * d_Z is evaluated after every entry once Z is complete; between two removals
- * of min(Z) it can only grow, so the minimum over these evaluations is the
- * one Algorithm 2 finds. */
+/* The same sweep for large instances.  Timestamps enter the table in ascending
+ * order, so its entries in order of arrival are sorted and the oldest one is the
+ * earliest arrival that has not been replaced: a queue of arrivals with a
+ * "replaced" mark.  d is evaluated after every arrival once every worker has
+ * an entry; at equal timestamps the later evaluations can only be smaller and
+ * the strict comparison takes them, so the result is d at the last of them. */
 int zl_range_sweep(const int64_t *t, int32_t P, int32_t R,
                    int64_t *barrier, int32_t *iters, int64_t *dmin)
 {
@@ -331,7 +323,7 @@ int zl_range_batch(const int64_t *ts, int64_t B, int32_t P, int32_t R,
         else if (method == 2)
             r = zl_range_naive(t, P, R, barrier + b, it, dmin + b);
         else
-            r = zl_range_zipline(t, P, R, barrier + b, it, dmin + b);
+            r = zl_range_latest(t, P, R, barrier + b, it, dmin + b);
         if (rc)
             rc[b] = r;
         if (r > worst)

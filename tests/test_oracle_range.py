@@ -16,7 +16,7 @@ import pytest
 
 from paper_2001_01347_amd import workloads
 
-ROUTES = ["sweep", "definition", "naive", "zipline"]
+ROUTES = ["sweep", "definition", "naive", "latest"]
 
 
 def run(oracle, ts, method="sweep"):
@@ -52,7 +52,7 @@ def test_routes_agree_on_random_small_inputs(oracle):
             continue
         ts = np.stack([workloads.random_small(rng, P, R, 0, 25, ties=(trial % 2 == 0)) for _ in range(3)])
         ref = run(oracle, ts, "naive")
-        for m in ["sweep", "definition", "zipline"]:
+        for m in ["sweep", "definition", "latest"]:
             got = run(oracle, ts, m)
             for a, b in zip(ref, got):
                 assert np.array_equal(a, b), (trial, m)
@@ -63,7 +63,7 @@ def test_sweeps_agree_with_the_definition_on_medium_inputs(oracle):
     for P, R in [(7, 40), (30, 12), (64, 9)]:
         ts = np.stack([workloads.random_small(rng, P, R, 0, 300, ties=(i % 2 == 0)) for i in range(4)])
         ref = run(oracle, ts, "definition")
-        for m in ["sweep", "zipline"]:
+        for m in ["sweep", "latest"]:
             for a, b in zip(ref, run(oracle, ts, m)):
                 assert np.array_equal(a, b), (P, R, m)
 
@@ -84,7 +84,7 @@ def test_staggered_periodic_workers_closed_form(oracle):
     for P, g, R in [(2, 5, 4), (5, 3, 7), (16, 11, 30)]:
         T = P * g
         t = np.array([[p * g + i * T for i in range(R)] for p in range(P)], dtype=np.int64)
-        for m in ["sweep", "zipline"] + (["definition"] if P * R <= 200 else []):
+        for m in ["sweep", "latest"] + (["definition"] if P * R <= 200 else []):
             bar, it, d = run(oracle, t[None], m)
             assert (int(bar[0]), int(d[0])) == ((P - 1) * g, (P - 1) * g), (P, m)
             assert list(it[0]) == [1] * P

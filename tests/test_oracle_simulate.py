@@ -143,3 +143,35 @@ def test_hand_worked_fixture(oracle):
         b, it, w, rc, _ = oracle.simulate(c["last_end0"], c["interval"], c["R"], c["sync_cost"])
         assert (rc == 0).all(), c["name"]
         assert b.tolist() == c["barrier"] and w.tolist() == c["wait"] and it.tolist() == c["iters"], c["name"]
+
+
+def test_fixture_is_what_its_script_writes():
+    # the stored expected values come from the committed script, which calls the oracle and nothing else
+    import importlib.util
+    import json
+    import os
+    here = os.path.join(os.path.dirname(__file__), "golden")
+    spec = importlib.util.spec_from_file_location("make_supersteps_fixture", os.path.join(here, "make_supersteps_fixture.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    assert json.load(open(os.path.join(here, "worked_examples_supersteps.json"))) == mod.build()
+    text = open(os.path.join(here, "make_supersteps_fixture.py")).read()
+    assert "paper_2001_01347_amd" not in text and "torch" not in text
+
+
+def test_supersteps_worked_on_paper(oracle):
+    # Values worked on paper (not read from the fixture): two workers with iteration times 2 and 3 and R = 3 have rows
+    # (2,4,6) and (3,6,9); candidates from 3 on: c=3 waits (3-2)+0 = 1, c=4 waits 0+(4-3) = 1, c=6 waits 0, c=9 waits 3.
+    # They meet at 6 and, restarting together, again every 6; with a synchronisation of 5 the restarts are at 11 and 22.
+    le, iv = np.zeros((1, 2), dtype=np.int64), np.tile(np.array([[[2, 3]]], dtype=np.int64), (3, 1, 1))
+    b, it, w, rc, _ = oracle.simulate(le, iv, 3, 0)
+    assert b.ravel().tolist() == [6, 12, 18] and w.ravel().tolist() == [0, 0, 0] and it.reshape(3, 2).tolist() == [[3, 2]] * 3
+    b, it, w, rc, _ = oracle.simulate(le, iv, 3, 5)
+    assert b.ravel().tolist() == [6, 17, 28] and w.ravel().tolist() == [0, 0, 0]
+    # R = 2: rows (2,4) and (3,6): c=3 waits 1, c=4 waits 1, c=6 waits 2: the first minimum is 3; then (5,7),(6,9): c=6 waits 1
+    b, it, w, rc, _ = oracle.simulate(le, iv, 2, 0)
+    assert b.ravel().tolist() == [3, 6, 9] and w.ravel().tolist() == [1, 1, 1] and it.reshape(3, 2).tolist() == [[1, 1]] * 3
+    # R = 1 is BSP: three workers ending at 5, 7, 6 wait 2 + 0 + 1 at barrier 7; with a synchronisation of 2 they restart at 9
+    # and, now taking 4, 4 and 9, end at 13, 13, 18: barrier 18, waits 5 + 5 + 0
+    b, it, w, rc, _ = oracle.simulate(np.zeros((1, 3), dtype=np.int64), np.array([[[5, 7, 6]], [[4, 4, 9]]], dtype=np.int64), 1, 2)
+    assert b.ravel().tolist() == [7, 18] and w.ravel().tolist() == [3, 10] and it.reshape(2, 3).tolist() == [[1, 1, 1]] * 2
