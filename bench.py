@@ -39,14 +39,23 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 
 # HBM bytes per launch of the dominant kernel, from `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE` runs of
 # this program (their summaries, with the commands, are under profiles/), each scaled by what the same counter
-# reads for the plain copy kernel of known size (FETCH_SIZE x 2048 B, WRITE_SIZE x 1024 B per count).  They
-# hold only for the kernel sources they were taken from: `traffic` is null once those have changed.
-COUNTED_SOURCES_SHA256 = "f835e57ff9849d4afdfdffc2214efd5caabfed39a751a349f7489bac15061102"
+# reads for the plain copy kernel of known size (FETCH_SIZE x 2048 B, WRITE_SIZE x 1024 B per count).  The
+# figures below are the counters' per-dispatch averages, kernel by kernel in launch order.  They hold only for
+# the kernel sources they were taken from: `traffic` is null once those have changed.
+COUNTED_SOURCES_SHA256 = "059840710679f11f92041f9ee35883d027fc2009283bd00be1f4519a0da9180d"
+FETCH_UNIT, WRITE_UNIT = 2048, 1024      # bytes per count: what the copy kernel's 2 GiB in, 2 GiB out read as (1 048 609 and 2 097 152)
 COUNTED_TRAFFIC = {     # (objective, predicted, config) -> (dominant kernel, its bytes, bytes of all kernels of a call)
-    ("sum", False, 5): ("zl_window_kernel", 2260923 * 2048 + 1223 * 1024, 7542405397),
-    ("sum", False, 3): ("zl_instance_kernel", 1189601 * 2048 + 5655 * 1024, 2459061408),
-    ("range", False, 5): ("zl_range_fast_kernel", 2233769 * 2048 + 1684 * 1024, 7495621707),
-    ("sum", True, 5): ("zl_window_kernel", 267418 * 2048 + 562 * 1024, 1176893707),
+    ("sum", False, 5): ("zl_window_kernel", 2261699 * FETCH_UNIT + 1232 * WRITE_UNIT,
+                        (16447 + 1048906 + 35886 + 658 + 2261699 + 358 + 8502) * FETCH_UNIT
+                        + (70 + 610512 + 1026 + 1239 + 1232 + 8192 + 258) * WRITE_UNIT),
+    ("sum", False, 3): ("zl_instance_kernel", 1189604 * FETCH_UNIT + 5654 * WRITE_UNIT,
+                        (1189604 + 97) * FETCH_UNIT + (5654 + 16384) * WRITE_UNIT),
+    ("range", False, 5): ("zl_range_fast_kernel", 2234822 * FETCH_UNIT + 1681 * WRITE_UNIT,
+                          (16447 + 1048907 + 35886 + 670 + 2234822 + 622 + 8917) * FETCH_UNIT
+                          + (70 + 610473 + 1026 + 1716 + 1681 + 14462 + 258) * WRITE_UNIT),
+    ("sum", True, 5): ("zl_window_kernel", 267419 * FETCH_UNIT + 559 * WRITE_UNIT,
+                       (574 + 10523 + 9004 + 658 + 267419 + 358 + 1673) * FETCH_UNIT
+                       + (582 + 557056 + 1024 + 1240 + 559 + 8192 + 258) * WRITE_UNIT),
 }
 
 
