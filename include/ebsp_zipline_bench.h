@@ -47,9 +47,10 @@ int ebsp_zipline_tune(int32_t window_cap, int32_t single_max, int32_t window_fil
 /*
  * Which stored-row batches ebsp_zipline_batch searches in one pass (the frontier
  * sweep) and how it slices them; process-wide, same rules as ebsp_zipline_tune.
- *   sweep_min   smallest P*R that takes the sweep; 0 = the default, negative =
- *               never (every batch takes the kernels that predicted rows and
- *               the range objective use).
+ *   sweep_min   positive: instances of at least that many entries (P*R) and at
+ *               most 1024 workers take the sweep; 0 = the default and negative:
+ *               no batch does (every batch takes the kernels that predicted
+ *               rows and the range objective use, which are faster today).
  *   slice_keys  entries per slice of an instance's value range (at least 256);
  *               0 = chosen from the batch.
  *   lines       128-byte lines of the input that one window of the sweep may
