@@ -72,6 +72,41 @@ def test_configs(zl, oracle):
     assert_same(zl, oracle, workloads.make(4, instances=range(1)), "config 4 (ties)")
 
 
+def test_degenerate_and_extreme_values(zl, oracle):
+    assert_same(zl, oracle, np.full((3, 8, 16), 42, dtype=np.int64), "all equal", "scan")
+    rng = np.random.default_rng(17)
+    base = np.stack([workloads.random_small(rng, 9, 33, 1, 1000, ties=True) for _ in range(3)])
+    assert_same(zl, oracle, base + (1 << 62) - 40_000, "near the top of int64 / 2", "scan")
+    assert_same(zl, oracle, base - (1 << 62), "near the bottom of int64 / 2", "scan")
+    wide = base.copy()
+    wide[:, ::2, :] += (1 << 61)                     # every other worker far away: the nearest point is a row's first or last
+    assert_same(zl, oracle, wide, "two groups of workers 2^61 apart", "scan")
+    far = np.sort(rng.integers(-(1 << 61), 1 << 61, size=(2, 5, 40)), axis=2)
+    assert_same(zl, oracle, far, "values all over +-2^61", "scan")
+
+
+def test_empty_batch_and_buffers_passed_in(zl, oracle):
+    empty = torch.zeros((0, 4, 8), dtype=torch.int64, device="cuda")
+    out = zl.ebsp_gridscan_batch(empty, True)
+    torch.cuda.synchronize()
+    assert [tuple(t.shape) for t in out] == [(0,), (0, 4), (0,), (0,)]
+    ts = workloads.make_workers(12, 30, 5)
+    d = torch.from_numpy(ts).cuda()
+    bufs = (torch.full((5,), -1, dtype=torch.int64, device="cuda"), torch.full((5, 12), -1, dtype=torch.int32, device="cuda"),
+            torch.full((5,), -1, dtype=torch.int64, device="cuda"), torch.full((5,), -1, dtype=torch.int32, device="cuda"))
+    ws = torch.empty(zl.ebsp_gridscan_workspace_bytes(5, 12, 30, True), dtype=torch.uint8, device="cuda")
+    got = zl.ebsp_gridscan_batch(d, True, *bufs, workspace=ws)
+    torch.cuda.synchronize()
+    assert all(a is b for a, b in zip(got, bufs))
+    ob, oi, od, rc, _ = oracle.gridscan(ts, True, "scan")
+    assert np.array_equal(bufs[0].cpu().numpy(), ob) and np.array_equal(bufs[1].cpu().numpy(), oi)
+    assert np.array_equal(bufs[2].cpu().numpy(), od) and (bufs[3].cpu().numpy() == 0).all()
+    with pytest.raises(ValueError):
+        zl.ebsp_gridscan_batch(d, True, bufs[0].to(torch.int32))
+    with pytest.raises(ValueError):
+        zl.ebsp_gridscan_batch(d, True, workspace=ws[:ws.numel() - 256])
+
+
 def test_never_below_the_exact_search(zl):
     # both scans build sets of one timestamp per worker: ebsp_zipline_range_batch's optimum bounds them from below
     ts = torch.from_numpy(workloads.make(2, instances=range(512))).cuda()
