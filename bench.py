@@ -330,13 +330,14 @@ def main() -> int:
     if args.copy_probe > 0 and ts is not None:
         nbytes = ts.numel() * 8
         dst = torch.empty_like(ts)
-        sink = torch.zeros(1, dtype=torch.int64, device=dev)
+        sink = torch.zeros(zipline.READ_SINK_WORDS, dtype=torch.int64, device=dev)
         zipline.ebsp_zipline_copy_probe(ts, dst)
         zipline.ebsp_zipline_read_probe(ts, sink)
         torch.cuda.synchronize()
         zipline.ebsp_zipline_profile_begin(2 * args.copy_probe)
         for _ in range(args.copy_probe):
             zipline.ebsp_zipline_copy_probe(ts, dst)
+        for _ in range(args.copy_probe):
             zipline.ebsp_zipline_read_probe(ts, sink)
         probe_ms, nprobe = zipline.ebsp_zipline_profile_end()
         copy_gbs = 2.0 * nbytes / (probe_ms["zl_copy_kernel"] / args.copy_probe * 1e-3) / 1e9

@@ -88,10 +88,13 @@ int ebsp_zipline_copy_probe(const void* src, void* dst, size_t bytes, void* stre
 
 /*
  * The same for kernels that mostly read: streams `bytes` (a positive multiple
- * of 16; src 16-byte aligned device memory) through a sum and adds the sum of
- * all 32-bit words to *sink (DEVICE, 8-byte aligned; the caller sets it to
- * zero if the value matters).  Counts as one call of an open profile.
+ * of 16; src 16-byte aligned device memory) through a sum and adds the sums of
+ * the workgroups' pieces to the EBSP_READ_SINK_WORDS words of sink (DEVICE,
+ * 8-byte aligned; the caller sets them to zero if the values matter: together
+ * they add up to the sum of all 32-bit words read).  Counts as one call of an
+ * open profile.
  */
+#define EBSP_READ_SINK_WORDS 256
 int ebsp_zipline_read_probe(const void* src, size_t bytes, uint64_t* sink, void* stream);
 
 /*

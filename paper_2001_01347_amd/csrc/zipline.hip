@@ -721,23 +721,25 @@ int ebsp_zipline_copy_probe(const void* src, void* dst, size_t bytes, void* stre
     if (int rc = check_device()) return rc;
     hipStream_t st = (hipStream_t)stream;
     const i64 n = (i64)(bytes / 16);
-    i64 blocks = (n + 255) / 256;
-    if (blocks > 256 * 32) blocks = 256 * 32;
+    i64 blocks = (n + 2047) / 2048;                     // pieces of 32 KiB or more
+    if (blocks > 256 * 256) blocks = 256 * 256;
     LAUNCH(K_COPY, zl_copy_kernel, dim3((unsigned)blocks), dim3(256), (const uint4*)src, (uint4*)dst, n);
     if (g_prof.on && g_prof.calls < g_prof.max_calls) ++g_prof.calls;
     return EBSP_OK;
 }
 
+static_assert(READ_SINK_WORDS == EBSP_READ_SINK_WORDS, "the header's word count is the kernel's");
+
 int ebsp_zipline_read_probe(const void* src, size_t bytes, uint64_t* sink, void* stream)
 {
     if (!src || !sink) return fail(EBSP_ERR_NULL, "src and sink must not be NULL");
     if (bytes == 0 || bytes % 16 != 0 || ((uintptr_t)src & 15u) || ((uintptr_t)sink & 7u))
-        return fail(EBSP_ERR_SHAPE, "read probe needs a positive multiple of 16 bytes, a 16-byte aligned source and an 8-byte aligned sink");
+        return fail(EBSP_ERR_SHAPE, "read probe needs a positive multiple of 16 bytes, a 16-byte aligned source and an 8-byte aligned sink of 256 words");
     if (int rc = check_device()) return rc;
     hipStream_t st = (hipStream_t)stream;
     const i64 n = (i64)(bytes / 16);
-    i64 blocks = (n + 255) / 256;
-    if (blocks > 256 * 16) blocks = 256 * 16;
+    i64 blocks = (n + 2047) / 2048;                     // pieces of 32 KiB or more
+    if (blocks > 256 * 256) blocks = 256 * 256;
     LAUNCH(K_READ, zl_read_kernel, dim3((unsigned)blocks), dim3(256), (const uint4*)src, n, (u64*)sink);
     if (g_prof.on && g_prof.calls < g_prof.max_calls) ++g_prof.calls;
     return EBSP_OK;

@@ -121,6 +121,67 @@ __global__ __launch_bounds__(NT) void zl_bounds_kernel(
     }
 }
 
+// One wave walks one row: out[k] = number of entries of the row that fall in fine bins below k, for
+// k = 0..nb (SUMS: every index written is also added to sums[k], an LDS array over the fine bins).  Every
+// pair of neighbours is compared on the way (the only place the multi-window path does), and the steps
+// of 2^32 or more of an instance whose values spread that far are remembered.  PART_AHEAD groups of 64
+// entries are asked for before the first is looked at: a wave with one load in flight leaves the memory idle.
+constexpr int PART_AHEAD = 4;
+template <class CT, bool SUMS>
+__device__ __forceinline__ void partition_row(const i64* __restrict__ row, int R, const InstInfo& ii, const SegEntry* tab,
+                                              CT* __restrict__ out, u32* sums, i64 b, InstInfo* info, u32* __restrict__ widebin,
+                                              int* __restrict__ status)
+{
+    const int lane = threadIdx.x & (WAVE - 1);
+    const u64 base = (u64)ii.base;
+    int carry = -1;                        // bin of the element before lane 0's
+    i64 carry_t = INT64_MIN;               // and its value
+    bool bad = false;
+    const bool wide = (ii.range >> 32) != 0;          // only then can two neighbours be 2^32 or more apart
+    int farbin = 0;                                   // the window kernels hold deltas in 32 bits: the bin such a
+    u32 far = 0;                                      // step ends in is remembered (this lane's last one, and how many)
+    for (u32 i0 = 0; i0 < (u32)R; i0 += PART_AHEAD * WAVE) {   // unsigned: R may be within a few waves' width of 2^31
+        i64 tv[PART_AHEAD];
+#pragma unroll
+        for (int u = 0; u < PART_AHEAD; ++u) {
+            const u32 i = i0 + (u32)(u * WAVE + lane);
+            tv[u] = i < (u32)R ? row[i] : INT64_MAX;
+        }
+#pragma unroll
+        for (int u = 0; u < PART_AHEAD; ++u) {
+            const u32 i = i0 + (u32)(u * WAVE + lane);
+            if (i0 + (u32)(u * WAVE) < (u32)R) {      // (the same in every lane)
+                const i64 t = tv[u];
+                int bin = -1;
+                if (i < (u32)R) bin = (int)fine_bin((u64)t - base, ii, tab);
+                // the neighbour's bin and value by a lane shift inside the vector ALU (lane 0: what the wave saw last)
+                const int pb = dpp_take<DPP_WAVE_SHR1, 0xf>(carry, bin);
+                const i64 pt = dpp_take<DPP_WAVE_SHR1, 0xf>(carry_t, t);
+                bad |= t < pt;
+                if (wide && i > 0 && i < (u32)R && (((u64)t - (u64)pt) >> 32) != 0) { farbin = bin; ++far; }
+                if (i < (u32)R)
+                    for (int k = pb + 1; k <= bin; ++k) {
+                        out[k] = (CT)i;
+                        if (SUMS) atomicAdd(&sums[k], i);
+                    }
+                carry = __builtin_amdgcn_readlane(bin, WAVE - 1);
+                carry_t = (i64)((u64)(u32)__builtin_amdgcn_readlane((int)(u32)(u64)t, WAVE - 1) |
+                                ((u64)(u32)__builtin_amdgcn_readlane((int)(u32)((u64)t >> 32), WAVE - 1) << 32));
+            }
+        }
+    }
+    if (__any(bad) && lane == 0 && status) atomicOr(status + b, (int)EBSP_STATUS_UNSORTED);
+    if (far) {                                        // (a lane with several such steps: more than the list takes)
+        const u32 slot = atomicAdd(&info[b].wide_steps, far == 1 ? 1u : WIDE_MARKS + 1u);
+        if (far == 1 && slot < WIDE_MARKS) widebin[b * (i64)WIDE_MARKS + slot] = (u32)farbin;
+    }
+    const int last_bin = (int)fine_bin((u64)row[R - 1] - base, ii, tab);
+    for (int k = last_bin + 1 + lane; k <= (int)ii.nb; k += WAVE) {
+        out[k] = (CT)R;
+        if (SUMS) atomicAdd(&sums[k], (u32)R);
+    }
+}
+
 // zl_partition: one wave per row.  cross[row][k] = number of entries of the row
 // that fall in fine bins below k, for k = 0..nb.
 template <int NT, class CT>
@@ -141,38 +202,7 @@ __global__ __launch_bounds__(NT) void zl_partition_kernel(
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");     // the wave's own stores, read by its other lanes below
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    const i64* __restrict__ row = ts + row_id * (i64)R;
-    CT* __restrict__ out = cross + row_id * (i64)stride;
-    const u64 base = (u64)ii.base;
-
-    int carry = -1;                        // bin of the element before lane 0's
-    i64 carry_t = INT64_MIN;               // and its value
-    bool bad = false;
-    const bool wide = (ii.range >> 32) != 0;          // only then can two neighbours be 2^32 or more apart
-    int farbin = 0;                                   // the window kernels hold deltas in 32 bits: the bin such a
-    u32 far = 0;                                      // step ends in is remembered (this lane's last one, and how many)
-    for (u32 i0 = 0; i0 < (u32)R; i0 += WAVE) {       // unsigned: R may be within a wave's width of 2^31
-        const u32 i = i0 + (u32)lane;
-        int bin = -1;
-        i64 t = INT64_MAX;
-        if (i < (u32)R) { t = row[i]; bin = (int)fine_bin((u64)t - base, ii, tab); }
-        int pb = __shfl_up(bin, 1, WAVE);
-        i64 pt = __shfl_up(t, 1, WAVE);
-        if (lane == 0) { pb = carry; pt = carry_t; }
-        bad |= t < pt;                     // the only place the multi-window path checks every pair of neighbours
-        if (wide && i > 0 && i < (u32)R && (((u64)t - (u64)pt) >> 32) != 0) { farbin = bin; ++far; }
-        if (i < (u32)R)
-            for (int k = pb + 1; k <= bin; ++k) out[k] = (CT)i;
-        carry = __shfl(bin, WAVE - 1, WAVE);
-        carry_t = __shfl(t, WAVE - 1, WAVE);
-    }
-    if (__any(bad) && lane == 0 && status) atomicOr(status + b, (int)EBSP_STATUS_UNSORTED);
-    if (far) {                                        // (a lane with several such steps: more than the list takes)
-        const u32 slot = atomicAdd(&info[b].wide_steps, far == 1 ? 1u : WIDE_MARKS + 1u);
-        if (far == 1 && slot < WIDE_MARKS) widebin[b * (i64)WIDE_MARKS + slot] = (u32)farbin;
-    }
-    const int last_bin = (int)fine_bin((u64)row[R - 1] - base, ii, tab);
-    for (int k = last_bin + 1 + lane; k <= (int)ii.nb; k += WAVE) out[k] = (CT)R;
+    partition_row<CT, false>(ts + row_id * (i64)R, R, ii, tab, cross + row_id * (i64)stride, nullptr, b, info, widebin, status);
 }
 
 // The same with the column sums on the way: a workgroup takes PART_ROWS consecutive rows of
@@ -191,7 +221,7 @@ __global__ __launch_bounds__(PART_ROWS * WAVE) void zl_partition_sum_kernel(
     constexpr int NT = PART_ROWS * WAVE;
     __shared__ SegEntry tab[SEGS];
     __shared__ u32 sums[PART_MAX_STRIDE];
-    const int tid = threadIdx.x, lane = tid & (WAVE - 1);
+    const int tid = threadIdx.x;
     const i64 b = blockIdx.x / (u32)groups;
     const int g = (int)(blockIdx.x % (u32)groups);
     const int p = g * PART_ROWS + (tid >> 6);
@@ -201,37 +231,7 @@ __global__ __launch_bounds__(PART_ROWS * WAVE) void zl_partition_sum_kernel(
     __syncthreads();
     if (p < P) {
         const i64 row_id = b * (i64)P + p;
-        const i64* __restrict__ row = ts + row_id * (i64)R;
-        CT* __restrict__ out = cross + row_id * (i64)stride;
-        const u64 base = (u64)ii.base;
-        int carry = -1;                        // bin of the element before lane 0's
-        i64 carry_t = INT64_MIN;               // and its value
-        bool bad = false;
-        const bool wide = (ii.range >> 32) != 0;      // only then can two neighbours be 2^32 or more apart
-        int farbin = 0;                               // the window kernels hold deltas in 32 bits: the bin such a
-        u32 far = 0;                                  // step ends in is remembered (this lane's last one, and how many)
-        for (u32 i0 = 0; i0 < (u32)R; i0 += WAVE) {   // unsigned: R may be within a wave's width of 2^31
-            const u32 i = i0 + (u32)lane;
-            int bin = -1;
-            i64 t = INT64_MAX;
-            if (i < (u32)R) { t = row[i]; bin = (int)fine_bin((u64)t - base, ii, tab); }
-            int pb = __shfl_up(bin, 1, WAVE);
-            i64 pt = __shfl_up(t, 1, WAVE);
-            if (lane == 0) { pb = carry; pt = carry_t; }
-            bad |= t < pt;                     // the only place the multi-window path checks every pair of neighbours
-            if (wide && i > 0 && i < (u32)R && (((u64)t - (u64)pt) >> 32) != 0) { farbin = bin; ++far; }
-            if (i < (u32)R)
-                for (int k = pb + 1; k <= bin; ++k) { out[k] = (CT)i; atomicAdd(&sums[k], i); }
-            carry = __shfl(bin, WAVE - 1, WAVE);
-            carry_t = __shfl(t, WAVE - 1, WAVE);
-        }
-        if (__any(bad) && lane == 0 && status) atomicOr(status + b, (int)EBSP_STATUS_UNSORTED);
-        if (far) {                                    // (a lane with several such steps: more than the list takes)
-            const u32 slot = atomicAdd(&info[b].wide_steps, far == 1 ? 1u : WIDE_MARKS + 1u);
-            if (far == 1 && slot < WIDE_MARKS) widebin[b * (i64)WIDE_MARKS + slot] = (u32)farbin;
-        }
-        const int last_bin = (int)fine_bin((u64)row[R - 1] - base, ii, tab);
-        for (int k = last_bin + 1 + lane; k <= (int)ii.nb; k += WAVE) { out[k] = (CT)R; atomicAdd(&sums[k], (u32)R); }
+        partition_row<CT, true>(ts + row_id * (i64)R, R, ii, tab, cross + row_id * (i64)stride, sums, b, info, widebin, status);
     }
     __syncthreads();
     u32* __restrict__ mine = part + (b * (i64)groups + g) * stride;

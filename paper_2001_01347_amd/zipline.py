@@ -28,6 +28,8 @@ EXPORTS = ("ebsp_gridscan_workspace_bytes", "ebsp_gridscan_batch", "ebsp_zipline
            "ebsp_zipline_kernel_count",
            "ebsp_zipline_kernel_name", "ebsp_last_error")
 
+READ_SINK_WORDS = 256     # EBSP_READ_SINK_WORDS of the bench header
+
 _lib = None
 
 
@@ -363,10 +365,10 @@ def ebsp_zipline_copy_probe(src: torch.Tensor, dst: torch.Tensor) -> None:
 
 
 def ebsp_zipline_read_probe(src: torch.Tensor, sink: torch.Tensor) -> None:
-    """Plain streaming device read of src on the current stream, summed into sink (one int64 on the device)."""
-    if not (src.is_cuda and src.is_contiguous() and sink.is_cuda and sink.dtype == torch.int64 and sink.numel() == 1
-            and sink.device == src.device):
-        raise ValueError("src must be a contiguous CUDA tensor and sink one int64 on the same device")
+    """Plain streaming device read of src on the current stream, summed into sink (READ_SINK_WORDS int64 on the device)."""
+    if not (src.is_cuda and src.is_contiguous() and sink.is_cuda and sink.dtype == torch.int64 and sink.is_contiguous()
+            and sink.numel() == READ_SINK_WORDS and sink.device == src.device):
+        raise ValueError(f"src must be a contiguous CUDA tensor and sink {READ_SINK_WORDS} int64 words on the same device")
     with torch.cuda.device(src.device):
         rc = load().ebsp_zipline_read_probe(src.data_ptr(), src.numel() * src.element_size(), sink.data_ptr(),
                                             torch.cuda.current_stream(src.device).cuda_stream)

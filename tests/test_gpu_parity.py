@@ -443,3 +443,19 @@ def test_a_few_long_pauses_in_nanosecond_rows(zl, oracle, pauses):
     # the same pauses at the very first step of a row (its first entry stays early, the second comes late)
     steps[:, :4, 1] += 2 ** 35
     all_three(zl, oracle, np.cumsum(steps, axis=2), f"{pauses} pauses and four early ones")
+
+
+@pytest.mark.parametrize("nbytes", [16, 4096 + 16, 16 * 1024 * 3 + 48, 8 * 1024 * 1024, 64 * 1024 * 1024 + 16 * 7])
+def test_the_yardstick_kernels_copy_and_read_everything(zl, nbytes):
+    # the copy probe copies every byte, the read probe sums every 32-bit word (pieces per workgroup, ragged ends)
+    g = torch.Generator(device="cuda").manual_seed(nbytes)
+    src = torch.randint(0, 1 << 31, (nbytes // 4,), dtype=torch.int32, device="cuda", generator=g)
+    dst = torch.zeros_like(src)
+    sink = torch.zeros(zl.READ_SINK_WORDS, dtype=torch.int64, device="cuda")
+    zl.ebsp_zipline_copy_probe(src, dst)
+    zl.ebsp_zipline_read_probe(src, sink)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+    assert int(sink.sum().item()) == int(src.to(torch.int64).sum().item())
+    with pytest.raises(ValueError):
+        zl.ebsp_zipline_read_probe(src, sink[:1])
