@@ -125,7 +125,7 @@ struct Plan {
     bool sweep;        // stored rows go through the frontier sweep
     int nslices;       // slices per instance there
     int lines;         // lines of a plan there
-    size_t off_spartial, sweep_bytes;
+    size_t off_spartial, off_best, sweep_bytes;
     bool multi;
     int cap;           // records per window workgroup
     int fill;          // most entries of a window (unless a single fine bin holds more)
@@ -172,6 +172,7 @@ bool make_plan(i64 B, int P, int R, Plan& pl, int single_limit = SINGLE_MAX, boo
             pl.off_info = o;     o = align_up(o + (size_t)B * sizeof(InstInfo), 256);
             pl.off_seg = o;      o = align_up(o + (size_t)B * SEGS * sizeof(SegEntry), 256);
             pl.off_spartial = o; o = align_up(o + (size_t)B * pl.nslices * sizeof(Partial), 256);
+            pl.off_best = o;     o = align_up(o + (size_t)B * sizeof(i64), 256);
             pl.sweep_bytes = o;
         }
     }
@@ -259,7 +260,8 @@ int plan_windows(const Plan& pl, const i64* ts, const i64* le, const i64* iv, i6
     const i64 kblocks = (pl.stride + 255) / 256;
     const i64 widest = pl.part_stored > pl.part_pred ? pl.part_stored : pl.part_pred;
     if (kblocks * B > 0x7fffffffll || widest * B > 0x7fffffffll) return fail(EBSP_ERR_SHAPE, "batch too large for one call");
-    LAUNCH(K_BOUNDS, (zl_bounds_kernel<256>), dim3((unsigned)B), dim3(256), ts, le, iv, P, R, pl.bins, info, segtab, rowpar, status, summed);
+    LAUNCH(K_BOUNDS, (zl_bounds_kernel<256>), dim3((unsigned)B), dim3(256), ts, le, iv, P, R, pl.bins, info, segtab, rowpar, status, summed,
+           (i64*)nullptr);
     int part_rows;                                    // rows of partial column sums per instance (0: none, count from cross)
     if (pred) {
         part_rows = pl.part_pred;
@@ -330,11 +332,12 @@ int run_batch(const i64* ts, const i64* le, const i64* iv, i64 B, int P, int R,
         InstInfo* info = (InstInfo*)(wsp + pl.off_info);
         SegEntry* segtab = (SegEntry*)(wsp + pl.off_seg);
         Partial* spartial = (Partial*)(wsp + pl.off_spartial);
+        i64* best = (i64*)(wsp + pl.off_best);
         LAUNCH(K_BOUNDS, (zl_bounds_kernel<256>), dim3((unsigned)B), dim3(256), ts, le, iv, P, R, pl.nslices, info, segtab,
-               (uint2*)nullptr, status, true);
+               (uint2*)nullptr, status, true, best);
         const dim3 sgrid((unsigned)(B * (i64)pl.nslices));
         LAUNCH(K_SWEEP, (zl_sweep_kernel<SWEEP_NT, SWEEP_LINES, SWEEP_BUCKETS, SWEEP_LIST, SWEEP_PMAX>), sgrid, dim3(SWEEP_NT),
-               ts, B, P, R, pl.nslices, pl.lines, info, segtab, spartial, status);
+               ts, B, P, R, pl.nslices, pl.lines, info, segtab, best, spartial, status);
         LAUNCH(K_SWEEP_FINISH, (zl_sweep_finish_kernel<256>), dim3((unsigned)(pblocks * B)), dim3(256),
                ts, P, R, pl.nslices, info, spartial, barrier, iters, wait);
         return EBSP_OK;

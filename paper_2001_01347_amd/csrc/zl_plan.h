@@ -12,9 +12,10 @@ template <int NT>
 __global__ __launch_bounds__(NT) void zl_bounds_kernel(
     const i64* __restrict__ ts, const i64* __restrict__ le, const i64* __restrict__ iv, int P, int R, int bins,
     InstInfo* __restrict__ info, SegEntry* __restrict__ segtab, uint2* __restrict__ rowpar, int* __restrict__ status,
-    bool summed)
+    bool summed, i64* __restrict__ best = nullptr)
 {
     static_assert(NT >= SEGS, "one thread per segment");
+    if (best && threadIdx.x == 0) best[blockIdx.x] = INT64_MAX;     // the instance's best upper bound so far (the sweep's slices share it)
     __shared__ i64 red[NT / WAVE];
     __shared__ u64 seg_part[SEGS];        // entries of rows that begin or end in a segment (x 2^16)
     __shared__ u64 seg_diff[SEGS + 1];    // difference array: entries per segment of the rows that cover it whole (x 2^16)

@@ -21,7 +21,7 @@ namespace {
 //     buckets survive - a second stream over the runs that lists their entries for the exact
 //     evaluation (zl_argmin).  The cursors move past the consumed entries, W0 = P*A - S(A-) is
 //     carried to the next window (no row is looked at again), and so is the best upper bound,
-//     which prunes later windows;
+//     which prunes later windows (the slices of an instance share theirs through a word in memory);
 //   * a window never holds more than the plan's lines, whatever the data: there is nothing to
 //     defer.  Buckets are 2^sh wide (exact bounds by shifts).  Where a surviving bucket is too
 //     deep to evaluate entry by entry (clustered or massively tied values), or the window holds a
@@ -53,7 +53,7 @@ struct SweepCfg {
     static constexpr int MISC_WORDS = 16;
     static_assert((1 << LOG_NB) == NB && BPT * NT == NB && BPT % 2 == 0, "a power of two, an even number of buckets per thread");
     static_assert(CAP < (1 << 18) && LIST < (int)SLOT_GONE, "18-bit count and slot fields");
-    static_assert(CAPL % (4 * NW) == 0, "whole rounds of the workgroup");
+    static_assert(CAPL % (4 * NW * SWEEP_BATCH) == 0, "whole rounds of the workgroup");
     __host__ __device__ static constexpr size_t bytes(int P)
     {
         return (size_t)(P + 2) * 16 + (size_t)((P + 3) / 4 * 4) * 4 + (size_t)NB * 8 + (size_t)LIST * 8 + (size_t)RED_WORDS * 8 +
@@ -74,7 +74,7 @@ struct SweepSm {
     u32* misc;        // [MISC_WORDS]
 };
 enum { M_LIVE = 0, M_OFFEND = 1, M_FLAGS = 2, M_STALE = 3, M_GIANT = 4 };
-constexpr u32 FLAG_NEG = 1;
+constexpr u32 FLAG_NEG = 1, FLAG_GIANT = 2;
 
 template <class C>
 __device__ __forceinline__ SweepSm carve_sweep(unsigned char* smem, int P)
@@ -219,24 +219,32 @@ __device__ __forceinline__ void sweep_plan(const SweepSm& sm, const i64* __restr
         }
     }
     if (tid == 0) sm.rowinfo[P] = make_uint4(0u, total, 0u, 0u);
+    // the lines behind the plan's last one, up to a whole round of the workgroup, belong to "row P", which has no entries
+    {
+        constexpr u32 ROUND = 4u * (u32)(NT / WAVE) * (u32)SWEEP_BATCH;
+        const u32 padded = (total + ROUND - 1) / ROUND * ROUND;
+        for (u32 l = total + (u32)tid; l < padded; l += NT) sm.linemap[l] = (unsigned short)P;
+    }
     for (int p = p0; p < p1; ++p) rates[p] = 0;
     __syncthreads();
 }
 
 // What a stream over the runs finds besides the keys.
 struct PassOut {
+    u32 giant;    // PASS_HIST: nonzero: some entry of the window lies 2^31 or more after its predecessor
     u32 neg;      // top bit set: some entry lies before its predecessor
     u32 stale;    // entries of the runs that lie before A although no window took them (each lane holds the wave's count)
     u32 count;    // PASS_ONE: the thread's entries of the window
     u64 dsum;     // PASS_ONE: the sum of their deltas
 };
-enum { PASS_HIST = 0, PASS_LIST = 1, PASS_ONE = 2 };
+enum { PASS_HIST = 0, PASS_LIST = 1, PASS_ONE = 2, PASS_GIANT = 3 };
 
 // zl_delta: one stream over the runs of a plan of T lines, sixteen lanes a line.  Every loaded entry becomes a key
 // (its value - A) and a delta (its value - its predecessor's, base for a row's entry 0): the predecessor is the
 // lane before, or (a line's first entry) loaded by itself.  Entries before the row's cursor are only predecessors.
-// PASS_HIST: the keys <= F go into the buckets (count and delta), the smallest key with a delta of 2^31 or more into
-// misc[M_GIANT] instead; the entries of the window and those before A ("stale": in sorted rows repeats of an earlier
+// PASS_HIST: the keys <= F go into the buckets (count and delta; a delta of 2^31 or more raises po.giant and the window
+// has to be taken again: PASS_GIANT then finds the smallest key with such a delta, into misc[M_GIANT]); the entries
+// of the window and those before A ("stale": in sorted rows repeats of an earlier
 // frontier that lay behind their run then) are consumed: curnew[] takes the offset behind each row's last one.
 // PASS_LIST: the keys <= F whose bucket survived go into the list.  PASS_ONE (F = 0): the entries of the window are
 // counted and their deltas summed; consumed as in PASS_HIST.  `take` false: no key is taken (stale entries only).
@@ -255,15 +263,14 @@ __device__ __forceinline__ void sweep_pass(const SweepSm& sm, const i64* __restr
         u32 rowf[SWEEP_BATCH];          // its row | before the cursor << 16 | the row's entry 0 << 17
 #pragma unroll
         for (int j = 0; j < SWEEP_BATCH; ++j) {
-            const u32 l = 4u * (q0 + (u32)(j * NW + wave)) + grp;
-            const u32 row = l < T ? (u32)sm.linemap[l] : 0xffffu;
-            uint4 ri = make_uint4(0u, 0u, 0u, 0u);
-            if (l < T) ri = sm.rowinfo[row];
+            const u32 l = 4u * (q0 + (u32)(j * NW + wave)) + grp;          // (behind the plan's lines: row P, no entries)
+            const u32 row = (u32)sm.linemap[l];
+            const uint4 ri = sm.rowinfo[row];
             const int e = (int)ri.w + (int)((l - ri.y) * LINE + sub);
             const int rs = (int)(row * (u32)R);
-            const bool ok = l < T && e >= rs && (u32)e < ri.z;
+            const bool ok = e >= rs && (u32)e < ri.z;
             ent[j] = ok ? e : -1;
-            rowf[j] = (row & 0xffffu) | ((u32)e < ri.x ? 1u << 16 : 0u) | (e == rs ? 1u << 17 : 0u);
+            rowf[j] = row | ((u32)e < ri.x ? 1u << 16 : 0u) | (e == rs ? 1u << 17 : 0u);
             cv[j] = inst[ok ? e : 0];
             pv[j] = 0;
             if (ok && sub == 0 && e > rs) pv[j] = inst[e - 1];
@@ -274,8 +281,8 @@ __device__ __forceinline__ void sweep_pass(const SweepSm& sm, const i64* __restr
             const bool pre = (rowf[j] >> 16) & 1u, head = (rowf[j] >> 17) & 1u;
             const u64 c = (u64)cv[j];
             u64 pr = dpp_take<DPP_ROW_SHR1, 0xf>((u64)0, c);
-            if (sub == 0) pr = (u64)pv[j];
-            if (head) pr = base;
+            pr = sub == 0 ? (u64)pv[j] : pr;
+            pr = head ? base : pr;
             const u64 rel = c - a_abs, d = c - pr;
             const bool old = ok && !pre && (i64)rel < 0;
             const bool in = ok && !pre && take && (rel >> 32) == 0 && (u32)rel <= F;
@@ -288,15 +295,17 @@ __device__ __forceinline__ void sweep_pass(const SweepSm& sm, const i64* __restr
                         if (slot < (u32)C::LIST) sm.recs[slot] = (u64)k | (d << 32);
                     }
                 }
+            } else if (MODE == PASS_GIANT) {
+                if (in && (d >> 31) != 0) atomicMin(&sm.misc[M_GIANT], k);
             } else {
-                if (ok) po.neg |= (u32)(d >> 32);
-                if (old && d != 0) po.neg |= 0x80000000u;
+                po.neg |= (ok ? (u32)(d >> 32) : 0u) | (old && d != 0 ? 0x80000000u : 0u);
                 po.stale += (u32)__popcll(__ballot(old));
                 if (MODE == PASS_ONE) {
-                    if (in) { po.count += 1u; po.dsum += d; }
-                } else if (in) {
-                    if ((d >> 31) == 0) atomicAdd(&hist[k >> sh], (1ull << 46) | d);
-                    else if ((i64)d > 0) atomicMin(&sm.misc[M_GIANT], k);
+                    po.count += in ? 1u : 0u;
+                    po.dsum += in ? d : 0ull;
+                } else {
+                    po.giant |= in ? (u32)(d >> 31) : 0u;                  // (a delta of 2^31 or more spoils its bucket: the window is taken again)
+                    if (in) atomicAdd(&hist[k >> sh], (1ull << 46) | (u64)((u32)d & 0x7fffffffu));
                 }
                 const bool cons = in || old;
                 const u64 m = __ballot(cons);
@@ -311,7 +320,7 @@ __device__ __forceinline__ void sweep_pass(const SweepSm& sm, const i64* __restr
 template <int NT, int CAPL, int NBK, int LISTN, int PMAX>       // PMAX: the most rows the workgroup's LDS is laid out for
 __global__ __launch_bounds__(NT, NT == 256 ? 2 : 4) void zl_sweep_kernel(
     const i64* __restrict__ ts, i64 B, int P, int R, int nslices, int lines,
-    const InstInfo* __restrict__ info, const SegEntry* __restrict__ segtab,
+    const InstInfo* __restrict__ info, const SegEntry* __restrict__ segtab, i64* __restrict__ best,
     Partial* __restrict__ partial, int* __restrict__ status)
 {
     using C = SweepCfg<NT, CAPL, NBK, LISTN>;
@@ -419,6 +428,8 @@ __global__ __launch_bounds__(NT, NT == 256 ? 2 : 4) void zl_sweep_kernel(
             fmin = wave_scan(fmin, OpMin());
             cmin = wave_scan(cmin, OpMin());
             if (lane == WAVE - 1) { ((u32*)sm.red)[wave] = fmin; sm.red[NW + wave] = cmin; }
+            // what the other slices of the instance have found bounds the minimum as well (any admissible candidate's wait does)
+            if (tid == 0) sm.red[2 * NW] = (u64)__atomic_load_n(best + b, __ATOMIC_RELAXED);
             __syncthreads();                                              // B1
             F1 = ((u32*)sm.red)[0];
             first_rel = sm.red[NW];
@@ -431,6 +442,8 @@ __global__ __launch_bounds__(NT, NT == 256 ? 2 : 4) void zl_sweep_kernel(
             }
             F1 = uniform(F1);
             first_rel = uniform(first_rel);
+            const i64 shared = (i64)uniform(sm.red[2 * NW]);
+            UB = shared < UB ? shared : UB;
             if (ve - A < (u64)F1) F1 = (u32)(ve - A);                     // the slice ends there: no entry of it lies beyond
         }
         const u64 need64 = thr > A ? thr - A : 0ull;
@@ -442,16 +455,17 @@ __global__ __launch_bounds__(NT, NT == 256 ? 2 : 4) void zl_sweep_kernel(
         u32 F = F1 ? F1 - 1u : 0u;
         u32 sh = 0, consumed = 0, stale = 0, live = 0;
         u64 dsum = 0;
+        const i64 ub_before = UB;
         for (;;) {
             sh = shift_for<C::LOG_NB>((u64)F + 1);
             PassOut po;
-            po.neg = po.stale = po.count = 0;
+            po.giant = po.neg = po.stale = po.count = 0;
             po.dsum = 0;
             const bool one = F == 0 && F1 != 0;
             if (one) sweep_pass<NT, C, PASS_ONE>(sm, inst, R, base, a_abs, F, sh, true, T, po);
             else sweep_pass<NT, C, PASS_HIST>(sm, inst, R, base, a_abs, F, sh, F1 != 0, T, po);
             if (lane == 0 && po.stale) atomicAdd(&sm.misc[M_STALE], po.stale);
-            if (po.neg >> 31) atomicOr(&sm.misc[M_FLAGS], FLAG_NEG);
+            if ((po.neg >> 31) || po.giant) atomicOr(&sm.misc[M_FLAGS], ((po.neg >> 31) ? FLAG_NEG : 0u) | (po.giant ? FLAG_GIANT : 0u));
             __syncthreads();                                              // B2: the bucket words are complete
             const u32 flags = uniform(sm.misc[M_FLAGS]);
             stale = uniform(sm.misc[M_STALE]);
@@ -468,12 +482,17 @@ __global__ __launch_bounds__(NT, NT == 256 ? 2 : 4) void zl_sweep_kernel(
                 if (consumed && need == 0) { const i64 x = (i64)(W0 - dsum); UB = x < UB ? x : UB; }
                 break;
             }
-            const u32 giant = uniform(sm.misc[M_GIANT]);
-            if (giant <= F) {
-                // a step of 2^31 or more inside the window: up to before it, or that value alone
-                F = giant ? giant - 1u : 0u;
+            if (flags & FLAG_GIANT) {
+                // a step of 2^31 or more inside the window: up to before the first such, or that value alone
+                PassOut unused;
+                unused.giant = unused.neg = unused.stale = unused.count = 0;
+                unused.dsum = 0;
+                sweep_pass<NT, C, PASS_GIANT>(sm, inst, R, base, a_abs, F, sh, true, T, unused);
                 __syncthreads();
-                if (tid == 0) { sm.misc[M_STALE] = 0; sm.misc[M_GIANT] = 0xffffffffu; }
+                const u32 giant = uniform(sm.misc[M_GIANT]);
+                F = giant != 0xffffffffu && giant ? giant - 1u : 0u;
+                __syncthreads();
+                if (tid == 0) { sm.misc[M_STALE] = 0; sm.misc[M_GIANT] = 0xffffffffu; sm.misc[M_FLAGS] = 0; }
                 zero_share<C::BPT>(hist);
                 for (int p = tid; p < P; p += NT) sm.curnew[p] = 0;
                 __syncthreads();
@@ -591,7 +610,7 @@ __global__ __launch_bounds__(NT, NT == 256 ? 2 : 4) void zl_sweep_kernel(
             // ---- zl_argmin: the entries of the surviving buckets are listed (their deltas formed again) and evaluated
             if (sh != 0 && live > 0) {
                 PassOut unused;
-                unused.neg = unused.stale = unused.count = 0;
+                unused.giant = unused.neg = unused.stale = unused.count = 0;
                 unused.dsum = 0;
                 sweep_pass<NT, C, PASS_LIST>(sm, inst, R, base, a_abs, F, sh, true, T, unused);
                 __syncthreads();                                          // B4: the list is complete
@@ -616,6 +635,7 @@ __global__ __launch_bounds__(NT, NT == 256 ? 2 : 4) void zl_sweep_kernel(
             A += (u64)F + 1;
         }
         remaining -= consumed + stale < remaining ? consumed + stale : remaining;
+        if (tid == 0 && UB < ub_before) atomicMin(best + b, UB);
         // the cursors move behind the consumed entries
         for (int p = tid; p < P; p += NT) {
             const u32 cn = sm.curnew[p];
