@@ -77,7 +77,7 @@ def algorithmic_bytes(kernel: str, B: int, P: int, R: int, bins: int, windows: i
     n = float(B) * P * R
     cw = 2.0 if R < 65536 else 4.0          # bytes of one crossing index
     rows = 16.0 * B * P if predicted else 8.0 * n       # predicted rows: 16 bytes per worker stand for R timestamps
-    if kernel == "zl_instance_kernel":      # every timestamp once, all three outputs
+    if kernel in ("zl_instance_kernel", "zl_instance_reg_kernel"):      # every timestamp once, all three outputs
         return rows + B * (16.0 + 4.0 * P)
     if kernel == "zl_window_kernel":        # every timestamp once, two crossing rows per window, one result
         return rows + windows * (2.0 * cw * P + 16.0)

@@ -82,13 +82,13 @@ int check_device()
 }
 
 enum KernelId { K_INSTANCE = 0, K_INSTANCE_GENERAL, K_BOUNDS, K_PARTITION, K_BINCOUNT, K_PLAN, K_WINDOW,
-                K_WINDOW_GENERAL, K_FINISH, K_COPY, K_RANGE_INSTANCE, K_RANGE_WINDOW, K_PARTITION_PRED, K_RANGE_FAST, K_ADVANCE, K_SWEEP, K_SWEEP_FINISH, K_GRIDSCAN, K_GRIDSCAN_FINISH, K_READ, K_COUNT };
+                K_WINDOW_GENERAL, K_FINISH, K_COPY, K_RANGE_INSTANCE, K_RANGE_WINDOW, K_PARTITION_PRED, K_RANGE_FAST, K_ADVANCE, K_SWEEP, K_SWEEP_FINISH, K_GRIDSCAN, K_GRIDSCAN_FINISH, K_READ, K_INSTANCE_REG, K_COUNT };
 const char* const kKernelNames[K_COUNT] = {
     "zl_instance_kernel", "zl_instance_general_kernel", "zl_bounds_kernel", "zl_partition_kernel",
     "zl_bincount_kernel", "zl_plan_kernel", "zl_window_kernel", "zl_window_general_kernel",
     "zl_finish_kernel", "zl_copy_kernel", "zl_range_instance_kernel", "zl_range_window_kernel",
     "zl_partition_pred_kernel", "zl_range_fast_kernel", "zl_advance_kernel", "zl_sweep_kernel", "zl_sweep_finish_kernel", "zl_gridscan_kernel",
-    "zl_gridscan_finish_kernel", "zl_read_kernel"};
+    "zl_gridscan_finish_kernel", "zl_read_kernel", "zl_instance_reg_kernel"};
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -354,10 +354,20 @@ int run_batch(const i64* ts, const i64* le, const i64* iv, i64 B, int P, int R,
         else LAUNCH(K_INSTANCE, (zl_instance_kernel<NT_, ITEMS_, false>), grid, dim3(NT_), ts, le, iv, P, R, rshift, \
                     barrier, iters, wait, status);                                                          \
     } while (0)
+        // larger instances keep their records in registers: less LDS, several workgroups per CU
+#define LAUNCH_INSTANCE_REG(ITEMS_)                                                                         \
+    do {                                                                                                    \
+        if (pred) LAUNCH(K_INSTANCE_REG, (zl_instance_reg_kernel<512, ITEMS_, true>), grid, dim3(512), ts, le, iv, P, R, rshift, \
+                         barrier, iters, wait, status);                                                     \
+        else LAUNCH(K_INSTANCE_REG, (zl_instance_reg_kernel<512, ITEMS_, false>), grid, dim3(512), ts, le, iv, P, R, rshift, \
+                    barrier, iters, wait, status);                                                          \
+    } while (0)
         if (n <= 256) LAUNCH_INSTANCE(128, 2);
         else if (n <= 1024) LAUNCH_INSTANCE(256, 4);
         else if (n <= 4096) LAUNCH_INSTANCE(512, 8);
+        else if (n <= 8192) LAUNCH_INSTANCE_REG(16);
         else LAUNCH_INSTANCE(1024, 16);
+#undef LAUNCH_INSTANCE_REG
 #undef LAUNCH_INSTANCE
         // what the kernel above left: the general search in the smallest workgroup whose records hold an
         // instance (half of NT * ITEMS with 64-bit deltas), as many workgroups as fit the chip at once

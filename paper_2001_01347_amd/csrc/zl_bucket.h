@@ -95,14 +95,25 @@ __device__ __forceinline__ Smem carve_hot(unsigned char* smem)
 // the record area may hold anything (it is overwritten).  On return some threads
 // may still be reading LDS: the caller passes a barrier before writing it again.
 // Returns false (nothing computed) if some bucket is over the limit.
-template <int NT, int ITEMS, bool WITH_W0, class Map>
+//
+// Which of a thread's items exist is the caller's to say: Present::operator()(j).  The default
+// is the strided layout above (SlotsBelow).  LIST_CAP > 0: the record area holds only that many
+// records (at least 2 * BUCKET_LIMIT); if more entries survive the bounds they are scattered and
+// evaluated in rounds, whole buckets at a time (only with a map that has bounds).
+template <int NT>
+struct SlotsBelow {           // item j of thread t is slot j*NT + t of `total`
+    int total;
+    __device__ __forceinline__ bool operator()(int j) const { return j * NT + (int)threadIdx.x < total; }
+};
+template <int NT, int ITEMS, bool WITH_W0, class Map, int LIST_CAP = 0, class Present = SlotsBelow<NT>>
 __device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key)[ITEMS], const u32 (&dl)[ITEMS],
-                                                 const Map bucket, int total, u64 a, u64 thr, u32 P, u64 w0,
+                                                 const Map bucket, const Present present, u64 a, u64 thr, u32 P, u64 w0,
                                                  u64& best_wait, u32& best_key)
 {
     using H = HotCfg<NT, ITEMS>;
+    static_assert(LIST_CAP == 0 || (Map::HAS_BOUNDS && LIST_CAP >= 2 * (int)BUCKET_LIMIT), "a short list needs the bounds");
     u64* recs = sm.recs;
-    u64* bsum = sm.recs + H::BSUM_AT;
+    u64* bsum = sm.red - H::NB;                                       // the bucket words end where the scratch begins
     u32* cnt = sm.cnt;
     const int tid = threadIdx.x;
     u32* live_count = (u32*)(sm.red + H::RED_WORDS - 1);              // entries of the compact list
@@ -111,7 +122,7 @@ __device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key
     // zl_sort, step 1: per bucket, entry count and sum of deltas in one word
 #pragma unroll
     for (int j = 0; j < ITEMS; ++j)
-        if (j * NT + tid < total) {
+        if (present(j)) {
             const u32 bid = bucket(key[j]);
             atomicAdd(&bsum[bid], (1ull << SUM_BITS) | (u64)dl[j]);
         }
@@ -158,27 +169,13 @@ __device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key
         if (live0) at0 = atomicAdd(live_count, c0);
         if (live1) at1 = atomicAdd(live_count, c1);
         cnt[2 * tid] = at0; cnt[2 * tid + 1] = at1;
-        bsum[2 * tid] = sbase | ((u64)(at0 & (DROPPED - 1)) << SUM_BITS);     // BP(bucket) and the bucket's first slot
-        bsum[2 * tid + 1] = e0 | ((u64)(at1 & (DROPPED - 1)) << SUM_BITS);
-        __syncthreads();
-        // step 3: scatter the entries of the live buckets; afterwards cnt[b] is the end of bucket b
-#pragma unroll
-        for (int j = 0; j < ITEMS; ++j)
-            if (j * NT + tid < total) {
-                const u32 bid = bucket(key[j]);
-                const u32 slot = atomicAdd(&cnt[bid], 1u);
-                if (slot < DROPPED) recs[slot] = (u64)key[j] | ((u64)dl[j] << 32);
-            }
+        // BP(bucket) and the bucket's first slot (all ones in that field: the bucket is dropped)
+        constexpr u32 FIRST_MASK = (1u << (64 - SUM_BITS)) - 1u;
+        bsum[2 * tid] = sbase | ((u64)(live0 ? at0 : (LIST_CAP ? FIRST_MASK : 0u)) << SUM_BITS);
+        bsum[2 * tid + 1] = e0 | ((u64)(live1 ? at1 : (LIST_CAP ? FIRST_MASK : 0u)) << SUM_BITS);
         __syncthreads();
         const int live = (int)*live_count;
-        // zl_scan + zl_argmin: every listed entry evaluates its own candidate
-        for (int q = tid; q < live; q += NT) {
-            const u32 k = (u32)recs[q];
-            const u32 bid = bucket(k);
-            const u32 e = cnt[bid];
-            const u64 hb = bsum[bid];
-            u32 x = (u32)(hb >> SUM_BITS);
-            u64 S = hb & SUM_MASK;
+        auto evaluate = [&](u32 k, u32 x, u32 e, u64 S) {           // candidate k: its bucket's records are [x, e)
             for (; x < e; ++x) {
                 const u64 r = recs[x];
                 S += ((u32)r <= k) ? r >> 32 : 0ull;
@@ -186,6 +183,54 @@ __device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key
             if ((u64)k >= need) {
                 const u64 w = (u64)P * k + W0 - S;
                 if (w < bw || (w == bw && k < bk)) { bw = w; bk = k; }
+            }
+        };
+        if (LIST_CAP == 0 || live <= LIST_CAP) {
+            // step 3: scatter the entries of the live buckets; afterwards cnt[b] is the end of bucket b
+#pragma unroll
+            for (int j = 0; j < ITEMS; ++j)
+                if (present(j)) {
+                    const u32 bid = bucket(key[j]);
+                    const u32 slot = atomicAdd(&cnt[bid], 1u);
+                    if (slot < DROPPED) recs[slot] = (u64)key[j] | ((u64)dl[j] << 32);
+                }
+            __syncthreads();
+            // zl_scan + zl_argmin: every listed entry evaluates its own candidate
+            for (int q = tid; q < live; q += NT) {
+                const u32 k = (u32)recs[q];
+                const u32 bid = bucket(k);
+                const u64 hb = bsum[bid];
+                evaluate(k, (u32)(hb >> SUM_BITS), cnt[bid], hb & SUM_MASK);
+            }
+        } else {
+            // More survivors than the list holds: rounds of whole buckets.  A bucket belongs to the round
+            // its first slot falls in; it has at most BUCKET_LIMIT entries, so a round's slots, counted
+            // from the round's start, stay below LIST_CAP.
+            constexpr u32 ROUND = (u32)LIST_CAP - BUCKET_LIMIT;
+            for (u32 r0 = 0; r0 < (u32)live; r0 += ROUND) {
+#pragma unroll
+                for (int j = 0; j < ITEMS; ++j)
+                    if (present(j)) {
+                        const u32 bid = bucket(key[j]);
+                        const u32 first = (u32)(bsum[bid] >> SUM_BITS);
+                        if (first >= r0 && first - r0 < ROUND) {
+                            const u32 slot = atomicAdd(&cnt[bid], 1u);
+                            recs[slot - r0] = (u64)key[j] | ((u64)dl[j] << 32);
+                        }
+                    }
+                __syncthreads();
+                const u32 span = (u32)live - r0 < (u32)LIST_CAP ? (u32)live - r0 : (u32)LIST_CAP;
+                for (u32 q = tid; q < span; q += NT) {
+                    // a slot of this round holds a record iff it lies inside its own bucket's slots and
+                    // that bucket belongs to the round (anything else is left over from earlier)
+                    const u32 k = (u32)recs[q];
+                    const u32 bid = bucket(k);
+                    const u64 hb = bsum[bid];
+                    const u32 first = (u32)(hb >> SUM_BITS), e = cnt[bid];
+                    if (first >= r0 && first - r0 < ROUND && q + r0 >= first && q + r0 < e)
+                        evaluate(k, first - r0, e - r0, hb & SUM_MASK);
+                }
+                __syncthreads();
             }
         }
     } else {
@@ -196,12 +241,13 @@ __device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key
     // step 3: scatter; afterwards cnt[b] is the end of bucket b
 #pragma unroll
     for (int j = 0; j < ITEMS; ++j)
-        if (j * NT + tid < total) {
+        if (present(j)) {
             const u32 bid = bucket(key[j]);
             const u32 slot = atomicAdd(&cnt[bid], 1u);
             recs[slot] = (u64)key[j] | ((u64)dl[j] << 32);
         }
     // a 4-wide read of the last bucket may run past the end: entries that add nothing
+    const int total = present.total;              // (this form is for the strided layout)
     if (tid < H::PAD - 1) recs[total + tid] = 0xffffffffull;
     __syncthreads();
     // zl_scan + zl_argmin: every element evaluates its own candidate.  The bucket map

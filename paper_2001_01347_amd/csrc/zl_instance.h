@@ -136,7 +136,163 @@ __global__ __launch_bounds__(NT) void zl_instance_kernel(
     __syncthreads();
     u64 best_wait;
     u32 bkey;
-    if (!zl_bucket_finish<NT, ITEMS, false>(sm, key, dl, bucket, n, 0ull, thr, (u32)P, 0ull, best_wait, bkey)) {
+    if (!zl_bucket_finish<NT, ITEMS, false>(sm, key, dl, bucket, SlotsBelow<NT>{n}, 0ull, thr, (u32)P, 0ull, best_wait, bkey)) {
+        if (tid == 0) wait[b] = DEFERRED;      // clustered values: left to zl_instance_general_kernel
+        return;
+    }
+    const i64 bar = (i64)((u64)base + bkey);
+    if (tid == 0) {
+        barrier[b] = bar;
+        wait[b] = (i64)best_wait;
+        if (status) status[b] = (int)flags;
+    }
+    for (int p = tid; p < P; p += NT)
+        iters[b * (i64)P + p] = zl_iters_of(inst, lep, ivp, p, R, bar);
+}
+
+// The same search for the larger single-workgroup instances (4096 < P*R <= NT*ITEMS) with the
+// records held in registers from the loads to the evaluation: LDS holds only the bucket words,
+// the tables and a short list of the entries that survive the bounds, so that several
+// workgroups share a CU and one loads while another searches.
+// Wave w holds elements [w*64*items, (w+1)*64*items), 64 consecutive ones per item, so an
+// element's predecessor sits in the neighbouring lane.
+template <int NT, int ITEMS>
+struct WaveItems {            // which of a thread's items exist in that layout
+    u32 mask;
+    __device__ __forceinline__ bool operator()(int j) const { return (mask >> j) & 1u; }
+};
+template <int NT, int ITEMS>
+struct RegCfg {
+    using H = HotCfg<NT, ITEMS>;
+    static constexpr int LIST = 4096;                     // records of the short list
+    static constexpr size_t BYTES = (size_t)LIST * 8 + (size_t)H::NB * 8 + (size_t)H::RED_WORDS * 8 + (size_t)H::NB * 4 +
+                                    (size_t)H::COARSE * 16;
+};
+template <int NT, int ITEMS, bool PRED>
+__global__ __launch_bounds__(NT, 4) void zl_instance_reg_kernel(
+    const i64* __restrict__ ts, const i64* __restrict__ le, const i64* __restrict__ iv, int P, int R, int rshift,
+    i64* __restrict__ barrier, int* __restrict__ iters, i64* __restrict__ wait,
+    int* __restrict__ status)
+{
+    using H = HotCfg<NT, ITEMS>;
+    using C = RegCfg<NT, ITEMS>;
+    static_assert(ITEMS <= 32 && ITEMS % 16 == 0, "item masks are one word; loads go in batches of 16");
+    __shared__ __align__(16) unsigned char smem[C::BYTES];
+    Smem sm;
+    sm.recs = (u64*)smem;                                  // the short list
+    sm.dhi = nullptr;
+    sm.red = sm.recs + C::LIST + H::NB;                    // the bucket words sit between the list and the scratch
+    sm.cnt = (u32*)(sm.red + H::RED_WORDS);                // followed by the coarse tables
+
+    const int tid = threadIdx.x;
+    const i64 b = blockIdx.x;
+    const int n = P * R;
+    const i64* __restrict__ inst = PRED ? nullptr : ts + b * (i64)n;
+    const i64* __restrict__ lep = PRED ? le + b * (i64)P : nullptr;
+    const i64* __restrict__ ivp = PRED ? iv + b * (i64)P : nullptr;
+    // e / R for e < 2^16 (n <= 16384 here): exact with the rounded-up reciprocal, R >= 3 where it is used
+    const u32 rinv = rshift >= 0 ? 0u : 0xffffffffu / (u32)R + 1u;
+    auto row_of = [&](int e) -> int { return rshift >= 0 ? (e >> rshift) : (int)__umulhi((u32)e, rinv); };
+    auto at = [&](int e) -> i64 {                          // element e of the instance
+        if (!PRED) return inst[e];
+        const int p = row_of(e);
+        return (i64)((u64)lep[p] + (u64)(e - p * R + 1) * (u64)ivp[p]);
+    };
+    {
+        u64* bsum = sm.red - H::NB;
+        bsum[tid] = 0; bsum[tid + NT] = 0;
+    }
+    const int lane = tid & (WAVE - 1), wave = tid >> 6;
+    const int items = (n + NT - 1) / NT;
+    const int wbase = wave * WAVE * items;
+    const i64 t00 = at(0);
+    i64 carry = (wbase > 0 && wbase < n) ? at(wbase - 1) : 0;    // element ahead of the wave's first
+    i64 mn = INT64_MAX, mxf = INT64_MIN, mxl = INT64_MIN;          // min first, max first, max last of the rows
+    int bad = 0;
+    u32 key[ITEMS], dl[ITEMS];
+    u32 have = 0, heads = 0;                               // items that exist; items that are a row's first entry
+    constexpr int LB = 16;                                 // loads of a thread in flight together
+#pragma unroll
+    for (int g = 0; g < ITEMS; g += LB) {
+#pragma unroll
+        for (int j = 0; j < LB; ++j) { key[g + j] = 0; dl[g + j] = 0; }
+        if (g < items) {
+            i64 v[LB];
+#pragma unroll
+            for (int j = 0; j < LB; ++j) {
+                const int e = wbase + (g + j) * WAVE + lane;
+                v[j] = (g + j < items && e < n) ? at(e) : 0;
+            }
+#pragma unroll
+            for (int j = 0; j < LB; ++j) {
+                const int e = wbase + (g + j) * WAVE + lane;
+                i64 prv = dpp_take<DPP_WAVE_SHR1, 0xf>((i64)0, v[j]);
+                if (lane == 0) prv = carry;
+                carry = __shfl(v[j], WAVE - 1, WAVE);
+                if (g + j < items && e < n) {
+                    const int i = e - row_of(e) * R;
+                    const u32 rel = (u32)((u64)v[j] - (u64)t00);
+                    have |= 1u << (g + j);
+                    key[g + j] = rel;
+                    if (i == 0) { heads |= 1u << (g + j); mn = v[j] < mn ? v[j] : mn; mxf = v[j] > mxf ? v[j] : mxf; }
+                    else { dl[g + j] = (u32)((u64)v[j] - (u64)prv); bad |= (v[j] < prv); }
+                    if (i == R - 1) mxl = v[j] > mxl ? v[j] : mxl;
+                }
+            }
+        }
+    }
+    i64 base, first_max, last_max;
+    block_bounds<NT>(mn, mxf, mxl, (i64*)sm.red, base, first_max, last_max);
+    const u64 range = (u64)last_max - (u64)base;
+    const u64 thr = (u64)first_max - (u64)base;
+    const u32 shift = (u32)((u64)t00 - (u64)base);                 // key relative to base = key relative to t00 + shift
+
+    u32 flags = 0;
+    if (range > (u64)INT64_MAX / (u64)P) flags |= EBSP_STATUS_OVERFLOW;
+    if (range >> 32) {
+        // deltas need more than 32 bits: left to zl_instance_general_kernel
+        if (tid == 0) wait[b] = DEFERRED;
+        return;
+    }
+    if (__syncthreads_or(bad)) flags |= EBSP_STATUS_UNSORTED;
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        key[j] += shift;
+        dl[j] = ((heads >> j) & 1u) ? key[j] : dl[j];              // a row's first delta is its key relative to base
+    }
+    const WaveItems<NT, ITEMS> present{have};
+    // the equalising bucket map: key counts of up to 256 coarse bins -> buckets per bin
+    u32* coarse = sm.cnt;                                   // free until the bucket scan
+    u64* tab = (u64*)(sm.cnt + H::NB);
+    const int bl = bit_length(range);
+    TableMap<true> bucket;
+    bucket.tab = tab;
+    bucket.cshift = bl > 8 ? (u32)(bl - 8) : 0u;
+    bucket.cmask = (1u << bucket.cshift) - 1u;
+    bucket.span = (u32)range;
+    static_assert(H::COARSE <= NT, "one coarse bin per thread at most");
+    if (tid < H::COARSE) coarse[tid] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j)
+        if (present(j)) atomicAdd(&coarse[bucket.coarse(key[j])], 1u);
+    __syncthreads();
+    {
+        const u32 c = tid < H::COARSE ? coarse[tid] : 0u;
+        u32 all;
+        const u32 below_c = block_excl_scan<u32, NT>(c, (u32*)sm.red, all);
+        if (tid < H::COARSE) {
+            u64 tw, iw;
+            table_entry(below_c, c, (u32)n, (u32)H::NB, bucket.cshift, tw, iw);
+            tab[tid] = tw;
+            tab[H::COARSE + tid] = iw;
+        }
+    }
+    __syncthreads();
+    u64 best_wait;
+    u32 bkey;
+    if (!zl_bucket_finish<NT, ITEMS, false, TableMap<true>, C::LIST>(sm, key, dl, bucket, present, 0ull, thr, (u32)P, 0ull,
+                                                                     best_wait, bkey)) {
         if (tid == 0) wait[b] = DEFERRED;      // clustered values: left to zl_instance_general_kernel
         return;
     }

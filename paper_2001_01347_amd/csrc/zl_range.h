@@ -347,20 +347,45 @@ __device__ __forceinline__ bool zl_range_bucket_search(const Smem& sm, const Row
         next = last ? NEVER : nxt - start;
         gone = inner ? start - prv : 0u;
     };
-    // sweep 2: reach, far and the entry count of every bucket; the keys stay in registers
+    // sweep 2: reach, far and the entry count of every bucket; the keys stay in registers.  The three
+    // words of every entry of a batch are asked for before any of them is used.
     u32 key[ITEMS];
+    constexpr int RB = ITEMS < GATHER_BATCH ? ITEMS : GATHER_BATCH;
+    static_assert(ITEMS % RB == 0, "batches must tile the items");
 #pragma unroll
-    for (int j = 0; j < ITEMS; ++j) {
-        const int q = j * NT + tid;
-        key[j] = 0;
-        if (j * NT < total) {
-            u32 next, gone;
-            read_entry(q < total ? recs[q] : (FIRST_OF_ROW | LAST_OF_ROW), key[j], next, gone);
-            if (q < total) {
-                const u32 b = bucket(key[j]);
-                atomicAdd(&flag[b], 1u);
-                atomicMax(&reach[b], next);
-                if (gone) atomicMax(&far[b], gone);
+    for (int g = 0; g < ITEMS; g += RB) {
+#pragma unroll
+        for (int j = 0; j < RB; ++j) key[g + j] = 0;
+        if (g * NT < total) {
+            u64 src[RB];
+            u32 cur[RB], nxt[RB], prv[RB];
+#pragma unroll
+            for (int j = 0; j < RB; ++j) {
+                const int q = (g + j) * NT + tid;
+                src[j] = q < total ? recs[q] : (FIRST_OF_ROW | LAST_OF_ROW);   // beyond the end: entry 0 alone, harmless
+            }
+#pragma unroll
+            for (int j = 0; j < RB; ++j) {
+                const u32 at = (u32)src[j];
+                const u32 up = (u32)(src[j] >> 32);
+                const u32 inner = (up >> 1) & ~up & 1u;                       // has a predecessor before the window
+                const u32 more = ~(up >> 2) & 1u;                              // not the row's last entry
+                cur[j] = *(const u32*)(bytes + (at << 3));
+                nxt[j] = *(const u32*)(bytes + ((at + more) << 3));
+                prv[j] = *(const u32*)(bytes + ((at - inner) << 3));
+            }
+#pragma unroll
+            for (int j = 0; j < RB; ++j) {
+                const int q = (g + j) * NT + tid;
+                const u32 up = (u32)(src[j] >> 32);
+                const bool inner = ((up >> 1) & ~up & 1u) != 0, last = ((up >> 2) & 1u) != 0;
+                key[g + j] = cur[j] - start;
+                if (q < total) {
+                    const u32 b = bucket(key[g + j]);
+                    atomicAdd(&flag[b], 1u);
+                    atomicMax(&reach[b], last ? NEVER : nxt[j] - start);
+                    if (inner && start != prv[j]) atomicMax(&far[b], start - prv[j]);
+                }
             }
         }
     }

@@ -79,7 +79,7 @@ __device__ __forceinline__ void window_search(const Smem& sm, const Rows& rw, co
                 if (zl_bucket_finish<NT, ITEMS, true>(sm, key, dl,
                                                       linear_map((u32)(wv.Elast - wv.A), H::NB, wv.scale ? wv.scale : 1u,
                                                                  wv.inv52),
-                                                      total, wv.A, ii.thr, (u32)rw.P, w0, r.wait, bkey))
+                                                      SlotsBelow<NT>{total}, wv.A, ii.thr, (u32)rw.P, w0, r.wait, bkey))
                     r.brel = wv.A + bkey;
                 else
                     defer = true;

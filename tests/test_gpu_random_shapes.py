@@ -82,3 +82,34 @@ def test_random_predicted_rows(zl, oracle, seed):
         ob, oi, ow, rc, _ = oracle.zipline(oracle.predicted_rows(le, iv, R), "sweep", threads=16)
         assert (rc == 0).all() and (st == 0).all(), label
         assert np.array_equal(bar, ob) and np.array_equal(w, ow) and np.array_equal(it, oi), label
+
+
+@pytest.mark.parametrize("P,R", [(2, 4096), (3, 2731), (5, 1000), (8, 1024), (64, 128), (100, 80), (1000, 8), (4100, 1), (4097, 2), (1, 8192), (1, 4097)])
+def test_instances_of_4097_to_8192_entries(zl, oracle, P, R):
+    """One workgroup each, records in registers: the short list of surviving entries is filled in one round where
+    most buckets are dropped (many workers) and in several where few are (few workers), stored and predicted rows;
+    equal values, a spread above 2^32 and unsorted rows take the exits to the general search."""
+    rng = np.random.default_rng(P * 10007 + R)
+    B = 12
+    steps = rng.integers(1, 2000, size=(B, P, R)).astype(np.int64)
+    steps[1] = rng.integers(0, 2, size=(P, R))                       # many equal values
+    steps[2] *= 40                                                    # wide
+    steps[3, :, R // 2] += 1 << 33                                    # spread above 2^32
+    steps[4] = 7                                                      # all rows alike
+    ts = np.cumsum(steps, axis=2) + rng.integers(0, 5000, size=(B, P, 1)) + 1_700_000_000_000_000
+    if R > 2:
+        ts[5, P // 2, 1], ts[5, P // 2, 2] = ts[5, P // 2, 2] + 5, ts[5, P // 2, 1]      # one row out of order
+    t = torch.from_numpy(ts).cuda()
+    bar, it, w, st = (x.cpu().numpy() for x in zl.ebsp_zipline_batch(t))
+    ob, oi, ow, rc, _ = oracle.zipline(ts, "sweep", threads=16)
+    ok = rc == 0
+    assert np.array_equal(st != 0, rc != 0) and ok.sum() >= B - 1
+    assert np.array_equal(bar[ok], ob[ok]) and np.array_equal(w[ok], ow[ok]) and np.array_equal(it[ok], oi[ok])
+    iv = rng.integers(1, 3000, size=(B, P)).astype(np.int64)
+    iv[1] = 0
+    iv[2] = 1 << 22
+    le = rng.integers(0, 10 ** 6, size=(B, P)).astype(np.int64)
+    bar, it, w, st = (x.cpu().numpy() for x in zl.ebsp_predict_zipline_batch(torch.from_numpy(le).cuda(), torch.from_numpy(iv).cuda(), R))
+    ob, oi, ow, rc, _ = oracle.zipline(oracle.predicted_rows(le, iv, R), "sweep", threads=16)
+    assert (rc == 0).all() and (st == 0).all()
+    assert np.array_equal(bar, ob) and np.array_equal(w, ow) and np.array_equal(it, oi)
