@@ -13,6 +13,8 @@ namespace {
 //      segment written into that element's slot (index into the instance;
 //      FIRST_OF_ROW: the row's very first entry, which has no predecessor;
 //      FIRST_OF_SEGMENT: the entry whose predecessor lies before the window).
+//      Stored rows: one 32-bit word (29 bits of index, the marks above them);
+//      predicted rows: 64 bits (index in the row, marks, row number).
 //      The crossing indices of a round are all fetched before any is used.
 //   2. one thread per slot: read the source word, load the low words of the
 //      element and of its predecessor (GATHER_BATCH elements of a thread in
@@ -23,12 +25,14 @@ namespace {
 //      of row p before the window) is collected from the segment-first entries;
 //      rows without any entry in the window add their share in sweep 1.
 // Returns the number of entries; nothing is loaded if it exceeds `cap`.
-constexpr u64 FIRST_OF_ROW = 1ull << 32, FIRST_OF_SEGMENT = 1ull << 33;
+constexpr u64 FIRST_OF_ROW = 1ull << 32, FIRST_OF_SEGMENT = 1ull << 33;      // predicted rows
 constexpr int PRED_ROW_SHIFT = 34;        // predicted rows: the row number sits above the two flags
+constexpr u32 SRC_INDEX = (1u << 29) - 1u, SRC_ROW = 1u << 29, SRC_SEGMENT = 1u << 30, SRC_LAST = 1u << 31;   // stored rows
 // rows a thread takes per round of sweep 1: one round covers 1024 rows
 template <int NT> constexpr int ROWS_PER_THREAD = NT >= 1024 ? 1 : 1024 / NT;
 constexpr int WINDOWS_PER_BLOCK = 2;      // consecutive windows a workgroup handles, one after the other
-constexpr u64 HOT_MAX_ENTRIES = 1ull << 29;   // P*R below this: byte offsets into an instance fit 32 bits
+constexpr u64 HOT_MAX_ENTRIES = 1ull << 29;   // P*R below this: byte offsets into an instance fit 32 bits, indices 29
+static_assert(HOT_MAX_ENTRIES - 1 <= SRC_INDEX, "an index must fit its field of the source word");
 
 template <int NT, class CT>
 __device__ __forceinline__ void load_ranges(const Rows& rw, int p0, u32 (&lo)[ROWS_PER_THREAD<NT>], u32 (&hi)[ROWS_PER_THREAD<NT>])
@@ -61,33 +65,50 @@ __device__ __forceinline__ void gather_batch(const u64* recs, const char* bytes,
 {
     const int tid = threadIdx.x;
     if (g * NT >= total) return;
-    u64 src[G];
     u32 cur[G], prv[G];
+    if constexpr (PRED) {
+        u64 src[G];
 #pragma unroll
-    for (int j = 0; j < G; ++j) {
-        const int q = (g + j) * NT + tid;
-        src[j] = q < total ? recs[q] : FIRST_OF_ROW;               // beyond the end: entry 0, harmless
-    }
+        for (int j = 0; j < G; ++j) {
+            const int q = (g + j) * NT + tid;
+            src[j] = q < total ? recs[q] : FIRST_OF_ROW;               // beyond the end: entry 0, harmless
+        }
 #pragma unroll
-    for (int j = 0; j < G; ++j) {
-        if (PRED) {
-            // predicted rows: the source word holds the row (above the flags) and the index in it
+        for (int j = 0; j < G; ++j) {
+            // the source word holds the row (above the flags) and the index in it
             const uint2 fs = par[(u32)(src[j] >> PRED_ROW_SHIFT)];  // first value of the row, interval
             cur[j] = fs.x + (u32)src[j] * fs.y;
             prv[j] = cur[j] - fs.y;
-        } else {
-            const u32 at = (u32)src[j];
-            const u32 pat = at - (1u - ((u32)(src[j] >> 32) & 1u));    // a row's first entry stands in for its predecessor
+        }
+#pragma unroll
+        for (int j = 0; j < G; ++j) {
+            const u32 from = (src[j] & FIRST_OF_ROW) ? start : prv[j];
+            key[g + j] = cur[j] - start;
+            dl[g + j] = cur[j] - from;
+            w0 += (src[j] & FIRST_OF_SEGMENT) ? (u64)(start - from) : 0ull;   // below 2^32 like every relative value
+        }
+    } else {
+        const u32* words = (const u32*)recs;
+        u32 src[G];
+#pragma unroll
+        for (int j = 0; j < G; ++j) {
+            const int q = (g + j) * NT + tid;
+            src[j] = q < total ? words[q] : SRC_ROW;                   // beyond the end: entry 0, harmless
+        }
+#pragma unroll
+        for (int j = 0; j < G; ++j) {
+            const u32 at = src[j] & SRC_INDEX;
+            const u32 pat = at - (1u - ((src[j] >> 29) & 1u));         // a row's first entry stands in for its predecessor
             cur[j] = *(const u32*)(bytes + (at << 3));
             prv[j] = *(const u32*)(bytes + (pat << 3));
         }
-    }
 #pragma unroll
-    for (int j = 0; j < G; ++j) {
-        const u32 from = (src[j] & FIRST_OF_ROW) ? start : prv[j];
-        key[g + j] = cur[j] - start;
-        dl[g + j] = cur[j] - from;
-        w0 += (src[j] & FIRST_OF_SEGMENT) ? (u64)(start - from) : 0ull;   // below 2^32 like every relative value
+        for (int j = 0; j < G; ++j) {
+            const u32 from = (src[j] & SRC_ROW) ? start : prv[j];
+            key[g + j] = cur[j] - start;
+            dl[g + j] = cur[j] - from;
+            w0 += (src[j] & SRC_SEGMENT) ? (u64)(start - from) : 0ull;  // below 2^32 like every relative value
+        }
     }
 }
 
@@ -95,8 +116,7 @@ __device__ __forceinline__ void gather_batch(const u64* recs, const char* bytes,
 // its slot.  Returns the number of entries (none is written if they exceed `cap`).  For the rows
 // without an entry in the window the distances from their last value before it to the window
 // start are summed into before_sum and their maximum goes to before_max.  WITH_LAST marks a
-// row's very last entry too (stored rows only: the mark shares its bit with the row number).
-constexpr u64 LAST_OF_ROW = 1ull << 34;
+// row's very last entry too (stored rows only).
 template <int NT, class CT, bool PRED, bool WITH_LAST>
 __device__ __forceinline__ int zl_place_rows(const Smem& sm, const Rows& rw, u64 start64, int cap,
                                              const u32 (&lo0)[ROWS_PER_THREAD<NT>], const u32 (&hi0)[ROWS_PER_THREAD<NT>],
@@ -140,27 +160,39 @@ __device__ __forceinline__ int zl_place_rows(const Smem& sm, const Rows& rw, u64
         u32 slot = (u32)total + block_excl_scan<u32, NT>(mine, (u32*)sm.red, round);
         total += (int)round;
         if (total > cap) return total;                       // the same for every thread: nothing is written
-        // The source words of a row's segment: (index, flags) pairs, two per trip.  This loop runs as
-        // long as the longest segment among a wave's rows, so it is kept to a store and two additions.
-        constexpr u32 SEGMENT_BIT = (u32)(FIRST_OF_SEGMENT >> 32), ROW_BIT = (u32)(FIRST_OF_ROW >> 32),
-                      LAST_BIT = (u32)(LAST_OF_ROW >> 32);
+        // The source words of a row's segment, two per trip.  This loop runs as long as the longest
+        // segment among a wave's rows, so it is kept to a store and two additions.
 #pragma unroll
         for (int c = 0; c < RPT; ++c) {
             const int p = p0 + c * NT + tid;
             const u32 n = hi[c] - lo[c];
             if (p < rw.P && n > 0) {
-                const u32 rest = PRED ? (u32)p << (PRED_ROW_SHIFT - 32) : 0u;       // upper word of every entry but the first
-                const u32 first = PRED ? lo[c] : (u32)p * (u32)rw.R + lo[c];
-                uint2* dst = (uint2*)recs + slot;
-                dst[0] = make_uint2(first, rest | SEGMENT_BIT | (lo[c] == 0 ? ROW_BIT : 0u));
-                u32 i = 1;
-                for (; i + 1 < n; i += 2) {
-                    dst[i] = make_uint2(first + i, rest);
-                    dst[i + 1] = make_uint2(first + i + 1, rest);
+                if constexpr (PRED) {
+                    constexpr u32 SEGMENT_BIT = (u32)(FIRST_OF_SEGMENT >> 32), ROW_BIT = (u32)(FIRST_OF_ROW >> 32);
+                    const u32 rest = (u32)p << (PRED_ROW_SHIFT - 32);            // upper word of every entry but the first
+                    const u32 first = lo[c];
+                    uint2* dst = (uint2*)recs + slot;
+                    dst[0] = make_uint2(first, rest | SEGMENT_BIT | (lo[c] == 0 ? ROW_BIT : 0u));
+                    u32 i = 1;
+                    for (; i + 1 < n; i += 2) {
+                        dst[i] = make_uint2(first + i, rest);
+                        dst[i + 1] = make_uint2(first + i + 1, rest);
+                    }
+                    if (i < n) dst[i] = make_uint2(first + i, rest);
+                } else {
+                    const u32 first = (u32)p * (u32)rw.R + lo[c];
+                    const u32 marks = SRC_SEGMENT | (lo[c] == 0 ? SRC_ROW : 0u);
+                    u32* dst = (u32*)recs + slot;
+                    dst[0] = first | marks;
+                    u32 i = 1;
+                    for (; i + 1 < n; i += 2) {
+                        dst[i] = first + i;
+                        dst[i + 1] = first + i + 1;
+                    }
+                    if (i < n) dst[i] = first + i;
+                    if (WITH_LAST && hi[c] == (u32)rw.R)             // the row's very last entry (after the stores above, same thread)
+                        dst[n - 1] = (first + n - 1) | (n == 1 ? marks : 0u) | SRC_LAST;
                 }
-                if (i < n) dst[i] = make_uint2(first + i, rest);
-                if (WITH_LAST && hi[c] == (u32)rw.R)             // the row's very last entry (after the stores above, same thread)
-                    dst[n - 1].y = (n == 1 ? rest | SEGMENT_BIT | (lo[c] == 0 ? ROW_BIT : 0u) : rest) | LAST_BIT;
                 slot += n;
             }
         }

@@ -169,14 +169,14 @@ struct RegCfg {
                                     (size_t)H::COARSE * 16;
 };
 template <int NT, int ITEMS, bool PRED>
-__global__ __launch_bounds__(NT, 4) void zl_instance_reg_kernel(
+__global__ __launch_bounds__(NT, 6) void zl_instance_reg_kernel(
     const i64* __restrict__ ts, const i64* __restrict__ le, const i64* __restrict__ iv, int P, int R, int rshift,
     i64* __restrict__ barrier, int* __restrict__ iters, i64* __restrict__ wait,
     int* __restrict__ status)
 {
     using H = HotCfg<NT, ITEMS>;
     using C = RegCfg<NT, ITEMS>;
-    static_assert(ITEMS <= 32 && ITEMS % 16 == 0, "item masks are one word; loads go in batches of 16");
+    static_assert(ITEMS <= 32 && ITEMS % 16 == 0, "item masks are one word; loads go in batches of 8");
     __shared__ __align__(16) unsigned char smem[C::BYTES];
     Smem sm;
     sm.recs = (u64*)smem;                                  // the short list
@@ -211,7 +211,7 @@ __global__ __launch_bounds__(NT, 4) void zl_instance_reg_kernel(
     int bad = 0;
     u32 key[ITEMS], dl[ITEMS];
     u32 have = 0, heads = 0;                               // items that exist; items that are a row's first entry
-    constexpr int LB = 16;                                 // loads of a thread in flight together
+    constexpr int LB = 8;                                  // loads of a thread in flight together
 #pragma unroll
     for (int g = 0; g < ITEMS; g += LB) {
 #pragma unroll

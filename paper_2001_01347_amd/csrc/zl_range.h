@@ -302,6 +302,7 @@ __device__ __forceinline__ void zl_range_window(const Smem& sm, const Rows& rw, 
 // the source words and d is evaluated exactly from that short list.
 // Returns false if the window has to be left to the sort-based search (too many
 // entries for the list to fit behind them, or too many listed).
+template <int NT> constexpr int RANGE_LIST_WORDS = 4 * 2 * NT;      // the short list: 2*NT entries of four words
 
 
 template <int NT, int ITEMS, class CT>
@@ -317,7 +318,7 @@ __device__ __forceinline__ bool zl_range_bucket_search(const Smem& sm, const Row
     constexpr int RANGE_LIST_CAP = 2 * NT;                  // entries of the short list (four words each, behind the source words)
     const int tid = threadIdx.x;
     u64* recs = sm.recs;
-    u32* reach = (u32*)(sm.recs + H::BSUM_AT);              // NB words, later M
+    u32* reach = (u32*)(sm.red - H::NB);                    // NB words, later M
     u32* far = reach + NB;                                  // NB words, later F (exclusive)
     u32* flag = sm.cnt;                                     // NB words: entry counts, later what a bucket is kept for
     u32* misc = (u32*)(sm.red + H::RED_WORDS - 3);          // listed holders, lowest and highest kept value, absent rows, listed others
@@ -336,10 +337,11 @@ __device__ __forceinline__ bool zl_range_bucket_search(const Smem& sm, const Row
     if (total > H::CAP - 2 * RANGE_LIST_CAP) return false;
     if (total == 0) return true;
     const LinearMap bucket = linear_map((u32)(wv.Elast - a), NB, wv.scale ? wv.scale : 1u, wv.inv52);
-    auto read_entry = [&](u64 src, u32& key, u32& next, u32& gone) {     // an entry through its source word
-        const u32 at = (u32)src;
-        const bool inner = (src & FIRST_OF_SEGMENT) && !(src & FIRST_OF_ROW);   // has a predecessor before the window
-        const bool last = (src & LAST_OF_ROW) != 0;
+    const u32* words = (const u32*)recs;                    // the source words
+    auto read_entry = [&](u32 src, u32& key, u32& next, u32& gone) {     // an entry through its source word
+        const u32 at = src & SRC_INDEX;
+        const bool inner = (src & SRC_SEGMENT) && !(src & SRC_ROW);   // has a predecessor before the window
+        const bool last = (src & SRC_LAST) != 0;
         const u32 cur = *(const u32*)(bytes + (at << 3));
         const u32 nxt = *(const u32*)(bytes + ((at + (last ? 0u : 1u)) << 3));
         const u32 prv = *(const u32*)(bytes + ((at - (inner ? 1u : 0u)) << 3));
@@ -357,17 +359,17 @@ __device__ __forceinline__ bool zl_range_bucket_search(const Smem& sm, const Row
 #pragma unroll
         for (int j = 0; j < RB; ++j) key[g + j] = 0;
         if (g * NT < total) {
-            u64 src[RB];
+            u32 src[RB];
             u32 cur[RB], nxt[RB], prv[RB];
 #pragma unroll
             for (int j = 0; j < RB; ++j) {
                 const int q = (g + j) * NT + tid;
-                src[j] = q < total ? recs[q] : (FIRST_OF_ROW | LAST_OF_ROW);   // beyond the end: entry 0 alone, harmless
+                src[j] = q < total ? words[q] : (SRC_ROW | SRC_LAST);          // beyond the end: entry 0 alone, harmless
             }
 #pragma unroll
             for (int j = 0; j < RB; ++j) {
-                const u32 at = (u32)src[j];
-                const u32 up = (u32)(src[j] >> 32);
+                const u32 at = src[j] & SRC_INDEX;
+                const u32 up = src[j] >> 29;                                   // the marks: row, segment, last
                 const u32 inner = (up >> 1) & ~up & 1u;                       // has a predecessor before the window
                 const u32 more = ~(up >> 2) & 1u;                              // not the row's last entry
                 cur[j] = *(const u32*)(bytes + (at << 3));
@@ -377,7 +379,7 @@ __device__ __forceinline__ bool zl_range_bucket_search(const Smem& sm, const Row
 #pragma unroll
             for (int j = 0; j < RB; ++j) {
                 const int q = (g + j) * NT + tid;
-                const u32 up = (u32)(src[j] >> 32);
+                const u32 up = src[j] >> 29;
                 const bool inner = ((up >> 1) & ~up & 1u) != 0, last = ((up >> 2) & 1u) != 0;
                 key[g + j] = cur[j] - start;
                 if (q < total) {
@@ -398,7 +400,7 @@ __device__ __forceinline__ bool zl_range_bucket_search(const Smem& sm, const Row
     // M: prefix maximum of reach (inclusive), F: maximum of far over the buckets behind (and the absent rows)
     const u32 m_before = block_excl_scan_op<u32, NT>(r0 > r1 ? r0 : r1, (u32*)sm.red, OpMax());
     const u32 M0 = m_before > r0 ? m_before : r0, M1 = M0 > r1 ? M0 : r1;
-    u32* mirror = (u32*)(recs + ((total + 1) & ~1));        // NT words behind the source words
+    u32* mirror = (u32*)recs + ((total + 3) & ~3);          // NT words behind the source words
     mirror[NT - 1 - tid] = g0 > g1 ? g0 : g1;
     __syncthreads();
     const u32 mv = mirror[tid];
@@ -489,7 +491,7 @@ __device__ __forceinline__ bool zl_range_bucket_search(const Smem& sm, const Row
     const int back = RANGE_LIST_CAP - others;               // the list is [0, holders) and [back, RANGE_LIST_CAP)
     for (int i = tid; i < holders + others; i += NT) {
         const int e = i < holders ? i : back + (i - holders);
-        read_entry(recs[lslot[e] & 0xffffu], lkey[e], lnext[e], lgone[e]);
+        read_entry(words[lslot[e] & 0xffffu], lkey[e], lnext[e], lgone[e]);
     }
     __syncthreads();
     u64 bd = U64_MAX;
@@ -564,15 +566,16 @@ struct RangeSearch {
 // The fast range search over all windows; windows it cannot take are marked for
 // zl_range_window_kernel.
 template <int NT, int ITEMS, class CT>
-__global__ __launch_bounds__(NT, 4) void zl_range_fast_kernel(
+__global__ __launch_bounds__(NT, (NT > 512 ? 4 : 6)) void zl_range_fast_kernel(
     const i64* __restrict__ ts, i64 B, int P, int R,
     const InstInfo* __restrict__ info, const CT* __restrict__ cross, int stride,
     const u32* __restrict__ winstart, const WinVal* __restrict__ winval, int max_win, u32 groups, u32 groups_inv,
     Partial* __restrict__ partial)
 {
-    using H = HotCfg<NT, ITEMS, false>;
-    __shared__ __align__(16) unsigned char smem[H::BYTES];
-    const Smem sm = carve_hot<NT, ITEMS>(smem);
+    // the source words of at most CAP - 2 * (2*NT) entries, then the short list
+    using L = WinHot<NT, ITEMS, false, RANGE_LIST_WORDS<NT> - 4 * NT>;
+    __shared__ __align__(16) unsigned char smem[L::BYTES];
+    const Smem sm = L::carve(smem);
     window_pairs<NT, ITEMS, CT, RangeSearch<NT, ITEMS, CT>>(sm, ts, nullptr, B, P, R, info, cross, stride, winstart,
                                                            winval, max_win, groups, groups_inv, partial);
 }

@@ -51,6 +51,28 @@ __device__ __forceinline__ WinPos locate_window(i64 b, int j, const InstInfo& ii
     return w;
 }
 
+// LDS of a fast window search.  The record area first holds the source words of the window's
+// entries and then the entries that survive the bounds.  Stored rows: 4 bytes per source word, so
+// the area is half the size and holds records for half the entries (more survivors than that are
+// listed in rounds); with the bucket words after it three workgroups of 512 threads share a CU.
+template <int NT, int ITEMS, bool PRED, int EXTRA_WORDS = 0>
+struct WinHot {
+    using H = HotCfg<NT, ITEMS, false>;                  // windows use the linear bucket map: no coarse table
+    static constexpr int LIST = PRED ? 0 : H::CAP / 2;    // records of the compact list (0: one per entry)
+    static constexpr size_t REC_BYTES = PRED ? (size_t)H::BSUM_AT * 8 : (size_t)H::CAP * 4 + (size_t)EXTRA_WORDS * 4;
+    static constexpr size_t BYTES = REC_BYTES + (size_t)H::NB * 8 + (size_t)H::RED_WORDS * 8 + (size_t)H::NB * 4;
+    static_assert(REC_BYTES % 8 == 0, "the bucket words are 8 bytes each");
+    __device__ __forceinline__ static Smem carve(unsigned char* smem)
+    {
+        Smem s;
+        s.recs = (u64*)smem;
+        s.dhi = nullptr;
+        s.red = (u64*)(smem + REC_BYTES) + H::NB;        // bucket words sit between the records and the scratch
+        s.cnt = (u32*)(s.red + H::RED_WORDS);
+        return s;
+    }
+};
+
 // The fast search of one window (see zl_window_kernel); lo/hi hold the index
 // ranges of the thread's first ROWS_PER_THREAD<NT> rows.
 template <int NT, int ITEMS, class CT, bool PRED>
@@ -60,7 +82,7 @@ __device__ __forceinline__ void window_search(const Smem& sm, const Rows& rw, co
 {
     using H = HotCfg<NT, ITEMS>;
     {
-        u64* bsum = sm.recs + H::BSUM_AT;
+        u64* bsum = sm.red - H::NB;
         bsum[threadIdx.x] = 0; bsum[threadIdx.x + NT] = 0;
     }
     Partial r;
@@ -76,7 +98,7 @@ __device__ __forceinline__ void window_search(const Smem& sm, const Rows& rw, co
             defer = total > H::CAP;
             if (!defer && total > 0) {
                 u32 bkey;
-                if (zl_bucket_finish<NT, ITEMS, true>(sm, key, dl,
+                if (zl_bucket_finish<NT, ITEMS, true, LinearMap, WinHot<NT, ITEMS, PRED>::LIST>(sm, key, dl,
                                                       linear_map((u32)(wv.Elast - wv.A), H::NB, wv.scale ? wv.scale : 1u,
                                                                  wv.inv52),
                                                       SlotsBelow<NT>{total}, wv.A, ii.thr, (u32)rw.P, w0, r.wait, bkey))
@@ -184,15 +206,15 @@ __device__ __forceinline__ void window_pairs(
 }
 
 template <int NT, int ITEMS, class CT, bool PRED>
-__global__ __launch_bounds__(NT, 4) void zl_window_kernel(
+__global__ __launch_bounds__(NT, (!PRED && NT == 256 ? 5 : 4)) void zl_window_kernel(
     const i64* __restrict__ ts, const uint2* __restrict__ rowpar, i64 B, int P, int R,
     const InstInfo* __restrict__ info, const CT* __restrict__ cross, int stride,
     const u32* __restrict__ winstart, const WinVal* __restrict__ winval, int max_win, u32 groups, u32 groups_inv,
     Partial* __restrict__ partial)
 {
-    using H = HotCfg<NT, ITEMS, false>;       // windows use the linear bucket map: no coarse table
-    __shared__ __align__(16) unsigned char smem[H::BYTES];
-    const Smem sm = carve_hot<NT, ITEMS>(smem);
+    using L = WinHot<NT, ITEMS, PRED>;
+    __shared__ __align__(16) unsigned char smem[L::BYTES];
+    const Smem sm = L::carve(smem);
     window_pairs<NT, ITEMS, CT, SumSearch<NT, ITEMS, CT, PRED>>(sm, ts, rowpar, B, P, R, info, cross, stride, winstart,
                                                                winval, max_win, groups, groups_inv, partial);
 }
