@@ -362,12 +362,20 @@ int run_batch(const i64* ts, const i64* le, const i64* iv, i64 B, int P, int R,
         else LAUNCH(K_INSTANCE_REG, (zl_instance_reg_kernel<512, ITEMS_, false>), grid, dim3(512), ts, le, iv, P, R, rshift, \
                     barrier, iters, wait, status);                                                          \
     } while (0)
+#define LAUNCH_INSTANCE_REG1K()                                                                              \
+    do {                                                                                                    \
+        if (pred) LAUNCH(K_INSTANCE_REG, (zl_instance_reg_kernel<1024, 16, true>), grid, dim3(1024), ts, le, iv, P, R, rshift, \
+                         barrier, iters, wait, status);                                                     \
+        else LAUNCH(K_INSTANCE_REG, (zl_instance_reg_kernel<1024, 16, false>), grid, dim3(1024), ts, le, iv, P, R, rshift, \
+                    barrier, iters, wait, status);                                                          \
+    } while (0)
         if (n <= 256) LAUNCH_INSTANCE(128, 2);
         else if (n <= 1024) LAUNCH_INSTANCE(256, 4);
         else if (n <= 4096) LAUNCH_INSTANCE(512, 8);
         else if (n <= 8192) LAUNCH_INSTANCE_REG(16);
-        else LAUNCH_INSTANCE(1024, 16);
+        else LAUNCH_INSTANCE_REG1K();
 #undef LAUNCH_INSTANCE_REG
+#undef LAUNCH_INSTANCE_REG1K
 #undef LAUNCH_INSTANCE
         // what the kernel above left: the general search in the smallest workgroup whose records hold an
         // instance (half of NT * ITEMS with 64-bit deltas), as many workgroups as fit the chip at once

@@ -105,8 +105,16 @@ struct SlotsBelow {           // item j of thread t is slot j*NT + t of `total`
     int total;
     __device__ __forceinline__ bool operator()(int j) const { return j * NT + (int)threadIdx.x < total; }
 };
-template <int NT, int ITEMS, bool WITH_W0, class Map, int LIST_CAP = 0, class Present = SlotsBelow<NT>>
-__device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key)[ITEMS], const u32 (&dl)[ITEMS],
+// The deltas are the caller's too: Delta::operator()(j), called by all threads together for every
+// j (also for items that do not exist), so that it may take its value from a neighbouring lane.
+template <int ITEMS>
+struct StoredDeltas {         // the deltas sit in registers
+    const u32 (&dl)[ITEMS];
+    __device__ __forceinline__ u32 operator()(int j) const { return dl[j]; }
+};
+template <int NT, int ITEMS, bool WITH_W0, class Map, int LIST_CAP = 0, class Present = SlotsBelow<NT>,
+          class Delta = StoredDeltas<ITEMS>>
+__device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key)[ITEMS], const Delta delta,
                                                  const Map bucket, const Present present, u64 a, u64 thr, u32 P, u64 w0,
                                                  u64& best_wait, u32& best_key)
 {
@@ -121,11 +129,13 @@ __device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key
     if (tid == 0) { *live_count = 0; *deep = 0; }
     // zl_sort, step 1: per bucket, entry count and sum of deltas in one word
 #pragma unroll
-    for (int j = 0; j < ITEMS; ++j)
+    for (int j = 0; j < ITEMS; ++j) {
+        const u32 d = delta(j);
         if (present(j)) {
             const u32 bid = bucket(key[j]);
-            atomicAdd(&bsum[bid], (1ull << SUM_BITS) | (u64)dl[j]);
+            atomicAdd(&bsum[bid], (1ull << SUM_BITS) | (u64)d);
         }
+    }
     __syncthreads();
     // step 2: exclusive scans over the buckets (two per thread)
     const u64 h0 = bsum[2 * tid], h1 = bsum[2 * tid + 1];
@@ -188,12 +198,14 @@ __device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key
         if (LIST_CAP == 0 || live <= LIST_CAP) {
             // step 3: scatter the entries of the live buckets; afterwards cnt[b] is the end of bucket b
 #pragma unroll
-            for (int j = 0; j < ITEMS; ++j)
+            for (int j = 0; j < ITEMS; ++j) {
+                const u32 d = delta(j);
                 if (present(j)) {
                     const u32 bid = bucket(key[j]);
                     const u32 slot = atomicAdd(&cnt[bid], 1u);
-                    if (slot < DROPPED) recs[slot] = (u64)key[j] | ((u64)dl[j] << 32);
+                    if (slot < DROPPED) recs[slot] = (u64)key[j] | ((u64)d << 32);
                 }
+            }
             __syncthreads();
             // zl_scan + zl_argmin: every listed entry evaluates its own candidate
             for (int q = tid; q < live; q += NT) {
@@ -209,15 +221,17 @@ __device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key
             constexpr u32 ROUND = (u32)LIST_CAP - BUCKET_LIMIT;
             for (u32 r0 = 0; r0 < (u32)live; r0 += ROUND) {
 #pragma unroll
-                for (int j = 0; j < ITEMS; ++j)
+                for (int j = 0; j < ITEMS; ++j) {
+                    const u32 d = delta(j);
                     if (present(j)) {
                         const u32 bid = bucket(key[j]);
                         const u32 first = (u32)(bsum[bid] >> SUM_BITS);
                         if (first >= r0 && first - r0 < ROUND) {
                             const u32 slot = atomicAdd(&cnt[bid], 1u);
-                            recs[slot - r0] = (u64)key[j] | ((u64)dl[j] << 32);
+                            recs[slot - r0] = (u64)key[j] | ((u64)d << 32);
                         }
                     }
+                }
                 __syncthreads();
                 const u32 span = (u32)live - r0 < (u32)LIST_CAP ? (u32)live - r0 : (u32)LIST_CAP;
                 for (u32 q = tid; q < span; q += NT) {
@@ -240,12 +254,14 @@ __device__ __forceinline__ bool zl_bucket_finish(const Smem& sm, const u32 (&key
     __syncthreads();
     // step 3: scatter; afterwards cnt[b] is the end of bucket b
 #pragma unroll
-    for (int j = 0; j < ITEMS; ++j)
+    for (int j = 0; j < ITEMS; ++j) {
+        const u32 d = delta(j);
         if (present(j)) {
             const u32 bid = bucket(key[j]);
             const u32 slot = atomicAdd(&cnt[bid], 1u);
-            recs[slot] = (u64)key[j] | ((u64)dl[j] << 32);
+            recs[slot] = (u64)key[j] | ((u64)d << 32);
         }
+    }
     // a 4-wide read of the last bucket may run past the end: entries that add nothing
     const int total = present.total;              // (this form is for the strided layout)
     if (tid < H::PAD - 1) recs[total + tid] = 0xffffffffull;

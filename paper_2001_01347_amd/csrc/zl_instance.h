@@ -136,7 +136,7 @@ __global__ __launch_bounds__(NT) void zl_instance_kernel(
     __syncthreads();
     u64 best_wait;
     u32 bkey;
-    if (!zl_bucket_finish<NT, ITEMS, false>(sm, key, dl, bucket, SlotsBelow<NT>{n}, 0ull, thr, (u32)P, 0ull, best_wait, bkey)) {
+    if (!zl_bucket_finish<NT, ITEMS, false>(sm, key, StoredDeltas<ITEMS>{dl}, bucket, SlotsBelow<NT>{n}, 0ull, thr, (u32)P, 0ull, best_wait, bkey)) {
         if (tid == 0) wait[b] = DEFERRED;      // clustered values: left to zl_instance_general_kernel
         return;
     }
@@ -161,15 +161,29 @@ struct WaveItems {            // which of a thread's items exist in that layout
     u32 mask;
     __device__ __forceinline__ bool operator()(int j) const { return (mask >> j) & 1u; }
 };
+template <int ITEMS>
+struct NeighbourDeltas {      // an entry's delta is its key minus the key in the lane before, a row's first entry's its key
+    const u32 (&key)[ITEMS];
+    u32 heads;                // items that are a row's first entry
+    u32 ahead;                // key of the element before the wave's first
+    __device__ __forceinline__ u32 operator()(int j) const
+    {
+        u32 pk = dpp_take<DPP_WAVE_SHR1, 0xf>(0u, key[j]);
+        const u32 edge = j > 0 ? (u32)__shfl((int)key[j > 0 ? j - 1 : 0], WAVE - 1, WAVE) : ahead;
+        if ((threadIdx.x & (WAVE - 1)) == 0) pk = edge;
+        return ((heads >> j) & 1u) ? key[j] : key[j] - pk;
+    }
+};
 template <int NT, int ITEMS>
 struct RegCfg {
     using H = HotCfg<NT, ITEMS>;
-    static constexpr int LIST = 4096;                     // records of the short list
+    static constexpr int LIST = NT >= 1024 ? 6144 : 4096; // records of the short list: two or three workgroups fit a CU
+    static constexpr bool STORED_DELTAS = NT < 1024;      // deltas kept in registers (else recomputed: 64 registers per thread)
     static constexpr size_t BYTES = (size_t)LIST * 8 + (size_t)H::NB * 8 + (size_t)H::RED_WORDS * 8 + (size_t)H::NB * 4 +
                                     (size_t)H::COARSE * 16;
 };
 template <int NT, int ITEMS, bool PRED>
-__global__ __launch_bounds__(NT, 6) void zl_instance_reg_kernel(
+__global__ __launch_bounds__(NT, (NT == 1024 ? 8 : 6)) void zl_instance_reg_kernel(
     const i64* __restrict__ ts, const i64* __restrict__ le, const i64* __restrict__ iv, int P, int R, int rshift,
     i64* __restrict__ barrier, int* __restrict__ iters, i64* __restrict__ wait,
     int* __restrict__ status)
@@ -207,15 +221,17 @@ __global__ __launch_bounds__(NT, 6) void zl_instance_reg_kernel(
     const int wbase = wave * WAVE * items;
     const i64 t00 = at(0);
     i64 carry = (wbase > 0 && wbase < n) ? at(wbase - 1) : 0;    // element ahead of the wave's first
+    const u32 ahead = (u32)((u64)carry - (u64)t00);                // its key (relative to t00 like the others at first)
     i64 mn = INT64_MAX, mxf = INT64_MIN, mxl = INT64_MIN;          // min first, max first, max last of the rows
     int bad = 0;
-    u32 key[ITEMS], dl[ITEMS];
+    u32 key[ITEMS];
+    u32 dl[C::STORED_DELTAS ? ITEMS : 1];                  // (not stored: differences of neighbouring lanes' keys)
     u32 have = 0, heads = 0;                               // items that exist; items that are a row's first entry
     constexpr int LB = 8;                                  // loads of a thread in flight together
 #pragma unroll
     for (int g = 0; g < ITEMS; g += LB) {
 #pragma unroll
-        for (int j = 0; j < LB; ++j) { key[g + j] = 0; dl[g + j] = 0; }
+        for (int j = 0; j < LB; ++j) { key[g + j] = 0; if (C::STORED_DELTAS) dl[g + j] = 0; }
         if (g < items) {
             i64 v[LB];
 #pragma unroll
@@ -235,7 +251,7 @@ __global__ __launch_bounds__(NT, 6) void zl_instance_reg_kernel(
                     have |= 1u << (g + j);
                     key[g + j] = rel;
                     if (i == 0) { heads |= 1u << (g + j); mn = v[j] < mn ? v[j] : mn; mxf = v[j] > mxf ? v[j] : mxf; }
-                    else { dl[g + j] = (u32)((u64)v[j] - (u64)prv); bad |= (v[j] < prv); }
+                    else { if (C::STORED_DELTAS) dl[g + j] = (u32)((u64)v[j] - (u64)prv); bad |= (v[j] < prv); }
                     if (i == R - 1) mxl = v[j] > mxl ? v[j] : mxl;
                 }
             }
@@ -258,7 +274,7 @@ __global__ __launch_bounds__(NT, 6) void zl_instance_reg_kernel(
 #pragma unroll
     for (int j = 0; j < ITEMS; ++j) {
         key[j] += shift;
-        dl[j] = ((heads >> j) & 1u) ? key[j] : dl[j];              // a row's first delta is its key relative to base
+        if (C::STORED_DELTAS) dl[j] = ((heads >> j) & 1u) ? key[j] : dl[j];    // a row's first delta is its key relative to base
     }
     const WaveItems<NT, ITEMS> present{have};
     // the equalising bucket map: key counts of up to 256 coarse bins -> buckets per bin
@@ -291,8 +307,14 @@ __global__ __launch_bounds__(NT, 6) void zl_instance_reg_kernel(
     __syncthreads();
     u64 best_wait;
     u32 bkey;
-    if (!zl_bucket_finish<NT, ITEMS, false, TableMap<true>, C::LIST>(sm, key, dl, bucket, present, 0ull, thr, (u32)P, 0ull,
-                                                                     best_wait, bkey)) {
+    bool found;
+    if constexpr (C::STORED_DELTAS)
+        found = zl_bucket_finish<NT, ITEMS, false, TableMap<true>, C::LIST, WaveItems<NT, ITEMS>>(
+            sm, key, StoredDeltas<ITEMS>{dl}, bucket, present, 0ull, thr, (u32)P, 0ull, best_wait, bkey);
+    else
+        found = zl_bucket_finish<NT, ITEMS, false, TableMap<true>, C::LIST, WaveItems<NT, ITEMS>, NeighbourDeltas<ITEMS>>(
+            sm, key, NeighbourDeltas<ITEMS>{key, heads, ahead + shift}, bucket, present, 0ull, thr, (u32)P, 0ull, best_wait, bkey);
+    if (!found) {
         if (tid == 0) wait[b] = DEFERRED;      // clustered values: left to zl_instance_general_kernel
         return;
     }

@@ -98,7 +98,7 @@ __device__ __forceinline__ void window_search(const Smem& sm, const Rows& rw, co
             defer = total > H::CAP;
             if (!defer && total > 0) {
                 u32 bkey;
-                if (zl_bucket_finish<NT, ITEMS, true, LinearMap, WinHot<NT, ITEMS, PRED>::LIST>(sm, key, dl,
+                if (zl_bucket_finish<NT, ITEMS, true, LinearMap, WinHot<NT, ITEMS, PRED>::LIST>(sm, key, StoredDeltas<ITEMS>{dl},
                                                       linear_map((u32)(wv.Elast - wv.A), H::NB, wv.scale ? wv.scale : 1u,
                                                                  wv.inv52),
                                                       SlotsBelow<NT>{total}, wv.A, ii.thr, (u32)rw.P, w0, r.wait, bkey))

@@ -84,9 +84,11 @@ def test_random_predicted_rows(zl, oracle, seed):
         assert np.array_equal(bar, ob) and np.array_equal(w, ow) and np.array_equal(it, oi), label
 
 
-@pytest.mark.parametrize("P,R", [(2, 4096), (3, 2731), (5, 1000), (8, 1024), (64, 128), (100, 80), (1000, 8), (4100, 1), (4097, 2), (1, 8192), (1, 4097)])
-def test_instances_of_4097_to_8192_entries(zl, oracle, P, R):
-    """One workgroup each, records in registers: the short list of surviving entries is filled in one round where
+@pytest.mark.parametrize("P,R", [(2, 4096), (3, 2731), (5, 1000), (8, 1024), (64, 128), (100, 80), (1000, 8), (4100, 1), (4097, 2), (1, 8192), (1, 4097),
+                                 (2, 8192), (3, 5461), (16, 1000), (64, 256), (100, 163), (2000, 8), (8193, 1), (8200, 2), (1, 16384), (1, 8193)])
+def test_instances_of_4097_to_16384_entries(zl, oracle, P, R):
+    """One workgroup each, records in registers (512 threads up to 8192 entries, 1024 threads and deltas taken from the
+    neighbouring lane's key above): the short list of surviving entries is filled in one round where
     most buckets are dropped (many workers) and in several where few are (few workers), stored and predicted rows;
     equal values, a spread above 2^32 and unsorted rows take the exits to the general search."""
     rng = np.random.default_rng(P * 10007 + R)
