@@ -355,27 +355,20 @@ int run_batch(const i64* ts, const i64* le, const i64* iv, i64 B, int P, int R,
                     barrier, iters, wait, status);                                                          \
     } while (0)
         // larger instances keep their records in registers: less LDS, several workgroups per CU
-#define LAUNCH_INSTANCE_REG(ITEMS_)                                                                         \
+#define LAUNCH_INSTANCE_REG(NT_, ITEMS_)                                                                    \
     do {                                                                                                    \
-        if (pred) LAUNCH(K_INSTANCE_REG, (zl_instance_reg_kernel<512, ITEMS_, true>), grid, dim3(512), ts, le, iv, P, R, rshift, \
+        if (pred) LAUNCH(K_INSTANCE_REG, (zl_instance_reg_kernel<NT_, ITEMS_, true>), grid, dim3(NT_), ts, le, iv, P, R, rshift, \
                          barrier, iters, wait, status);                                                     \
-        else LAUNCH(K_INSTANCE_REG, (zl_instance_reg_kernel<512, ITEMS_, false>), grid, dim3(512), ts, le, iv, P, R, rshift, \
-                    barrier, iters, wait, status);                                                          \
-    } while (0)
-#define LAUNCH_INSTANCE_REG1K()                                                                              \
-    do {                                                                                                    \
-        if (pred) LAUNCH(K_INSTANCE_REG, (zl_instance_reg_kernel<1024, 16, true>), grid, dim3(1024), ts, le, iv, P, R, rshift, \
-                         barrier, iters, wait, status);                                                     \
-        else LAUNCH(K_INSTANCE_REG, (zl_instance_reg_kernel<1024, 16, false>), grid, dim3(1024), ts, le, iv, P, R, rshift, \
+        else LAUNCH(K_INSTANCE_REG, (zl_instance_reg_kernel<NT_, ITEMS_, false>), grid, dim3(NT_), ts, le, iv, P, R, rshift, \
                     barrier, iters, wait, status);                                                          \
     } while (0)
         if (n <= 256) LAUNCH_INSTANCE(128, 2);
         else if (n <= 1024) LAUNCH_INSTANCE(256, 4);
-        else if (n <= 4096) LAUNCH_INSTANCE(512, 8);
-        else if (n <= 8192) LAUNCH_INSTANCE_REG(16);
-        else LAUNCH_INSTANCE_REG1K();
+        else if (n <= 2048) LAUNCH_INSTANCE_REG(256, 8);
+        else if (n <= 4096) LAUNCH_INSTANCE_REG(256, 16);
+        else if (n <= 8192) LAUNCH_INSTANCE_REG(512, 16);
+        else LAUNCH_INSTANCE_REG(1024, 16);
 #undef LAUNCH_INSTANCE_REG
-#undef LAUNCH_INSTANCE_REG1K
 #undef LAUNCH_INSTANCE
         // what the kernel above left: the general search in the smallest workgroup whose records hold an
         // instance (half of NT * ITEMS with 64-bit deltas), as many workgroups as fit the chip at once

@@ -177,7 +177,7 @@ struct NeighbourDeltas {      // an entry's delta is its key minus the key in th
 template <int NT, int ITEMS>
 struct RegCfg {
     using H = HotCfg<NT, ITEMS>;
-    static constexpr int LIST = NT >= 1024 ? 6144 : 4096; // records of the short list: two or three workgroups fit a CU
+    static constexpr int LIST = NT >= 1024 ? 6144 : NT * ITEMS / 2;   // records of the short list: two, three or six workgroups fit a CU
     static constexpr bool STORED_DELTAS = NT < 1024;      // deltas kept in registers (else recomputed: 64 registers per thread)
     static constexpr size_t BYTES = (size_t)LIST * 8 + (size_t)H::NB * 8 + (size_t)H::RED_WORDS * 8 + (size_t)H::NB * 4 +
                                     (size_t)H::COARSE * 16;
@@ -190,7 +190,7 @@ __global__ __launch_bounds__(NT, (NT == 1024 ? 8 : 6)) void zl_instance_reg_kern
 {
     using H = HotCfg<NT, ITEMS>;
     using C = RegCfg<NT, ITEMS>;
-    static_assert(ITEMS <= 32 && ITEMS % 16 == 0, "item masks are one word; loads go in batches of 8");
+    static_assert(ITEMS <= 32 && ITEMS % 8 == 0, "item masks are one word; loads go in batches of 8");
     __shared__ __align__(16) unsigned char smem[C::BYTES];
     Smem sm;
     sm.recs = (u64*)smem;                                  // the short list
