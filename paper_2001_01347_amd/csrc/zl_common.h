@@ -60,6 +60,14 @@ constexpr int DPP_ROW_SHR1 = 0x111, DPP_ROW_SHR2 = 0x112, DPP_ROW_SHR4 = 0x114, 
               DPP_ROW_BCAST15 = 0x142, DPP_ROW_BCAST31 = 0x143,
               DPP_WAVE_SHR1 = 0x138;      // every lane takes the value of the lane before it (across rows)
 
+// A value that all lanes of a wave hold alike, moved to scalar registers.
+__device__ __forceinline__ u32 uniform(u32 x) { return (u32)__builtin_amdgcn_readfirstlane((int)x); }
+__device__ __forceinline__ u64 uniform(u64 x) { return (u64)uniform((u32)x) | ((u64)uniform((u32)(x >> 32)) << 32); }
+
+// The value that lane 63 holds, for every lane (scalar registers).
+__device__ __forceinline__ u32 last_lane(u32 x) { return (u32)__builtin_amdgcn_readlane((int)x, WAVE - 1); }
+__device__ __forceinline__ u64 last_lane(u64 x) { return (u64)last_lane((u32)x) | ((u64)last_lane((u32)(x >> 32)) << 32); }
+
 struct OpMin {
     template <class T> __device__ T operator()(T a, T b) const { return a < b ? a : b; }
     template <class T> static constexpr T identity() { return std::numeric_limits<T>::max(); }

@@ -150,12 +150,13 @@ __global__ __launch_bounds__(NT) void zl_instance_kernel(
         iters[b * (i64)P + p] = zl_iters_of(inst, lep, ivp, p, R, bar);
 }
 
-// The same search for the larger single-workgroup instances (4096 < P*R <= NT*ITEMS) with the
-// records held in registers from the loads to the evaluation: LDS holds only the bucket words,
+// The same search for the larger single-workgroup instances (1024 < P*R <= NT*ITEMS) with the
+// keys held in registers from the loads to the evaluation: LDS holds only the bucket words,
 // the tables and a short list of the entries that survive the bounds, so that several
-// workgroups share a CU and one loads while another searches.
-// Wave w holds elements [w*64*items, (w+1)*64*items), 64 consecutive ones per item, so an
-// element's predecessor sits in the neighbouring lane.
+// workgroups share a CU and one loads while another searches.  The instance's bounds come first,
+// from the ends of its rows, and stay in scalar registers; the keys are relative to base from
+// the start.  Wave w holds elements [w*64*items, (w+1)*64*items), 64 consecutive ones per item,
+// so an element's predecessor sits in the neighbouring lane and its delta is never stored.
 template <int NT, int ITEMS>
 struct WaveItems {            // which of a thread's items exist in that layout
     u32 mask;
@@ -169,7 +170,7 @@ struct NeighbourDeltas {      // an entry's delta is its key minus the key in th
     __device__ __forceinline__ u32 operator()(int j) const
     {
         u32 pk = dpp_take<DPP_WAVE_SHR1, 0xf>(0u, key[j]);
-        const u32 edge = j > 0 ? (u32)__shfl((int)key[j > 0 ? j - 1 : 0], WAVE - 1, WAVE) : ahead;
+        const u32 edge = j > 0 ? last_lane(key[j > 0 ? j - 1 : 0]) : ahead;
         if ((threadIdx.x & (WAVE - 1)) == 0) pk = edge;
         return ((heads >> j) & 1u) ? key[j] : key[j] - pk;
     }
@@ -178,7 +179,6 @@ template <int NT, int ITEMS>
 struct RegCfg {
     using H = HotCfg<NT, ITEMS>;
     static constexpr int LIST = NT >= 1024 ? 6144 : NT * ITEMS / 2;   // records of the short list: two, three or six workgroups fit a CU
-    static constexpr bool STORED_DELTAS = NT < 1024;      // deltas kept in registers (else recomputed: 64 registers per thread)
     static constexpr size_t BYTES = (size_t)LIST * 8 + (size_t)H::NB * 8 + (size_t)H::RED_WORDS * 8 + (size_t)H::NB * 4 +
                                     (size_t)H::COARSE * 16;
 };
@@ -216,22 +216,55 @@ __global__ __launch_bounds__(NT, (NT == 1024 ? 8 : 6)) void zl_instance_reg_kern
         u64* bsum = sm.red - H::NB;
         bsum[tid] = 0; bsum[tid + NT] = 0;
     }
+    // the equalising bucket map needs the key counts of up to 256 coarse bins: counted while the records load
+    u32* coarse = sm.cnt;                                   // free until the bucket scan
+    u64* tab = (u64*)(sm.cnt + H::NB);
+    static_assert(H::COARSE <= NT, "one coarse bin per thread at most");
+    if (tid < H::COARSE) coarse[tid] = 0;
+    // the instance's bounds from the ends of its rows (the exchange also orders the zeroes above)
+    i64 base, first_max, last_max;
+    {
+        i64 mn = INT64_MAX, mxf = INT64_MIN, mxl = INT64_MIN;      // min first, max first, max last of the rows
+        for (int p = tid; p < P; p += NT) {
+            const i64 f = at(p * R), l = at(p * R + R - 1);
+            mn = f < mn ? f : mn;
+            mxf = f > mxf ? f : mxf;
+            mxl = l > mxl ? l : mxl;
+        }
+        block_bounds<NT>(mn, mxf, mxl, (i64*)sm.red, base, first_max, last_max);
+        base = (i64)uniform((u64)base);                    // the same in every thread: scalar registers
+        first_max = (i64)uniform((u64)first_max);
+        last_max = (i64)uniform((u64)last_max);
+    }
+    const u64 range = (u64)last_max - (u64)base;
+    const u64 thr = (u64)first_max - (u64)base;
+    u32 flags = 0;
+    if (range > (u64)INT64_MAX / (u64)P) flags |= EBSP_STATUS_OVERFLOW;
+    if (range >> 32) {
+        // deltas need more than 32 bits: left to zl_instance_general_kernel
+        if (tid == 0) wait[b] = DEFERRED;
+        return;
+    }
+    const int bl = bit_length(range);
+    TableMap<true> bucket;
+    bucket.tab = tab;
+    bucket.cshift = bl > 8 ? (u32)(bl - 8) : 0u;
+    bucket.cmask = (1u << bucket.cshift) - 1u;
+    bucket.span = (u32)range;
+
     const int lane = tid & (WAVE - 1), wave = tid >> 6;
     const int items = (n + NT - 1) / NT;
     const int wbase = wave * WAVE * items;
-    const i64 t00 = at(0);
-    i64 carry = (wbase > 0 && wbase < n) ? at(wbase - 1) : 0;    // element ahead of the wave's first
-    const u32 ahead = (u32)((u64)carry - (u64)t00);                // its key (relative to t00 like the others at first)
-    i64 mn = INT64_MAX, mxf = INT64_MIN, mxl = INT64_MIN;          // min first, max first, max last of the rows
+    i64 carry = (wbase > 0 && wbase < n) ? at(wbase - 1) : base;  // element ahead of the wave's first
+    const u32 ahead = (u32)((u64)carry - (u64)base);               // its key
     int bad = 0;
-    u32 key[ITEMS];
-    u32 dl[C::STORED_DELTAS ? ITEMS : 1];                  // (not stored: differences of neighbouring lanes' keys)
+    u32 key[ITEMS];                                        // relative to base
     u32 have = 0, heads = 0;                               // items that exist; items that are a row's first entry
     constexpr int LB = 8;                                  // loads of a thread in flight together
 #pragma unroll
     for (int g = 0; g < ITEMS; g += LB) {
 #pragma unroll
-        for (int j = 0; j < LB; ++j) { key[g + j] = 0; if (C::STORED_DELTAS) dl[g + j] = 0; }
+        for (int j = 0; j < LB; ++j) key[g + j] = 0;
         if (g < items) {
             i64 v[LB];
 #pragma unroll
@@ -244,55 +277,21 @@ __global__ __launch_bounds__(NT, (NT == 1024 ? 8 : 6)) void zl_instance_reg_kern
                 const int e = wbase + (g + j) * WAVE + lane;
                 i64 prv = dpp_take<DPP_WAVE_SHR1, 0xf>((i64)0, v[j]);
                 if (lane == 0) prv = carry;
-                carry = __shfl(v[j], WAVE - 1, WAVE);
+                carry = (i64)last_lane((u64)v[j]);
                 if (g + j < items && e < n) {
-                    const int i = e - row_of(e) * R;
-                    const u32 rel = (u32)((u64)v[j] - (u64)t00);
+                    const bool first = e == row_of(e) * R;
+                    const u32 rel = (u32)((u64)v[j] - (u64)base);   // (beyond the range only in unsorted rows: the maps clamp)
                     have |= 1u << (g + j);
                     key[g + j] = rel;
-                    if (i == 0) { heads |= 1u << (g + j); mn = v[j] < mn ? v[j] : mn; mxf = v[j] > mxf ? v[j] : mxf; }
-                    else { if (C::STORED_DELTAS) dl[g + j] = (u32)((u64)v[j] - (u64)prv); bad |= (v[j] < prv); }
-                    if (i == R - 1) mxl = v[j] > mxl ? v[j] : mxl;
+                    if (first) heads |= 1u << (g + j);
+                    else bad |= (v[j] < prv);
+                    atomicAdd(&coarse[bucket.coarse(rel)], 1u);
                 }
             }
         }
     }
-    i64 base, first_max, last_max;
-    block_bounds<NT>(mn, mxf, mxl, (i64*)sm.red, base, first_max, last_max);
-    const u64 range = (u64)last_max - (u64)base;
-    const u64 thr = (u64)first_max - (u64)base;
-    const u32 shift = (u32)((u64)t00 - (u64)base);                 // key relative to base = key relative to t00 + shift
-
-    u32 flags = 0;
-    if (range > (u64)INT64_MAX / (u64)P) flags |= EBSP_STATUS_OVERFLOW;
-    if (range >> 32) {
-        // deltas need more than 32 bits: left to zl_instance_general_kernel
-        if (tid == 0) wait[b] = DEFERRED;
-        return;
-    }
-    if (__syncthreads_or(bad)) flags |= EBSP_STATUS_UNSORTED;
-#pragma unroll
-    for (int j = 0; j < ITEMS; ++j) {
-        key[j] += shift;
-        if (C::STORED_DELTAS) dl[j] = ((heads >> j) & 1u) ? key[j] : dl[j];    // a row's first delta is its key relative to base
-    }
     const WaveItems<NT, ITEMS> present{have};
-    // the equalising bucket map: key counts of up to 256 coarse bins -> buckets per bin
-    u32* coarse = sm.cnt;                                   // free until the bucket scan
-    u64* tab = (u64*)(sm.cnt + H::NB);
-    const int bl = bit_length(range);
-    TableMap<true> bucket;
-    bucket.tab = tab;
-    bucket.cshift = bl > 8 ? (u32)(bl - 8) : 0u;
-    bucket.cmask = (1u << bucket.cshift) - 1u;
-    bucket.span = (u32)range;
-    static_assert(H::COARSE <= NT, "one coarse bin per thread at most");
-    if (tid < H::COARSE) coarse[tid] = 0;
-    __syncthreads();
-#pragma unroll
-    for (int j = 0; j < ITEMS; ++j)
-        if (present(j)) atomicAdd(&coarse[bucket.coarse(key[j])], 1u);
-    __syncthreads();
+    if (__syncthreads_or(bad)) flags |= EBSP_STATUS_UNSORTED;       // also: the coarse counts are complete
     {
         const u32 c = tid < H::COARSE ? coarse[tid] : 0u;
         u32 all;
@@ -307,13 +306,10 @@ __global__ __launch_bounds__(NT, (NT == 1024 ? 8 : 6)) void zl_instance_reg_kern
     __syncthreads();
     u64 best_wait;
     u32 bkey;
-    bool found;
-    if constexpr (C::STORED_DELTAS)
-        found = zl_bucket_finish<NT, ITEMS, false, TableMap<true>, C::LIST, WaveItems<NT, ITEMS>>(
-            sm, key, StoredDeltas<ITEMS>{dl}, bucket, present, 0ull, thr, (u32)P, 0ull, best_wait, bkey);
-    else
-        found = zl_bucket_finish<NT, ITEMS, false, TableMap<true>, C::LIST, WaveItems<NT, ITEMS>, NeighbourDeltas<ITEMS>>(
-            sm, key, NeighbourDeltas<ITEMS>{key, heads, ahead + shift}, bucket, present, 0ull, thr, (u32)P, 0ull, best_wait, bkey);
+    // the deltas are not stored: an entry's delta is its key minus the key in the lane before (a row's first
+    // delta is its key relative to base)
+    const bool found = zl_bucket_finish<NT, ITEMS, false, TableMap<true>, C::LIST, WaveItems<NT, ITEMS>, NeighbourDeltas<ITEMS>>(
+        sm, key, NeighbourDeltas<ITEMS>{key, heads, ahead}, bucket, present, 0ull, thr, (u32)P, 0ull, best_wait, bkey);
     if (!found) {
         if (tid == 0) wait[b] = DEFERRED;      // clustered values: left to zl_instance_general_kernel
         return;

@@ -132,10 +132,6 @@ __device__ __forceinline__ void zero_share(u64* words)
     for (int i = 0; i < BPT / 2; ++i) z[i] = make_uint4(0u, 0u, 0u, 0u);
 }
 
-// A value that is the same in every lane, moved to where such values live.
-__device__ __forceinline__ u32 uniform(u32 x) { return (u32)__builtin_amdgcn_readfirstlane((int)x); }
-__device__ __forceinline__ u64 uniform(u64 x) { return (u64)uniform((u32)x) | ((u64)uniform((u32)(x >> 32)) << 32); }
-
 // Smallest shift that puts the values below x into NB buckets.
 template <int LOG_NB>
 __device__ __forceinline__ u32 shift_for(u64 x)
