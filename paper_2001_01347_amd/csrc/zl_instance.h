@@ -183,7 +183,7 @@ struct RegCfg {
                                     (size_t)H::COARSE * 16;
 };
 template <int NT, int ITEMS, bool PRED>
-__global__ __launch_bounds__(NT, (NT == 1024 ? 8 : 6)) void zl_instance_reg_kernel(
+__global__ __launch_bounds__(NT, (NT == 1024 ? 8 : (NT == 128 ? 5 : 6))) void zl_instance_reg_kernel(
     const i64* __restrict__ ts, const i64* __restrict__ le, const i64* __restrict__ iv, int P, int R, int rshift,
     i64* __restrict__ barrier, int* __restrict__ iters, i64* __restrict__ wait,
     int* __restrict__ status)
@@ -219,8 +219,11 @@ __global__ __launch_bounds__(NT, (NT == 1024 ? 8 : 6)) void zl_instance_reg_kern
     // the equalising bucket map needs the key counts of up to 256 coarse bins: counted while the records load
     u32* coarse = sm.cnt;                                   // free until the bucket scan
     u64* tab = (u64*)(sm.cnt + H::NB);
-    static_assert(H::COARSE <= NT, "one coarse bin per thread at most");
-    if (tid < H::COARSE) coarse[tid] = 0;
+    constexpr int CPT = H::COARSE / NT > 1 ? H::COARSE / NT : 1;      // coarse bins per thread
+    static_assert(H::NB >= H::COARSE, "the counters' area holds the coarse counts first");
+#pragma unroll
+    for (int i = 0; i < CPT; ++i)
+        if (tid * CPT + i < H::COARSE) coarse[tid * CPT + i] = 0;
     // the instance's bounds from the ends of its rows (the exchange also orders the zeroes above)
     i64 base, first_max, last_max;
     {
@@ -293,14 +296,23 @@ __global__ __launch_bounds__(NT, (NT == 1024 ? 8 : 6)) void zl_instance_reg_kern
     const WaveItems<NT, ITEMS> present{have};
     if (__syncthreads_or(bad)) flags |= EBSP_STATUS_UNSORTED;       // also: the coarse counts are complete
     {
-        const u32 c = tid < H::COARSE ? coarse[tid] : 0u;
+        u32 c[CPT], mine = 0;
+#pragma unroll
+        for (int i = 0; i < CPT; ++i) {
+            c[i] = tid * CPT + i < H::COARSE ? coarse[tid * CPT + i] : 0u;
+            mine += c[i];
+        }
         u32 all;
-        const u32 below_c = block_excl_scan<u32, NT>(c, (u32*)sm.red, all);
-        if (tid < H::COARSE) {
-            u64 tw, iw;
-            table_entry(below_c, c, (u32)n, (u32)H::NB, bucket.cshift, tw, iw);
-            tab[tid] = tw;
-            tab[H::COARSE + tid] = iw;
+        u32 below_c = block_excl_scan<u32, NT>(mine, (u32*)sm.red, all);
+#pragma unroll
+        for (int i = 0; i < CPT; ++i) {
+            if (tid * CPT + i < H::COARSE) {
+                u64 tw, iw;
+                table_entry(below_c, c[i], (u32)n, (u32)H::NB, bucket.cshift, tw, iw);
+                tab[tid * CPT + i] = tw;
+                tab[H::COARSE + tid * CPT + i] = iw;
+            }
+            below_c += c[i];
         }
     }
     __syncthreads();

@@ -86,10 +86,11 @@ def test_random_predicted_rows(zl, oracle, seed):
 
 @pytest.mark.parametrize("P,R", [(2, 4096), (3, 2731), (5, 1000), (8, 1024), (64, 128), (100, 80), (1000, 8), (4100, 1), (4097, 2), (1, 8192), (1, 4097),
                                  (2, 8192), (3, 5461), (16, 1000), (64, 256), (100, 163), (2000, 8), (8193, 1), (8200, 2), (1, 16384), (1, 8193),
-                                 (2, 1024), (3, 700), (64, 32), (33, 100), (1025, 1), (1, 2048), (2, 600), (5, 819), (4096, 1), (1, 1025)])
-def test_instances_of_1025_to_16384_entries(zl, oracle, P, R):
-    """One workgroup each, records in registers (256 threads up to 4096 entries, 512 up to 8192, 1024 threads and deltas
-    taken from the neighbouring lane's key above): the short list of surviving entries is filled in one round where
+                                 (2, 1024), (3, 700), (64, 32), (33, 100), (1025, 1), (1, 2048), (2, 600), (5, 819), (4096, 1), (1, 1025),
+                                 (2, 512), (3, 300), (16, 64), (1000, 1), (1, 1024), (257, 1), (1, 257), (5, 60)])
+def test_instances_of_257_to_16384_entries(zl, oracle, P, R):
+    """One workgroup each, keys in registers and deltas taken from the neighbouring lane's key (128 threads up to 1024
+    entries, 256 up to 4096, 512 up to 8192, 1024 above): the short list of surviving entries is filled in one round where
     most buckets are dropped (many workers) and in several where few are (few workers), stored and predicted rows;
     equal values, a spread above 2^32 and unsorted rows take the exits to the general search."""
     rng = np.random.default_rng(P * 10007 + R)
