@@ -363,7 +363,7 @@ int run_batch(const i64* ts, const i64* le, const i64* iv, i64 B, int P, int R,
                     barrier, iters, wait, status);                                                          \
     } while (0)
         if (n <= 256) LAUNCH_INSTANCE(128, 2);
-        else if (n <= 1024) LAUNCH_INSTANCE_REG(128, 8);
+        else if (n <= 1024) LAUNCH_INSTANCE(256, 4);       // (batches of so small instances are often small too: the shorter chain per thread wins)
         else if (n <= 2048) LAUNCH_INSTANCE_REG(256, 8);
         else if (n <= 4096) LAUNCH_INSTANCE_REG(256, 16);
         else if (n <= 8192) LAUNCH_INSTANCE_REG(512, 16);
