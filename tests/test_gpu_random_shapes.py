@@ -117,3 +117,29 @@ def test_instances_of_257_to_16384_entries(zl, oracle, P, R):
     ob, oi, ow, rc, _ = oracle.zipline(oracle.predicted_rows(le, iv, R), "sweep", threads=16)
     assert (rc == 0).all() and (st == 0).all()
     assert np.array_equal(bar, ob) and np.array_equal(w, ow) and np.array_equal(it, oi)
+
+
+@pytest.mark.parametrize("P,R", [(1, 50000), (2, 20000), (3, 30000), (7, 9000), (40, 3000)])
+def test_windows_whose_survivors_outnumber_the_list(zl, oracle, P, R):
+    """Few workers in the multi-window path: the bounds drop little, so more entries of a window survive than its
+    compact list holds (half a window with stored rows) and they are listed and evaluated in rounds; both objectives,
+    stored and predicted rows."""
+    rng = np.random.default_rng(P * 7919 + R)
+    B = 5
+    steps = rng.integers(1, 3000, size=(B, P, R)).astype(np.int64)
+    steps[1] = 1000                                                    # every worker alike: all candidates tie
+    ts = np.cumsum(steps, axis=2) + rng.integers(0, 4000, size=(B, P, 1))
+    t = torch.from_numpy(ts).cuda()
+    bar, it, w, st = (x.cpu().numpy() for x in zl.ebsp_zipline_batch(t))
+    ob, oi, ow, rc, _ = oracle.zipline(ts, "sweep", threads=16)
+    assert (rc == 0).all() and (st == 0).all()
+    assert np.array_equal(bar, ob) and np.array_equal(w, ow) and np.array_equal(it, oi)
+    rbar, rit, rd, rst = (x.cpu().numpy() for x in zl.ebsp_zipline_range_batch(t))
+    qb, qi, qd, _, _ = oracle.zipline_range(ts, "sweep", threads=16)
+    assert (rst == 0).all() and np.array_equal(rbar, qb) and np.array_equal(rd, qd) and np.array_equal(rit, qi)
+    iv = rng.integers(1, 3000, size=(B, P)).astype(np.int64)
+    le = rng.integers(0, 10 ** 6, size=(B, P)).astype(np.int64)
+    bar, it, w, st = (x.cpu().numpy() for x in zl.ebsp_predict_zipline_batch(torch.from_numpy(le).cuda(), torch.from_numpy(iv).cuda(), R))
+    ob, oi, ow, rc, _ = oracle.zipline(oracle.predicted_rows(le, iv, R), "sweep", threads=16)
+    assert (rc == 0).all() and (st == 0).all()
+    assert np.array_equal(bar, ob) and np.array_equal(w, ow) and np.array_equal(it, oi)
