@@ -265,12 +265,17 @@ int plan_windows(const Plan& pl, const i64* ts, const i64* le, const i64* iv, i6
     int part_rows;                                    // rows of partial column sums per instance (0: none, count from cross)
     if (pred) {
         part_rows = pl.part_pred;
-        if (pl.narrow)
-            LAUNCH(K_PARTITION_PRED, zl_partition_pred_kernel<unsigned short>, dim3((unsigned)(kblocks * B), (unsigned)part_rows),
-                   dim3(256), le, iv, P, R, info, segtab, (unsigned short*)cross, pl.stride, part);
-        else
-            LAUNCH(K_PARTITION_PRED, zl_partition_pred_kernel<u32>, dim3((unsigned)(kblocks * B), (unsigned)part_rows),
-                   dim3(256), le, iv, P, R, info, segtab, (u32*)cross, pl.stride, part);
+        // two bins per thread where an instance's bins still make many workgroups
+#define LAUNCH_PARTITION_PRED(CT_, KPT_)                                                                         \
+    LAUNCH(K_PARTITION_PRED, (zl_partition_pred_kernel<CT_, KPT_>),                                              \
+           dim3((unsigned)((pl.stride + 256 * KPT_ - 1) / (256 * KPT_) * B), (unsigned)part_rows), dim3(256),     \
+           le, iv, P, R, info, segtab, (CT_*)cross, pl.stride, part)
+        if (pl.stride >= 2048) {
+            if (pl.narrow) LAUNCH_PARTITION_PRED(unsigned short, 2); else LAUNCH_PARTITION_PRED(u32, 2);
+        } else {
+            if (pl.narrow) LAUNCH_PARTITION_PRED(unsigned short, 1); else LAUNCH_PARTITION_PRED(u32, 1);
+        }
+#undef LAUNCH_PARTITION_PRED
     } else if (pl.part_stored > 0) {
         part_rows = pl.part_stored;
         if (pl.narrow)

@@ -244,41 +244,75 @@ __global__ __launch_bounds__(PART_ROWS * WAVE) void zl_partition_sum_kernel(
 // fine bins below k are those below the first value of bin k.  One thread per bin
 // (consecutive threads write consecutive indices of a row), looping over the rows.
 constexpr int PRED_ROWS_PER_BLOCK = 64;
-template <class CT>
+// KPT neighbouring bins per thread (1 or 2: one store for both indices; pays where an instance has bins for many workgroups)
+template <class CT, int KPT>
 __global__ __launch_bounds__(256) void zl_partition_pred_kernel(
     const i64* __restrict__ le, const i64* __restrict__ iv, int P, int R,
     const InstInfo* __restrict__ info, const SegEntry* __restrict__ segtab, CT* __restrict__ cross, int stride,
     u32* __restrict__ part)
 {
-    const u32 kblocks = (u32)(stride + 255) / 256;
+    struct alignas(KPT * sizeof(CT)) Some { CT v[KPT]; };
+    constexpr int PRED_BINS_PER_BLOCK = 256 * KPT;
+    const u32 kblocks = (u32)(stride + PRED_BINS_PER_BLOCK - 1) / PRED_BINS_PER_BLOCK;
     const i64 b = blockIdx.x / kblocks;
-    const int k = (int)(blockIdx.x % kblocks) * 256 + (int)threadIdx.x;
+    const int k = (int)(blockIdx.x % kblocks) * PRED_BINS_PER_BLOCK + KPT * (int)threadIdx.x;   // bins k .. k + KPT - 1 (stride is even)
     const int p_begin = (int)blockIdx.y * PRED_ROWS_PER_BLOCK;           // a slice of the rows per workgroup
     const int p_end = p_begin + PRED_ROWS_PER_BLOCK < P ? p_begin + PRED_ROWS_PER_BLOCK : P;
     const InstInfo ii = info[b];
-    if (k > (int)ii.nb) return;
-    const bool broken = (ii.flags & EBSP_STATUS_UNSORTED) != 0;      // a negative interval: indices stay zero
-    const u64 edge = k >= (int)ii.nb ? U64_MAX : fine_bin_start((u32)k, ii, segtab + b * (i64)SEGS);   // bin nb: everything lies below
     const i64* __restrict__ lep = le + b * (i64)P;
     const i64* __restrict__ ivp = iv + b * (i64)P;
+    // Division by a row's interval, once per (row, bin), is most of this kernel's work: the rows' reciprocals
+    // are taken once per workgroup.  With m = floor((2^32 - 1) / d) + 1 the product's upper word
+    // floor(n * m / 2^32) is floor(n / d) or one more, for every n below 2^32 (m * d - 2^32 lies in [0, d)).
+    __shared__ u32 inv[PRED_ROWS_PER_BLOCK];
+    if ((int)threadIdx.x < p_end - p_begin) {
+        const u64 st = (u64)ivp[p_begin + (int)threadIdx.x];
+        inv[threadIdx.x] = (st >> 32) == 0 && (u32)st > 1u ? 0xffffffffu / (u32)st + 1u : 0u;     // 0: divide the long way
+    }
+    __syncthreads();
+    if (k > (int)ii.nb) return;
+    const bool broken = (ii.flags & EBSP_STATUS_UNSORTED) != 0;      // a negative interval: indices stay zero
+    // bin nb and beyond (the row's padding): everything lies below
+    u64 edge[KPT];
+#pragma unroll
+    for (int j = 0; j < KPT; ++j)
+        edge[j] = k + j >= (int)ii.nb ? U64_MAX : fine_bin_start((u32)(k + j), ii, segtab + b * (i64)SEGS);
     CT* __restrict__ out = cross + (b * (i64)P) * stride + k;
     const bool narrow_values = (ii.range >> 32) == 0;
-    u32 sum = 0;
+    u32 sum[KPT] = {};
     for (int p = p_begin; p < p_end; ++p) {
         const u64 step = (u64)ivp[p];
         const u64 first = (u64)lep[p] + step - (u64)ii.base;
-        u64 below;                                                   // entries with first + i * step < edge
-        if (broken) below = 0;
-        else if (edge == U64_MAX) below = (u64)R;
-        else if (edge <= first) below = 0;
-        else if (step == 0) below = (u64)R;
-        else if (narrow_values && (step >> 32) == 0) below = (u64)(((u32)(edge - first) - 1u) / (u32)step) + 1u;
-        else below = (edge - first - 1) / step + 1;
-        const u32 c = (u32)(below < (u64)R ? below : (u64)R);
-        out[(i64)p * stride] = (CT)c;
-        sum += c;
+        const u32 m = inv[p - p_begin];
+        Some c;
+#pragma unroll
+        for (int j = 0; j < KPT; ++j) {
+            u64 below;                                               // entries with first + i * step < edge
+            if (broken) below = 0;
+            else if (edge[j] == U64_MAX) below = (u64)R;
+            else if (edge[j] <= first) below = 0;
+            else if (step == 0) below = (u64)R;
+            else if (narrow_values && (step >> 32) == 0) {
+                const u32 n = (u32)(edge[j] - first) - 1u;
+                u32 q;
+                if (m) {
+                    q = __umulhi(n, m);
+                    q -= (u64)q * (u32)step > (u64)n ? 1u : 0u;
+                } else {
+                    q = n / (u32)step;                                   // an interval of 1 (or none of the above)
+                }
+                below = (u64)q + 1u;
+            }
+            else below = (edge[j] - first - 1) / step + 1;
+            const u32 cj = (u32)(below < (u64)R ? below : (u64)R);
+            c.v[j] = (CT)cj;
+            sum[j] += cj;
+        }
+        *(Some*)(out + (i64)p * stride) = c;
     }
-    part[(b * (i64)gridDim.y + blockIdx.y) * stride + k] = sum;      // this slice's share of the column sum
+    u32* __restrict__ mine = part + (b * (i64)gridDim.y + blockIdx.y) * stride + k;      // this slice's share of the column sums
+#pragma unroll
+    for (int j = 0; j < KPT; ++j) mine[j] = sum[j];
 }
 
 // zl_bincount: below[b][k] = number of keys of instance b under fine bin k, k = 0..nb:
