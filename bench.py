@@ -42,7 +42,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 # reads for the plain copy kernel of known size (FETCH_SIZE x 2048 B, WRITE_SIZE x 1024 B per count).  The
 # figures below are the counters' per-dispatch averages, kernel by kernel in launch order.  They hold only for
 # the kernel sources they were taken from: `traffic` is null once those have changed.
-COUNTED_SOURCES_SHA256 = "b9520f26830ffda555e5b1534db79747729e727886076320120761515f3753df"
+COUNTED_SOURCES_SHA256 = "ca528c90569634376fc1cf51db5c7b9191783465719178502cc4b7a961625652"
 FETCH_UNIT, WRITE_UNIT = 2048, 1024      # bytes per count: what the copy kernel's 2 GiB in, 2 GiB out read as (1 048 607 and 2 097 152)
 COUNTED_TRAFFIC = {     # (objective, predicted, config) -> (dominant kernel, its bytes, bytes of all kernels of a call)
     ("sum", False, 5): ("zl_window_kernel", 2263792 * FETCH_UNIT + 1238 * WRITE_UNIT,
@@ -53,9 +53,9 @@ COUNTED_TRAFFIC = {     # (objective, predicted, config) -> (dominant kernel, it
     ("range", False, 5): ("zl_range_fast_kernel", 2443329 * FETCH_UNIT + 2042 * WRITE_UNIT,
                           (16448 + 1049291 + 35887 + 670 + 2443329 + 638 + 8917) * FETCH_UNIT
                           + (70 + 608522 + 1026 + 1716 + 2042 + 14474 + 258) * WRITE_UNIT),
-    ("sum", True, 5): ("zl_window_kernel", 267410 * FETCH_UNIT + 560 * WRITE_UNIT,
-                       (575 + 10524 + 9004 + 658 + 267410 + 357 + 1673) * FETCH_UNIT
-                       + (582 + 557056 + 1024 + 1240 + 560 + 8192 + 258) * WRITE_UNIT),
+    ("sum", True, 5): ("zl_window_kernel", 267414 * FETCH_UNIT + 561 * WRITE_UNIT,
+                       (575 + 10356 + 9004 + 658 + 267414 + 357 + 1666) * FETCH_UNIT
+                       + (582 + 548866 + 1024 + 1240 + 561 + 8192 + 258) * WRITE_UNIT),
     ("sum", False, 4): ("zl_window_kernel", 2054930 * FETCH_UNIT + 2672 * WRITE_UNIT,
                         (65606 + 1053106 + 18132 + 1875 + 2054930 + 656 + 36371) * FETCH_UNIT
                         + (1120 + 306295 + 2048 + 2519 + 2672 + 0 + 1088) * WRITE_UNIT),
