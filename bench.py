@@ -42,7 +42,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 # reads for the plain copy kernel of known size (FETCH_SIZE x 2048 B, WRITE_SIZE x 1024 B per count).  The
 # figures below are the counters' per-dispatch averages, kernel by kernel in launch order.  They hold only for
 # the kernel sources they were taken from: `traffic` is null once those have changed.
-COUNTED_SOURCES_SHA256 = "ca528c90569634376fc1cf51db5c7b9191783465719178502cc4b7a961625652"
+COUNTED_SOURCES_SHA256 = "9d66ce1abff89f61c0e283e87f6297ddf71601affebcece1b110e6f2d583e638"
 FETCH_UNIT, WRITE_UNIT = 2048, 1024      # bytes per count: what the copy kernel's 2 GiB in, 2 GiB out read as (1 048 607 and 2 097 152)
 COUNTED_TRAFFIC = {     # (objective, predicted, config) -> (dominant kernel, its bytes, bytes of all kernels of a call)
     ("sum", False, 5): ("zl_window_kernel", 2263792 * FETCH_UNIT + 1238 * WRITE_UNIT,
@@ -50,9 +50,9 @@ COUNTED_TRAFFIC = {     # (objective, predicted, config) -> (dominant kernel, it
                         + (70 + 608424 + 1025 + 1239 + 1238 + 8192 + 258) * WRITE_UNIT),
     ("sum", False, 3): ("zl_instance_reg_kernel", 1405244 * FETCH_UNIT + 144188 * WRITE_UNIT,
                         (1405244 + 97) * FETCH_UNIT + (144188 + 16384) * WRITE_UNIT),
-    ("range", False, 5): ("zl_range_fast_kernel", 2443329 * FETCH_UNIT + 2042 * WRITE_UNIT,
-                          (16448 + 1049291 + 35887 + 670 + 2443329 + 638 + 8917) * FETCH_UNIT
-                          + (70 + 608522 + 1026 + 1716 + 2042 + 14474 + 258) * WRITE_UNIT),
+    ("range", False, 5): ("zl_range_fast_kernel", 2461671 * FETCH_UNIT + 2071 * WRITE_UNIT,
+                          (16447 + 1049295 + 35886 + 670 + 2461671 + 617 + 8911) * FETCH_UNIT
+                          + (70 + 608466 + 1025 + 1716 + 2071 + 14459 + 258) * WRITE_UNIT),
     ("sum", True, 5): ("zl_window_kernel", 267414 * FETCH_UNIT + 561 * WRITE_UNIT,
                        (575 + 10356 + 9004 + 658 + 267414 + 357 + 1666) * FETCH_UNIT
                        + (582 + 548866 + 1024 + 1240 + 561 + 8192 + 258) * WRITE_UNIT),

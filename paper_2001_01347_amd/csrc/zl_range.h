@@ -352,7 +352,7 @@ __device__ __forceinline__ bool zl_range_bucket_search(const Smem& sm, const Row
     // sweep 2: reach, far and the entry count of every bucket; the keys stay in registers.  The three
     // words of every entry of a batch are asked for before any of them is used.
     u32 key[ITEMS];
-    constexpr int RB = ITEMS < GATHER_BATCH ? ITEMS : GATHER_BATCH;
+    constexpr int RB = ITEMS;                               // (measured: all of a thread's entries at once, 2 % over batches of 8)
     static_assert(ITEMS % RB == 0, "batches must tile the items");
 #pragma unroll
     for (int g = 0; g < ITEMS; g += RB) {

@@ -54,7 +54,9 @@ __device__ __forceinline__ WinPos locate_window(i64 b, int j, const InstInfo& ii
 // LDS of a fast window search.  The record area first holds the source words of the window's
 // entries and then the entries that survive the bounds.  Stored rows: 4 bytes per source word, so
 // the area is half the size and holds records for half the entries (more survivors than that are
-// listed in rounds); with the bucket words after it three workgroups of 512 threads share a CU.
+// listed in rounds); with the bucket words after it the LDS of a CU takes three workgroups of 512
+// threads (how many run is then a matter of registers: three of the range search, two of the
+// summed-wait search, five of its 256-thread form).  EXTRA_WORDS: room behind the source words.
 template <int NT, int ITEMS, bool PRED, int EXTRA_WORDS = 0>
 struct WinHot {
     using H = HotCfg<NT, ITEMS, false>;                  // windows use the linear bucket map: no coarse table
