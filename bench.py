@@ -42,7 +42,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 # reads for the plain copy kernel of known size (FETCH_SIZE x 2048 B, WRITE_SIZE x 1024 B per count).  The
 # figures below are the counters' per-dispatch averages, kernel by kernel in launch order.  They hold only for
 # the kernel sources they were taken from: `traffic` is null once those have changed.
-COUNTED_SOURCES_SHA256 = "9d66ce1abff89f61c0e283e87f6297ddf71601affebcece1b110e6f2d583e638"
+COUNTED_SOURCES_SHA256 = "8a357e189d87dc08d46985853e941fb98f575fecc7a2489b26f751e3dec9a5a9"
 FETCH_UNIT, WRITE_UNIT = 2048, 1024      # bytes per count: what the copy kernel's 2 GiB in, 2 GiB out read as (1 048 607 and 2 097 152)
 COUNTED_TRAFFIC = {     # (objective, predicted, config) -> (dominant kernel, its bytes, bytes of all kernels of a call)
     ("sum", False, 5): ("zl_window_kernel", 2263792 * FETCH_UNIT + 1238 * WRITE_UNIT,

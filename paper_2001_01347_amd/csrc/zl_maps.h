@@ -78,6 +78,16 @@ ZL_FN u32 seg_slope_of(u64 est, u64 even, u64 total2, int bins, u64 len)
     return sl < 4294967295.0 ? (u32)sl : 0xffffffffu;
 }
 
+// Division of many 32-bit numbers by one divisor d >= 2: with m = floor((2^32 - 1) / d) + 1 (one division, once)
+// m * d - 2^32 lies in [0, d), so for every n below 2^32 the upper word of n * m is floor(n / d) or one more,
+// and one comparison settles it.  (d = 1 has no such m in 32 bits: row_reciprocal gives 0 and the caller divides.)
+ZL_FN u32 row_reciprocal(u64 d) { return (d >> 32) == 0 && (u32)d > 1u ? 0xffffffffu / (u32)d + 1u : 0u; }
+ZL_FN u32 div_by_reciprocal(u32 n, u32 d, u32 m)
+{
+    const u32 q = (u32)(((u64)n * (u64)m) >> 32);
+    return q - ((u64)q * (u64)d > (u64)n ? 1u : 0u);
+}
+
 // Monotone maps of keys onto value buckets [0, NB).
 // LinearMap: bucket = (key * scale) >> 32, equal slices of [0, span]; right when the
 // keys are spread evenly, as inside a window of the multi-window path.

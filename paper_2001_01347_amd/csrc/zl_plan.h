@@ -262,13 +262,9 @@ __global__ __launch_bounds__(256) void zl_partition_pred_kernel(
     const i64* __restrict__ lep = le + b * (i64)P;
     const i64* __restrict__ ivp = iv + b * (i64)P;
     // Division by a row's interval, once per (row, bin), is most of this kernel's work: the rows' reciprocals
-    // are taken once per workgroup.  With m = floor((2^32 - 1) / d) + 1 the product's upper word
-    // floor(n * m / 2^32) is floor(n / d) or one more, for every n below 2^32 (m * d - 2^32 lies in [0, d)).
+    // (row_reciprocal) are taken once per workgroup.
     __shared__ u32 inv[PRED_ROWS_PER_BLOCK];
-    if ((int)threadIdx.x < p_end - p_begin) {
-        const u64 st = (u64)ivp[p_begin + (int)threadIdx.x];
-        inv[threadIdx.x] = (st >> 32) == 0 && (u32)st > 1u ? 0xffffffffu / (u32)st + 1u : 0u;     // 0: divide the long way
-    }
+    if ((int)threadIdx.x < p_end - p_begin) inv[threadIdx.x] = row_reciprocal((u64)ivp[p_begin + (int)threadIdx.x]);   // 0: divide the long way
     __syncthreads();
     if (k > (int)ii.nb) return;
     const bool broken = (ii.flags & EBSP_STATUS_UNSORTED) != 0;      // a negative interval: indices stay zero
@@ -294,13 +290,7 @@ __global__ __launch_bounds__(256) void zl_partition_pred_kernel(
             else if (step == 0) below = (u64)R;
             else if (narrow_values && (step >> 32) == 0) {
                 const u32 n = (u32)(edge[j] - first) - 1u;
-                u32 q;
-                if (m) {
-                    q = __umulhi(n, m);
-                    q -= (u64)q * (u32)step > (u64)n ? 1u : 0u;
-                } else {
-                    q = n / (u32)step;                                   // an interval of 1 (or none of the above)
-                }
+                const u32 q = m ? div_by_reciprocal(n, (u32)step, m) : n / (u32)step;     // (no reciprocal: an interval of 1)
                 below = (u64)q + 1u;
             }
             else below = (edge[j] - first - 1) / step + 1;

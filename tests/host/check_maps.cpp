@@ -274,8 +274,38 @@ static void check_fine()
             for (int kind = 0; kind < 5; ++kind) fine_case(range, bins, kind);
 }
 
+// Division by a remembered reciprocal (the predicted rows' partition kernel divides by every row's interval
+// once per fine bin): exact for every numerator, divisors from 2 to 2^32 - 1; 0 and 1 and wider divisors get
+// no reciprocal.
+static void check_reciprocal()
+{
+    std::vector<u32> ds = {2u, 3u, 4u, 5u, 7u, 255u, 256u, 257u, 65535u, 65536u, 65537u, 0x7fffffffu, 0x80000000u,
+                           0x80000001u, 0xfffffffeu, 0xffffffffu};
+    for (int i = 0; i < 3000; ++i) ds.push_back((u32)(rnd() >> (32 + rnd() % 31)) | 2u);
+    for (u32 d : ds) {
+        const u32 m = row_reciprocal(d);
+        std::vector<u32> ns = {0u, 1u, d - 1u, d, d + 1u, 2u * d - 1u, 2u * d, 0x7fffffffu, 0x80000000u, 0xfffffffeu, 0xffffffffu,
+                               0xffffffffu / d * d, 0xffffffffu / d * d - 1u};
+        for (int i = 0; i < 400; ++i) ns.push_back((u32)rnd());
+        for (int i = 0; i < 100; ++i) ns.push_back((u32)(rnd() % 64) * d + (u32)(rnd() % 3) - 1u);     // around multiples of d
+        for (u32 n : ns) {
+            ++checks;
+            if (m == 0 || div_by_reciprocal(n, d, m) != n / d) {
+                if (++failures < 20) std::printf("reciprocal: n=%u d=%u m=%u gives %u, want %u\n", n, d, m, m ? div_by_reciprocal(n, d, m) : 0u, n / d);
+            }
+        }
+    }
+    ++checks;
+    if (row_reciprocal(0) != 0u || row_reciprocal(1) != 0u || row_reciprocal(1ull << 32) != 0u || row_reciprocal(~0ull) != 0u) {
+        ++failures;
+        std::printf("reciprocal: a divisor without one got one\n");
+    }
+}
+
 int main()
 {
+    check_reciprocal();
+    std::printf("reciprocals: %lld checks, %lld failures so far\n", checks, failures);
     check_linear();
     std::printf("linear maps: %lld checks, %lld failures so far\n", checks, failures);
     check_table();

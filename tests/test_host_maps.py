@@ -4,7 +4,8 @@
 of a whole instance, with the bounds on a bucket's keys that decide which buckets are dropped unseen.  It has no
 device intrinsics, so ``tests/host/check_maps.cpp`` includes it into a host program and checks every bound against
 exact 128-bit arithmetic or a walk over every key: spans from 0 to 2^32 - 1, scales from 1 to 2^32 - 1, ranges up to
-2^62, even, clustered and degenerate key sets.  A bound that is too tight would not crash anything: the search would
+2^62, even, clustered and degenerate key sets; and the division by a remembered reciprocal that the predicted rows'
+partition kernel uses, against the plain quotient.  A bound that is too tight would not crash anything: the search would
 return a barrier that is not the best one, on the rare input that hits it.
 """
 import os
